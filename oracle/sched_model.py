@@ -1,0 +1,504 @@
+"""CPU oracle, part S: a tick model of the daemon kernel's scheduler (liveness, not speed).
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product path may import this file.
+It shares no code with the HIP path.
+
+The model follows the paper's scheduling algorithm (Alg. 1, Sec. 4.3) for R ranks,
+one daemon ("block") per rank:
+
+    while not exit:
+        fetch SQE (FIFO order policy)            -- Sec. 4.3 "FIFO Ordering"
+        set initial spin thresholds by position  -- largest at the queue front
+        for collective in task queue:
+            load its context
+            for primitive in collective:
+                two-phase blocking execute       -- Sec. 4.2 (3): poll <= threshold times
+                success -> raise the threshold of the following primitives
+                failure -> preempt, (lazily) save dynamic context, next collective
+            complete -> CQE
+
+A collective's per-rank program is the ring primitive sequence (Sec. 4.1) repeated
+once per slice ("round"); the dynamic context is (round, primitive index), the pair
+the paper calls current chunk id / aborted primitive id.  Connectors are bounded
+FIFOs of K slots with monotone head/tail counters per (collective, ring edge); a
+primitive touches nothing until BOTH its conditions hold, so an aborted wait leaves
+connectors and buffers unchanged (Sec. 4.5: restart without under- or re-sending).
+A preempted collective keeps its queue position (Sec. 4.3).
+
+Readings where the paper is silent (listed in the design notes): spin threshold unit
+= poll attempts; thr(pos) = max(spin_min, spin_init >> pos); after a success
+thr = min(spin_max, thr*boost) until preemption or completion; "cannot progress for
+a while" = one whole pass over the task queue with no successful primitive, after
+which at most one SQE is fetched.
+
+One tick of a rank = its local bookkeeping up to and including ONE poll attempt,
+plus the slice's data movement when the poll succeeds.  Which actor ticks next is
+chosen from outside (round-robin, seeded random, or exhaustive search), which is
+what lets tests explore interleavings.  Host submitters are actors too.
+
+Slices carry real numpy data, so the model's final buffers can be compared with the
+data oracle bit for bit; they also carry (round, step) tags that the receiver checks.
+"""
+from __future__ import annotations
+
+import copy
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import ring_data as rd
+
+AR, AG, RS, BC = 0, 1, 2, 3
+INF = 1 << 60
+
+# primitive name -> (needs recv, needs send)
+PRIMS = {
+    "send": (False, True),
+    "copy_send": (False, True),
+    "copy": (False, False),
+    "recv_reduce_send": (True, True),
+    "recv_reduce_copy_send": (True, True),
+    "recv_reduce_copy": (True, False),
+    "recv_copy_send": (True, True),
+    "recv_copy": (True, False),
+}
+
+
+@dataclass
+class Policy:
+    spin_init: int = 8
+    spin_min: int = 1
+    spin_max: int = 64
+    boost: int = 4
+    preempt: bool = True
+    taskq_cap: int = 1 << 20
+    sq_depth: int = 1 << 20
+    K: int = 2                    # slots per connector FIFO
+    slice_elems: int = 1 << 30    # elements per slice (per round)
+
+
+@dataclass
+class Coll:
+    kind: int
+    dtype: int
+    count: int
+    root: int = 0
+
+
+def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
+            recv_blocks: List[Tuple[int, int]]):
+    """Per-rank primitive sequence: list of (name, send-buffer block, recv-buffer block).
+    `blocks` / `recv_blocks` are the element ranges of ring chunk j in the send / recv buffer."""
+    none = None
+    if R == 1:
+        return [("copy", blocks[0], recv_blocks[0])]
+    b = lambda j: blocks[j % R]
+    d = lambda j: recv_blocks[j % R]
+    if kind == AR:
+        p = [("send", b(r - 1), none)]
+        p += [("recv_reduce_send", b(r - 1 - s), none) for s in range(1, R - 1)]
+        p += [("recv_reduce_copy_send", b(r), d(r))]
+        p += [("recv_copy_send", none, d(r - j)) for j in range(1, R - 1)]
+        p += [("recv_copy", none, d(r + 1))]
+        return p
+    if kind == RS:
+        p = [("send", b(r - 1), none)]
+        p += [("recv_reduce_send", b(r - 1 - s), none) for s in range(1, R - 1)]
+        p += [("recv_reduce_copy", b(r), recv_blocks[0])]
+        return p
+    if kind == AG:
+        p = [("copy_send", blocks[0], d(r))]
+        p += [("recv_copy_send", none, d(r - j)) for j in range(1, R - 1)]
+        p += [("recv_copy", none, d(r + 1))]
+        return p
+    if kind == BC:
+        pos = (r - root) % R
+        if pos == 0:
+            return [("copy_send", blocks[0], recv_blocks[0])]
+        if pos == R - 1:
+            return [("recv_copy", none, recv_blocks[0])]
+        return [("recv_copy_send", none, recv_blocks[0])]
+    raise ValueError(kind)
+
+
+def layout(c: Coll, R: int):
+    """(send blocks, recv blocks, block length used for slicing) for a collective."""
+    eb = rd.ELEM_BYTES[c.dtype]
+    if c.kind == AR:
+        cb = rd.chunk_bounds(c.count, R, eb) if R > 1 else [(0, c.count)]
+        return cb, cb, max(hi - lo for lo, hi in cb)
+    if c.kind == RS:
+        return [(j * c.count, (j + 1) * c.count) for j in range(R)], [(0, c.count)] * R, c.count
+    if c.kind == AG:
+        return [(0, c.count)] * R, [(j * c.count, (j + 1) * c.count) for j in range(R)], c.count
+    return [(0, c.count)] * R, [(0, c.count)] * R, c.count
+
+
+class Fifo:
+    __slots__ = ("K", "head", "tail", "slots")
+
+    def __init__(self, K):
+        self.K, self.head, self.tail = K, 0, 0
+        self.slots = [None] * K
+
+    def readable(self):
+        return self.tail > self.head
+
+    def writable(self):
+        return self.tail - self.head < self.K
+
+    def push(self, x):
+        assert self.writable()
+        self.slots[self.tail % self.K] = x
+        self.tail += 1
+
+    def pop(self):
+        assert self.readable()
+        x = self.slots[self.head % self.K]
+        self.head += 1
+        return x
+
+
+@dataclass
+class Stats:
+    preemptions: int = 0
+    ctx_loads: int = 0
+    ctx_saves: int = 0
+    lazy_skips: int = 0
+    polls: int = 0
+    prims: int = 0
+    max_taskq: int = 0
+    fetches: int = 0
+
+
+class Daemon:
+    """One rank's daemon: Alg. 1 as an explicit state machine."""
+
+    def __init__(self, sysm: "System", r: int):
+        self.S, self.r = sysm, r
+        self.sq: List[Tuple[int, int]] = []   # (coll, seq) submitted, not yet fetched
+        self.taskq: List[int] = []
+        self.pos = 0                          # position in task queue of the pass in flight
+        self.in_pass = False
+        self.pass_progress = False
+        self.loaded: Optional[int] = None     # collective in the active context slot
+        self.active = None                    # [round, prim] of the loaded collective
+        self.dirty = False                    # progressed since load (lazy save)
+        self.saved: Dict[int, List[int]] = {} # context buffer: coll -> [round, prim]
+        self.spin = 0
+        self.thr = 0
+        self.exit = False
+        self.cq: List[Tuple[int, int]] = []
+        self.seq_of: Dict[int, int] = {}
+        self.stats = Stats()
+
+    # -- Alg. 1 helpers
+    def _thr_init(self, pos):
+        P = self.S.policy
+        if not P.preempt:
+            return INF
+        return max(P.spin_min, P.spin_init >> min(pos, 60))
+
+    def _fetch(self):
+        P = self.S.policy
+        if self.sq and len(self.taskq) < P.taskq_cap:
+            coll, seq = self.sq.pop(0)
+            self.stats.fetches += 1
+            if coll < 0:
+                self.exit = True
+                return
+            self.taskq.append(coll)
+            self.seq_of[coll] = seq
+            self.saved[coll] = [0, 0]
+            self.stats.max_taskq = max(self.stats.max_taskq, len(self.taskq))
+
+    def _load(self, coll):
+        self.loaded = coll
+        self.active = list(self.saved[coll])
+        self.dirty = False
+        self.stats.ctx_loads += 1
+
+    def _save(self):
+        if self.dirty:
+            self.saved[self.loaded] = list(self.active)
+            self.stats.ctx_saves += 1
+        else:
+            self.stats.lazy_skips += 1
+        self.loaded = None
+
+    def idle(self):
+        return not self.taskq and not self.sq
+
+    def tick(self) -> bool:
+        """Advance to (and perform) one poll attempt. Returns True if the state changed."""
+        if self.exit:
+            return False
+        changed = False
+        while True:
+            if not self.in_pass:
+                # FetchSQE: when the queue is empty, or the last pass made no progress
+                before = (len(self.taskq), len(self.sq))
+                if not self.taskq or not self.pass_progress:
+                    self._fetch()
+                if self.exit:
+                    return True
+                if (len(self.taskq), len(self.sq)) != before:
+                    changed = True
+                if not self.taskq:
+                    return changed
+                self.in_pass, self.pos, self.pass_progress = True, 0, False
+            if self.pos >= len(self.taskq):
+                self.in_pass = False
+                if self.loaded is not None:
+                    self._save()
+                # a pass ended; a new pass (and maybe a fetch) starts at the next tick
+                return True
+            coll = self.taskq[self.pos]
+            if self.loaded != coll:
+                if self.loaded is not None:
+                    self._save()
+                self._load(coll)
+                self.thr = self._thr_init(self.pos)
+                self.spin = 0
+                changed = True
+            return self._poll_and_run(coll) or changed
+
+    def _poll_and_run(self, coll) -> bool:
+        S = self.S
+        rounds, prog = S.rounds[coll], S.progs[coll][self.r]
+        g, p = self.active
+        name, sblk, dblk = prog[p]
+        need_recv, need_send = PRIMS[name]
+        fin = S.fifo[coll][(self.r - 1) % S.R]
+        fout = S.fifo[coll][self.r]
+        self.stats.polls += 1
+        ok = (not need_recv or fin.readable()) and (not need_send or fout.writable())
+        if not ok:
+            if self.thr >= INF:
+                return False               # spins forever: no state change
+            self.spin += 1
+            if self.spin >= self.thr:
+                self.stats.preemptions += 1
+                self._save()
+                self.pos += 1
+            return True
+        # ---- data phase of one slice
+        S.move(coll, self.r, g, p, name, sblk, dblk, fin, fout)
+        self.stats.prims += 1
+        self.dirty = True
+        self.pass_progress = True
+        self.spin = 0
+        P = S.policy
+        if P.preempt:
+            self.thr = min(P.spin_max, self.thr * P.boost)
+        p += 1
+        if p == len(prog):
+            p, g = 0, g + 1
+        self.active = [g, p]
+        if g == rounds:
+            # CollectiveSuccess -> SendCQE; entry leaves the queue, position stays
+            self.cq.append((coll, self.seq_of[coll]))
+            self.taskq.pop(self.pos)
+            self.saved[coll] = [0, 0]
+            self.loaded = None
+        return True
+
+
+class System:
+    def __init__(self, R: int, colls: Sequence[Coll], sends: Optional[List[List[np.ndarray]]],
+                 policy: Policy):
+        """sends[ci][r] = rank r's send buffer for collective ci (None -> tokens only)."""
+        self.R, self.colls, self.policy = R, list(colls), policy
+        self.with_data = sends is not None
+        self.sends = sends
+        self.recvs = None
+        if self.with_data:
+            self.recvs = []
+            for ci, c in enumerate(colls):
+                n = c.count * R if c.kind == AG else c.count
+                self.recvs.append([np.zeros(n, dtype=sends[ci][0].dtype) for _ in range(R)])
+        self.progs, self.rounds, self.fifo = [], [], []
+        for c in colls:
+            sb, db, blen = layout(c, R)
+            self.progs.append([program(c.kind, R, r, c.root, sb, db) for r in range(R)])
+            self.rounds.append(max(1, -(-blen // policy.slice_elems)))
+            self.fifo.append([Fifo(policy.K) for _ in range(R)])
+        self.daemons = [Daemon(self, r) for r in range(R)]
+        self.pending = [[] for _ in range(R)]   # host side: submissions not yet pushed to the SQ
+        self.nsub = [0] * R
+
+    # -- host side
+    def plan(self, orders: Sequence[Sequence[int]]):
+        for r, o in enumerate(orders):
+            self.pending[r] = list(o)
+
+    def host_tick(self, r) -> bool:
+        """Host thread of rank r pushes its next submission if the SQ has room."""
+        if not self.pending[r] or len(self.daemons[r].sq) >= self.policy.sq_depth:
+            return False
+        self.daemons[r].sq.append((self.pending[r].pop(0), self.nsub[r]))
+        self.nsub[r] += 1
+        return True
+
+    def submit_all(self):
+        for r in range(self.R):
+            while self.host_tick(r):
+                pass
+
+    # -- data phase
+    def _slice(self, blk, g):
+        if blk is None:
+            return None
+        s = self.policy.slice_elems
+        lo, hi = blk
+        return (min(lo + g * s, hi), min(lo + (g + 1) * s, hi))
+
+    def move(self, ci, r, g, p, name, sblk, dblk, fin, fout):
+        c = self.colls[ci]
+        tag_out = (g, p)
+        x = None
+        if PRIMS[name][0]:
+            tag, x = fin.pop()
+            # the sender's primitive index of this hop is p-1 in every ring sequence here,
+            # except the broadcast chain where every rank has a one-primitive program
+            want = (g, 0) if c.kind == BC else (g, p - 1)
+            assert tag == want, f"slice out of sequence: got {tag}, want {want}"
+        if self.with_data:
+            ss, ds = self._slice(sblk, g), self._slice(dblk, g)
+            src = self.sends[ci][r]
+            dst = self.recvs[ci][r]
+            if name in ("send", "copy_send", "copy"):
+                y = src[ss[0]:ss[1]].copy()
+            elif name.startswith("recv_reduce"):
+                y = rd.add_hop(x, src[ss[0]:ss[1]], c.dtype)
+            else:
+                y = x
+            if "copy" in name:
+                dst[ds[0]:ds[1]] = y
+        else:
+            y = None
+        if PRIMS[name][1]:
+            fout.push((tag_out, y))
+
+    # -- global predicates
+    def done(self):
+        return all(not d.taskq and not d.sq for d in self.daemons) and not any(self.pending)
+
+    def total_cqes(self):
+        return sum(len(d.cq) for d in self.daemons)
+
+    def key(self):
+        """Hashable control state (data excluded: it is a function of the counters)."""
+        ds = []
+        for d in self.daemons:
+            ds.append((tuple(d.sq), tuple(d.taskq), d.pos, d.in_pass, d.pass_progress, d.loaded,
+                       tuple(d.active) if d.active and d.loaded is not None else None, d.dirty,
+                       tuple(sorted((k, tuple(v)) for k, v in d.saved.items())), d.spin, d.thr, len(d.cq)))
+        fs = tuple((f.head, f.tail) for fl in self.fifo for f in fl)
+        return (tuple(ds), fs, tuple(tuple(p) for p in self.pending))
+
+    def clone(self):
+        """Copy of the token-only model (immutable program tables are shared)."""
+        assert not self.with_data, "clone only the token-only model"
+        T = System.__new__(System)
+        T.R, T.colls, T.policy = self.R, self.colls, self.policy
+        T.with_data, T.sends, T.recvs = False, None, None
+        T.progs, T.rounds = self.progs, self.rounds
+        T.fifo = []
+        for fl in self.fifo:
+            row = []
+            for f in fl:
+                g = Fifo(f.K)
+                g.head, g.tail, g.slots = f.head, f.tail, list(f.slots)
+                row.append(g)
+            T.fifo.append(row)
+        T.daemons = []
+        for d in self.daemons:
+            e = Daemon.__new__(Daemon)
+            e.S, e.r = T, d.r
+            e.sq, e.taskq = list(d.sq), list(d.taskq)
+            e.pos, e.in_pass, e.pass_progress = d.pos, d.in_pass, d.pass_progress
+            e.loaded, e.dirty = d.loaded, d.dirty
+            e.active = list(d.active) if d.active is not None else None
+            e.saved = {k: list(v) for k, v in d.saved.items()}
+            e.spin, e.thr, e.exit = d.spin, d.thr, d.exit
+            e.cq, e.seq_of = list(d.cq), dict(d.seq_of)
+            e.stats = copy.copy(d.stats)
+            T.daemons.append(e)
+        T.pending = [list(p) for p in self.pending]
+        T.nsub = list(self.nsub)
+        return T
+
+
+# ----------------------------------------------------------------------------
+# choosers
+# ----------------------------------------------------------------------------
+def run_round_robin(S: System, max_ticks: int = 10_000_000) -> int:
+    """Fair chooser. Returns ticks used; raises TimeoutError at the watchdog."""
+    t = 0
+    while not S.done():
+        for r in range(S.R):
+            S.host_tick(r)
+            S.daemons[r].tick()
+            t += 1
+        if t > max_ticks:
+            raise TimeoutError("tick watchdog")
+    return t
+
+
+def run_random(S: System, seed: int, max_ticks: int = 10_000_000, host_weight: float = 0.2) -> int:
+    """Seeded random chooser over daemons and host submitters (fair with probability 1)."""
+    g = np.random.default_rng(seed)
+    t = 0
+    R = S.R
+    while not S.done():
+        # draw a batch of choices at once
+        for a in g.integers(0, 2 * R, size=256):
+            a = int(a)
+            if a >= R:
+                if g.random() < host_weight * 2:
+                    S.host_tick(a - R)
+            else:
+                S.daemons[a].tick()
+            t += 1
+        if t > max_ticks:
+            raise TimeoutError("tick watchdog")
+    return t
+
+
+def is_deadlocked(S: System) -> bool:
+    """True if work is outstanding and no actor's tick changes the control state."""
+    if S.done():
+        return False
+    k0 = S.key()
+    T = S.clone()
+    for r in range(T.R):
+        T.host_tick(r)
+        T.daemons[r].tick()
+    return T.key() == k0
+
+
+def explore(S0: System, max_states: int = 2_000_000):
+    """Exhaustive search over all interleavings of daemon ticks (token-only model).
+    Returns (number of states, list of reachable keys -> a representative System)."""
+    assert not S0.with_data
+    seen = {S0.key(): S0}
+    stack = [S0]
+    while stack:
+        S = stack.pop()
+        for a in range(2 * S.R):
+            T = S.clone()
+            if a >= S.R:
+                moved = T.host_tick(a - S.R)
+            else:
+                moved = T.daemons[a].tick()
+            if not moved:
+                continue
+            k = T.key()
+            if k not in seen:
+                seen[k] = T
+                stack.append(T)
+                if len(seen) > max_states:
+                    raise MemoryError("state bound exceeded")
+    return seen

@@ -1,0 +1,167 @@
+"""Pins for the scheduler model (oracle/sched_model.py): liveness under deadlock-prone
+issue orders, the no-preemption negative control, and preemption transparency (the data an
+interleaved, preempted execution produces equals the data oracle's, bit for bit)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import workload_inputs as wi
+from oracle import ring_data as rd
+from oracle import sched_model as sm
+
+
+def _system(w: wi.Workload, policy: sm.Policy, data=True):
+    colls = [sm.Coll(c.kind, c.dtype, c.count, c.root) for c in w.colls]
+    sends = [wi.all_sends(w, ci) for ci in range(len(w.colls))] if data else None
+    S = sm.System(w.R, colls, sends, policy)
+    S.plan(w.orders)
+    return S
+
+
+def _check_data(S, w):
+    for ci, c in enumerate(w.colls):
+        want = rd.run_closed_form(c.kind, S.sends[ci], c.dtype, c.root)
+        for r in range(w.R):
+            assert np.array_equal(S.recvs[ci][r].view(np.uint8), want[r].view(np.uint8)), (ci, r)
+
+
+ORDERS2 = list(itertools.product([(0, 1), (1, 0)], repeat=2))
+
+
+@pytest.mark.parametrize("orders", ORDERS2)
+@pytest.mark.parametrize("K,slice_elems,spin", [(2, 256, 2), (2, 128, 3), (3, 64, 1), (4, 1024, 8)])
+def test_config1_all_issue_orders_complete_and_match(orders, K, slice_elems, spin):
+    w = wi.config1(*orders)
+    S = _system(w, sm.Policy(spin_init=spin, spin_min=1, spin_max=4 * spin, boost=2, K=K, slice_elems=slice_elems))
+    sm.run_round_robin(S, max_ticks=200_000)
+    assert S.total_cqes() == 4
+    _check_data(S, w)
+    # values are small integers: exact sums regardless of order
+    for ci in range(2):
+        exact = sum(s.astype(np.int64) for s in S.sends[ci])
+        for r in range(2):
+            assert np.array_equal(S.recvs[ci][r].astype(np.int64), exact)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_config1_random_interleavings(seed):
+    w = wi.config1((0, 1), (1, 0))
+    S = _system(w, sm.Policy(spin_init=3, spin_max=12, boost=2, K=2, slice_elems=128))
+    sm.run_random(S, seed, max_ticks=500_000)
+    _check_data(S, w)
+    assert sum(d.stats.preemptions for d in S.daemons) > 0
+
+
+def test_negative_control_without_preemption_deadlocks():
+    """Opposite issue orders + no preemption = the single-queue deadlock of Sec. 2.3 / Fig. 1(c);
+    the paper reports a 100 % deadlock ratio for the non-preemptive library (Sec. 6.1)."""
+    w = wi.config1((0, 1), (1, 0))
+    S = _system(w, sm.Policy(preempt=False, K=2, slice_elems=256, taskq_cap=1), data=False)
+    S.submit_all()
+    with pytest.raises(TimeoutError):
+        sm.run_round_robin(S, max_ticks=5_000)
+    assert sm.is_deadlocked(S)
+    assert S.total_cqes() == 0
+
+
+def test_same_order_without_preemption_completes():
+    w = wi.config1((0, 1), (0, 1))
+    S = _system(w, sm.Policy(preempt=False, K=2, slice_elems=256, taskq_cap=1))
+    sm.run_round_robin(S, max_ticks=100_000)
+    _check_data(S, w)
+    assert not sm.is_deadlocked(S)
+
+
+@pytest.mark.parametrize("orders", ORDERS2)
+@pytest.mark.parametrize("K", [2, 3])
+def test_exhaustive_interleavings_tiny(orders, K):
+    """2 ranks, 2 collectives, 2 slices each, K slots: every reachable control state (all
+    interleavings of daemon ticks and host submissions) can still finish under a fair chooser,
+    and no reachable state is a deadlock."""
+    w = wi.config1(*orders, n=8)
+    pol = sm.Policy(spin_init=2, spin_min=1, spin_max=2, boost=2, K=K, slice_elems=2)
+    S0 = _system(w, pol, data=False)
+    seen = sm.explore(S0, max_states=400_000)
+    assert len(seen) > 100
+    finals = 0
+    # every 17th state (plus all states when the space is small) is driven to completion
+    keys = list(seen)
+    step = 1 if len(keys) < 3000 else 17
+    for k in keys[::step]:
+        T = seen[k].clone()
+        assert not sm.is_deadlocked(T)
+        sm.run_round_robin(T, max_ticks=50_000)
+        assert T.total_cqes() == 4
+        finals += 1
+    assert finals > 0
+
+
+def test_R3_three_collectives_all_216_orders():
+    R = 3
+    colls = [wi.CollSpec(i, wi.AR, wi.F32, 48) for i in range(3)]
+    perms = list(itertools.permutations(range(3)))
+    for o0, o1, o2 in itertools.product(perms, repeat=3):
+        w = wi.Workload("r3", R, colls, [list(o0), list(o1), list(o2)], seed=5, cfg=90)
+        S = _system(w, sm.Policy(spin_init=4, spin_max=16, boost=2, K=2, slice_elems=8), data=False)
+        sm.run_round_robin(S, max_ticks=200_000)
+        assert S.total_cqes() == 9
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_mixed_kinds_preemption_transparent(seed):
+    """All four kinds, three dtypes, uneven sizes, random per-rank orders, tiny thresholds:
+    thousands of preemptions, results identical to the data oracle."""
+    w = wi.config4(n_colls=10, min_bytes=256, max_bytes=4096, seed=seed, R=4)
+    S = _system(w, sm.Policy(spin_init=4, spin_min=1, spin_max=16, boost=2, K=2, slice_elems=40, sq_depth=3))
+    sm.run_random(S, seed + 100, max_ticks=5_000_000)
+    assert S.total_cqes() == 10 * 4
+    _check_data(S, w)
+    assert sum(d.stats.preemptions for d in S.daemons) > 50
+    assert sum(d.stats.lazy_skips for d in S.daemons) > 0
+
+
+def test_uneven_allreduce_bf16_through_scheduler():
+    R = 5
+    colls = [wi.CollSpec(0, wi.AR, wi.BF16, 131), wi.CollSpec(1, wi.AR, wi.F16, 7), wi.CollSpec(2, wi.AR, wi.I32, 3)]
+    orders = [list(np.random.default_rng(r).permutation(3)) for r in range(R)]
+    w = wi.Workload("uneven", R, colls, orders, seed=9, cfg=91)
+    S = _system(w, sm.Policy(spin_init=2, spin_max=8, boost=2, K=2, slice_elems=8))
+    sm.run_round_robin(S, max_ticks=1_000_000)
+    _check_data(S, w)
+
+
+def test_stickiness_thresholds_follow_position_and_boost():
+    w = wi.config1((0, 1), (0, 1))
+    pol = sm.Policy(spin_init=64, spin_min=4, spin_max=1000, boost=20)
+    S = _system(w, pol, data=False)
+    d = S.daemons[0]
+    assert [d._thr_init(p) for p in range(6)] == [64, 32, 16, 8, 4, 4]
+    S.submit_all()
+    d.tick()                       # loads collective 0 and runs its first primitive (send: always possible)
+    assert d.thr == min(1000, 64 * 20)
+    assert d.stats.prims == 1
+
+
+def test_task_queue_capacity_is_a_liveness_condition():
+    """With preemption on but a one-entry task queue, opposite orders still deadlock: the peer's
+    collective can never be fetched. Capacity >= outstanding collectives restores liveness."""
+    w = wi.config1((0, 1), (1, 0))
+    S = _system(w, sm.Policy(spin_init=2, spin_max=4, boost=2, K=2, slice_elems=256, taskq_cap=1), data=False)
+    with pytest.raises(TimeoutError):
+        sm.run_round_robin(S, max_ticks=20_000)
+    assert S.total_cqes() == 0
+    S = _system(w, sm.Policy(spin_init=2, spin_max=4, boost=2, K=2, slice_elems=256, taskq_cap=2), data=False)
+    sm.run_round_robin(S, max_ticks=20_000)
+    assert S.total_cqes() == 4
+
+
+def test_one_slot_connectors_cannot_run_a_fused_ring():
+    """K = 1 is not a valid connector depth: after every rank's opening `send` all connectors are
+    full and every next primitive needs its send side writable AND its recv side readable, so even
+    a single collective in a consistent order stalls. The library therefore requires K >= 2."""
+    w = wi.config1((0, 1), (0, 1))
+    S = _system(w, sm.Policy(spin_init=2, spin_max=8, boost=2, K=1, slice_elems=256), data=False)
+    with pytest.raises(TimeoutError):
+        sm.run_round_robin(S, max_ticks=20_000)
+    assert S.total_cqes() == 0
