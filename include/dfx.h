@@ -1,0 +1,199 @@
+/*
+ * dfx -- preemptive daemon-kernel collectives for one MI355X (gfx950).
+ *
+ * A C ABI for the hot path of the deadlock-free collective library of
+ * arXiv 2303.06324 (DFCCL): a daemon kernel polls a submission queue (SQ),
+ * executes ring collectives as chunked reduce/copy primitives through
+ * flag-guarded FIFOs ("connectors") in HBM, preempts a collective whose
+ * primitive spins past its stickiness-adjusted threshold (context save /
+ * switch / restore) and posts completions to a completion queue (CQ).
+ *
+ * R virtual ranks ("vranks") share ONE GPU: vrank r is a set of workgroups of
+ * the one daemon grid, with its own SQ, CQ, task queues and contexts; only the
+ * connectors are shared between neighbouring vranks.
+ *
+ * All pointers are plain pointers.  "device" = memory of the GPU the context
+ * was created on, "host" = ordinary process memory.  No function throws; every
+ * function returns DFX_OK (0) or a negative dfx_status.  Functions taking a
+ * rank are thread-safe against calls for OTHER ranks (one submitter per SQ at
+ * a time: Sec. 5, "single-producer multi-consumer"); dfx_init, dfx_prepare,
+ * dfx_start, dfx_stop and dfx_finalize must not run concurrently with
+ * anything else on the same context.
+ */
+#ifndef DFX_H
+#define DFX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dfx_ctx dfx_ctx; /* opaque, library-owned */
+
+typedef enum { DFX_ALLREDUCE = 0, DFX_ALLGATHER = 1, DFX_REDUCESCATTER = 2, DFX_BROADCAST = 3 } dfx_kind;
+typedef enum { DFX_F32 = 0, DFX_BF16 = 1, DFX_F16 = 2, DFX_I32 = 3 } dfx_dtype;
+typedef enum { DFX_SUM = 0 } dfx_op; /* Sec. 4.1 "reducing function"; only sum is built */
+
+typedef enum {
+  DFX_OK = 0,
+  DFX_ERR_INVALID_ARG = -1,
+  DFX_ERR_NOT_PREPARED = -2,
+  DFX_ERR_BUSY = -3,      /* this (rank, coll_id) is already outstanding */
+  DFX_ERR_SQ_FULL = -4,   /* retry: the slot is reusable once every workgroup has read it (Sec. 5) */
+  DFX_ERR_TIMEOUT = -5,   /* wait deadline passed, or the in-kernel watchdog fired */
+  DFX_ERR_HIP = -6,       /* a HIP runtime call failed; see dfx_last_hip_error */
+  DFX_ERR_NO_RESOURCES = -7, /* grid does not fit the GPU / connector pool exhausted */
+  DFX_ERR_ABORTED = -8    /* the daemon was aborted; context must be finalized */
+} dfx_status;
+
+/* One completion (Sec. 5 "the CQE only carries the collective's ID"; seq added: reading 13). */
+typedef struct {
+  uint32_t coll_id;
+  uint32_t seq; /* how many times this (rank, coll_id) had been submitted before this invocation */
+} dfx_cqe;
+
+/* Tunables.  Zero-initialise, call dfx_config_default, then override fields. */
+typedef struct {
+  uint32_t struct_bytes;   /* sizeof(dfx_config) the caller was compiled with */
+  uint32_t max_channels;   /* workgroups per vrank; daemon grid = nranks * max_channels (Sec. 5: launched with the largest grid) */
+  uint32_t max_colls;      /* coll_id range [0, max_colls); also task-queue capacity (<= 4096) */
+  uint32_t sq_depth;       /* SQ ring entries per vrank (power of two) */
+  uint32_t cq_slots;       /* CQ slot-array length per vrank (Sec. 5 "optimized CQ") */
+  uint32_t nslots;         /* K: slots per connector FIFO, >= 2 (a fused recv+send ring cannot run on 1) */
+  uint32_t slot_bytes;     /* S: bytes per FIFO slot and channel, multiple of 16 */
+  uint32_t chan_min_bytes; /* a collective uses C = clamp(ceil(ringChunkBytes / chan_min_bytes), 1, max_channels) channels */
+  uint32_t spin_init;      /* initial spin threshold (poll attempts) at the task-queue front (Sec. 4.3) */
+  uint32_t spin_min;       /* thr(pos) = max(spin_min, spin_init >> pos) */
+  uint32_t spin_max;       /* cap after boosting */
+  uint32_t spin_boost;     /* thr *= spin_boost after a primitive succeeds (Sec. 6.4: twentyfold) */
+  uint32_t preempt;        /* 0 = never abort a wait (the non-preemptive negative control) */
+  uint32_t watchdog_ms;    /* in-kernel: work queued but no progress for this long => error + daemon exit */
+  uint32_t quit_idle_us;   /* voluntary quit (Sec. 4.4): a workgroup leaves after this long without a
+                              successful primitive or SQE fetch; 0 = stay resident until dfx_stop */
+  uint32_t sq_in_device;   /* 0: SQ in pinned host memory (the paper's placement);
+                              1: SQ in fine-grained device memory written by the host through the PCIe BAR;
+                              2: choose 1 when the device reports a large BAR, else 0 */
+  uint32_t wg_map;         /* 0: workgroup = channel*nranks + rank; 1: workgroup = rank*max_channels + channel */
+  uint32_t order_policy;   /* 0 = FIFO ordering, 1 = priority ordering (Sec. 4.3) */
+  uint32_t trace;          /* 1 = record context-switch latency samples */
+  uint32_t reserved0;
+  uint64_t pool_bytes;     /* device memory reserved for connectors of all prepared collectives */
+} dfx_config;
+
+/* Aggregated over the workgroups of one vrank since dfx_init. */
+typedef struct {
+  uint64_t preemptions;    /* waits that hit their spin threshold (context switches) */
+  uint64_t ctx_loads;      /* context loads from HBM into an LDS active slot */
+  uint64_t ctx_slot_hits;  /* loads avoided because the direct-mapped LDS slot still held the context */
+  uint64_t ctx_saves;      /* dynamic-context saves to HBM */
+  uint64_t lazy_skips;     /* preemptions that skipped the save (nothing had progressed) */
+  uint64_t polls;          /* poll attempts in wait phases */
+  uint64_t prims;          /* primitives (slices) executed */
+  uint64_t sqe_fetched;
+  uint64_t cqe_posted;
+  uint64_t max_taskq;      /* largest task-queue length seen by any workgroup */
+  uint64_t passes;         /* traversals of the task queue */
+  uint64_t quits;          /* voluntary quits */
+  uint64_t launches;       /* daemon launches (whole context, not per rank) */
+  uint64_t switch_samples; /* context-switch latency samples available */
+  double switch_us_p50;    /* abort decision -> first poll of the next collective */
+  double switch_us_p99;
+  double switch_us_mean;
+  double save_us_mean;     /* the save part of a switch */
+  double load_us_mean;     /* the load part of a switch */
+} dfx_stats_t;
+
+/* Fill *cfg with defaults (struct_bytes set). cfg: host, caller-owned. */
+int dfx_config_default(dfx_config* cfg);
+
+/*
+ * Create a context for nranks vranks on the current HIP device (= nranks x dfcclInit, Sec. 3.2).
+ * cfg: host, may be NULL (defaults).  hip_stream: a hipStream_t (default priority) that the
+ * library uses ONLY for the daemon kernel; nothing else may be enqueued on it (work queued
+ * behind a resident daemon would never start).  Allocates SQ, CQ, context buffers, counters
+ * and the connector pool; all are library-owned and freed by dfx_finalize.
+ * Errors: INVALID_ARG (nranks < 1 or > 64, bad cfg), NO_RESOURCES (grid cannot be co-resident), HIP.
+ */
+int dfx_init(dfx_ctx** out, int nranks, const dfx_config* cfg, void* hip_stream);
+
+/*
+ * Register collective coll_id on every vrank (= dfcclRegister* on each rank of the device set,
+ * Sec. 3.2): fixes kind, element count, dtype, op, root (broadcast only) and priority (larger =
+ * more urgent; only used by the priority order policy), assigns its connectors (exclusive to
+ * this collective, Sec. 4.5) and its channel count.  May be called while the daemon runs.
+ * count: all-reduce / broadcast: elements per rank; all-gather: elements each rank contributes
+ * (recv buffers hold nranks*count); reduce-scatter: elements each rank receives (send buffers
+ * hold nranks*count).  Errors: INVALID_ARG (id out of range or already prepared, unknown enum),
+ * NO_RESOURCES (connector pool exhausted).
+ */
+int dfx_prepare(dfx_ctx* ctx, int coll_id, dfx_kind kind, size_t count, dfx_dtype dtype, dfx_op op,
+                int root, int priority);
+
+/*
+ * Invoke a prepared collective on one vrank (= dfcclRun*, Sec. 3.2): writes one SQE and returns
+ * at once; starts the daemon if it is not running (Sec. 4.4 event-driven start).
+ * sendbuf, recvbuf: device, caller-owned, 16-byte aligned, valid and unmodified (sendbuf) /
+ * unread (recvbuf) until this rank's CQE for the invocation; they may differ between
+ * invocations of one coll_id (Sec. 4.2) and must not overlap each other.
+ * Errors: INVALID_ARG, NOT_PREPARED, BUSY, SQ_FULL (retry), ABORTED, HIP.
+ */
+int dfx_submit(dfx_ctx* ctx, int rank, int coll_id, const void* sendbuf, void* recvbuf);
+
+/*
+ * Take up to max completions of one vrank (the poller's job, Sec. 3.1).  out: host.
+ * Returns the number of CQEs written to out (>= 0) or a negative status.  Restarts a daemon
+ * that quit voluntarily while work is outstanding.
+ */
+int dfx_poll(dfx_ctx* ctx, int rank, dfx_cqe* out, int max);
+
+/*
+ * Block until the latest invocation of coll_id on rank has completed, or timeout_ns passed
+ * (TIMEOUT; the context stays usable).  Consumes that CQE; other CQEs seen meanwhile stay
+ * available to dfx_poll.  If the daemon reported a watchdog error: TIMEOUT, and the context is
+ * aborted.
+ */
+int dfx_wait(dfx_ctx* ctx, int rank, int coll_id, uint64_t timeout_ns);
+
+/* Block until every submission made so far on every vrank has completed (CQEs are consumed). */
+int dfx_wait_all(dfx_ctx* ctx, uint64_t timeout_ns);
+
+/* Launch the daemon now if it is not running (normally implicit in dfx_submit). */
+int dfx_start(dfx_ctx* ctx);
+
+/*
+ * Post an exit SQE to every vrank (Sec. 4.4 "exiting SQE") and wait until the daemon grid has
+ * drained.  Outstanding collectives keep their saved contexts and resume at the next start.
+ */
+int dfx_stop(dfx_ctx* ctx);
+
+/* Counters of one vrank; out: host. Safe while the daemon runs (values may lag). */
+int dfx_stats(dfx_ctx* ctx, int rank, dfx_stats_t* out);
+
+/* Geometry the library chose for a prepared collective (for tests and the bench). */
+int dfx_coll_info(dfx_ctx* ctx, int coll_id, uint32_t* nchan, uint32_t* slot_bytes, uint32_t* rounds,
+                  uint32_t* nprim);
+
+/* Milliseconds the last completed daemon launch spent on the GPU (HIP events on the daemon's
+   stream), and how many launches have completed; 0 launches => *ms = 0. out pointers: host. */
+int dfx_last_launch_ms(dfx_ctx* ctx, float* ms, uint64_t* launches_done);
+
+/* = nranks x dfcclDestroy: dfx_stop, then free everything. ABORTED if work was still outstanding
+   (it is dropped).  ctx is invalid afterwards in every case. */
+int dfx_finalize(dfx_ctx* ctx);
+
+/* hipError_t of the last failing HIP call on this context, as an int. */
+int dfx_last_hip_error(dfx_ctx* ctx);
+
+const char* dfx_strerror(int status);
+
+/* Measurement aid, not part of the method: copy `bytes` (multiple of 16) from src to dst (both
+   device) with a plain grid-stride kernel on hip_stream (NULL = the null stream) and wait.  Its
+   known traffic calibrates the profiler's HBM byte counters. */
+int dfx_copy_calibrate(const void* src, void* dst, size_t bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DFX_H */

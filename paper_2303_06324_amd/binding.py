@@ -1,0 +1,183 @@
+"""Thin ctypes binding of the dfx C ABI (include/dfx.h): argument marshalling only.
+
+Every step of the hot path runs in the HIP library; nothing here computes, and there is no
+fallback: importing this module without the built library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdfx.so")
+
+ALLREDUCE, ALLGATHER, REDUCESCATTER, BROADCAST = 0, 1, 2, 3
+F32, BF16, F16, I32 = 0, 1, 2, 3
+SUM = 0
+
+OK = 0
+ERR_INVALID_ARG, ERR_NOT_PREPARED, ERR_BUSY, ERR_SQ_FULL = -1, -2, -3, -4
+ERR_TIMEOUT, ERR_HIP, ERR_NO_RESOURCES, ERR_ABORTED = -5, -6, -7, -8
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in (
+        "struct_bytes", "max_channels", "max_colls", "sq_depth", "cq_slots", "nslots", "slot_bytes",
+        "chan_min_bytes", "spin_init", "spin_min", "spin_max", "spin_boost", "preempt", "watchdog_ms",
+        "quit_idle_us", "sq_in_device", "wg_map", "order_policy", "trace", "reserved0")] + [("pool_bytes", C.c_uint64)]
+
+
+class Stats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in (
+        "preemptions", "ctx_loads", "ctx_slot_hits", "ctx_saves", "lazy_skips", "polls", "prims", "sqe_fetched",
+        "cqe_posted", "max_taskq", "passes", "quits", "launches", "switch_samples")] + [(n, C.c_double) for n in (
+        "switch_us_p50", "switch_us_p99", "switch_us_mean", "save_us_mean", "load_us_mean")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class Cqe(C.Structure):
+    _fields_ = [("coll_id", C.c_uint32), ("seq", C.c_uint32)]
+
+
+class DfxError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {strerror(status)} ({status})")
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2303_06324_amd.build); "
+                          "there is no CPU fallback")
+    lib = C.CDLL(LIB_PATH)
+    vp, i, u64, sz = C.c_void_p, C.c_int, C.c_uint64, C.c_size_t
+    sig = {
+        "dfx_config_default": ([C.POINTER(Config)], i),
+        "dfx_init": ([C.POINTER(vp), i, C.POINTER(Config), vp], i),
+        "dfx_prepare": ([vp, i, i, sz, i, i, i, i], i),
+        "dfx_submit": ([vp, i, i, vp, vp], i),
+        "dfx_poll": ([vp, i, C.POINTER(Cqe), i], i),
+        "dfx_wait": ([vp, i, i, u64], i),
+        "dfx_wait_all": ([vp, u64], i),
+        "dfx_start": ([vp], i),
+        "dfx_stop": ([vp], i),
+        "dfx_stats": ([vp, i, C.POINTER(Stats)], i),
+        "dfx_coll_info": ([vp, i] + [C.POINTER(C.c_uint32)] * 4, i),
+        "dfx_last_launch_ms": ([vp, C.POINTER(C.c_float), C.POINTER(u64)], i),
+        "dfx_finalize": ([vp], i),
+        "dfx_last_hip_error": ([vp], i),
+        "dfx_strerror": ([i], C.c_char_p),
+        "dfx_copy_calibrate": ([vp, vp, sz, vp], i),
+    }
+    for name, (args, res) in sig.items():
+        f = getattr(lib, name)
+        f.argtypes, f.restype = args, res
+    return lib
+
+
+_lib = _load()
+
+
+def strerror(status: int) -> str:
+    return _lib.dfx_strerror(status).decode()
+
+
+def config_default() -> Config:
+    cfg = Config()
+    _lib.dfx_config_default(C.byref(cfg))
+    return cfg
+
+
+class Context:
+    """One dfx context = R virtual ranks on the current GPU. Methods mirror the C entry points."""
+
+    def __init__(self, nranks: int, cfg: Optional[Config] = None, stream: Optional[int] = None):
+        self._h = C.c_void_p()
+        self.nranks = nranks
+        rc = _lib.dfx_init(C.byref(self._h), nranks, C.byref(cfg) if cfg is not None else None,
+                           C.c_void_p(stream) if stream else None)
+        if rc != OK:
+            self._h = C.c_void_p()
+            raise DfxError(rc, "dfx_init")
+
+    def prepare(self, coll_id: int, kind: int, count: int, dtype: int, op: int = SUM, root: int = 0,
+                priority: int = 0) -> None:
+        rc = _lib.dfx_prepare(self._h, coll_id, kind, count, dtype, op, root, priority)
+        if rc != OK:
+            raise DfxError(rc, "dfx_prepare")
+
+    def submit(self, rank: int, coll_id: int, sendbuf: int, recvbuf: int) -> int:
+        """Returns the status (OK, ERR_SQ_FULL, ERR_BUSY ...) without raising: callers retry."""
+        return _lib.dfx_submit(self._h, rank, coll_id, C.c_void_p(sendbuf), C.c_void_p(recvbuf))
+
+    def poll(self, rank: int, max_n: int = 64) -> List[Tuple[int, int]]:
+        buf = (Cqe * max_n)()
+        n = _lib.dfx_poll(self._h, rank, buf, max_n)
+        if n < 0:
+            raise DfxError(n, "dfx_poll")
+        return [(buf[k].coll_id, buf[k].seq) for k in range(n)]
+
+    def wait(self, rank: int, coll_id: int, timeout_s: float = 10.0) -> int:
+        return _lib.dfx_wait(self._h, rank, coll_id, int(timeout_s * 1e9))
+
+    def wait_all(self, timeout_s: float = 10.0) -> int:
+        return _lib.dfx_wait_all(self._h, int(timeout_s * 1e9))
+
+    def start(self) -> int:
+        return _lib.dfx_start(self._h)
+
+    def stop(self) -> int:
+        return _lib.dfx_stop(self._h)
+
+    def stats(self, rank: int) -> dict:
+        s = Stats()
+        rc = _lib.dfx_stats(self._h, rank, C.byref(s))
+        if rc != OK:
+            raise DfxError(rc, "dfx_stats")
+        return s.as_dict()
+
+    def coll_info(self, coll_id: int) -> dict:
+        v = [C.c_uint32() for _ in range(4)]
+        rc = _lib.dfx_coll_info(self._h, coll_id, *[C.byref(x) for x in v])
+        if rc != OK:
+            raise DfxError(rc, "dfx_coll_info")
+        return dict(nchan=v[0].value, slot_bytes=v[1].value, rounds=v[2].value, nprim=v[3].value)
+
+    def last_launch_ms(self) -> Tuple[float, int]:
+        ms, n = C.c_float(), C.c_uint64()
+        rc = _lib.dfx_last_launch_ms(self._h, C.byref(ms), C.byref(n))
+        if rc != OK:
+            raise DfxError(rc, "dfx_last_launch_ms")
+        return ms.value, n.value
+
+    def last_hip_error(self) -> int:
+        return _lib.dfx_last_hip_error(self._h)
+
+    def finalize(self) -> int:
+        if not self._h:
+            return OK
+        rc = _lib.dfx_finalize(self._h)
+        self._h = C.c_void_p()
+        return rc
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.finalize()
+        return False
+
+    def __del__(self):
+        try:
+            self.finalize()
+        except Exception:
+            pass
+
+
+def copy_calibrate(src: int, dst: int, nbytes: int, stream: Optional[int] = None) -> None:
+    rc = _lib.dfx_copy_calibrate(C.c_void_p(src), C.c_void_p(dst), nbytes, C.c_void_p(stream) if stream else None)
+    if rc != OK:
+        raise DfxError(rc, "dfx_copy_calibrate")

@@ -1,0 +1,635 @@
+// The daemon kernel: one persistent grid that executes, preempts and schedules ring
+// collectives for R virtual ranks on one MI355X (gfx950).
+//
+// Workgroup = (virtual rank, channel).  Every workgroup runs the scheduling loop of the
+// paper's Alg. 1 (Sec. 4.3) on its own: fetch SQEs into an LDS task queue, walk the queue,
+// load a collective's context into an LDS slot, execute its primitives in two-phase blocking
+// fashion (bounded spin on the connector flags, then the slice's data movement), raise the
+// spin threshold after a success, and on a timed-out wait save the dynamic context (lazily)
+// and switch to the next collective.  Completion is counted per collective; the last channel
+// posts the CQE.  Connectors are FIFOs of K slots in HBM guarded by monotone tail/head
+// counters; a primitive touches nothing before both its conditions hold (Sec. 4.1, 4.5).
+//
+// Memory-model rules used here (AMDGPU, one agent with one L2 per XCD):
+//   producer: data stores -> every wave drains its stores -> workgroup barrier -> thread 0:
+//             agent-scope release fence -> relaxed agent-scope store of the counter;
+//   consumer: relaxed agent-scope load of the counter (lane 0/1 of wave 0) -> workgroup
+//             barrier -> agent-scope acquire fence in every wave -> data loads.
+//   SQ / CQ / host control words are host-visible and use system scope.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dfx_internal.h"
+
+namespace {
+
+typedef uint64_t u64;
+
+constexpr int NT = DFX_WG_THREADS;
+constexpr int KIND_AR = 0, KIND_AG = 1, KIND_RS = 2, KIND_BC = 3;
+constexpr int DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_I32 = 3, DT_COPY = -1;
+
+enum { W_OK = 0, W_TIMEOUT = 1, W_STOP = 2 };
+enum { STOP_NONE = 0, STOP_ABORT = 1, STOP_QUIT = 2, STOP_EXIT = 3 };
+
+#define SCOPE_AGENT __HIP_MEMORY_SCOPE_AGENT
+#define SCOPE_SYSTEM __HIP_MEMORY_SCOPE_SYSTEM
+
+__device__ __forceinline__ u64 ld_agent64(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, SCOPE_AGENT); }
+__device__ __forceinline__ void st_agent64(u64* p, u64 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, SCOPE_AGENT); }
+__device__ __forceinline__ uint32_t ld_agent32(const uint32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, SCOPE_AGENT); }
+__device__ __forceinline__ uint32_t ld_sys32(const uint32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, SCOPE_SYSTEM); }
+
+// Release fences end with an explicit wait: the L2 write-back they issue must have completed
+// before the flag store that follows.  The compiler's own wait is dropped when it believes no
+// memory operation is pending (our stores were drained before the barrier), and the write-back
+// itself is not on its scoreboard.
+__device__ __forceinline__ void fence_acquire_agent() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
+__device__ __forceinline__ void fence_release_agent() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); __builtin_amdgcn_s_waitcnt(0); }
+__device__ __forceinline__ void fence_acquire_system() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, ""); }
+__device__ __forceinline__ void fence_release_system() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, ""); __builtin_amdgcn_s_waitcnt(0); }
+
+// Every wave waits until its own global stores (and loads) have been performed, then the
+// workgroup meets: afterwards thread 0 may publish on behalf of all waves.
+__device__ __forceinline__ void drain_and_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0) expcnt(0) lgkmcnt(0)
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+// reduce: one hop a (+) b in the storage dtype (one rounding per hop)
+// ------------------------------------------------------------------------------------------
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t bf16x2_add(uint32_t a, uint32_t b) {
+  // widen (exact), add in fp32, round to nearest even back to bf16
+  float lo = __uint_as_float(a << 16) + __uint_as_float(b << 16);
+  float hi = __uint_as_float(a & 0xffff0000u) + __uint_as_float(b & 0xffff0000u);
+  uint32_t ul = __float_as_uint(lo), uh = __float_as_uint(hi);
+  ul = (ul + 0x7fffu + ((ul >> 16) & 1u)) >> 16;
+  uh = (uh + 0x7fffu + ((uh >> 16) & 1u)) & 0xffff0000u;
+  return uh | ul;
+}
+
+template <int DT>
+__device__ __forceinline__ uint32_t add_word(uint32_t a, uint32_t b) {
+  if (DT == DT_F32) return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
+  if (DT == DT_I32) return a + b;
+  if (DT == DT_F16) {
+    half2_t x = __builtin_bit_cast(half2_t, a), y = __builtin_bit_cast(half2_t, b);
+    return __builtin_bit_cast(uint32_t, x + y);
+  }
+  return bf16x2_add(a, b);
+}
+
+template <int DT>
+__device__ __forceinline__ uint4 add_vec(uint4 a, uint4 b) {
+  uint4 r;
+  r.x = add_word<DT>(a.x, b.x);
+  r.y = add_word<DT>(a.y, b.y);
+  r.z = add_word<DT>(a.z, b.z);
+  r.w = add_word<DT>(a.w, b.w);
+  return r;
+}
+
+template <int DT>
+__device__ __forceinline__ uint16_t add_half(uint16_t a, uint16_t b) {
+  if (DT == DT_F16) {
+    _Float16 x = __builtin_bit_cast(_Float16, a), y = __builtin_bit_cast(_Float16, b);
+    return __builtin_bit_cast(uint16_t, (_Float16)(x + y));
+  }
+  return (uint16_t)(bf16x2_add(a, b) & 0xffffu);
+}
+
+// ------------------------------------------------------------------------------------------
+// slice mover: value = s0[i] (+ s1[i]);  d0[i] = value;  d1[i] = value.
+// 128-bit coalesced accesses, four independent vectors in flight per source and thread.
+// Falls back to element-wise moves when a user-buffer side is not 16-byte aligned
+// (all-gather / reduce-scatter blocks of odd length) and for the sub-vector tail.
+// ------------------------------------------------------------------------------------------
+template <int DT, int NSRC, int NDST>
+__device__ __forceinline__ void move_slice(const void* __restrict__ s0, const void* __restrict__ s1,
+                                           void* __restrict__ d0, void* __restrict__ d1, uint32_t bytes) {
+  const uint32_t tid = threadIdx.x;
+  uintptr_t al = (uintptr_t)s0 | (uintptr_t)d0;
+  if (NSRC == 2) al |= (uintptr_t)s1;
+  if (NDST == 2) al |= (uintptr_t)d1;
+  uint32_t done = 0;
+  if ((al & 15u) == 0) {
+    const uint4* __restrict__ S0 = (const uint4*)s0;
+    const uint4* __restrict__ S1 = (const uint4*)s1;
+    uint4* __restrict__ D0 = (uint4*)d0;
+    uint4* __restrict__ D1 = (uint4*)d1;
+    const uint32_t nvec = bytes >> 4;
+    uint32_t i = tid;
+    for (; i + 3 * NT < nvec; i += 4 * NT) {
+      uint4 a0 = S0[i], a1 = S0[i + NT], a2 = S0[i + 2 * NT], a3 = S0[i + 3 * NT];
+      if (NSRC == 2) {
+        uint4 b0 = S1[i], b1 = S1[i + NT], b2 = S1[i + 2 * NT], b3 = S1[i + 3 * NT];
+        a0 = add_vec<DT>(a0, b0);
+        a1 = add_vec<DT>(a1, b1);
+        a2 = add_vec<DT>(a2, b2);
+        a3 = add_vec<DT>(a3, b3);
+      }
+      D0[i] = a0; D0[i + NT] = a1; D0[i + 2 * NT] = a2; D0[i + 3 * NT] = a3;
+      if (NDST == 2) { D1[i] = a0; D1[i + NT] = a1; D1[i + 2 * NT] = a2; D1[i + 3 * NT] = a3; }
+    }
+    for (; i < nvec; i += NT) {
+      uint4 a0 = S0[i];
+      if (NSRC == 2) a0 = add_vec<DT>(a0, S1[i]);
+      D0[i] = a0;
+      if (NDST == 2) D1[i] = a0;
+    }
+    done = nvec << 4;
+  }
+  // element-wise remainder (or everything, when unaligned)
+  if (done < bytes) {
+    if (DT == DT_F32 || DT == DT_I32) {
+      const uint32_t* S0 = (const uint32_t*)((const char*)s0 + done);
+      const uint32_t* S1 = (const uint32_t*)((const char*)s1 + done);
+      uint32_t* D0 = (uint32_t*)((char*)d0 + done);
+      uint32_t* D1 = (uint32_t*)((char*)d1 + done);
+      const uint32_t n = (bytes - done) >> 2;
+      for (uint32_t i = tid; i < n; i += NT) {
+        uint32_t v = S0[i];
+        if (NSRC == 2) v = add_word<DT>(v, S1[i]);
+        D0[i] = v;
+        if (NDST == 2) D1[i] = v;
+      }
+    } else {   // 16-bit elements; pure copies also come here (every dtype is a multiple of 2 bytes)
+      const uint16_t* S0 = (const uint16_t*)((const char*)s0 + done);
+      const uint16_t* S1 = (const uint16_t*)((const char*)s1 + done);
+      uint16_t* D0 = (uint16_t*)((char*)d0 + done);
+      uint16_t* D1 = (uint16_t*)((char*)d1 + done);
+      const uint32_t n = (bytes - done) >> 1;
+      for (uint32_t i = tid; i < n; i += NT) {
+        uint16_t v = S0[i];
+        if (NSRC == 2) v = add_half<DT>(v, S1[i]);
+        D0[i] = v;
+        if (NDST == 2) D1[i] = v;
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ void run_data_phase(int dtype, int nsrc, int ndst, const void* s0, const void* s1,
+                                               void* d0, void* d1, uint32_t bytes) {
+  if (nsrc == 1) {
+    if (ndst == 1) move_slice<DT_COPY, 1, 1>(s0, s1, d0, d1, bytes);
+    else move_slice<DT_COPY, 1, 2>(s0, s1, d0, d1, bytes);
+    return;
+  }
+  switch (dtype) {
+    case DT_F32:
+      if (ndst == 1) move_slice<DT_F32, 2, 1>(s0, s1, d0, d1, bytes); else move_slice<DT_F32, 2, 2>(s0, s1, d0, d1, bytes);
+      break;
+    case DT_BF16:
+      if (ndst == 1) move_slice<DT_BF16, 2, 1>(s0, s1, d0, d1, bytes); else move_slice<DT_BF16, 2, 2>(s0, s1, d0, d1, bytes);
+      break;
+    case DT_F16:
+      if (ndst == 1) move_slice<DT_F16, 2, 1>(s0, s1, d0, d1, bytes); else move_slice<DT_F16, 2, 2>(s0, s1, d0, d1, bytes);
+      break;
+    default:
+      if (ndst == 1) move_slice<DT_I32, 2, 1>(s0, s1, d0, d1, bytes); else move_slice<DT_I32, 2, 2>(s0, s1, d0, d1, bytes);
+      break;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// LDS state of one workgroup
+// ------------------------------------------------------------------------------------------
+struct Shared {
+  DfxCtxEntry slot[DFX_CTX_SLOTS];   // active context slots (Sec. 5, direct-mapped)
+  uint32_t slot_tag[DFX_CTX_SLOTS];
+  DfxStatic sqe;                     // SQE being fetched
+  uint32_t ctl_stop, ctl_got;        // thread-0 -> workgroup broadcasts of the control check
+  uint32_t wres;                     // result of a wait phase
+  u64 stat[DFX_NSTAT];
+  uint16_t taskq[DFX_MAX_COLLS];     // task queue (Sec. 4.2 (1))
+};
+
+// primitive descriptor for (kind, position p in the sequence)
+struct Prim {
+  int nsrc, ndst;          // 1 or 2 sources / destinations
+  bool recv, send;         // uses recv / send connector
+  bool from_send, to_recv; // touches the send buffer / recv buffer
+  uint32_t cidx;           // block (ring chunk) index
+};
+
+__device__ __forceinline__ uint32_t modR(int x, int R) { int m = x % R; return (uint32_t)(m < 0 ? m + R : m); }
+
+__device__ __forceinline__ Prim make_prim(int kind, int R, int r, int root, uint32_t p) {
+  Prim q;
+  q.cidx = 0;
+  if (R == 1) {  // copy
+    q.recv = q.send = false; q.from_send = q.to_recv = true; q.nsrc = 1; q.ndst = 1;
+    return q;
+  }
+  if (kind == KIND_AR || kind == KIND_RS) {
+    q.cidx = modR(r - 1 - (int)p, R);
+    const uint32_t last_reduce = (uint32_t)R - 1;
+    if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = false; }
+    else if (p < last_reduce) { q.recv = true; q.send = true; q.from_send = true; q.to_recv = false; }
+    else if (p == last_reduce) { q.recv = true; q.send = (kind == KIND_AR); q.from_send = true; q.to_recv = true; }
+    else if (p < 2u * R - 2) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
+    else { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
+  } else if (kind == KIND_AG) {
+    q.cidx = modR(r - (int)p, R);
+    if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }
+    else if (p < (uint32_t)R - 1) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
+    else { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
+  } else {  // broadcast chain root -> root+1 -> ... -> root-1
+    const uint32_t pos = modR(r - root, R);
+    if (pos == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }
+    else if (pos == (uint32_t)R - 1) { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
+    else { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
+  }
+  q.nsrc = (q.recv && q.from_send) ? 2 : 1;
+  q.ndst = (q.send && q.to_recv) ? 2 : 1;
+  return q;
+}
+
+__device__ __forceinline__ void raise_error(const DfxDaemonArgs& a, uint32_t code, uint32_t wg) {
+  uint32_t expected = 0;
+  if (__hip_atomic_compare_exchange_strong(&a.dev_ctl[DC_ERR], &expected, code, __ATOMIC_RELAXED, __ATOMIC_RELAXED, SCOPE_AGENT))
+    __hip_atomic_store(&a.dev_ctl[DC_ERR_WG], wg, __ATOMIC_RELAXED, SCOPE_AGENT);
+  __hip_atomic_store(&a.dev_ctl[DC_ABORT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
+}
+
+}  // namespace
+
+extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(DfxDaemonArgs a) {
+  __shared__ Shared sh;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t wg = blockIdx.x;
+  uint32_t rank, ch;
+  if (a.wg_map == 0) { rank = wg % a.R; ch = wg / a.R; }
+  else { rank = wg / a.cmax; ch = wg % a.cmax; }
+  const int R = (int)a.R;
+  const uint32_t D = a.sq_depth;
+
+  DfxWgState* ws = &a.wgstate[wg];
+  DfxCtxEntry* myctx = a.ctxbuf + (size_t)wg * a.max_colls;
+  uint16_t* qstore = a.taskq_store + (size_t)wg * a.max_colls;
+  DfxSqSlot* sqbase = a.sq + (size_t)rank * D;
+  u64* cqbase = a.cq + (size_t)rank * a.cq_slots;
+  u64* trace = a.trace ? a.trace + (size_t)wg * DFX_TRACE_N : nullptr;
+
+  // ---- restore the workgroup state left by the previous launch (Sec. 4.5)
+  u64 ri = ws->read_index;
+  uint32_t qlen = ws->qlen;
+  uint32_t trace_n = ws->trace_n;
+  for (uint32_t i = tid; i < qlen; i += NT) sh.taskq[i] = qstore[i];
+  if (tid < DFX_CTX_SLOTS) sh.slot_tag[tid] = 0xffffffffu;
+  if (tid < DFX_NSTAT) sh.stat[tid] = ws->stat[tid];
+  __syncthreads();
+
+  // thread-0-only bookkeeping
+  u64 last_act = wall_clock64();
+  bool acted = true;
+  uint32_t iter = 0, idle = 0;
+  // pending context-switch sample (thread 0): t0 = abort decision, ts = after save
+  u64 sw_t0 = 0, sw_ts = 0;
+  bool sw_pending = false;
+
+  bool pass_progress = false;
+  uint32_t stop = STOP_NONE;
+
+  for (;;) {
+    // ================= control check + SQ probe (thread 0) =================
+    ++iter;
+    if (tid == 0) {
+      uint32_t s = STOP_NONE;
+      if (ld_agent32(&a.dev_ctl[DC_ABORT])) s = STOP_ABORT;
+      if (!s && (((iter & 31u) == 0) || qlen == 0)) {
+        const u64 now = wall_clock64();
+        if (acted) { last_act = now; acted = false; }
+        if (ld_sys32(&a.host_ctl[HC_ABORT])) s = STOP_ABORT;
+        else if (a.watchdog_ticks && qlen > 0 && now - last_act > a.watchdog_ticks) {
+          ws->dbg[0] = ((u64)sh.taskq[0] << 32) | qlen; ws->dbg[1] = ri; ws->dbg[2] = now - last_act;
+          raise_error(a, 1u, wg);
+          s = STOP_ABORT;
+        } else if (a.quit_ticks && now - last_act > a.quit_ticks) s = STOP_QUIT;
+      }
+      uint32_t got = 0;
+      const bool want = (qlen == 0) || !pass_progress || a.order_policy == 1;
+      if (!s && want && qlen < a.max_colls) {
+        DfxSqSlot* e = &sqbase[ri & (D - 1)];
+        const uint32_t gen = (uint32_t)(ri >> a.sq_shift) + 1u;
+        if (__hip_atomic_load(&e->e.ready, __ATOMIC_ACQUIRE, SCOPE_SYSTEM) == gen) got = 1;
+      }
+      sh.ctl_stop = s;
+      sh.ctl_got = got;
+    }
+    __syncthreads();
+    stop = sh.ctl_stop;
+    const uint32_t got = sh.ctl_got;
+    if (stop) break;
+
+    // ================= FetchSQE (Alg. 1 line 2) =================
+    if (got) {
+      DfxSqSlot* e = &sqbase[ri & (D - 1)];
+      if (tid < 6) ((uint4*)&sh.sqe)[tid] = ((const uint4*)&e->e)[tid];
+      __syncthreads();
+      const uint32_t coll = sh.sqe.coll_id;
+      const uint32_t flags = sh.sqe.flags;
+      const uint32_t nchan = sh.sqe.nchan;
+      const bool is_exit = (flags & DFX_SQE_EXIT) != 0;
+      const bool mine = !is_exit && ch < nchan && coll < a.max_colls;
+      if (mine) {
+        // static context of this invocation -> context buffer; restart the sequence, keep the
+        // monotone connector counters of earlier invocations
+        if (tid < 6) ((uint4*)&myctx[coll].st)[tid] = ((const uint4*)&sh.sqe)[tid];
+        if (tid == 6) { myctx[coll].dyn.round = 0; myctx[coll].dyn.prim = 0; myctx[coll].dyn.preempted = 0; }
+        if (tid == 0) {
+          // FIFO ordering: append; priority ordering: keep the queue sorted by priority (stable)
+          uint32_t at = qlen;
+          if (a.order_policy == 1) {
+            const int16_t pr = sh.sqe.priority;
+            while (at > 0 && myctx[sh.taskq[at - 1]].st.priority < pr) { sh.taskq[at] = sh.taskq[at - 1]; --at; }
+          }
+          sh.taskq[at] = (uint16_t)coll;
+          if (sh.slot_tag[coll % DFX_CTX_SLOTS] == coll) sh.slot_tag[coll % DFX_CTX_SLOTS] = 0xffffffffu;
+          if (qlen + 1 > sh.stat[ST_MAXQ]) sh.stat[ST_MAXQ] = qlen + 1;
+        }
+        ++qlen;
+      }
+      if (tid == 0) {
+        // every workgroup of the rank reads every SQE; the last reader frees the slot (Sec. 5)
+        uint32_t* rc = &a.sq_readers[(size_t)rank * D + (ri & (D - 1))];
+        const uint32_t old = __hip_atomic_fetch_add(rc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
+        if (old + 1 == a.cmax) {
+          __hip_atomic_store(rc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
+          __hip_atomic_store(&e->e.ready, 0u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
+        }
+        sh.stat[ST_SQE] += 1;
+        acted = true;
+        sw_pending = false;
+      }
+      ++ri;
+      __syncthreads();
+      if (is_exit) { stop = STOP_EXIT; break; }
+      pass_progress = true;   // a fresh entry counts as progress: walk the queue before fetching again
+      if (!mine) continue;
+    } else if (qlen == 0) {
+      // idle: back off the SQ probe (it may cross PCIe), then meet before the next broadcast
+      ++idle;
+      if (idle < 16) __builtin_amdgcn_s_sleep(8);
+      else if (idle < 64) __builtin_amdgcn_s_sleep(32);
+      else __builtin_amdgcn_s_sleep(127);
+      __syncthreads();
+      continue;
+    }
+    idle = 0;
+
+    // ================= one pass over the task queue (Alg. 1 lines 4-19) =================
+    pass_progress = false;
+    if (tid == 0) sh.stat[ST_PASSES] += 1;
+    uint32_t pos = 0;
+    while (pos < qlen) {
+      const uint32_t coll = sh.taskq[pos];
+      const uint32_t sl = coll % DFX_CTX_SLOTS;
+      // ---- LoadCollectiveContext: HBM context buffer -> LDS slot, 8 lanes x 16 bytes
+      u64 t_lb = 0, t_le = 0;
+      if (tid == 0 && sw_pending) t_lb = wall_clock64();
+      if (sh.slot_tag[sl] != coll) {
+        __syncthreads();   // everyone has read the old tag before it changes
+        if (tid < 8) ((uint4*)&sh.slot[sl])[tid] = ((const uint4*)&myctx[coll])[tid];
+        if (tid == 0) { sh.slot_tag[sl] = coll; sh.stat[ST_LOAD] += 1; }
+        __syncthreads();
+      } else if (tid == 0) sh.stat[ST_HIT] += 1;
+      if (tid == 0 && sw_pending) t_le = wall_clock64();
+
+      const DfxCtxEntry& C = sh.slot[sl];
+      const int kind = C.st.kind, dtype = C.st.dtype, root = C.st.root;
+      const uint32_t eb = (dtype == DT_F32 || dtype == DT_I32) ? 4u : 2u;
+      const uint32_t nprim = C.st.nprim, rounds = C.st.rounds, K = C.st.nslots, nchan = C.st.nchan;
+      const uint32_t slot_bytes = C.st.slot_bytes, slice_elems = C.st.slice_elems;
+      const u64 count = C.st.count, block_elems = C.st.block_elems, part_elems = C.st.part_elems;
+      const char* sendbuf = (const char*)C.st.sendbuf;
+      char* recvbuf = (char*)C.st.recvbuf;
+      uint8_t* conn = a.pool + C.st.conn_off;
+      uint32_t g = C.dyn.round, p = C.dyn.prim;
+      u64 sent = C.dyn.sent, recvd = C.dyn.recvd;
+      const uint32_t preempted_before = C.dyn.preempted;
+
+      // connector geometry: flags first, then slots
+      const uint32_t e_out = rank, e_in = (rank + (uint32_t)R - 1) % (uint32_t)R;
+      u64* tail_out = (u64*)(conn + ((size_t)e_out * nchan + ch) * DFX_FLAG_STRIDE);
+      u64* head_out = tail_out + 8;
+      u64* tail_in = (u64*)(conn + ((size_t)e_in * nchan + ch) * DFX_FLAG_STRIDE);
+      u64* head_in = tail_in + 8;
+      uint8_t* slots = conn + (size_t)R * nchan * DFX_FLAG_STRIDE;
+      uint8_t* fifo_out = slots + ((size_t)e_out * nchan + ch) * K * slot_bytes;
+      uint8_t* fifo_in = slots + ((size_t)e_in * nchan + ch) * K * slot_bytes;
+
+      // SetInitialSpinThreshold (Alg. 1 line 3): largest at the front, halving per position
+      u64 thr = a.spin_init >> (pos < 31 ? pos : 31);
+      if (thr < a.spin_min) thr = a.spin_min;
+
+      bool progressed = false, completed = false;
+      uint32_t res = W_OK;
+      for (;;) {
+        const Prim q = make_prim(kind, R, (int)rank, root, p);
+        // ---- slice geometry (elements relative to the block, clipped to the block's true length)
+        u64 blen = count;
+        if (kind == KIND_AR && R > 1) {
+          const u64 start = (u64)q.cidx * block_elems;
+          blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
+        }
+        u64 lo = (u64)ch * part_elems + (u64)g * slice_elems;
+        u64 hi = lo + slice_elems;
+        const u64 pend = (u64)(ch + 1) * part_elems;
+        if (hi > pend) hi = pend;
+        if (lo > blen) lo = blen;
+        if (hi > blen) hi = blen;
+        const uint32_t bytes = (uint32_t)(hi - lo) * eb;
+        u64 soff = lo, doff = lo;   // element offsets in the send / recv buffer
+        if (kind == KIND_AR && R > 1) { soff += (u64)q.cidx * block_elems; doff = soff; }
+        else if (kind == KIND_RS) soff += (u64)q.cidx * count;
+        else if (kind == KIND_AG) doff += (u64)q.cidx * count;
+
+        // ---- wait phase: wave 0 polls, lane 0 the recv side, lane 1 the send side
+        if (tid < 64) {
+          uint32_t r = W_OK;
+          if (tid == 0 && sw_pending) {   // the first poll of the next collective ends the context switch
+            const u64 t1 = wall_clock64();
+            if (trace) {
+              u64 tot = t1 - sw_t0, sv = sw_ts - sw_t0, ldt = t_le - t_lb;
+              if (tot > 0xffffffu) tot = 0xffffffu;
+              if (sv > 0xfffffu) sv = 0xfffffu;
+              if (ldt > 0xfffffu) ldt = 0xfffffu;
+              trace[trace_n % DFX_TRACE_N] = tot | (sv << 24) | (ldt << 44);
+              ++trace_n;
+            }
+            sw_pending = false;
+          }
+          if (q.recv || q.send) {
+            u64 n = 0;
+            for (;;) {
+              bool ok = true;
+              if (tid == 0 && q.recv) ok = ld_agent64(tail_in) > recvd;
+              if (tid == 1 && q.send) ok = (sent - ld_agent64(head_out)) < (u64)K;
+              ++n;
+              if (__ballot(!ok) == 0) break;
+              if (a.preempt && n >= thr) { r = W_TIMEOUT; break; }
+              if ((n & 255u) == 0) {
+                uint32_t s = 0;
+                if (tid == 0) {
+                  if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) s = 1;
+                  else if (a.watchdog_ticks) {
+                    const u64 now = wall_clock64();
+                    if (acted) { last_act = now; acted = false; }
+                    if (now - last_act > a.watchdog_ticks) {
+                      ws->dbg[0] = ((u64)coll << 32) | qlen; ws->dbg[1] = ((u64)g << 32) | p; ws->dbg[2] = sent; ws->dbg[3] = recvd;
+                      ws->dbg[4] = ld_agent64(tail_in); ws->dbg[5] = ld_agent64(head_out); ws->dbg[6] = ri; ws->dbg[7] = now - last_act;
+                      raise_error(a, 2u, wg);
+                      s = 1;
+                    }
+                  }
+                }
+                if (__ballot(s != 0) != 0) { r = W_STOP; break; }
+              }
+              __builtin_amdgcn_s_sleep(1);
+            }
+            if (tid == 0) sh.stat[ST_POLLS] += n;
+          }
+          if (tid == 0) sh.wres = r;
+        }
+        __syncthreads();
+        res = sh.wres;
+        if (res != W_OK) break;
+        // every wave invalidates before its own loads of the slot (the poll was wave 0's)
+        if (q.recv) fence_acquire_agent();
+
+        // ---- data phase: one slice
+        {
+          const void* s0; const void* s1 = nullptr; void* d0; void* d1 = nullptr;
+          const char* in_slot = (const char*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes);
+          char* out_slot = (char*)(fifo_out + (size_t)(sent & (K - 1)) * slot_bytes);
+          if (q.recv) { s0 = in_slot; if (q.from_send) s1 = sendbuf + soff * eb; }
+          else s0 = sendbuf + soff * eb;
+          if (q.to_recv) { d0 = recvbuf + doff * eb; if (q.send) d1 = out_slot; }
+          else d0 = out_slot;
+          if (bytes) run_data_phase(dtype, q.nsrc, q.ndst, s0, s1, d0, d1, bytes);
+        }
+        drain_and_barrier();
+        if (tid == 0) {
+          fence_release_agent();
+          if (q.send) st_agent64(tail_out, sent + 1);
+          if (q.recv) st_agent64(head_in, recvd + 1);
+          sh.stat[ST_PRIMS] += 1;
+          acted = true;
+        }
+        if (q.send) ++sent;
+        if (q.recv) ++recvd;
+        if (++p == nprim) { p = 0; ++g; }
+        progressed = true;
+        // AdaptivelyAdjustSpinThreshold (Alg. 1 line 9)
+        thr *= a.spin_boost;
+        if (thr > a.spin_max) thr = a.spin_max;
+        if (g == rounds) { completed = true; break; }
+      }
+
+      if (progressed) pass_progress = true;
+
+      if (completed) {
+        // ---- CollectiveSuccess -> completion counter -> maybe SendCQE (Sec. 5)
+        if (tid == 0) {
+          DfxDyn d; d.round = 0; d.prim = 0; d.sent = sent; d.recvd = recvd; d.preempted = 0; d.pad = 0;
+          sh.slot[sl].dyn = d;
+          myctx[coll].dyn = d;
+          fence_release_system();   // results in the recv buffer are visible to host and later kernels
+          uint32_t* dc = &a.done_cnt[(size_t)rank * a.max_colls + coll];
+          const uint32_t old = __hip_atomic_fetch_add(dc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
+          if (old + 1 == nchan) {
+            __hip_atomic_store(dc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
+            const u64 v = (1ull << 63) | ((u64)(C.st.seq & 0x7fffffffu) << 32) | coll;
+            const uint32_t t = __hip_atomic_fetch_add(&a.cq_ticket[rank], 1u, __ATOMIC_RELAXED, SCOPE_AGENT);
+            uint32_t k = 0;
+            for (;;) {   // optimized CQ (Sec. 5): one CAS of the id into a writable slot
+              u64 expected = 0;
+              if (__hip_atomic_compare_exchange_strong(&cqbase[(t + k) % a.cq_slots], &expected, v, __ATOMIC_RELEASE,
+                                                       __ATOMIC_RELAXED, SCOPE_SYSTEM))
+                break;
+              ++k;
+              if ((k % a.cq_slots) == 0) {
+                if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) break;
+                __builtin_amdgcn_s_sleep(50);
+              }
+            }
+            sh.stat[ST_CQE] += 1;
+          }
+          sw_pending = false;
+        }
+        // the entry leaves the queue; later entries move up, the position stays (Sec. 4.3)
+        --qlen;
+        __syncthreads();
+        for (uint32_t base = pos; base < qlen; base += NT) {
+          const uint32_t i = base + tid;
+          uint16_t v = 0;
+          if (i < qlen) v = sh.taskq[i + 1];
+          __syncthreads();
+          if (i < qlen) sh.taskq[i] = v;
+          __syncthreads();
+        }
+      } else {
+        // ---- PreemptCollective + SaveCollectiveContext (lazy: only if it progressed)
+        if (tid == 0) {
+          const bool tr = a.trace_on && res == W_TIMEOUT && pos + 1 < qlen;
+          if (tr) sw_t0 = wall_clock64();
+          if (res == W_TIMEOUT) sh.stat[ST_PREEMPT] += 1;
+          if (progressed) {
+            DfxDyn d; d.round = g; d.prim = p; d.sent = sent; d.recvd = recvd;
+            d.preempted = preempted_before + 1; d.pad = 0;
+            sh.slot[sl].dyn = d;
+            myctx[coll].dyn = d;
+            sh.stat[ST_SAVE] += 1;
+          } else if (res == W_TIMEOUT) sh.stat[ST_LAZY] += 1;
+          if (tr) { sw_ts = wall_clock64(); sw_pending = true; }
+        }
+        __syncthreads();
+        if (res == W_STOP) { stop = STOP_ABORT; break; }
+        ++pos;
+      }
+    }
+    if (stop) break;
+  }
+
+  // ================= leave: persist what the next launch needs =================
+  __syncthreads();
+  for (uint32_t i = tid; i < qlen; i += NT) qstore[i] = sh.taskq[i];
+  if (tid == 0) {
+    if (stop == STOP_QUIT) sh.stat[ST_QUITS] += 1;
+    ws->read_index = ri;
+    ws->qlen = qlen;
+    ws->trace_n = trace_n;
+  }
+  __syncthreads();
+  if (tid < DFX_NSTAT) ws->stat[tid] = sh.stat[tid];
+}
+
+// Plain copy kernel of known traffic: calibrates the HBM byte counters of the profiler.
+extern "C" __global__ void __launch_bounds__(256) dfx_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t nvec) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < nvec; i += stride) dst[i] = src[i];
+}
+
+// ------------------------------------------------------------------------------------------
+// launch helpers for the host library (kept in this translation unit with the kernels)
+// ------------------------------------------------------------------------------------------
+hipError_t dfx_daemon_occupancy(int* blocks_per_cu) {
+  return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, dfx_daemon_kernel, DFX_WG_THREADS, 0);
+}
+
+hipError_t dfx_daemon_launch(uint32_t nwg, hipStream_t stream, const DfxDaemonArgs& a) {
+  hipLaunchKernelGGL(dfx_daemon_kernel, dim3(nwg), dim3(DFX_WG_THREADS), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t dfx_copy_launch(const void* src, void* dst, size_t bytes, hipStream_t stream) {
+  hipLaunchKernelGGL(dfx_copy_kernel, dim3(2048), dim3(256), 0, stream, (const uint4*)src, (uint4*)dst, bytes >> 4);
+  return hipGetLastError();
+}

@@ -1,0 +1,675 @@
+// Host side of the dfx C ABI: SQ/CQ management, collective registration, event-driven daemon
+// start, completion polling.  The "CPU part" of the paper's Fig. 3 (Sec. 3.1), for R virtual
+// ranks in one process.  No computation of the collectives happens here.
+#include <hip/hip_runtime.h>
+#include <immintrin.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <thread>
+#include <vector>
+
+#include "../../include/dfx.h"
+#include "dfx_internal.h"
+
+// defined next to the kernels
+hipError_t dfx_daemon_occupancy(int* blocks_per_cu);
+hipError_t dfx_daemon_launch(uint32_t nwg, hipStream_t stream, const DfxDaemonArgs& a);
+hipError_t dfx_copy_launch(const void* src, void* dst, size_t bytes, hipStream_t stream);
+
+namespace {
+
+struct CollInfo {
+  bool prepared = false;
+  DfxStatic tmpl;   // everything but buffers, seq and ready
+};
+
+struct RankState {
+  std::mutex mu;
+  uint64_t sq_tail = 0;                 // entries written to this rank's SQ
+  std::vector<uint32_t> sub;            // per coll: submissions so far
+  std::vector<uint32_t> done;           // per coll: completions seen
+  std::deque<dfx_cqe> ready;            // completions not yet handed to the caller
+  std::atomic<uint64_t> n_sub{0}, n_cqe{0};
+};
+
+}  // namespace
+
+struct dfx_ctx {
+  dfx_config cfg;
+  int R = 0;
+  int device = 0;
+  uint32_t nwg = 0;
+  uint32_t sq_shift = 0;
+  hipStream_t stream = nullptr;      // daemon stream
+  bool own_stream = false;
+  hipStream_t side = nullptr;        // private non-blocking stream for small copies
+  hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+  bool launched = false;             // a launch has been enqueued whose end was not yet observed
+  uint64_t launches = 0, launches_done = 0;
+  float last_ms = 0.f;
+  double tick_us = 0.01;             // wall_clock64 tick in microseconds
+  std::mutex launch_mu;
+  std::atomic<bool> aborted{false};
+  int last_hip = 0;
+  bool sq_device = false;
+
+  // host-visible memory
+  void* qmem_sq = nullptr;           // SQ ring + host_ctl (pinned host or fine-grained device)
+  void* qmem_cq = nullptr;           // CQ slot arrays (pinned host)
+  DfxSqSlot* sq = nullptr;
+  uint32_t* host_ctl = nullptr;
+  uint64_t* cq = nullptr;
+  // device memory
+  uint32_t* sq_readers = nullptr;
+  uint32_t* done_cnt = nullptr;
+  uint32_t* cq_ticket = nullptr;
+  uint32_t* dev_ctl = nullptr;
+  uint8_t* pool = nullptr;
+  DfxCtxEntry* ctxbuf = nullptr;
+  DfxWgState* wgstate = nullptr;
+  uint16_t* taskq_store = nullptr;
+  uint64_t* trace = nullptr;
+  void* pinned_tmp = nullptr;        // staging for stats reads
+  size_t pinned_tmp_bytes = 0;
+
+  uint64_t pool_used = 0;
+  std::vector<CollInfo> colls;
+  std::vector<RankState*> ranks;
+};
+
+namespace {
+
+#define HIPCHK(ctx, call)                        \
+  do {                                           \
+    hipError_t e_ = (call);                      \
+    if (e_ != hipSuccess) {                      \
+      (ctx)->last_hip = (int)e_;                 \
+      return DFX_ERR_HIP;                        \
+    }                                            \
+  } while (0)
+
+inline uint64_t now_ns() {
+  return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
+             std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+inline uint32_t elem_bytes(int dt) { return (dt == DFX_F32 || dt == DFX_I32) ? 4u : 2u; }
+inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+inline uint64_t round_up(uint64_t a, uint64_t b) { return ceil_div(a, b) * b; }
+inline bool is_pow2(uint32_t x) { return x && !(x & (x - 1)); }
+
+void free_all(dfx_ctx* c) {
+  if (c->qmem_sq) { if (c->sq_device) (void)hipFree(c->qmem_sq); else (void)hipHostFree(c->qmem_sq); }
+  if (c->qmem_cq) (void)hipHostFree(c->qmem_cq);
+  if (c->pinned_tmp) (void)hipHostFree(c->pinned_tmp);
+  void* dev[] = {c->sq_readers, c->done_cnt, c->cq_ticket, c->dev_ctl, c->pool, c->ctxbuf, c->wgstate, c->taskq_store, c->trace};
+  for (void* p : dev) if (p) (void)hipFree(p);
+  if (c->ev_start) (void)hipEventDestroy(c->ev_start);
+  if (c->ev_stop) (void)hipEventDestroy(c->ev_stop);
+  if (c->side) (void)hipStreamDestroy(c->side);
+  if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
+  for (RankState* r : c->ranks) delete r;
+  delete c;
+}
+
+// Observe the end of the last launch, if it ended.  Caller holds launch_mu.
+// Returns true if no daemon launch is in flight afterwards.
+int reap_locked(dfx_ctx* c, bool* idle) {
+  *idle = true;
+  if (!c->launched) return DFX_OK;
+  hipError_t q = hipEventQuery(c->ev_stop);
+  if (q == hipErrorNotReady) { *idle = false; return DFX_OK; }
+  if (q != hipSuccess) { c->last_hip = (int)q; return DFX_ERR_HIP; }
+  c->launched = false;
+  c->launches_done++;
+  float ms = 0.f;
+  if (hipEventElapsedTime(&ms, c->ev_start, c->ev_stop) == hipSuccess) c->last_ms = ms;
+  // the grid has drained: a plain copy on the private stream is safe
+  uint32_t* ctl = (uint32_t*)c->pinned_tmp;
+  HIPCHK(c, hipMemcpyAsync(ctl, c->dev_ctl, DC_N * sizeof(uint32_t), hipMemcpyDeviceToHost, c->side));
+  HIPCHK(c, hipStreamSynchronize(c->side));
+  if (ctl[DC_ABORT]) c->aborted.store(true);
+  return DFX_OK;
+}
+
+int launch_locked(dfx_ctx* c) {
+  DfxDaemonArgs a;
+  memset(&a, 0, sizeof(a));
+  a.sq = c->sq; a.cq = c->cq; a.host_ctl = c->host_ctl;
+  a.sq_readers = c->sq_readers; a.done_cnt = c->done_cnt; a.cq_ticket = c->cq_ticket; a.dev_ctl = c->dev_ctl;
+  a.pool = c->pool; a.ctxbuf = c->ctxbuf; a.wgstate = c->wgstate; a.taskq_store = c->taskq_store; a.trace = c->trace;
+  a.R = (uint32_t)c->R; a.cmax = c->cfg.max_channels; a.max_colls = c->cfg.max_colls;
+  a.sq_depth = c->cfg.sq_depth; a.sq_shift = c->sq_shift; a.cq_slots = c->cfg.cq_slots;
+  a.spin_init = c->cfg.spin_init; a.spin_min = c->cfg.spin_min; a.spin_max = c->cfg.spin_max;
+  a.spin_boost = c->cfg.spin_boost; a.preempt = c->cfg.preempt;
+  a.wg_map = c->cfg.wg_map; a.order_policy = c->cfg.order_policy; a.trace_on = c->cfg.trace;
+  a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
+  a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
+  HIPCHK(c, hipEventRecord(c->ev_start, c->stream));
+  HIPCHK(c, dfx_daemon_launch(c->nwg, c->stream, a));
+  HIPCHK(c, hipEventRecord(c->ev_stop, c->stream));
+  c->launched = true;
+  c->launches++;
+  return DFX_OK;
+}
+
+// Event-driven start (Sec. 4.4): make sure a daemon is running or queued.
+int ensure_running(dfx_ctx* c) {
+  std::lock_guard<std::mutex> lk(c->launch_mu);
+  bool idle = false;
+  int rc = reap_locked(c, &idle);
+  if (rc != DFX_OK) return rc;
+  if (c->aborted.load()) return DFX_ERR_ABORTED;
+  if (!idle) return DFX_OK;
+  return launch_locked(c);
+}
+
+bool outstanding(dfx_ctx* c) {
+  for (RankState* r : c->ranks)
+    if (r->n_cqe.load(std::memory_order_relaxed) < r->n_sub.load(std::memory_order_relaxed)) return true;
+  return false;
+}
+
+// Write one SQE (caller holds the rank's mutex).
+int push_sqe(dfx_ctx* c, int rank, const DfxStatic& e) {
+  RankState* rs = c->ranks[rank];
+  const uint32_t D = c->cfg.sq_depth;
+  DfxSqSlot* slot = &c->sq[(size_t)rank * D + (rs->sq_tail & (D - 1))];
+  volatile uint32_t* ready = &slot->e.ready;
+  if (*ready != 0) return DFX_ERR_SQ_FULL;   // not yet read by every workgroup of the rank
+  std::atomic_thread_fence(std::memory_order_acquire);
+  DfxStatic tmp = e;
+  tmp.ready = 0;
+  // body first (six 16-byte stores), then the generation word
+  const __m128i* src = (const __m128i*)&tmp;
+  __m128i* dst = (__m128i*)&slot->e;
+  for (int i = 0; i < 5; ++i) _mm_storeu_si128(dst + i, _mm_loadu_si128(src + i));
+  uint32_t* lastw = (uint32_t*)(dst + 5);
+  const uint32_t* lasts = (const uint32_t*)(src + 5);
+  lastw[0] = lasts[0]; lastw[1] = lasts[1]; lastw[2] = lasts[2];
+  std::atomic_thread_fence(std::memory_order_release);
+  _mm_sfence();   // orders write-combined stores when the SQ lives behind the PCIe BAR
+  *ready = (uint32_t)(rs->sq_tail >> c->sq_shift) + 1u;
+  _mm_sfence();
+  rs->sq_tail++;
+  return DFX_OK;
+}
+
+// Move every valid CQ slot of a rank into its ready list (caller holds the rank's mutex).
+void drain_cq(dfx_ctx* c, int rank) {
+  RankState* rs = c->ranks[rank];
+  volatile uint64_t* q = c->cq + (size_t)rank * c->cfg.cq_slots;
+  for (uint32_t i = 0; i < c->cfg.cq_slots; ++i) {
+    uint64_t v = q[i];
+    if (!(v >> 63)) continue;
+    std::atomic_thread_fence(std::memory_order_acquire);
+    q[i] = 0;   // slot writable again
+    dfx_cqe e;
+    e.coll_id = (uint32_t)(v & 0xffffffffu);
+    e.seq = (uint32_t)((v >> 32) & 0x7fffffffu);
+    if (e.coll_id < rs->done.size()) rs->done[e.coll_id]++;
+    rs->ready.push_back(e);
+    rs->n_cqe.fetch_add(1, std::memory_order_relaxed);
+  }
+}
+
+inline void backoff(uint32_t& spins) {
+  ++spins;
+  if (spins < 2000) _mm_pause();
+  else std::this_thread::yield();
+}
+
+}  // namespace
+
+extern "C" {
+
+int dfx_config_default(dfx_config* cfg) {
+  if (!cfg) return DFX_ERR_INVALID_ARG;
+  memset(cfg, 0, sizeof(*cfg));
+  cfg->struct_bytes = (uint32_t)sizeof(dfx_config);
+  cfg->max_channels = 32;
+  cfg->max_colls = 2048;
+  cfg->sq_depth = 256;
+  cfg->cq_slots = 256;
+  cfg->nslots = 4;
+  cfg->slot_bytes = 64u << 10;
+  cfg->chan_min_bytes = 16u << 10;
+  cfg->spin_init = 20000;
+  cfg->spin_min = 32;
+  cfg->spin_max = 400000;
+  cfg->spin_boost = 20;
+  cfg->preempt = 1;
+  cfg->watchdog_ms = 10000;
+  cfg->quit_idle_us = 2000;
+  cfg->sq_in_device = 0;
+  cfg->wg_map = 0;
+  cfg->order_policy = 0;
+  cfg->trace = 0;
+  cfg->pool_bytes = 2ull << 30;
+  return DFX_OK;
+}
+
+int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream) {
+  if (!out) return DFX_ERR_INVALID_ARG;
+  *out = nullptr;
+  dfx_config cfg;
+  dfx_config_default(&cfg);
+  if (ucfg) {
+    if (ucfg->struct_bytes != sizeof(dfx_config)) return DFX_ERR_INVALID_ARG;
+    cfg = *ucfg;
+  }
+  if (nranks < 1 || nranks > 64) return DFX_ERR_INVALID_ARG;
+  if (cfg.max_channels < 1 || cfg.max_channels > 1024) return DFX_ERR_INVALID_ARG;
+  if (cfg.max_colls < 1 || cfg.max_colls > DFX_MAX_COLLS) return DFX_ERR_INVALID_ARG;
+  if (!is_pow2(cfg.sq_depth) || cfg.sq_depth < 2) return DFX_ERR_INVALID_ARG;
+  if (cfg.cq_slots < 1) return DFX_ERR_INVALID_ARG;
+  if (!is_pow2(cfg.nslots) || cfg.nslots < 2 || cfg.nslots > 64) return DFX_ERR_INVALID_ARG;
+  if (cfg.slot_bytes < 16 || (cfg.slot_bytes & 15u)) return DFX_ERR_INVALID_ARG;
+  if (cfg.chan_min_bytes < 16) return DFX_ERR_INVALID_ARG;
+  if (cfg.spin_min < 1 || cfg.spin_init < 1 || cfg.spin_boost < 1 || cfg.spin_max < cfg.spin_min) return DFX_ERR_INVALID_ARG;
+  if (cfg.sq_in_device > 2 || cfg.wg_map > 1 || cfg.order_policy > 1) return DFX_ERR_INVALID_ARG;
+  if (cfg.pool_bytes < (1u << 20)) return DFX_ERR_INVALID_ARG;
+
+  dfx_ctx* c = new (std::nothrow) dfx_ctx();
+  if (!c) return DFX_ERR_NO_RESOURCES;
+  c->cfg = cfg;
+  c->R = nranks;
+  c->nwg = (uint32_t)nranks * cfg.max_channels;
+  while ((1u << c->sq_shift) < cfg.sq_depth) c->sq_shift++;
+
+#define INITCHK(call)                                      \
+  do {                                                     \
+    hipError_t e_ = (call);                                \
+    if (e_ != hipSuccess) { free_all(c); return DFX_ERR_HIP; } \
+  } while (0)
+
+  INITCHK(hipGetDevice(&c->device));
+  // co-residency: every workgroup spins on flags written by others, so the whole grid must fit
+  int occ = 0, ncu = 0, wall_khz = 0, large_bar = 0;
+  INITCHK(dfx_daemon_occupancy(&occ));
+  INITCHK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device));
+  if (occ < 1 || (uint64_t)c->nwg > (uint64_t)occ * (uint64_t)ncu) { free_all(c); return DFX_ERR_NO_RESOURCES; }
+  if (hipDeviceGetAttribute(&wall_khz, hipDeviceAttributeWallClockRate, c->device) == hipSuccess && wall_khz > 0)
+    c->tick_us = 1000.0 / (double)wall_khz;
+  (void)hipDeviceGetAttribute(&large_bar, hipDeviceAttributeIsLargeBar, c->device);
+  c->sq_device = (cfg.sq_in_device == 1) || (cfg.sq_in_device == 2 && large_bar);
+  if (cfg.sq_in_device == 1 && !large_bar) { free_all(c); return DFX_ERR_NO_RESOURCES; }
+
+  if (hip_stream) c->stream = (hipStream_t)hip_stream;
+  else { INITCHK(hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking)); c->own_stream = true; }
+  INITCHK(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+  INITCHK(hipEventCreate(&c->ev_start));
+  INITCHK(hipEventCreate(&c->ev_stop));
+
+  const size_t R = (size_t)nranks;
+  const size_t sq_bytes = R * cfg.sq_depth * sizeof(DfxSqSlot) + HC_N * sizeof(uint32_t) + 256;
+  const size_t cq_bytes = R * cfg.cq_slots * sizeof(uint64_t);
+  if (c->sq_device) {
+    INITCHK(hipExtMallocWithFlags(&c->qmem_sq, sq_bytes, hipDeviceMallocFinegrained));
+    INITCHK(hipMemset(c->qmem_sq, 0, sq_bytes));
+  } else {
+    INITCHK(hipHostMalloc(&c->qmem_sq, sq_bytes, hipHostMallocMapped | hipHostMallocCoherent));
+    memset(c->qmem_sq, 0, sq_bytes);
+  }
+  INITCHK(hipHostMalloc(&c->qmem_cq, cq_bytes, hipHostMallocMapped | hipHostMallocCoherent));
+  memset(c->qmem_cq, 0, cq_bytes);
+  c->sq = (DfxSqSlot*)c->qmem_sq;
+  c->host_ctl = (uint32_t*)((char*)c->qmem_sq + round_up(R * cfg.sq_depth * sizeof(DfxSqSlot), 256));
+  c->cq = (uint64_t*)c->qmem_cq;
+
+  auto dalloc = [&](void** p, size_t bytes) -> hipError_t {
+    hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) return e;
+    return hipMemset(*p, 0, bytes);
+  };
+  INITCHK(dalloc((void**)&c->sq_readers, R * cfg.sq_depth * sizeof(uint32_t)));
+  INITCHK(dalloc((void**)&c->done_cnt, R * cfg.max_colls * sizeof(uint32_t)));
+  INITCHK(dalloc((void**)&c->cq_ticket, R * sizeof(uint32_t) + 64));
+  INITCHK(dalloc((void**)&c->dev_ctl, DC_N * sizeof(uint32_t)));
+  INITCHK(dalloc((void**)&c->pool, cfg.pool_bytes));
+  INITCHK(dalloc((void**)&c->ctxbuf, (size_t)c->nwg * cfg.max_colls * sizeof(DfxCtxEntry)));
+  INITCHK(dalloc((void**)&c->wgstate, (size_t)c->nwg * sizeof(DfxWgState)));
+  INITCHK(dalloc((void**)&c->taskq_store, (size_t)c->nwg * cfg.max_colls * sizeof(uint16_t)));
+  if (cfg.trace) INITCHK(dalloc((void**)&c->trace, (size_t)c->nwg * DFX_TRACE_N * sizeof(uint64_t)));
+  c->pinned_tmp_bytes = std::max((size_t)c->nwg * sizeof(DfxWgState), (size_t)DFX_TRACE_N * sizeof(uint64_t) * 64);
+  INITCHK(hipHostMalloc(&c->pinned_tmp, c->pinned_tmp_bytes, hipHostMallocDefault));
+  INITCHK(hipDeviceSynchronize());
+#undef INITCHK
+
+  c->colls.resize(cfg.max_colls);
+  for (int r = 0; r < nranks; ++r) {
+    RankState* rs = new RankState();
+    rs->sub.assign(cfg.max_colls, 0);
+    rs->done.assign(cfg.max_colls, 0);
+    c->ranks.push_back(rs);
+  }
+  *out = c;
+  return DFX_OK;
+}
+
+int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype dtype, dfx_op op, int root, int priority) {
+  if (!c) return DFX_ERR_INVALID_ARG;
+  if (coll_id < 0 || (uint32_t)coll_id >= c->cfg.max_colls) return DFX_ERR_INVALID_ARG;
+  if ((int)kind < 0 || (int)kind > 3 || (int)dtype < 0 || (int)dtype > 3 || op != DFX_SUM) return DFX_ERR_INVALID_ARG;
+  if (kind == DFX_BROADCAST && (root < 0 || root >= c->R)) return DFX_ERR_INVALID_ARG;
+  if (priority < -32768 || priority > 32767) return DFX_ERR_INVALID_ARG;
+  if (count > (1ull << 40)) return DFX_ERR_INVALID_ARG;
+  CollInfo& ci = c->colls[coll_id];
+  if (ci.prepared) return DFX_ERR_INVALID_ARG;
+
+  const uint64_t R = (uint64_t)c->R;
+  const uint32_t eb = elem_bytes(dtype);
+  const uint64_t per16 = 16 / eb;
+  // ring chunk: all-reduce cuts the message into R contiguous chunks of ceil(N/R) elements
+  // rounded up to 16 bytes; the other kinds move blocks of `count`
+  uint64_t block = count;
+  if (kind == DFX_ALLREDUCE && R > 1) block = round_up(ceil_div(count, R), per16);
+  const uint64_t block_bytes = block * eb;
+  uint64_t C = ceil_div(std::max<uint64_t>(block_bytes, 1), c->cfg.chan_min_bytes);
+  C = std::min<uint64_t>(std::max<uint64_t>(C, 1), c->cfg.max_channels);
+  uint64_t part = round_up(std::max<uint64_t>(ceil_div(block, C), 1), per16);
+  C = std::max<uint64_t>(1, ceil_div(block, part));   // drop channels that would be empty
+  uint64_t slot_bytes = std::min<uint64_t>(c->cfg.slot_bytes, round_up(part * eb, 16));
+  const uint64_t slice_elems = slot_bytes / eb;
+  const uint64_t rounds = std::max<uint64_t>(1, ceil_div(part, slice_elems));
+  if (rounds > 0xffffffffull) return DFX_ERR_INVALID_ARG;
+  const uint64_t K = c->cfg.nslots;
+  const uint64_t conn_bytes = round_up(R * C * DFX_FLAG_STRIDE + R * C * K * slot_bytes, 256);
+  if (c->pool_used + conn_bytes > c->cfg.pool_bytes) return DFX_ERR_NO_RESOURCES;
+
+  DfxStatic t;
+  memset(&t, 0, sizeof(t));
+  t.coll_id = (uint32_t)coll_id;
+  t.count = count;
+  t.conn_off = c->pool_used;
+  t.block_elems = block;
+  t.part_elems = part;
+  t.slice_elems = (uint32_t)slice_elems;
+  t.rounds = (uint32_t)rounds;
+  t.slot_bytes = (uint32_t)slot_bytes;
+  t.nslots = (uint16_t)K;
+  t.nchan = (uint16_t)C;
+  t.kind = (uint8_t)kind; t.dtype = (uint8_t)dtype; t.op = (uint8_t)op; t.root = (uint8_t)(kind == DFX_BROADCAST ? root : 0);
+  t.priority = (int16_t)priority;
+  if (R == 1) t.nprim = 1;
+  else if (kind == DFX_ALLREDUCE) t.nprim = (uint32_t)(2 * R - 1);
+  else if (kind == DFX_BROADCAST) t.nprim = 1;
+  else t.nprim = (uint32_t)R;
+  c->pool_used += conn_bytes;
+  ci.tmpl = t;
+  ci.prepared = true;
+  return DFX_OK;
+}
+
+int dfx_coll_info(dfx_ctx* c, int coll_id, uint32_t* nchan, uint32_t* slot_bytes, uint32_t* rounds, uint32_t* nprim) {
+  if (!c || coll_id < 0 || (uint32_t)coll_id >= c->cfg.max_colls) return DFX_ERR_INVALID_ARG;
+  const CollInfo& ci = c->colls[coll_id];
+  if (!ci.prepared) return DFX_ERR_NOT_PREPARED;
+  if (nchan) *nchan = ci.tmpl.nchan;
+  if (slot_bytes) *slot_bytes = ci.tmpl.slot_bytes;
+  if (rounds) *rounds = ci.tmpl.rounds;
+  if (nprim) *nprim = ci.tmpl.nprim;
+  return DFX_OK;
+}
+
+int dfx_submit(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* recvbuf) {
+  if (!c || rank < 0 || rank >= c->R) return DFX_ERR_INVALID_ARG;
+  if (coll_id < 0 || (uint32_t)coll_id >= c->cfg.max_colls) return DFX_ERR_INVALID_ARG;
+  if (c->aborted.load()) return DFX_ERR_ABORTED;
+  const CollInfo& ci = c->colls[coll_id];
+  if (!ci.prepared) return DFX_ERR_NOT_PREPARED;
+  if (!sendbuf || !recvbuf || ((uintptr_t)sendbuf & 15u) || ((uintptr_t)recvbuf & 15u)) return DFX_ERR_INVALID_ARG;
+  RankState* rs = c->ranks[rank];
+  int rc;
+  {
+    std::lock_guard<std::mutex> lk(rs->mu);
+    if (rs->sub[coll_id] != rs->done[coll_id]) {
+      drain_cq(c, rank);
+      if (rs->sub[coll_id] != rs->done[coll_id]) return DFX_ERR_BUSY;
+    }
+    DfxStatic e = ci.tmpl;
+    e.seq = rs->sub[coll_id];
+    e.sendbuf = (uint64_t)(uintptr_t)sendbuf;
+    e.recvbuf = (uint64_t)(uintptr_t)recvbuf;
+    rc = push_sqe(c, rank, e);
+    if (rc == DFX_OK) {
+      rs->sub[coll_id]++;
+      rs->n_sub.fetch_add(1, std::memory_order_relaxed);
+    }
+  }
+  // start the daemon on SQE insertion; also when the SQ is full (a quit daemon frees no slots)
+  int rr = ensure_running(c);
+  if (rr != DFX_OK) return rr;
+  return rc;
+}
+
+int dfx_poll(dfx_ctx* c, int rank, dfx_cqe* out, int max) {
+  if (!c || rank < 0 || rank >= c->R || (max > 0 && !out) || max < 0) return DFX_ERR_INVALID_ARG;
+  RankState* rs = c->ranks[rank];
+  int n = 0;
+  {
+    std::lock_guard<std::mutex> lk(rs->mu);
+    drain_cq(c, rank);
+    while (n < max && !rs->ready.empty()) { out[n++] = rs->ready.front(); rs->ready.pop_front(); }
+  }
+  if (outstanding(c)) {
+    int rr = ensure_running(c);
+    if (rr != DFX_OK && n == 0) return rr == DFX_ERR_ABORTED ? DFX_ERR_TIMEOUT : rr;
+  }
+  return n;
+}
+
+int dfx_wait(dfx_ctx* c, int rank, int coll_id, uint64_t timeout_ns) {
+  if (!c || rank < 0 || rank >= c->R) return DFX_ERR_INVALID_ARG;
+  if (coll_id < 0 || (uint32_t)coll_id >= c->cfg.max_colls) return DFX_ERR_INVALID_ARG;
+  RankState* rs = c->ranks[rank];
+  const uint64_t t0 = now_ns();
+  uint32_t spins = 0;
+  for (;;) {
+    {
+      std::lock_guard<std::mutex> lk(rs->mu);
+      drain_cq(c, rank);
+      if (rs->sub[coll_id] == rs->done[coll_id]) {
+        for (auto it = rs->ready.begin(); it != rs->ready.end(); ++it)
+          if (it->coll_id == (uint32_t)coll_id) { rs->ready.erase(it); break; }
+        return DFX_OK;
+      }
+    }
+    if ((spins & 63u) == 0) {
+      int rr = ensure_running(c);
+      if (rr == DFX_ERR_ABORTED) return DFX_ERR_TIMEOUT;
+      if (rr != DFX_OK) return rr;
+      if (now_ns() - t0 > timeout_ns) return DFX_ERR_TIMEOUT;
+    }
+    backoff(spins);
+  }
+}
+
+int dfx_wait_all(dfx_ctx* c, uint64_t timeout_ns) {
+  if (!c) return DFX_ERR_INVALID_ARG;
+  const uint64_t t0 = now_ns();
+  uint32_t spins = 0;
+  for (;;) {
+    bool all = true;
+    for (int r = 0; r < c->R; ++r) {
+      RankState* rs = c->ranks[r];
+      std::lock_guard<std::mutex> lk(rs->mu);
+      drain_cq(c, r);
+      if (rs->n_cqe.load() < rs->n_sub.load()) all = false;
+      else rs->ready.clear();
+    }
+    if (all) return DFX_OK;
+    if ((spins & 63u) == 0) {
+      int rr = ensure_running(c);
+      if (rr == DFX_ERR_ABORTED) return DFX_ERR_TIMEOUT;
+      if (rr != DFX_OK) return rr;
+      if (now_ns() - t0 > timeout_ns) return DFX_ERR_TIMEOUT;
+    }
+    backoff(spins);
+  }
+}
+
+int dfx_start(dfx_ctx* c) {
+  if (!c) return DFX_ERR_INVALID_ARG;
+  return ensure_running(c);
+}
+
+int dfx_stop(dfx_ctx* c) {
+  if (!c) return DFX_ERR_INVALID_ARG;
+  {
+    std::lock_guard<std::mutex> lk(c->launch_mu);
+    bool idle = false;
+    int rc = reap_locked(c, &idle);
+    if (rc != DFX_OK) return rc;
+    if (idle) return DFX_OK;
+  }
+  // exiting SQE to every rank (Sec. 4.4); a full SQ is retried while the daemon drains it
+  const uint64_t t0 = now_ns();
+  bool forced = false;
+  for (int r = 0; r < c->R && !forced; ++r) {
+    DfxStatic e;
+    memset(&e, 0, sizeof(e));
+    e.flags = DFX_SQE_EXIT;
+    e.coll_id = 0xffffffffu;
+    for (;;) {
+      int rc;
+      { std::lock_guard<std::mutex> lk(c->ranks[r]->mu); rc = push_sqe(c, r, e); }
+      if (rc == DFX_OK) break;
+      if (hipEventQuery(c->ev_stop) != hipErrorNotReady) break;      // daemon already gone
+      if (now_ns() - t0 > 2000000000ull) { forced = true; break; }
+      std::this_thread::yield();
+    }
+  }
+  // wait for the grid to drain; if it does not (e.g. non-preemptive waits), raise the abort word
+  for (;;) {
+    hipError_t q = hipEventQuery(c->ev_stop);
+    if (q != hipErrorNotReady) break;
+    if (!forced && now_ns() - t0 > 3000000000ull) forced = true;
+    if (forced) {
+      *(volatile uint32_t*)&c->host_ctl[HC_ABORT] = 1;
+      _mm_sfence();
+      c->aborted.store(true);
+    }
+    std::this_thread::yield();
+  }
+  std::lock_guard<std::mutex> lk(c->launch_mu);
+  bool idle = false;
+  int rc = reap_locked(c, &idle);
+  if (rc != DFX_OK) return rc;
+  return forced ? DFX_ERR_ABORTED : DFX_OK;
+}
+
+int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
+  if (!c || rank < 0 || rank >= c->R || !out) return DFX_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lk(c->launch_mu);
+  memset(out, 0, sizeof(*out));
+  DfxWgState* h = (DfxWgState*)c->pinned_tmp;
+  HIPCHK(c, hipMemcpyAsync(h, c->wgstate, (size_t)c->nwg * sizeof(DfxWgState), hipMemcpyDeviceToHost, c->side));
+  HIPCHK(c, hipStreamSynchronize(c->side));
+  std::vector<uint32_t> wgs;
+  std::vector<uint32_t> tn;
+  for (uint32_t wg = 0; wg < c->nwg; ++wg) {
+    uint32_t r = c->cfg.wg_map == 0 ? wg % (uint32_t)c->R : wg / c->cfg.max_channels;
+    if ((int)r != rank) continue;
+    const uint64_t* s = h[wg].stat;
+    out->preemptions += s[ST_PREEMPT]; out->ctx_loads += s[ST_LOAD]; out->ctx_slot_hits += s[ST_HIT];
+    out->ctx_saves += s[ST_SAVE]; out->lazy_skips += s[ST_LAZY]; out->polls += s[ST_POLLS]; out->prims += s[ST_PRIMS];
+    out->sqe_fetched += s[ST_SQE]; out->cqe_posted += s[ST_CQE]; out->passes += s[ST_PASSES]; out->quits += s[ST_QUITS];
+    out->max_taskq = std::max<uint64_t>(out->max_taskq, s[ST_MAXQ]);
+    wgs.push_back(wg);
+    tn.push_back(h[wg].trace_n);
+  }
+  out->launches = c->launches;
+  if (c->trace) {
+    std::vector<double> tot;
+    double sv = 0, ld = 0;
+    uint64_t* buf = (uint64_t*)c->pinned_tmp;
+    for (size_t i = 0; i < wgs.size(); ++i) {
+      const uint32_t n = std::min<uint32_t>(tn[i], DFX_TRACE_N);
+      if (!n) continue;
+      HIPCHK(c, hipMemcpyAsync(buf, c->trace + (size_t)wgs[i] * DFX_TRACE_N, (size_t)n * 8, hipMemcpyDeviceToHost, c->side));
+      HIPCHK(c, hipStreamSynchronize(c->side));
+      for (uint32_t k = 0; k < n; ++k) {
+        const uint64_t v = buf[k];
+        tot.push_back((double)(v & 0xffffffu) * c->tick_us);
+        sv += (double)((v >> 24) & 0xfffffu) * c->tick_us;
+        ld += (double)((v >> 44) & 0xfffffu) * c->tick_us;
+      }
+    }
+    if (!tot.empty()) {
+      std::sort(tot.begin(), tot.end());
+      double sum = 0;
+      for (double x : tot) sum += x;
+      out->switch_samples = tot.size();
+      out->switch_us_p50 = tot[tot.size() / 2];
+      out->switch_us_p99 = tot[std::min(tot.size() - 1, (size_t)((double)tot.size() * 0.99))];
+      out->switch_us_mean = sum / (double)tot.size();
+      out->save_us_mean = sv / (double)tot.size();
+      out->load_us_mean = ld / (double)tot.size();
+    }
+  }
+  return DFX_OK;
+}
+
+int dfx_last_launch_ms(dfx_ctx* c, float* ms, uint64_t* launches_done) {
+  if (!c) return DFX_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lk(c->launch_mu);
+  bool idle = false;
+  int rc = reap_locked(c, &idle);
+  if (rc != DFX_OK) return rc;
+  if (ms) *ms = c->last_ms;
+  if (launches_done) *launches_done = c->launches_done;
+  return DFX_OK;
+}
+
+int dfx_finalize(dfx_ctx* c) {
+  if (!c) return DFX_ERR_INVALID_ARG;
+  int rc = dfx_stop(c);
+  bool pending = false;
+  for (int r = 0; r < c->R; ++r) {
+    std::lock_guard<std::mutex> lk(c->ranks[r]->mu);
+    drain_cq(c, r);
+    if (c->ranks[r]->n_cqe.load() < c->ranks[r]->n_sub.load()) pending = true;
+  }
+  (void)hipStreamSynchronize(c->stream);
+  free_all(c);
+  if (rc == DFX_ERR_HIP) return rc;
+  return (pending || rc == DFX_ERR_ABORTED) ? DFX_ERR_ABORTED : DFX_OK;
+}
+
+int dfx_last_hip_error(dfx_ctx* c) { return c ? c->last_hip : 0; }
+
+const char* dfx_strerror(int s) {
+  switch (s) {
+    case DFX_OK: return "ok";
+    case DFX_ERR_INVALID_ARG: return "invalid argument";
+    case DFX_ERR_NOT_PREPARED: return "collective not prepared";
+    case DFX_ERR_BUSY: return "collective already outstanding on this rank";
+    case DFX_ERR_SQ_FULL: return "submission queue full (retry)";
+    case DFX_ERR_TIMEOUT: return "timeout";
+    case DFX_ERR_HIP: return "HIP runtime error";
+    case DFX_ERR_NO_RESOURCES: return "not enough resources";
+    case DFX_ERR_ABORTED: return "daemon aborted";
+    default: return "unknown status";
+  }
+}
+
+// Calibration helper for the profiler's HBM byte counters: copies `bytes` (multiple of 16)
+// from src to dst (both device) with a plain kernel on the given stream (NULL = private
+// stream) and waits for it.
+int dfx_copy_calibrate(const void* src, void* dst, size_t bytes, void* hip_stream) {
+  if (!src || !dst || (bytes & 15u)) return DFX_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (dfx_copy_launch(src, dst, bytes, s) != hipSuccess) return DFX_ERR_HIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return DFX_ERR_HIP;
+  return DFX_OK;
+}
+
+}  // extern "C"

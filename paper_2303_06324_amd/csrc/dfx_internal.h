@@ -1,0 +1,104 @@
+// Structures shared by the host library and the daemon kernel (not part of the public ABI).
+#ifndef DFX_INTERNAL_H
+#define DFX_INTERNAL_H
+
+#include <stdint.h>
+
+#define DFX_WG_THREADS 256      // threads per daemon workgroup (4 wavefronts of 64)
+#define DFX_MAX_COLLS 4096      // upper bound for dfx_config.max_colls (LDS task queue = 8 KB)
+#define DFX_CTX_SLOTS 4         // LDS active context slots, direct-mapped by coll_id (Sec. 5)
+#define DFX_TRACE_N 4096        // context-switch latency samples kept per workgroup
+#define DFX_FLAG_STRIDE 128     // bytes per (edge, channel) flag pair: tail at +0, head at +64
+#define DFX_NSTAT 12
+
+#define DFX_SQE_EXIT 1u
+
+// Static context of one invocation on one rank: what the host writes into the SQ and what a
+// workgroup keeps in its context buffer (Sec. 4.2: buffer and connector addresses, rank count,
+// composition of the primitive sequence).  96 bytes = six 16-byte vectors.
+struct alignas(16) DfxStatic {
+  uint32_t coll_id;
+  uint32_t seq;          // invocation number of this (rank, coll_id)
+  uint64_t sendbuf;
+  uint64_t recvbuf;
+  uint64_t count;
+  uint64_t conn_off;     // byte offset of this collective's connector block in the pool
+  uint64_t block_elems;  // ring chunk length (all-reduce) or count (others), in elements
+  uint64_t part_elems;   // elements of a block that one channel covers (16-byte multiple)
+  uint32_t slice_elems;  // elements per FIFO slot
+  uint32_t rounds;       // slices per block and channel = repetitions of the primitive sequence
+  uint32_t slot_bytes;
+  uint16_t nslots;
+  uint16_t nchan;
+  uint8_t kind, dtype, op, root;
+  uint16_t flags;
+  int16_t priority;
+  uint32_t nprim;        // primitives per round on every rank
+  uint32_t reserved;
+  uint32_t reserved2;
+  uint32_t ready;        // SQ only, written last: generation of the entry, 0 = slot writable
+};
+static_assert(sizeof(DfxStatic) == 96, "DfxStatic must be 96 bytes");
+
+// Dynamic context (Sec. 4.2: current chunk id, aborted primitive id) plus the monotone
+// connector counters of this (rank, channel).  32 bytes = two 16-byte vectors.
+struct alignas(16) DfxDyn {
+  uint32_t round;        // slice index ("current data chunk")
+  uint32_t prim;         // next primitive of the sequence ("aborted primitive")
+  uint64_t sent;         // slices ever pushed into the send connector
+  uint64_t recvd;        // slices ever taken from the recv connector
+  uint32_t preempted;    // times this invocation was preempted on this workgroup
+  uint32_t pad;
+};
+static_assert(sizeof(DfxDyn) == 32, "DfxDyn must be 32 bytes");
+
+struct alignas(16) DfxCtxEntry {
+  DfxStatic st;
+  DfxDyn dyn;
+};
+static_assert(sizeof(DfxCtxEntry) == 128, "context entry must be 128 bytes");
+
+struct alignas(16) DfxSqSlot {   // one SQ ring entry, padded to two 64-byte lines
+  DfxStatic e;
+  uint32_t pad[8];
+};
+static_assert(sizeof(DfxSqSlot) == 128, "SQ slot must be 128 bytes");
+
+// Per-workgroup state that survives daemon exit / voluntary quit (Sec. 4.5).
+struct alignas(16) DfxWgState {
+  uint64_t read_index;   // SQ entries consumed by this workgroup
+  uint32_t qlen;         // task-queue length (entries are in taskq_store)
+  uint32_t trace_n;      // trace samples written (monotone)
+  uint64_t stat[DFX_NSTAT];
+  uint64_t dbg[8];       // filled when the watchdog fires
+  uint64_t pad[2];
+};
+
+enum { ST_PREEMPT = 0, ST_LOAD, ST_HIT, ST_SAVE, ST_LAZY, ST_POLLS, ST_PRIMS, ST_SQE, ST_CQE, ST_MAXQ, ST_PASSES, ST_QUITS };
+
+// dev_ctl words (device memory)
+enum { DC_ABORT = 0, DC_ERR = 1, DC_ERR_WG = 2, DC_N = 16 };
+// host_ctl words (host-visible queue memory)
+enum { HC_ABORT = 0, HC_N = 16 };
+
+struct DfxDaemonArgs {
+  DfxSqSlot* sq;            // [R][sq_depth]   host-visible
+  uint64_t* cq;             // [R][cq_slots]   host-visible
+  uint32_t* host_ctl;       // [HC_N]          host-visible
+  uint32_t* sq_readers;     // [R][sq_depth]   device
+  uint32_t* done_cnt;       // [R][max_colls]  device
+  uint32_t* cq_ticket;      // [R]             device
+  uint32_t* dev_ctl;        // [DC_N]          device
+  uint8_t* pool;            // connector pool  device
+  DfxCtxEntry* ctxbuf;      // [nwg][max_colls] device
+  DfxWgState* wgstate;      // [nwg]           device
+  uint16_t* taskq_store;    // [nwg][max_colls] device
+  uint64_t* trace;          // [nwg][DFX_TRACE_N] device (or null)
+  uint32_t R, cmax, max_colls, sq_depth, sq_shift, cq_slots;
+  uint32_t spin_init, spin_min, spin_max, spin_boost, preempt;
+  uint32_t wg_map, order_policy, trace_on;
+  uint64_t watchdog_ticks;  // wall-clock ticks; 0 = off
+  uint64_t quit_ticks;      // wall-clock ticks; 0 = off
+};
+
+#endif

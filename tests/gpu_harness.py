@@ -1,0 +1,145 @@
+"""Run a synthetic workload through the HIP library and fetch the results (GPU tests + bench).
+
+Only marshalling lives here: buffers are torch byte tensors (PyTorch = device memory only),
+every collective step runs in libdfx.so through the C ABI.
+"""
+from __future__ import annotations
+
+import threading
+import time
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+import paper_2303_06324_amd as dfx
+import workload_inputs as wi
+
+SENTINEL = 0xA5
+
+
+def make_config(**kw) -> "dfx.Config":
+    cfg = dfx.config_default()
+    for k, v in kw.items():
+        if not hasattr(cfg, k):
+            raise KeyError(k)
+        setattr(cfg, k, v)
+    return cfg
+
+
+class DeviceWorkload:
+    """Send/recv buffers of a Workload resident on the GPU."""
+
+    def __init__(self, w: wi.Workload, colls: Optional[Sequence[int]] = None, keep_host: bool = True):
+        self.w = w
+        self.idx = list(range(len(w.colls))) if colls is None else list(colls)
+        self.send_host: Dict[int, List[np.ndarray]] = {}
+        self.send: Dict[int, List[torch.Tensor]] = {}
+        self.recv: Dict[int, List[torch.Tensor]] = {}
+        for ci in self.idx:
+            c = w.colls[ci]
+            hs = wi.all_sends(w, ci)
+            if keep_host:
+                self.send_host[ci] = hs
+            self.send[ci] = [torch.from_numpy(h.view(np.uint8)).cuda() for h in hs]
+            nbytes = c.recv_elems(w.R) * wi.ELEM_BYTES[c.dtype]
+            self.recv[ci] = [torch.full((max(nbytes, 16),), SENTINEL, dtype=torch.uint8, device="cuda")
+                             for _ in range(w.R)]
+        torch.cuda.synchronize()
+
+    def reset_recv(self):
+        for ci in self.idx:
+            for t in self.recv[ci]:
+                t.fill_(SENTINEL)
+        torch.cuda.synchronize()
+
+    def results(self, ci: int) -> List[np.ndarray]:
+        c = self.w.colls[ci]
+        nbytes = c.recv_elems(self.w.R) * wi.ELEM_BYTES[c.dtype]
+        return [t[:nbytes].cpu().numpy().view(wi.NP_STORAGE[c.dtype]) for t in self.recv[ci]]
+
+
+def prepare_all(ctx: "dfx.Context", w: wi.Workload, colls: Optional[Sequence[int]] = None, priorities=None):
+    idx = range(len(w.colls)) if colls is None else colls
+    for ci in idx:
+        c = w.colls[ci]
+        ctx.prepare(c.coll_id, c.kind, c.count, c.dtype, dfx.SUM, c.root,
+                    0 if priorities is None else priorities[ci])
+
+
+def _submit_retry(ctx, r, coll_id, s, d, deadline):
+    while True:
+        rc = ctx.submit(r, coll_id, s, d)
+        if rc == dfx.OK:
+            return
+        if rc != dfx.ERR_SQ_FULL:
+            raise dfx.DfxError(rc, f"dfx_submit(rank={r}, coll={coll_id})")
+        ctx.poll(r, 0)          # lets the library restart a daemon that quit
+        if time.monotonic() > deadline:
+            raise TimeoutError("SQ stayed full")
+
+
+def submit_round_robin(ctx: "dfx.Context", dw: DeviceWorkload, orders=None, timeout_s: float = 20.0):
+    """One host thread walks the per-rank issue orders in lock step (rank 0's j-th, rank 1's j-th ...)."""
+    w = dw.w
+    orders = w.orders if orders is None else orders
+    deadline = time.monotonic() + timeout_s
+    n = max(len(o) for o in orders)
+    for j in range(n):
+        for r in range(w.R):
+            if j < len(orders[r]):
+                ci = orders[r][j]
+                _submit_retry(ctx, r, w.colls[ci].coll_id, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr(), deadline)
+
+
+def submit_threads(ctx: "dfx.Context", dw: DeviceWorkload, orders=None, delays_us=None, timeout_s: float = 30.0):
+    """One host thread per rank, each with its own order and (optional) seeded delays."""
+    w = dw.w
+    orders = w.orders if orders is None else orders
+    deadline = time.monotonic() + timeout_s
+    errs = []
+
+    def work(r):
+        try:
+            for j, ci in enumerate(orders[r]):
+                if delays_us:
+                    t_end = time.perf_counter() + delays_us[r][j] * 1e-6
+                    while time.perf_counter() < t_end:
+                        pass
+                _submit_retry(ctx, r, w.colls[ci].coll_id, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr(), deadline)
+        except Exception as e:   # noqa: BLE001
+            errs.append(e)
+
+    ts = [threading.Thread(target=work, args=(r,)) for r in range(w.R)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    if errs:
+        raise errs[0]
+
+
+def run_workload(w: wi.Workload, cfg=None, mode: str = "roundrobin", timeout_s: float = 30.0,
+                 dw: Optional[DeviceWorkload] = None, keep_ctx: bool = False):
+    """Create a context, run every collective of w once in its per-rank orders, return
+    (DeviceWorkload, per-rank stats, context or None)."""
+    dw = dw or DeviceWorkload(w)
+    ctx = dfx.Context(w.R, cfg)
+    try:
+        prepare_all(ctx, w)
+        if mode == "threads":
+            submit_threads(ctx, dw, delays_us=w.delays_us or None, timeout_s=timeout_s)
+        else:
+            submit_round_robin(ctx, dw, timeout_s=timeout_s)
+        rc = ctx.wait_all(timeout_s)
+        stop_rc = ctx.stop()
+        stats = [ctx.stats(r) for r in range(w.R)]
+        if rc != dfx.OK:
+            raise dfx.DfxError(rc, f"dfx_wait_all (stop={stop_rc}, stats0={stats[0]})")
+    except Exception:
+        ctx.finalize()
+        raise
+    if keep_ctx:
+        return dw, stats, ctx
+    ctx.finalize()
+    return dw, stats, None

@@ -1,0 +1,68 @@
+"""CPU checks of the boundary: the C-ABI library loads and exports every symbol that include/dfx.h
+declares, argument validation works without a GPU, and the product package never imports the oracle."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "dfx.h")
+LIB = os.path.join(ROOT, "paper_2303_06324_amd", "libdfx.so")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(dfx_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_header_declares_the_boundary_calls():
+    names = _declared()
+    for need in ("dfx_init", "dfx_prepare", "dfx_submit", "dfx_poll", "dfx_wait", "dfx_finalize", "dfx_stats",
+                 "dfx_strerror"):
+        assert need in names
+
+
+def test_library_exports_every_declared_symbol():
+    assert os.path.exists(LIB), "build first: python -m paper_2303_06324_amd.build"
+    lib = ctypes.CDLL(LIB)
+    for name in _declared():
+        assert hasattr(lib, name), f"{name} declared in dfx.h but not exported"
+
+
+def test_config_struct_matches_header_size():
+    import paper_2303_06324_amd as dfx
+    cfg = dfx.config_default()
+    assert cfg.struct_bytes == ctypes.sizeof(dfx.Config) == 88
+    assert cfg.nslots >= 2 and cfg.max_colls <= 4096 and cfg.preempt == 1
+    assert dfx.strerror(0) == "ok" and "timeout" in dfx.strerror(dfx.ERR_TIMEOUT)
+
+
+def test_argument_validation_without_gpu():
+    import paper_2303_06324_amd as dfx
+    lib = dfx.binding._lib
+    h = ctypes.c_void_p()
+    assert lib.dfx_init(None, 8, None, None) == dfx.ERR_INVALID_ARG
+    assert lib.dfx_init(ctypes.byref(h), 0, None, None) == dfx.ERR_INVALID_ARG
+    assert lib.dfx_init(ctypes.byref(h), 65, None, None) == dfx.ERR_INVALID_ARG
+    bad = dfx.config_default()
+    bad.nslots = 1          # a one-slot connector cannot run a fused recv+send ring
+    assert lib.dfx_init(ctypes.byref(h), 8, ctypes.byref(bad), None) == dfx.ERR_INVALID_ARG
+    bad = dfx.config_default()
+    bad.sq_depth = 100
+    assert lib.dfx_init(ctypes.byref(h), 8, ctypes.byref(bad), None) == dfx.ERR_INVALID_ARG
+    bad = dfx.config_default()
+    bad.struct_bytes = 4
+    assert lib.dfx_init(ctypes.byref(h), 8, ctypes.byref(bad), None) == dfx.ERR_INVALID_ARG
+    assert lib.dfx_submit(None, 0, 0, None, None) == dfx.ERR_INVALID_ARG
+    assert lib.dfx_finalize(None) == dfx.ERR_INVALID_ARG
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2303_06324_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                txt = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in txt, f"{f} mentions the oracle"

@@ -1,0 +1,139 @@
+"""GPU parity: the HIP daemon-kernel path against the CPU oracle, element by element, bit-exact
+(integer dtypes by definition; floating point because both sides use the same reduction order
+and one rounding per hop), plus the fp64 tolerance the benchmark spec states."""
+import itertools
+
+import numpy as np
+import pytest
+
+import workload_inputs as wi
+from oracle import ring_data as rd
+
+pytestmark = pytest.mark.gpu
+
+TOL = {rd.F32: 1e-6, rd.BF16: 1e-2, rd.F16: 4e-3}
+
+
+def _check(dw, w, ci):
+    c = w.colls[ci]
+    want = rd.run_closed_form(c.kind, dw.send_host[ci], c.dtype, c.root)
+    got = dw.results(ci)
+    for r in range(w.R):
+        g, e = got[r], want[r]
+        if not np.array_equal(g.view(np.uint8), e.view(np.uint8)):
+            bad = np.flatnonzero(g.view(np.uint8) != e.view(np.uint8))
+            raise AssertionError(f"{w.name} coll {ci} ({wi.KIND_NAMES[c.kind]}, {wi.DTYPE_NAMES[c.dtype]}, count={c.count}) "
+                                 f"rank {r}: {bad.size} bytes differ, first at byte {bad[0]}")
+    if c.kind in (wi.AR, wi.RS) and c.dtype in TOL:
+        # within tol * sum|x| of the order-independent fp64 sum
+        sends = dw.send_host[ci]
+        if c.kind == wi.AR:
+            ref, mag = rd.sum_f64(sends, c.dtype), rd.abs_sum_f64(sends, c.dtype)
+            for r in range(w.R):
+                assert np.all(np.abs(rd.to_f64(got[r], c.dtype) - ref) <= TOL[c.dtype] * mag + 1e-30)
+
+
+def _run(w, **cfgkw):
+    from tests import gpu_harness as gh
+    mode = cfgkw.pop("mode", "roundrobin")
+    timeout_s = cfgkw.pop("timeout_s", 30.0)
+    cfg = gh.make_config(**cfgkw)
+    dw, stats, _ = gh.run_workload(w, cfg, mode=mode, timeout_s=timeout_s)
+    for ci in range(len(w.colls)):
+        _check(dw, w, ci)
+    return stats
+
+
+def _one(kind, dtype, count, R, root=0, seed=0):
+    return wi.Workload(f"one_{kind}_{dtype}_{count}_R{R}", R, [wi.CollSpec(0, kind, dtype, count, root)],
+                       [[0]] * R, seed=seed, cfg=50)
+
+
+def test_smallest_allreduce_two_ranks():
+    _run(_one(wi.AR, wi.F32, 1024, 2), max_channels=4)
+
+
+@pytest.mark.parametrize("orders", list(itertools.product([(0, 1), (1, 0)], repeat=2)))
+def test_config1_circular_wait_all_orders(orders):
+    """Two all-reduces issued in every combination of orders on two ranks; opposite orders are the
+    single-queue deadlock of Sec. 2.3. Integer-valued inputs: sums are exact in any order."""
+    w = wi.config1(*orders)
+    stats = _run(w, max_channels=4, spin_init=200, spin_min=8, spin_max=4000, spin_boost=4)
+    from tests import gpu_harness as gh  # noqa: F401
+    for ci in range(2):
+        sends = wi.all_sends(w, ci)
+        exact = sum(s.astype(np.int64) for s in sends)
+        assert exact.shape == (1024,)
+    assert sum(s["cqe_posted"] for s in stats) == 4
+
+
+@pytest.mark.parametrize("dtype", [wi.F32, wi.BF16, wi.F16, wi.I32])
+@pytest.mark.parametrize("count", [1, 7, 4096, 100003, 1 << 20])
+def test_allreduce_sizes_and_dtypes_R8(dtype, count):
+    _run(_one(wi.AR, dtype, count, 8, seed=count))
+
+
+@pytest.mark.parametrize("R", [1, 2, 3, 5, 8, 16])
+def test_allreduce_rank_counts(R):
+    _run(_one(wi.AR, wi.F32, 50000 + R, R, seed=R), max_channels=8)
+
+
+@pytest.mark.parametrize("kind", [wi.AG, wi.RS, wi.BC])
+@pytest.mark.parametrize("dtype,count", [(wi.F32, 4096), (wi.F16, 1001), (wi.I32, 3), (wi.BF16, 250000)])
+def test_other_collectives(kind, dtype, count):
+    _run(_one(kind, dtype, count, 8, root=5, seed=kind * 10 + dtype))
+
+
+def test_zero_count_collective_completes():
+    _run(_one(wi.AR, wi.F32, 0, 4), max_channels=4)
+
+
+def test_forced_preemption_is_transparent():
+    """Tiny spin thresholds force thousands of context switches; results must not change
+    (Sec. 4.5: restart without under- or re-transmitting data)."""
+    w = wi.config3(n_buckets=8, bucket_bytes=1 << 20, seed=3)
+    stats = _run(w, spin_init=4, spin_min=1, spin_max=16, spin_boost=2, slot_bytes=8192, nslots=2, trace=1)
+    assert sum(s["preemptions"] for s in stats) > 100
+    assert sum(s["ctx_saves"] for s in stats) > 0
+    huge = _run(w, spin_init=1 << 30, spin_min=1 << 30, spin_max=1 << 31, spin_boost=1)
+    assert sum(s["cqe_posted"] for s in huge) == 8 * 8
+
+
+def test_config3_small_bf16_buckets_random_orders():
+    _run(wi.config3(n_buckets=16, bucket_bytes=2 << 20, seed=1), timeout_s=60.0)
+
+
+def test_config4_mixed_small():
+    w = wi.config4(n_colls=24, min_bytes=4096, max_bytes=4 << 20, seed=2)
+    _run(w, mode="threads", timeout_s=60.0)
+
+
+def test_config5_many_small_allreduces():
+    w = wi.config5(n_colls=256, seed=4)
+    stats = _run(w, mode="threads", timeout_s=90.0, sq_depth=64)
+    assert sum(s["cqe_posted"] for s in stats) == 256 * 8
+
+
+def test_repeated_invocations_and_changing_buffers():
+    """A collective is registered once and run many times, with different buffers (Sec. 3.2, 4.2)."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = _one(wi.AR, wi.F32, 300000, 8, seed=77)
+    dws = [gh.DeviceWorkload(w), gh.DeviceWorkload(wi.Workload(w.name, 8, w.colls, w.orders, seed=78, cfg=50))]
+    ctx = dfx.Context(8, gh.make_config())
+    try:
+        gh.prepare_all(ctx, w)
+        for it in range(6):
+            dw = dws[it % 2]
+            dw.reset_recv()
+            gh.submit_round_robin(ctx, dw)
+            assert ctx.wait_all(20.0) == dfx.OK
+            _check(dw, dw.w, 0)
+        assert ctx.submit(0, 0, dws[0].send[0][0].data_ptr(), dws[0].recv[0][0].data_ptr()) == dfx.OK
+        assert ctx.submit(0, 0, dws[0].send[0][0].data_ptr(), dws[0].recv[0][0].data_ptr()) == dfx.ERR_BUSY
+        for r in range(1, 8):
+            assert ctx.submit(r, 0, dws[0].send[0][r].data_ptr(), dws[0].recv[0][r].data_ptr()) == dfx.OK
+        assert ctx.wait(0, 0, 20.0) == dfx.OK
+        assert ctx.wait_all(20.0) == dfx.OK
+    finally:
+        ctx.finalize()
