@@ -78,7 +78,7 @@ typedef struct {
   uint32_t wg_map;         /* 0: workgroup = channel*nranks + rank; 1: workgroup = rank*max_channels + channel */
   uint32_t order_policy;   /* 0 = FIFO ordering, 1 = priority ordering (Sec. 4.3) */
   uint32_t trace;          /* 1 = record context-switch latency samples */
-  uint32_t reserved0;
+  uint32_t fetch_batch;    /* SQEs a workgroup may fetch in a row when its queue is empty or stuck; 0 = all available */
   uint64_t pool_bytes;     /* device memory reserved for connectors of all prepared collectives */
 } dfx_config;
 

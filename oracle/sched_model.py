@@ -29,7 +29,7 @@ Readings where the paper is silent (listed in the design notes): spin threshold 
 = poll attempts; thr(pos) = max(spin_min, spin_init >> pos); after a success
 thr = min(spin_max, thr*boost) until preemption or completion; "cannot progress for
 a while" = one whole pass over the task queue with no successful primitive, after
-which at most one SQE is fetched.
+which up to `fetch_batch` SQEs are fetched (the paper does not say how many).
 
 One tick of a rank = its local bookkeeping up to and including ONE poll attempt,
 plus the slice's data movement when the poll succeeds.  Which actor ticks next is
@@ -76,6 +76,7 @@ class Policy:
     sq_depth: int = 1 << 20
     K: int = 2                    # slots per connector FIFO
     slice_elems: int = 1 << 30    # elements per slice (per round)
+    fetch_batch: int = 1          # SQEs fetched in a row when the queue is empty or stuck (0 = all available)
 
 
 @dataclass
@@ -240,7 +241,10 @@ class Daemon:
                 # FetchSQE: when the queue is empty, or the last pass made no progress
                 before = (len(self.taskq), len(self.sq))
                 if not self.taskq or not self.pass_progress:
-                    self._fetch()
+                    n = self.S.policy.fetch_batch or (1 << 30)
+                    while n > 0 and self.sq and not self.exit and len(self.taskq) < self.S.policy.taskq_cap:
+                        self._fetch()
+                        n -= 1
                 if self.exit:
                     return True
                 if (len(self.taskq), len(self.sq)) != before:

@@ -288,7 +288,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   // thread-0-only bookkeeping
   u64 last_act = wall_clock64();
   bool acted = true;
-  uint32_t iter = 0, idle = 0;
+  uint32_t iter = 0, idle = 0, burst = 0;
   // pending context-switch sample (thread 0): t0 = abort decision, ts = after save
   u64 sw_t0 = 0, sw_ts = 0;
   bool sw_pending = false;
@@ -313,7 +313,10 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         } else if (a.quit_ticks && now - last_act > a.quit_ticks) s = STOP_QUIT;
       }
       uint32_t got = 0;
-      const bool want = (qlen == 0) || !pass_progress || a.order_policy == 1;
+      // FIFO ordering (Sec. 4.3): fetch when the queue is empty or a whole pass made no progress,
+      // then keep fetching what is already there (up to fetch_batch); priority ordering probes
+      // the SQ before every pass.
+      const bool want = (qlen == 0) || !pass_progress || a.order_policy == 1 || (burst > 0 && burst < a.fetch_batch);
       if (!s && want && qlen < a.max_colls) {
         DfxSqSlot* e = &sqbase[ri & (D - 1)];
         const uint32_t gen = (uint32_t)(ri >> a.sq_shift) + 1u;
@@ -370,9 +373,11 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       ++ri;
       __syncthreads();
       if (is_exit) { stop = STOP_EXIT; break; }
-      pass_progress = true;   // a fresh entry counts as progress: walk the queue before fetching again
-      if (!mine) continue;
+      ++burst;
+      idle = 0;
+      continue;               // probe the SQ again before walking the queue
     } else if (qlen == 0) {
+      burst = 0;
       // idle: back off the SQ probe (it may cross PCIe), then meet before the next broadcast
       ++idle;
       if (idle < 16) __builtin_amdgcn_s_sleep(8);
@@ -382,6 +387,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       continue;
     }
     idle = 0;
+    burst = 0;
 
     // ================= one pass over the task queue (Alg. 1 lines 4-19) =================
     pass_progress = false;

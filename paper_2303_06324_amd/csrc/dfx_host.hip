@@ -150,6 +150,7 @@ int launch_locked(dfx_ctx* c) {
   a.spin_init = c->cfg.spin_init; a.spin_min = c->cfg.spin_min; a.spin_max = c->cfg.spin_max;
   a.spin_boost = c->cfg.spin_boost; a.preempt = c->cfg.preempt;
   a.wg_map = c->cfg.wg_map; a.order_policy = c->cfg.order_policy; a.trace_on = c->cfg.trace;
+  a.fetch_batch = c->cfg.fetch_batch ? c->cfg.fetch_batch : 0xffffffffu;
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   HIPCHK(c, hipEventRecord(c->ev_start, c->stream));
@@ -241,10 +242,11 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->nslots = 4;
   cfg->slot_bytes = 64u << 10;
   cfg->chan_min_bytes = 16u << 10;
-  cfg->spin_init = 20000;
-  cfg->spin_min = 32;
-  cfg->spin_max = 400000;
-  cfg->spin_boost = 20;
+  cfg->spin_init = 512;
+  cfg->spin_min = 4;
+  cfg->spin_max = 2048;
+  cfg->spin_boost = 4;
+  cfg->fetch_batch = 0;
   cfg->preempt = 1;
   cfg->watchdog_ms = 10000;
   cfg->quit_idle_us = 2000;

@@ -41,7 +41,13 @@ class DeviceWorkload:
             hs = wi.all_sends(w, ci)
             if keep_host:
                 self.send_host[ci] = hs
-            self.send[ci] = [torch.from_numpy(h.view(np.uint8)).cuda() for h in hs]
+            self.send[ci] = []
+            for h in hs:
+                b = h.view(np.uint8)
+                t = torch.zeros(max(b.size, 16), dtype=torch.uint8, device="cuda")   # never a null pointer
+                if b.size:
+                    t[:b.size].copy_(torch.from_numpy(b))
+                self.send[ci].append(t)
             nbytes = c.recv_elems(w.R) * wi.ELEM_BYTES[c.dtype]
             self.recv[ci] = [torch.full((max(nbytes, 16),), SENTINEL, dtype=torch.uint8, device="cuda")
                              for _ in range(w.R)]

@@ -165,3 +165,13 @@ def test_one_slot_connectors_cannot_run_a_fused_ring():
     with pytest.raises(TimeoutError):
         sm.run_round_robin(S, max_ticks=20_000)
     assert S.total_cqes() == 0
+
+
+@pytest.mark.parametrize("batch", [0, 3])
+def test_batch_fetch_keeps_liveness_and_values(batch):
+    """Fetching several SQEs at once when stuck (the GPU path's default) changes timing only."""
+    w = wi.config4(n_colls=8, min_bytes=256, max_bytes=2048, seed=11, R=3)
+    S = _system(w, sm.Policy(spin_init=3, spin_min=1, spin_max=12, boost=2, K=2, slice_elems=32, fetch_batch=batch))
+    sm.run_random(S, 5, max_ticks=5_000_000)
+    assert S.total_cqes() == 8 * 3
+    _check_data(S, w)
