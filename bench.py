@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Headline benchmark: 8-virtual-rank ring all-reduce through the preemptive daemon kernel.
+
+One "step" = one pass of the whole hot path over one batch: launch the daemon, every vrank
+submits its SQE, primitives run through the HBM connectors, CQEs are posted and polled, the exit
+SQE drains the grid.  Workload = the large-message point of the size sweep (R = 8, fp32 sum,
+256 MiB per rank, inputs resident in HBM before the timed region).
+
+Prints ONE JSON line: busbw (whole job, one GPU), the HBM roofline of the daemon kernel from its
+HIP-event launch durations, and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+R = 8
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
+# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md); None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def algorithmic_bytes(msg_bytes: int, nranks: int) -> int:
+    """(6R-4)/R * M per rank: every ring step's reads and writes of send buffer, recv buffer and
+    connector slots (send 2B, recv-reduce-send 3B, recv-reduce-copy-send 4B, recv-copy-send 3B,
+    recv-copy 2B with B = M/R), summed over the R ranks."""
+    return (6 * nranks - 4) * msg_bytes
+
+
+def cpu_baseline(sample_bytes: int):
+    """The oracle as it stands (single-threaded numpy replay of the ring schedule) on a bounded sample."""
+    import numpy as np
+    import workload_inputs as wi
+    from oracle import ring_data as rd
+    w = wi.config2(sample_bytes)
+    sends = wi.all_sends(w, 0)
+    t0 = time.perf_counter()
+    out = rd.all_reduce_replay(sends, rd.F32)
+    dt = time.perf_counter() - t0
+    assert len(out) == R
+    busbw = sample_bytes / dt * 2 * (R - 1) / R / 1e9
+    return {"value": round(busbw, 4), "unit": "GB/s busbw", "cores": 1, "kind": "oracle",
+            "sample": f"one all-reduce of {sample_bytes >> 20} MiB per rank, R=8 fp32 (ring replay in numpy), {dt:.2f} s"}
+
+
+def switch_latency():
+    """Context-switch latency (abort decision -> first poll of the next collective) from a short
+    run of many small all-reduces issued in a different random order on every vrank."""
+    import workload_inputs as wi
+    import paper_2303_06324_amd as dfx
+    from tests import gpu_harness as gh
+    w = wi.config5(n_colls=256, seed=4)
+    dw = gh.DeviceWorkload(w, keep_host=False)
+    ctx = dfx.Context(R, gh.make_config(trace=1))
+    try:
+        gh.prepare_all(ctx, w)
+        t0 = time.perf_counter()
+        gh.submit_threads(ctx, dw, timeout_s=60)
+        rc = ctx.wait_all(60.0)
+        dt = time.perf_counter() - t0
+        ctx.stop()
+        st = [ctx.stats(r) for r in range(R)]
+    finally:
+        ctx.finalize()
+    n = sum(s["switch_samples"] for s in st)
+    return {"completed": rc == 0, "collectives": len(w.colls), "seconds": round(dt, 4),
+            "collectives_per_s": round(len(w.colls) / dt, 1),
+            "preemptions": sum(s["preemptions"] for s in st), "samples": n,
+            "p50_us": round(max(s["switch_us_p50"] for s in st), 3),
+            "p99_us": round(max(s["switch_us_p99"] for s in st), 3),
+            "save_us_mean": round(sum(s["save_us_mean"] for s in st) / R, 3),
+            "load_us_mean": round(sum(s["load_us_mean"] for s in st) / R, 3)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--msg-mib", type=int, default=256, help="per-rank message size in MiB")
+    ap.add_argument("--cpu-sample-mib", type=int, default=64)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-switch", action="store_true", help="skip the context-switch latency leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (virtual ranks share it); --gpus must be 1")
+
+    import torch
+    import paper_2303_06324_amd as dfx
+    from tests import gpu_harness as gh
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    M = args.msg_mib << 20
+    n = M // 4
+    torch.manual_seed(0)
+    send = [torch.randn(n, device="cuda", dtype=torch.float32) for _ in range(R)]
+    recv = [torch.empty(n, device="cuda", dtype=torch.float32) for _ in range(R)]
+    torch.cuda.synchronize()
+
+    cfg = gh.make_config(quit_idle_us=0)       # the step brackets the daemon itself: start ... exit SQE
+    ctx = dfx.Context(R, cfg)
+    ctx.prepare(0, dfx.ALLREDUCE, n, dfx.F32)
+    info = ctx.coll_info(0)
+
+    def step():
+        rc = ctx.start()
+        assert rc == dfx.OK, dfx.strerror(rc)
+        for r in range(R):
+            rc = ctx.submit(r, 0, send[r].data_ptr(), recv[r].data_ptr())
+            assert rc == dfx.OK, dfx.strerror(rc)
+        rc = ctx.wait_all(30.0)
+        assert rc == dfx.OK, dfx.strerror(rc)
+        rc = ctx.stop()
+        assert rc == dfx.OK, dfx.strerror(rc)
+        return ctx.last_launch_ms()[0]
+
+    try:
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        kern_ms = []
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            kern_ms.append(step())
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        launches = ctx.stats(0)["launches"]
+    finally:
+        ctx.finalize()
+
+    ms_per_step = wall / args.steps * 1e3
+    algbw = M / (ms_per_step * 1e-3) / 1e9
+    busbw = algbw * 2 * (R - 1) / R
+    k_ms = sum(kern_ms) / len(kern_ms)
+    achieved = algorithmic_bytes(M, R) / (k_ms * 1e-3) / 1e9
+    out = {
+        "metric": "8-vrank ring all-reduce busbw (emulated on one GPU)",
+        "value": round(busbw, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config 2: R=8 virtual ranks, one all-reduce(sum) fp32, {args.msg_mib} MiB per rank, "
+                               f"ring chunk = size/8, N(0,1) inputs resident in HBM",
+                   "channels_per_rank": info["nchan"], "slot_bytes": info["slot_bytes"], "rounds": info["rounds"],
+                   "daemon_launches": int(launches)},
+        "algbw_GBs": round(algbw, 2),
+        "hbm_frac_wall": round(algorithmic_bytes(M, R) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
+                     "kernel": "dfx_daemon_kernel", "kernel_ms_avg": round(k_ms, 4),
+                     "algorithmic_bytes_per_launch": algorithmic_bytes(M, R)},
+    }
+    if not args.no_switch:
+        out["preempt_switch"] = switch_latency()
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_sample_mib << 20)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -186,6 +186,9 @@ int dfx_finalize(dfx_ctx* ctx);
 /* hipError_t of the last failing HIP call on this context, as an int. */
 int dfx_last_hip_error(dfx_ctx* ctx);
 
+/* hipError_t of the HIP call that made the last dfx_init in this process fail (0 if none). */
+int dfx_last_init_error(void);
+
 const char* dfx_strerror(int status);
 
 /* Measurement aid, not part of the method: copy `bytes` (multiple of 16) from src to dst (both

@@ -52,6 +52,12 @@ def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2303_06324_amd.build); "
                           "there is no CPU fallback")
+    # PyTorch (device memory and streams) ships its own HIP runtime: load it first so that this
+    # library binds to the same runtime instance instead of a second copy.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     vp, i, u64, sz = C.c_void_p, C.c_int, C.c_uint64, C.c_size_t
     sig = {
@@ -69,6 +75,7 @@ def _load() -> C.CDLL:
         "dfx_last_launch_ms": ([vp, C.POINTER(C.c_float), C.POINTER(u64)], i),
         "dfx_finalize": ([vp], i),
         "dfx_last_hip_error": ([vp], i),
+        "dfx_last_init_error": ([], i),
         "dfx_strerror": ([i], C.c_char_p),
         "dfx_copy_calibrate": ([vp, vp, sz, vp], i),
     }
@@ -101,7 +108,7 @@ class Context:
                            C.c_void_p(stream) if stream else None)
         if rc != OK:
             self._h = C.c_void_p()
-            raise DfxError(rc, "dfx_init")
+            raise DfxError(rc, f"dfx_init (hipError {_lib.dfx_last_init_error()})")
 
     def prepare(self, coll_id: int, kind: int, count: int, dtype: int, op: int = SUM, root: int = 0,
                 priority: int = 0) -> None:

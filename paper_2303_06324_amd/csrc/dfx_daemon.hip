@@ -10,11 +10,20 @@
 // posts the CQE.  Connectors are FIFOs of K slots in HBM guarded by monotone tail/head
 // counters; a primitive touches nothing before both its conditions hold (Sec. 4.1, 4.5).
 //
-// Memory-model rules used here (AMDGPU, one agent with one L2 per XCD):
-//   producer: data stores -> every wave drains its stores -> workgroup barrier -> thread 0:
-//             agent-scope release fence -> relaxed agent-scope store of the counter;
-//   consumer: relaxed agent-scope load of the counter (lane 0/1 of wave 0) -> workgroup
-//             barrier -> agent-scope acquire fence in every wave -> data loads.
+// Memory-model rules used here (AMDGPU, one agent with one L2 per XCD), two connector modes:
+//   fenced (fifo_coherent = 0)
+//     producer: data stores -> every wave drains its stores -> workgroup barrier -> thread 0:
+//               agent-scope release fence -> relaxed agent-scope store of the counter;
+//     consumer: relaxed agent-scope load of the counter (lane 0/1 of wave 0) -> workgroup
+//               barrier -> agent-scope acquire fence in every wave -> data loads.
+//   device-coherent accesses (fifo_coherent = 1)
+//     connector slots are only ever touched by sc1 (device-scope) buffer loads/stores, which
+//     do not linger in the per-XCD caches; the producer drains them (vmcnt(0)) before the
+//     barrier and thread 0 then stores the counter with an sc1 store; the consumer polls the
+//     counter with sc1 loads and reads the slot with sc1 loads.  No bulk L2 write-back or
+//     invalidate per slice.  User buffers stay ordinary cached memory: the send buffer is made
+//     visible by the system-scope acquire at SQE fetch, the recv buffer is flushed by the
+//     system-scope release before the completion counter.
 //   SQ / CQ / host control words are host-visible and use system scope.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -103,96 +112,128 @@ __device__ __forceinline__ uint16_t add_half(uint16_t a, uint16_t b) {
 }
 
 // ------------------------------------------------------------------------------------------
-// slice mover: value = s0[i] (+ s1[i]);  d0[i] = value;  d1[i] = value.
-// 128-bit coalesced accesses, four independent vectors in flight per source and thread.
-// Falls back to element-wise moves when a user-buffer side is not 16-byte aligned
-// (all-gather / reduce-scatter blocks of odd length) and for the sub-vector tail.
+// slice mover: value = [fifo_in[i]] (+) [sendbuf[i]];  recvbuf[i] = value;  fifo_out[i] = value
+// (each side present or not, as the primitive says).  128-bit coalesced accesses, four
+// independent vectors in flight per source and thread.
+//
+// Connector slots are accessed through buffer instructions.  COH = 1 marks those accesses
+// device-coherent (sc1: they bypass the non-coherent levels and write through), so that
+// connector traffic needs no bulk L2 write-back / invalidate around every slice; COH = 0 uses
+// ordinary cached accesses and relies on the agent-scope fences of the caller.
+// User buffers are plain pointers; when one of them is not 16-byte aligned (all-gather /
+// reduce-scatter blocks of odd length) the slice is moved element-wise, as is the sub-vector
+// tail of a slice.
 // ------------------------------------------------------------------------------------------
-template <int DT, int NSRC, int NDST>
-__device__ __forceinline__ void move_slice(const void* __restrict__ s0, const void* __restrict__ s1,
-                                           void* __restrict__ d0, void* __restrict__ d1, uint32_t bytes) {
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+template <int COH>
+struct Slot {   // one connector slot seen through a buffer resource
+  __amdgpu_buffer_rsrc_t rsrc;
+  static constexpr int AUX = COH ? 16 : 0;   // cache-policy bit 4 = sc1
+  __device__ __forceinline__ Slot(const void* base, uint32_t bytes) {
+    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+  }
+  __device__ __forceinline__ uint4 ld16(uint32_t off) const {
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, AUX));
+  }
+  __device__ __forceinline__ void st16(uint32_t off, uint4 v) const {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), rsrc, (int)off, 0, AUX);
+  }
+  __device__ __forceinline__ uint32_t ld4(uint32_t off) const { return __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)off, 0, AUX); }
+  __device__ __forceinline__ void st4(uint32_t off, uint32_t v) const { __builtin_amdgcn_raw_buffer_store_b32(v, rsrc, (int)off, 0, AUX); }
+  __device__ __forceinline__ uint16_t ld2(uint32_t off) const { return __builtin_amdgcn_raw_buffer_load_b16(rsrc, (int)off, 0, AUX); }
+  __device__ __forceinline__ void st2(uint32_t off, uint16_t v) const { __builtin_amdgcn_raw_buffer_store_b16(v, rsrc, (int)off, 0, AUX); }
+};
+
+template <int DT, int COH, bool FIN, bool SB, bool RB, bool FOUT>
+__device__ __forceinline__ void move_slice(const void* fin_p, const char* __restrict__ sb, char* __restrict__ rb,
+                                           void* fout_p, uint32_t bytes) {
+  static_assert(FIN || SB, "a primitive has a source");
+  static_assert(RB || FOUT, "a primitive has a destination");
   const uint32_t tid = threadIdx.x;
-  uintptr_t al = (uintptr_t)s0 | (uintptr_t)d0;
-  if (NSRC == 2) al |= (uintptr_t)s1;
-  if (NDST == 2) al |= (uintptr_t)d1;
+  const Slot<COH> fin(fin_p, FIN ? bytes : 0), fout(fout_p, FOUT ? bytes : 0);
+  uintptr_t al = 0;
+  if (SB) al |= (uintptr_t)sb;
+  if (RB) al |= (uintptr_t)rb;
   uint32_t done = 0;
   if ((al & 15u) == 0) {
-    const uint4* __restrict__ S0 = (const uint4*)s0;
-    const uint4* __restrict__ S1 = (const uint4*)s1;
-    uint4* __restrict__ D0 = (uint4*)d0;
-    uint4* __restrict__ D1 = (uint4*)d1;
+    const uint4* __restrict__ S = (const uint4*)sb;
+    uint4* __restrict__ D = (uint4*)rb;
     const uint32_t nvec = bytes >> 4;
     uint32_t i = tid;
     for (; i + 3 * NT < nvec; i += 4 * NT) {
-      uint4 a0 = S0[i], a1 = S0[i + NT], a2 = S0[i + 2 * NT], a3 = S0[i + 3 * NT];
-      if (NSRC == 2) {
-        uint4 b0 = S1[i], b1 = S1[i + NT], b2 = S1[i + 2 * NT], b3 = S1[i + 3 * NT];
-        a0 = add_vec<DT>(a0, b0);
-        a1 = add_vec<DT>(a1, b1);
-        a2 = add_vec<DT>(a2, b2);
-        a3 = add_vec<DT>(a3, b3);
+      uint4 a0, a1, a2, a3;
+      if (FIN) { a0 = fin.ld16(i << 4); a1 = fin.ld16((i + NT) << 4); a2 = fin.ld16((i + 2 * NT) << 4); a3 = fin.ld16((i + 3 * NT) << 4); }
+      if (SB) {
+        uint4 b0 = S[i], b1 = S[i + NT], b2 = S[i + 2 * NT], b3 = S[i + 3 * NT];
+        if (FIN) { a0 = add_vec<DT>(a0, b0); a1 = add_vec<DT>(a1, b1); a2 = add_vec<DT>(a2, b2); a3 = add_vec<DT>(a3, b3); }
+        else { a0 = b0; a1 = b1; a2 = b2; a3 = b3; }
       }
-      D0[i] = a0; D0[i + NT] = a1; D0[i + 2 * NT] = a2; D0[i + 3 * NT] = a3;
-      if (NDST == 2) { D1[i] = a0; D1[i + NT] = a1; D1[i + 2 * NT] = a2; D1[i + 3 * NT] = a3; }
+      if (FOUT) { fout.st16(i << 4, a0); fout.st16((i + NT) << 4, a1); fout.st16((i + 2 * NT) << 4, a2); fout.st16((i + 3 * NT) << 4, a3); }
+      if (RB) { D[i] = a0; D[i + NT] = a1; D[i + 2 * NT] = a2; D[i + 3 * NT] = a3; }
     }
     for (; i < nvec; i += NT) {
-      uint4 a0 = S0[i];
-      if (NSRC == 2) a0 = add_vec<DT>(a0, S1[i]);
-      D0[i] = a0;
-      if (NDST == 2) D1[i] = a0;
+      uint4 a0;
+      if (FIN) a0 = fin.ld16(i << 4);
+      if (SB) { uint4 b0 = S[i]; a0 = FIN ? add_vec<DT>(a0, b0) : b0; }
+      if (FOUT) fout.st16(i << 4, a0);
+      if (RB) D[i] = a0;
     }
     done = nvec << 4;
   }
-  // element-wise remainder (or everything, when unaligned)
+  // element-wise remainder (or everything, when a user buffer is unaligned)
   if (done < bytes) {
     if (DT == DT_F32 || DT == DT_I32) {
-      const uint32_t* S0 = (const uint32_t*)((const char*)s0 + done);
-      const uint32_t* S1 = (const uint32_t*)((const char*)s1 + done);
-      uint32_t* D0 = (uint32_t*)((char*)d0 + done);
-      uint32_t* D1 = (uint32_t*)((char*)d1 + done);
-      const uint32_t n = (bytes - done) >> 2;
-      for (uint32_t i = tid; i < n; i += NT) {
-        uint32_t v = S0[i];
-        if (NSRC == 2) v = add_word<DT>(v, S1[i]);
-        D0[i] = v;
-        if (NDST == 2) D1[i] = v;
+      const uint32_t* S = (const uint32_t*)sb;
+      uint32_t* D = (uint32_t*)rb;
+      for (uint32_t o = done + (tid << 2); o < bytes; o += NT << 2) {
+        uint32_t v = 0;
+        if (FIN) v = fin.ld4(o);
+        if (SB) { uint32_t w = S[o >> 2]; v = FIN ? add_word<DT>(v, w) : w; }
+        if (FOUT) fout.st4(o, v);
+        if (RB) D[o >> 2] = v;
       }
     } else {   // 16-bit elements; pure copies also come here (every dtype is a multiple of 2 bytes)
-      const uint16_t* S0 = (const uint16_t*)((const char*)s0 + done);
-      const uint16_t* S1 = (const uint16_t*)((const char*)s1 + done);
-      uint16_t* D0 = (uint16_t*)((char*)d0 + done);
-      uint16_t* D1 = (uint16_t*)((char*)d1 + done);
-      const uint32_t n = (bytes - done) >> 1;
-      for (uint32_t i = tid; i < n; i += NT) {
-        uint16_t v = S0[i];
-        if (NSRC == 2) v = add_half<DT>(v, S1[i]);
-        D0[i] = v;
-        if (NDST == 2) D1[i] = v;
+      const uint16_t* S = (const uint16_t*)sb;
+      uint16_t* D = (uint16_t*)rb;
+      for (uint32_t o = done + (tid << 1); o < bytes; o += NT << 1) {
+        uint16_t v = 0;
+        if (FIN) v = fin.ld2(o);
+        if (SB) { uint16_t w = S[o >> 1]; v = FIN ? add_half<DT>(v, w) : w; }
+        if (FOUT) fout.st2(o, v);
+        if (RB) D[o >> 1] = v;
       }
     }
   }
 }
 
-__device__ __forceinline__ void run_data_phase(int dtype, int nsrc, int ndst, const void* s0, const void* s1,
-                                               void* d0, void* d1, uint32_t bytes) {
-  if (nsrc == 1) {
-    if (ndst == 1) move_slice<DT_COPY, 1, 1>(s0, s1, d0, d1, bytes);
-    else move_slice<DT_COPY, 1, 2>(s0, s1, d0, d1, bytes);
-    return;
-  }
+template <int COH, bool FIN, bool SB, bool RB, bool FOUT>
+__device__ __forceinline__ void move_dispatch(int dtype, const void* fin, const char* sb, char* rb, void* fout, uint32_t bytes) {
+  if (!(FIN && SB)) { move_slice<DT_COPY, COH, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); return; }
   switch (dtype) {
-    case DT_F32:
-      if (ndst == 1) move_slice<DT_F32, 2, 1>(s0, s1, d0, d1, bytes); else move_slice<DT_F32, 2, 2>(s0, s1, d0, d1, bytes);
-      break;
-    case DT_BF16:
-      if (ndst == 1) move_slice<DT_BF16, 2, 1>(s0, s1, d0, d1, bytes); else move_slice<DT_BF16, 2, 2>(s0, s1, d0, d1, bytes);
-      break;
-    case DT_F16:
-      if (ndst == 1) move_slice<DT_F16, 2, 1>(s0, s1, d0, d1, bytes); else move_slice<DT_F16, 2, 2>(s0, s1, d0, d1, bytes);
-      break;
-    default:
-      if (ndst == 1) move_slice<DT_I32, 2, 1>(s0, s1, d0, d1, bytes); else move_slice<DT_I32, 2, 2>(s0, s1, d0, d1, bytes);
-      break;
+    case DT_F32: move_slice<DT_F32, COH, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
+    case DT_BF16: move_slice<DT_BF16, COH, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
+    case DT_F16: move_slice<DT_F16, COH, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
+    default: move_slice<DT_I32, COH, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
+  }
+}
+
+// fin / sb / rb / fout are null when the primitive does not use that side
+template <int COH>
+__device__ __forceinline__ void run_data_phase(int dtype, const void* fin, const char* sb, char* rb, void* fout, uint32_t bytes) {
+  if (fin) {
+    if (sb) {
+      if (rb) { if (fout) move_dispatch<COH, true, true, true, true>(dtype, fin, sb, rb, fout, bytes);   // recv-reduce-copy-send
+                else move_dispatch<COH, true, true, true, false>(dtype, fin, sb, rb, fout, bytes); }      // recv-reduce-copy
+      else move_dispatch<COH, true, true, false, true>(dtype, fin, sb, rb, fout, bytes);                  // recv-reduce-send
+    } else {
+      if (fout) move_dispatch<COH, true, false, true, true>(dtype, fin, sb, rb, fout, bytes);             // recv-copy-send
+      else move_dispatch<COH, true, false, true, false>(dtype, fin, sb, rb, fout, bytes);                 // recv-copy
+    }
+  } else {
+    if (rb) { if (fout) move_dispatch<COH, false, true, true, true>(dtype, fin, sb, rb, fout, bytes);     // copy-send
+              else move_dispatch<COH, false, true, true, false>(dtype, fin, sb, rb, fout, bytes); }       // copy
+    else move_dispatch<COH, false, true, false, true>(dtype, fin, sb, rb, fout, bytes);                   // send
   }
 }
 
@@ -267,6 +308,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   if (a.wg_map == 0) { rank = wg % a.R; ch = wg / a.R; }
   else { rank = wg / a.cmax; ch = wg % a.cmax; }
   const int R = (int)a.R;
+  const bool coh = a.fifo_coherent != 0;
   const uint32_t D = a.sq_depth;
 
   DfxWgState* ws = &a.wgstate[wg];
@@ -333,6 +375,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
     // ================= FetchSQE (Alg. 1 line 2) =================
     if (got) {
       DfxSqSlot* e = &sqbase[ri & (D - 1)];
+      // the submitter wrote the send buffer before the SQE: make that visible to every wave
+      fence_acquire_system();
       if (tid < 6) ((uint4*)&sh.sqe)[tid] = ((const uint4*)&e->e)[tid];
       __syncthreads();
       const uint32_t coll = sh.sqe.coll_id;
@@ -507,22 +551,22 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         res = sh.wres;
         if (res != W_OK) break;
         // every wave invalidates before its own loads of the slot (the poll was wave 0's)
-        if (q.recv) fence_acquire_agent();
+        if (q.recv && !coh) fence_acquire_agent();
 
         // ---- data phase: one slice
         {
-          const void* s0; const void* s1 = nullptr; void* d0; void* d1 = nullptr;
-          const char* in_slot = (const char*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes);
-          char* out_slot = (char*)(fifo_out + (size_t)(sent & (K - 1)) * slot_bytes);
-          if (q.recv) { s0 = in_slot; if (q.from_send) s1 = sendbuf + soff * eb; }
-          else s0 = sendbuf + soff * eb;
-          if (q.to_recv) { d0 = recvbuf + doff * eb; if (q.send) d1 = out_slot; }
-          else d0 = out_slot;
-          if (bytes) run_data_phase(dtype, q.nsrc, q.ndst, s0, s1, d0, d1, bytes);
+          const void* fin = q.recv ? (const void*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
+          void* fout = q.send ? (void*)(fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
+          const char* sb = q.from_send ? sendbuf + soff * eb : nullptr;
+          char* rb = q.to_recv ? recvbuf + doff * eb : nullptr;
+          if (bytes) {
+            if (coh) run_data_phase<1>(dtype, fin, sb, rb, fout, bytes);
+            else run_data_phase<0>(dtype, fin, sb, rb, fout, bytes);
+          }
         }
         drain_and_barrier();
         if (tid == 0) {
-          fence_release_agent();
+          if (!coh) fence_release_agent();
           if (q.send) st_agent64(tail_out, sent + 1);
           if (q.recv) st_agent64(head_in, recvd + 1);
           sh.stat[ST_PRIMS] += 1;

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <immintrin.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -59,6 +60,7 @@ struct dfx_ctx {
   std::atomic<bool> aborted{false};
   int last_hip = 0;
   bool sq_device = false;
+  uint32_t fifo_coherent = 1;        // connector accesses: 1 = device-coherent (sc1), 0 = cached + fences
 
   // host-visible memory
   void* qmem_sq = nullptr;           // SQ ring + host_ctl (pinned host or fine-grained device)
@@ -94,6 +96,8 @@ namespace {
       return DFX_ERR_HIP;                        \
     }                                            \
   } while (0)
+
+int g_init_hip_error = 0;   // hipError_t of the last failing call inside dfx_init
 
 inline uint64_t now_ns() {
   return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(
@@ -151,6 +155,7 @@ int launch_locked(dfx_ctx* c) {
   a.spin_boost = c->cfg.spin_boost; a.preempt = c->cfg.preempt;
   a.wg_map = c->cfg.wg_map; a.order_policy = c->cfg.order_policy; a.trace_on = c->cfg.trace;
   a.fetch_batch = c->cfg.fetch_batch ? c->cfg.fetch_batch : 0xffffffffu;
+  a.fifo_coherent = c->fifo_coherent;
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   HIPCHK(c, hipEventRecord(c->ev_start, c->stream));
@@ -282,6 +287,7 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   dfx_ctx* c = new (std::nothrow) dfx_ctx();
   if (!c) return DFX_ERR_NO_RESOURCES;
   c->cfg = cfg;
+  if (const char* e = getenv("DFX_FIFO_FENCED")) c->fifo_coherent = (e[0] == '1') ? 0u : 1u;   // experiment switch
   c->R = nranks;
   c->nwg = (uint32_t)nranks * cfg.max_channels;
   while ((1u << c->sq_shift) < cfg.sq_depth) c->sq_shift++;
@@ -289,7 +295,7 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
 #define INITCHK(call)                                      \
   do {                                                     \
     hipError_t e_ = (call);                                \
-    if (e_ != hipSuccess) { free_all(c); return DFX_ERR_HIP; } \
+    if (e_ != hipSuccess) { g_init_hip_error = (int)e_; free_all(c); return DFX_ERR_HIP; } \
   } while (0)
 
   INITCHK(hipGetDevice(&c->device));
@@ -647,6 +653,8 @@ int dfx_finalize(dfx_ctx* c) {
 }
 
 int dfx_last_hip_error(dfx_ctx* c) { return c ? c->last_hip : 0; }
+
+int dfx_last_init_error(void) { return g_init_hip_error; }
 
 const char* dfx_strerror(int s) {
   switch (s) {

@@ -96,7 +96,7 @@ struct DfxDaemonArgs {
   uint64_t* trace;          // [nwg][DFX_TRACE_N] device (or null)
   uint32_t R, cmax, max_colls, sq_depth, sq_shift, cq_slots;
   uint32_t spin_init, spin_min, spin_max, spin_boost, preempt;
-  uint32_t wg_map, order_policy, trace_on, fetch_batch;
+  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent;
   uint64_t watchdog_ticks;  // wall-clock ticks; 0 = off
   uint64_t quit_ticks;      // wall-clock ticks; 0 = off
 };
