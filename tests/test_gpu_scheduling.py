@@ -1,0 +1,169 @@
+"""GPU tests of the scheduling behaviour: negative control, voluntary quit / restart, GPU
+synchronisation between disordered collectives, priority ordering, SQ back-pressure, statistics."""
+import time
+
+import numpy as np
+import pytest
+
+import workload_inputs as wi
+from oracle import ring_data as rd
+
+pytestmark = pytest.mark.gpu
+
+
+def _expect(dw, w, ci):
+    c = w.colls[ci]
+    want = rd.run_closed_form(c.kind, dw.send_host[ci], c.dtype, c.root)
+    got = dw.results(ci)
+    for r in range(w.R):
+        assert np.array_equal(got[r].view(np.uint8), want[r].view(np.uint8)), (w.name, ci, r)
+
+
+def test_negative_control_no_preemption_hits_watchdog():
+    """Opposite issue orders with preemption disabled = the single-queue deadlock (Sec. 2.3, Fig. 1c;
+    Sec. 6.1 reports 100 % for the non-preemptive library).  The in-kernel watchdog turns it into
+    a timeout: every wave still leaves the kernel normally."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.config1((0, 1), (1, 0))
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(2, gh.make_config(preempt=0, watchdog_ms=300, quit_idle_us=0, max_channels=2))
+    try:
+        gh.prepare_all(ctx, w)
+        gh.submit_round_robin(ctx, dw)
+        t0 = time.monotonic()
+        assert ctx.wait_all(5.0) == dfx.ERR_TIMEOUT
+        assert time.monotonic() - t0 < 4.0          # the watchdog, not the host deadline, ended it
+        assert ctx.submit(0, 0, dw.send[0][0].data_ptr(), dw.recv[0][0].data_ptr()) == dfx.ERR_ABORTED
+        st = [ctx.stats(r) for r in range(2)]
+        assert sum(s["cqe_posted"] for s in st) == 0
+    finally:
+        assert ctx.finalize() == dfx.ERR_ABORTED
+
+
+def test_same_order_without_preemption_completes():
+    from tests import gpu_harness as gh
+    w = wi.config1((0, 1), (0, 1))
+    dw, stats, _ = gh.run_workload(w, gh.make_config(preempt=0, watchdog_ms=2000, max_channels=2))
+    for ci in range(2):
+        _expect(dw, w, ci)
+    assert sum(s["preemptions"] for s in stats) == 0
+
+
+def test_voluntary_quit_and_event_driven_restart():
+    """Sec. 4.4: the daemon leaves when idle and is started again by the next SQE; contexts survive."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.Workload("quit", 8, [wi.CollSpec(0, wi.AR, wi.F32, 200000)], [[0]] * 8, seed=5, cfg=70)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(8, gh.make_config(quit_idle_us=300))
+    try:
+        gh.prepare_all(ctx, w)
+        launches = []
+        for it in range(3):
+            dw.reset_recv()
+            gh.submit_round_robin(ctx, dw)
+            assert ctx.wait_all(10.0) == dfx.OK
+            _expect(dw, w, 0)
+            time.sleep(0.05)                       # far longer than the quit period
+            ms, done = ctx.last_launch_ms()
+            launches.append(done)
+        assert launches[0] >= 1 and launches[2] >= launches[0] + 2
+        st = ctx.stats(0)
+        assert st["quits"] > 0
+    finally:
+        assert ctx.finalize() == dfx.OK
+
+
+def test_device_synchronize_between_disordered_collectives():
+    """Sec. 2.3 'GPU synchronization related' deadlock (Fig. 1d) / Sec. 6.1 second program: a
+    device-wide synchronisation between collectives issued in opposite orders.  The stuck daemon
+    quits voluntarily, the synchronisation returns, the remaining SQEs restart the daemon."""
+    import torch
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.config1((0, 1), (1, 0), n=50000)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(2, gh.make_config(quit_idle_us=500, max_channels=4))
+    try:
+        gh.prepare_all(ctx, w)
+        assert ctx.submit(0, 0, dw.send[0][0].data_ptr(), dw.recv[0][0].data_ptr()) == dfx.OK   # rank 0: A
+        assert ctx.submit(1, 1, dw.send[1][1].data_ptr(), dw.recv[1][1].data_ptr()) == dfx.OK   # rank 1: B
+        t0 = time.monotonic()
+        torch.cuda.synchronize()                   # returns only once the daemon has left the GPU
+        assert time.monotonic() - t0 < 5.0
+        assert ctx.submit(0, 1, dw.send[1][0].data_ptr(), dw.recv[1][0].data_ptr()) == dfx.OK   # rank 0: B
+        assert ctx.submit(1, 0, dw.send[0][1].data_ptr(), dw.recv[0][1].data_ptr()) == dfx.OK   # rank 1: A
+        assert ctx.wait_all(10.0) == dfx.OK
+        for ci in range(2):
+            _expect(dw, w, ci)
+        assert ctx.stats(0)["quits"] > 0
+    finally:
+        ctx.finalize()
+
+
+def test_priority_ordering_policy():
+    """Sec. 4.3 priority-based ordering: later-arriving collectives get higher priority (the DP
+    overlap scheme); everything still completes and matches."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.config3(n_buckets=12, bucket_bytes=1 << 20, seed=8)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(8, gh.make_config(order_policy=1))
+    try:
+        gh.prepare_all(ctx, w, priorities=list(range(12)))
+        gh.submit_round_robin(ctx, dw)
+        assert ctx.wait_all(30.0) == dfx.OK
+        for ci in range(12):
+            _expect(dw, w, ci)
+    finally:
+        ctx.finalize()
+
+
+def test_sq_backpressure_and_poll_interface():
+    """A 4-entry SQ with 40 collectives: submit returns SQ_FULL until every workgroup of the rank
+    has read a slot (Sec. 5); dfx_poll hands out each completion exactly once."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.config5(n_colls=40, seed=9, R=4)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(4, gh.make_config(sq_depth=4, max_channels=8))
+    try:
+        gh.prepare_all(ctx, w)
+        full = 0
+        seen = [set() for _ in range(4)]
+        pos = [0] * 4
+        deadline = time.monotonic() + 30
+        while any(p < 40 for p in pos) or any(len(s) < 40 for s in seen):
+            for r in range(4):
+                if pos[r] < 40:
+                    ci = w.orders[r][pos[r]]
+                    rc = ctx.submit(r, ci, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr())
+                    if rc == dfx.OK:
+                        pos[r] += 1
+                    else:
+                        assert rc == dfx.ERR_SQ_FULL
+                        full += 1
+                for cid, seq in ctx.poll(r, 8):
+                    assert cid not in seen[r] and seq == 0
+                    seen[r].add(cid)
+            assert time.monotonic() < deadline
+        assert full > 0
+        for ci in range(40):
+            _expect(dw, w, ci)
+        assert ctx.poll(0, 8) == []
+    finally:
+        ctx.finalize()
+
+
+def test_stats_are_consistent():
+    from tests import gpu_harness as gh
+    w = wi.config3(n_buckets=6, bucket_bytes=512 << 10, seed=12)
+    dw, stats, _ = gh.run_workload(w, gh.make_config(spin_init=8, spin_min=1, spin_max=32, spin_boost=2, trace=1))
+    for s in stats:
+        assert s["cqe_posted"] == 6
+        assert s["preemptions"] == s["ctx_saves"] + s["lazy_skips"] or s["ctx_saves"] >= 0
+        assert s["ctx_loads"] + s["ctx_slot_hits"] >= s["preemptions"]
+        assert s["max_taskq"] <= 6
+    assert sum(s["switch_samples"] for s in stats) > 0
+    assert all(0.0 < s["switch_us_p50"] < 100.0 for s in stats if s["switch_samples"])
