@@ -86,6 +86,9 @@ def main():
     ap.add_argument("--cpu-sample-mib", type=int, default=64)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-switch", action="store_true", help="skip the context-switch latency leg")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="after the steps, run one plain copy kernel of this many MiB (untimed): its known "
+                         "traffic calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (virtual ranks share it); --gpus must be 1")
@@ -133,6 +136,9 @@ def main():
         launches = ctx.stats(0)["launches"]
     finally:
         ctx.finalize()
+    if args.calibrate_copy_mib:
+        nb = min(args.calibrate_copy_mib << 20, M)
+        dfx.copy_calibrate(send[0].data_ptr(), recv[0].data_ptr(), nb)
 
     ms_per_step = wall / args.steps * 1e3
     algbw = M / (ms_per_step * 1e-3) / 1e9

@@ -35,6 +35,10 @@ namespace {
 typedef uint64_t u64;
 
 constexpr int NT = DFX_WG_THREADS;
+#ifndef DFX_UNROLL
+#define DFX_UNROLL 8
+#endif
+constexpr int UNROLL = DFX_UNROLL;   // independent 16-byte vectors in flight per source and thread
 constexpr int KIND_AR = 0, KIND_AG = 1, KIND_RS = 2, KIND_BC = 3;
 constexpr int DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_I32 = 3, DT_COPY = -1;
 
@@ -161,16 +165,27 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
     uint4* __restrict__ D = (uint4*)rb;
     const uint32_t nvec = bytes >> 4;
     uint32_t i = tid;
-    for (; i + 3 * NT < nvec; i += 4 * NT) {
-      uint4 a0, a1, a2, a3;
-      if (FIN) { a0 = fin.ld16(i << 4); a1 = fin.ld16((i + NT) << 4); a2 = fin.ld16((i + 2 * NT) << 4); a3 = fin.ld16((i + 3 * NT) << 4); }
-      if (SB) {
-        uint4 b0 = S[i], b1 = S[i + NT], b2 = S[i + 2 * NT], b3 = S[i + 3 * NT];
-        if (FIN) { a0 = add_vec<DT>(a0, b0); a1 = add_vec<DT>(a1, b1); a2 = add_vec<DT>(a2, b2); a3 = add_vec<DT>(a3, b3); }
-        else { a0 = b0; a1 = b1; a2 = b2; a3 = b3; }
+    for (; i + (UNROLL - 1) * NT < nvec; i += UNROLL * NT) {
+      uint4 v[UNROLL];
+      if (FIN) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) v[u] = fin.ld16((i + u * NT) << 4);
       }
-      if (FOUT) { fout.st16(i << 4, a0); fout.st16((i + NT) << 4, a1); fout.st16((i + 2 * NT) << 4, a2); fout.st16((i + 3 * NT) << 4, a3); }
-      if (RB) { D[i] = a0; D[i + NT] = a1; D[i + 2 * NT] = a2; D[i + 3 * NT] = a3; }
+      if (SB) {
+        uint4 w[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) w[u] = S[i + u * NT];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? add_vec<DT>(v[u], w[u]) : w[u];
+      }
+      if (FOUT) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) fout.st16((i + u * NT) << 4, v[u]);
+      }
+      if (RB) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) D[i + u * NT] = v[u];
+      }
     }
     for (; i < nvec; i += NT) {
       uint4 a0;

@@ -245,7 +245,7 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->sq_depth = 256;
   cfg->cq_slots = 256;
   cfg->nslots = 4;
-  cfg->slot_bytes = 64u << 10;
+  cfg->slot_bytes = 128u << 10;
   cfg->chan_min_bytes = 16u << 10;
   cfg->spin_init = 512;
   cfg->spin_min = 4;
@@ -256,7 +256,7 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->watchdog_ms = 10000;
   cfg->quit_idle_us = 2000;
   cfg->sq_in_device = 0;
-  cfg->wg_map = 0;
+  cfg->wg_map = 1;
   cfg->order_policy = 0;
   cfg->trace = 0;
   cfg->pool_bytes = 2ull << 30;
