@@ -21,8 +21,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 R = 8
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
-# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md); None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md): reads 5 810 615 KiB + writes
+# 5 769 075 KiB per launch at the default workload.  Reported only for that workload.
+MEASURED_TRAFFIC_BYTES = 11857602560
 
 
 def algorithmic_bytes(msg_bytes: int, nranks: int) -> int:
@@ -158,7 +159,8 @@ def main():
         "algbw_GBs": round(algbw, 2),
         "hbm_frac_wall": round(algorithmic_bytes(M, R) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES if args.msg_mib == 256 else None,
                      "kernel": "dfx_daemon_kernel", "kernel_ms_avg": round(k_ms, 4),
                      "algorithmic_bytes_per_launch": algorithmic_bytes(M, R)},
     }

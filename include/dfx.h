@@ -103,6 +103,9 @@ typedef struct {
   double switch_us_mean;
   double save_us_mean;     /* the save part of a switch */
   double load_us_mean;     /* the load part of a switch */
+  double wait_us;          /* with trace on: time in wait phases, summed over the vrank's workgroups */
+  double data_us;          /* ... in data phases (loads issued until stores issued) */
+  double publish_us;       /* ... draining stores, barrier and counter stores */
 } dfx_stats_t;
 
 /* Fill *cfg with defaults (struct_bytes set). cfg: host, caller-owned. */

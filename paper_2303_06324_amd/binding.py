@@ -32,7 +32,8 @@ class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "preemptions", "ctx_loads", "ctx_slot_hits", "ctx_saves", "lazy_skips", "polls", "prims", "sqe_fetched",
         "cqe_posted", "max_taskq", "passes", "quits", "launches", "switch_samples")] + [(n, C.c_double) for n in (
-        "switch_us_p50", "switch_us_p99", "switch_us_mean", "save_us_mean", "load_us_mean")]
+        "switch_us_p50", "switch_us_p99", "switch_us_mean", "save_us_mean", "load_us_mean", "wait_us", "data_us",
+        "publish_us")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

@@ -18,16 +18,18 @@ FLAGS = [
 
 def build(verbose: bool = False) -> str:
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
-    cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB + ".tmp", "-lpthread"]
+    extra = os.environ.get("DFX_EXTRA_DEFS", "").split()      # e.g. "-DDFX_UNROLL=4" for experiments
+    out = os.environ.get("DFX_BUILD_OUT", LIB)
+    cmd = [hipcc] + FLAGS + extra + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out + ".tmp", "-lpthread"]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + err)
-    os.replace(LIB + ".tmp", LIB)
+    os.replace(out + ".tmp", out)
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -130,10 +130,33 @@ __device__ __forceinline__ uint16_t add_half(uint16_t a, uint16_t b) {
 // ------------------------------------------------------------------------------------------
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
-template <int COH>
+#ifndef DFX_USER_NT
+#define DFX_USER_NT 1
+#endif
+// user-buffer accesses of the main loop are marked non-temporal: each byte is touched once, and
+// keeping it out of the way leaves the memory-side cache to the connector slots (+3 % measured)
+__device__ __forceinline__ uint4 ld_user(const uint4* p) {
+#if DFX_USER_NT
+  return __builtin_bit_cast(uint4, __builtin_nontemporal_load((const v4u*)p));
+#else
+  return *p;
+#endif
+}
+__device__ __forceinline__ void st_user(uint4* p, uint4 v) {
+#if DFX_USER_NT
+  __builtin_nontemporal_store(__builtin_bit_cast(v4u, v), (v4u*)p);
+#else
+  *p = v;
+#endif
+}
+
+// cache-policy operand of the buffer instructions (gfx940+): bit 0 = sc0, bit 4 = sc1
+constexpr int AUX_CACHED = 0;    // ordinary cached access (per-CU cache, write-back in this XCD's L2)
+constexpr int AUX_DEVICE = 16;   // sc1: device scope, coherent across the XCDs' L2s
+
+template <int AUX>
 struct Slot {   // one connector slot seen through a buffer resource
   __amdgpu_buffer_rsrc_t rsrc;
-  static constexpr int AUX = COH ? 16 : 0;   // cache-policy bit 4 = sc1
   __device__ __forceinline__ Slot(const void* base, uint32_t bytes) {
     rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
   }
@@ -149,13 +172,14 @@ struct Slot {   // one connector slot seen through a buffer resource
   __device__ __forceinline__ void st2(uint32_t off, uint16_t v) const { __builtin_amdgcn_raw_buffer_store_b16(v, rsrc, (int)off, 0, AUX); }
 };
 
-template <int DT, int COH, bool FIN, bool SB, bool RB, bool FOUT>
+template <int DT, int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT>
 __device__ __forceinline__ void move_slice(const void* fin_p, const char* __restrict__ sb, char* __restrict__ rb,
                                            void* fout_p, uint32_t bytes) {
   static_assert(FIN || SB, "a primitive has a source");
   static_assert(RB || FOUT, "a primitive has a destination");
   const uint32_t tid = threadIdx.x;
-  const Slot<COH> fin(fin_p, FIN ? bytes : 0), fout(fout_p, FOUT ? bytes : 0);
+  const Slot<AIN> fin(fin_p, FIN ? bytes : 0);
+  const Slot<AOUT> fout(fout_p, FOUT ? bytes : 0);
   uintptr_t al = 0;
   if (SB) al |= (uintptr_t)sb;
   if (RB) al |= (uintptr_t)rb;
@@ -174,7 +198,7 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
       if (SB) {
         uint4 w[UNROLL];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) w[u] = S[i + u * NT];
+        for (int u = 0; u < UNROLL; ++u) w[u] = ld_user(&S[i + u * NT]);
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? add_vec<DT>(v[u], w[u]) : w[u];
       }
@@ -184,7 +208,7 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
       }
       if (RB) {
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) D[i + u * NT] = v[u];
+        for (int u = 0; u < UNROLL; ++u) st_user(&D[i + u * NT], v[u]);
       }
     }
     for (; i < nvec; i += NT) {
@@ -222,33 +246,34 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
   }
 }
 
-template <int COH, bool FIN, bool SB, bool RB, bool FOUT>
+template <int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT>
 __device__ __forceinline__ void move_dispatch(int dtype, const void* fin, const char* sb, char* rb, void* fout, uint32_t bytes) {
-  if (!(FIN && SB)) { move_slice<DT_COPY, COH, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); return; }
+  if (!(FIN && SB)) { move_slice<DT_COPY, AIN, AOUT, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); return; }
   switch (dtype) {
-    case DT_F32: move_slice<DT_F32, COH, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
-    case DT_BF16: move_slice<DT_BF16, COH, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
-    case DT_F16: move_slice<DT_F16, COH, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
-    default: move_slice<DT_I32, COH, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
+    case DT_F32: move_slice<DT_F32, AIN, AOUT, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
+    case DT_BF16: move_slice<DT_BF16, AIN, AOUT, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
+    case DT_F16: move_slice<DT_F16, AIN, AOUT, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
+    default: move_slice<DT_I32, AIN, AOUT, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
   }
 }
 
-// fin / sb / rb / fout are null when the primitive does not use that side
-template <int COH>
-__device__ __forceinline__ void run_data_phase(int dtype, const void* fin, const char* sb, char* rb, void* fout, uint32_t bytes) {
+// fin / sb / rb / fout are null when the primitive does not use that side.
+// AUX: how connector slots are accessed (AUX_DEVICE, or AUX_CACHED in the fenced mode).
+template <int AUX>
+__device__ __forceinline__ void run_prim(int dtype, const void* fin, const char* sb, char* rb, void* fout, uint32_t bytes) {
   if (fin) {
     if (sb) {
-      if (rb) { if (fout) move_dispatch<COH, true, true, true, true>(dtype, fin, sb, rb, fout, bytes);   // recv-reduce-copy-send
-                else move_dispatch<COH, true, true, true, false>(dtype, fin, sb, rb, fout, bytes); }      // recv-reduce-copy
-      else move_dispatch<COH, true, true, false, true>(dtype, fin, sb, rb, fout, bytes);                  // recv-reduce-send
+      if (rb) { if (fout) move_dispatch<AUX, AUX, true, true, true, true>(dtype, fin, sb, rb, fout, bytes);    // recv-reduce-copy-send
+                else move_dispatch<AUX, AUX, true, true, true, false>(dtype, fin, sb, rb, fout, bytes); }      // recv-reduce-copy
+      else move_dispatch<AUX, AUX, true, true, false, true>(dtype, fin, sb, rb, fout, bytes);                  // recv-reduce-send
     } else {
-      if (fout) move_dispatch<COH, true, false, true, true>(dtype, fin, sb, rb, fout, bytes);             // recv-copy-send
-      else move_dispatch<COH, true, false, true, false>(dtype, fin, sb, rb, fout, bytes);                 // recv-copy
+      if (fout) move_dispatch<AUX, AUX, true, false, true, true>(dtype, fin, sb, rb, fout, bytes);             // recv-copy-send
+      else move_dispatch<AUX, AUX, true, false, true, false>(dtype, fin, sb, rb, fout, bytes);                 // recv-copy
     }
   } else {
-    if (rb) { if (fout) move_dispatch<COH, false, true, true, true>(dtype, fin, sb, rb, fout, bytes);     // copy-send
-              else move_dispatch<COH, false, true, true, false>(dtype, fin, sb, rb, fout, bytes); }       // copy
-    else move_dispatch<COH, false, true, false, true>(dtype, fin, sb, rb, fout, bytes);                   // send
+    if (rb) { if (fout) move_dispatch<AUX, AUX, false, true, true, true>(dtype, fin, sb, rb, fout, bytes);     // copy-send
+              else move_dispatch<AUX, AUX, false, true, true, false>(dtype, fin, sb, rb, fout, bytes); }       // copy
+    else move_dispatch<AUX, AUX, false, true, false, true>(dtype, fin, sb, rb, fout, bytes);                   // send
   }
 }
 
@@ -515,6 +540,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         else if (kind == KIND_RS) soff += (u64)q.cidx * count;
         else if (kind == KIND_AG) doff += (u64)q.cidx * count;
 
+        u64 tm0 = 0, tm1 = 0, tm2 = 0;
+        if (tid == 0 && a.trace_on) tm0 = wall_clock64();
         // ---- wait phase: wave 0 polls, lane 0 the recv side, lane 1 the send side
         if (tid < 64) {
           uint32_t r = W_OK;
@@ -566,8 +593,9 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         res = sh.wres;
         if (res != W_OK) break;
         // every wave invalidates before its own loads of the slot (the poll was wave 0's)
+        // fenced mode: every wave invalidates before its own loads of the slot (the poll was wave 0's)
         if (q.recv && !coh) fence_acquire_agent();
-
+        if (tid == 0 && a.trace_on) tm1 = wall_clock64();
         // ---- data phase: one slice
         {
           const void* fin = q.recv ? (const void*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
@@ -575,10 +603,11 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           const char* sb = q.from_send ? sendbuf + soff * eb : nullptr;
           char* rb = q.to_recv ? recvbuf + doff * eb : nullptr;
           if (bytes) {
-            if (coh) run_data_phase<1>(dtype, fin, sb, rb, fout, bytes);
-            else run_data_phase<0>(dtype, fin, sb, rb, fout, bytes);
+            if (coh) run_prim<AUX_DEVICE>(dtype, fin, sb, rb, fout, bytes);
+            else run_prim<AUX_CACHED>(dtype, fin, sb, rb, fout, bytes);
           }
         }
+        if (tid == 0 && a.trace_on) tm2 = wall_clock64();
         drain_and_barrier();
         if (tid == 0) {
           if (!coh) fence_release_agent();
@@ -586,6 +615,10 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           if (q.recv) st_agent64(head_in, recvd + 1);
           sh.stat[ST_PRIMS] += 1;
           acted = true;
+          if (a.trace_on) {
+            const u64 tm3 = wall_clock64();
+            sh.stat[ST_T_WAIT] += tm1 - tm0; sh.stat[ST_T_DATA] += tm2 - tm1; sh.stat[ST_T_PUB] += tm3 - tm2;
+          }
         }
         if (q.send) ++sent;
         if (q.recv) ++recvd;

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <immintrin.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -60,7 +61,7 @@ struct dfx_ctx {
   std::atomic<bool> aborted{false};
   int last_hip = 0;
   bool sq_device = false;
-  uint32_t fifo_coherent = 1;        // connector accesses: 1 = device-coherent (sc1), 0 = cached + fences
+  uint32_t fifo_coherent = 1;        // connector accesses: 1 = device-coherent (sc1), 0 = cached + agent-scope fences
 
   // host-visible memory
   void* qmem_sq = nullptr;           // SQ ring + host_ctl (pinned host or fine-grained device)
@@ -287,7 +288,7 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   dfx_ctx* c = new (std::nothrow) dfx_ctx();
   if (!c) return DFX_ERR_NO_RESOURCES;
   c->cfg = cfg;
-  if (const char* e = getenv("DFX_FIFO_FENCED")) c->fifo_coherent = (e[0] == '1') ? 0u : 1u;   // experiment switch
+  if (const char* e = getenv("DFX_FIFO_FENCED")) c->fifo_coherent = (e[0] == '1') ? 0u : 1u;   // comparison switch
   c->R = nranks;
   c->nwg = (uint32_t)nranks * cfg.max_channels;
   while ((1u << c->sq_shift) < cfg.sq_depth) c->sq_shift++;
@@ -591,6 +592,8 @@ int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
     out->ctx_saves += s[ST_SAVE]; out->lazy_skips += s[ST_LAZY]; out->polls += s[ST_POLLS]; out->prims += s[ST_PRIMS];
     out->sqe_fetched += s[ST_SQE]; out->cqe_posted += s[ST_CQE]; out->passes += s[ST_PASSES]; out->quits += s[ST_QUITS];
     out->max_taskq = std::max<uint64_t>(out->max_taskq, s[ST_MAXQ]);
+    out->wait_us += (double)s[ST_T_WAIT] * c->tick_us; out->data_us += (double)s[ST_T_DATA] * c->tick_us;
+    out->publish_us += (double)s[ST_T_PUB] * c->tick_us;
     wgs.push_back(wg);
     tn.push_back(h[wg].trace_n);
   }

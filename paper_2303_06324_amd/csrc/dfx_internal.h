@@ -9,7 +9,7 @@
 #define DFX_CTX_SLOTS 4         // LDS active context slots, direct-mapped by coll_id (Sec. 5)
 #define DFX_TRACE_N 4096        // context-switch latency samples kept per workgroup
 #define DFX_FLAG_STRIDE 128     // bytes per (edge, channel) flag pair: tail at +0, head at +64
-#define DFX_NSTAT 12
+#define DFX_NSTAT 16
 
 #define DFX_SQE_EXIT 1u
 
@@ -71,10 +71,11 @@ struct alignas(16) DfxWgState {
   uint32_t trace_n;      // trace samples written (monotone)
   uint64_t stat[DFX_NSTAT];
   uint64_t dbg[8];       // filled when the watchdog fires
-  uint64_t pad[2];
+  uint64_t pad[6];
 };
 
-enum { ST_PREEMPT = 0, ST_LOAD, ST_HIT, ST_SAVE, ST_LAZY, ST_POLLS, ST_PRIMS, ST_SQE, ST_CQE, ST_MAXQ, ST_PASSES, ST_QUITS };
+enum { ST_PREEMPT = 0, ST_LOAD, ST_HIT, ST_SAVE, ST_LAZY, ST_POLLS, ST_PRIMS, ST_SQE, ST_CQE, ST_MAXQ, ST_PASSES, ST_QUITS,
+       ST_T_WAIT, ST_T_DATA, ST_T_PUB, ST_T_SPARE };   // wall-clock ticks, only with trace on
 
 // dev_ctl words (device memory)
 enum { DC_ABORT = 0, DC_ERR = 1, DC_ERR_WG = 2, DC_N = 16 };
