@@ -145,6 +145,17 @@ int dfx_prepare(dfx_ctx* ctx, int coll_id, dfx_kind kind, size_t count, dfx_dtyp
 int dfx_submit(dfx_ctx* ctx, int rank, int coll_id, const void* sendbuf, void* recvbuf);
 
 /*
+ * Submit n collectives of one vrank in the given order (a burst of dfcclRun* calls, e.g. the
+ * gradient buckets of one backward pass): element i is dfx_submit(ctx, rank, coll_ids[i],
+ * sendbufs[i], recvbufs[i]).  A full SQ is retried until timeout_ns has passed.  The three arrays
+ * are host arrays of n entries, read only during the call; the buffers they point to are device
+ * memory under the rules of dfx_submit.  Returns how many were submitted (n on success, fewer on
+ * timeout or on an error after the first), or the negative status of the first submission.
+ */
+int dfx_submit_many(dfx_ctx* ctx, int rank, int n, const int* coll_ids, const void* const* sendbufs,
+                    void* const* recvbufs, uint64_t timeout_ns);
+
+/*
  * Take up to max completions of one vrank (the poller's job, Sec. 3.1).  out: host.
  * Returns the number of CQEs written to out (>= 0) or a negative status.  Restarts a daemon
  * that quit voluntarily while work is outstanding.

@@ -66,6 +66,7 @@ def _load() -> C.CDLL:
         "dfx_init": ([C.POINTER(vp), i, C.POINTER(Config), vp], i),
         "dfx_prepare": ([vp, i, i, sz, i, i, i, i], i),
         "dfx_submit": ([vp, i, i, vp, vp], i),
+        "dfx_submit_many": ([vp, i, i, C.POINTER(C.c_int), C.POINTER(vp), C.POINTER(vp), u64], i),
         "dfx_poll": ([vp, i, C.POINTER(Cqe), i], i),
         "dfx_wait": ([vp, i, i, u64], i),
         "dfx_wait_all": ([vp, u64], i),
@@ -120,6 +121,14 @@ class Context:
     def submit(self, rank: int, coll_id: int, sendbuf: int, recvbuf: int) -> int:
         """Returns the status (OK, ERR_SQ_FULL, ERR_BUSY ...) without raising: callers retry."""
         return _lib.dfx_submit(self._h, rank, coll_id, C.c_void_p(sendbuf), C.c_void_p(recvbuf))
+
+    def submit_many(self, rank: int, coll_ids, sendbufs, recvbufs, timeout_s: float = 30.0) -> int:
+        """Burst submission in C (the GIL is released for the whole call). Returns the count submitted."""
+        n = len(coll_ids)
+        ids = (C.c_int * n)(*coll_ids)
+        sb = (C.c_void_p * n)(*sendbufs)
+        rb = (C.c_void_p * n)(*recvbufs)
+        return _lib.dfx_submit_many(self._h, rank, n, ids, sb, rb, int(timeout_s * 1e9))
 
     def poll(self, rank: int, max_n: int = 64) -> List[Tuple[int, int]]:
         buf = (Cqe * max_n)()

@@ -211,12 +211,29 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
         for (int u = 0; u < UNROLL; ++u) st_user(&D[i + u * NT], v[u]);
       }
     }
-    for (; i < nvec; i += NT) {
-      uint4 a0;
-      if (FIN) a0 = fin.ld16(i << 4);
-      if (SB) { uint4 b0 = S[i]; a0 = FIN ? add_vec<DT>(a0, b0) : b0; }
-      if (FOUT) fout.st16(i << 4, a0);
-      if (RB) D[i] = a0;
+    if (i < nvec) {
+      // remainder: the same unrolled shape with per-vector predicates, so that all loads of the
+      // tail are in flight together (a short slice is one such block: one memory round trip)
+      uint4 v[UNROLL];
+      if (FIN) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) v[u] = fin.ld16((i + u * NT) << 4);   // out of range reads return 0
+      }
+      if (SB) {
+        uint4 w[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) w[u] = (i + u * NT < nvec) ? ld_user(&S[i + u * NT]) : uint4{0, 0, 0, 0};
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? add_vec<DT>(v[u], w[u]) : w[u];
+      }
+      if (FOUT) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) if (i + u * NT < nvec) fout.st16((i + u * NT) << 4, v[u]);
+      }
+      if (RB) {
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) if (i + u * NT < nvec) st_user(&D[i + u * NT], v[u]);
+      }
     }
     done = nvec << 4;
   }

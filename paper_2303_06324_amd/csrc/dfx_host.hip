@@ -248,10 +248,10 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->nslots = 4;
   cfg->slot_bytes = 128u << 10;
   cfg->chan_min_bytes = 16u << 10;
-  cfg->spin_init = 512;
-  cfg->spin_min = 4;
-  cfg->spin_max = 2048;
-  cfg->spin_boost = 4;
+  cfg->spin_init = 16;
+  cfg->spin_min = 2;
+  cfg->spin_max = 64;
+  cfg->spin_boost = 2;
   cfg->fetch_batch = 0;
   cfg->preempt = 1;
   cfg->watchdog_ms = 10000;
@@ -457,6 +457,22 @@ int dfx_submit(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* rec
   int rr = ensure_running(c);
   if (rr != DFX_OK) return rr;
   return rc;
+}
+
+int dfx_submit_many(dfx_ctx* c, int rank, int n, const int* coll_ids, const void* const* sendbufs,
+                    void* const* recvbufs, uint64_t timeout_ns) {
+  if (!c || n < 0 || (n > 0 && (!coll_ids || !sendbufs || !recvbufs))) return DFX_ERR_INVALID_ARG;
+  const uint64_t t0 = now_ns();
+  uint32_t spins = 0;
+  int i = 0;
+  while (i < n) {
+    const int rc = dfx_submit(c, rank, coll_ids[i], sendbufs[i], recvbufs[i]);
+    if (rc == DFX_OK) { ++i; spins = 0; continue; }
+    if (rc != DFX_ERR_SQ_FULL) return i > 0 ? i : rc;
+    if (now_ns() - t0 > timeout_ns) return i;
+    backoff(spins);
+  }
+  return i;
 }
 
 int dfx_poll(dfx_ctx* c, int rank, dfx_cqe* out, int max) {

@@ -107,6 +107,13 @@ def submit_threads(ctx: "dfx.Context", dw: DeviceWorkload, orders=None, delays_u
 
     def work(r):
         try:
+            if not delays_us:      # one native burst per rank: the host threads really run concurrently
+                ids = [w.colls[ci].coll_id for ci in orders[r]]
+                n = ctx.submit_many(r, ids, [dw.send[ci][r].data_ptr() for ci in orders[r]],
+                                    [dw.recv[ci][r].data_ptr() for ci in orders[r]], timeout_s)
+                if n != len(ids):
+                    raise dfx.DfxError(n if n < 0 else dfx.ERR_TIMEOUT, f"dfx_submit_many(rank={r}) -> {n}")
+                return
             for j, ci in enumerate(orders[r]):
                 if delays_us:
                     t_end = time.perf_counter() + delays_us[r][j] * 1e-6
