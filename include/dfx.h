@@ -77,7 +77,8 @@ typedef struct {
                               2: choose 1 when the device reports a large BAR, else 0 */
   uint32_t wg_map;         /* 0: workgroup = channel*nranks + rank; 1: workgroup = rank*max_channels + channel */
   uint32_t order_policy;   /* 0 = FIFO ordering, 1 = priority ordering (Sec. 4.3) */
-  uint32_t trace;          /* 1 = record context-switch latency samples */
+  uint32_t trace;          /* 1 = record context-switch latency samples (two clock reads per switch);
+                              2 = also time the save / load parts and the wait / data / publish phases */
   uint32_t fetch_batch;    /* SQEs a workgroup may fetch in a row when its queue is empty or stuck; 0 = all available */
   uint64_t pool_bytes;     /* device memory reserved for connectors of all prepared collectives */
 } dfx_config;
@@ -141,6 +142,9 @@ int dfx_prepare(dfx_ctx* ctx, int coll_id, dfx_kind kind, size_t count, dfx_dtyp
  * unread (recvbuf) until this rank's CQE for the invocation; they may differ between
  * invocations of one coll_id (Sec. 4.2) and must not overlap each other.
  * Errors: INVALID_ARG, NOT_PREPARED, BUSY, SQ_FULL (retry), ABORTED, HIP.
+ * There is no poller thread: completions wait in the CQ (cq_slots entries per vrank) until
+ * dfx_poll / dfx_wait / dfx_wait_all take them, or until a dfx_submit on that vrank finds the SQ full
+ * and moves them to the host-side list itself.  A vrank whose CQ is full stops making progress.
  */
 int dfx_submit(dfx_ctx* ctx, int rank, int coll_id, const void* sendbuf, void* recvbuf);
 

@@ -297,19 +297,25 @@ __device__ __forceinline__ void run_prim(int dtype, const void* fin, const char*
 // ------------------------------------------------------------------------------------------
 // LDS state of one workgroup
 // ------------------------------------------------------------------------------------------
+struct Job {                         // what the scheduler wave hands to all waves for one slice
+  const void* fin; const char* sb; char* rb; void* fout;
+  uint32_t bytes; int dtype;
+};
+
 struct Shared {
   DfxCtxEntry slot[DFX_CTX_SLOTS];   // active context slots (Sec. 5, direct-mapped)
   uint32_t slot_tag[DFX_CTX_SLOTS];
   DfxStatic sqe;                     // SQE being fetched
-  uint32_t ctl_stop, ctl_got;        // thread-0 -> workgroup broadcasts of the control check
-  uint32_t wres;                     // result of a wait phase
+  Job job;
+  uint32_t cmd;                      // scheduler wave -> workgroup: CMD_MOVE or CMD_STOP
   u64 stat[DFX_NSTAT];
   uint16_t taskq[DFX_MAX_COLLS];     // task queue (Sec. 4.2 (1))
 };
 
+enum { CMD_NONE = 0, CMD_MOVE = 1, CMD_STOP = 2 };
+
 // primitive descriptor for (kind, position p in the sequence)
 struct Prim {
-  int nsrc, ndst;          // 1 or 2 sources / destinations
   bool recv, send;         // uses recv / send connector
   bool from_send, to_recv; // touches the send buffer / recv buffer
   uint32_t cidx;           // block (ring chunk) index
@@ -321,7 +327,7 @@ __device__ __forceinline__ Prim make_prim(int kind, int R, int r, int root, uint
   Prim q;
   q.cidx = 0;
   if (R == 1) {  // copy
-    q.recv = q.send = false; q.from_send = q.to_recv = true; q.nsrc = 1; q.ndst = 1;
+    q.recv = q.send = false; q.from_send = q.to_recv = true;
     return q;
   }
   if (kind == KIND_AR || kind == KIND_RS) {
@@ -343,8 +349,6 @@ __device__ __forceinline__ Prim make_prim(int kind, int R, int r, int root, uint
     else if (pos == (uint32_t)R - 1) { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
     else { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
   }
-  q.nsrc = (q.recv && q.from_send) ? 2 : 1;
-  q.ndst = (q.send && q.to_recv) ? 2 : 1;
   return q;
 }
 
@@ -355,18 +359,30 @@ __device__ __forceinline__ void raise_error(const DfxDaemonArgs& a, uint32_t cod
   __hip_atomic_store(&a.dev_ctl[DC_ABORT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
 }
 
+__device__ __forceinline__ uint32_t bcast0(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
 }  // namespace
 
+// Structure of a workgroup: wave 0 is the SCHEDULER, all four waves are MOVERS.
+// The scheduler wave runs Alg. 1 on its own -- control checks, SQE fetch, queue walk, context
+// load, bounded polling, preemption, lazy save, completion -- without any workgroup barrier;
+// its state lives in its registers, the task queue and context slots in LDS.  Only when a poll
+// has succeeded does it post a job (the slice's four pointers) in LDS and meet the other waves
+// at a barrier; all waves move the slice, drain their stores and meet again; the scheduler
+// then publishes the connector counters and goes on.  A context switch therefore costs no
+// barrier at all, a primitive costs two.
 extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(DfxDaemonArgs a) {
   __shared__ Shared sh;
   const uint32_t tid = threadIdx.x;
+  const uint32_t lane = tid & 63u;
+  const bool sched = tid < 64;       // the scheduler wave
   const uint32_t wg = blockIdx.x;
   uint32_t rank, ch;
   if (a.wg_map == 0) { rank = wg % a.R; ch = wg / a.R; }
   else { rank = wg / a.cmax; ch = wg % a.cmax; }
   const int R = (int)a.R;
-  const bool coh = a.fifo_coherent != 0;
   const uint32_t D = a.sq_depth;
+  const bool coh = a.fifo_coherent != 0;
 
   DfxWgState* ws = &a.wgstate[wg];
   DfxCtxEntry* myctx = a.ctxbuf + (size_t)wg * a.max_colls;
@@ -382,164 +398,258 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   for (uint32_t i = tid; i < qlen; i += NT) sh.taskq[i] = qstore[i];
   if (tid < DFX_CTX_SLOTS) sh.slot_tag[tid] = 0xffffffffu;
   if (tid < DFX_NSTAT) sh.stat[tid] = ws->stat[tid];
+  if (tid == 0) sh.cmd = CMD_NONE;
   __syncthreads();
 
-  // thread-0-only bookkeeping
+  // ---- scheduler state (registers of wave 0; the other waves never look at it)
   u64 last_act = wall_clock64();
-  bool acted = true;
+  bool acted = true, voted = false;
   uint32_t iter = 0, idle = 0, burst = 0;
-  // pending context-switch sample (thread 0): t0 = abort decision, ts = after save
-  u64 sw_t0 = 0, sw_ts = 0;
-  bool sw_pending = false;
-
-  bool pass_progress = false;
+  bool in_pass = false, pass_progress = false;
+  uint32_t pos = 0;
   uint32_t stop = STOP_NONE;
+  // context-switch sample in flight: t0 = abort decision, ts = after the save, lb/le = load
+  u64 sw_t0 = 0, sw_ts = 0, sw_lb = 0, sw_le = 0;
+  bool sw_pending = false;
+  // the collective in the active slot
+  bool have = false;
+  uint32_t coll = 0, sl = 0, nprim = 0, rounds = 0, K = 0, nchan = 0, slot_bytes = 0, slice_elems = 0, eb = 4;
+  uint32_t g = 0, p = 0, preempted_before = 0, seq = 0;
+  int kind = 0, dtype = 0, root = 0;
+  u64 count = 0, block_elems = 0, part_elems = 0, sent = 0, recvd = 0, thr = 0;
+  const char* sendbuf = nullptr;
+  char* recvbuf = nullptr;
+  u64 *tail_out = nullptr, *head_out = nullptr, *tail_in = nullptr, *head_in = nullptr;
+  uint8_t *fifo_out = nullptr, *fifo_in = nullptr;
+  bool progressed = false;
+  // a slice that has been handed to the movers and still has to be published
+  bool pending_pub = false, pend_send = false, pend_recv = false;
+  u64 tm1 = 0, tm2 = 0;
 
   for (;;) {
-    // ================= control check + SQ probe (thread 0) =================
-    ++iter;
-    if (tid == 0) {
-      uint32_t s = STOP_NONE;
-      if (ld_agent32(&a.dev_ctl[DC_ABORT])) s = STOP_ABORT;
-      if (!s && (((iter & 31u) == 0) || qlen == 0)) {
-        const u64 now = wall_clock64();
-        if (acted) { last_act = now; acted = false; }
-        if (ld_sys32(&a.host_ctl[HC_ABORT])) s = STOP_ABORT;
-        else if (a.watchdog_ticks && qlen > 0 && now - last_act > a.watchdog_ticks) {
-          ws->dbg[0] = ((u64)sh.taskq[0] << 32) | qlen; ws->dbg[1] = ri; ws->dbg[2] = now - last_act;
-          raise_error(a, 1u, wg);
-          s = STOP_ABORT;
-        } else if (a.quit_ticks && now - last_act > a.quit_ticks) s = STOP_QUIT;
-      }
-      uint32_t got = 0;
-      // FIFO ordering (Sec. 4.3): fetch when the queue is empty or a whole pass made no progress,
-      // then keep fetching what is already there (up to fetch_batch); priority ordering probes
-      // the SQ before every pass.
-      const bool want = (qlen == 0) || !pass_progress || a.order_policy == 1 || (burst > 0 && burst < a.fetch_batch);
-      if (!s && want && qlen < a.max_colls) {
-        DfxSqSlot* e = &sqbase[ri & (D - 1)];
-        const uint32_t gen = (uint32_t)(ri >> a.sq_shift) + 1u;
-        if (__hip_atomic_load(&e->e.ready, __ATOMIC_ACQUIRE, SCOPE_SYSTEM) == gen) got = 1;
-      }
-      sh.ctl_stop = s;
-      sh.ctl_got = got;
-    }
-    __syncthreads();
-    stop = sh.ctl_stop;
-    const uint32_t got = sh.ctl_got;
-    if (stop) break;
-
-    // ================= FetchSQE (Alg. 1 line 2) =================
-    if (got) {
-      DfxSqSlot* e = &sqbase[ri & (D - 1)];
-      // the submitter wrote the send buffer before the SQE: make that visible to every wave
-      fence_acquire_system();
-      if (tid < 6) ((uint4*)&sh.sqe)[tid] = ((const uint4*)&e->e)[tid];
-      __syncthreads();
-      const uint32_t coll = sh.sqe.coll_id;
-      const uint32_t flags = sh.sqe.flags;
-      const uint32_t nchan = sh.sqe.nchan;
-      const bool is_exit = (flags & DFX_SQE_EXIT) != 0;
-      const bool mine = !is_exit && ch < nchan && coll < a.max_colls;
-      if (mine) {
-        // static context of this invocation -> context buffer; restart the sequence, keep the
-        // monotone connector counters of earlier invocations
-        if (tid < 6) ((uint4*)&myctx[coll].st)[tid] = ((const uint4*)&sh.sqe)[tid];
-        if (tid == 6) { myctx[coll].dyn.round = 0; myctx[coll].dyn.prim = 0; myctx[coll].dyn.preempted = 0; }
-        if (tid == 0) {
-          // FIFO ordering: append; priority ordering: keep the queue sorted by priority (stable)
-          uint32_t at = qlen;
-          if (a.order_policy == 1) {
-            const int16_t pr = sh.sqe.priority;
-            while (at > 0 && myctx[sh.taskq[at - 1]].st.priority < pr) { sh.taskq[at] = sh.taskq[at - 1]; --at; }
+    if (sched) {
+      uint32_t cmd = CMD_NONE;
+      while (cmd == CMD_NONE) {
+        // ================= publish the slice the movers have just finished =================
+        if (pending_pub) {
+          pending_pub = false;
+          if (lane == 0) {
+            if (!coh) fence_release_agent();
+            if (pend_send) st_agent64(tail_out, sent + 1);
+            if (pend_recv) st_agent64(head_in, recvd + 1);
+            sh.stat[ST_PRIMS] += 1;
+            if (a.trace_on > 1) { sh.stat[ST_T_DATA] += tm2 - tm1; sh.stat[ST_T_PUB] += wall_clock64() - tm2; }
           }
-          sh.taskq[at] = (uint16_t)coll;
-          if (sh.slot_tag[coll % DFX_CTX_SLOTS] == coll) sh.slot_tag[coll % DFX_CTX_SLOTS] = 0xffffffffu;
-          if (qlen + 1 > sh.stat[ST_MAXQ]) sh.stat[ST_MAXQ] = qlen + 1;
+          acted = true;
+          if (pend_send) ++sent;
+          if (pend_recv) ++recvd;
+          if (++p == nprim) { p = 0; ++g; }
+          progressed = true;
+          pass_progress = true;
+          // AdaptivelyAdjustSpinThreshold (Alg. 1 line 9)
+          thr *= a.spin_boost;
+          if (thr > a.spin_max) thr = a.spin_max;
+          if (g == rounds) {
+            // ---- CollectiveSuccess -> completion counter -> maybe SendCQE (Sec. 5)
+            if (lane == 0) {
+              DfxDyn d; d.round = 0; d.prim = 0; d.sent = sent; d.recvd = recvd; d.preempted = 0; d.pad = 0;
+              sh.slot[sl].dyn = d;
+              myctx[coll].dyn = d;
+              fence_release_system();   // results in the recv buffer are visible to host and later kernels
+              uint32_t* dc = &a.done_cnt[(size_t)rank * a.max_colls + coll];
+              const uint32_t old = __hip_atomic_fetch_add(dc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
+              if (old + 1 == nchan) {
+                __hip_atomic_store(dc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
+                const u64 v = (1ull << 63) | ((u64)(seq & 0x7fffffffu) << 32) | coll;
+                const uint32_t t = __hip_atomic_fetch_add(&a.cq_ticket[rank], 1u, __ATOMIC_RELAXED, SCOPE_AGENT);
+                uint32_t k = 0;
+                for (;;) {   // optimized CQ (Sec. 5): one CAS of the id into a writable slot
+                  u64 expected = 0;
+                  if (__hip_atomic_compare_exchange_strong(&cqbase[(t + k) % a.cq_slots], &expected, v, __ATOMIC_RELEASE,
+                                                           __ATOMIC_RELAXED, SCOPE_SYSTEM))
+                    break;
+                  ++k;
+                  if ((k % a.cq_slots) == 0) {
+                    if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) break;
+                    __builtin_amdgcn_s_sleep(50);
+                  }
+                }
+                sh.stat[ST_CQE] += 1;
+              }
+            }
+            // the entry leaves the queue; later entries move up, the position stays (Sec. 4.3)
+            --qlen;
+            for (uint32_t base = pos; base < qlen; base += 64) {
+              const uint32_t i = base + lane;
+              uint16_t v = 0;
+              if (i < qlen) v = sh.taskq[i + 1];
+              __builtin_amdgcn_wave_barrier();
+              if (i < qlen) sh.taskq[i] = v;
+              __builtin_amdgcn_wave_barrier();
+            }
+            have = false;
+            sw_pending = false;
+          }
+          continue;
         }
-        ++qlen;
-      }
-      if (tid == 0) {
-        // every workgroup of the rank reads every SQE; the last reader frees the slot (Sec. 5)
-        uint32_t* rc = &a.sq_readers[(size_t)rank * D + (ri & (D - 1))];
-        const uint32_t old = __hip_atomic_fetch_add(rc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
-        if (old + 1 == a.cmax) {
-          __hip_atomic_store(rc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
-          __hip_atomic_store(&e->e.ready, 0u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
+
+        // ================= no collective in hand: control check, fetch, next queue entry =================
+        if (!have) {
+          if (!in_pass) {
+            ++iter;
+            uint32_t s = STOP_NONE, got = 0;
+            if (lane == 0) {
+              if (ld_agent32(&a.dev_ctl[DC_ABORT])) s = STOP_ABORT;
+              else if (ld_agent32(&a.dev_ctl[DC_QUIT])) s = STOP_QUIT;
+              if (!s && (((iter & 31u) == 0) || qlen == 0 || !pass_progress)) {
+                const u64 now = wall_clock64();
+                if (acted) { last_act = now; acted = false; }
+                if (ld_sys32(&a.host_ctl[HC_ABORT])) s = STOP_ABORT;
+                else if (a.watchdog_ticks && qlen > 0 && now - last_act > a.watchdog_ticks) {
+                  ws->dbg[0] = ((u64)sh.taskq[0] << 32) | qlen; ws->dbg[1] = ri; ws->dbg[2] = now - last_act;
+                  raise_error(a, 1u, wg);
+                  s = STOP_ABORT;
+                } else if (a.quit_ticks) {
+                  // Voluntary quit (Sec. 4.4).  Every workgroup has duties towards the others (each
+                  // must read every SQE of its rank before the slot is reusable), so the grid leaves
+                  // as a whole: a workgroup that has been idle or stuck for the quit period casts a
+                  // vote and keeps running; it withdraws the vote when it becomes active again; the
+                  // vote that completes the set raises the quit flag, which everybody obeys.
+                  const bool tired = now - last_act > a.quit_ticks;
+                  if (tired && !voted) {
+                    voted = true;
+                    if (__hip_atomic_fetch_add(&a.dev_ctl[DC_VOTES], 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT) + 1 == a.nwg) {
+                      __hip_atomic_store(&a.dev_ctl[DC_QUIT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
+                      s = STOP_QUIT;
+                    }
+                  } else if (!tired && voted) {
+                    voted = false;
+                    __hip_atomic_fetch_sub(&a.dev_ctl[DC_VOTES], 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
+                  }
+                }
+              }
+              // FIFO ordering (Sec. 4.3): fetch when the queue is empty or a whole pass made no
+              // progress, then keep fetching what is already there (up to fetch_batch); priority
+              // ordering probes the SQ before every pass.
+              const bool want = (qlen == 0) || !pass_progress || a.order_policy == 1 || (burst > 0 && burst < a.fetch_batch);
+              if (!s && want && qlen < a.max_colls) {
+                DfxSqSlot* e = &sqbase[ri & (D - 1)];
+                const uint32_t gen = (uint32_t)(ri >> a.sq_shift) + 1u;
+                if (__hip_atomic_load(&e->e.ready, __ATOMIC_ACQUIRE, SCOPE_SYSTEM) == gen) got = 1;
+              }
+            }
+            s = bcast0(s);
+            got = bcast0(got);
+            if (s) { stop = s; cmd = CMD_STOP; break; }
+
+            // ---- FetchSQE (Alg. 1 line 2)
+            if (got) {
+              DfxSqSlot* e = &sqbase[ri & (D - 1)];
+              // the submitter wrote the send buffer before the SQE: drop what this CU / XCD cached
+              fence_acquire_system();
+              if (lane < 6) ((uint4*)&sh.sqe)[lane] = ((const uint4*)&e->e)[lane];
+              __builtin_amdgcn_wave_barrier();
+              const uint32_t c_id = sh.sqe.coll_id;
+              const uint32_t flags = sh.sqe.flags;
+              const bool is_exit = (flags & DFX_SQE_EXIT) != 0;
+              const bool mine = !is_exit && ch < sh.sqe.nchan && c_id < a.max_colls;
+              if (mine) {
+                // static context of this invocation -> context buffer; restart the sequence, keep
+                // the monotone connector counters of earlier invocations
+                if (lane < 6) ((uint4*)&myctx[c_id].st)[lane] = ((const uint4*)&sh.sqe)[lane];
+                if (lane == 6) { myctx[c_id].dyn.round = 0; myctx[c_id].dyn.prim = 0; myctx[c_id].dyn.preempted = 0; }
+                if (lane == 0) {
+                  // FIFO ordering: append; priority ordering: keep the queue sorted (stable)
+                  uint32_t at = qlen;
+                  if (a.order_policy == 1) {
+                    const int16_t pr = sh.sqe.priority;
+                    while (at > 0 && myctx[sh.taskq[at - 1]].st.priority < pr) { sh.taskq[at] = sh.taskq[at - 1]; --at; }
+                  }
+                  sh.taskq[at] = (uint16_t)c_id;
+                  if (sh.slot_tag[c_id % DFX_CTX_SLOTS] == c_id) sh.slot_tag[c_id % DFX_CTX_SLOTS] = 0xffffffffu;
+                  if (qlen + 1 > sh.stat[ST_MAXQ]) sh.stat[ST_MAXQ] = qlen + 1;
+                }
+                ++qlen;
+              }
+              if (lane == 0) {
+                // every workgroup of the rank reads every SQE; the last reader frees the slot (Sec. 5)
+                uint32_t* rc = &a.sq_readers[(size_t)rank * D + (ri & (D - 1))];
+                const uint32_t old = __hip_atomic_fetch_add(rc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
+                if (old + 1 == a.cmax) {
+                  __hip_atomic_store(rc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
+                  __hip_atomic_store(&e->e.ready, 0u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
+                }
+                sh.stat[ST_SQE] += 1;
+              }
+              __builtin_amdgcn_wave_barrier();
+              acted = true;
+              sw_pending = false;
+              ++ri;
+              if (is_exit) { stop = STOP_EXIT; cmd = CMD_STOP; break; }
+              ++burst;
+              idle = 0;
+              continue;               // probe the SQ again before walking the queue
+            }
+            burst = 0;
+            if (qlen == 0) {
+              // idle: back off the SQ probe (it may cross PCIe)
+              ++idle;
+              if (idle < 16) __builtin_amdgcn_s_sleep(8);
+              else if (idle < 64) __builtin_amdgcn_s_sleep(32);
+              else __builtin_amdgcn_s_sleep(127);
+              continue;
+            }
+            idle = 0;
+            // ---- start one pass over the task queue (Alg. 1 lines 4-19)
+            in_pass = true;
+            pass_progress = false;
+            pos = 0;
+            if (lane == 0) sh.stat[ST_PASSES] += 1;
+          }
+          if (pos >= qlen) { in_pass = false; continue; }
+
+          // ---- LoadCollectiveContext: HBM context buffer -> LDS slot, 8 lanes x 16 bytes
+          coll = sh.taskq[pos];
+          sl = coll % DFX_CTX_SLOTS;
+          if (sw_pending && a.trace_on > 1) sw_lb = wall_clock64();
+          if (sh.slot_tag[sl] != coll) {
+            if (lane < 8) ((uint4*)&sh.slot[sl])[lane] = ((const uint4*)&myctx[coll])[lane];
+            if (lane == 0) { sh.slot_tag[sl] = coll; sh.stat[ST_LOAD] += 1; }
+            __builtin_amdgcn_wave_barrier();
+          } else if (lane == 0) sh.stat[ST_HIT] += 1;
+          if (sw_pending && a.trace_on > 1) sw_le = wall_clock64();
+          {
+            const DfxCtxEntry& C = sh.slot[sl];
+            kind = C.st.kind; dtype = C.st.dtype; root = C.st.root;
+            eb = (dtype == DT_F32 || dtype == DT_I32) ? 4u : 2u;
+            nprim = C.st.nprim; rounds = C.st.rounds; K = C.st.nslots; nchan = C.st.nchan;
+            slot_bytes = C.st.slot_bytes; slice_elems = C.st.slice_elems; seq = C.st.seq;
+            count = C.st.count; block_elems = C.st.block_elems; part_elems = C.st.part_elems;
+            sendbuf = (const char*)C.st.sendbuf;
+            recvbuf = (char*)C.st.recvbuf;
+            g = C.dyn.round; p = C.dyn.prim; sent = C.dyn.sent; recvd = C.dyn.recvd;
+            preempted_before = C.dyn.preempted;
+            // connector geometry: flags first, then slots
+            uint8_t* conn = a.pool + C.st.conn_off;
+            const uint32_t e_out = rank, e_in = (rank + (uint32_t)R - 1) % (uint32_t)R;
+            tail_out = (u64*)(conn + ((size_t)e_out * nchan + ch) * DFX_FLAG_STRIDE);
+            head_out = tail_out + 8;
+            tail_in = (u64*)(conn + ((size_t)e_in * nchan + ch) * DFX_FLAG_STRIDE);
+            head_in = tail_in + 8;
+            uint8_t* slots = conn + (size_t)R * nchan * DFX_FLAG_STRIDE;
+            fifo_out = slots + ((size_t)e_out * nchan + ch) * K * slot_bytes;
+            fifo_in = slots + ((size_t)e_in * nchan + ch) * K * slot_bytes;
+          }
+          // SetInitialSpinThreshold (Alg. 1 line 3): largest at the front, halving per position
+          thr = a.spin_init >> (pos < 31 ? pos : 31);
+          if (thr < a.spin_min) thr = a.spin_min;
+          progressed = false;
+          have = true;
         }
-        sh.stat[ST_SQE] += 1;
-        acted = true;
-        sw_pending = false;
-      }
-      ++ri;
-      __syncthreads();
-      if (is_exit) { stop = STOP_EXIT; break; }
-      ++burst;
-      idle = 0;
-      continue;               // probe the SQ again before walking the queue
-    } else if (qlen == 0) {
-      burst = 0;
-      // idle: back off the SQ probe (it may cross PCIe), then meet before the next broadcast
-      ++idle;
-      if (idle < 16) __builtin_amdgcn_s_sleep(8);
-      else if (idle < 64) __builtin_amdgcn_s_sleep(32);
-      else __builtin_amdgcn_s_sleep(127);
-      __syncthreads();
-      continue;
-    }
-    idle = 0;
-    burst = 0;
 
-    // ================= one pass over the task queue (Alg. 1 lines 4-19) =================
-    pass_progress = false;
-    if (tid == 0) sh.stat[ST_PASSES] += 1;
-    uint32_t pos = 0;
-    while (pos < qlen) {
-      const uint32_t coll = sh.taskq[pos];
-      const uint32_t sl = coll % DFX_CTX_SLOTS;
-      // ---- LoadCollectiveContext: HBM context buffer -> LDS slot, 8 lanes x 16 bytes
-      u64 t_lb = 0, t_le = 0;
-      if (tid == 0 && sw_pending) t_lb = wall_clock64();
-      if (sh.slot_tag[sl] != coll) {
-        __syncthreads();   // everyone has read the old tag before it changes
-        if (tid < 8) ((uint4*)&sh.slot[sl])[tid] = ((const uint4*)&myctx[coll])[tid];
-        if (tid == 0) { sh.slot_tag[sl] = coll; sh.stat[ST_LOAD] += 1; }
-        __syncthreads();
-      } else if (tid == 0) sh.stat[ST_HIT] += 1;
-      if (tid == 0 && sw_pending) t_le = wall_clock64();
-
-      const DfxCtxEntry& C = sh.slot[sl];
-      const int kind = C.st.kind, dtype = C.st.dtype, root = C.st.root;
-      const uint32_t eb = (dtype == DT_F32 || dtype == DT_I32) ? 4u : 2u;
-      const uint32_t nprim = C.st.nprim, rounds = C.st.rounds, K = C.st.nslots, nchan = C.st.nchan;
-      const uint32_t slot_bytes = C.st.slot_bytes, slice_elems = C.st.slice_elems;
-      const u64 count = C.st.count, block_elems = C.st.block_elems, part_elems = C.st.part_elems;
-      const char* sendbuf = (const char*)C.st.sendbuf;
-      char* recvbuf = (char*)C.st.recvbuf;
-      uint8_t* conn = a.pool + C.st.conn_off;
-      uint32_t g = C.dyn.round, p = C.dyn.prim;
-      u64 sent = C.dyn.sent, recvd = C.dyn.recvd;
-      const uint32_t preempted_before = C.dyn.preempted;
-
-      // connector geometry: flags first, then slots
-      const uint32_t e_out = rank, e_in = (rank + (uint32_t)R - 1) % (uint32_t)R;
-      u64* tail_out = (u64*)(conn + ((size_t)e_out * nchan + ch) * DFX_FLAG_STRIDE);
-      u64* head_out = tail_out + 8;
-      u64* tail_in = (u64*)(conn + ((size_t)e_in * nchan + ch) * DFX_FLAG_STRIDE);
-      u64* head_in = tail_in + 8;
-      uint8_t* slots = conn + (size_t)R * nchan * DFX_FLAG_STRIDE;
-      uint8_t* fifo_out = slots + ((size_t)e_out * nchan + ch) * K * slot_bytes;
-      uint8_t* fifo_in = slots + ((size_t)e_in * nchan + ch) * K * slot_bytes;
-
-      // SetInitialSpinThreshold (Alg. 1 line 3): largest at the front, halving per position
-      u64 thr = a.spin_init >> (pos < 31 ? pos : 31);
-      if (thr < a.spin_min) thr = a.spin_min;
-
-      bool progressed = false, completed = false;
-      uint32_t res = W_OK;
-      for (;;) {
+        // ================= next primitive of the collective in hand =================
         const Prim q = make_prim(kind, R, (int)rank, root, p);
-        // ---- slice geometry (elements relative to the block, clipped to the block's true length)
+        // slice geometry (elements relative to the block, clipped to the block's true length)
         u64 blen = count;
         if (kind == KIND_AR && R > 1) {
           const u64 start = (u64)q.cidx * block_elems;
@@ -557,171 +667,123 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         else if (kind == KIND_RS) soff += (u64)q.cidx * count;
         else if (kind == KIND_AG) doff += (u64)q.cidx * count;
 
-        u64 tm0 = 0, tm1 = 0, tm2 = 0;
-        if (tid == 0 && a.trace_on) tm0 = wall_clock64();
-        // ---- wait phase: wave 0 polls, lane 0 the recv side, lane 1 the send side
-        if (tid < 64) {
-          uint32_t r = W_OK;
-          if (tid == 0 && sw_pending) {   // the first poll of the next collective ends the context switch
-            const u64 t1 = wall_clock64();
-            if (trace) {
-              u64 tot = t1 - sw_t0, sv = sw_ts - sw_t0, ldt = t_le - t_lb;
-              if (tot > 0xffffffu) tot = 0xffffffu;
-              if (sv > 0xfffffu) sv = 0xfffffu;
-              if (ldt > 0xfffffu) ldt = 0xfffffu;
-              trace[trace_n % DFX_TRACE_N] = tot | (sv << 24) | (ldt << 44);
-              ++trace_n;
-            }
-            sw_pending = false;
+        u64 tm0 = 0;
+        if (a.trace_on > 1) tm0 = wall_clock64();
+        if (sw_pending) {   // the first poll of the next collective ends the context switch
+          const u64 t1 = wall_clock64();
+          if (trace && lane == 0) {
+            u64 tot = t1 - sw_t0, sv = sw_ts - sw_t0, ldt = sw_le - sw_lb;
+            if (a.trace_on < 2) { sv = 0; ldt = 0; }
+            if (tot > 0xffffffu) tot = 0xffffffu;
+            if (sv > 0xfffffu) sv = 0xfffffu;
+            if (ldt > 0xfffffu) ldt = 0xfffffu;
+            trace[trace_n % DFX_TRACE_N] = tot | (sv << 24) | (ldt << 44);
           }
-          if (q.recv || q.send) {
-            u64 n = 0;
-            for (;;) {
-              bool ok = true;
-              if (tid == 0 && q.recv) ok = ld_agent64(tail_in) > recvd;
-              if (tid == 1 && q.send) ok = (sent - ld_agent64(head_out)) < (u64)K;
-              ++n;
-              if (__ballot(!ok) == 0) break;
-              if (a.preempt && n >= thr) { r = W_TIMEOUT; break; }
-              if ((n & 255u) == 0) {
-                uint32_t s = 0;
-                if (tid == 0) {
-                  if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) s = 1;
-                  else if (a.watchdog_ticks) {
-                    const u64 now = wall_clock64();
-                    if (acted) { last_act = now; acted = false; }
-                    if (now - last_act > a.watchdog_ticks) {
-                      ws->dbg[0] = ((u64)coll << 32) | qlen; ws->dbg[1] = ((u64)g << 32) | p; ws->dbg[2] = sent; ws->dbg[3] = recvd;
-                      ws->dbg[4] = ld_agent64(tail_in); ws->dbg[5] = ld_agent64(head_out); ws->dbg[6] = ri; ws->dbg[7] = now - last_act;
-                      raise_error(a, 2u, wg);
-                      s = 1;
-                    }
-                  }
-                }
-                if (__ballot(s != 0) != 0) { r = W_STOP; break; }
-              }
-              __builtin_amdgcn_s_sleep(1);
-            }
-            if (tid == 0) sh.stat[ST_POLLS] += n;
-          }
-          if (tid == 0) sh.wres = r;
-        }
-        __syncthreads();
-        res = sh.wres;
-        if (res != W_OK) break;
-        // every wave invalidates before its own loads of the slot (the poll was wave 0's)
-        // fenced mode: every wave invalidates before its own loads of the slot (the poll was wave 0's)
-        if (q.recv && !coh) fence_acquire_agent();
-        if (tid == 0 && a.trace_on) tm1 = wall_clock64();
-        // ---- data phase: one slice
-        {
-          const void* fin = q.recv ? (const void*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
-          void* fout = q.send ? (void*)(fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
-          const char* sb = q.from_send ? sendbuf + soff * eb : nullptr;
-          char* rb = q.to_recv ? recvbuf + doff * eb : nullptr;
-          if (bytes) {
-            if (coh) run_prim<AUX_DEVICE>(dtype, fin, sb, rb, fout, bytes);
-            else run_prim<AUX_CACHED>(dtype, fin, sb, rb, fout, bytes);
-          }
-        }
-        if (tid == 0 && a.trace_on) tm2 = wall_clock64();
-        drain_and_barrier();
-        if (tid == 0) {
-          if (!coh) fence_release_agent();
-          if (q.send) st_agent64(tail_out, sent + 1);
-          if (q.recv) st_agent64(head_in, recvd + 1);
-          sh.stat[ST_PRIMS] += 1;
-          acted = true;
-          if (a.trace_on) {
-            const u64 tm3 = wall_clock64();
-            sh.stat[ST_T_WAIT] += tm1 - tm0; sh.stat[ST_T_DATA] += tm2 - tm1; sh.stat[ST_T_PUB] += tm3 - tm2;
-          }
-        }
-        if (q.send) ++sent;
-        if (q.recv) ++recvd;
-        if (++p == nprim) { p = 0; ++g; }
-        progressed = true;
-        // AdaptivelyAdjustSpinThreshold (Alg. 1 line 9)
-        thr *= a.spin_boost;
-        if (thr > a.spin_max) thr = a.spin_max;
-        if (g == rounds) { completed = true; break; }
-      }
-
-      if (progressed) pass_progress = true;
-
-      if (completed) {
-        // ---- CollectiveSuccess -> completion counter -> maybe SendCQE (Sec. 5)
-        if (tid == 0) {
-          DfxDyn d; d.round = 0; d.prim = 0; d.sent = sent; d.recvd = recvd; d.preempted = 0; d.pad = 0;
-          sh.slot[sl].dyn = d;
-          myctx[coll].dyn = d;
-          fence_release_system();   // results in the recv buffer are visible to host and later kernels
-          uint32_t* dc = &a.done_cnt[(size_t)rank * a.max_colls + coll];
-          const uint32_t old = __hip_atomic_fetch_add(dc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
-          if (old + 1 == nchan) {
-            __hip_atomic_store(dc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
-            const u64 v = (1ull << 63) | ((u64)(C.st.seq & 0x7fffffffu) << 32) | coll;
-            const uint32_t t = __hip_atomic_fetch_add(&a.cq_ticket[rank], 1u, __ATOMIC_RELAXED, SCOPE_AGENT);
-            uint32_t k = 0;
-            for (;;) {   // optimized CQ (Sec. 5): one CAS of the id into a writable slot
-              u64 expected = 0;
-              if (__hip_atomic_compare_exchange_strong(&cqbase[(t + k) % a.cq_slots], &expected, v, __ATOMIC_RELEASE,
-                                                       __ATOMIC_RELAXED, SCOPE_SYSTEM))
-                break;
-              ++k;
-              if ((k % a.cq_slots) == 0) {
-                if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) break;
-                __builtin_amdgcn_s_sleep(50);
-              }
-            }
-            sh.stat[ST_CQE] += 1;
-          }
+          ++trace_n;
           sw_pending = false;
         }
-        // the entry leaves the queue; later entries move up, the position stays (Sec. 4.3)
-        --qlen;
-        __syncthreads();
-        for (uint32_t base = pos; base < qlen; base += NT) {
-          const uint32_t i = base + tid;
-          uint16_t v = 0;
-          if (i < qlen) v = sh.taskq[i + 1];
-          __syncthreads();
-          if (i < qlen) sh.taskq[i] = v;
-          __syncthreads();
+
+        // ---- wait phase: lane 0 polls the recv side, lane 1 the send side (Sec. 4.2 (3))
+        uint32_t res = W_OK;
+        if (q.recv || q.send) {
+          u64 n = 0;
+          for (;;) {
+            bool ok = true;
+            if (lane == 0 && q.recv) ok = ld_agent64(tail_in) > recvd;
+            if (lane == 1 && q.send) ok = (sent - ld_agent64(head_out)) < (u64)K;
+            ++n;
+            if (__ballot(!ok) == 0) break;
+            if (a.preempt && n >= thr) { res = W_TIMEOUT; break; }
+            if ((n & 255u) == 0) {
+              uint32_t s = 0;
+              if (lane == 0) {
+                if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) s = 1;
+                else if (a.watchdog_ticks) {
+                  const u64 now = wall_clock64();
+                  if (acted) { last_act = now; acted = false; }
+                  if (now - last_act > a.watchdog_ticks) {
+                    ws->dbg[0] = ((u64)coll << 32) | qlen; ws->dbg[1] = ((u64)g << 32) | p; ws->dbg[2] = sent; ws->dbg[3] = recvd;
+                    ws->dbg[4] = ld_agent64(tail_in); ws->dbg[5] = ld_agent64(head_out); ws->dbg[6] = ri; ws->dbg[7] = now - last_act;
+                    raise_error(a, 2u, wg);
+                    s = 1;
+                  }
+                }
+              }
+              if (bcast0(s)) { res = W_STOP; break; }
+            }
+            __builtin_amdgcn_s_sleep(1);
+          }
+          if (lane == 0) sh.stat[ST_POLLS] += n;
         }
-      } else {
-        // ---- PreemptCollective + SaveCollectiveContext (lazy: only if it progressed)
-        if (tid == 0) {
+
+        if (res == W_OK) {
+          pend_send = q.send;
+          pend_recv = q.recv;
+          pending_pub = true;
+          if (a.trace_on > 1) { tm1 = wall_clock64(); if (lane == 0) sh.stat[ST_T_WAIT] += tm1 - tm0; tm2 = tm1; }
+          if (bytes) {
+            if (lane == 0) {
+              Job j;
+              j.fin = q.recv ? (const void*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
+              j.fout = q.send ? (void*)(fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
+              j.sb = q.from_send ? sendbuf + soff * eb : nullptr;
+              j.rb = q.to_recv ? recvbuf + doff * eb : nullptr;
+              j.bytes = bytes;
+              j.dtype = dtype;
+              sh.job = j;
+            }
+            cmd = CMD_MOVE;
+          }
+          // an empty slice is only a handshake: it is published at the top of the loop
+        } else {
+          // ---- PreemptCollective + SaveCollectiveContext (lazy: only if it progressed)
           const bool tr = a.trace_on && res == W_TIMEOUT && pos + 1 < qlen;
           if (tr) sw_t0 = wall_clock64();
-          if (res == W_TIMEOUT) sh.stat[ST_PREEMPT] += 1;
-          if (progressed) {
-            DfxDyn d; d.round = g; d.prim = p; d.sent = sent; d.recvd = recvd;
-            d.preempted = preempted_before + 1; d.pad = 0;
-            sh.slot[sl].dyn = d;
-            myctx[coll].dyn = d;
-            sh.stat[ST_SAVE] += 1;
-          } else if (res == W_TIMEOUT) sh.stat[ST_LAZY] += 1;
-          if (tr) { sw_ts = wall_clock64(); sw_pending = true; }
+          if (lane == 0) {
+            if (res == W_TIMEOUT) sh.stat[ST_PREEMPT] += 1;
+            if (progressed) {
+              DfxDyn d; d.round = g; d.prim = p; d.sent = sent; d.recvd = recvd;
+              d.preempted = preempted_before + 1; d.pad = 0;
+              sh.slot[sl].dyn = d;
+              myctx[coll].dyn = d;
+              sh.stat[ST_SAVE] += 1;
+            } else if (res == W_TIMEOUT) sh.stat[ST_LAZY] += 1;
+          }
+          if (tr) { if (a.trace_on > 1) sw_ts = wall_clock64(); sw_pending = true; }
+          have = false;
+          if (res == W_STOP) { stop = STOP_ABORT; cmd = CMD_STOP; break; }
+          ++pos;
         }
-        __syncthreads();
-        if (res == W_STOP) { stop = STOP_ABORT; break; }
-        ++pos;
       }
+      if (lane == 0) sh.cmd = cmd;
     }
-    if (stop) break;
+    __syncthreads();
+    if (sh.cmd == CMD_STOP) break;
+
+    // ================= data phase: all waves move the slice the scheduler posted =================
+    {
+      const Job j = sh.job;
+      // fenced mode: every wave invalidates before its own loads of the slot (the poll was wave 0's)
+      if (!coh && j.fin) fence_acquire_agent();
+      if (coh) run_prim<AUX_DEVICE>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes);
+      else run_prim<AUX_CACHED>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes);
+    }
+    if (sched && a.trace_on > 1) tm2 = wall_clock64();
+    drain_and_barrier();
   }
 
   // ================= leave: persist what the next launch needs =================
-  __syncthreads();
-  for (uint32_t i = tid; i < qlen; i += NT) qstore[i] = sh.taskq[i];
+  // (the scheduler wave owns the truth about ri / qlen / trace_n; hand it over through LDS)
   if (tid == 0) {
     if (stop == STOP_QUIT) sh.stat[ST_QUITS] += 1;
     ws->read_index = ri;
     ws->qlen = qlen;
     ws->trace_n = trace_n;
+    sh.slot_tag[0] = qlen;    // reuse as a broadcast word: nobody needs the tags any more
   }
   __syncthreads();
+  const uint32_t qn = sh.slot_tag[0];
+  for (uint32_t i = tid; i < qn; i += NT) qstore[i] = sh.taskq[i];
   if (tid < DFX_NSTAT) ws->stat[tid] = sh.stat[tid];
 }
 

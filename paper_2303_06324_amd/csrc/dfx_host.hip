@@ -159,6 +159,9 @@ int launch_locked(dfx_ctx* c) {
   a.fifo_coherent = c->fifo_coherent;
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
+  a.nwg = c->nwg;
+  // quit votes and the quit flag belong to one launch
+  HIPCHK(c, hipMemsetAsync(c->dev_ctl + DC_QUIT, 0, 2 * sizeof(uint32_t), c->stream));
   HIPCHK(c, hipEventRecord(c->ev_start, c->stream));
   HIPCHK(c, dfx_daemon_launch(c->nwg, c->stream, a));
   HIPCHK(c, hipEventRecord(c->ev_stop, c->stream));
@@ -451,6 +454,10 @@ int dfx_submit(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* rec
     if (rc == DFX_OK) {
       rs->sub[coll_id]++;
       rs->n_sub.fetch_add(1, std::memory_order_relaxed);
+    } else {
+      // There is no poller thread: a caller that only retries submissions must still empty the
+      // CQ, or a workgroup blocked on a full CQ stops reading SQEs and the SQ never drains.
+      drain_cq(c, rank);
     }
   }
   // start the daemon on SQE insertion; also when the SQ is full (a quit daemon frees no slots)

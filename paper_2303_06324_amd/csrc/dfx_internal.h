@@ -78,7 +78,7 @@ enum { ST_PREEMPT = 0, ST_LOAD, ST_HIT, ST_SAVE, ST_LAZY, ST_POLLS, ST_PRIMS, ST
        ST_T_WAIT, ST_T_DATA, ST_T_PUB, ST_T_SPARE };   // wall-clock ticks, only with trace on
 
 // dev_ctl words (device memory)
-enum { DC_ABORT = 0, DC_ERR = 1, DC_ERR_WG = 2, DC_N = 16 };
+enum { DC_ABORT = 0, DC_ERR = 1, DC_ERR_WG = 2, DC_QUIT = 3, DC_VOTES = 4, DC_N = 16 };
 // host_ctl words (host-visible queue memory)
 enum { HC_ABORT = 0, HC_N = 16 };
 
@@ -95,6 +95,7 @@ struct DfxDaemonArgs {
   DfxWgState* wgstate;      // [nwg]           device
   uint16_t* taskq_store;    // [nwg][max_colls] device
   uint64_t* trace;          // [nwg][DFX_TRACE_N] device (or null)
+  uint32_t nwg;
   uint32_t R, cmax, max_colls, sq_depth, sq_shift, cq_slots;
   uint32_t spin_init, spin_min, spin_max, spin_boost, preempt;
   uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent;

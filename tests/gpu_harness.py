@@ -150,6 +150,13 @@ def run_workload(w: wi.Workload, cfg=None, mode: str = "roundrobin", timeout_s: 
         if rc != dfx.OK:
             raise dfx.DfxError(rc, f"dfx_wait_all (stop={stop_rc}, stats0={stats[0]})")
     except Exception:
+        try:                      # leave a trace of where every vrank stood
+            ctx.stop()
+            for r in range(w.R):
+                st = ctx.stats(r)
+                print(f"[harness] rank {r}: " + " ".join(f"{k}={v}" for k, v in st.items() if isinstance(v, int) and v))
+        except Exception as e2:   # noqa: BLE001
+            print("[harness] no stats:", e2)
         ctx.finalize()
         raise
     if keep_ctx:
