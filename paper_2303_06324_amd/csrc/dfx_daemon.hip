@@ -303,50 +303,43 @@ struct Job {                         // what the scheduler wave hands to all wav
 };
 
 struct Shared {
+  DfxDaemonArgs args;
   DfxCtxEntry slot[DFX_CTX_SLOTS];   // active context slots (Sec. 5, direct-mapped)
   uint32_t slot_tag[DFX_CTX_SLOTS];
   DfxStatic sqe;                     // SQE being fetched
   Job job;
   uint32_t cmd;                      // scheduler wave -> workgroup: CMD_MOVE or CMD_STOP
-  u64 stat[DFX_NSTAT];
+  uint32_t qlen_out;                 // queue length handed to all waves when leaving
+  u64 stat[DFX_NSTAT];               // counters (LDS atomics without return: one instruction, no wait)
   uint16_t taskq[DFX_MAX_COLLS];     // task queue (Sec. 4.2 (1))
 };
 
 enum { CMD_NONE = 0, CMD_MOVE = 1, CMD_STOP = 2 };
 
-// primitive descriptor for (kind, position p in the sequence)
+// primitive descriptor for (kind, position p in the sequence); the ring-chunk index travels in
+// the dynamic context and is stepped by next_cidx, so nothing here divides
 struct Prim {
   bool recv, send;         // uses recv / send connector
   bool from_send, to_recv; // touches the send buffer / recv buffer
-  uint32_t cidx;           // block (ring chunk) index
 };
 
-__device__ __forceinline__ uint32_t modR(int x, int R) { int m = x % R; return (uint32_t)(m < 0 ? m + R : m); }
-
-__device__ __forceinline__ Prim make_prim(int kind, int R, int r, int root, uint32_t p) {
+__device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos, uint32_t p) {
   Prim q;
-  q.cidx = 0;
-  if (R == 1) {  // copy
-    q.recv = q.send = false; q.from_send = q.to_recv = true;
-    return q;
-  }
+  if (R == 1) { q.recv = q.send = false; q.from_send = q.to_recv = true; return q; }   // copy
   if (kind == KIND_AR || kind == KIND_RS) {
-    q.cidx = modR(r - 1 - (int)p, R);
-    const uint32_t last_reduce = (uint32_t)R - 1;
-    if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = false; }
-    else if (p < last_reduce) { q.recv = true; q.send = true; q.from_send = true; q.to_recv = false; }
-    else if (p == last_reduce) { q.recv = true; q.send = (kind == KIND_AR); q.from_send = true; q.to_recv = true; }
-    else if (p < 2u * R - 2) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
-    else { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
+    const uint32_t last_reduce = R - 1;
+    if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = false; }                         // send
+    else if (p < last_reduce) { q.recv = true; q.send = true; q.from_send = true; q.to_recv = false; }           // recv-reduce-send
+    else if (p == last_reduce) { q.recv = true; q.send = (kind == KIND_AR); q.from_send = true; q.to_recv = true; }  // recv-reduce-copy(-send)
+    else if (p < 2u * R - 2) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }            // recv-copy-send
+    else { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }                               // recv-copy
   } else if (kind == KIND_AG) {
-    q.cidx = modR(r - (int)p, R);
-    if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }
-    else if (p < (uint32_t)R - 1) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
+    if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }                          // copy-send
+    else if (p < R - 1) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
     else { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
   } else {  // broadcast chain root -> root+1 -> ... -> root-1
-    const uint32_t pos = modR(r - root, R);
-    if (pos == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }
-    else if (pos == (uint32_t)R - 1) { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
+    if (bc_pos == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }
+    else if (bc_pos == 2) { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
     else { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
   }
   return q;
@@ -357,6 +350,10 @@ __device__ __forceinline__ void raise_error(const DfxDaemonArgs& a, uint32_t cod
   if (__hip_atomic_compare_exchange_strong(&a.dev_ctl[DC_ERR], &expected, code, __ATOMIC_RELAXED, __ATOMIC_RELAXED, SCOPE_AGENT))
     __hip_atomic_store(&a.dev_ctl[DC_ERR_WG], wg, __ATOMIC_RELAXED, SCOPE_AGENT);
   __hip_atomic_store(&a.dev_ctl[DC_ABORT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void bump(u64* stat, int i, u64 v) {
+  (void)__hip_atomic_fetch_add(&stat[i], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 __device__ __forceinline__ uint32_t bcast0(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -371,8 +368,14 @@ __device__ __forceinline__ uint32_t bcast0(uint32_t v) { return __builtin_amdgcn
 // at a barrier; all waves move the slice, drain their stores and meet again; the scheduler
 // then publishes the connector counters and goes on.  A context switch therefore costs no
 // barrier at all, a primitive costs two.
-extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(DfxDaemonArgs a) {
+extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(DfxDaemonArgs kargs) {
   __shared__ Shared sh;
+  // The arguments are read from an LDS copy: kept in scalar registers for the whole kernel they
+  // overflow the scalar register file, and the spill reloads at every loop head cost more than
+  // the LDS reads.
+  if (threadIdx.x == 0) sh.args = kargs;
+  __syncthreads();
+  const DfxDaemonArgs& a = sh.args;
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u;
   const bool sched = tid < 64;       // the scheduler wave
@@ -402,6 +405,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   __syncthreads();
 
   // ---- scheduler state (registers of wave 0; the other waves never look at it)
+  // start values of the ring-chunk index of a fresh sequence (see DfxDyn.cidx)
+  const uint32_t cidx0_reduce = (rank + a.R - 1) % a.R;   // all-reduce / reduce-scatter: chunk rank-1
   u64 last_act = wall_clock64();
   bool acted = true, voted = false;
   uint32_t iter = 0, idle = 0, burst = 0;
@@ -415,7 +420,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   bool have = false;
   uint32_t coll = 0, sl = 0, nprim = 0, rounds = 0, K = 0, nchan = 0, slot_bytes = 0, slice_elems = 0, eb = 4;
   uint32_t g = 0, p = 0, preempted_before = 0, seq = 0;
-  int kind = 0, dtype = 0, root = 0;
+  int kind = 0, dtype = 0;
+  uint32_t bc_pos = 0, cidx = 0;
   u64 count = 0, block_elems = 0, part_elems = 0, sent = 0, recvd = 0, thr = 0;
   const char* sendbuf = nullptr;
   char* recvbuf = nullptr;
@@ -437,13 +443,19 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             if (!coh) fence_release_agent();
             if (pend_send) st_agent64(tail_out, sent + 1);
             if (pend_recv) st_agent64(head_in, recvd + 1);
-            sh.stat[ST_PRIMS] += 1;
-            if (a.trace_on > 1) { sh.stat[ST_T_DATA] += tm2 - tm1; sh.stat[ST_T_PUB] += wall_clock64() - tm2; }
+            bump(sh.stat, ST_PRIMS, 1);
+            if (a.trace_on > 1) { bump(sh.stat, ST_T_DATA, tm2 - tm1); bump(sh.stat, ST_T_PUB, wall_clock64() - tm2); }
           }
           acted = true;
           if (pend_send) ++sent;
           if (pend_recv) ++recvd;
-          if (++p == nprim) { p = 0; ++g; }
+          // next primitive: the chunk index steps down the ring; a new round starts over
+          cidx = (cidx == 0) ? a.R - 1 : cidx - 1;
+          if (++p == nprim) {
+            p = 0; ++g;
+            cidx = (kind == KIND_AG) ? rank : ((kind == KIND_BC || a.R == 1) ? 0u : cidx0_reduce);
+          }
+          if (kind == KIND_BC) cidx = 0;
           progressed = true;
           pass_progress = true;
           // AdaptivelyAdjustSpinThreshold (Alg. 1 line 9)
@@ -452,7 +464,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           if (g == rounds) {
             // ---- CollectiveSuccess -> completion counter -> maybe SendCQE (Sec. 5)
             if (lane == 0) {
-              DfxDyn d; d.round = 0; d.prim = 0; d.sent = sent; d.recvd = recvd; d.preempted = 0; d.pad = 0;
+              DfxDyn d; d.round = 0; d.prim = 0; d.sent = sent; d.recvd = recvd; d.preempted = 0; d.cidx = 0;
               sh.slot[sl].dyn = d;
               myctx[coll].dyn = d;
               fence_release_system();   // results in the recv buffer are visible to host and later kernels
@@ -474,7 +486,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                     __builtin_amdgcn_s_sleep(50);
                   }
                 }
-                sh.stat[ST_CQE] += 1;
+                bump(sh.stat, ST_CQE, 1);
               }
             }
             // the entry leaves the queue; later entries move up, the position stays (Sec. 4.3)
@@ -554,22 +566,42 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
               const bool is_exit = (flags & DFX_SQE_EXIT) != 0;
               const bool mine = !is_exit && ch < sh.sqe.nchan && c_id < a.max_colls;
               if (mine) {
-                // static context of this invocation -> context buffer; restart the sequence, keep
-                // the monotone connector counters of earlier invocations
-                if (lane < 6) ((uint4*)&myctx[c_id].st)[lane] = ((const uint4*)&sh.sqe)[lane];
-                if (lane == 6) { myctx[c_id].dyn.round = 0; myctx[c_id].dyn.prim = 0; myctx[c_id].dyn.preempted = 0; }
+                // cook the static context of this invocation into the context buffer (addresses
+                // resolved once, here); restart the sequence, keep the monotone connector counters
                 if (lane == 0) {
+                  const DfxStatic& q = sh.sqe;
+                  DfxCooked k;
+                  k.sendbuf = q.sendbuf; k.recvbuf = q.recvbuf; k.count = q.count;
+                  k.block_elems = q.block_elems; k.part_elems = q.part_elems;
+                  uint8_t* conn = a.pool + q.conn_off;   // flags first, then slots
+                  const uint32_t e_out = rank, e_in = (rank + a.R - 1) % a.R;
+                  const size_t fo = (size_t)e_out * q.nchan + ch, fi = (size_t)e_in * q.nchan + ch;
+                  uint8_t* slots = conn + (size_t)a.R * q.nchan * DFX_FLAG_STRIDE;
+                  k.flags_out = (uint64_t)(conn + fo * DFX_FLAG_STRIDE);
+                  k.flags_in = (uint64_t)(conn + fi * DFX_FLAG_STRIDE);
+                  k.fifo_out = (uint64_t)(slots + fo * q.nslots * q.slot_bytes);
+                  k.fifo_in = (uint64_t)(slots + fi * q.nslots * q.slot_bytes);
+                  k.slice_elems = q.slice_elems; k.rounds = q.rounds; k.seq = q.seq;
+                  k.nprim = (uint16_t)q.nprim; k.nchan = q.nchan;
+                  k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = q.dtype;
+                  const uint32_t bpos = (rank + a.R - q.root) % a.R;
+                  k.bc_pos = bpos == 0 ? 0 : (bpos == a.R - 1 ? 2 : 1);
+                  k.priority = q.priority; k.pad = 0;
+                  myctx[c_id].st = k;
+                  DfxDyn* dy = &myctx[c_id].dyn;
+                  dy->round = 0; dy->prim = 0; dy->preempted = 0;
+                  dy->cidx = (q.kind == KIND_AG) ? rank : ((q.kind == KIND_BC || a.R == 1) ? 0u : cidx0_reduce);
                   // FIFO ordering: append; priority ordering: keep the queue sorted (stable)
                   uint32_t at = qlen;
                   if (a.order_policy == 1) {
-                    const int16_t pr = sh.sqe.priority;
+                    const int16_t pr = q.priority;
                     while (at > 0 && myctx[sh.taskq[at - 1]].st.priority < pr) { sh.taskq[at] = sh.taskq[at - 1]; --at; }
                   }
                   sh.taskq[at] = (uint16_t)c_id;
                   if (sh.slot_tag[c_id % DFX_CTX_SLOTS] == c_id) sh.slot_tag[c_id % DFX_CTX_SLOTS] = 0xffffffffu;
-                  if (qlen + 1 > sh.stat[ST_MAXQ]) sh.stat[ST_MAXQ] = qlen + 1;
                 }
                 ++qlen;
+                if (lane == 0) __hip_atomic_fetch_max(&sh.stat[ST_MAXQ], (u64)qlen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
               }
               if (lane == 0) {
                 // every workgroup of the rank reads every SQE; the last reader frees the slot (Sec. 5)
@@ -579,7 +611,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                   __hip_atomic_store(rc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
                   __hip_atomic_store(&e->e.ready, 0u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
                 }
-                sh.stat[ST_SQE] += 1;
+                bump(sh.stat, ST_SQE, 1);
               }
               __builtin_amdgcn_wave_barrier();
               acted = true;
@@ -604,7 +636,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             in_pass = true;
             pass_progress = false;
             pos = 0;
-            if (lane == 0) sh.stat[ST_PASSES] += 1;
+            if (lane == 0) bump(sh.stat, ST_PASSES, 1);
           }
           if (pos >= qlen) { in_pass = false; continue; }
 
@@ -614,31 +646,25 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           if (sw_pending && a.trace_on > 1) sw_lb = wall_clock64();
           if (sh.slot_tag[sl] != coll) {
             if (lane < 8) ((uint4*)&sh.slot[sl])[lane] = ((const uint4*)&myctx[coll])[lane];
-            if (lane == 0) { sh.slot_tag[sl] = coll; sh.stat[ST_LOAD] += 1; }
+            if (lane == 0) { sh.slot_tag[sl] = coll; bump(sh.stat, ST_LOAD, 1); }
             __builtin_amdgcn_wave_barrier();
-          } else if (lane == 0) sh.stat[ST_HIT] += 1;
+          } else if (lane == 0) bump(sh.stat, ST_HIT, 1);
           if (sw_pending && a.trace_on > 1) sw_le = wall_clock64();
           {
             const DfxCtxEntry& C = sh.slot[sl];
-            kind = C.st.kind; dtype = C.st.dtype; root = C.st.root;
+            kind = C.st.kind; dtype = C.st.dtype; bc_pos = C.st.bc_pos;
             eb = (dtype == DT_F32 || dtype == DT_I32) ? 4u : 2u;
             nprim = C.st.nprim; rounds = C.st.rounds; K = C.st.nslots; nchan = C.st.nchan;
-            slot_bytes = C.st.slot_bytes; slice_elems = C.st.slice_elems; seq = C.st.seq;
+            slice_elems = C.st.slice_elems; slot_bytes = slice_elems * eb; seq = C.st.seq;
             count = C.st.count; block_elems = C.st.block_elems; part_elems = C.st.part_elems;
             sendbuf = (const char*)C.st.sendbuf;
             recvbuf = (char*)C.st.recvbuf;
-            g = C.dyn.round; p = C.dyn.prim; sent = C.dyn.sent; recvd = C.dyn.recvd;
+            tail_out = (u64*)C.st.flags_out; head_out = tail_out + 8;
+            tail_in = (u64*)C.st.flags_in; head_in = tail_in + 8;
+            fifo_out = (uint8_t*)C.st.fifo_out;
+            fifo_in = (uint8_t*)C.st.fifo_in;
+            g = C.dyn.round; p = C.dyn.prim; sent = C.dyn.sent; recvd = C.dyn.recvd; cidx = C.dyn.cidx;
             preempted_before = C.dyn.preempted;
-            // connector geometry: flags first, then slots
-            uint8_t* conn = a.pool + C.st.conn_off;
-            const uint32_t e_out = rank, e_in = (rank + (uint32_t)R - 1) % (uint32_t)R;
-            tail_out = (u64*)(conn + ((size_t)e_out * nchan + ch) * DFX_FLAG_STRIDE);
-            head_out = tail_out + 8;
-            tail_in = (u64*)(conn + ((size_t)e_in * nchan + ch) * DFX_FLAG_STRIDE);
-            head_in = tail_in + 8;
-            uint8_t* slots = conn + (size_t)R * nchan * DFX_FLAG_STRIDE;
-            fifo_out = slots + ((size_t)e_out * nchan + ch) * K * slot_bytes;
-            fifo_in = slots + ((size_t)e_in * nchan + ch) * K * slot_bytes;
           }
           // SetInitialSpinThreshold (Alg. 1 line 3): largest at the front, halving per position
           thr = a.spin_init >> (pos < 31 ? pos : 31);
@@ -648,11 +674,12 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         }
 
         // ================= next primitive of the collective in hand =================
-        const Prim q = make_prim(kind, R, (int)rank, root, p);
+        const Prim q = make_prim(kind, a.R, bc_pos, p);
         // slice geometry (elements relative to the block, clipped to the block's true length)
+        const bool ring_chunks = (kind == KIND_AR && a.R > 1);
         u64 blen = count;
-        if (kind == KIND_AR && R > 1) {
-          const u64 start = (u64)q.cidx * block_elems;
+        if (ring_chunks) {
+          const u64 start = (u64)cidx * block_elems;
           blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
         }
         u64 lo = (u64)ch * part_elems + (u64)g * slice_elems;
@@ -663,9 +690,9 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         if (hi > blen) hi = blen;
         const uint32_t bytes = (uint32_t)(hi - lo) * eb;
         u64 soff = lo, doff = lo;   // element offsets in the send / recv buffer
-        if (kind == KIND_AR && R > 1) { soff += (u64)q.cidx * block_elems; doff = soff; }
-        else if (kind == KIND_RS) soff += (u64)q.cidx * count;
-        else if (kind == KIND_AG) doff += (u64)q.cidx * count;
+        if (ring_chunks) { soff += (u64)cidx * block_elems; doff = soff; }
+        else if (kind == KIND_RS) soff += (u64)cidx * count;
+        else if (kind == KIND_AG) doff += (u64)cidx * count;
 
         u64 tm0 = 0;
         if (a.trace_on > 1) tm0 = wall_clock64();
@@ -713,14 +740,14 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             }
             __builtin_amdgcn_s_sleep(1);
           }
-          if (lane == 0) sh.stat[ST_POLLS] += n;
+          if (lane == 0) bump(sh.stat, ST_POLLS, n);
         }
 
         if (res == W_OK) {
           pend_send = q.send;
           pend_recv = q.recv;
           pending_pub = true;
-          if (a.trace_on > 1) { tm1 = wall_clock64(); if (lane == 0) sh.stat[ST_T_WAIT] += tm1 - tm0; tm2 = tm1; }
+          if (a.trace_on > 1) { tm1 = wall_clock64(); if (lane == 0) bump(sh.stat, ST_T_WAIT, tm1 - tm0); tm2 = tm1; }
           if (bytes) {
             if (lane == 0) {
               Job j;
@@ -740,14 +767,14 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           const bool tr = a.trace_on && res == W_TIMEOUT && pos + 1 < qlen;
           if (tr) sw_t0 = wall_clock64();
           if (lane == 0) {
-            if (res == W_TIMEOUT) sh.stat[ST_PREEMPT] += 1;
+            if (res == W_TIMEOUT) bump(sh.stat, ST_PREEMPT, 1);
             if (progressed) {
               DfxDyn d; d.round = g; d.prim = p; d.sent = sent; d.recvd = recvd;
-              d.preempted = preempted_before + 1; d.pad = 0;
+              d.preempted = preempted_before + 1; d.cidx = cidx;
               sh.slot[sl].dyn = d;
               myctx[coll].dyn = d;
-              sh.stat[ST_SAVE] += 1;
-            } else if (res == W_TIMEOUT) sh.stat[ST_LAZY] += 1;
+              bump(sh.stat, ST_SAVE, 1);
+            } else if (res == W_TIMEOUT) bump(sh.stat, ST_LAZY, 1);
           }
           if (tr) { if (a.trace_on > 1) sw_ts = wall_clock64(); sw_pending = true; }
           have = false;
@@ -765,8 +792,12 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       const Job j = sh.job;
       // fenced mode: every wave invalidates before its own loads of the slot (the poll was wave 0's)
       if (!coh && j.fin) fence_acquire_agent();
+#ifdef DFX_NO_FENCED
+      run_prim<AUX_DEVICE>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes);
+#else
       if (coh) run_prim<AUX_DEVICE>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes);
       else run_prim<AUX_CACHED>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes);
+#endif
     }
     if (sched && a.trace_on > 1) tm2 = wall_clock64();
     drain_and_barrier();
@@ -779,12 +810,12 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
     ws->read_index = ri;
     ws->qlen = qlen;
     ws->trace_n = trace_n;
-    sh.slot_tag[0] = qlen;    // reuse as a broadcast word: nobody needs the tags any more
+    for (int i = 0; i < DFX_NSTAT; ++i) ws->stat[i] = sh.stat[i];
+    sh.qlen_out = qlen;
   }
   __syncthreads();
-  const uint32_t qn = sh.slot_tag[0];
+  const uint32_t qn = sh.qlen_out;
   for (uint32_t i = tid; i < qn; i += NT) qstore[i] = sh.taskq[i];
-  if (tid < DFX_NSTAT) ws->stat[tid] = sh.stat[tid];
 }
 
 // Plain copy kernel of known traffic: calibrates the HBM byte counters of the profiler.

@@ -48,12 +48,29 @@ struct alignas(16) DfxDyn {
   uint64_t sent;         // slices ever pushed into the send connector
   uint64_t recvd;        // slices ever taken from the recv connector
   uint32_t preempted;    // times this invocation was preempted on this workgroup
-  uint32_t pad;
+  uint32_t cidx;         // ring-chunk index of the next primitive (kept so that no division is needed)
 };
 static_assert(sizeof(DfxDyn) == 32, "DfxDyn must be 32 bytes");
 
+// What a workgroup keeps of an invocation (device-private): the SQE "cooked" once at fetch time
+// into ready-to-use addresses, so that a context load needs no address arithmetic.  96 bytes.
+struct alignas(16) DfxCooked {
+  uint64_t sendbuf, recvbuf, count, block_elems, part_elems;
+  uint64_t flags_out;    // tail counter of my send connector (head at +64 bytes)
+  uint64_t flags_in;     // tail counter of my recv connector (head at +64 bytes)
+  uint64_t fifo_out;     // first slot of my send connector
+  uint64_t fifo_in;      // first slot of my recv connector
+  uint32_t slice_elems, rounds, seq;
+  uint16_t nprim, nchan;
+  uint8_t nslots, kind, dtype;
+  uint8_t bc_pos;        // broadcast: 0 = root, 1 = middle of the chain, 2 = last
+  int16_t priority;
+  uint16_t pad;
+};
+static_assert(sizeof(DfxCooked) == 96, "DfxCooked must be 96 bytes");
+
 struct alignas(16) DfxCtxEntry {
-  DfxStatic st;
+  DfxCooked st;
   DfxDyn dyn;
 };
 static_assert(sizeof(DfxCtxEntry) == 128, "context entry must be 128 bytes");
