@@ -167,3 +167,20 @@ def test_stats_are_consistent():
         assert s["max_taskq"] <= 6
     assert sum(s["switch_samples"] for s in stats) > 0
     assert all(0.0 < s["switch_us_p50"] < 100.0 for s in stats if s["switch_samples"])
+
+
+@pytest.mark.parametrize("placement", [0, 1])
+def test_sq_placements(placement):
+    """SQ in pinned host memory (the paper's placement, Sec. 5) and in fine-grained device memory
+    written by the host through the PCIe BAR: same results; the device placement needs a large BAR."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.config4(n_colls=12, min_bytes=4096, max_bytes=1 << 20, seed=21)
+    try:
+        dw, stats, _ = gh.run_workload(w, gh.make_config(sq_in_device=placement), mode="threads", timeout_s=30.0)
+    except dfx.DfxError as e:
+        if placement == 1 and e.status == dfx.ERR_NO_RESOURCES:
+            pytest.skip("device does not report a large BAR")
+        raise
+    for ci in range(12):
+        _expect(dw, w, ci)
