@@ -90,6 +90,84 @@ def switch_latency():
             "load_us_mean": round(sum(s["load_us_mean"] for s in st2) / R, 3)}
 
 
+def deadlock_prone():
+    """Completion under deadlock-prone issue orders: the circular wait in its four order
+    combinations, the sixteen 25 MiB bf16 buckets, 64 mixed collectives and 1024 small all-reduces,
+    every vrank submitting in its own order (values are checked by the GPU tests, not here)."""
+    import itertools
+    import workload_inputs as wi
+    import paper_2303_06324_amd as dfx
+    from tests import gpu_harness as gh
+    out = {}
+    ok = True
+    t_c1 = 0.0
+    for o in itertools.product([(0, 1), (1, 0)], repeat=2):
+        w = wi.config1(*o)
+        dw = gh.DeviceWorkload(w, keep_host=False)
+        t0 = time.perf_counter()
+        _, st, _ = gh.run_workload(w, gh.make_config(max_channels=4), dw=dw, timeout_s=20.0)
+        t_c1 += time.perf_counter() - t0
+        ok = ok and sum(s["cqe_posted"] for s in st) == 4
+    out["config1_four_order_combinations"] = {"completed": ok, "seconds": round(t_c1, 4)}
+    for name, w, mode in (("config3_16x25MiB_bf16", wi.config3(), "roundrobin"),
+                          ("config4_64_mixed", wi.config4(), "threads"),
+                          ("config5_1024_small", wi.config5(), "threads")):
+        dw = gh.DeviceWorkload(w, keep_host=False)
+        ctx = dfx.Context(R, gh.make_config())
+        try:
+            gh.prepare_all(ctx, w)
+            t0 = time.perf_counter()
+            if mode == "threads":
+                gh.submit_threads(ctx, dw, delays_us=w.delays_us or None, timeout_s=60)
+            else:
+                gh.submit_round_robin(ctx, dw, timeout_s=60)
+            rc = ctx.wait_all(60.0)
+            dt = time.perf_counter() - t0
+            ctx.stop()
+            st = [ctx.stats(r) for r in range(R)]
+        finally:
+            ctx.finalize()
+        del dw
+        out[name] = {"completed": rc == 0 and sum(s["cqe_posted"] for s in st) == len(w.colls) * R,
+                     "seconds": round(dt, 4), "preemptions": sum(s["preemptions"] for s in st),
+                     "max_task_queue": max(s["max_taskq"] for s in st)}
+    return out
+
+
+def size_sweep(iters: int = 10):
+    """All-reduce latency / bandwidth over the sweep's sizes inside one resident daemon
+    (submit of the first vrank -> last CQE seen by the host; best of `iters`)."""
+    import torch
+    import paper_2303_06324_amd as dfx
+    from tests import gpu_harness as gh
+    import workload_inputs as wi
+    rows = []
+    for nbytes in wi.CONFIG2_SIZES:
+        n = nbytes // 4
+        send = [torch.randn(n, device="cuda") for _ in range(R)]
+        recv = [torch.empty(n, device="cuda") for _ in range(R)]
+        torch.cuda.synchronize()
+        ctx = dfx.Context(R, gh.make_config())
+        try:
+            ctx.prepare(0, dfx.ALLREDUCE, n, dfx.F32)
+            best = 1e9
+            for _ in range(iters + 2):
+                t0 = time.perf_counter()
+                for r in range(R):
+                    assert ctx.submit(r, 0, send[r].data_ptr(), recv[r].data_ptr()) == dfx.OK
+                assert ctx.wait_all(30.0) == dfx.OK
+                best = min(best, time.perf_counter() - t0)
+            nchan = ctx.coll_info(0)["nchan"]
+        finally:
+            ctx.finalize()
+        rows.append({"bytes": nbytes, "us": round(best * 1e6, 1), "channels": nchan,
+                     "algbw_GBs": round(nbytes / best / 1e9, 2),
+                     "busbw_GBs": round(nbytes / best * 2 * (R - 1) / R / 1e9, 2),
+                     "hbm_frac": round(algorithmic_bytes(nbytes, R) / best / 1e9 / HBM_PEAK_GBS, 4)})
+        del send, recv
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,6 +177,8 @@ def main():
     ap.add_argument("--cpu-sample-mib", type=int, default=256)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-switch", action="store_true", help="skip the context-switch latency leg")
+    ap.add_argument("--no-orders", action="store_true", help="skip the deadlock-prone-orders leg")
+    ap.add_argument("--sweep", action="store_true", help="add the 8 KiB .. 256 MiB size sweep to the JSON line")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="after the steps, run one plain copy kernel of this many MiB (untimed): its known "
                          "traffic calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters")
@@ -176,8 +256,14 @@ def main():
                      "kernel": "dfx_daemon_kernel", "kernel_ms_avg": round(k_ms, 4),
                      "algorithmic_bytes_per_launch": algorithmic_bytes(M, R)},
     }
+    del send, recv
+    torch.cuda.empty_cache()
     if not args.no_switch:
         out["preempt_switch"] = switch_latency()
+    if not args.no_orders:
+        out["deadlock_prone_orders"] = deadlock_prone()
+    if args.sweep:
+        out["size_sweep"] = size_sweep()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_mib << 20)
     print(json.dumps(out), flush=True)
