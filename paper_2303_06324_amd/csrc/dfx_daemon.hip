@@ -35,6 +35,11 @@ namespace {
 typedef uint64_t u64;
 
 constexpr int NT = DFX_WG_THREADS;
+#ifndef DFX_SOLO_BYTES
+#define DFX_SOLO_BYTES 8192
+#endif
+// slices up to this size are moved by the scheduler wave alone (no barrier, no hand-off)
+constexpr uint32_t SOLO_BYTES = DFX_SOLO_BYTES;
 #ifndef DFX_UNROLL
 #define DFX_UNROLL 8
 #endif
@@ -172,12 +177,12 @@ struct Slot {   // one connector slot seen through a buffer resource
   __device__ __forceinline__ void st2(uint32_t off, uint16_t v) const { __builtin_amdgcn_raw_buffer_store_b16(v, rsrc, (int)off, 0, AUX); }
 };
 
-template <int DT, int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT>
+template <int DT, int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT, int NTH>
 __device__ __forceinline__ void move_slice(const void* fin_p, const char* __restrict__ sb, char* __restrict__ rb,
-                                           void* fout_p, uint32_t bytes) {
+                                           void* fout_p, uint32_t bytes, uint32_t tid) {
+  constexpr int NT = NTH;   // threads that share the slice: the whole workgroup, or the scheduler wave alone
   static_assert(FIN || SB, "a primitive has a source");
   static_assert(RB || FOUT, "a primitive has a destination");
-  const uint32_t tid = threadIdx.x;
   const Slot<AIN> fin(fin_p, FIN ? bytes : 0);
   const Slot<AOUT> fout(fout_p, FOUT ? bytes : 0);
   uintptr_t al = 0;
@@ -263,34 +268,34 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
   }
 }
 
-template <int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT>
-__device__ __forceinline__ void move_dispatch(int dtype, const void* fin, const char* sb, char* rb, void* fout, uint32_t bytes) {
-  if (!(FIN && SB)) { move_slice<DT_COPY, AIN, AOUT, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); return; }
+template <int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT, int NTH>
+__device__ __forceinline__ void move_dispatch(int dtype, const void* fin, const char* sb, char* rb, void* fout, uint32_t bytes, uint32_t tid) {
+  if (!(FIN && SB)) { move_slice<DT_COPY, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid); return; }
   switch (dtype) {
-    case DT_F32: move_slice<DT_F32, AIN, AOUT, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
-    case DT_BF16: move_slice<DT_BF16, AIN, AOUT, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
-    case DT_F16: move_slice<DT_F16, AIN, AOUT, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
-    default: move_slice<DT_I32, AIN, AOUT, FIN, SB, RB, FOUT>(fin, sb, rb, fout, bytes); break;
+    case DT_F32: move_slice<DT_F32, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid); break;
+    case DT_BF16: move_slice<DT_BF16, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid); break;
+    case DT_F16: move_slice<DT_F16, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid); break;
+    default: move_slice<DT_I32, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid); break;
   }
 }
 
 // fin / sb / rb / fout are null when the primitive does not use that side.
 // AUX: how connector slots are accessed (AUX_DEVICE, or AUX_CACHED in the fenced mode).
-template <int AUX>
-__device__ __forceinline__ void run_prim(int dtype, const void* fin, const char* sb, char* rb, void* fout, uint32_t bytes) {
+template <int AUX, int NTH>
+__device__ __forceinline__ void run_prim(int dtype, const void* fin, const char* sb, char* rb, void* fout, uint32_t bytes, uint32_t tid) {
   if (fin) {
     if (sb) {
-      if (rb) { if (fout) move_dispatch<AUX, AUX, true, true, true, true>(dtype, fin, sb, rb, fout, bytes);    // recv-reduce-copy-send
-                else move_dispatch<AUX, AUX, true, true, true, false>(dtype, fin, sb, rb, fout, bytes); }      // recv-reduce-copy
-      else move_dispatch<AUX, AUX, true, true, false, true>(dtype, fin, sb, rb, fout, bytes);                  // recv-reduce-send
+      if (rb) { if (fout) move_dispatch<AUX, AUX, true, true, true, true, NTH>(dtype, fin, sb, rb, fout, bytes, tid);    // recv-reduce-copy-send
+                else move_dispatch<AUX, AUX, true, true, true, false, NTH>(dtype, fin, sb, rb, fout, bytes, tid); }      // recv-reduce-copy
+      else move_dispatch<AUX, AUX, true, true, false, true, NTH>(dtype, fin, sb, rb, fout, bytes, tid);                  // recv-reduce-send
     } else {
-      if (fout) move_dispatch<AUX, AUX, true, false, true, true>(dtype, fin, sb, rb, fout, bytes);             // recv-copy-send
-      else move_dispatch<AUX, AUX, true, false, true, false>(dtype, fin, sb, rb, fout, bytes);                 // recv-copy
+      if (fout) move_dispatch<AUX, AUX, true, false, true, true, NTH>(dtype, fin, sb, rb, fout, bytes, tid);             // recv-copy-send
+      else move_dispatch<AUX, AUX, true, false, true, false, NTH>(dtype, fin, sb, rb, fout, bytes, tid);                 // recv-copy
     }
   } else {
-    if (rb) { if (fout) move_dispatch<AUX, AUX, false, true, true, true>(dtype, fin, sb, rb, fout, bytes);     // copy-send
-              else move_dispatch<AUX, AUX, false, true, true, false>(dtype, fin, sb, rb, fout, bytes); }       // copy
-    else move_dispatch<AUX, AUX, false, true, false, true>(dtype, fin, sb, rb, fout, bytes);                   // send
+    if (rb) { if (fout) move_dispatch<AUX, AUX, false, true, true, true, NTH>(dtype, fin, sb, rb, fout, bytes, tid);     // copy-send
+              else move_dispatch<AUX, AUX, false, true, true, false, NTH>(dtype, fin, sb, rb, fout, bytes, tid); }       // copy
+    else move_dispatch<AUX, AUX, false, true, false, true, NTH>(dtype, fin, sb, rb, fout, bytes, tid);                   // send
   }
 }
 
@@ -563,8 +568,11 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
               __builtin_amdgcn_wave_barrier();
               const uint32_t c_id = sh.sqe.coll_id;
               const uint32_t flags = sh.sqe.flags;
-              const bool is_exit = (flags & DFX_SQE_EXIT) != 0;
-              const bool mine = !is_exit && ch < sh.sqe.nchan && c_id < a.max_colls;
+              // an exit SQE ends the launch it was posted for; one left over from an earlier launch
+              // (some workgroups had already gone when it arrived) is consumed and ignored
+              const bool is_exit_sqe = (flags & DFX_SQE_EXIT) != 0;
+              const bool is_exit = is_exit_sqe && sh.sqe.seq == a.epoch;
+              const bool mine = !is_exit_sqe && ch < sh.sqe.nchan && c_id < a.max_colls;
               if (mine) {
                 // cook the static context of this invocation into the context buffer (addresses
                 // resolved once, here); restart the sequence, keep the monotone connector counters
@@ -617,7 +625,11 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
               acted = true;
               sw_pending = false;
               ++ri;
-              if (is_exit) { stop = STOP_EXIT; cmd = CMD_STOP; break; }
+              if (is_exit) {
+                // the whole grid leaves (every workgroup has reader duties towards its rank's SQ)
+                if (lane == 0) __hip_atomic_store(&a.dev_ctl[DC_QUIT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
+                stop = STOP_EXIT; cmd = CMD_STOP; break;
+              }
               ++burst;
               idle = 0;
               continue;               // probe the SQ again before walking the queue
@@ -749,17 +761,27 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           pending_pub = true;
           if (a.trace_on > 1) { tm1 = wall_clock64(); if (lane == 0) bump(sh.stat, ST_T_WAIT, tm1 - tm0); tm2 = tm1; }
           if (bytes) {
-            if (lane == 0) {
-              Job j;
-              j.fin = q.recv ? (const void*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
-              j.fout = q.send ? (void*)(fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
-              j.sb = q.from_send ? sendbuf + soff * eb : nullptr;
-              j.rb = q.to_recv ? recvbuf + doff * eb : nullptr;
-              j.bytes = bytes;
-              j.dtype = dtype;
-              sh.job = j;
+            const void* jfin = q.recv ? (const void*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
+            void* jfout = q.send ? (void*)(fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
+            const char* jsb = q.from_send ? sendbuf + soff * eb : nullptr;
+            char* jrb = q.to_recv ? recvbuf + doff * eb : nullptr;
+            if (coh && bytes <= SOLO_BYTES) {
+              // a short slice: this wave moves it on its own (one load batch), drains, and
+              // publishes at the top of the loop
+              run_prim<AUX_DEVICE, 64>(dtype, jfin, jsb, jrb, jfout, bytes, lane);
+              __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+              __builtin_amdgcn_s_waitcnt(0);
+              if (a.trace_on > 1) tm2 = wall_clock64();
+            } else {
+              if (lane == 0) {
+                Job j;
+                j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
+                j.bytes = bytes;
+                j.dtype = dtype;
+                sh.job = j;
+              }
+              cmd = CMD_MOVE;
             }
-            cmd = CMD_MOVE;
           }
           // an empty slice is only a handshake: it is published at the top of the loop
         } else {
@@ -793,10 +815,10 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       // fenced mode: every wave invalidates before its own loads of the slot (the poll was wave 0's)
       if (!coh && j.fin) fence_acquire_agent();
 #ifdef DFX_NO_FENCED
-      run_prim<AUX_DEVICE>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes);
+      run_prim<AUX_DEVICE, NT>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, tid);
 #else
-      if (coh) run_prim<AUX_DEVICE>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes);
-      else run_prim<AUX_CACHED>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes);
+      if (coh) run_prim<AUX_DEVICE, NT>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, tid);
+      else run_prim<AUX_CACHED, NT>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, tid);
 #endif
     }
     if (sched && a.trace_on > 1) tm2 = wall_clock64();

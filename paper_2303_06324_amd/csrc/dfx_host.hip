@@ -160,6 +160,7 @@ int launch_locked(dfx_ctx* c) {
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   a.nwg = c->nwg;
+  a.epoch = (uint32_t)(c->launches + 1);
   // quit votes and the quit flag belong to one launch
   HIPCHK(c, hipMemsetAsync(c->dev_ctl + DC_QUIT, 0, 2 * sizeof(uint32_t), c->stream));
   HIPCHK(c, hipEventRecord(c->ev_start, c->stream));
@@ -569,6 +570,7 @@ int dfx_stop(dfx_ctx* c) {
     DfxStatic e;
     memset(&e, 0, sizeof(e));
     e.flags = DFX_SQE_EXIT;
+    e.seq = (uint32_t)c->launches;   // the launch in flight
     e.coll_id = 0xffffffffu;
     for (;;) {
       int rc;

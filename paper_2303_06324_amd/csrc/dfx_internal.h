@@ -113,6 +113,7 @@ struct DfxDaemonArgs {
   uint16_t* taskq_store;    // [nwg][max_colls] device
   uint64_t* trace;          // [nwg][DFX_TRACE_N] device (or null)
   uint32_t nwg;
+  uint32_t epoch;           // number of this launch (exit SQEs name the launch they end)
   uint32_t R, cmax, max_colls, sq_depth, sq_shift, cq_slots;
   uint32_t spin_init, spin_min, spin_max, spin_boost, preempt;
   uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent;

@@ -184,3 +184,32 @@ def test_sq_placements(placement):
         raise
     for ci in range(12):
         _expect(dw, w, ci)
+
+
+def test_stop_with_outstanding_work_and_resume():
+    """dfx_stop (exit SQE, Sec. 4.4) while collectives are stuck: their contexts survive in the
+    context buffer (Sec. 4.5) and the next start resumes them."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.config3(n_buckets=4, bucket_bytes=1 << 20, seed=15)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(8, gh.make_config(quit_idle_us=0))
+    try:
+        gh.prepare_all(ctx, w)
+        for ci in range(4):                      # only ranks 0..5 submit: nothing can complete
+            for r in range(6):
+                assert ctx.submit(r, ci, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr()) == dfx.OK
+        time.sleep(0.02)
+        assert ctx.stop() == dfx.OK
+        assert ctx.poll(0, 8) == []
+        for cycle in range(2):                   # an empty start/stop cycle in between
+            assert ctx.start() == dfx.OK
+            assert ctx.stop() == dfx.OK
+        for ci in range(4):
+            for r in (6, 7):
+                assert ctx.submit(r, ci, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr()) == dfx.OK
+        assert ctx.wait_all(20.0) == dfx.OK
+        for ci in range(4):
+            _expect(dw, w, ci)
+    finally:
+        assert ctx.finalize() == dfx.OK
