@@ -168,6 +168,41 @@ def size_sweep(iters: int = 10):
     return rows
 
 
+def spin_sweep():
+    """Overhead against the spin threshold (the paper's Eq. 1-2: T = t[spin] + t[switch] + t[q_len],
+    expected U-shaped in N_spin): a FIXED threshold N for every position and no boost (the naive
+    policy of Sec. 6.4), on the disordered bucket and small-collective workloads, next to the
+    adaptive default."""
+    import workload_inputs as wi
+    import paper_2303_06324_amd as dfx
+    from tests import gpu_harness as gh
+    w3, w5 = wi.config3(), wi.config5(n_colls=256, seed=4)
+    d3, d5 = gh.DeviceWorkload(w3, keep_host=False), gh.DeviceWorkload(w5, keep_host=False)
+
+    def one(w, dw, mode, **kw):
+        ctx = dfx.Context(R, gh.make_config(**kw))
+        try:
+            gh.prepare_all(ctx, w)
+            t0 = time.perf_counter()
+            (gh.submit_threads if mode == "threads" else gh.submit_round_robin)(ctx, dw, timeout_s=120)
+            rc = ctx.wait_all(120.0)
+            dt = time.perf_counter() - t0
+            ctx.stop()
+            pre = sum(ctx.stats(r)["preemptions"] for r in range(R))
+        finally:
+            ctx.finalize()
+        return {"completed": rc == 0, "ms": round(dt * 1e3, 2), "preemptions": pre}
+
+    rows = []
+    for n in (1, 2, 4, 8, 16, 64, 256, 1024, 4096, 16384):
+        kw = dict(spin_init=n, spin_min=n, spin_max=n, spin_boost=1)
+        rows.append({"fixed_threshold": n, "config3_16x25MiB": one(w3, d3, "roundrobin", **kw),
+                     "config5_256_small": one(w5, d5, "threads", **kw)})
+    rows.append({"fixed_threshold": None, "policy": "adaptive default",
+                 "config3_16x25MiB": one(w3, d3, "roundrobin"), "config5_256_small": one(w5, d5, "threads")})
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -179,6 +214,7 @@ def main():
     ap.add_argument("--no-switch", action="store_true", help="skip the context-switch latency leg")
     ap.add_argument("--no-orders", action="store_true", help="skip the deadlock-prone-orders leg")
     ap.add_argument("--sweep", action="store_true", help="add the 8 KiB .. 256 MiB size sweep to the JSON line")
+    ap.add_argument("--spin-sweep", action="store_true", help="add the fixed-spin-threshold sweep to the JSON line")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="after the steps, run one plain copy kernel of this many MiB (untimed): its known "
                          "traffic calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters")
@@ -264,6 +300,8 @@ def main():
         out["deadlock_prone_orders"] = deadlock_prone()
     if args.sweep:
         out["size_sweep"] = size_sweep()
+    if args.spin_sweep:
+        out["spin_sweep"] = spin_sweep()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_mib << 20)
     print(json.dumps(out), flush=True)

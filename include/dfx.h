@@ -48,7 +48,8 @@ typedef enum {
   DFX_ERR_ABORTED = -8    /* the daemon was aborted; context must be finalized */
 } dfx_status;
 
-/* One completion (Sec. 5 "the CQE only carries the collective's ID"; seq added: reading 13). */
+/* One completion.  In the paper the CQE carries only the collective's ID (Sec. 5); the invocation
+   number is added here so that repeated runs of one ID can be told apart. */
 typedef struct {
   uint32_t coll_id;
   uint32_t seq; /* how many times this (rank, coll_id) had been submitted before this invocation */

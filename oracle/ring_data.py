@@ -25,7 +25,7 @@ mod R), one rounding per + in the storage dtype.  FIFO slices and channels of
 the GPU path only subdivide a chunk; they never move an element to another
 chunk, so the values do not depend on them.
 
-Arithmetic (paper silent; reading listed in the design notes): fp32 = one
+Arithmetic (the paper is silent; this is the reading taken): fp32 = one
 IEEE binary32 round-to-nearest-even add per hop, gradual underflow; fp16 and
 bf16 = widen both operands to fp32, add, round to nearest even back to 16 bits
 at every hop (partials travel in the storage dtype); int32 = wraparound.

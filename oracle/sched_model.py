@@ -25,7 +25,7 @@ primitive touches nothing until BOTH its conditions hold, so an aborted wait lea
 connectors and buffers unchanged (Sec. 4.5: restart without under- or re-sending).
 A preempted collective keeps its queue position (Sec. 4.3).
 
-Readings where the paper is silent (listed in the design notes): spin threshold unit
+Readings taken where the paper is silent: spin threshold unit
 = poll attempts; thr(pos) = max(spin_min, spin_init >> pos); after a success
 thr = min(spin_max, thr*boost) until preemption or completion; "cannot progress for
 a while" = one whole pass over the task queue with no successful primitive, after
