@@ -252,9 +252,9 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->nslots = 4;
   cfg->slot_bytes = 128u << 10;
   cfg->chan_min_bytes = 16u << 10;
-  cfg->spin_init = 16;
-  cfg->spin_min = 2;
-  cfg->spin_max = 64;
+  cfg->spin_init = 8;
+  cfg->spin_min = 1;
+  cfg->spin_max = 32;
   cfg->spin_boost = 2;
   cfg->fetch_batch = 0;
   cfg->preempt = 1;
