@@ -105,7 +105,7 @@ def deadlock_prone():
         w = wi.config1(*o)
         dw = gh.DeviceWorkload(w, keep_host=False)
         t0 = time.perf_counter()
-        _, st, _ = gh.run_workload(w, gh.make_config(max_channels=4), dw=dw, timeout_s=20.0)
+        _, st, _ = gh.run_workload(w, gh.make_config(max_channels=4, chan_spread=0), dw=dw, timeout_s=20.0)
         t_c1 += time.perf_counter() - t0
         ok = ok and sum(s["cqe_posted"] for s in st) == 4
     out["config1_four_order_combinations"] = {"completed": ok, "seconds": round(t_c1, 4)}

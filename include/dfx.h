@@ -82,6 +82,14 @@ typedef struct {
                               2 = also time the save / load parts and the wait / data / publish phases */
   uint32_t fetch_batch;    /* SQEs a workgroup may fetch in a row when its queue is empty or stuck; 0 = all available */
   uint64_t pool_bytes;     /* device memory reserved for connectors of all prepared collectives */
+  uint32_t scan_min;       /* a pass over a task queue of at least this many entries starts with a readiness
+                              scan (64 entries polled at once, one per lane) and visits only runnable
+                              entries; 0 = never scan, poll every entry in turn as Alg. 1 is written */
+  uint32_t chan_spread;    /* 1: a collective that uses fewer channels than max_channels starts at workgroup
+                              (coll_id * channels) mod max_channels of its rank, so that many small
+                              collectives spread over the grid; 0: every collective starts at workgroup 0
+                              (small collectives all share the first task queues: the single-queue
+                              setting of Sec. 2.3) */
 } dfx_config;
 
 /* Aggregated over the workgroups of one vrank since dfx_init. */
@@ -108,6 +116,7 @@ typedef struct {
   double wait_us;          /* with trace on: time in wait phases, summed over the vrank's workgroups */
   double data_us;          /* ... in data phases (loads issued until stores issued) */
   double publish_us;       /* ... draining stores, barrier and counter stores */
+  uint64_t scan_skips;     /* queue entries a readiness scan found not runnable (no context load, no spin) */
 } dfx_stats_t;
 
 /* Fill *cfg with defaults (struct_bytes set). cfg: host, caller-owned. */

@@ -25,7 +25,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in (
         "struct_bytes", "max_channels", "max_colls", "sq_depth", "cq_slots", "nslots", "slot_bytes",
         "chan_min_bytes", "spin_init", "spin_min", "spin_max", "spin_boost", "preempt", "watchdog_ms",
-        "quit_idle_us", "sq_in_device", "wg_map", "order_policy", "trace", "fetch_batch")] + [("pool_bytes", C.c_uint64)]
+        "quit_idle_us", "sq_in_device", "wg_map", "order_policy", "trace", "fetch_batch")] + [("pool_bytes", C.c_uint64), ("scan_min", C.c_uint32), ("chan_spread", C.c_uint32)]
 
 
 class Stats(C.Structure):
@@ -33,7 +33,7 @@ class Stats(C.Structure):
         "preemptions", "ctx_loads", "ctx_slot_hits", "ctx_saves", "lazy_skips", "polls", "prims", "sqe_fetched",
         "cqe_posted", "max_taskq", "passes", "quits", "launches", "switch_samples")] + [(n, C.c_double) for n in (
         "switch_us_p50", "switch_us_p99", "switch_us_mean", "save_us_mean", "load_us_mean", "wait_us", "data_us",
-        "publish_us")]
+        "publish_us")] + [("scan_skips", C.c_uint64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

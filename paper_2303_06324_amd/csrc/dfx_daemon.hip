@@ -316,6 +316,7 @@ struct Shared {
   uint32_t cmd;                      // scheduler wave -> workgroup: CMD_MOVE or CMD_STOP
   uint32_t qlen_out;                 // queue length handed to all waves when leaving
   u64 stat[DFX_NSTAT];               // counters (LDS atomics without return: one instruction, no wait)
+  uint16_t rlist[DFX_MAX_COLLS];     // queue positions the readiness scan found runnable, ascending
   uint16_t taskq[DFX_MAX_COLLS];     // task queue (Sec. 4.2 (1))
 };
 
@@ -415,7 +416,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   u64 last_act = wall_clock64();
   bool acted = true, voted = false;
   uint32_t iter = 0, idle = 0, burst = 0;
-  bool in_pass = false, pass_progress = false;
+  bool in_pass = false, pass_progress = false, scanned = false;
+  uint32_t nready = 0, rk = 0, removed = 0;   // readiness list of the pass: length, cursor, entries completed
   uint32_t pos = 0;
   uint32_t stop = STOP_NONE;
   // context-switch sample in flight: t0 = abort decision, ts = after the save, lb/le = load
@@ -426,7 +428,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   uint32_t coll = 0, sl = 0, nprim = 0, rounds = 0, K = 0, nchan = 0, slot_bytes = 0, slice_elems = 0, eb = 4;
   uint32_t g = 0, p = 0, preempted_before = 0, seq = 0;
   int kind = 0, dtype = 0;
-  uint32_t bc_pos = 0, cidx = 0;
+  uint32_t bc_pos = 0, cidx = 0, vch = 0;
   u64 count = 0, block_elems = 0, part_elems = 0, sent = 0, recvd = 0, thr = 0;
   const char* sendbuf = nullptr;
   char* recvbuf = nullptr;
@@ -506,6 +508,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             }
             have = false;
             sw_pending = false;
+            if (scanned) { ++rk; ++removed; }
           }
           continue;
         }
@@ -572,7 +575,14 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
               // (some workgroups had already gone when it arrived) is consumed and ignored
               const bool is_exit_sqe = (flags & DFX_SQE_EXIT) != 0;
               const bool is_exit = is_exit_sqe && sh.sqe.seq == a.epoch;
-              const bool mine = !is_exit_sqe && ch < sh.sqe.nchan && c_id < a.max_colls;
+              // A collective with fewer channels than the grid has per rank starts at workgroup
+              // (coll_id * nchan) mod cmax, so that many small collectives spread over the rank's
+              // workgroups instead of queueing on the first ones; every rank derives the same
+              // start from the id, which keeps both ends of a connector on the same channel.
+              uint32_t my_vch = ch;
+              if (a.chan_spread && !is_exit_sqe && sh.sqe.nchan < a.cmax)
+                my_vch = (ch + a.cmax - (c_id * sh.sqe.nchan) % a.cmax) % a.cmax;
+              const bool mine = !is_exit_sqe && my_vch < sh.sqe.nchan && c_id < a.max_colls;
               if (mine) {
                 // cook the static context of this invocation into the context buffer (addresses
                 // resolved once, here); restart the sequence, keep the monotone connector counters
@@ -583,7 +593,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                   k.block_elems = q.block_elems; k.part_elems = q.part_elems;
                   uint8_t* conn = a.pool + q.conn_off;   // flags first, then slots
                   const uint32_t e_out = rank, e_in = (rank + a.R - 1) % a.R;
-                  const size_t fo = (size_t)e_out * q.nchan + ch, fi = (size_t)e_in * q.nchan + ch;
+                  const size_t fo = (size_t)e_out * q.nchan + my_vch, fi = (size_t)e_in * q.nchan + my_vch;
                   uint8_t* slots = conn + (size_t)a.R * q.nchan * DFX_FLAG_STRIDE;
                   k.flags_out = (uint64_t)(conn + fo * DFX_FLAG_STRIDE);
                   k.flags_in = (uint64_t)(conn + fi * DFX_FLAG_STRIDE);
@@ -594,7 +604,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                   k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = q.dtype;
                   const uint32_t bpos = (rank + a.R - q.root) % a.R;
                   k.bc_pos = bpos == 0 ? 0 : (bpos == a.R - 1 ? 2 : 1);
-                  k.priority = q.priority; k.pad = 0;
+                  k.priority = q.priority; k.vch = (uint16_t)my_vch;
                   myctx[c_id].st = k;
                   DfxDyn* dy = &myctx[c_id].dyn;
                   dy->round = 0; dy->prim = 0; dy->preempted = 0;
@@ -649,8 +659,53 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             pass_progress = false;
             pos = 0;
             if (lane == 0) bump(sh.stat, ST_PASSES, 1);
+            // ---- readiness scan: 64 queue entries per step, one per lane.  Each lane reads the
+            // saved context of its entry, works out which connector sides its next primitive
+            // needs, loads those counters and votes; the runnable positions are compacted into a list
+            // (ballot + popcount) and the pass visits only those: entries whose next
+            // primitive can run (the conditions are monotone: only this workgroup consumes its recv
+            // side and fills its send side, so "ready" stays true until it acts).  A queue of a
+            // thousand stuck collectives costs sixteen memory round trips instead of a thousand
+            // context loads and bounded spins.
+            scanned = a.scan_min && qlen >= a.scan_min;
+            if (scanned) {
+              nready = 0; rk = 0; removed = 0;
+              for (uint32_t base = 0; base < qlen; base += 64) {
+                const uint32_t i = base + lane;
+                bool rdy = false;
+                if (i < qlen) {
+                  const uint4* e = (const uint4*)&myctx[sh.taskq[i]];
+                  const uint4 fl = e[2];    // bytes 32..47: part_elems | flags_out
+                  const uint4 fi = e[3];    // bytes 48..63: flags_in | fifo_out
+                  const uint4 ge = e[5];    // bytes 80..95: seq | nprim,nchan | nslots,kind,dtype,bc_pos | priority
+                  const uint4 d0 = e[6];    // dyn: round | prim | sent
+                  const uint4 d1 = e[7];    // dyn: recvd | preempted | cidx
+                  const Prim pq = make_prim((int)((ge.z >> 8) & 0xffu), a.R, ge.z >> 24, d0.y);
+                  const u64 f_out = ((u64)fl.w << 32) | fl.z, f_in = ((u64)fi.y << 32) | fi.x;
+                  const u64 e_sent = ((u64)d0.w << 32) | d0.z, e_recvd = ((u64)d1.y << 32) | d1.x;
+                  bool okr = true, oks = true;
+                  if (pq.recv) okr = ld_agent64((const u64*)f_in) > e_recvd;
+                  if (pq.send) oks = (e_sent - ld_agent64((const u64*)f_out + 8)) < (u64)(ge.z & 0xffu);
+                  rdy = okr && oks;
+                }
+                const u64 mask = __ballot(rdy);
+                if (rdy) sh.rlist[nready + (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull))] = (uint16_t)i;
+                nready += (uint32_t)__builtin_popcountll(mask);
+              }
+              __builtin_amdgcn_wave_barrier();
+              if (lane == 0) { bump(sh.stat, ST_POLLS, (qlen + 63) / 64); bump(sh.stat, ST_SCAN_SKIPS, qlen - nready); }
+              if (nready == 0) {           // nothing can run: the pass is over before it began
+                in_pass = false;
+                __builtin_amdgcn_s_sleep(4);
+                continue;
+              }
+            }
           }
-          if (pos >= qlen) { in_pass = false; continue; }
+          if (scanned) {
+            // entries completed earlier in this pass moved the later ones up by one each
+            if (rk >= nready) { in_pass = false; continue; }
+            pos = (uint32_t)sh.rlist[rk] - removed;
+          } else if (pos >= qlen) { in_pass = false; continue; }
 
           // ---- LoadCollectiveContext: HBM context buffer -> LDS slot, 8 lanes x 16 bytes
           coll = sh.taskq[pos];
@@ -677,6 +732,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             fifo_in = (uint8_t*)C.st.fifo_in;
             g = C.dyn.round; p = C.dyn.prim; sent = C.dyn.sent; recvd = C.dyn.recvd; cidx = C.dyn.cidx;
             preempted_before = C.dyn.preempted;
+            vch = C.st.vch;
           }
           // SetInitialSpinThreshold (Alg. 1 line 3): largest at the front, halving per position
           thr = a.spin_init >> (pos < 31 ? pos : 31);
@@ -694,9 +750,9 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           const u64 start = (u64)cidx * block_elems;
           blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
         }
-        u64 lo = (u64)ch * part_elems + (u64)g * slice_elems;
+        u64 lo = (u64)vch * part_elems + (u64)g * slice_elems;
         u64 hi = lo + slice_elems;
-        const u64 pend = (u64)(ch + 1) * part_elems;
+        const u64 pend = (u64)(vch + 1) * part_elems;
         if (hi > pend) hi = pend;
         if (lo > blen) lo = blen;
         if (hi > blen) hi = blen;
@@ -801,7 +857,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           if (tr) { if (a.trace_on > 1) sw_ts = wall_clock64(); sw_pending = true; }
           have = false;
           if (res == W_STOP) { stop = STOP_ABORT; cmd = CMD_STOP; break; }
-          ++pos;
+          if (scanned) ++rk; else ++pos;
         }
       }
       if (lane == 0) sh.cmd = cmd;

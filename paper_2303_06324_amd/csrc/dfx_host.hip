@@ -160,6 +160,8 @@ int launch_locked(dfx_ctx* c) {
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   a.nwg = c->nwg;
+  a.scan_min = c->cfg.scan_min;
+  a.chan_spread = c->cfg.chan_spread;
   a.epoch = (uint32_t)(c->launches + 1);
   // quit votes and the quit flag belong to one launch
   HIPCHK(c, hipMemsetAsync(c->dev_ctl + DC_QUIT, 0, 2 * sizeof(uint32_t), c->stream));
@@ -252,11 +254,13 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->nslots = 4;
   cfg->slot_bytes = 128u << 10;
   cfg->chan_min_bytes = 16u << 10;
-  cfg->spin_init = 8;
-  cfg->spin_min = 1;
-  cfg->spin_max = 32;
+  cfg->spin_init = 16;
+  cfg->spin_min = 2;
+  cfg->spin_max = 64;
   cfg->spin_boost = 2;
   cfg->fetch_batch = 0;
+  cfg->scan_min = 3;
+  cfg->chan_spread = 1;
   cfg->preempt = 1;
   cfg->watchdog_ms = 10000;
   cfg->quit_idle_us = 2000;
@@ -619,6 +623,7 @@ int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
     out->max_taskq = std::max<uint64_t>(out->max_taskq, s[ST_MAXQ]);
     out->wait_us += (double)s[ST_T_WAIT] * c->tick_us; out->data_us += (double)s[ST_T_DATA] * c->tick_us;
     out->publish_us += (double)s[ST_T_PUB] * c->tick_us;
+    out->scan_skips += s[ST_SCAN_SKIPS];
     wgs.push_back(wg);
     tn.push_back(h[wg].trace_n);
   }

@@ -65,7 +65,7 @@ struct alignas(16) DfxCooked {
   uint8_t nslots, kind, dtype;
   uint8_t bc_pos;        // broadcast: 0 = root, 1 = middle of the chain, 2 = last
   int16_t priority;
-  uint16_t pad;
+  uint16_t vch;          // channel of the collective that this workgroup serves (0 .. nchan-1)
 };
 static_assert(sizeof(DfxCooked) == 96, "DfxCooked must be 96 bytes");
 
@@ -92,7 +92,7 @@ struct alignas(16) DfxWgState {
 };
 
 enum { ST_PREEMPT = 0, ST_LOAD, ST_HIT, ST_SAVE, ST_LAZY, ST_POLLS, ST_PRIMS, ST_SQE, ST_CQE, ST_MAXQ, ST_PASSES, ST_QUITS,
-       ST_T_WAIT, ST_T_DATA, ST_T_PUB, ST_T_SPARE };   // wall-clock ticks, only with trace on
+       ST_T_WAIT, ST_T_DATA, ST_T_PUB, ST_SCAN_SKIPS };   // wall-clock ticks, only with trace on
 
 // dev_ctl words (device memory)
 enum { DC_ABORT = 0, DC_ERR = 1, DC_ERR_WG = 2, DC_QUIT = 3, DC_VOTES = 4, DC_N = 16 };
@@ -113,10 +113,11 @@ struct DfxDaemonArgs {
   uint16_t* taskq_store;    // [nwg][max_colls] device
   uint64_t* trace;          // [nwg][DFX_TRACE_N] device (or null)
   uint32_t nwg;
+  uint32_t scan_min;        // queue length from which a pass starts with a readiness scan (0 = never)
   uint32_t epoch;           // number of this launch (exit SQEs name the launch they end)
   uint32_t R, cmax, max_colls, sq_depth, sq_shift, cq_slots;
   uint32_t spin_init, spin_min, spin_max, spin_boost, preempt;
-  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent;
+  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent, chan_spread;
   uint64_t watchdog_ticks;  // wall-clock ticks; 0 = off
   uint64_t quit_ticks;      // wall-clock ticks; 0 = off
 };

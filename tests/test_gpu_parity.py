@@ -69,12 +69,14 @@ def test_smallest_allreduce_two_ranks():
     _run(_one(wi.AR, wi.F32, 1024, 2), max_channels=4)
 
 
+@pytest.mark.parametrize("spread", [0, 1])
 @pytest.mark.parametrize("orders", list(itertools.product([(0, 1), (1, 0)], repeat=2)))
-def test_config1_circular_wait_all_orders(orders):
+def test_config1_circular_wait_all_orders(orders, spread):
     """Two all-reduces issued in every combination of orders on two ranks; opposite orders are the
-    single-queue deadlock of Sec. 2.3. Integer-valued inputs: sums are exact in any order."""
+    single-queue deadlock of Sec. 2.3 when both share one workgroup (spread=0). Integer-valued
+    inputs: sums are exact in any order."""
     w = wi.config1(*orders)
-    stats = _run(w, max_channels=4, spin_init=200, spin_min=8, spin_max=4000, spin_boost=4)
+    stats = _run(w, max_channels=4, spin_init=200, spin_min=8, spin_max=4000, spin_boost=4, chan_spread=spread)
     from tests import gpu_harness as gh  # noqa: F401
     for ci in range(2):
         sends = wi.all_sends(w, ci)

@@ -27,7 +27,7 @@ def test_negative_control_no_preemption_hits_watchdog():
     import paper_2303_06324_amd as dfx
     w = wi.config1((0, 1), (1, 0))
     dw = gh.DeviceWorkload(w)
-    ctx = dfx.Context(2, gh.make_config(preempt=0, watchdog_ms=300, quit_idle_us=0, max_channels=2))
+    ctx = dfx.Context(2, gh.make_config(preempt=0, watchdog_ms=300, quit_idle_us=0, max_channels=2, chan_spread=0))
     try:
         gh.prepare_all(ctx, w)
         gh.submit_round_robin(ctx, dw)
@@ -44,7 +44,7 @@ def test_negative_control_no_preemption_hits_watchdog():
 def test_same_order_without_preemption_completes():
     from tests import gpu_harness as gh
     w = wi.config1((0, 1), (0, 1))
-    dw, stats, _ = gh.run_workload(w, gh.make_config(preempt=0, watchdog_ms=2000, max_channels=2))
+    dw, stats, _ = gh.run_workload(w, gh.make_config(preempt=0, watchdog_ms=2000, max_channels=2, chan_spread=0))
     for ci in range(2):
         _expect(dw, w, ci)
     assert sum(s["preemptions"] for s in stats) == 0
@@ -159,7 +159,8 @@ def test_sq_backpressure_and_poll_interface():
 def test_stats_are_consistent():
     from tests import gpu_harness as gh
     w = wi.config3(n_buckets=6, bucket_bytes=512 << 10, seed=12)
-    dw, stats, _ = gh.run_workload(w, gh.make_config(spin_init=8, spin_min=1, spin_max=32, spin_boost=2, trace=1))
+    dw, stats, _ = gh.run_workload(w, gh.make_config(spin_init=8, spin_min=1, spin_max=32, spin_boost=2, trace=1,
+                                                      chan_spread=0, scan_min=0))   # shared queues, polled in turn
     for s in stats:
         assert s["cqe_posted"] == 6
         assert s["preemptions"] == s["ctx_saves"] + s["lazy_skips"] or s["ctx_saves"] >= 0
