@@ -79,7 +79,9 @@ typedef struct {
   uint32_t wg_map;         /* 0: workgroup = channel*nranks + rank; 1: workgroup = rank*max_channels + channel */
   uint32_t order_policy;   /* 0 = FIFO ordering, 1 = priority ordering (Sec. 4.3) */
   uint32_t trace;          /* 1 = record context-switch latency samples (two clock reads per switch);
-                              2 = also time the save / load parts and the wait / data / publish phases */
+                              2 = also time the save / load parts and the wait / data / publish phases;
+                              3 = phases as in 2, and the trace holds one sample per executed primitive
+                                  instead of one per switch (see dfx_trace_read) */
   uint32_t fetch_batch;    /* SQEs a workgroup may fetch in a row when its queue is empty or stuck; 0 = all available */
   uint64_t pool_bytes;     /* device memory reserved for connectors of all prepared collectives */
   uint32_t scan_min;       /* a pass over a task queue of at least this many entries starts with a readiness
@@ -202,6 +204,17 @@ int dfx_stats(dfx_ctx* ctx, int rank, dfx_stats_t* out);
 /* Geometry the library chose for a prepared collective (for tests and the bench). */
 int dfx_coll_info(dfx_ctx* ctx, int coll_id, uint32_t* nchan, uint32_t* slot_bytes, uint32_t* rounds,
                   uint32_t* nprim);
+
+/* Raw trace samples of one workgroup (0 <= wg < nranks * max_channels), oldest first while fewer than
+   4096 have been written (a ring afterwards); valid once the daemon has stopped or quit.  With
+   trace = 1 or 2 a sample is one context switch: bits 0-23 total ticks, 24-43 save ticks, 44-63 load
+   ticks.  With trace = 3 a sample is one executed primitive (the breakdown of Sec. 6.3 per
+   workgroup): bits 0-31 low word of the wall clock when its data phase began, 32-47 ticks the data
+   phase took (saturating), 48-59 collective id (low 12 bits), 60-63 index in the primitive sequence
+   (low 4 bits), or 15 for a wait phase that ended in preemption (then the two times are those of
+   the wait); switch-latency statistics are not collected in that mode.  *tick_us: microseconds
+   per tick.  out, tick_us: host.  Returns the number of samples copied, or a negative error. */
+int dfx_trace_read(dfx_ctx* ctx, uint32_t wg, uint64_t* out, uint32_t max, double* tick_us);
 
 /* Milliseconds the last completed daemon launch spent on the GPU (HIP events on the daemon's
    stream), and how many launches have completed; 0 launches => *ms = 0. out pointers: host. */

@@ -75,6 +75,7 @@ def _load() -> C.CDLL:
         "dfx_stats": ([vp, i, C.POINTER(Stats)], i),
         "dfx_coll_info": ([vp, i] + [C.POINTER(C.c_uint32)] * 4, i),
         "dfx_last_launch_ms": ([vp, C.POINTER(C.c_float), C.POINTER(u64)], i),
+        "dfx_trace_read": ([vp, C.c_uint32, C.POINTER(u64), C.c_uint32, C.POINTER(C.c_double)], i),
         "dfx_finalize": ([vp], i),
         "dfx_last_hip_error": ([vp], i),
         "dfx_last_init_error": ([], i),
@@ -169,6 +170,14 @@ class Context:
         if rc != OK:
             raise DfxError(rc, "dfx_last_launch_ms")
         return ms.value, n.value
+
+    def trace_read(self, wg: int, max_samples: int = 4096) -> Tuple[list, float]:
+        buf = (C.c_uint64 * max_samples)()
+        tick = C.c_double()
+        n = _lib.dfx_trace_read(self._h, wg, buf, max_samples, C.byref(tick))
+        if n < 0:
+            raise DfxError(n, "dfx_trace_read")
+        return list(buf[:n]), tick.value
 
     def last_hip_error(self) -> int:
         return _lib.dfx_last_hip_error(self._h)

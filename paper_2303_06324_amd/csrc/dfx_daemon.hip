@@ -452,7 +452,13 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             if (pend_recv) st_agent64(head_in, recvd + 1);
             bump(sh.stat, ST_PRIMS, 1);
             if (a.trace_on > 1) { bump(sh.stat, ST_T_DATA, tm2 - tm1); bump(sh.stat, ST_T_PUB, wall_clock64() - tm2); }
+            if (a.trace_on == 3 && trace) {   // primitive timeline: data-phase start | length | collective | primitive
+              u64 dur = tm2 - tm1;
+              if (dur > 0xffffu) dur = 0xffffu;
+              trace[trace_n % DFX_TRACE_N] = (tm1 & 0xffffffffull) | (dur << 32) | ((u64)(coll & 0xfffu) << 48) | ((u64)(p & 0xfu) << 60);
+            }
           }
+          if (a.trace_on == 3) ++trace_n;
           acted = true;
           if (pend_send) ++sent;
           if (pend_recv) ++recvd;
@@ -518,14 +524,32 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           if (!in_pass) {
             ++iter;
             uint32_t s = STOP_NONE, got = 0;
+            // FIFO ordering (Sec. 4.3): fetch when the queue is empty or a whole pass made no
+            // progress, then keep fetching what is already there (up to fetch_batch); priority
+            // ordering probes the SQ before every pass.
+            const bool want = (qlen == 0) || !pass_progress || a.order_policy == 1 || (burst > 0 && burst < a.fetch_batch);
+            const bool probe = want && qlen < a.max_colls;
+            const bool slow = ((iter & 31u) == 0) || qlen == 0 || !pass_progress;
+            const bool host_look = ((iter & 31u) == 0) || qlen == 0;
+            // the three control words live in different memories; three lanes fetch them at once
+            uint32_t w0 = 0, w1 = 0;
             if (lane == 0) {
-              if (ld_agent32(&a.dev_ctl[DC_ABORT])) s = STOP_ABORT;
-              else if (ld_agent32(&a.dev_ctl[DC_QUIT])) s = STOP_QUIT;
-              if (!s && (((iter & 31u) == 0) || qlen == 0 || !pass_progress)) {
+              const u64 c2 = ld_agent64((const u64*)&a.dev_ctl[DC_ABORT]);   // abort | quit
+              w0 = (uint32_t)c2; w1 = (uint32_t)(c2 >> 32);
+            } else if (lane == 1) {
+              if (probe) w0 = __hip_atomic_load(&sqbase[ri & (D - 1)].e.ready, __ATOMIC_RELAXED, SCOPE_SYSTEM);
+            } else if (lane == 2) {
+              if (host_look) w0 = ld_sys32(&a.host_ctl[HC_ABORT]);
+            }
+            const uint32_t c_abort = __builtin_amdgcn_readlane(w0, 0), c_quit = __builtin_amdgcn_readlane(w1, 0);
+            const uint32_t c_ready = __builtin_amdgcn_readlane(w0, 1), c_habort = __builtin_amdgcn_readlane(w0, 2);
+            if (c_abort || c_habort) s = STOP_ABORT;
+            else if (c_quit) s = STOP_QUIT;
+            if (lane == 0) {
+              if (!s && slow) {
                 const u64 now = wall_clock64();
                 if (acted) { last_act = now; acted = false; }
-                if (ld_sys32(&a.host_ctl[HC_ABORT])) s = STOP_ABORT;
-                else if (a.watchdog_ticks && qlen > 0 && now - last_act > a.watchdog_ticks) {
+                if (a.watchdog_ticks && qlen > 0 && now - last_act > a.watchdog_ticks) {
                   ws->dbg[0] = ((u64)sh.taskq[0] << 32) | qlen; ws->dbg[1] = ri; ws->dbg[2] = now - last_act;
                   raise_error(a, 1u, wg);
                   s = STOP_ABORT;
@@ -548,14 +572,9 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                   }
                 }
               }
-              // FIFO ordering (Sec. 4.3): fetch when the queue is empty or a whole pass made no
-              // progress, then keep fetching what is already there (up to fetch_batch); priority
-              // ordering probes the SQ before every pass.
-              const bool want = (qlen == 0) || !pass_progress || a.order_policy == 1 || (burst > 0 && burst < a.fetch_batch);
-              if (!s && want && qlen < a.max_colls) {
-                DfxSqSlot* e = &sqbase[ri & (D - 1)];
+              if (!s && probe) {
                 const uint32_t gen = (uint32_t)(ri >> a.sq_shift) + 1u;
-                if (__hip_atomic_load(&e->e.ready, __ATOMIC_ACQUIRE, SCOPE_SYSTEM) == gen) got = 1;
+                if (c_ready == gen) got = 1;
               }
             }
             s = bcast0(s);
@@ -766,7 +785,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         if (a.trace_on > 1) tm0 = wall_clock64();
         if (sw_pending) {   // the first poll of the next collective ends the context switch
           const u64 t1 = wall_clock64();
-          if (trace && lane == 0) {
+          if (trace && a.trace_on < 3 && lane == 0) {
             u64 tot = t1 - sw_t0, sv = sw_ts - sw_t0, ldt = sw_le - sw_lb;
             if (a.trace_on < 2) { sv = 0; ldt = 0; }
             if (tot > 0xffffffu) tot = 0xffffffu;
@@ -774,7 +793,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             if (ldt > 0xfffffu) ldt = 0xfffffu;
             trace[trace_n % DFX_TRACE_N] = tot | (sv << 24) | (ldt << 44);
           }
-          ++trace_n;
+          if (a.trace_on < 3) ++trace_n;
           sw_pending = false;
         }
 
@@ -842,6 +861,12 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           // an empty slice is only a handshake: it is published at the top of the loop
         } else {
           // ---- PreemptCollective + SaveCollectiveContext (lazy: only if it progressed)
+          if (a.trace_on == 3 && trace) {   // timeline sample of a wait that ended without the primitive: index 15
+            u64 dur = wall_clock64() - tm0;
+            if (dur > 0xffffu) dur = 0xffffu;
+            if (lane == 0) trace[trace_n % DFX_TRACE_N] = (tm0 & 0xffffffffull) | (dur << 32) | ((u64)(coll & 0xfffu) << 48) | (15ull << 60);
+            ++trace_n;
+          }
           const bool tr = a.trace_on && res == W_TIMEOUT && pos + 1 < qlen;
           if (tr) sw_t0 = wall_clock64();
           if (lane == 0) {

@@ -628,7 +628,7 @@ int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
     tn.push_back(h[wg].trace_n);
   }
   out->launches = c->launches;
-  if (c->trace) {
+  if (c->trace && c->cfg.trace < 3) {
     std::vector<double> tot;
     double sv = 0, ld = 0;
     uint64_t* buf = (uint64_t*)c->pinned_tmp;
@@ -657,6 +657,23 @@ int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
     }
   }
   return DFX_OK;
+}
+
+int dfx_trace_read(dfx_ctx* c, uint32_t wg, uint64_t* out, uint32_t max, double* tick_us) {
+  if (!c || !out || wg >= c->nwg) return DFX_ERR_INVALID_ARG;
+  if (!c->trace) return 0;
+  std::lock_guard<std::mutex> lk(c->launch_mu);
+  DfxWgState* h = (DfxWgState*)c->pinned_tmp;
+  HIPCHK(c, hipMemcpyAsync(h, c->wgstate + wg, sizeof(DfxWgState), hipMemcpyDeviceToHost, c->side));
+  HIPCHK(c, hipStreamSynchronize(c->side));
+  const uint32_t n = std::min<uint32_t>(std::min<uint32_t>(h->trace_n, DFX_TRACE_N), max);
+  if (tick_us) *tick_us = c->tick_us;
+  if (!n) return 0;
+  uint64_t* buf = (uint64_t*)c->pinned_tmp;
+  HIPCHK(c, hipMemcpyAsync(buf, c->trace + (size_t)wg * DFX_TRACE_N, (size_t)n * 8, hipMemcpyDeviceToHost, c->side));
+  HIPCHK(c, hipStreamSynchronize(c->side));
+  memcpy(out, buf, (size_t)n * 8);
+  return (int)n;
 }
 
 int dfx_last_launch_ms(dfx_ctx* c, float* ms, uint64_t* launches_done) {

@@ -95,7 +95,9 @@ enum { ST_PREEMPT = 0, ST_LOAD, ST_HIT, ST_SAVE, ST_LAZY, ST_POLLS, ST_PRIMS, ST
        ST_T_WAIT, ST_T_DATA, ST_T_PUB, ST_SCAN_SKIPS };   // wall-clock ticks, only with trace on
 
 // dev_ctl words (device memory)
-enum { DC_ABORT = 0, DC_ERR = 1, DC_ERR_WG = 2, DC_QUIT = 3, DC_VOTES = 4, DC_N = 16 };
+// (abort and quit share one aligned 64-bit word: the scheduler reads both with one load; the host
+// clears quit and votes, which are adjacent, with one memset)
+enum { DC_ERR = 0, DC_ERR_WG = 1, DC_ABORT = 2, DC_QUIT = 3, DC_VOTES = 4, DC_N = 16 };
 // host_ctl words (host-visible queue memory)
 enum { HC_ABORT = 0, HC_N = 16 };
 

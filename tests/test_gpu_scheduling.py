@@ -214,3 +214,41 @@ def test_stop_with_outstanding_work_and_resume():
             _expect(dw, w, ci)
     finally:
         assert ctx.finalize() == dfx.OK
+
+
+def test_primitive_timeline_trace():
+    """trace = 3: one sample per executed primitive and per wait that ended in preemption; every
+    workgroup that served the collective reports its 2R-1 primitives per slice, in sequence order,
+    with data phases that do not overlap in time."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.Workload("timeline", 8, [wi.CollSpec(0, wi.AR, wi.F32, 1 << 20)], [[0]] * 8, seed=21, cfg=71)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(8, gh.make_config(trace=3, quit_idle_us=0))
+    try:
+        gh.prepare_all(ctx, w)
+        gh.submit_round_robin(ctx, dw)
+        assert ctx.wait_all(20.0) == dfx.OK
+        assert ctx.stop() == dfx.OK
+        _expect(dw, w, 0)
+        info = ctx.coll_info(0)
+        cmax = gh.make_config().max_channels
+        served = 0
+        for wg in range(8 * cmax):
+            samples, tick_us = ctx.trace_read(wg)
+            assert 0.0 < tick_us < 1.0
+            prims = [s for s in samples if (s >> 60) != 15]
+            if not prims:
+                continue
+            served += 1
+            assert len(prims) == info["rounds"] * info["nprim"]
+            assert [s >> 60 for s in prims] == list(range(info["nprim"])) * info["rounds"]
+            assert all(((s >> 48) & 0xfff) == 0 for s in samples)
+            end = None
+            for s in prims:
+                start, dur = s & 0xffffffff, (s >> 32) & 0xffff
+                assert end is None or ((start - end) & 0xffffffff) < (1 << 31)
+                end = (start + dur) & 0xffffffff
+        assert served == 8 * info["nchan"]
+    finally:
+        assert ctx.finalize() == dfx.OK
