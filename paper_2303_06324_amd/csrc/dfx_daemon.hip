@@ -11,19 +11,19 @@
 // counters; a primitive touches nothing before both its conditions hold (Sec. 4.1, 4.5).
 //
 // Memory-model rules used here (AMDGPU, one agent with one L2 per XCD), two connector modes:
-//   fenced (fifo_coherent = 0)
-//     producer: data stores -> every wave drains its stores -> workgroup barrier -> thread 0:
-//               agent-scope release fence -> relaxed agent-scope store of the counter;
-//     consumer: relaxed agent-scope load of the counter (lane 0/1 of wave 0) -> workgroup
-//               barrier -> agent-scope acquire fence in every wave -> data loads.
-//   device-coherent accesses (fifo_coherent = 1)
+//   device-coherent accesses (fifo_coherent = 1, the default)
 //     connector slots are only ever touched by sc1 (device-scope) buffer loads/stores, which
-//     do not linger in the per-XCD caches; the producer drains them (vmcnt(0)) before the
-//     barrier and thread 0 then stores the counter with an sc1 store; the consumer polls the
-//     counter with sc1 loads and reads the slot with sc1 loads.  No bulk L2 write-back or
+//     do not linger in the per-XCD caches; every mover wave drains its stores (vmcnt(0)) and
+//     counts itself done in LDS; the wave that completes the count raises the connector
+//     counter with a device-scope atomic; the consumer's scheduler wave polls the counter with
+//     sc1 loads and its movers read the slot with sc1 loads.  No bulk L2 write-back or
 //     invalidate per slice.  User buffers stay ordinary cached memory: the send buffer is made
 //     visible by the system-scope acquire at SQE fetch, the recv buffer is flushed by the
 //     system-scope release before the completion counter.
+//   fenced (fifo_coherent = 0, kept for comparison)
+//     connector slots are ordinary cached memory; the publishing wave issues an agent-scope
+//     release fence (L2 write-back) before it raises the counter, and every mover wave an
+//     agent-scope acquire fence (invalidate) before its loads of a slot.
 //   SQ / CQ / host control words are host-visible and use system scope.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -38,7 +38,7 @@ constexpr int NT = DFX_WG_THREADS;
 #ifndef DFX_SOLO_BYTES
 #define DFX_SOLO_BYTES 8192
 #endif
-// slices up to this size are moved by the scheduler wave alone (no barrier, no hand-off)
+// slices up to this size are moved by the scheduler wave alone (no hand-off to the movers)
 constexpr uint32_t SOLO_BYTES = DFX_SOLO_BYTES;
 #ifndef DFX_UNROLL
 #define DFX_UNROLL 8
@@ -66,14 +66,6 @@ __device__ __forceinline__ void fence_acquire_agent() { __builtin_amdgcn_fence(_
 __device__ __forceinline__ void fence_release_agent() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); __builtin_amdgcn_s_waitcnt(0); }
 __device__ __forceinline__ void fence_acquire_system() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, ""); }
 __device__ __forceinline__ void fence_release_system() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, ""); __builtin_amdgcn_s_waitcnt(0); }
-
-// Every wave waits until its own global stores (and loads) have been performed, then the
-// workgroup meets: afterwards thread 0 may publish on behalf of all waves.
-__device__ __forceinline__ void drain_and_barrier() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0) expcnt(0) lgkmcnt(0)
-  __syncthreads();
-}
 
 // ------------------------------------------------------------------------------------------
 // reduce: one hop a (+) b in the storage dtype (one rounding per hop)
@@ -180,7 +172,7 @@ struct Slot {   // one connector slot seen through a buffer resource
 template <int DT, int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT, int NTH>
 __device__ __forceinline__ void move_slice(const void* fin_p, const char* __restrict__ sb, char* __restrict__ rb,
                                            void* fout_p, uint32_t bytes, uint32_t tid) {
-  constexpr int NT = NTH;   // threads that share the slice: the whole workgroup, or the scheduler wave alone
+  constexpr int NT = NTH;   // threads that share the slice: the mover waves, or the scheduler wave alone
   static_assert(FIN || SB, "a primitive has a source");
   static_assert(RB || FOUT, "a primitive has a destination");
   const Slot<AIN> fin(fin_p, FIN ? bytes : 0);
@@ -302,9 +294,20 @@ __device__ __forceinline__ void run_prim(int dtype, const void* fin, const char*
 // ------------------------------------------------------------------------------------------
 // LDS state of one workgroup
 // ------------------------------------------------------------------------------------------
-struct Job {                         // what the scheduler wave hands to all waves for one slice
+struct Job {                         // what the scheduler wave hands to the mover waves for one slice
   const void* fin; const char* sb; char* rb; void* fout;
   uint32_t bytes; int dtype;
+  uint32_t coll, prim;               // for the timeline trace only
+};
+
+// What publishing and retiring a posted job needs.  Written by the scheduler when it posts the
+// job; read by the mover wave that finishes the job last (counter updates) and by the scheduler
+// when it retires the job (statistics, completion).
+struct Flight {
+  u64* tail_out; u64* head_in;       // counters to raise (null = that side is not used)
+  u64 sent_new, recvd_new;           // their new values
+  uint32_t last;                     // the primitive ends this workgroup's share of the invocation
+  uint32_t coll, seq, nchan;
 };
 
 struct Shared {
@@ -312,15 +315,18 @@ struct Shared {
   DfxCtxEntry slot[DFX_CTX_SLOTS];   // active context slots (Sec. 5, direct-mapped)
   uint32_t slot_tag[DFX_CTX_SLOTS];
   DfxStatic sqe;                     // SQE being fetched
-  Job job;
-  uint32_t cmd;                      // scheduler wave -> workgroup: CMD_MOVE or CMD_STOP
+  Job job[2];                        // posted jobs, indexed by job number & 1
+  Flight fl[2];
+  uint32_t job_seq;                  // jobs posted so far (scheduler -> movers)
+  uint32_t wave_done[2];             // mover waves that have finished job k, at index k & 1
+  uint32_t jobs_done;                // jobs finished and published (movers -> scheduler)
+  uint32_t leave;                    // scheduler -> movers: no more jobs
+  uint32_t trace_n;                  // trace samples written (monotone)
   uint32_t qlen_out;                 // queue length handed to all waves when leaving
   u64 stat[DFX_NSTAT];               // counters (LDS atomics without return: one instruction, no wait)
   uint16_t rlist[DFX_MAX_COLLS];     // queue positions the readiness scan found runnable, ascending
   uint16_t taskq[DFX_MAX_COLLS];     // task queue (Sec. 4.2 (1))
 };
-
-enum { CMD_NONE = 0, CMD_MOVE = 1, CMD_STOP = 2 };
 
 // primitive descriptor for (kind, position p in the sequence); the ring-chunk index travels in
 // the dynamic context and is stepped by next_cidx, so nothing here divides
@@ -364,16 +370,47 @@ __device__ __forceinline__ void bump(u64* stat, int i, u64 v) {
 
 __device__ __forceinline__ uint32_t bcast0(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
+// LDS words shared between the scheduler and the mover waves
+__device__ __forceinline__ uint32_t lds_ld(const uint32_t* p) { return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP); }
+__device__ __forceinline__ void lds_st(uint32_t* p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP); }
+
+// Raise a connector counter.  A maximum instead of a store: the waves that publish two
+// consecutive jobs are different ones, and their updates may reach memory in either order.
+__device__ __forceinline__ void raise_counter(u64* p, u64 v) {
+  (void)__hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, SCOPE_AGENT);
+}
+
+// one trace sample; the index comes from an LDS counter that both kinds of wave use
+__device__ __forceinline__ void trace_put(u64* trace, uint32_t* trace_n, u64 v) {
+  const uint32_t i = __hip_atomic_fetch_add(trace_n, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  trace[i % DFX_TRACE_N] = v;
+}
+
+__device__ __forceinline__ u64 timeline_sample(u64 t0, u64 t1, uint32_t coll, uint32_t prim) {
+  u64 dur = t1 - t0;
+  if (dur > 0xffffu) dur = 0xffffu;
+  return (t0 & 0xffffffffull) | (dur << 32) | ((u64)(coll & 0xfffu) << 48) | ((u64)(prim & 0xfu) << 60);
+}
+
 }  // namespace
 
-// Structure of a workgroup: wave 0 is the SCHEDULER, all four waves are MOVERS.
+// Structure of a workgroup: wave 0 is the SCHEDULER, waves 1..4 are the MOVERS.
+//
 // The scheduler wave runs Alg. 1 on its own -- control checks, SQE fetch, queue walk, context
-// load, bounded polling, preemption, lazy save, completion -- without any workgroup barrier;
-// its state lives in its registers, the task queue and context slots in LDS.  Only when a poll
-// has succeeded does it post a job (the slice's four pointers) in LDS and meet the other waves
-// at a barrier; all waves move the slice, drain their stores and meet again; the scheduler
-// then publishes the connector counters and goes on.  A context switch therefore costs no
-// barrier at all, a primitive costs two.
+// load, bounded polling, preemption, lazy save, completion -- with its state in its registers
+// and the task queue and context slots in LDS.  When a primitive's wait phase has succeeded it
+// claims the connector slots (its private counters advance), posts the slice as a job in LDS and
+// goes straight on to the wait phase of whatever comes next, while the movers carry the data.
+// Up to two jobs are posted at a time, so the movers run from one slice into the next without
+// waiting for the scheduler, and everything the scheduler does -- polling flags that live in
+// HBM, scanning the queue, switching contexts -- overlaps with data movement.
+//
+// A mover wave takes the jobs in order; after its part of a slice it drains its stores and
+// counts itself done in LDS.  The wave that completes the count raises the connector counters
+// of that job (the data of all waves is then in memory) and reports the job finished; the
+// scheduler retires finished jobs in order (statistics; for the last primitive of an invocation
+// the completion counter and the CQE).  No workgroup barrier is used after start-up; short
+// slices are moved by the scheduler wave itself once the movers are idle.
 extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(DfxDaemonArgs kargs) {
   __shared__ Shared sh;
   // The arguments are read from an LDS copy: kept in scalar registers for the whole kernel they
@@ -389,7 +426,6 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   uint32_t rank, ch;
   if (a.wg_map == 0) { rank = wg % a.R; ch = wg / a.R; }
   else { rank = wg / a.cmax; ch = wg % a.cmax; }
-  const int R = (int)a.R;
   const uint32_t D = a.sq_depth;
   const bool coh = a.fifo_coherent != 0;
 
@@ -403,520 +439,612 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   // ---- restore the workgroup state left by the previous launch (Sec. 4.5)
   u64 ri = ws->read_index;
   uint32_t qlen = ws->qlen;
-  uint32_t trace_n = ws->trace_n;
   for (uint32_t i = tid; i < qlen; i += NT) sh.taskq[i] = qstore[i];
   if (tid < DFX_CTX_SLOTS) sh.slot_tag[tid] = 0xffffffffu;
   if (tid < DFX_NSTAT) sh.stat[tid] = ws->stat[tid];
-  if (tid == 0) sh.cmd = CMD_NONE;
+  if (tid == 0) {
+    sh.job_seq = 0; sh.wave_done[0] = 0; sh.wave_done[1] = 0; sh.jobs_done = 0; sh.leave = 0;
+    sh.trace_n = ws->trace_n;
+  }
   __syncthreads();
 
-  // ---- scheduler state (registers of wave 0; the other waves never look at it)
-  // start values of the ring-chunk index of a fresh sequence (see DfxDyn.cidx)
-  const uint32_t cidx0_reduce = (rank + a.R - 1) % a.R;   // all-reduce / reduce-scatter: chunk rank-1
-  u64 last_act = wall_clock64();
-  bool acted = true, voted = false;
-  uint32_t iter = 0, idle = 0, burst = 0;
-  bool in_pass = false, pass_progress = false, scanned = false;
-  uint32_t nready = 0, rk = 0, removed = 0;   // readiness list of the pass: length, cursor, entries completed
-  uint32_t pos = 0;
   uint32_t stop = STOP_NONE;
-  // context-switch sample in flight: t0 = abort decision, ts = after the save, lb/le = load
-  u64 sw_t0 = 0, sw_ts = 0, sw_lb = 0, sw_le = 0;
-  bool sw_pending = false;
-  // the collective in the active slot
-  bool have = false;
-  uint32_t coll = 0, sl = 0, nprim = 0, rounds = 0, K = 0, nchan = 0, slot_bytes = 0, slice_elems = 0, eb = 4;
-  uint32_t g = 0, p = 0, preempted_before = 0, seq = 0;
-  int kind = 0, dtype = 0;
-  uint32_t bc_pos = 0, cidx = 0, vch = 0;
-  u64 count = 0, block_elems = 0, part_elems = 0, sent = 0, recvd = 0, thr = 0;
-  const char* sendbuf = nullptr;
-  char* recvbuf = nullptr;
-  u64 *tail_out = nullptr, *head_out = nullptr, *tail_in = nullptr, *head_in = nullptr;
-  uint8_t *fifo_out = nullptr, *fifo_in = nullptr;
-  bool progressed = false;
-  // a slice that has been handed to the movers and still has to be published
-  bool pending_pub = false, pend_send = false, pend_recv = false;
-  u64 tm1 = 0, tm2 = 0;
 
-  for (;;) {
-    if (sched) {
-      uint32_t cmd = CMD_NONE;
-      while (cmd == CMD_NONE) {
-        // ================= publish the slice the movers have just finished =================
-        if (pending_pub) {
-          pending_pub = false;
-          if (lane == 0) {
-            if (!coh) fence_release_agent();
-            if (pend_send) st_agent64(tail_out, sent + 1);
-            if (pend_recv) st_agent64(head_in, recvd + 1);
-            bump(sh.stat, ST_PRIMS, 1);
-            if (a.trace_on > 1) { bump(sh.stat, ST_T_DATA, tm2 - tm1); bump(sh.stat, ST_T_PUB, wall_clock64() - tm2); }
-            if (a.trace_on == 3 && trace) {   // primitive timeline: data-phase start | length | collective | primitive
-              u64 dur = tm2 - tm1;
-              if (dur > 0xffffu) dur = 0xffffu;
-              trace[trace_n % DFX_TRACE_N] = (tm1 & 0xffffffffull) | (dur << 32) | ((u64)(coll & 0xfffu) << 48) | ((u64)(p & 0xfu) << 60);
-            }
-          }
-          if (a.trace_on == 3) ++trace_n;
-          acted = true;
-          if (pend_send) ++sent;
-          if (pend_recv) ++recvd;
-          // next primitive: the chunk index steps down the ring; a new round starts over
-          cidx = (cidx == 0) ? a.R - 1 : cidx - 1;
-          if (++p == nprim) {
-            p = 0; ++g;
-            cidx = (kind == KIND_AG) ? rank : ((kind == KIND_BC || a.R == 1) ? 0u : cidx0_reduce);
-          }
-          if (kind == KIND_BC) cidx = 0;
-          progressed = true;
-          pass_progress = true;
-          // AdaptivelyAdjustSpinThreshold (Alg. 1 line 9)
-          thr *= a.spin_boost;
-          if (thr > a.spin_max) thr = a.spin_max;
-          if (g == rounds) {
-            // ---- CollectiveSuccess -> completion counter -> maybe SendCQE (Sec. 5)
-            if (lane == 0) {
-              DfxDyn d; d.round = 0; d.prim = 0; d.sent = sent; d.recvd = recvd; d.preempted = 0; d.cidx = 0;
-              sh.slot[sl].dyn = d;
-              myctx[coll].dyn = d;
-              fence_release_system();   // results in the recv buffer are visible to host and later kernels
-              uint32_t* dc = &a.done_cnt[(size_t)rank * a.max_colls + coll];
-              const uint32_t old = __hip_atomic_fetch_add(dc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
-              if (old + 1 == nchan) {
-                __hip_atomic_store(dc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
-                const u64 v = (1ull << 63) | ((u64)(seq & 0x7fffffffu) << 32) | coll;
-                const uint32_t t = __hip_atomic_fetch_add(&a.cq_ticket[rank], 1u, __ATOMIC_RELAXED, SCOPE_AGENT);
-                uint32_t k = 0;
-                for (;;) {   // optimized CQ (Sec. 5): one CAS of the id into a writable slot
-                  u64 expected = 0;
-                  if (__hip_atomic_compare_exchange_strong(&cqbase[(t + k) % a.cq_slots], &expected, v, __ATOMIC_RELEASE,
-                                                           __ATOMIC_RELAXED, SCOPE_SYSTEM))
-                    break;
-                  ++k;
-                  if ((k % a.cq_slots) == 0) {
-                    if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) break;
-                    __builtin_amdgcn_s_sleep(50);
-                  }
-                }
-                bump(sh.stat, ST_CQE, 1);
-              }
-            }
-            // the entry leaves the queue; later entries move up, the position stays (Sec. 4.3)
-            --qlen;
-            for (uint32_t base = pos; base < qlen; base += 64) {
-              const uint32_t i = base + lane;
-              uint16_t v = 0;
-              if (i < qlen) v = sh.taskq[i + 1];
-              __builtin_amdgcn_wave_barrier();
-              if (i < qlen) sh.taskq[i] = v;
-              __builtin_amdgcn_wave_barrier();
-            }
-            have = false;
-            sw_pending = false;
-            if (scanned) { ++rk; ++removed; }
-          }
-          continue;
-        }
-
-        // ================= no collective in hand: control check, fetch, next queue entry =================
-        if (!have) {
-          if (!in_pass) {
-            ++iter;
-            uint32_t s = STOP_NONE, got = 0;
-            // FIFO ordering (Sec. 4.3): fetch when the queue is empty or a whole pass made no
-            // progress, then keep fetching what is already there (up to fetch_batch); priority
-            // ordering probes the SQ before every pass.
-            const bool want = (qlen == 0) || !pass_progress || a.order_policy == 1 || (burst > 0 && burst < a.fetch_batch);
-            const bool probe = want && qlen < a.max_colls;
-            const bool slow = ((iter & 31u) == 0) || qlen == 0 || !pass_progress;
-            const bool host_look = ((iter & 31u) == 0) || qlen == 0;
-            // the three control words live in different memories; three lanes fetch them at once
-            uint32_t w0 = 0, w1 = 0;
-            if (lane == 0) {
-              const u64 c2 = ld_agent64((const u64*)&a.dev_ctl[DC_ABORT]);   // abort | quit
-              w0 = (uint32_t)c2; w1 = (uint32_t)(c2 >> 32);
-            } else if (lane == 1) {
-              if (probe) w0 = __hip_atomic_load(&sqbase[ri & (D - 1)].e.ready, __ATOMIC_RELAXED, SCOPE_SYSTEM);
-            } else if (lane == 2) {
-              if (host_look) w0 = ld_sys32(&a.host_ctl[HC_ABORT]);
-            }
-            const uint32_t c_abort = __builtin_amdgcn_readlane(w0, 0), c_quit = __builtin_amdgcn_readlane(w1, 0);
-            const uint32_t c_ready = __builtin_amdgcn_readlane(w0, 1), c_habort = __builtin_amdgcn_readlane(w0, 2);
-            if (c_abort || c_habort) s = STOP_ABORT;
-            else if (c_quit) s = STOP_QUIT;
-            if (lane == 0) {
-              if (!s && slow) {
-                const u64 now = wall_clock64();
-                if (acted) { last_act = now; acted = false; }
-                if (a.watchdog_ticks && qlen > 0 && now - last_act > a.watchdog_ticks) {
-                  ws->dbg[0] = ((u64)sh.taskq[0] << 32) | qlen; ws->dbg[1] = ri; ws->dbg[2] = now - last_act;
-                  raise_error(a, 1u, wg);
-                  s = STOP_ABORT;
-                } else if (a.quit_ticks) {
-                  // Voluntary quit (Sec. 4.4).  Every workgroup has duties towards the others (each
-                  // must read every SQE of its rank before the slot is reusable), so the grid leaves
-                  // as a whole: a workgroup that has been idle or stuck for the quit period casts a
-                  // vote and keeps running; it withdraws the vote when it becomes active again; the
-                  // vote that completes the set raises the quit flag, which everybody obeys.
-                  const bool tired = now - last_act > a.quit_ticks;
-                  if (tired && !voted) {
-                    voted = true;
-                    if (__hip_atomic_fetch_add(&a.dev_ctl[DC_VOTES], 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT) + 1 == a.nwg) {
-                      __hip_atomic_store(&a.dev_ctl[DC_QUIT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
-                      s = STOP_QUIT;
-                    }
-                  } else if (!tired && voted) {
-                    voted = false;
-                    __hip_atomic_fetch_sub(&a.dev_ctl[DC_VOTES], 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
-                  }
-                }
-              }
-              if (!s && probe) {
-                const uint32_t gen = (uint32_t)(ri >> a.sq_shift) + 1u;
-                if (c_ready == gen) got = 1;
-              }
-            }
-            s = bcast0(s);
-            got = bcast0(got);
-            if (s) { stop = s; cmd = CMD_STOP; break; }
-
-            // ---- FetchSQE (Alg. 1 line 2)
-            if (got) {
-              DfxSqSlot* e = &sqbase[ri & (D - 1)];
-              // the submitter wrote the send buffer before the SQE: drop what this CU / XCD cached
-              fence_acquire_system();
-              if (lane < 6) ((uint4*)&sh.sqe)[lane] = ((const uint4*)&e->e)[lane];
-              __builtin_amdgcn_wave_barrier();
-              const uint32_t c_id = sh.sqe.coll_id;
-              const uint32_t flags = sh.sqe.flags;
-              // an exit SQE ends the launch it was posted for; one left over from an earlier launch
-              // (some workgroups had already gone when it arrived) is consumed and ignored
-              const bool is_exit_sqe = (flags & DFX_SQE_EXIT) != 0;
-              const bool is_exit = is_exit_sqe && sh.sqe.seq == a.epoch;
-              // A collective with fewer channels than the grid has per rank starts at workgroup
-              // (coll_id * nchan) mod cmax, so that many small collectives spread over the rank's
-              // workgroups instead of queueing on the first ones; every rank derives the same
-              // start from the id, which keeps both ends of a connector on the same channel.
-              uint32_t my_vch = ch;
-              if (a.chan_spread && !is_exit_sqe && sh.sqe.nchan < a.cmax)
-                my_vch = (ch + a.cmax - (c_id * sh.sqe.nchan) % a.cmax) % a.cmax;
-              const bool mine = !is_exit_sqe && my_vch < sh.sqe.nchan && c_id < a.max_colls;
-              if (mine) {
-                // cook the static context of this invocation into the context buffer (addresses
-                // resolved once, here); restart the sequence, keep the monotone connector counters
-                if (lane == 0) {
-                  const DfxStatic& q = sh.sqe;
-                  DfxCooked k;
-                  k.sendbuf = q.sendbuf; k.recvbuf = q.recvbuf; k.count = q.count;
-                  k.block_elems = q.block_elems; k.part_elems = q.part_elems;
-                  uint8_t* conn = a.pool + q.conn_off;   // flags first, then slots
-                  const uint32_t e_out = rank, e_in = (rank + a.R - 1) % a.R;
-                  const size_t fo = (size_t)e_out * q.nchan + my_vch, fi = (size_t)e_in * q.nchan + my_vch;
-                  uint8_t* slots = conn + (size_t)a.R * q.nchan * DFX_FLAG_STRIDE;
-                  k.flags_out = (uint64_t)(conn + fo * DFX_FLAG_STRIDE);
-                  k.flags_in = (uint64_t)(conn + fi * DFX_FLAG_STRIDE);
-                  k.fifo_out = (uint64_t)(slots + fo * q.nslots * q.slot_bytes);
-                  k.fifo_in = (uint64_t)(slots + fi * q.nslots * q.slot_bytes);
-                  k.slice_elems = q.slice_elems; k.rounds = q.rounds; k.seq = q.seq;
-                  k.nprim = (uint16_t)q.nprim; k.nchan = q.nchan;
-                  k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = q.dtype;
-                  const uint32_t bpos = (rank + a.R - q.root) % a.R;
-                  k.bc_pos = bpos == 0 ? 0 : (bpos == a.R - 1 ? 2 : 1);
-                  k.priority = q.priority; k.vch = (uint16_t)my_vch;
-                  myctx[c_id].st = k;
-                  DfxDyn* dy = &myctx[c_id].dyn;
-                  dy->round = 0; dy->prim = 0; dy->preempted = 0;
-                  dy->cidx = (q.kind == KIND_AG) ? rank : ((q.kind == KIND_BC || a.R == 1) ? 0u : cidx0_reduce);
-                  // FIFO ordering: append; priority ordering: keep the queue sorted (stable)
-                  uint32_t at = qlen;
-                  if (a.order_policy == 1) {
-                    const int16_t pr = q.priority;
-                    while (at > 0 && myctx[sh.taskq[at - 1]].st.priority < pr) { sh.taskq[at] = sh.taskq[at - 1]; --at; }
-                  }
-                  sh.taskq[at] = (uint16_t)c_id;
-                  if (sh.slot_tag[c_id % DFX_CTX_SLOTS] == c_id) sh.slot_tag[c_id % DFX_CTX_SLOTS] = 0xffffffffu;
-                }
-                ++qlen;
-                if (lane == 0) __hip_atomic_fetch_max(&sh.stat[ST_MAXQ], (u64)qlen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-              }
-              if (lane == 0) {
-                // every workgroup of the rank reads every SQE; the last reader frees the slot (Sec. 5)
-                uint32_t* rc = &a.sq_readers[(size_t)rank * D + (ri & (D - 1))];
-                const uint32_t old = __hip_atomic_fetch_add(rc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
-                if (old + 1 == a.cmax) {
-                  __hip_atomic_store(rc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
-                  __hip_atomic_store(&e->e.ready, 0u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
-                }
-                bump(sh.stat, ST_SQE, 1);
-              }
-              __builtin_amdgcn_wave_barrier();
-              acted = true;
-              sw_pending = false;
-              ++ri;
-              if (is_exit) {
-                // the whole grid leaves (every workgroup has reader duties towards its rank's SQ)
-                if (lane == 0) __hip_atomic_store(&a.dev_ctl[DC_QUIT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
-                stop = STOP_EXIT; cmd = CMD_STOP; break;
-              }
-              ++burst;
-              idle = 0;
-              continue;               // probe the SQ again before walking the queue
-            }
-            burst = 0;
-            if (qlen == 0) {
-              // idle: back off the SQ probe (it may cross PCIe)
-              ++idle;
-              if (idle < 16) __builtin_amdgcn_s_sleep(8);
-              else if (idle < 64) __builtin_amdgcn_s_sleep(32);
-              else __builtin_amdgcn_s_sleep(127);
-              continue;
-            }
-            idle = 0;
-            // ---- start one pass over the task queue (Alg. 1 lines 4-19)
-            in_pass = true;
-            pass_progress = false;
-            pos = 0;
-            if (lane == 0) bump(sh.stat, ST_PASSES, 1);
-            // ---- readiness scan: 64 queue entries per step, one per lane.  Each lane reads the
-            // saved context of its entry, works out which connector sides its next primitive
-            // needs, loads those counters and votes; the runnable positions are compacted into a list
-            // (ballot + popcount) and the pass visits only those: entries whose next
-            // primitive can run (the conditions are monotone: only this workgroup consumes its recv
-            // side and fills its send side, so "ready" stays true until it acts).  A queue of a
-            // thousand stuck collectives costs sixteen memory round trips instead of a thousand
-            // context loads and bounded spins.
-            scanned = a.scan_min && qlen >= a.scan_min;
-            if (scanned) {
-              nready = 0; rk = 0; removed = 0;
-              for (uint32_t base = 0; base < qlen; base += 64) {
-                const uint32_t i = base + lane;
-                bool rdy = false;
-                if (i < qlen) {
-                  const uint4* e = (const uint4*)&myctx[sh.taskq[i]];
-                  const uint4 fl = e[2];    // bytes 32..47: part_elems | flags_out
-                  const uint4 fi = e[3];    // bytes 48..63: flags_in | fifo_out
-                  const uint4 ge = e[5];    // bytes 80..95: seq | nprim,nchan | nslots,kind,dtype,bc_pos | priority
-                  const uint4 d0 = e[6];    // dyn: round | prim | sent
-                  const uint4 d1 = e[7];    // dyn: recvd | preempted | cidx
-                  const Prim pq = make_prim((int)((ge.z >> 8) & 0xffu), a.R, ge.z >> 24, d0.y);
-                  const u64 f_out = ((u64)fl.w << 32) | fl.z, f_in = ((u64)fi.y << 32) | fi.x;
-                  const u64 e_sent = ((u64)d0.w << 32) | d0.z, e_recvd = ((u64)d1.y << 32) | d1.x;
-                  bool okr = true, oks = true;
-                  if (pq.recv) okr = ld_agent64((const u64*)f_in) > e_recvd;
-                  if (pq.send) oks = (e_sent - ld_agent64((const u64*)f_out + 8)) < (u64)(ge.z & 0xffu);
-                  rdy = okr && oks;
-                }
-                const u64 mask = __ballot(rdy);
-                if (rdy) sh.rlist[nready + (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull))] = (uint16_t)i;
-                nready += (uint32_t)__builtin_popcountll(mask);
-              }
-              __builtin_amdgcn_wave_barrier();
-              if (lane == 0) { bump(sh.stat, ST_POLLS, (qlen + 63) / 64); bump(sh.stat, ST_SCAN_SKIPS, qlen - nready); }
-              if (nready == 0) {           // nothing can run: the pass is over before it began
-                in_pass = false;
-                __builtin_amdgcn_s_sleep(4);
-                continue;
-              }
-            }
-          }
-          if (scanned) {
-            // entries completed earlier in this pass moved the later ones up by one each
-            if (rk >= nready) { in_pass = false; continue; }
-            pos = (uint32_t)sh.rlist[rk] - removed;
-          } else if (pos >= qlen) { in_pass = false; continue; }
-
-          // ---- LoadCollectiveContext: HBM context buffer -> LDS slot, 8 lanes x 16 bytes
-          coll = sh.taskq[pos];
-          sl = coll % DFX_CTX_SLOTS;
-          if (sw_pending && a.trace_on > 1) sw_lb = wall_clock64();
-          if (sh.slot_tag[sl] != coll) {
-            if (lane < 8) ((uint4*)&sh.slot[sl])[lane] = ((const uint4*)&myctx[coll])[lane];
-            if (lane == 0) { sh.slot_tag[sl] = coll; bump(sh.stat, ST_LOAD, 1); }
-            __builtin_amdgcn_wave_barrier();
-          } else if (lane == 0) bump(sh.stat, ST_HIT, 1);
-          if (sw_pending && a.trace_on > 1) sw_le = wall_clock64();
-          {
-            const DfxCtxEntry& C = sh.slot[sl];
-            kind = C.st.kind; dtype = C.st.dtype; bc_pos = C.st.bc_pos;
-            eb = (dtype == DT_F32 || dtype == DT_I32) ? 4u : 2u;
-            nprim = C.st.nprim; rounds = C.st.rounds; K = C.st.nslots; nchan = C.st.nchan;
-            slice_elems = C.st.slice_elems; slot_bytes = slice_elems * eb; seq = C.st.seq;
-            count = C.st.count; block_elems = C.st.block_elems; part_elems = C.st.part_elems;
-            sendbuf = (const char*)C.st.sendbuf;
-            recvbuf = (char*)C.st.recvbuf;
-            tail_out = (u64*)C.st.flags_out; head_out = tail_out + 8;
-            tail_in = (u64*)C.st.flags_in; head_in = tail_in + 8;
-            fifo_out = (uint8_t*)C.st.fifo_out;
-            fifo_in = (uint8_t*)C.st.fifo_in;
-            g = C.dyn.round; p = C.dyn.prim; sent = C.dyn.sent; recvd = C.dyn.recvd; cidx = C.dyn.cidx;
-            preempted_before = C.dyn.preempted;
-            vch = C.st.vch;
-          }
-          // SetInitialSpinThreshold (Alg. 1 line 3): largest at the front, halving per position
-          thr = a.spin_init >> (pos < 31 ? pos : 31);
-          if (thr < a.spin_min) thr = a.spin_min;
-          progressed = false;
-          have = true;
-        }
-
-        // ================= next primitive of the collective in hand =================
-        const Prim q = make_prim(kind, a.R, bc_pos, p);
-        // slice geometry (elements relative to the block, clipped to the block's true length)
-        const bool ring_chunks = (kind == KIND_AR && a.R > 1);
-        u64 blen = count;
-        if (ring_chunks) {
-          const u64 start = (u64)cidx * block_elems;
-          blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
-        }
-        u64 lo = (u64)vch * part_elems + (u64)g * slice_elems;
-        u64 hi = lo + slice_elems;
-        const u64 pend = (u64)(vch + 1) * part_elems;
-        if (hi > pend) hi = pend;
-        if (lo > blen) lo = blen;
-        if (hi > blen) hi = blen;
-        const uint32_t bytes = (uint32_t)(hi - lo) * eb;
-        u64 soff = lo, doff = lo;   // element offsets in the send / recv buffer
-        if (ring_chunks) { soff += (u64)cidx * block_elems; doff = soff; }
-        else if (kind == KIND_RS) soff += (u64)cidx * count;
-        else if (kind == KIND_AG) doff += (u64)cidx * count;
-
-        u64 tm0 = 0;
-        if (a.trace_on > 1) tm0 = wall_clock64();
-        if (sw_pending) {   // the first poll of the next collective ends the context switch
-          const u64 t1 = wall_clock64();
-          if (trace && a.trace_on < 3 && lane == 0) {
-            u64 tot = t1 - sw_t0, sv = sw_ts - sw_t0, ldt = sw_le - sw_lb;
-            if (a.trace_on < 2) { sv = 0; ldt = 0; }
-            if (tot > 0xffffffu) tot = 0xffffffu;
-            if (sv > 0xfffffu) sv = 0xfffffu;
-            if (ldt > 0xfffffu) ldt = 0xfffffu;
-            trace[trace_n % DFX_TRACE_N] = tot | (sv << 24) | (ldt << 44);
-          }
-          if (a.trace_on < 3) ++trace_n;
-          sw_pending = false;
-        }
-
-        // ---- wait phase: lane 0 polls the recv side, lane 1 the send side (Sec. 4.2 (3))
-        uint32_t res = W_OK;
-        if (q.recv || q.send) {
-          u64 n = 0;
-          for (;;) {
-            bool ok = true;
-            if (lane == 0 && q.recv) ok = ld_agent64(tail_in) > recvd;
-            if (lane == 1 && q.send) ok = (sent - ld_agent64(head_out)) < (u64)K;
-            ++n;
-            if (__ballot(!ok) == 0) break;
-            if (a.preempt && n >= thr) { res = W_TIMEOUT; break; }
-            if ((n & 255u) == 0) {
-              uint32_t s = 0;
-              if (lane == 0) {
-                if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) s = 1;
-                else if (a.watchdog_ticks) {
-                  const u64 now = wall_clock64();
-                  if (acted) { last_act = now; acted = false; }
-                  if (now - last_act > a.watchdog_ticks) {
-                    ws->dbg[0] = ((u64)coll << 32) | qlen; ws->dbg[1] = ((u64)g << 32) | p; ws->dbg[2] = sent; ws->dbg[3] = recvd;
-                    ws->dbg[4] = ld_agent64(tail_in); ws->dbg[5] = ld_agent64(head_out); ws->dbg[6] = ri; ws->dbg[7] = now - last_act;
-                    raise_error(a, 2u, wg);
-                    s = 1;
-                  }
-                }
-              }
-              if (bcast0(s)) { res = W_STOP; break; }
-            }
-            __builtin_amdgcn_s_sleep(1);
-          }
-          if (lane == 0) bump(sh.stat, ST_POLLS, n);
-        }
-
-        if (res == W_OK) {
-          pend_send = q.send;
-          pend_recv = q.recv;
-          pending_pub = true;
-          if (a.trace_on > 1) { tm1 = wall_clock64(); if (lane == 0) bump(sh.stat, ST_T_WAIT, tm1 - tm0); tm2 = tm1; }
-          if (bytes) {
-            const void* jfin = q.recv ? (const void*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
-            void* jfout = q.send ? (void*)(fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
-            const char* jsb = q.from_send ? sendbuf + soff * eb : nullptr;
-            char* jrb = q.to_recv ? recvbuf + doff * eb : nullptr;
-            if (coh && bytes <= SOLO_BYTES) {
-              // a short slice: this wave moves it on its own (one load batch), drains, and
-              // publishes at the top of the loop
-              run_prim<AUX_DEVICE, 64>(dtype, jfin, jsb, jrb, jfout, bytes, lane);
-              __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-              __builtin_amdgcn_s_waitcnt(0);
-              if (a.trace_on > 1) tm2 = wall_clock64();
-            } else {
-              if (lane == 0) {
-                Job j;
-                j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
-                j.bytes = bytes;
-                j.dtype = dtype;
-                sh.job = j;
-              }
-              cmd = CMD_MOVE;
-            }
-          }
-          // an empty slice is only a handshake: it is published at the top of the loop
-        } else {
-          // ---- PreemptCollective + SaveCollectiveContext (lazy: only if it progressed)
-          if (a.trace_on == 3 && trace) {   // timeline sample of a wait that ended without the primitive: index 15
-            u64 dur = wall_clock64() - tm0;
-            if (dur > 0xffffu) dur = 0xffffu;
-            if (lane == 0) trace[trace_n % DFX_TRACE_N] = (tm0 & 0xffffffffull) | (dur << 32) | ((u64)(coll & 0xfffu) << 48) | (15ull << 60);
-            ++trace_n;
-          }
-          const bool tr = a.trace_on && res == W_TIMEOUT && pos + 1 < qlen;
-          if (tr) sw_t0 = wall_clock64();
-          if (lane == 0) {
-            if (res == W_TIMEOUT) bump(sh.stat, ST_PREEMPT, 1);
-            if (progressed) {
-              DfxDyn d; d.round = g; d.prim = p; d.sent = sent; d.recvd = recvd;
-              d.preempted = preempted_before + 1; d.cidx = cidx;
-              sh.slot[sl].dyn = d;
-              myctx[coll].dyn = d;
-              bump(sh.stat, ST_SAVE, 1);
-            } else if (res == W_TIMEOUT) bump(sh.stat, ST_LAZY, 1);
-          }
-          if (tr) { if (a.trace_on > 1) sw_ts = wall_clock64(); sw_pending = true; }
-          have = false;
-          if (res == W_STOP) { stop = STOP_ABORT; cmd = CMD_STOP; break; }
-          if (scanned) ++rk; else ++pos;
-        }
+  if (!sched) {
+    // =====================================================================================
+    // mover waves
+    // =====================================================================================
+    const uint32_t mtid = tid - 64;
+    const bool first_wave = mtid < 64;
+    uint32_t seen = 0;
+    for (;;) {
+      // the leave flag is looked at only when no job is waiting: every posted job is executed
+      bool go = true;
+      while (lds_ld(&sh.job_seq) == seen) {
+        if (lds_ld(&sh.leave)) { go = false; break; }
+        __builtin_amdgcn_s_sleep(1);
       }
-      if (lane == 0) sh.cmd = cmd;
-    }
-    __syncthreads();
-    if (sh.cmd == CMD_STOP) break;
-
-    // ================= data phase: all waves move the slice the scheduler posted =================
-    {
-      const Job j = sh.job;
-      // fenced mode: every wave invalidates before its own loads of the slot (the poll was wave 0's)
+      if (!go) break;
+      const Job j = sh.job[seen & 1];
+      u64 t0 = 0;
+      if (a.trace_on > 1 && first_wave) t0 = wall_clock64();
+      // fenced mode: every wave invalidates before its own loads of the slot (the poll was the scheduler's)
       if (!coh && j.fin) fence_acquire_agent();
 #ifdef DFX_NO_FENCED
-      run_prim<AUX_DEVICE, NT>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, tid);
+      run_prim<AUX_DEVICE, DFX_MOVERS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
 #else
-      if (coh) run_prim<AUX_DEVICE, NT>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, tid);
-      else run_prim<AUX_CACHED, NT>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, tid);
+      if (coh) run_prim<AUX_DEVICE, DFX_MOVERS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
+      else run_prim<AUX_CACHED, DFX_MOVERS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
 #endif
+      // this wave's stores (and loads) have been performed before it counts itself done
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __builtin_amdgcn_s_waitcnt(0);
+      u64 t1 = 0;
+      if (a.trace_on > 1) t1 = wall_clock64();
+      uint32_t last = 0;
+      if (lane == 0) {
+        const uint32_t old = __hip_atomic_fetch_add(&sh.wave_done[seen & 1], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
+        last = (old + 1 == DFX_MOVERS / 64) ? 1u : 0u;
+        if (first_wave && a.trace_on > 1) {
+          bump(sh.stat, ST_T_DATA, t1 - t0);
+          if (a.trace_on == 3 && trace) trace_put(trace, &sh.trace_n, timeline_sample(t0, t1, j.coll, j.prim));
+        }
+      }
+      if (bcast0(last)) {
+        // all mover waves have drained job `seen`: its data is in memory, raise the counters
+        if (lane == 0) {
+          const Flight f = sh.fl[seen & 1];
+          if (!coh) fence_release_agent();
+          if (f.tail_out) raise_counter(f.tail_out, f.sent_new);
+          if (f.head_in) raise_counter(f.head_in, f.recvd_new);
+          __hip_atomic_store(&sh.wave_done[seen & 1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          if (a.trace_on > 1) bump(sh.stat, ST_T_PUB, wall_clock64() - t1);
+          // jobs finish in order (every wave takes them in order), but the publisher of the job
+          // before may still be a few instructions short of reporting it: let it go first (it
+          // waits for nothing), so that the scheduler retires jobs strictly in order
+          while (lds_ld(&sh.jobs_done) != seen) __builtin_amdgcn_s_sleep(0);
+          lds_st(&sh.jobs_done, seen + 1);
+        }
+      }
+      ++seen;
     }
-    if (sched && a.trace_on > 1) tm2 = wall_clock64();
-    drain_and_barrier();
+  } else {
+    // =====================================================================================
+    // scheduler wave
+    // =====================================================================================
+    // start values of the ring-chunk index of a fresh sequence (see DfxDyn.cidx)
+    const uint32_t cidx0_reduce = (rank + a.R - 1) % a.R;   // all-reduce / reduce-scatter: chunk rank-1
+    u64 last_act = wall_clock64();
+    bool acted = true, voted = false;
+    uint32_t iter = 0, idle = 0, burst = 0;
+    bool in_pass = false, pass_progress = false, scanned = false;
+    uint32_t nready = 0, rk = 0, removed = 0;   // readiness list of the pass: length, cursor, entries completed
+    uint32_t pos = 0;
+    // context-switch sample in flight: t0 = abort decision, ts = after the save, lb/le = load
+    u64 sw_t0 = 0, sw_ts = 0, sw_lb = 0, sw_le = 0;
+    bool sw_pending = false;
+    // the collective in the active slot; sent / recvd count the slots this workgroup has CLAIMED
+    // (posted or moved), which may run ahead of the counters in memory by the jobs in flight
+    bool have = false;
+    uint32_t coll = 0, sl = 0, nprim = 0, rounds = 0, K = 0, nchan = 0, slot_bytes = 0, slice_elems = 0, eb = 4;
+    uint32_t g = 0, p = 0, preempted_before = 0, seq = 0;
+    int kind = 0, dtype = 0;
+    uint32_t bc_pos = 0, cidx = 0, vch = 0;
+    u64 count = 0, block_elems = 0, part_elems = 0, sent = 0, recvd = 0, thr = 0;
+    const char* sendbuf = nullptr;
+    char* recvbuf = nullptr;
+    u64 *tail_out = nullptr, *head_out = nullptr, *tail_in = nullptr, *head_in = nullptr;
+    uint8_t *fifo_out = nullptr, *fifo_in = nullptr;
+    bool progressed = false;
+    uint32_t posted = 0, retired = 0;   // jobs handed to the movers / jobs whose bookkeeping is done
+
+    // ---- completion of this workgroup's share of an invocation (Sec. 5): completion counter,
+    // and the last channel posts the CQE.  Lane 0 only.
+    auto complete = [&](uint32_t c_coll, uint32_t c_seq, uint32_t c_nchan) {
+      fence_release_system();   // results in the recv buffer are visible to host and later kernels
+      uint32_t* dc = &a.done_cnt[(size_t)rank * a.max_colls + c_coll];
+      const uint32_t old = __hip_atomic_fetch_add(dc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
+      if (old + 1 == c_nchan) {
+        __hip_atomic_store(dc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
+        const u64 v = (1ull << 63) | ((u64)(c_seq & 0x7fffffffu) << 32) | c_coll;
+        const uint32_t t = __hip_atomic_fetch_add(&a.cq_ticket[rank], 1u, __ATOMIC_RELAXED, SCOPE_AGENT);
+        uint32_t k = 0;
+        for (;;) {   // optimized CQ (Sec. 5): one CAS of the id into a writable slot
+          u64 expected = 0;
+          if (__hip_atomic_compare_exchange_strong(&cqbase[(t + k) % a.cq_slots], &expected, v, __ATOMIC_RELEASE,
+                                                   __ATOMIC_RELAXED, SCOPE_SYSTEM))
+            break;
+          ++k;
+          if ((k % a.cq_slots) == 0) {
+            if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) break;
+            __builtin_amdgcn_s_sleep(50);
+          }
+        }
+        bump(sh.stat, ST_CQE, 1);
+      }
+    };
+
+    // ---- retire the jobs the movers have finished (their counters are already raised)
+    auto retire_finished = [&]() {
+      while (retired != posted && lds_ld(&sh.jobs_done) != retired) {
+        if (lane == 0) {
+          const Flight f = sh.fl[retired & 1];
+          bump(sh.stat, ST_PRIMS, 1);
+          if (f.last) complete(f.coll, f.seq, f.nchan);
+        }
+        ++retired;
+        acted = true;
+      }
+    };
+
+    // The movers wait for nothing but their own memory operations, so the loops below that wait
+    // for them end on their own; they still look at the abort words now and then, so that the
+    // host can always get the grid back.
+    uint32_t spins = 0;
+    auto abort_seen = [&]() -> bool {
+      uint32_t s = 0;
+      if (lane == 0) s = (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) ? 1u : 0u;
+      return bcast0(s) != 0;
+    };
+
+    for (;;) {
+      retire_finished();
+      if (stop != STOP_NONE) {
+        // leaving: the posted jobs run to their end first (their slots are claimed in the saved contexts)
+        if (retired == posted) break;
+        if ((++spins & 0xffffu) == 0 && abort_seen()) break;
+        __builtin_amdgcn_s_sleep(1);
+        continue;
+      }
+
+      // ================= no collective in hand: control check, fetch, next queue entry =================
+      if (!have) {
+        if (!in_pass) {
+          ++iter;
+          uint32_t s = STOP_NONE, got = 0;
+          // FIFO ordering (Sec. 4.3): fetch when the queue is empty or a whole pass made no
+          // progress, then keep fetching what is already there (up to fetch_batch); priority
+          // ordering probes the SQ before every pass.
+          const bool want = (qlen == 0) || !pass_progress || a.order_policy == 1 || (burst > 0 && burst < a.fetch_batch);
+          const bool probe = want && qlen < a.max_colls;
+          const bool slow = ((iter & 31u) == 0) || qlen == 0 || !pass_progress;
+          const bool host_look = ((iter & 31u) == 0) || qlen == 0;
+          // the three control words live in different memories; three lanes fetch them at once
+          uint32_t w0 = 0, w1 = 0;
+          if (lane == 0) {
+            const u64 c2 = ld_agent64((const u64*)&a.dev_ctl[DC_ABORT]);   // abort | quit
+            w0 = (uint32_t)c2; w1 = (uint32_t)(c2 >> 32);
+          } else if (lane == 1) {
+            if (probe) w0 = __hip_atomic_load(&sqbase[ri & (D - 1)].e.ready, __ATOMIC_RELAXED, SCOPE_SYSTEM);
+          } else if (lane == 2) {
+            if (host_look) w0 = ld_sys32(&a.host_ctl[HC_ABORT]);
+          }
+          const uint32_t c_abort = __builtin_amdgcn_readlane(w0, 0), c_quit = __builtin_amdgcn_readlane(w1, 0);
+          const uint32_t c_ready = __builtin_amdgcn_readlane(w0, 1), c_habort = __builtin_amdgcn_readlane(w0, 2);
+          if (c_abort || c_habort) s = STOP_ABORT;
+          else if (c_quit) s = STOP_QUIT;
+          if (lane == 0) {
+            if (!s && slow) {
+              const u64 now = wall_clock64();
+              if (acted) { last_act = now; acted = false; }
+              if (a.watchdog_ticks && qlen > 0 && now - last_act > a.watchdog_ticks) {
+                ws->dbg[0] = ((u64)sh.taskq[0] << 32) | qlen; ws->dbg[1] = ri; ws->dbg[2] = now - last_act;
+                raise_error(a, 1u, wg);
+                s = STOP_ABORT;
+              } else if (a.quit_ticks) {
+                // Voluntary quit (Sec. 4.4).  Every workgroup has duties towards the others (each
+                // must read every SQE of its rank before the slot is reusable), so the grid leaves
+                // as a whole: a workgroup that has been idle or stuck for the quit period casts a
+                // vote and keeps running; it withdraws the vote when it becomes active again; the
+                // vote that completes the set raises the quit flag, which everybody obeys.
+                const bool tired = now - last_act > a.quit_ticks;
+                if (tired && !voted) {
+                  voted = true;
+                  if (__hip_atomic_fetch_add(&a.dev_ctl[DC_VOTES], 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT) + 1 == a.nwg) {
+                    __hip_atomic_store(&a.dev_ctl[DC_QUIT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
+                    s = STOP_QUIT;
+                  }
+                } else if (!tired && voted) {
+                  voted = false;
+                  __hip_atomic_fetch_sub(&a.dev_ctl[DC_VOTES], 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
+                }
+              }
+            }
+            if (!s && probe) {
+              const uint32_t gen = (uint32_t)(ri >> a.sq_shift) + 1u;
+              if (c_ready == gen) got = 1;
+            }
+          }
+          s = bcast0(s);
+          got = bcast0(got);
+          if (s) { stop = s; continue; }
+
+          // ---- FetchSQE (Alg. 1 line 2)
+          if (got) {
+            DfxSqSlot* e = &sqbase[ri & (D - 1)];
+            // the submitter wrote the send buffer before the SQE: drop what this CU / XCD cached
+            fence_acquire_system();
+            if (lane < 6) ((uint4*)&sh.sqe)[lane] = ((const uint4*)&e->e)[lane];
+            __builtin_amdgcn_wave_barrier();
+            const uint32_t c_id = sh.sqe.coll_id;
+            const uint32_t flags = sh.sqe.flags;
+            // an exit SQE ends the launch it was posted for; one left over from an earlier launch
+            // (some workgroups had already gone when it arrived) is consumed and ignored
+            const bool is_exit_sqe = (flags & DFX_SQE_EXIT) != 0;
+            const bool is_exit = is_exit_sqe && sh.sqe.seq == a.epoch;
+            // A collective with fewer channels than the grid has per rank starts at workgroup
+            // (coll_id * nchan) mod cmax, so that many small collectives spread over the rank's
+            // workgroups instead of queueing on the first ones; every rank derives the same
+            // start from the id, which keeps both ends of a connector on the same channel.
+            uint32_t my_vch = ch;
+            if (a.chan_spread && !is_exit_sqe && sh.sqe.nchan < a.cmax)
+              my_vch = (ch + a.cmax - (c_id * sh.sqe.nchan) % a.cmax) % a.cmax;
+            const bool mine = !is_exit_sqe && my_vch < sh.sqe.nchan && c_id < a.max_colls;
+            if (mine) {
+              // cook the static context of this invocation into the context buffer (addresses
+              // resolved once, here); restart the sequence, keep the monotone connector counters
+              if (lane == 0) {
+                const DfxStatic& q = sh.sqe;
+                DfxCooked k;
+                k.sendbuf = q.sendbuf; k.recvbuf = q.recvbuf; k.count = q.count;
+                k.block_elems = q.block_elems; k.part_elems = q.part_elems;
+                uint8_t* conn = a.pool + q.conn_off;   // flags first, then slots
+                const uint32_t e_out = rank, e_in = (rank + a.R - 1) % a.R;
+                const size_t fo = (size_t)e_out * q.nchan + my_vch, fi = (size_t)e_in * q.nchan + my_vch;
+                uint8_t* slots = conn + (size_t)a.R * q.nchan * DFX_FLAG_STRIDE;
+                k.flags_out = (uint64_t)(conn + fo * DFX_FLAG_STRIDE);
+                k.flags_in = (uint64_t)(conn + fi * DFX_FLAG_STRIDE);
+                k.fifo_out = (uint64_t)(slots + fo * q.nslots * q.slot_bytes);
+                k.fifo_in = (uint64_t)(slots + fi * q.nslots * q.slot_bytes);
+                k.slice_elems = q.slice_elems; k.rounds = q.rounds; k.seq = q.seq;
+                k.nprim = (uint16_t)q.nprim; k.nchan = q.nchan;
+                k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = q.dtype;
+                const uint32_t bpos = (rank + a.R - q.root) % a.R;
+                k.bc_pos = bpos == 0 ? 0 : (bpos == a.R - 1 ? 2 : 1);
+                k.priority = q.priority; k.vch = (uint16_t)my_vch;
+                myctx[c_id].st = k;
+                DfxDyn* dy = &myctx[c_id].dyn;
+                dy->round = 0; dy->prim = 0; dy->preempted = 0;
+                dy->cidx = (q.kind == KIND_AG) ? rank : ((q.kind == KIND_BC || a.R == 1) ? 0u : cidx0_reduce);
+                // FIFO ordering: append; priority ordering: keep the queue sorted (stable)
+                uint32_t at = qlen;
+                if (a.order_policy == 1) {
+                  const int16_t pr = q.priority;
+                  while (at > 0 && myctx[sh.taskq[at - 1]].st.priority < pr) { sh.taskq[at] = sh.taskq[at - 1]; --at; }
+                }
+                sh.taskq[at] = (uint16_t)c_id;
+                if (sh.slot_tag[c_id % DFX_CTX_SLOTS] == c_id) sh.slot_tag[c_id % DFX_CTX_SLOTS] = 0xffffffffu;
+              }
+              ++qlen;
+              if (lane == 0) __hip_atomic_fetch_max(&sh.stat[ST_MAXQ], (u64)qlen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+            if (lane == 0) {
+              // every workgroup of the rank reads every SQE; the last reader frees the slot (Sec. 5)
+              uint32_t* rc = &a.sq_readers[(size_t)rank * D + (ri & (D - 1))];
+              const uint32_t old = __hip_atomic_fetch_add(rc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
+              if (old + 1 == a.cmax) {
+                __hip_atomic_store(rc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
+                __hip_atomic_store(&e->e.ready, 0u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
+              }
+              bump(sh.stat, ST_SQE, 1);
+            }
+            __builtin_amdgcn_wave_barrier();
+            acted = true;
+            sw_pending = false;
+            ++ri;
+            if (is_exit) {
+              // the whole grid leaves (every workgroup has reader duties towards its rank's SQ)
+              if (lane == 0) __hip_atomic_store(&a.dev_ctl[DC_QUIT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
+              stop = STOP_EXIT;
+              continue;
+            }
+            ++burst;
+            idle = 0;
+            continue;               // probe the SQ again before walking the queue
+          }
+          burst = 0;
+          if (qlen == 0) {
+            // idle: back off the SQ probe (it may cross PCIe)
+            ++idle;
+            if (idle < 16) __builtin_amdgcn_s_sleep(8);
+            else if (idle < 64) __builtin_amdgcn_s_sleep(32);
+            else __builtin_amdgcn_s_sleep(127);
+            continue;
+          }
+          idle = 0;
+          // ---- start one pass over the task queue (Alg. 1 lines 4-19)
+          in_pass = true;
+          pass_progress = false;
+          pos = 0;
+          if (lane == 0) bump(sh.stat, ST_PASSES, 1);
+          // ---- readiness scan: 64 queue entries per step, one per lane.  Each lane reads the
+          // saved context of its entry, works out which connector sides its next primitive
+          // needs, loads those counters and votes; the runnable positions are compacted into a
+          // list (ballot + popcount) and the pass visits only those.  The conditions are
+          // monotone: only this workgroup consumes its recv side and fills its send side, so
+          // "ready" stays true until it acts.  A queue of a thousand stuck collectives costs
+          // sixteen memory round trips instead of a thousand context loads and bounded spins.
+          scanned = a.scan_min && qlen >= a.scan_min;
+          if (scanned) {
+            nready = 0; rk = 0; removed = 0;
+            for (uint32_t base = 0; base < qlen; base += 64) {
+              const uint32_t i = base + lane;
+              bool rdy = false;
+              if (i < qlen) {
+                const uint4* e = (const uint4*)&myctx[sh.taskq[i]];
+                const uint4 fl = e[2];    // bytes 32..47: part_elems | flags_out
+                const uint4 fi = e[3];    // bytes 48..63: flags_in | fifo_out
+                const uint4 ge = e[5];    // bytes 80..95: seq | nprim,nchan | nslots,kind,dtype,bc_pos | priority,vch
+                const uint4 d0 = e[6];    // dyn: round | prim | sent
+                const uint4 d1 = e[7];    // dyn: recvd | preempted | cidx
+                const Prim pq = make_prim((int)((ge.z >> 8) & 0xffu), a.R, ge.z >> 24, d0.y);
+                const u64 f_out = ((u64)fl.w << 32) | fl.z, f_in = ((u64)fi.y << 32) | fi.x;
+                const u64 e_sent = ((u64)d0.w << 32) | d0.z, e_recvd = ((u64)d1.y << 32) | d1.x;
+                bool okr = true, oks = true;
+                if (pq.recv) okr = ld_agent64((const u64*)f_in) > e_recvd;
+                if (pq.send) oks = (e_sent - ld_agent64((const u64*)f_out + 8)) < (u64)(ge.z & 0xffu);
+                rdy = okr && oks;
+              }
+              const u64 mask = __ballot(rdy);
+              if (rdy) sh.rlist[nready + (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull))] = (uint16_t)i;
+              nready += (uint32_t)__builtin_popcountll(mask);
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (lane == 0) { bump(sh.stat, ST_POLLS, (qlen + 63) / 64); bump(sh.stat, ST_SCAN_SKIPS, qlen - nready); }
+            if (nready == 0) {           // nothing can run: the pass is over before it began
+              in_pass = false;
+              __builtin_amdgcn_s_sleep(4);
+              continue;
+            }
+          }
+        }
+        if (scanned) {
+          // entries completed earlier in this pass moved the later ones up by one each
+          if (rk >= nready) { in_pass = false; continue; }
+          pos = (uint32_t)sh.rlist[rk] - removed;
+        } else if (pos >= qlen) { in_pass = false; continue; }
+
+        // ---- LoadCollectiveContext: HBM context buffer -> LDS slot, 8 lanes x 16 bytes
+        coll = sh.taskq[pos];
+        sl = coll % DFX_CTX_SLOTS;
+        if (sw_pending && a.trace_on > 1) sw_lb = wall_clock64();
+        if (sh.slot_tag[sl] != coll) {
+          if (lane < 8) ((uint4*)&sh.slot[sl])[lane] = ((const uint4*)&myctx[coll])[lane];
+          if (lane == 0) { sh.slot_tag[sl] = coll; bump(sh.stat, ST_LOAD, 1); }
+          __builtin_amdgcn_wave_barrier();
+        } else if (lane == 0) bump(sh.stat, ST_HIT, 1);
+        if (sw_pending && a.trace_on > 1) sw_le = wall_clock64();
+        {
+          const DfxCtxEntry& C = sh.slot[sl];
+          kind = C.st.kind; dtype = C.st.dtype; bc_pos = C.st.bc_pos;
+          eb = (dtype == DT_F32 || dtype == DT_I32) ? 4u : 2u;
+          nprim = C.st.nprim; rounds = C.st.rounds; K = C.st.nslots; nchan = C.st.nchan;
+          slice_elems = C.st.slice_elems; slot_bytes = slice_elems * eb; seq = C.st.seq;
+          count = C.st.count; block_elems = C.st.block_elems; part_elems = C.st.part_elems;
+          sendbuf = (const char*)C.st.sendbuf;
+          recvbuf = (char*)C.st.recvbuf;
+          tail_out = (u64*)C.st.flags_out; head_out = tail_out + 8;
+          tail_in = (u64*)C.st.flags_in; head_in = tail_in + 8;
+          fifo_out = (uint8_t*)C.st.fifo_out;
+          fifo_in = (uint8_t*)C.st.fifo_in;
+          g = C.dyn.round; p = C.dyn.prim; sent = C.dyn.sent; recvd = C.dyn.recvd; cidx = C.dyn.cidx;
+          preempted_before = C.dyn.preempted;
+          vch = C.st.vch;
+        }
+        // SetInitialSpinThreshold (Alg. 1 line 3): largest at the front, halving per position
+        thr = a.spin_init >> (pos < 31 ? pos : 31);
+        if (thr < a.spin_min) thr = a.spin_min;
+        progressed = false;
+        have = true;
+      }
+
+      // ================= next primitive of the collective in hand =================
+      const Prim q = make_prim(kind, a.R, bc_pos, p);
+      // slice geometry (elements relative to the block, clipped to the block's true length)
+      const bool ring_chunks = (kind == KIND_AR && a.R > 1);
+      u64 blen = count;
+      if (ring_chunks) {
+        const u64 start = (u64)cidx * block_elems;
+        blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
+      }
+      u64 lo = (u64)vch * part_elems + (u64)g * slice_elems;
+      u64 hi = lo + slice_elems;
+      const u64 pend = (u64)(vch + 1) * part_elems;
+      if (hi > pend) hi = pend;
+      if (lo > blen) lo = blen;
+      if (hi > blen) hi = blen;
+      const uint32_t bytes = (uint32_t)(hi - lo) * eb;
+      u64 soff = lo, doff = lo;   // element offsets in the send / recv buffer
+      if (ring_chunks) { soff += (u64)cidx * block_elems; doff = soff; }
+      else if (kind == KIND_RS) soff += (u64)cidx * count;
+      else if (kind == KIND_AG) doff += (u64)cidx * count;
+
+      u64 tm0 = 0;
+      if (a.trace_on > 1) tm0 = wall_clock64();
+      if (sw_pending) {   // the first poll of the next collective ends the context switch
+        const u64 t1 = wall_clock64();
+        if (trace && a.trace_on < 3 && lane == 0) {
+          u64 tot = t1 - sw_t0, sv = sw_ts - sw_t0, ldt = sw_le - sw_lb;
+          if (a.trace_on < 2) { sv = 0; ldt = 0; }
+          if (tot > 0xffffffu) tot = 0xffffffu;
+          if (sv > 0xfffffu) sv = 0xfffffu;
+          if (ldt > 0xfffffu) ldt = 0xfffffu;
+          trace_put(trace, &sh.trace_n, tot | (sv << 24) | (ldt << 44));
+        }
+        sw_pending = false;
+      }
+
+      // ---- wait phase: lane 0 polls the recv side, lane 1 the send side (Sec. 4.2 (3)).
+      // The movers may be busy with earlier slices meanwhile; finished ones are retired between polls.
+      uint32_t res = W_OK;
+      if (q.recv || q.send) {
+        u64 n = 0;
+        for (;;) {
+          bool ok = true;
+          if (lane == 0 && q.recv) ok = ld_agent64(tail_in) > recvd;
+          if (lane == 1 && q.send) ok = (sent - ld_agent64(head_out)) < (u64)K;
+          ++n;
+          if (__ballot(!ok) == 0) break;
+          retire_finished();
+          if (a.preempt && n >= thr) { res = W_TIMEOUT; break; }
+          if ((n & 255u) == 0) {
+            uint32_t s = 0;
+            if (lane == 0) {
+              if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) s = 1;
+              else if (a.watchdog_ticks) {
+                const u64 now = wall_clock64();
+                if (acted) { last_act = now; acted = false; }
+                if (now - last_act > a.watchdog_ticks) {
+                  ws->dbg[0] = ((u64)coll << 32) | qlen; ws->dbg[1] = ((u64)g << 32) | p; ws->dbg[2] = sent; ws->dbg[3] = recvd;
+                  ws->dbg[4] = ld_agent64(tail_in); ws->dbg[5] = ld_agent64(head_out); ws->dbg[6] = ri; ws->dbg[7] = now - last_act;
+                  raise_error(a, 2u, wg);
+                  s = 1;
+                }
+              }
+            }
+            if (bcast0(s)) { res = W_STOP; break; }
+          }
+          __builtin_amdgcn_s_sleep(1);
+        }
+        if (lane == 0) bump(sh.stat, ST_POLLS, n);
+      }
+
+      if (res == W_OK) {
+        u64 tm1 = 0;
+        if (a.trace_on > 1) { tm1 = wall_clock64(); if (lane == 0) bump(sh.stat, ST_T_WAIT, tm1 - tm0); }
+        const bool solo = !bytes || (coh && bytes <= SOLO_BYTES);
+        // a flight slot: at most two jobs are posted and not yet retired; a slice this wave moves
+        // itself (or an empty one, which is only a handshake) waits until the movers are idle, so
+        // that counters of one connector are raised in order
+        bool given_up = false;
+        while (posted - retired >= (solo ? 1u : 2u)) {
+          retire_finished();
+          if (posted - retired >= (solo ? 1u : 2u)) {
+            if ((++spins & 0xffffu) == 0 && abort_seen()) { given_up = true; break; }
+            __builtin_amdgcn_s_sleep(1);
+          }
+        }
+        if (given_up) { stop = STOP_ABORT; have = false; continue; }
+        // ---- claim the slots and step the sequence (the data follows, the counters after it)
+        const void* jfin = q.recv ? (const void*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
+        void* jfout = q.send ? (void*)(fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
+        const char* jsb = q.from_send ? sendbuf + soff * eb : nullptr;
+        char* jrb = q.to_recv ? recvbuf + doff * eb : nullptr;
+        const uint32_t this_p = p;
+        if (q.send) ++sent;
+        if (q.recv) ++recvd;
+        // next primitive: the chunk index steps down the ring; a new round starts over
+        cidx = (cidx == 0) ? a.R - 1 : cidx - 1;
+        if (++p == nprim) {
+          p = 0; ++g;
+          cidx = (kind == KIND_AG) ? rank : ((kind == KIND_BC || a.R == 1) ? 0u : cidx0_reduce);
+        }
+        if (kind == KIND_BC) cidx = 0;
+        progressed = true;
+        pass_progress = true;
+        acted = true;
+        // AdaptivelyAdjustSpinThreshold (Alg. 1 line 9)
+        thr *= a.spin_boost;
+        if (thr > a.spin_max) thr = a.spin_max;
+        const bool last = (g == rounds);
+
+        if (solo) {
+          if (bytes) {
+            run_prim<AUX_DEVICE, 64>(dtype, jfin, jsb, jrb, jfout, bytes, lane);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0);
+          }
+          u64 tm2 = 0;
+          if (a.trace_on > 1) tm2 = wall_clock64();
+          if (lane == 0) {
+            if (!coh) fence_release_agent();
+            if (q.send) raise_counter(tail_out, sent);
+            if (q.recv) raise_counter(head_in, recvd);
+            bump(sh.stat, ST_PRIMS, 1);
+            if (a.trace_on > 1) {
+              bump(sh.stat, ST_T_DATA, tm2 - tm1); bump(sh.stat, ST_T_PUB, wall_clock64() - tm2);
+              if (a.trace_on == 3 && trace) trace_put(trace, &sh.trace_n, timeline_sample(tm1, tm2, coll, this_p));
+            }
+          }
+        } else {
+          if (lane == 0) {
+            Job j;
+            j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
+            j.bytes = bytes; j.dtype = dtype; j.coll = coll; j.prim = this_p;
+            sh.job[posted & 1] = j;
+            Flight f;
+            f.tail_out = q.send ? tail_out : nullptr; f.head_in = q.recv ? head_in : nullptr;
+            f.sent_new = sent; f.recvd_new = recvd;
+            f.last = last ? 1u : 0u; f.coll = coll; f.seq = seq; f.nchan = nchan;
+            sh.fl[posted & 1] = f;
+            lds_st(&sh.job_seq, posted + 1);
+          }
+          ++posted;
+        }
+
+        if (last) {
+          // ---- CollectiveSuccess: the entry leaves the queue now; the completion counter and the
+          // CQE follow when the data is in memory (here for a slice this wave moved, at retirement
+          // for a posted one)
+          if (lane == 0) {
+            DfxDyn d; d.round = 0; d.prim = 0; d.sent = sent; d.recvd = recvd; d.preempted = 0; d.cidx = 0;
+            sh.slot[sl].dyn = d;
+            myctx[coll].dyn = d;
+            if (solo) complete(coll, seq, nchan);
+          }
+          // later entries move up, the position stays (Sec. 4.3)
+          --qlen;
+          for (uint32_t base = pos; base < qlen; base += 64) {
+            const uint32_t i = base + lane;
+            uint16_t v = 0;
+            if (i < qlen) v = sh.taskq[i + 1];
+            __builtin_amdgcn_wave_barrier();
+            if (i < qlen) sh.taskq[i] = v;
+            __builtin_amdgcn_wave_barrier();
+          }
+          have = false;
+          sw_pending = false;
+          if (scanned) { ++rk; ++removed; }
+        }
+      } else {
+        // ---- PreemptCollective + SaveCollectiveContext (lazy: only if it progressed)
+        if (a.trace_on == 3 && trace && lane == 0)   // timeline sample of a wait that ended without the primitive: index 15
+          trace_put(trace, &sh.trace_n, timeline_sample(tm0, wall_clock64(), coll, 15));
+        const bool tr = a.trace_on && res == W_TIMEOUT && pos + 1 < qlen;
+        if (tr) sw_t0 = wall_clock64();
+        if (lane == 0) {
+          if (res == W_TIMEOUT) bump(sh.stat, ST_PREEMPT, 1);
+          if (progressed) {
+            DfxDyn d; d.round = g; d.prim = p; d.sent = sent; d.recvd = recvd;
+            d.preempted = preempted_before + 1; d.cidx = cidx;
+            sh.slot[sl].dyn = d;
+            myctx[coll].dyn = d;
+            bump(sh.stat, ST_SAVE, 1);
+          } else if (res == W_TIMEOUT) bump(sh.stat, ST_LAZY, 1);
+        }
+        if (tr) { if (a.trace_on > 1) sw_ts = wall_clock64(); sw_pending = true; }
+        have = false;
+        if (res == W_STOP) { stop = STOP_ABORT; continue; }
+        if (scanned) ++rk; else ++pos;
+      }
+    }
+
+    // every posted job has been retired and no collective is in hand: the movers may go
+    if (lane == 0) {
+      if (stop == STOP_QUIT) bump(sh.stat, ST_QUITS, 1);
+      ws->read_index = ri;
+      ws->qlen = qlen;
+      sh.qlen_out = qlen;
+      lds_st(&sh.leave, 1u);
+    }
   }
 
   // ================= leave: persist what the next launch needs =================
-  // (the scheduler wave owns the truth about ri / qlen / trace_n; hand it over through LDS)
-  if (tid == 0) {
-    if (stop == STOP_QUIT) sh.stat[ST_QUITS] += 1;
-    ws->read_index = ri;
-    ws->qlen = qlen;
-    ws->trace_n = trace_n;
-    for (int i = 0; i < DFX_NSTAT; ++i) ws->stat[i] = sh.stat[i];
-    sh.qlen_out = qlen;
-  }
   __syncthreads();
+  if (tid == 0) {
+    ws->trace_n = sh.trace_n;
+    for (int i = 0; i < DFX_NSTAT; ++i) ws->stat[i] = sh.stat[i];
+  }
   const uint32_t qn = sh.qlen_out;
   for (uint32_t i = tid; i < qn; i += NT) qstore[i] = sh.taskq[i];
 }
