@@ -35,11 +35,6 @@ namespace {
 typedef uint64_t u64;
 
 constexpr int NT = DFX_WG_THREADS;
-#ifndef DFX_SOLO_BYTES
-#define DFX_SOLO_BYTES 8192
-#endif
-// slices up to this size are moved by the scheduler wave alone (no hand-off to the movers)
-constexpr uint32_t SOLO_BYTES = DFX_SOLO_BYTES;
 #ifndef DFX_UNROLL
 #define DFX_UNROLL 8
 #endif
@@ -172,7 +167,7 @@ struct Slot {   // one connector slot seen through a buffer resource
 template <int DT, int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT, int NTH>
 __device__ __forceinline__ void move_slice(const void* fin_p, const char* __restrict__ sb, char* __restrict__ rb,
                                            void* fout_p, uint32_t bytes, uint32_t tid) {
-  constexpr int NT = NTH;   // threads that share the slice: the mover waves, or the scheduler wave alone
+  constexpr int NT = NTH;   // threads that share the slice: the mover waves
   static_assert(FIN || SB, "a primitive has a source");
   static_assert(RB || FOUT, "a primitive has a destination");
   const Slot<AIN> fin(fin_p, FIN ? bytes : 0);
@@ -409,8 +404,7 @@ __device__ __forceinline__ u64 timeline_sample(u64 t0, u64 t1, uint32_t coll, ui
 // counts itself done in LDS.  The wave that completes the count raises the connector counters
 // of that job (the data of all waves is then in memory) and reports the job finished; the
 // scheduler retires finished jobs in order (statistics; for the last primitive of an invocation
-// the completion counter and the CQE).  No workgroup barrier is used after start-up; short
-// slices are moved by the scheduler wave itself once the movers are idle.
+// the completion counter and the CQE).  No workgroup barrier is used after start-up.
 extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(DfxDaemonArgs kargs) {
   __shared__ Shared sh;
   // The arguments are read from an LDS copy: kept in scalar registers for the whole kernel they
@@ -469,7 +463,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       u64 t0 = 0;
       if (a.trace_on > 1 && first_wave) t0 = wall_clock64();
       // fenced mode: every wave invalidates before its own loads of the slot (the poll was the scheduler's)
-      if (!coh && j.fin) fence_acquire_agent();
+      if (!coh && j.fin && j.bytes) fence_acquire_agent();
 #ifdef DFX_NO_FENCED
       run_prim<AUX_DEVICE, DFX_MOVERS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
 #else
@@ -523,18 +517,14 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
     // context-switch sample in flight: t0 = abort decision, ts = after the save, lb/le = load
     u64 sw_t0 = 0, sw_ts = 0, sw_lb = 0, sw_le = 0;
     bool sw_pending = false;
-    // the collective in the active slot; sent / recvd count the slots this workgroup has CLAIMED
-    // (posted or moved), which may run ahead of the counters in memory by the jobs in flight
+    // The collective in hand.  Its static context stays in the LDS slot and is read where it is
+    // needed (few values live across a wait); the dynamic part is in registers.  sent / recvd
+    // count the slots this workgroup has CLAIMED (posted to the movers), which may run ahead
+    // of the counters in memory by the jobs in flight.
     bool have = false;
-    uint32_t coll = 0, sl = 0, nprim = 0, rounds = 0, K = 0, nchan = 0, slot_bytes = 0, slice_elems = 0, eb = 4;
-    uint32_t g = 0, p = 0, preempted_before = 0, seq = 0;
-    int kind = 0, dtype = 0;
-    uint32_t bc_pos = 0, cidx = 0, vch = 0;
-    u64 count = 0, block_elems = 0, part_elems = 0, sent = 0, recvd = 0, thr = 0;
-    const char* sendbuf = nullptr;
-    char* recvbuf = nullptr;
-    u64 *tail_out = nullptr, *head_out = nullptr, *tail_in = nullptr, *head_in = nullptr;
-    uint8_t *fifo_out = nullptr, *fifo_in = nullptr;
+    uint32_t coll = 0, sl = 0;
+    uint32_t g = 0, p = 0, cidx = 0;
+    u64 sent = 0, recvd = 0, thr = 0;
     bool progressed = false;
     uint32_t posted = 0, retired = 0;   // jobs handed to the movers / jobs whose bookkeeping is done
 
@@ -815,49 +805,25 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         } else if (lane == 0) bump(sh.stat, ST_HIT, 1);
         if (sw_pending && a.trace_on > 1) sw_le = wall_clock64();
         {
-          const DfxCtxEntry& C = sh.slot[sl];
-          kind = C.st.kind; dtype = C.st.dtype; bc_pos = C.st.bc_pos;
-          eb = (dtype == DT_F32 || dtype == DT_I32) ? 4u : 2u;
-          nprim = C.st.nprim; rounds = C.st.rounds; K = C.st.nslots; nchan = C.st.nchan;
-          slice_elems = C.st.slice_elems; slot_bytes = slice_elems * eb; seq = C.st.seq;
-          count = C.st.count; block_elems = C.st.block_elems; part_elems = C.st.part_elems;
-          sendbuf = (const char*)C.st.sendbuf;
-          recvbuf = (char*)C.st.recvbuf;
-          tail_out = (u64*)C.st.flags_out; head_out = tail_out + 8;
-          tail_in = (u64*)C.st.flags_in; head_in = tail_in + 8;
-          fifo_out = (uint8_t*)C.st.fifo_out;
-          fifo_in = (uint8_t*)C.st.fifo_in;
-          g = C.dyn.round; p = C.dyn.prim; sent = C.dyn.sent; recvd = C.dyn.recvd; cidx = C.dyn.cidx;
-          preempted_before = C.dyn.preempted;
-          vch = C.st.vch;
+          const DfxDyn& Y = sh.slot[sl].dyn;
+          g = Y.round; p = Y.prim; sent = Y.sent; recvd = Y.recvd; cidx = Y.cidx;
         }
-        // SetInitialSpinThreshold (Alg. 1 line 3): largest at the front, halving per position
+        // SetInitialSpinThreshold (Alg. 1 line 3): largest at the front, halving per position.
+        // In a scanned pass every entry visited was seen runnable, and the rest of the list is
+        // known work: waiting on one collective would only keep the movers idle, so the
+        // threshold stays at its minimum there.
         thr = a.spin_init >> (pos < 31 ? pos : 31);
-        if (thr < a.spin_min) thr = a.spin_min;
+        if (thr < a.spin_min || scanned) thr = a.spin_min;
         progressed = false;
         have = true;
       }
 
       // ================= next primitive of the collective in hand =================
-      const Prim q = make_prim(kind, a.R, bc_pos, p);
-      // slice geometry (elements relative to the block, clipped to the block's true length)
-      const bool ring_chunks = (kind == KIND_AR && a.R > 1);
-      u64 blen = count;
-      if (ring_chunks) {
-        const u64 start = (u64)cidx * block_elems;
-        blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
-      }
-      u64 lo = (u64)vch * part_elems + (u64)g * slice_elems;
-      u64 hi = lo + slice_elems;
-      const u64 pend = (u64)(vch + 1) * part_elems;
-      if (hi > pend) hi = pend;
-      if (lo > blen) lo = blen;
-      if (hi > blen) hi = blen;
-      const uint32_t bytes = (uint32_t)(hi - lo) * eb;
-      u64 soff = lo, doff = lo;   // element offsets in the send / recv buffer
-      if (ring_chunks) { soff += (u64)cidx * block_elems; doff = soff; }
-      else if (kind == KIND_RS) soff += (u64)cidx * count;
-      else if (kind == KIND_AG) doff += (u64)cidx * count;
+      const DfxCooked& S = sh.slot[sl].st;
+      const Prim q = make_prim((int)S.kind, a.R, S.bc_pos, p);
+      u64* const tail_out = (u64*)S.flags_out;
+      u64* const tail_in = (u64*)S.flags_in;
+      const uint32_t K = S.nslots;
 
       u64 tm0 = 0;
       if (a.trace_on > 1) tm0 = wall_clock64();
@@ -882,7 +848,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         for (;;) {
           bool ok = true;
           if (lane == 0 && q.recv) ok = ld_agent64(tail_in) > recvd;
-          if (lane == 1 && q.send) ok = (sent - ld_agent64(head_out)) < (u64)K;
+          if (lane == 1 && q.send) ok = (sent - ld_agent64(tail_out + 8)) < (u64)K;
           ++n;
           if (__ballot(!ok) == 0) break;
           retire_finished();
@@ -896,7 +862,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 if (acted) { last_act = now; acted = false; }
                 if (now - last_act > a.watchdog_ticks) {
                   ws->dbg[0] = ((u64)coll << 32) | qlen; ws->dbg[1] = ((u64)g << 32) | p; ws->dbg[2] = sent; ws->dbg[3] = recvd;
-                  ws->dbg[4] = ld_agent64(tail_in); ws->dbg[5] = ld_agent64(head_out); ws->dbg[6] = ri; ws->dbg[7] = now - last_act;
+                  ws->dbg[4] = ld_agent64(tail_in); ws->dbg[5] = ld_agent64(tail_out + 8); ws->dbg[6] = ri; ws->dbg[7] = now - last_act;
                   raise_error(a, 2u, wg);
                   s = 1;
                 }
@@ -912,30 +878,50 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       if (res == W_OK) {
         u64 tm1 = 0;
         if (a.trace_on > 1) { tm1 = wall_clock64(); if (lane == 0) bump(sh.stat, ST_T_WAIT, tm1 - tm0); }
-        const bool solo = !bytes || (coh && bytes <= SOLO_BYTES);
-        // a flight slot: at most two jobs are posted and not yet retired; a slice this wave moves
-        // itself (or an empty one, which is only a handshake) waits until the movers are idle, so
-        // that counters of one connector are raised in order
+        // a flight slot: at most two jobs are posted and not yet retired
         bool given_up = false;
-        while (posted - retired >= (solo ? 1u : 2u)) {
+        while (posted - retired >= 2u) {
           retire_finished();
-          if (posted - retired >= (solo ? 1u : 2u)) {
+          if (posted - retired >= 2u) {
             if ((++spins & 0xffffu) == 0 && abort_seen()) { given_up = true; break; }
             __builtin_amdgcn_s_sleep(1);
           }
         }
         if (given_up) { stop = STOP_ABORT; have = false; continue; }
+        // ---- slice geometry (elements relative to the block, clipped to the block's true length)
+        const int kind = S.kind, dtype = S.dtype;
+        const uint32_t eb = (dtype == DT_F32 || dtype == DT_I32) ? 4u : 2u;
+        const uint32_t slice_elems = S.slice_elems, vch = S.vch;
+        const u64 count = S.count, block_elems = S.block_elems, part_elems = S.part_elems;
+        const bool ring_chunks = (kind == KIND_AR && a.R > 1);
+        u64 blen = count;
+        if (ring_chunks) {
+          const u64 start = (u64)cidx * block_elems;
+          blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
+        }
+        u64 lo = (u64)vch * part_elems + (u64)g * slice_elems;
+        u64 hi = lo + slice_elems;
+        const u64 pend = (u64)(vch + 1) * part_elems;
+        if (hi > pend) hi = pend;
+        if (lo > blen) lo = blen;
+        if (hi > blen) hi = blen;
+        const uint32_t bytes = (uint32_t)(hi - lo) * eb;
+        u64 soff = lo, doff = lo;   // element offsets in the send / recv buffer
+        if (ring_chunks) { soff += (u64)cidx * block_elems; doff = soff; }
+        else if (kind == KIND_RS) soff += (u64)cidx * count;
+        else if (kind == KIND_AG) doff += (u64)cidx * count;
         // ---- claim the slots and step the sequence (the data follows, the counters after it)
-        const void* jfin = q.recv ? (const void*)(fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
-        void* jfout = q.send ? (void*)(fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
-        const char* jsb = q.from_send ? sendbuf + soff * eb : nullptr;
-        char* jrb = q.to_recv ? recvbuf + doff * eb : nullptr;
+        const size_t slot_bytes = (size_t)slice_elems * eb;
+        const void* jfin = q.recv ? (const void*)((const uint8_t*)S.fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
+        void* jfout = q.send ? (void*)((uint8_t*)S.fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
+        const char* jsb = q.from_send ? (const char*)S.sendbuf + soff * eb : nullptr;
+        char* jrb = q.to_recv ? (char*)S.recvbuf + doff * eb : nullptr;
         const uint32_t this_p = p;
         if (q.send) ++sent;
         if (q.recv) ++recvd;
         // next primitive: the chunk index steps down the ring; a new round starts over
         cidx = (cidx == 0) ? a.R - 1 : cidx - 1;
-        if (++p == nprim) {
+        if (++p == S.nprim) {
           p = 0; ++g;
           cidx = (kind == KIND_AG) ? rank : ((kind == KIND_BC || a.R == 1) ? 0u : cidx0_reduce);
         }
@@ -944,53 +930,34 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         pass_progress = true;
         acted = true;
         // AdaptivelyAdjustSpinThreshold (Alg. 1 line 9)
-        thr *= a.spin_boost;
-        if (thr > a.spin_max) thr = a.spin_max;
-        const bool last = (g == rounds);
-
-        if (solo) {
-          if (bytes) {
-            run_prim<AUX_DEVICE, 64>(dtype, jfin, jsb, jrb, jfout, bytes, lane);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            __builtin_amdgcn_s_waitcnt(0);
-          }
-          u64 tm2 = 0;
-          if (a.trace_on > 1) tm2 = wall_clock64();
-          if (lane == 0) {
-            if (!coh) fence_release_agent();
-            if (q.send) raise_counter(tail_out, sent);
-            if (q.recv) raise_counter(head_in, recvd);
-            bump(sh.stat, ST_PRIMS, 1);
-            if (a.trace_on > 1) {
-              bump(sh.stat, ST_T_DATA, tm2 - tm1); bump(sh.stat, ST_T_PUB, wall_clock64() - tm2);
-              if (a.trace_on == 3 && trace) trace_put(trace, &sh.trace_n, timeline_sample(tm1, tm2, coll, this_p));
-            }
-          }
-        } else {
-          if (lane == 0) {
-            Job j;
-            j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
-            j.bytes = bytes; j.dtype = dtype; j.coll = coll; j.prim = this_p;
-            sh.job[posted & 1] = j;
-            Flight f;
-            f.tail_out = q.send ? tail_out : nullptr; f.head_in = q.recv ? head_in : nullptr;
-            f.sent_new = sent; f.recvd_new = recvd;
-            f.last = last ? 1u : 0u; f.coll = coll; f.seq = seq; f.nchan = nchan;
-            sh.fl[posted & 1] = f;
-            lds_st(&sh.job_seq, posted + 1);
-          }
-          ++posted;
+        if (!scanned) {
+          thr *= a.spin_boost;
+          if (thr > a.spin_max) thr = a.spin_max;
         }
+        const bool last = (g == S.rounds);
+
+        // ---- post the slice (an empty one is only a handshake: the movers just raise the counters)
+        if (lane == 0) {
+          Job j;
+          j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
+          j.bytes = bytes; j.dtype = dtype; j.coll = coll; j.prim = this_p;
+          sh.job[posted & 1] = j;
+          Flight f;
+          f.tail_out = q.send ? tail_out : nullptr; f.head_in = q.recv ? tail_in + 8 : nullptr;
+          f.sent_new = sent; f.recvd_new = recvd;
+          f.last = last ? 1u : 0u; f.coll = coll; f.seq = S.seq; f.nchan = S.nchan;
+          sh.fl[posted & 1] = f;
+          lds_st(&sh.job_seq, posted + 1);
+        }
+        ++posted;
 
         if (last) {
           // ---- CollectiveSuccess: the entry leaves the queue now; the completion counter and the
-          // CQE follow when the data is in memory (here for a slice this wave moved, at retirement
-          // for a posted one)
+          // CQE follow at retirement, when the data is in memory
           if (lane == 0) {
             DfxDyn d; d.round = 0; d.prim = 0; d.sent = sent; d.recvd = recvd; d.preempted = 0; d.cidx = 0;
             sh.slot[sl].dyn = d;
             myctx[coll].dyn = d;
-            if (solo) complete(coll, seq, nchan);
           }
           // later entries move up, the position stays (Sec. 4.3)
           --qlen;
@@ -1016,7 +983,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           if (res == W_TIMEOUT) bump(sh.stat, ST_PREEMPT, 1);
           if (progressed) {
             DfxDyn d; d.round = g; d.prim = p; d.sent = sent; d.recvd = recvd;
-            d.preempted = preempted_before + 1; d.cidx = cidx;
+            d.preempted = sh.slot[sl].dyn.preempted + 1; d.cidx = cidx;
             sh.slot[sl].dyn = d;
             myctx[coll].dyn = d;
             bump(sh.stat, ST_SAVE, 1);

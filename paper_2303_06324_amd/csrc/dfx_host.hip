@@ -255,7 +255,7 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->slot_bytes = 128u << 10;
   cfg->chan_min_bytes = 16u << 10;
   cfg->spin_init = 16;
-  cfg->spin_min = 2;
+  cfg->spin_min = 1;
   cfg->spin_max = 64;
   cfg->spin_boost = 2;
   cfg->fetch_batch = 0;
@@ -312,6 +312,11 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   int occ = 0, ncu = 0, wall_khz = 0, large_bar = 0;
   INITCHK(dfx_daemon_occupancy(&occ));
   INITCHK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device));
+  // A workgroup whose wavefront count is not a multiple of the four SIMDs of a compute unit loads them
+  // unevenly, and which SIMD gets the extra wavefront is the dispatcher's choice: two such
+  // workgroups may not fit one compute unit even when the register arithmetic says they do.
+  // Count one per compute unit then.
+  if (((DFX_WG_THREADS / 64) & 3) != 0 && occ > 1) occ = 1;
   if (occ < 1 || (uint64_t)c->nwg > (uint64_t)occ * (uint64_t)ncu) { free_all(c); return DFX_ERR_NO_RESOURCES; }
   if (hipDeviceGetAttribute(&wall_khz, hipDeviceAttributeWallClockRate, c->device) == hipSuccess && wall_khz > 0)
     c->tick_us = 1000.0 / (double)wall_khz;

@@ -4,8 +4,10 @@
 
 #include <stdint.h>
 
-#define DFX_WG_THREADS 320      // threads per daemon workgroup: one scheduler wavefront + four mover wavefronts
-#define DFX_MOVERS 256          // threads of the mover wavefronts
+#ifndef DFX_WG_THREADS
+#define DFX_WG_THREADS 320      // threads per daemon workgroup: one scheduler wavefront + the mover wavefronts
+#endif
+#define DFX_MOVERS (DFX_WG_THREADS - 64)   // threads of the mover wavefronts
 #define DFX_MAX_COLLS 4096      // upper bound for dfx_config.max_colls (LDS task queue = 8 KB)
 #define DFX_CTX_SLOTS 4         // LDS active context slots, direct-mapped by coll_id (Sec. 5)
 #define DFX_TRACE_N 4096        // context-switch latency samples kept per workgroup
