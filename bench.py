@@ -265,6 +265,12 @@ def main():
         launches = ctx.stats(0)["launches"]
     finally:
         ctx.finalize()
+    # what a plain copy kernel reaches on this chip (reads + writes over its HIP-event time): context
+    # for the roofline fraction, which is priced against the published 8 TB/s
+    copy_ms = []
+    for rep in range(3):
+        copy_ms.append(sum(dfx.copy_calibrate(send[r].data_ptr(), recv[r].data_ptr(), M) for r in range(R)))
+    copy_gbs = 2 * R * M / (min(copy_ms) * 1e-3) / 1e9
     if args.calibrate_copy_mib:
         nb = min(args.calibrate_copy_mib << 20, M)
         dfx.copy_calibrate(send[0].data_ptr(), recv[0].data_ptr(), nb)
@@ -291,6 +297,7 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES if args.msg_mib == 256 else None,
                      "kernel": "dfx_daemon_kernel", "kernel_ms_avg": round(k_ms, 4),
                      "algorithmic_bytes_per_launch": algorithmic_bytes(M, R)},
+        "copy_kernel_GBs": round(copy_gbs, 1),
     }
     del send, recv
     torch.cuda.empty_cache()

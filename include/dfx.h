@@ -234,8 +234,9 @@ const char* dfx_strerror(int status);
 
 /* Measurement aid, not part of the method: copy `bytes` (multiple of 16) from src to dst (both
    device) with a plain grid-stride kernel on hip_stream (NULL = the null stream) and wait.  Its
-   known traffic calibrates the profiler's HBM byte counters. */
-int dfx_copy_calibrate(const void* src, void* dst, size_t bytes, void* hip_stream);
+   known traffic calibrates the profiler's HBM byte counters; with ms != NULL (host) the kernel is
+   timed with HIP events on that stream, which gives the copy bandwidth the chip reaches. */
+int dfx_copy_calibrate(const void* src, void* dst, size_t bytes, void* hip_stream, float* ms);
 
 #ifdef __cplusplus
 }

@@ -80,7 +80,7 @@ def _load() -> C.CDLL:
         "dfx_last_hip_error": ([vp], i),
         "dfx_last_init_error": ([], i),
         "dfx_strerror": ([i], C.c_char_p),
-        "dfx_copy_calibrate": ([vp, vp, sz, vp], i),
+        "dfx_copy_calibrate": ([vp, vp, sz, vp, C.POINTER(C.c_float)], i),
     }
     for name, (args, res) in sig.items():
         f = getattr(lib, name)
@@ -203,7 +203,11 @@ class Context:
             pass
 
 
-def copy_calibrate(src: int, dst: int, nbytes: int, stream: Optional[int] = None) -> None:
-    rc = _lib.dfx_copy_calibrate(C.c_void_p(src), C.c_void_p(dst), nbytes, C.c_void_p(stream) if stream else None)
+def copy_calibrate(src: int, dst: int, nbytes: int, stream: Optional[int] = None) -> float:
+    """Plain copy kernel of known traffic; returns its duration in milliseconds (HIP events)."""
+    ms = C.c_float()
+    rc = _lib.dfx_copy_calibrate(C.c_void_p(src), C.c_void_p(dst), nbytes, C.c_void_p(stream) if stream else None,
+                                 C.byref(ms))
     if rc != OK:
         raise DfxError(rc, "dfx_copy_calibrate")
+    return ms.value

@@ -790,9 +790,10 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         }
         if (scanned) {
           // entries completed earlier in this pass moved the later ones up by one each
-          if (rk >= nready) { in_pass = false; continue; }
+          // (a pass that ends is not a switch between two collectives: the latency sample is dropped)
+          if (rk >= nready) { in_pass = false; sw_pending = false; continue; }
           pos = (uint32_t)sh.rlist[rk] - removed;
-        } else if (pos >= qlen) { in_pass = false; continue; }
+        } else if (pos >= qlen) { in_pass = false; sw_pending = false; continue; }
 
         // ---- LoadCollectiveContext: HBM context buffer -> LDS slot, 8 lanes x 16 bytes
         coll = sh.taskq[pos];
@@ -1016,10 +1017,18 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   for (uint32_t i = tid; i < qn; i += NT) qstore[i] = sh.taskq[i];
 }
 
-// Plain copy kernel of known traffic: calibrates the HBM byte counters of the profiler.
+// Plain copy kernel of known traffic: calibrates the HBM byte counters of the profiler and shows
+// what a streaming copy reaches.  Four independent 16-byte vectors in flight per thread.
 extern "C" __global__ void __launch_bounds__(256) dfx_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t nvec) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < nvec; i += 4 * stride) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = ld_user(&src[i + u * stride]);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) st_user(&dst[i + u * stride], v[u]);
+  }
   for (; i < nvec; i += stride) dst[i] = src[i];
 }
 
@@ -1036,6 +1045,6 @@ hipError_t dfx_daemon_launch(uint32_t nwg, hipStream_t stream, const DfxDaemonAr
 }
 
 hipError_t dfx_copy_launch(const void* src, void* dst, size_t bytes, hipStream_t stream) {
-  hipLaunchKernelGGL(dfx_copy_kernel, dim3(2048), dim3(256), 0, stream, (const uint4*)src, (uint4*)dst, bytes >> 4);
+  hipLaunchKernelGGL(dfx_copy_kernel, dim3(4096), dim3(256), 0, stream, (const uint4*)src, (uint4*)dst, bytes >> 4);
   return hipGetLastError();
 }

@@ -729,12 +729,25 @@ const char* dfx_strerror(int s) {
 // Calibration helper for the profiler's HBM byte counters: copies `bytes` (multiple of 16)
 // from src to dst (both device) with a plain kernel on the given stream (NULL = private
 // stream) and waits for it.
-int dfx_copy_calibrate(const void* src, void* dst, size_t bytes, void* hip_stream) {
+int dfx_copy_calibrate(const void* src, void* dst, size_t bytes, void* hip_stream, float* ms) {
   if (!src || !dst || (bytes & 15u)) return DFX_ERR_INVALID_ARG;
   hipStream_t s = (hipStream_t)hip_stream;
-  if (dfx_copy_launch(src, dst, bytes, s) != hipSuccess) return DFX_ERR_HIP;
-  if (hipStreamSynchronize(s) != hipSuccess) return DFX_ERR_HIP;
-  return DFX_OK;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (ms) {
+    if (hipEventCreate(&e0) != hipSuccess) return DFX_ERR_HIP;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return DFX_ERR_HIP; }
+    (void)hipEventRecord(e0, s);
+  }
+  int rc = DFX_OK;
+  if (dfx_copy_launch(src, dst, bytes, s) != hipSuccess) rc = DFX_ERR_HIP;
+  if (ms) (void)hipEventRecord(e1, s);
+  if (hipStreamSynchronize(s) != hipSuccess) rc = DFX_ERR_HIP;
+  if (ms) {
+    if (rc == DFX_OK && hipEventElapsedTime(ms, e0, e1) != hipSuccess) rc = DFX_ERR_HIP;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+  }
+  return rc;
 }
 
 }  // extern "C"
