@@ -25,10 +25,25 @@ mod R), one rounding per + in the storage dtype.  FIFO slices and channels of
 the GPU path only subdivide a chunk; they never move an element to another
 chunk, so the values do not depend on them.
 
+The `reduce` collective (Sec. 4.1 lists it with the others) is the same
+reduce phase run along a chain that ends at the root: rank root+1 sends its
+whole buffer, the ranks after it receive, combine with their own and forward,
+the root receives, combines and keeps.  The root's result is therefore the
+left fold  ((x[root+1] (+) x[root+2]) (+) ...) (+) x[root]; the other ranks'
+recv buffers are not written.
+
+The reducing function (Sec. 4.1: "a specified reducing function") may be sum,
+product, maximum or minimum; `partial (op) own` is evaluated at every hop with
+the partial that arrived from the left as the first operand.
+
 Arithmetic (the paper is silent; this is the reading taken): fp32 = one
 IEEE binary32 round-to-nearest-even add per hop, gradual underflow; fp16 and
 bf16 = widen both operands to fp32, add, round to nearest even back to 16 bits
 at every hop (partials travel in the storage dtype); int32 = wraparound.
+Product follows the same rule with * for +.  Maximum / minimum select one of
+the two operands unchanged:  max = partial if partial > own else own,
+min = partial if partial < own else own  (so equal values, +0 / -0 included,
+yield the own operand; NaN is outside what is tested).
 
 Two implementations live here on purpose: `*_replay` literally runs R rank
 objects exchanging chunks through per-edge queues with the seven primitives;
@@ -38,6 +53,8 @@ adds and integer-valued inputs.
 
 bf16 buffers are numpy uint16 bit patterns; fp16 = numpy float16; fp32 =
 float32; int32 = int32.  dtype codes: 0 fp32, 1 bf16, 2 fp16, 3 int32.
+op codes: 0 sum, 1 product, 2 maximum, 3 minimum.  kind codes: 0 all-reduce,
+1 all-gather, 2 reduce-scatter, 3 broadcast, 4 reduce.
 """
 from __future__ import annotations
 
@@ -47,6 +64,7 @@ from typing import List, Sequence, Tuple
 import numpy as np
 
 F32, BF16, F16, I32 = 0, 1, 2, 3
+SUM, PROD, MAX, MIN = 0, 1, 2, 3
 ELEM_BYTES = {F32: 4, BF16: 2, F16: 2, I32: 4}
 
 
@@ -81,6 +99,45 @@ def add_hop(a: np.ndarray, b: np.ndarray, dtype: int) -> np.ndarray:
     raise ValueError(f"dtype {dtype}")
 
 
+def mul_hop(a: np.ndarray, b: np.ndarray, dtype: int) -> np.ndarray:
+    """One product hop a (*) b with a single rounding in the storage dtype."""
+    if dtype == F32:
+        return (a.astype(np.float32, copy=False) * b.astype(np.float32, copy=False)).astype(np.float32)
+    if dtype == F16:
+        return (a.astype(np.float32) * b.astype(np.float32)).astype(np.float16)
+    if dtype == BF16:
+        return f32_to_bf16_bits_rne(bf16_bits_to_f32(a) * bf16_bits_to_f32(b))
+    if dtype == I32:
+        return (a.view(np.uint32) * b.view(np.uint32)).view(np.int32)
+    raise ValueError(f"dtype {dtype}")
+
+
+def _ordered(a: np.ndarray, dtype: int) -> np.ndarray:
+    """The values comparisons are made on (bf16 bit patterns are widened; the rest compare as stored)."""
+    return bf16_bits_to_f32(a) if dtype == BF16 else a
+
+
+def select_hop(a: np.ndarray, b: np.ndarray, dtype: int, want_max: bool) -> np.ndarray:
+    """Maximum / minimum hop: the partial `a` if it is strictly greater (smaller) than the own
+    value `b`, else `b`; the chosen operand is passed on bit for bit."""
+    va, vb = _ordered(a, dtype), _ordered(b, dtype)
+    take_a = (va > vb) if want_max else (va < vb)
+    return np.where(take_a, a, b).astype(a.dtype)
+
+
+def op_hop(a: np.ndarray, b: np.ndarray, dtype: int, op: int) -> np.ndarray:
+    """partial (op) own for one hop."""
+    if op == SUM:
+        return add_hop(a, b, dtype)
+    if op == PROD:
+        return mul_hop(a, b, dtype)
+    if op == MAX:
+        return select_hop(a, b, dtype, True)
+    if op == MIN:
+        return select_hop(a, b, dtype, False)
+    raise ValueError(f"op {op}")
+
+
 def to_f64(a: np.ndarray, dtype: int) -> np.ndarray:
     if dtype == BF16:
         return bf16_bits_to_f32(a).astype(np.float64)
@@ -108,8 +165,8 @@ class _Rank:
     """One rank's four buffers (Sec. 4.1): send buffer, recv buffer, and the
     send / recv connectors (here: queues towards r+1 and from r-1)."""
 
-    def __init__(self, r, R, sendbuf, recvbuf, dtype, q_in, q_out):
-        self.r, self.R, self.dtype = r, R, dtype
+    def __init__(self, r, R, sendbuf, recvbuf, dtype, q_in, q_out, op=SUM):
+        self.r, self.R, self.dtype, self.op = r, R, dtype, op
         self.sendbuf, self.recvbuf = sendbuf, recvbuf
         self.q_in, self.q_out = q_in, q_out
         self.pc = 0            # index of the next primitive in this rank's sequence
@@ -136,13 +193,13 @@ class _Rank:
     def recv_reduce_send(self, s, d):
         if not self._readable():
             return False
-        self.q_out.append(add_hop(self.q_in.popleft(), self.sendbuf[s[0]:s[1]], self.dtype))
+        self.q_out.append(op_hop(self.q_in.popleft(), self.sendbuf[s[0]:s[1]], self.dtype, self.op))
         return True
 
     def recv_reduce_copy_send(self, s, d):
         if not self._readable():
             return False
-        x = add_hop(self.q_in.popleft(), self.sendbuf[s[0]:s[1]], self.dtype)
+        x = op_hop(self.q_in.popleft(), self.sendbuf[s[0]:s[1]], self.dtype, self.op)
         self.recvbuf[d[0]:d[1]] = x
         self.q_out.append(x)
         return True
@@ -150,7 +207,7 @@ class _Rank:
     def recv_reduce_copy(self, s, d):
         if not self._readable():
             return False
-        self.recvbuf[d[0]:d[1]] = add_hop(self.q_in.popleft(), self.sendbuf[s[0]:s[1]], self.dtype)
+        self.recvbuf[d[0]:d[1]] = op_hop(self.q_in.popleft(), self.sendbuf[s[0]:s[1]], self.dtype, self.op)
         return True
 
     def recv_copy_send(self, s, d):
@@ -191,20 +248,20 @@ def _run(ranks: Sequence[_Rank]) -> None:
         assert len(k.q_in) == 0, "a connector still holds data: something was sent but never received"
 
 
-def _make_ranks(sends, recv_elems, dtype):
+def _make_ranks(sends, recv_elems, dtype, op=SUM):
     R = len(sends)
     queues = [deque() for _ in range(R)]          # queues[r] = edge r -> r+1
     recvs = [np.zeros(recv_elems, dtype=sends[0].dtype) for _ in range(R)]
-    ranks = [_Rank(r, R, sends[r], recvs[r], dtype, queues[(r - 1) % R], queues[r]) for r in range(R)]
+    ranks = [_Rank(r, R, sends[r], recvs[r], dtype, queues[(r - 1) % R], queues[r], op) for r in range(R)]
     return ranks, recvs
 
 
 # ----------------------------------------------------------------------------
 # all-reduce
 # ----------------------------------------------------------------------------
-def all_reduce_replay(sends: Sequence[np.ndarray], dtype: int) -> List[np.ndarray]:
+def all_reduce_replay(sends: Sequence[np.ndarray], dtype: int, op: int = SUM) -> List[np.ndarray]:
     R, N = len(sends), len(sends[0])
-    ranks, recvs = _make_ranks(sends, N, dtype)
+    ranks, recvs = _make_ranks(sends, N, dtype, op)
     if R == 1:
         ranks[0].prog = [("copy", (0, N), (0, N))]
         _run(ranks)
@@ -226,16 +283,16 @@ def all_reduce_replay(sends: Sequence[np.ndarray], dtype: int) -> List[np.ndarra
     return recvs
 
 
-def fold_rotated(blocks: Sequence[np.ndarray], start: int, dtype: int) -> np.ndarray:
-    """((b[start] + b[start+1]) + ...) + b[start-1], indices mod R."""
+def fold_rotated(blocks: Sequence[np.ndarray], start: int, dtype: int, op: int = SUM) -> np.ndarray:
+    """((b[start] (op) b[start+1]) (op) ...) (op) b[start-1], indices mod R."""
     R = len(blocks)
     v = blocks[start % R].copy()
     for j in range(1, R):
-        v = add_hop(v, blocks[(start + j) % R], dtype)
+        v = op_hop(v, blocks[(start + j) % R], dtype, op)
     return v
 
 
-def all_reduce_fold(sends: Sequence[np.ndarray], dtype: int) -> np.ndarray:
+def all_reduce_fold(sends: Sequence[np.ndarray], dtype: int, op: int = SUM) -> np.ndarray:
     """Closed form: the buffer every rank ends with."""
     R, N = len(sends), len(sends[0])
     out = np.zeros(N, dtype=sends[0].dtype)
@@ -244,17 +301,17 @@ def all_reduce_fold(sends: Sequence[np.ndarray], dtype: int) -> np.ndarray:
         return out
     for c, (lo, hi) in enumerate(chunk_bounds(N, R, ELEM_BYTES[dtype])):
         if hi > lo:
-            out[lo:hi] = fold_rotated([x[lo:hi] for x in sends], c + 1, dtype)
+            out[lo:hi] = fold_rotated([x[lo:hi] for x in sends], c + 1, dtype, op)
     return out
 
 
 # ----------------------------------------------------------------------------
 # reduce-scatter: send holds R blocks of `count`; rank r ends with block r reduced
 # ----------------------------------------------------------------------------
-def reduce_scatter_replay(sends: Sequence[np.ndarray], dtype: int) -> List[np.ndarray]:
+def reduce_scatter_replay(sends: Sequence[np.ndarray], dtype: int, op: int = SUM) -> List[np.ndarray]:
     R = len(sends)
     count = len(sends[0]) // R
-    ranks, recvs = _make_ranks(sends, count, dtype)
+    ranks, recvs = _make_ranks(sends, count, dtype, op)
     blk = lambda j: ((j % R) * count, (j % R + 1) * count)
     for k in ranks:
         r = k.r
@@ -269,10 +326,10 @@ def reduce_scatter_replay(sends: Sequence[np.ndarray], dtype: int) -> List[np.nd
     return recvs
 
 
-def reduce_scatter_fold(sends: Sequence[np.ndarray], dtype: int) -> List[np.ndarray]:
+def reduce_scatter_fold(sends: Sequence[np.ndarray], dtype: int, op: int = SUM) -> List[np.ndarray]:
     R = len(sends)
     count = len(sends[0]) // R
-    return [fold_rotated([x[r * count:(r + 1) * count] for x in sends], r + 1, dtype) for r in range(R)]
+    return [fold_rotated([x[r * count:(r + 1) * count] for x in sends], r + 1, dtype, op) for r in range(R)]
 
 
 # ----------------------------------------------------------------------------
@@ -324,6 +381,31 @@ def broadcast_definition(sends: Sequence[np.ndarray], root: int) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
+# reduce: chain root+1 -> root+2 -> ... -> root; only the root's recv buffer is written
+# ----------------------------------------------------------------------------
+def reduce_replay(sends: Sequence[np.ndarray], root: int, dtype: int, op: int = SUM) -> List[np.ndarray]:
+    R, N = len(sends), len(sends[0])
+    ranks, recvs = _make_ranks(sends, N, dtype, op)
+    for k in ranks:
+        pos = (k.r - root - 1) % R      # place in the chain: 0 = first sender, R-1 = the root
+        if R == 1:
+            k.prog = [("copy", (0, N), (0, N))]
+        elif pos == 0:
+            k.prog = [("send", (0, N), (0, 0))]
+        elif pos == R - 1:
+            k.prog = [("recv_reduce_copy", (0, N), (0, N))]
+        else:
+            k.prog = [("recv_reduce_send", (0, N), (0, 0))]
+    _run(ranks)
+    return recvs
+
+
+def reduce_fold(sends: Sequence[np.ndarray], root: int, dtype: int, op: int = SUM) -> np.ndarray:
+    """Closed form: what the root ends with."""
+    return fold_rotated(list(sends), root + 1, dtype, op)
+
+
+# ----------------------------------------------------------------------------
 # order-independent references and dispatch
 # ----------------------------------------------------------------------------
 def sum_f64(blocks: Sequence[np.ndarray], dtype: int) -> np.ndarray:
@@ -340,30 +422,37 @@ def abs_sum_f64(blocks: Sequence[np.ndarray], dtype: int) -> np.ndarray:
     return acc
 
 
-def run_replay(kind: int, sends: Sequence[np.ndarray], dtype: int, root: int = 0) -> List[np.ndarray]:
-    """kind: 0 all-reduce, 1 all-gather, 2 reduce-scatter, 3 broadcast. Returns every rank's recv buffer."""
+def run_replay(kind: int, sends: Sequence[np.ndarray], dtype: int, root: int = 0, op: int = SUM) -> List[np.ndarray]:
+    """kind: 0 all-reduce, 1 all-gather, 2 reduce-scatter, 3 broadcast, 4 reduce.  Returns every rank's
+    recv buffer (reduce: zeros on the ranks that are not the root, which the collective does not write)."""
     if kind == 0:
-        return all_reduce_replay(sends, dtype)
+        return all_reduce_replay(sends, dtype, op)
     if kind == 1:
         return all_gather_replay(sends, dtype)
     if kind == 2:
-        return reduce_scatter_replay(sends, dtype)
+        return reduce_scatter_replay(sends, dtype, op)
     if kind == 3:
         return broadcast_replay(sends, root, dtype)
+    if kind == 4:
+        return reduce_replay(sends, root, dtype, op)
     raise ValueError(f"kind {kind}")
 
 
-def run_closed_form(kind: int, sends: Sequence[np.ndarray], dtype: int, root: int = 0) -> List[np.ndarray]:
+def run_closed_form(kind: int, sends: Sequence[np.ndarray], dtype: int, root: int = 0, op: int = SUM) -> List[np.ndarray]:
     R = len(sends)
     if kind == 0:
-        v = all_reduce_fold(sends, dtype)
+        v = all_reduce_fold(sends, dtype, op)
         return [v] * R
     if kind == 1:
         v = all_gather_definition(sends)
         return [v] * R
     if kind == 2:
-        return reduce_scatter_fold(sends, dtype)
+        return reduce_scatter_fold(sends, dtype, op)
     if kind == 3:
         v = broadcast_definition(sends, root)
         return [v] * R
+    if kind == 4:
+        v = reduce_fold(sends, root, dtype, op)
+        zero = np.zeros_like(v)
+        return [v if r == root % R else zero for r in range(R)]
     raise ValueError(f"kind {kind}")

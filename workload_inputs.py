@@ -7,10 +7,11 @@ the shapes of the five benchmark configurations (circular wait, size sweep,
 gradient buckets in random order, mixed collectives, many small all-reduces).
 
 Encodings (shared with the C ABI enums, restated here as plain integers):
-  kind : 0 all-reduce, 1 all-gather, 2 reduce-scatter, 3 broadcast
+  kind : 0 all-reduce, 1 all-gather, 2 reduce-scatter, 3 broadcast, 4 reduce
+  op   : 0 sum, 1 product, 2 maximum, 3 minimum
   dtype: 0 fp32, 1 bf16 (carried as uint16 bit patterns), 2 fp16, 3 int32
 
-Count convention: all-reduce / broadcast: elements per rank; all-gather:
+Count convention: all-reduce / broadcast / reduce: elements per rank; all-gather:
 elements each rank contributes (recv holds R*count); reduce-scatter: elements
 each rank receives (send holds R*count).
 """
@@ -21,10 +22,12 @@ from typing import List
 
 import numpy as np
 
-AR, AG, RS, BC = 0, 1, 2, 3
+AR, AG, RS, BC, RD = 0, 1, 2, 3, 4
+SUM, PROD, MAX, MIN = 0, 1, 2, 3
 F32, BF16, F16, I32 = 0, 1, 2, 3
 
-KIND_NAMES = {AR: "all_reduce", AG: "all_gather", RS: "reduce_scatter", BC: "broadcast"}
+KIND_NAMES = {AR: "all_reduce", AG: "all_gather", RS: "reduce_scatter", BC: "broadcast", RD: "reduce"}
+OP_NAMES = {SUM: "sum", PROD: "prod", MAX: "max", MIN: "min"}
 DTYPE_NAMES = {F32: "fp32", BF16: "bf16", F16: "fp16", I32: "int32"}
 ELEM_BYTES = {F32: 4, BF16: 2, F16: 2, I32: 4}
 NP_STORAGE = {F32: np.float32, BF16: np.uint16, F16: np.float16, I32: np.int32}
@@ -40,6 +43,7 @@ class CollSpec:
     dtype: int
     count: int
     root: int = 0
+    op: int = 0
 
     def send_elems(self, R: int) -> int:
         return self.count * R if self.kind == RS else self.count
