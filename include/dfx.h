@@ -32,9 +32,15 @@ extern "C" {
 
 typedef struct dfx_ctx dfx_ctx; /* opaque, library-owned */
 
-typedef enum { DFX_ALLREDUCE = 0, DFX_ALLGATHER = 1, DFX_REDUCESCATTER = 2, DFX_BROADCAST = 3 } dfx_kind;
+/* The collectives of Sec. 4.1.  DFX_REDUCE: a chain that ends at the root (rank root+1 sends, the ranks
+   after it combine and forward, the root combines and keeps); only the root's recv buffer is written. */
+typedef enum { DFX_ALLREDUCE = 0, DFX_ALLGATHER = 1, DFX_REDUCESCATTER = 2, DFX_BROADCAST = 3, DFX_REDUCE = 4 } dfx_kind;
 typedef enum { DFX_F32 = 0, DFX_BF16 = 1, DFX_F16 = 2, DFX_I32 = 3 } dfx_dtype;
-typedef enum { DFX_SUM = 0 } dfx_op; /* Sec. 4.1 "reducing function"; only sum is built */
+/* Sec. 4.1 "reducing function", evaluated at every hop as partial (op) own, the partial that arrived
+   first.  Sum and product round once per hop in the storage type (16-bit types: widen to fp32, operate,
+   round to nearest even; int32 wraps).  Maximum / minimum pass on the partial if it is strictly greater
+   (smaller), else the own value, bit for bit; NaN inputs are not supported. */
+typedef enum { DFX_SUM = 0, DFX_PROD = 1, DFX_MAX = 2, DFX_MIN = 3 } dfx_op;
 
 typedef enum {
   DFX_OK = 0,
@@ -136,10 +142,11 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* cfg, void* hip_stream)
 
 /*
  * Register collective coll_id on every vrank (= dfcclRegister* on each rank of the device set,
- * Sec. 3.2): fixes kind, element count, dtype, op, root (broadcast only) and priority (larger =
+ * Sec. 3.2): fixes kind, element count, dtype, op (ignored by all-gather and broadcast), root
+ * (broadcast and reduce) and priority (larger =
  * more urgent; only used by the priority order policy), assigns its connectors (exclusive to
  * this collective, Sec. 4.5) and its channel count.  May be called while the daemon runs.
- * count: all-reduce / broadcast: elements per rank; all-gather: elements each rank contributes
+ * count: all-reduce / broadcast / reduce: elements per rank; all-gather: elements each rank contributes
  * (recv buffers hold nranks*count); reduce-scatter: elements each rank receives (send buffers
  * hold nranks*count).  Errors: INVALID_ARG (id out of range or already prepared, unknown enum),
  * NO_RESOURCES (connector pool exhausted).

@@ -12,9 +12,9 @@ from typing import List, Optional, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdfx.so")
 
-ALLREDUCE, ALLGATHER, REDUCESCATTER, BROADCAST = 0, 1, 2, 3
+ALLREDUCE, ALLGATHER, REDUCESCATTER, BROADCAST, REDUCE = 0, 1, 2, 3, 4
 F32, BF16, F16, I32 = 0, 1, 2, 3
-SUM = 0
+SUM, PROD, MAX, MIN = 0, 1, 2, 3
 
 OK = 0
 ERR_INVALID_ARG, ERR_NOT_PREPARED, ERR_BUSY, ERR_SQ_FULL = -1, -2, -3, -4

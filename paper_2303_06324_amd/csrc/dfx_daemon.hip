@@ -39,7 +39,7 @@ constexpr int NT = DFX_WG_THREADS;
 #define DFX_UNROLL 8
 #endif
 constexpr int UNROLL = DFX_UNROLL;   // independent 16-byte vectors in flight per source and thread
-constexpr int KIND_AR = 0, KIND_AG = 1, KIND_RS = 2, KIND_BC = 3;
+constexpr int KIND_AR = 0, KIND_AG = 1, KIND_RS = 2, KIND_BC = 3, KIND_RD = 4;
 constexpr int DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_I32 = 3, DT_COPY = -1;
 
 enum { W_OK = 0, W_TIMEOUT = 1, W_STOP = 2 };
@@ -107,6 +107,66 @@ __device__ __forceinline__ uint16_t add_half(uint16_t a, uint16_t b) {
   return (uint16_t)(bf16x2_add(a, b) & 0xffffu);
 }
 
+// The other reducing functions (Sec. 4.1: "a specified reducing function"), evaluated as
+// partial (op) own with the partial that arrived from the left first.  Product rounds once per
+// hop like the sum; maximum / minimum pass one operand on unchanged: the partial if it is
+// strictly greater (smaller), else the own value -- plain compare-and-select, so that equal
+// values (+0 / -0 included) behave the same everywhere.
+enum { OP_SUM = 0, OP_PROD = 1, OP_MAX = 2, OP_MIN = 3 };
+
+__device__ __forceinline__ uint32_t bf16x2_op(uint32_t a, uint32_t b, int op) {
+  const float al = __uint_as_float(a << 16), bl = __uint_as_float(b << 16);
+  const float ah = __uint_as_float(a & 0xffff0000u), bh = __uint_as_float(b & 0xffff0000u);
+  if (op == OP_PROD) {
+    uint32_t ul = __float_as_uint(al * bl), uh = __float_as_uint(ah * bh);
+    ul = (ul + 0x7fffu + ((ul >> 16) & 1u)) >> 16;
+    uh = (uh + 0x7fffu + ((uh >> 16) & 1u)) & 0xffff0000u;
+    return uh | ul;
+  }
+  const bool tl = (op == OP_MAX) ? (al > bl) : (al < bl);
+  const bool th = (op == OP_MAX) ? (ah > bh) : (ah < bh);
+  return ((tl ? a : b) & 0xffffu) | ((th ? a : b) & 0xffff0000u);
+}
+
+template <int DT>
+__device__ __forceinline__ uint32_t op_word(uint32_t a, uint32_t b, int op) {
+  if (op == OP_SUM) return add_word<DT>(a, b);
+  if (DT == DT_F32) {
+    const float x = __uint_as_float(a), y = __uint_as_float(b);
+    if (op == OP_PROD) return __float_as_uint(x * y);
+    return ((op == OP_MAX) ? (x > y) : (x < y)) ? a : b;
+  }
+  if (DT == DT_I32) {
+    if (op == OP_PROD) return a * b;
+    const int x = (int)a, y = (int)b;
+    return ((op == OP_MAX) ? (x > y) : (x < y)) ? a : b;
+  }
+  if (DT == DT_F16) {
+    const half2_t x = __builtin_bit_cast(half2_t, a), y = __builtin_bit_cast(half2_t, b);
+    if (op == OP_PROD) return __builtin_bit_cast(uint32_t, x * y);
+    const bool tl = (op == OP_MAX) ? (x[0] > y[0]) : (x[0] < y[0]);
+    const bool th = (op == OP_MAX) ? (x[1] > y[1]) : (x[1] < y[1]);
+    return ((tl ? a : b) & 0xffffu) | ((th ? a : b) & 0xffff0000u);
+  }
+  return bf16x2_op(a, b, op);
+}
+
+template <int DT>
+__device__ __forceinline__ uint4 op_vec(uint4 a, uint4 b, int op) {
+  uint4 r;
+  r.x = op_word<DT>(a.x, b.x, op);
+  r.y = op_word<DT>(a.y, b.y, op);
+  r.z = op_word<DT>(a.z, b.z, op);
+  r.w = op_word<DT>(a.w, b.w, op);
+  return r;
+}
+
+template <int DT>
+__device__ __forceinline__ uint16_t op_half(uint16_t a, uint16_t b, int op) {
+  if (op == OP_SUM) return add_half<DT>(a, b);
+  return (uint16_t)(op_word<DT>(a, b, op) & 0xffffu);   // the upper half combines zeros and is dropped
+}
+
 // ------------------------------------------------------------------------------------------
 // slice mover: value = [fifo_in[i]] (+) [sendbuf[i]];  recvbuf[i] = value;  fifo_out[i] = value
 // (each side present or not, as the primitive says).  128-bit coalesced accesses, four
@@ -164,9 +224,11 @@ struct Slot {   // one connector slot seen through a buffer resource
   __device__ __forceinline__ void st2(uint32_t off, uint16_t v) const { __builtin_amdgcn_raw_buffer_store_b16(v, rsrc, (int)off, 0, AUX); }
 };
 
-template <int DT, int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT, int NTH>
+// GEN = false: the sum only (the common case keeps its own instantiation); GEN = true: `op` picks
+// the reducing function at run time (a wave-uniform branch per vector).
+template <int DT, bool GEN, int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT, int NTH>
 __device__ __forceinline__ void move_slice(const void* fin_p, const char* __restrict__ sb, char* __restrict__ rb,
-                                           void* fout_p, uint32_t bytes, uint32_t tid) {
+                                           void* fout_p, uint32_t bytes, uint32_t tid, int op) {
   constexpr int NT = NTH;   // threads that share the slice: the mover waves
   static_assert(FIN || SB, "a primitive has a source");
   static_assert(RB || FOUT, "a primitive has a destination");
@@ -192,7 +254,7 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) w[u] = ld_user(&S[i + u * NT]);
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? add_vec<DT>(v[u], w[u]) : w[u];
+        for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? (GEN ? op_vec<DT>(v[u], w[u], op) : add_vec<DT>(v[u], w[u])) : w[u];
       }
       if (FOUT) {
 #pragma unroll
@@ -216,7 +278,7 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) w[u] = (i + u * NT < nvec) ? ld_user(&S[i + u * NT]) : uint4{0, 0, 0, 0};
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? add_vec<DT>(v[u], w[u]) : w[u];
+        for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? (GEN ? op_vec<DT>(v[u], w[u], op) : add_vec<DT>(v[u], w[u])) : w[u];
       }
       if (FOUT) {
 #pragma unroll
@@ -237,7 +299,7 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
       for (uint32_t o = done + (tid << 2); o < bytes; o += NT << 2) {
         uint32_t v = 0;
         if (FIN) v = fin.ld4(o);
-        if (SB) { uint32_t w = S[o >> 2]; v = FIN ? add_word<DT>(v, w) : w; }
+        if (SB) { uint32_t w = S[o >> 2]; v = FIN ? (GEN ? op_word<DT>(v, w, op) : add_word<DT>(v, w)) : w; }
         if (FOUT) fout.st4(o, v);
         if (RB) D[o >> 2] = v;
       }
@@ -247,7 +309,7 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
       for (uint32_t o = done + (tid << 1); o < bytes; o += NT << 1) {
         uint16_t v = 0;
         if (FIN) v = fin.ld2(o);
-        if (SB) { uint16_t w = S[o >> 1]; v = FIN ? add_half<DT>(v, w) : w; }
+        if (SB) { uint16_t w = S[o >> 1]; v = FIN ? (GEN ? op_half<DT>(v, w, op) : add_half<DT>(v, w)) : w; }
         if (FOUT) fout.st2(o, v);
         if (RB) D[o >> 1] = v;
       }
@@ -255,14 +317,25 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
   }
 }
 
+// `dtype` carries the element type in its low four bits and the reducing function above them.
 template <int AIN, int AOUT, bool FIN, bool SB, bool RB, bool FOUT, int NTH>
 __device__ __forceinline__ void move_dispatch(int dtype, const void* fin, const char* sb, char* rb, void* fout, uint32_t bytes, uint32_t tid) {
-  if (!(FIN && SB)) { move_slice<DT_COPY, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid); return; }
-  switch (dtype) {
-    case DT_F32: move_slice<DT_F32, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid); break;
-    case DT_BF16: move_slice<DT_BF16, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid); break;
-    case DT_F16: move_slice<DT_F16, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid); break;
-    default: move_slice<DT_I32, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid); break;
+  if (!(FIN && SB)) { move_slice<DT_COPY, false, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid, 0); return; }
+  const int dt = dtype & 15, op = dtype >> 4;
+  if (op == OP_SUM) {
+    switch (dt) {
+      case DT_F32: move_slice<DT_F32, false, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid, 0); break;
+      case DT_BF16: move_slice<DT_BF16, false, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid, 0); break;
+      case DT_F16: move_slice<DT_F16, false, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid, 0); break;
+      default: move_slice<DT_I32, false, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid, 0); break;
+    }
+  } else {
+    switch (dt) {
+      case DT_F32: move_slice<DT_F32, true, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid, op); break;
+      case DT_BF16: move_slice<DT_BF16, true, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid, op); break;
+      case DT_F16: move_slice<DT_F16, true, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid, op); break;
+      default: move_slice<DT_I32, true, AIN, AOUT, FIN, SB, RB, FOUT, NTH>(fin, sb, rb, fout, bytes, tid, op); break;
+    }
   }
 }
 
@@ -344,6 +417,10 @@ __device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos,
     if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }                          // copy-send
     else if (p < R - 1) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
     else { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
+  } else if (kind == KIND_RD) {  // reduce chain root+1 -> root+2 -> ... -> root (bc_pos: 0 first, 1 middle, 2 the root)
+    if (bc_pos == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = false; }                    // send
+    else if (bc_pos == 2) { q.recv = true; q.send = false; q.from_send = true; q.to_recv = true; }               // recv-reduce-copy
+    else { q.recv = true; q.send = true; q.from_send = true; q.to_recv = false; }                                 // recv-reduce-send
   } else {  // broadcast chain root -> root+1 -> ... -> root-1
     if (bc_pos == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }
     else if (bc_pos == 2) { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
@@ -688,14 +765,15 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 k.fifo_in = (uint64_t)(slots + fi * q.nslots * q.slot_bytes);
                 k.slice_elems = q.slice_elems; k.rounds = q.rounds; k.seq = q.seq;
                 k.nprim = (uint16_t)q.nprim; k.nchan = q.nchan;
-                k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = q.dtype;
-                const uint32_t bpos = (rank + a.R - q.root) % a.R;
+                k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = (uint8_t)(q.dtype | (q.op << 4));
+                // place in the chain: broadcast starts at the root, reduce at the rank after it
+                const uint32_t bpos = (rank + 2 * a.R - q.root - (q.kind == KIND_RD ? 1u : 0u)) % a.R;
                 k.bc_pos = bpos == 0 ? 0 : (bpos == a.R - 1 ? 2 : 1);
                 k.priority = q.priority; k.vch = (uint16_t)my_vch;
                 myctx[c_id].st = k;
                 DfxDyn* dy = &myctx[c_id].dyn;
                 dy->round = 0; dy->prim = 0; dy->preempted = 0;
-                dy->cidx = (q.kind == KIND_AG) ? rank : ((q.kind == KIND_BC || a.R == 1) ? 0u : cidx0_reduce);
+                dy->cidx = (q.kind == KIND_AG) ? rank : ((q.kind == KIND_BC || q.kind == KIND_RD || a.R == 1) ? 0u : cidx0_reduce);
                 // FIFO ordering: append; priority ordering: keep the queue sorted (stable)
                 uint32_t at = qlen;
                 if (a.order_policy == 1) {
@@ -890,8 +968,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         }
         if (given_up) { stop = STOP_ABORT; have = false; continue; }
         // ---- slice geometry (elements relative to the block, clipped to the block's true length)
-        const int kind = S.kind, dtype = S.dtype;
-        const uint32_t eb = (dtype == DT_F32 || dtype == DT_I32) ? 4u : 2u;
+        const int kind = S.kind, dtype = S.dtype;   // dtype: element type | reducing function << 4
+        const uint32_t eb = ((dtype & 15) == DT_F32 || (dtype & 15) == DT_I32) ? 4u : 2u;
         const uint32_t slice_elems = S.slice_elems, vch = S.vch;
         const u64 count = S.count, block_elems = S.block_elems, part_elems = S.part_elems;
         const bool ring_chunks = (kind == KIND_AR && a.R > 1);
@@ -924,9 +1002,9 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         cidx = (cidx == 0) ? a.R - 1 : cidx - 1;
         if (++p == S.nprim) {
           p = 0; ++g;
-          cidx = (kind == KIND_AG) ? rank : ((kind == KIND_BC || a.R == 1) ? 0u : cidx0_reduce);
+          cidx = (kind == KIND_AG) ? rank : ((kind == KIND_BC || kind == KIND_RD || a.R == 1) ? 0u : cidx0_reduce);
         }
-        if (kind == KIND_BC) cidx = 0;
+        if (kind == KIND_BC || kind == KIND_RD) cidx = 0;
         progressed = true;
         pass_progress = true;
         acted = true;

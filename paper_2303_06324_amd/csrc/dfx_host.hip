@@ -379,8 +379,9 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
 int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype dtype, dfx_op op, int root, int priority) {
   if (!c) return DFX_ERR_INVALID_ARG;
   if (coll_id < 0 || (uint32_t)coll_id >= c->cfg.max_colls) return DFX_ERR_INVALID_ARG;
-  if ((int)kind < 0 || (int)kind > 3 || (int)dtype < 0 || (int)dtype > 3 || op != DFX_SUM) return DFX_ERR_INVALID_ARG;
-  if (kind == DFX_BROADCAST && (root < 0 || root >= c->R)) return DFX_ERR_INVALID_ARG;
+  if ((int)kind < 0 || (int)kind > 4 || (int)dtype < 0 || (int)dtype > 3 || (int)op < 0 || (int)op > 3) return DFX_ERR_INVALID_ARG;
+  const bool rooted = (kind == DFX_BROADCAST || kind == DFX_REDUCE);
+  if (rooted && (root < 0 || root >= c->R)) return DFX_ERR_INVALID_ARG;
   if (priority < -32768 || priority > 32767) return DFX_ERR_INVALID_ARG;
   if (count > (1ull << 40)) return DFX_ERR_INVALID_ARG;
   CollInfo& ci = c->colls[coll_id];
@@ -418,11 +419,11 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
   t.slot_bytes = (uint32_t)slot_bytes;
   t.nslots = (uint16_t)K;
   t.nchan = (uint16_t)C;
-  t.kind = (uint8_t)kind; t.dtype = (uint8_t)dtype; t.op = (uint8_t)op; t.root = (uint8_t)(kind == DFX_BROADCAST ? root : 0);
+  t.kind = (uint8_t)kind; t.dtype = (uint8_t)dtype; t.op = (uint8_t)op; t.root = (uint8_t)(rooted ? root : 0);
   t.priority = (int16_t)priority;
   if (R == 1) t.nprim = 1;
   else if (kind == DFX_ALLREDUCE) t.nprim = (uint32_t)(2 * R - 1);
-  else if (kind == DFX_BROADCAST) t.nprim = 1;
+  else if (rooted) t.nprim = 1;   // one primitive per slice, which one depends on the place in the chain
   else t.nprim = (uint32_t)R;
   c->pool_used += conn_bytes;
   ci.tmpl = t;

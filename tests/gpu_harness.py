@@ -69,7 +69,7 @@ def prepare_all(ctx: "dfx.Context", w: wi.Workload, colls: Optional[Sequence[int
     idx = range(len(w.colls)) if colls is None else colls
     for ci in idx:
         c = w.colls[ci]
-        ctx.prepare(c.coll_id, c.kind, c.count, c.dtype, dfx.SUM, c.root,
+        ctx.prepare(c.coll_id, c.kind, c.count, c.dtype, c.op, c.root,
                     0 if priorities is None else priorities[ci])
 
 

@@ -99,11 +99,11 @@ def test_config4_full_mixed_collectives():
         got = dw.results(ci)
         nbytes = c.send_elems(8) * wi.ELEM_BYTES[c.dtype]
         if nbytes <= (8 << 20):
-            want = rd.run_closed_form(c.kind, dw.send_host[ci], c.dtype, c.root)
+            want = rd.run_closed_form(c.kind, dw.send_host[ci], c.dtype, c.root, c.op)
             for r in range(8):
                 assert np.array_equal(got[r].view(np.uint8), want[r].view(np.uint8)), (ci, r)
         else:                                    # large ones: closed form on rank 0 and one other, identity across ranks
-            want = rd.run_closed_form(c.kind, dw.send_host[ci], c.dtype, c.root)
+            want = rd.run_closed_form(c.kind, dw.send_host[ci], c.dtype, c.root, c.op)
             for r in (0, 6):
                 assert np.array_equal(got[r].view(np.uint8), want[r].view(np.uint8)), (ci, r)
             if c.kind != wi.RS:

@@ -24,15 +24,19 @@ TOL_L2 = {rd.F32: 1e-6, rd.BF16: 1e-2, rd.F16: 4e-3}
 
 def _check(dw, w, ci):
     c = w.colls[ci]
-    want = rd.run_closed_form(c.kind, dw.send_host[ci], c.dtype, c.root)
+    want = rd.run_closed_form(c.kind, dw.send_host[ci], c.dtype, c.root, c.op)
     got = dw.results(ci)
     for r in range(w.R):
         g, e = got[r], want[r]
+        if c.kind == wi.RD and r != c.root:
+            # reduce writes the root's recv buffer only: the others still hold the harness's fill pattern
+            assert np.all(g.view(np.uint8) == 0xA5), f"{w.name} coll {ci}: reduce wrote rank {r}'s recv buffer"
+            continue
         if not np.array_equal(g.view(np.uint8), e.view(np.uint8)):
             bad = np.flatnonzero(g.view(np.uint8) != e.view(np.uint8))
             raise AssertionError(f"{w.name} coll {ci} ({wi.KIND_NAMES[c.kind]}, {wi.DTYPE_NAMES[c.dtype]}, count={c.count}) "
                                  f"rank {r}: {bad.size} bytes differ, first at byte {bad[0]}")
-    if c.kind == wi.AR and c.dtype in U and c.count > 0:
+    if c.kind == wi.AR and c.op == wi.SUM and c.dtype in U and c.count > 0:
         sends = dw.send_host[ci]
         R = w.R
         ref, mag = rd.sum_f64(sends, c.dtype), rd.abs_sum_f64(sends, c.dtype)
@@ -60,8 +64,8 @@ def _run(w, **cfgkw):
     return stats
 
 
-def _one(kind, dtype, count, R, root=0, seed=0):
-    return wi.Workload(f"one_{kind}_{dtype}_{count}_R{R}", R, [wi.CollSpec(0, kind, dtype, count, root)],
+def _one(kind, dtype, count, R, root=0, seed=0, op=wi.SUM):
+    return wi.Workload(f"one_{kind}_{dtype}_{count}_R{R}_op{op}", R, [wi.CollSpec(0, kind, dtype, count, root, op)],
                        [[0]] * R, seed=seed, cfg=50)
 
 
@@ -159,3 +163,52 @@ def test_repeated_invocations_and_changing_buffers():
         assert ctx.wait_all(20.0) == dfx.OK
     finally:
         ctx.finalize()
+
+
+@pytest.mark.parametrize("dtype", [wi.F32, wi.BF16, wi.F16, wi.I32])
+@pytest.mark.parametrize("count", [1, 4099, 1 << 20])
+def test_reduce_to_every_root_R8(dtype, count):
+    """The reduce collective (Sec. 4.1): chain ending at the root; only the root's recv buffer changes."""
+    for root in (0, 3, 7):
+        _run(_one(wi.RD, dtype, count, 8, root=root, seed=count + root))
+
+
+@pytest.mark.parametrize("R", [1, 2, 3, 5, 16])
+def test_reduce_other_rank_counts(R):
+    _run(_one(wi.RD, wi.F32, 30000 + R, R, root=R - 1, seed=R), max_channels=8)
+
+
+@pytest.mark.parametrize("op", [wi.PROD, wi.MAX, wi.MIN])
+@pytest.mark.parametrize("dtype", [wi.F32, wi.BF16, wi.F16, wi.I32])
+@pytest.mark.parametrize("kind", [wi.AR, wi.RS, wi.RD])
+def test_other_reducing_functions(kind, dtype, op):
+    """Product / maximum / minimum as the reducing function (Sec. 4.1), bit-exact against the oracle's fold,
+    at a ragged size that exercises the vector loop, its predicated tail and the element-wise path."""
+    for count in (7, 100003):
+        _run(_one(kind, dtype, count, 8, root=5, seed=op * 10 + kind, op=op))
+
+
+def test_max_min_ties_and_signed_zeros():
+    """Equal values (and +0 / -0) pass on the own operand: checked on buffers made of few distinct values."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    R, n = 4, 8192
+    g = np.random.default_rng(77)
+    vals = np.array([0.0, -0.0, 1.0, -1.0, 2.5], np.float32)
+    sends = [vals[g.integers(0, len(vals), size=n)] for _ in range(R)]
+    for op in (wi.MAX, wi.MIN):
+        want = rd.all_reduce_fold(sends, rd.F32, op)
+        ctx = dfx.Context(R, gh.make_config())
+        try:
+            ctx.prepare(0, dfx.ALLREDUCE, n, dfx.F32, op)
+            import torch
+            s = [torch.from_numpy(x).cuda() for x in sends]
+            d = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(R)]
+            torch.cuda.synchronize()
+            for r in range(R):
+                assert ctx.submit(r, 0, s[r].data_ptr(), d[r].data_ptr()) == dfx.OK
+            assert ctx.wait_all(20.0) == dfx.OK
+            for r in range(R):
+                assert np.array_equal(d[r].cpu().numpy().view(np.uint32), want.view(np.uint32))
+        finally:
+            ctx.finalize()

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 def _expect(dw, w, ci):
     c = w.colls[ci]
-    want = rd.run_closed_form(c.kind, dw.send_host[ci], c.dtype, c.root)
+    want = rd.run_closed_form(c.kind, dw.send_host[ci], c.dtype, c.root, c.op)
     got = dw.results(ci)
     for r in range(w.R):
         assert np.array_equal(got[r].view(np.uint8), want[r].view(np.uint8)), (w.name, ci, r)
