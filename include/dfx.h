@@ -98,6 +98,11 @@ typedef struct {
                               collectives spread over the grid; 0: every collective starts at workgroup 0
                               (small collectives all share the first task queues: the single-queue
                               setting of Sec. 2.3) */
+  uint32_t cq_mode;        /* completion-queue variant (Sec. 5 "Optimizing CQ"): 0 = optimized CQ, one
+                              system-scope CAS of the id into a free slot (default); 1 = vanilla ring buffer
+                              (reserve, entry, fence, in-order tail update); 2 = optimized ring buffer (id and
+                              position in one 64-bit atomic write, validated by the poller against its head) */
+  uint32_t reserved0;
 } dfx_config;
 
 /* Aggregated over the workgroups of one vrank since dfx_init. */
@@ -121,10 +126,11 @@ typedef struct {
   double switch_us_mean;
   double save_us_mean;     /* the save part of a switch */
   double load_us_mean;     /* the load part of a switch */
-  double wait_us;          /* with trace on: time in wait phases, summed over the vrank's workgroups */
-  double data_us;          /* ... in data phases (loads issued until stores issued) */
-  double publish_us;       /* ... draining stores, barrier and counter stores */
+  double wait_us;          /* with trace >= 2: time in successful wait phases, summed over the vrank's workgroups */
+  double data_us;          /* ... in data phases (first mover wave: job taken until its stores are drained) */
+  double publish_us;       /* ... between the last mover wave's drain and its counter updates */
   uint64_t scan_skips;     /* queue entries a readiness scan found not runnable (no context load, no spin) */
+  double cqe_us;           /* time spent writing CQEs (first to last host-memory operation), summed; always counted */
 } dfx_stats_t;
 
 /* Fill *cfg with defaults (struct_bytes set). cfg: host, caller-owned. */
@@ -184,6 +190,17 @@ int dfx_submit_many(dfx_ctx* ctx, int rank, int n, const int* coll_ids, const vo
  * that quit voluntarily while work is outstanding.
  */
 int dfx_poll(dfx_ctx* ctx, int rank, dfx_cqe* out, int max);
+
+/*
+ * Callback delivery (Sec. 3.1: the poller thread reads CQEs and runs the callback bound to the
+ * collective).  With fn != NULL the library starts one poller thread that drains the CQs of all
+ * vranks, restarts a daemon that quit while work is outstanding, and calls fn(user, rank, coll_id,
+ * seq) once per completion, outside any library lock (fn may submit).  Completions delivered this
+ * way are not returned by dfx_poll any more; dfx_wait / dfx_wait_all keep working.  fn == NULL stops
+ * and joins the thread.  fn runs on the poller thread; user is passed through untouched.
+ */
+typedef void (*dfx_callback)(void* user, int rank, uint32_t coll_id, uint32_t seq);
+int dfx_set_callback(dfx_ctx* ctx, dfx_callback fn, void* user);
 
 /*
  * Block until the latest invocation of coll_id on rank has completed, or timeout_ns passed

@@ -25,7 +25,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in (
         "struct_bytes", "max_channels", "max_colls", "sq_depth", "cq_slots", "nslots", "slot_bytes",
         "chan_min_bytes", "spin_init", "spin_min", "spin_max", "spin_boost", "preempt", "watchdog_ms",
-        "quit_idle_us", "sq_in_device", "wg_map", "order_policy", "trace", "fetch_batch")] + [("pool_bytes", C.c_uint64), ("scan_min", C.c_uint32), ("chan_spread", C.c_uint32)]
+        "quit_idle_us", "sq_in_device", "wg_map", "order_policy", "trace", "fetch_batch")] + [("pool_bytes", C.c_uint64), ("scan_min", C.c_uint32), ("chan_spread", C.c_uint32), ("cq_mode", C.c_uint32), ("reserved0", C.c_uint32)]
 
 
 class Stats(C.Structure):
@@ -33,10 +33,13 @@ class Stats(C.Structure):
         "preemptions", "ctx_loads", "ctx_slot_hits", "ctx_saves", "lazy_skips", "polls", "prims", "sqe_fetched",
         "cqe_posted", "max_taskq", "passes", "quits", "launches", "switch_samples")] + [(n, C.c_double) for n in (
         "switch_us_p50", "switch_us_p99", "switch_us_mean", "save_us_mean", "load_us_mean", "wait_us", "data_us",
-        "publish_us")] + [("scan_skips", C.c_uint64)]
+        "publish_us")] + [("scan_skips", C.c_uint64), ("cqe_us", C.c_double)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+CALLBACK = C.CFUNCTYPE(None, C.c_void_p, C.c_int, C.c_uint32, C.c_uint32)
 
 
 class Cqe(C.Structure):
@@ -76,6 +79,7 @@ def _load() -> C.CDLL:
         "dfx_coll_info": ([vp, i] + [C.POINTER(C.c_uint32)] * 4, i),
         "dfx_last_launch_ms": ([vp, C.POINTER(C.c_float), C.POINTER(u64)], i),
         "dfx_trace_read": ([vp, C.c_uint32, C.POINTER(u64), C.c_uint32, C.POINTER(C.c_double)], i),
+        "dfx_set_callback": ([vp, CALLBACK, vp], i),
         "dfx_finalize": ([vp], i),
         "dfx_last_hip_error": ([vp], i),
         "dfx_last_init_error": ([], i),
@@ -170,6 +174,18 @@ class Context:
         if rc != OK:
             raise DfxError(rc, "dfx_last_launch_ms")
         return ms.value, n.value
+
+    def set_callback(self, fn) -> None:
+        """fn(rank, coll_id, seq) is called on the library's poller thread for every completion; None stops it."""
+        if fn is None:
+            rc = _lib.dfx_set_callback(self._h, C.cast(None, CALLBACK), None)
+            self._cb = None
+        else:
+            cb = CALLBACK(lambda user, rank, coll_id, seq: fn(rank, coll_id, seq))
+            rc = _lib.dfx_set_callback(self._h, cb, None)
+            self._cb = cb           # keep the trampoline alive while the thread may call it
+        if rc != OK:
+            raise DfxError(rc, "dfx_set_callback")
 
     def trace_read(self, wg: int, max_samples: int = 4096) -> Tuple[list, float]:
         buf = (C.c_uint64 * max_samples)()

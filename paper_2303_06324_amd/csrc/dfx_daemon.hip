@@ -613,20 +613,53 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       const uint32_t old = __hip_atomic_fetch_add(dc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
       if (old + 1 == c_nchan) {
         __hip_atomic_store(dc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
-        const u64 v = (1ull << 63) | ((u64)(c_seq & 0x7fffffffu) << 32) | c_coll;
-        const uint32_t t = __hip_atomic_fetch_add(&a.cq_ticket[rank], 1u, __ATOMIC_RELAXED, SCOPE_AGENT);
-        uint32_t k = 0;
-        for (;;) {   // optimized CQ (Sec. 5): one CAS of the id into a writable slot
-          u64 expected = 0;
-          if (__hip_atomic_compare_exchange_strong(&cqbase[(t + k) % a.cq_slots], &expected, v, __ATOMIC_RELEASE,
-                                                   __ATOMIC_RELAXED, SCOPE_SYSTEM))
-            break;
-          ++k;
-          if ((k % a.cq_slots) == 0) {
-            if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) break;
-            __builtin_amdgcn_s_sleep(50);
+        const u64 tq0 = wall_clock64();
+        if (a.cq_mode == 0) {
+          // optimized CQ (Sec. 5): one CAS of the id into a writable slot, no ring semantics
+          const u64 v = (1ull << 63) | ((u64)(c_seq & 0x7fffffffu) << 32) | c_coll;
+          const uint32_t t = __hip_atomic_fetch_add(&a.cq_ticket[rank], 1u, __ATOMIC_RELAXED, SCOPE_AGENT);
+          uint32_t k = 0;
+          for (;;) {
+            u64 expected = 0;
+            if (__hip_atomic_compare_exchange_strong(&cqbase[(t + k) % a.cq_slots], &expected, v, __ATOMIC_RELEASE,
+                                                     __ATOMIC_RELAXED, SCOPE_SYSTEM))
+              break;
+            ++k;
+            if ((k % a.cq_slots) == 0) {
+              if (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT])) break;
+              __builtin_amdgcn_s_sleep(50);
+            }
+          }
+        } else {
+          // The two ring-buffer CQs that Sec. 5 compares the optimized one with.  Both reserve a
+          // position with an atomic in host memory and read the consumer's head to see whether
+          // the ring has room.
+          u64* ctl = a.cq_ctl + (size_t)rank * DFX_CQ_CTL_WORDS;
+          const u64 t = __hip_atomic_fetch_add(&ctl[0], 1ull, __ATOMIC_RELAXED, SCOPE_SYSTEM);
+          bool give_up = false;
+          uint32_t k = 0;
+          while (t - __hip_atomic_load(&ctl[16], __ATOMIC_RELAXED, SCOPE_SYSTEM) >= (u64)a.cq_slots) {
+            if ((++k & 63u) == 0 && (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT]))) { give_up = true; break; }
+            __builtin_amdgcn_s_sleep(20);
+          }
+          if (!give_up && a.cq_mode == 1) {
+            // vanilla ring: entry, fence, then the shared tail, which moves in position order
+            const u64 v = ((u64)(c_seq & 0x7fffffffu) << 32) | c_coll;
+            __hip_atomic_store(&cqbase[t % a.cq_slots], v, __ATOMIC_RELAXED, SCOPE_SYSTEM);
+            fence_release_system();
+            while (__hip_atomic_load(&ctl[8], __ATOMIC_RELAXED, SCOPE_SYSTEM) != t) {
+              if ((++k & 63u) == 0 && (ld_agent32(&a.dev_ctl[DC_ABORT]) || ld_sys32(&a.host_ctl[HC_ABORT]))) { give_up = true; break; }
+              __builtin_amdgcn_s_sleep(2);
+            }
+            if (!give_up) __hip_atomic_store(&ctl[8], t + 1, __ATOMIC_RELEASE, SCOPE_SYSTEM);
+          } else if (!give_up) {
+            // optimized ring: id and position travel in one 64-bit atomic write, no tail, no fence;
+            // the poller accepts the entry at its head when the position in it says head + 1
+            const u64 v = (((t + 1) & 0xffffffffull) << 32) | ((u64)(c_seq & 0xffffu) << 16) | (c_coll & 0xffffu);
+            __hip_atomic_store(&cqbase[t % a.cq_slots], v, __ATOMIC_RELEASE, SCOPE_SYSTEM);
           }
         }
+        bump(sh.stat, ST_T_CQE, wall_clock64() - tq0);
         bump(sh.stat, ST_CQE, 1);
       }
     };

@@ -38,6 +38,7 @@ struct RankState {
   std::vector<uint32_t> sub;            // per coll: submissions so far
   std::vector<uint32_t> done;           // per coll: completions seen
   std::deque<dfx_cqe> ready;            // completions not yet handed to the caller
+  uint64_t cq_head = 0;                 // ring-buffer CQ variants: entries consumed
   std::atomic<uint64_t> n_sub{0}, n_cqe{0};
 };
 
@@ -69,6 +70,7 @@ struct dfx_ctx {
   DfxSqSlot* sq = nullptr;
   uint32_t* host_ctl = nullptr;
   uint64_t* cq = nullptr;
+  uint64_t* cq_ctl = nullptr;        // ring bookkeeping of the ring-buffer CQ variants (same allocation as cq)
   // device memory
   uint32_t* sq_readers = nullptr;
   uint32_t* done_cnt = nullptr;
@@ -85,6 +87,13 @@ struct dfx_ctx {
   uint64_t pool_used = 0;
   std::vector<CollInfo> colls;
   std::vector<RankState*> ranks;
+
+  // callback delivery
+  std::thread poller;
+  std::atomic<bool> poller_run{false};
+  std::atomic<bool> user_stopped{false};   // dfx_stop was the last word: the poller thread does not restart the daemon
+  dfx_callback cb = nullptr;
+  void* cb_user = nullptr;
 };
 
 namespace {
@@ -160,6 +169,7 @@ int launch_locked(dfx_ctx* c) {
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   a.nwg = c->nwg;
+  a.cq_ctl = c->cq_ctl; a.cq_mode = c->cfg.cq_mode;
   a.scan_min = c->cfg.scan_min;
   a.chan_spread = c->cfg.chan_spread;
   a.epoch = (uint32_t)(c->launches + 1);
@@ -215,21 +225,54 @@ int push_sqe(dfx_ctx* c, int rank, const DfxStatic& e) {
   return DFX_OK;
 }
 
-// Move every valid CQ slot of a rank into its ready list (caller holds the rank's mutex).
+// Move every completion of a rank that has arrived into its ready list (caller holds the rank's mutex).
 void drain_cq(dfx_ctx* c, int rank) {
   RankState* rs = c->ranks[rank];
   volatile uint64_t* q = c->cq + (size_t)rank * c->cfg.cq_slots;
-  for (uint32_t i = 0; i < c->cfg.cq_slots; ++i) {
-    uint64_t v = q[i];
-    if (!(v >> 63)) continue;
-    std::atomic_thread_fence(std::memory_order_acquire);
-    q[i] = 0;   // slot writable again
+  auto take = [&](uint32_t coll, uint32_t seq) {
     dfx_cqe e;
-    e.coll_id = (uint32_t)(v & 0xffffffffu);
-    e.seq = (uint32_t)((v >> 32) & 0x7fffffffu);
+    e.coll_id = coll;
+    e.seq = seq;
     if (e.coll_id < rs->done.size()) rs->done[e.coll_id]++;
     rs->ready.push_back(e);
     rs->n_cqe.fetch_add(1, std::memory_order_relaxed);
+  };
+  if (c->cfg.cq_mode == 0) {
+    // optimized CQ: scan the slots, take the valid ones and mark them writable
+    for (uint32_t i = 0; i < c->cfg.cq_slots; ++i) {
+      uint64_t v = q[i];
+      if (!(v >> 63)) continue;
+      std::atomic_thread_fence(std::memory_order_acquire);
+      q[i] = 0;
+      take((uint32_t)(v & 0xffffffffu), (uint32_t)((v >> 32) & 0x7fffffffu));
+    }
+    return;
+  }
+  volatile uint64_t* ctl = c->cq_ctl + (size_t)rank * DFX_CQ_CTL_WORDS;
+  const uint64_t head0 = rs->cq_head;
+  if (c->cfg.cq_mode == 1) {
+    // vanilla ring: everything below the producers' tail is complete
+    const uint64_t tail = ctl[8];
+    std::atomic_thread_fence(std::memory_order_acquire);
+    for (; rs->cq_head < tail; ++rs->cq_head) {
+      const uint64_t v = q[rs->cq_head % c->cfg.cq_slots];
+      take((uint32_t)(v & 0xffffffffu), (uint32_t)((v >> 32) & 0x7fffffffu));
+    }
+  } else {
+    // optimized ring: the entry at the head is valid when the position written into it is head + 1;
+    // the invocation number is the host's own count (one invocation of an id is outstanding at a time)
+    for (;;) {
+      const uint64_t v = q[rs->cq_head % c->cfg.cq_slots];
+      if ((uint32_t)(v >> 32) != (uint32_t)(rs->cq_head + 1)) break;
+      std::atomic_thread_fence(std::memory_order_acquire);
+      const uint32_t coll = (uint32_t)(v & 0xffffu);
+      take(coll, coll < rs->done.size() ? rs->done[coll] : 0u);
+      ++rs->cq_head;
+    }
+  }
+  if (rs->cq_head != head0) {
+    std::atomic_thread_fence(std::memory_order_release);
+    ctl[16] = rs->cq_head;   // room for the producers
   }
 }
 
@@ -261,6 +304,8 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->fetch_batch = 0;
   cfg->scan_min = 3;
   cfg->chan_spread = 1;
+  cfg->cq_mode = 0;
+  cfg->reserved0 = 0;
   cfg->preempt = 1;
   cfg->watchdog_ms = 10000;
   cfg->quit_idle_us = 2000;
@@ -285,7 +330,7 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   if (cfg.max_channels < 1 || cfg.max_channels > 1024) return DFX_ERR_INVALID_ARG;
   if (cfg.max_colls < 1 || cfg.max_colls > DFX_MAX_COLLS) return DFX_ERR_INVALID_ARG;
   if (!is_pow2(cfg.sq_depth) || cfg.sq_depth < 2) return DFX_ERR_INVALID_ARG;
-  if (cfg.cq_slots < 1) return DFX_ERR_INVALID_ARG;
+  if (cfg.cq_slots < 1 || cfg.cq_mode > 2) return DFX_ERR_INVALID_ARG;
   if (!is_pow2(cfg.nslots) || cfg.nslots < 2 || cfg.nslots > 64) return DFX_ERR_INVALID_ARG;
   if (cfg.slot_bytes < 16 || (cfg.slot_bytes & 15u)) return DFX_ERR_INVALID_ARG;
   if (cfg.chan_min_bytes < 16) return DFX_ERR_INVALID_ARG;
@@ -332,7 +377,8 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
 
   const size_t R = (size_t)nranks;
   const size_t sq_bytes = R * cfg.sq_depth * sizeof(DfxSqSlot) + HC_N * sizeof(uint32_t) + 256;
-  const size_t cq_bytes = R * cfg.cq_slots * sizeof(uint64_t);
+  const size_t cq_slots_bytes = round_up(R * cfg.cq_slots * sizeof(uint64_t), 64);
+  const size_t cq_bytes = cq_slots_bytes + R * DFX_CQ_CTL_WORDS * sizeof(uint64_t);
   if (c->sq_device) {
     INITCHK(hipExtMallocWithFlags(&c->qmem_sq, sq_bytes, hipDeviceMallocFinegrained));
     INITCHK(hipMemset(c->qmem_sq, 0, sq_bytes));
@@ -345,6 +391,7 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   c->sq = (DfxSqSlot*)c->qmem_sq;
   c->host_ctl = (uint32_t*)((char*)c->qmem_sq + round_up(R * cfg.sq_depth * sizeof(DfxSqSlot), 256));
   c->cq = (uint64_t*)c->qmem_cq;
+  c->cq_ctl = (uint64_t*)((char*)c->qmem_cq + cq_slots_bytes);
 
   auto dalloc = [&](void** p, size_t bytes) -> hipError_t {
     hipError_t e = hipMalloc(p, bytes);
@@ -472,6 +519,7 @@ int dfx_submit(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* rec
     }
   }
   // start the daemon on SQE insertion; also when the SQ is full (a quit daemon frees no slots)
+  c->user_stopped.store(false);
   int rr = ensure_running(c);
   if (rr != DFX_OK) return rr;
   return rc;
@@ -520,8 +568,9 @@ int dfx_wait(dfx_ctx* c, int rank, int coll_id, uint64_t timeout_ns) {
       std::lock_guard<std::mutex> lk(rs->mu);
       drain_cq(c, rank);
       if (rs->sub[coll_id] == rs->done[coll_id]) {
-        for (auto it = rs->ready.begin(); it != rs->ready.end(); ++it)
-          if (it->coll_id == (uint32_t)coll_id) { rs->ready.erase(it); break; }
+        if (!c->cb)   // with a callback set the completion belongs to the poller thread
+          for (auto it = rs->ready.begin(); it != rs->ready.end(); ++it)
+            if (it->coll_id == (uint32_t)coll_id) { rs->ready.erase(it); break; }
         return DFX_OK;
       }
     }
@@ -546,7 +595,7 @@ int dfx_wait_all(dfx_ctx* c, uint64_t timeout_ns) {
       std::lock_guard<std::mutex> lk(rs->mu);
       drain_cq(c, r);
       if (rs->n_cqe.load() < rs->n_sub.load()) all = false;
-      else rs->ready.clear();
+      else if (!c->cb) rs->ready.clear();
     }
     if (all) return DFX_OK;
     if ((spins & 63u) == 0) {
@@ -561,11 +610,13 @@ int dfx_wait_all(dfx_ctx* c, uint64_t timeout_ns) {
 
 int dfx_start(dfx_ctx* c) {
   if (!c) return DFX_ERR_INVALID_ARG;
+  c->user_stopped.store(false);
   return ensure_running(c);
 }
 
 int dfx_stop(dfx_ctx* c) {
   if (!c) return DFX_ERR_INVALID_ARG;
+  c->user_stopped.store(true);
   {
     std::lock_guard<std::mutex> lk(c->launch_mu);
     bool idle = false;
@@ -630,6 +681,7 @@ int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
     out->wait_us += (double)s[ST_T_WAIT] * c->tick_us; out->data_us += (double)s[ST_T_DATA] * c->tick_us;
     out->publish_us += (double)s[ST_T_PUB] * c->tick_us;
     out->scan_skips += s[ST_SCAN_SKIPS];
+    out->cqe_us += (double)s[ST_T_CQE] * c->tick_us;
     wgs.push_back(wg);
     tn.push_back(h[wg].trace_n);
   }
@@ -693,8 +745,46 @@ int dfx_last_launch_ms(dfx_ctx* c, float* ms, uint64_t* launches_done) {
   return DFX_OK;
 }
 
+int dfx_set_callback(dfx_ctx* c, dfx_callback fn, void* user) {
+  if (!c) return DFX_ERR_INVALID_ARG;
+  if (c->poller.joinable()) {
+    c->poller_run.store(false);
+    c->poller.join();
+  }
+  c->cb = fn;
+  c->cb_user = user;
+  if (!fn) return DFX_OK;
+  c->poller_run.store(true);
+  c->poller = std::thread([c]() {
+    std::vector<dfx_cqe> got;
+    uint32_t idle = 0;
+    while (c->poller_run.load(std::memory_order_relaxed)) {
+      bool any = false;
+      for (int r = 0; r < c->R; ++r) {
+        got.clear();
+        {
+          RankState* rs = c->ranks[r];
+          std::lock_guard<std::mutex> lk(rs->mu);
+          drain_cq(c, r);
+          got.assign(rs->ready.begin(), rs->ready.end());
+          rs->ready.clear();
+        }
+        for (const dfx_cqe& e : got) c->cb(c->cb_user, r, e.coll_id, e.seq);
+        any = any || !got.empty();
+      }
+      if (any) { idle = 0; continue; }
+      // event-driven start (Sec. 4.4) without the caller polling
+      if ((++idle & 255u) == 0 && !c->user_stopped.load() && !c->aborted.load() && outstanding(c)) (void)ensure_running(c);
+      if (idle < 4096) _mm_pause();
+      else std::this_thread::sleep_for(std::chrono::microseconds(50));
+    }
+  });
+  return DFX_OK;
+}
+
 int dfx_finalize(dfx_ctx* c) {
   if (!c) return DFX_ERR_INVALID_ARG;
+  (void)dfx_set_callback(c, nullptr, nullptr);
   int rc = dfx_stop(c);
   bool pending = false;
   for (int r = 0; r < c->R; ++r) {

@@ -12,7 +12,8 @@
 #define DFX_CTX_SLOTS 4         // LDS active context slots, direct-mapped by coll_id (Sec. 5)
 #define DFX_TRACE_N 4096        // context-switch latency samples kept per workgroup
 #define DFX_FLAG_STRIDE 128     // bytes per (edge, channel) flag pair: tail at +0, head at +64
-#define DFX_NSTAT 16
+#define DFX_NSTAT 24
+#define DFX_CQ_CTL_WORDS 24      // 64-bit words of ring bookkeeping per vrank: reserve at 0, tail at 8, head at 16
 
 #define DFX_SQE_EXIT 1u
 
@@ -95,7 +96,8 @@ struct alignas(16) DfxWgState {
 };
 
 enum { ST_PREEMPT = 0, ST_LOAD, ST_HIT, ST_SAVE, ST_LAZY, ST_POLLS, ST_PRIMS, ST_SQE, ST_CQE, ST_MAXQ, ST_PASSES, ST_QUITS,
-       ST_T_WAIT, ST_T_DATA, ST_T_PUB, ST_SCAN_SKIPS };   // wall-clock ticks, only with trace on
+       ST_T_WAIT, ST_T_DATA, ST_T_PUB, ST_SCAN_SKIPS,   // T_*: wall-clock ticks, only with trace on
+       ST_T_CQE };                                       // ticks spent writing CQEs (always counted)
 
 // dev_ctl words (device memory)
 // (abort and quit share one aligned 64-bit word: the scheduler reads both with one load; the host
@@ -107,6 +109,7 @@ enum { HC_ABORT = 0, HC_N = 16 };
 struct DfxDaemonArgs {
   DfxSqSlot* sq;            // [R][sq_depth]   host-visible
   uint64_t* cq;             // [R][cq_slots]   host-visible
+  uint64_t* cq_ctl;         // [R][DFX_CQ_CTL_WORDS] host-visible: bookkeeping of the ring-buffer CQ variants
   uint32_t* host_ctl;       // [HC_N]          host-visible
   uint32_t* sq_readers;     // [R][sq_depth]   device
   uint32_t* done_cnt;       // [R][max_colls]  device
@@ -122,7 +125,7 @@ struct DfxDaemonArgs {
   uint32_t epoch;           // number of this launch (exit SQEs name the launch they end)
   uint32_t R, cmax, max_colls, sq_depth, sq_shift, cq_slots;
   uint32_t spin_init, spin_min, spin_max, spin_boost, preempt;
-  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent, chan_spread;
+  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent, chan_spread, cq_mode;
   uint64_t watchdog_ticks;  // wall-clock ticks; 0 = off
   uint64_t quit_ticks;      // wall-clock ticks; 0 = off
 };

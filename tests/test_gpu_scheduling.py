@@ -252,3 +252,79 @@ def test_primitive_timeline_trace():
         assert served == 8 * info["nchan"]
     finally:
         assert ctx.finalize() == dfx.OK
+
+
+@pytest.mark.parametrize("cq_mode", [0, 1, 2])
+def test_cq_variants_deliver_every_completion_once(cq_mode):
+    """The three completion queues of Sec. 5 (CAS slot array, vanilla ring, 64-bit packed ring) behind a
+    16-slot CQ that must wrap many times: 200 collectives per rank, every CQE handed out exactly once."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.config5(n_colls=200, seed=23)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(8, gh.make_config(cq_mode=cq_mode, cq_slots=16))
+    try:
+        gh.prepare_all(ctx, w)
+        seen = [dict() for _ in range(8)]
+        pos = [0] * 8
+        deadline = time.monotonic() + 60
+        while any(p < 200 for p in pos) or any(len(s) < 200 for s in seen):
+            for r in range(8):
+                for _ in range(4):
+                    if pos[r] < 200:
+                        ci = w.orders[r][pos[r]]
+                        rc = ctx.submit(r, ci, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr())
+                        if rc == dfx.OK:
+                            pos[r] += 1
+                        else:
+                            assert rc == dfx.ERR_SQ_FULL
+                for cid, seq in ctx.poll(r, 64):
+                    assert cid not in seen[r] and seq == 0
+                    seen[r][cid] = seq
+            assert time.monotonic() < deadline
+        for ci in range(200):
+            _expect(dw, w, ci)
+        st = ctx.stats(0)
+        assert st["cqe_posted"] == 200 and st["cqe_us"] > 0.0
+    finally:
+        assert ctx.finalize() == dfx.OK
+
+
+def test_callback_poller_thread():
+    """Sec. 3.1: a poller thread reads the CQEs and runs the callback; nothing is left for dfx_poll, and
+    the thread restarts a daemon that quit while work was outstanding."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    import threading
+    w = wi.config3(n_buckets=8, bucket_bytes=256 << 10, seed=24)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(8, gh.make_config(quit_idle_us=200))
+    got, lock, all_done = [], threading.Lock(), threading.Event()
+
+    def on_done(rank, coll_id, seq):
+        with lock:
+            got.append((rank, coll_id, seq))
+            if len(got) == 2 * 8 * 8:
+                all_done.set()
+
+    try:
+        gh.prepare_all(ctx, w)
+        ctx.set_callback(on_done)
+        for rep in range(2):
+            for ci in range(8):                      # ranks 0..6 first: the daemon gets stuck and quits
+                for r in range(7):
+                    assert ctx.submit(r, ci, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr()) == dfx.OK
+            time.sleep(0.01)
+            for ci in range(8):
+                assert ctx.submit(7, ci, dw.send[ci][7].data_ptr(), dw.recv[ci][7].data_ptr()) == dfx.OK
+            assert ctx.wait_all(20.0) == dfx.OK
+        assert all_done.wait(10.0)
+        for r in range(8):
+            assert ctx.poll(r, 8) == []
+        with lock:
+            assert sorted(got) == sorted((r, ci, rep) for rep in range(2) for r in range(8) for ci in range(8))
+        ctx.set_callback(None)
+        for ci in range(8):
+            _expect(dw, w, ci)
+    finally:
+        assert ctx.finalize() == dfx.OK
