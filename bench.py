@@ -54,13 +54,13 @@ def cpu_baseline(sample_bytes: int, min_seconds: float = 10.0, max_reps: int = 4
                       f"{total:.1f} s in all, {dt * 1e3:.0f} ms each; same busbw formula as value"}
 
 
-def _switch_run(trace: int):
+def _switch_run(trace: int, n_colls: int = 1024, **kw):
     import workload_inputs as wi
     import paper_2303_06324_amd as dfx
     from tests import gpu_harness as gh
-    w = wi.config5(n_colls=256, seed=4)
+    w = wi.config5(n_colls=n_colls, seed=4)
     dw = gh.DeviceWorkload(w, keep_host=False)
-    ctx = dfx.Context(R, gh.make_config(trace=trace))
+    ctx = dfx.Context(R, gh.make_config(trace=trace, **kw))
     try:
         gh.prepare_all(ctx, w)
         t0 = time.perf_counter()
@@ -74,20 +74,54 @@ def _switch_run(trace: int):
     return rc, dt, st, len(w.colls)
 
 
-def switch_latency():
-    """Context-switch latency (abort decision -> first poll of the next collective) from short runs
-    of 256 small all-reduces issued in a different random order on every vrank: one run with two
-    clock reads per switch (the latency), one with the save / load parts timed as well."""
-    rc, dt, st, n = _switch_run(1)
-    rc2, _, st2, _ = _switch_run(2)
-    return {"completed": rc == 0 and rc2 == 0, "collectives": n, "seconds": round(dt, 4),
+def _switch_summary(rc, dt, st, n, st2):
+    return {"completed": rc == 0, "collectives": n, "seconds": round(dt, 4),
             "collectives_per_s": round(n / dt, 1),
             "preemptions": sum(s["preemptions"] for s in st),
             "samples": sum(s["switch_samples"] for s in st),
             "p50_us": round(max(s["switch_us_p50"] for s in st), 3),
             "p99_us": round(max(s["switch_us_p99"] for s in st), 3),
-            "save_us_mean": round(sum(s["save_us_mean"] for s in st2) / R, 3),
-            "load_us_mean": round(sum(s["load_us_mean"] for s in st2) / R, 3)}
+            "save_us_mean": round(sum(s["save_us_mean"] for s in st2) / len(st2), 3),
+            "load_us_mean": round(sum(s["load_us_mean"] for s in st2) / len(st2), 3)}
+
+
+def _switch_config1(trace: int, iters: int = 400):
+    """Config 1 (two all-reduces, opposite orders on the two vranks) with the smallest thresholds,
+    invoked `iters` times inside one context, both collectives on one workgroup per vrank."""
+    import workload_inputs as wi
+    import paper_2303_06324_amd as dfx
+    from tests import gpu_harness as gh
+    w = wi.config1()
+    dw = gh.DeviceWorkload(w, keep_host=False)
+    ctx = dfx.Context(2, gh.make_config(trace=trace, max_channels=4, chan_spread=0, scan_min=0,
+                                        spin_init=1, spin_min=1, spin_max=1, spin_boost=1))
+    try:
+        gh.prepare_all(ctx, w)
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            gh.submit_round_robin(ctx, dw, timeout_s=20)
+            rc = ctx.wait_all(20.0)
+            if rc != 0:
+                break
+        dt = time.perf_counter() - t0
+        ctx.stop()
+        st = [ctx.stats(r) for r in range(2)]
+    finally:
+        ctx.finalize()
+    return rc, dt, st, 2 * iters
+
+
+def switch_latency():
+    """Context-switch latency (abort decision -> first poll of the next collective of the same pass):
+    1024 small all-reduces issued in a different random order on every vrank, with the library
+    defaults and with the queue handling of Alg. 1 as written (one shared queue per vrank, every
+    entry polled in turn); and the circular-wait pair with the smallest thresholds.  Each case runs
+    twice: with two clock reads per switch (the latency), and with the save / load parts timed too."""
+    out = _switch_summary(*_switch_run(1), _switch_run(2)[2])
+    alg1 = dict(chan_spread=0, scan_min=0)
+    out["alg1_single_queue"] = _switch_summary(*_switch_run(1, **alg1), _switch_run(2, **alg1)[2])
+    out["config1_tiny_threshold"] = _switch_summary(*_switch_config1(1), _switch_config1(2)[2])
+    return out
 
 
 def deadlock_prone():
@@ -203,6 +237,63 @@ def spin_sweep():
     return rows
 
 
+def studies():
+    """Two comparisons the paper makes (Sec. 5 "Optimizing CQ", Fig. 7c; Sec. 4.3 ordering policies):
+    CQE write time of the three completion-queue variants on the small-collective workload, and FIFO
+    against priority ordering ("later = more urgent") on the gradient buckets."""
+    import workload_inputs as wi
+    import paper_2303_06324_amd as dfx
+    from tests import gpu_harness as gh
+    out = {"cq_variants": [], "ordering_config3": []}
+    w5 = wi.config5(n_colls=1024, seed=4)
+    d5 = gh.DeviceWorkload(w5, keep_host=False)
+    for mode, name in ((0, "optimized CQ: one CAS into a free slot"), (1, "vanilla ring buffer"),
+                       (2, "optimized ring buffer: id + position in one 64-bit write")):
+        best = None
+        for rep in range(3):
+            ctx = dfx.Context(R, gh.make_config(cq_mode=mode))
+            try:
+                gh.prepare_all(ctx, w5)
+                t0 = time.perf_counter()
+                gh.submit_threads(ctx, d5, timeout_s=60)
+                rc = ctx.wait_all(60.0)
+                dt = time.perf_counter() - t0
+                ctx.stop()
+                st = [ctx.stats(r) for r in range(R)]
+            finally:
+                ctx.finalize()
+            n = sum(s["cqe_posted"] for s in st)
+            row = {"cq_mode": mode, "variant": name, "completed": rc == 0 and n == 1024 * R,
+                   "cqe_write_us_mean": round(sum(s["cqe_us"] for s in st) / max(1, n), 3),
+                   "collectives_per_s": round(1024 / dt, 1), "ms": round(dt * 1e3, 2)}
+            if best is None or row["cqe_write_us_mean"] < best["cqe_write_us_mean"]:
+                best = row
+        out["cq_variants"].append(best)
+    del d5
+    w3 = wi.config3()
+    d3 = gh.DeviceWorkload(w3, keep_host=False)
+    for policy, name in ((0, "FIFO ordering"), (1, "priority ordering, later bucket = higher priority")):
+        best = None
+        for rep in range(3):
+            ctx = dfx.Context(R, gh.make_config(order_policy=policy))
+            try:
+                gh.prepare_all(ctx, w3, priorities=list(range(len(w3.colls))))
+                t0 = time.perf_counter()
+                gh.submit_round_robin(ctx, d3, timeout_s=60)
+                rc = ctx.wait_all(60.0)
+                dt = time.perf_counter() - t0
+                ctx.stop()
+                pre = sum(ctx.stats(r)["preemptions"] for r in range(R))
+            finally:
+                ctx.finalize()
+            row = {"order_policy": policy, "policy": name, "completed": rc == 0, "ms": round(dt * 1e3, 3),
+                   "preemptions": pre}
+            if best is None or row["ms"] < best["ms"]:
+                best = row
+        out["ordering_config3"].append(best)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -215,6 +306,8 @@ def main():
     ap.add_argument("--no-orders", action="store_true", help="skip the deadlock-prone-orders leg")
     ap.add_argument("--sweep", action="store_true", help="add the 8 KiB .. 256 MiB size sweep to the JSON line")
     ap.add_argument("--spin-sweep", action="store_true", help="add the fixed-spin-threshold sweep to the JSON line")
+    ap.add_argument("--studies", action="store_true",
+                    help="add the CQ-variant and ordering-policy comparisons to the JSON line")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="after the steps, run one plain copy kernel of this many MiB (untimed): its known "
                          "traffic calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters")
@@ -309,6 +402,8 @@ def main():
         out["size_sweep"] = size_sweep()
     if args.spin_sweep:
         out["spin_sweep"] = spin_sweep()
+    if args.studies:
+        out["studies"] = studies()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_mib << 20)
     print(json.dumps(out), flush=True)
