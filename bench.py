@@ -21,9 +21,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 R = 8
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
-# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md): reads 5 810 615 KiB + writes
-# 5 769 075 KiB per launch at the default workload.  Reported only for that workload.
-MEASURED_TRAFFIC_BYTES = 11857602560
+# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md): reads 5 816 200 KiB + writes
+# 5 768 800 KiB per launch at the default workload.  Reported only for that workload.
+MEASURED_TRAFFIC_BYTES = 11863040000
 
 
 def algorithmic_bytes(msg_bytes: int, nranks: int) -> int:
