@@ -102,7 +102,8 @@ typedef struct {
                               system-scope CAS of the id into a free slot (default); 1 = vanilla ring buffer
                               (reserve, entry, fence, in-order tail update); 2 = optimized ring buffer (id and
                               position in one 64-bit atomic write, validated by the poller against its head) */
-  uint32_t reserved0;
+  uint32_t sq_eager;       /* 1 (default): a workgroup probes the SQ before every pass over its queue; 0: only when
+                              its queue is empty or a whole pass made no progress (FIFO ordering as Sec. 4.3 words it) */
 } dfx_config;
 
 /* Aggregated over the workgroups of one vrank since dfx_init. */

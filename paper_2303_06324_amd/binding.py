@@ -25,7 +25,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in (
         "struct_bytes", "max_channels", "max_colls", "sq_depth", "cq_slots", "nslots", "slot_bytes",
         "chan_min_bytes", "spin_init", "spin_min", "spin_max", "spin_boost", "preempt", "watchdog_ms",
-        "quit_idle_us", "sq_in_device", "wg_map", "order_policy", "trace", "fetch_batch")] + [("pool_bytes", C.c_uint64), ("scan_min", C.c_uint32), ("chan_spread", C.c_uint32), ("cq_mode", C.c_uint32), ("reserved0", C.c_uint32)]
+        "quit_idle_us", "sq_in_device", "wg_map", "order_policy", "trace", "fetch_batch")] + [("pool_bytes", C.c_uint64), ("scan_min", C.c_uint32), ("chan_spread", C.c_uint32), ("cq_mode", C.c_uint32), ("sq_eager", C.c_uint32)]
 
 
 class Stats(C.Structure):
@@ -127,13 +127,19 @@ class Context:
         """Returns the status (OK, ERR_SQ_FULL, ERR_BUSY ...) without raising: callers retry."""
         return _lib.dfx_submit(self._h, rank, coll_id, C.c_void_p(sendbuf), C.c_void_p(recvbuf))
 
-    def submit_many(self, rank: int, coll_ids, sendbufs, recvbufs, timeout_s: float = 30.0) -> int:
-        """Burst submission in C (the GIL is released for the whole call). Returns the count submitted."""
+    @staticmethod
+    def make_burst(coll_ids, sendbufs, recvbufs):
+        """Marshal a burst once (three C arrays), so that submitting it costs no Python work."""
         n = len(coll_ids)
-        ids = (C.c_int * n)(*coll_ids)
-        sb = (C.c_void_p * n)(*sendbufs)
-        rb = (C.c_void_p * n)(*recvbufs)
+        return n, (C.c_int * n)(*coll_ids), (C.c_void_p * n)(*sendbufs), (C.c_void_p * n)(*recvbufs)
+
+    def submit_burst(self, rank: int, burst, timeout_s: float = 30.0) -> int:
+        """Burst submission in C (the GIL is released for the whole call). Returns the count submitted."""
+        n, ids, sb, rb = burst
         return _lib.dfx_submit_many(self._h, rank, n, ids, sb, rb, int(timeout_s * 1e9))
+
+    def submit_many(self, rank: int, coll_ids, sendbufs, recvbufs, timeout_s: float = 30.0) -> int:
+        return self.submit_burst(rank, self.make_burst(coll_ids, sendbufs, recvbufs), timeout_s)
 
     def poll(self, rank: int, max_n: int = 64) -> List[Tuple[int, int]]:
         buf = (Cqe * max_n)()

@@ -382,7 +382,6 @@ struct Shared {
   DfxDaemonArgs args;
   DfxCtxEntry slot[DFX_CTX_SLOTS];   // active context slots (Sec. 5, direct-mapped)
   uint32_t slot_tag[DFX_CTX_SLOTS];
-  DfxStatic sqe;                     // SQE being fetched
   Job job[2];                        // posted jobs, indexed by job number & 1
   Flight fl[2];
   uint32_t job_seq;                  // jobs posted so far (scheduler -> movers)
@@ -702,10 +701,13 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         if (!in_pass) {
           ++iter;
           uint32_t s = STOP_NONE, got = 0;
-          // FIFO ordering (Sec. 4.3): fetch when the queue is empty or a whole pass made no
-          // progress, then keep fetching what is already there (up to fetch_batch); priority
-          // ordering probes the SQ before every pass.
-          const bool want = (qlen == 0) || !pass_progress || a.order_policy == 1 || (burst > 0 && burst < a.fetch_batch);
+          // The SQ is probed before every pass.  (Sec. 4.3 has FIFO ordering fetch only when the queue
+          // is empty or stuck and priority ordering before every pass.  Here the probe rides along
+          // with the control words and costs nothing, new entries join the queue's tail either way,
+          // and a workgroup that kept working without reading the SQ held back its rank's SQ slots
+          // -- every workgroup must read every SQE -- and with them the submitter and the rest of
+          // the grid.)  A fetch is followed by further fetches, up to fetch_batch in a row.
+          const bool want = (a.sq_eager && burst < a.fetch_batch) || (qlen == 0) || !pass_progress || a.order_policy == 1 || (burst > 0 && burst < a.fetch_batch);
           const bool probe = want && qlen < a.max_colls;
           const bool slow = ((iter & 31u) == 0) || qlen == 0 || !pass_progress;
           const bool host_look = ((iter & 31u) == 0) || qlen == 0;
@@ -759,32 +761,57 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           got = bcast0(got);
           if (s) { stop = s; continue; }
 
-          // ---- FetchSQE (Alg. 1 line 2)
+          // ---- FetchSQE (Alg. 1 line 2), up to 64 entries at a time: one per lane.
+          // Every workgroup of a rank reads every SQE of the rank (Sec. 5), so a burst of a thousand
+          // submissions is a thousand entries for each of them, most of them for other channels;
+          // taken one by one (a fence, six loads, an atomic with its answer) they cost more than
+          // the collectives they describe.
           if (got) {
-            DfxSqSlot* e = &sqbase[ri & (D - 1)];
-            // the submitter wrote the send buffer before the SQE: drop what this CU / XCD cached
+            // how many consecutive entries from the read index on are there?
+            uint32_t room = a.max_colls - qlen;
+            if (room > 64) room = 64;
+            const uint32_t left = burst < a.fetch_batch ? a.fetch_batch - burst : 1u;
+            if (left < room) room = left;
+            if (a.order_policy == 1) room = 1;       // the sorted insert below is written for one entry
+            bool here = false;
+            if (lane == 0) here = true;               // the control check has seen this one
+            else if (lane < room) {
+              const u64 idx = ri + lane;
+              here = __hip_atomic_load(&sqbase[idx & (D - 1)].e.ready, __ATOMIC_RELAXED, SCOPE_SYSTEM) == (uint32_t)(idx >> a.sq_shift) + 1u;
+            }
+            const u64 here_mask = __ballot(here);
+            uint32_t n = (here_mask == ~0ull) ? 64u : (uint32_t)__builtin_ctzll(~here_mask);   // length of the run that starts at lane 0
+            // the submitter wrote the send buffers before the SQEs: drop what this CU / XCD cached
             fence_acquire_system();
-            if (lane < 6) ((uint4*)&sh.sqe)[lane] = ((const uint4*)&e->e)[lane];
-            __builtin_amdgcn_wave_barrier();
-            const uint32_t c_id = sh.sqe.coll_id;
-            const uint32_t flags = sh.sqe.flags;
-            // an exit SQE ends the launch it was posted for; one left over from an earlier launch
-            // (some workgroups had already gone when it arrived) is consumed and ignored
-            const bool is_exit_sqe = (flags & DFX_SQE_EXIT) != 0;
-            const bool is_exit = is_exit_sqe && sh.sqe.seq == a.epoch;
-            // A collective with fewer channels than the grid has per rank starts at workgroup
-            // (coll_id * nchan) mod cmax, so that many small collectives spread over the rank's
-            // workgroups instead of queueing on the first ones; every rank derives the same
-            // start from the id, which keeps both ends of a connector on the same channel.
-            uint32_t my_vch = ch;
-            if (a.chan_spread && !is_exit_sqe && sh.sqe.nchan < a.cmax)
-              my_vch = (ch + a.cmax - (c_id * sh.sqe.nchan) % a.cmax) % a.cmax;
-            const bool mine = !is_exit_sqe && my_vch < sh.sqe.nchan && c_id < a.max_colls;
-            if (mine) {
-              // cook the static context of this invocation into the context buffer (addresses
-              // resolved once, here); restart the sequence, keep the monotone connector counters
-              if (lane == 0) {
-                const DfxStatic& q = sh.sqe;
+            DfxStatic q;
+            bool is_exit_sqe = false, is_exit = false;
+            if (lane < n) {
+              const uint4* src = (const uint4*)&sqbase[(ri + lane) & (D - 1)].e;
+              uint4* qv = (uint4*)&q;
+#pragma unroll
+              for (int i = 0; i < 6; ++i) qv[i] = src[i];
+              // an exit SQE ends the launch it was posted for; one left over from an earlier launch
+              // (some workgroups had already gone when it arrived) is consumed and ignored
+              is_exit_sqe = (q.flags & DFX_SQE_EXIT) != 0;
+              is_exit = is_exit_sqe && q.seq == a.epoch;
+            }
+            const u64 exit_mask = __ballot(is_exit);
+            if (exit_mask) n = (uint32_t)__builtin_ctzll(exit_mask) + 1;   // nothing behind an exit SQE is touched
+            bool mine = false;
+            uint32_t c_id = 0;
+            if (lane < n) {
+              c_id = q.coll_id;
+              // A collective with fewer channels than the grid has per rank starts at workgroup
+              // (coll_id * nchan) mod cmax, so that many small collectives spread over the rank's
+              // workgroups instead of queueing on the first ones; every rank derives the same
+              // start from the id, which keeps both ends of a connector on the same channel.
+              uint32_t my_vch = ch;
+              if (a.chan_spread && !is_exit_sqe && q.nchan < a.cmax)
+                my_vch = (ch + a.cmax - (c_id * q.nchan) % a.cmax) % a.cmax;
+              mine = !is_exit_sqe && my_vch < q.nchan && c_id < a.max_colls;
+              if (mine) {
+                // cook the static context of this invocation into the context buffer (addresses
+                // resolved once, here); restart the sequence, keep the monotone connector counters
                 DfxCooked k;
                 k.sendbuf = q.sendbuf; k.recvbuf = q.recvbuf; k.count = q.count;
                 k.block_elems = q.block_elems; k.part_elems = q.part_elems;
@@ -807,39 +834,45 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 DfxDyn* dy = &myctx[c_id].dyn;
                 dy->round = 0; dy->prim = 0; dy->preempted = 0;
                 dy->cidx = (q.kind == KIND_AG) ? rank : ((q.kind == KIND_BC || q.kind == KIND_RD || a.R == 1) ? 0u : cidx0_reduce);
-                // FIFO ordering: append; priority ordering: keep the queue sorted (stable)
-                uint32_t at = qlen;
-                if (a.order_policy == 1) {
-                  const int16_t pr = q.priority;
-                  while (at > 0 && myctx[sh.taskq[at - 1]].st.priority < pr) { sh.taskq[at] = sh.taskq[at - 1]; --at; }
-                }
-                sh.taskq[at] = (uint16_t)c_id;
                 if (sh.slot_tag[c_id % DFX_CTX_SLOTS] == c_id) sh.slot_tag[c_id % DFX_CTX_SLOTS] = 0xffffffffu;
               }
-              ++qlen;
-              if (lane == 0) __hip_atomic_fetch_max(&sh.stat[ST_MAXQ], (u64)qlen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
-            if (lane == 0) {
               // every workgroup of the rank reads every SQE; the last reader frees the slot (Sec. 5)
-              uint32_t* rc = &a.sq_readers[(size_t)rank * D + (ri & (D - 1))];
+              uint32_t* rc = &a.sq_readers[(size_t)rank * D + ((ri + lane) & (D - 1))];
               const uint32_t old = __hip_atomic_fetch_add(rc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
               if (old + 1 == a.cmax) {
                 __hip_atomic_store(rc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
-                __hip_atomic_store(&e->e.ready, 0u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
+                __hip_atomic_store(&sqbase[(ri + lane) & (D - 1)].e.ready, 0u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
               }
-              bump(sh.stat, ST_SQE, 1);
+            }
+            // the entries that are this workgroup's join the task queue in SQ order
+            const u64 mine_mask = __ballot(mine);
+            if (mine) {
+              if (a.order_policy == 1) {
+                // priority ordering: keep the queue sorted (stable); one entry per fetch in this mode
+                uint32_t at = qlen;
+                const int16_t pr = q.priority;
+                while (at > 0 && myctx[sh.taskq[at - 1]].st.priority < pr) { sh.taskq[at] = sh.taskq[at - 1]; --at; }
+                sh.taskq[at] = (uint16_t)c_id;
+              } else {
+                sh.taskq[qlen + (uint32_t)__builtin_popcountll(mine_mask & ((1ull << lane) - 1ull))] = (uint16_t)c_id;
+              }
+            }
+            qlen += (uint32_t)__builtin_popcountll(mine_mask);
+            if (lane == 0) {
+              bump(sh.stat, ST_SQE, n);
+              __hip_atomic_fetch_max(&sh.stat[ST_MAXQ], (u64)qlen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
             __builtin_amdgcn_wave_barrier();
             acted = true;
             sw_pending = false;
-            ++ri;
-            if (is_exit) {
+            ri += n;
+            if (exit_mask) {
               // the whole grid leaves (every workgroup has reader duties towards its rank's SQ)
               if (lane == 0) __hip_atomic_store(&a.dev_ctl[DC_QUIT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
               stop = STOP_EXIT;
               continue;
             }
-            ++burst;
+            burst += n;
             idle = 0;
             continue;               // probe the SQ again before walking the queue
           }

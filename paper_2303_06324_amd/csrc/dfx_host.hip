@@ -169,7 +169,7 @@ int launch_locked(dfx_ctx* c) {
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   a.nwg = c->nwg;
-  a.cq_ctl = c->cq_ctl; a.cq_mode = c->cfg.cq_mode;
+  a.cq_ctl = c->cq_ctl; a.cq_mode = c->cfg.cq_mode; a.sq_eager = c->cfg.sq_eager;
   a.scan_min = c->cfg.scan_min;
   a.chan_spread = c->cfg.chan_spread;
   a.epoch = (uint32_t)(c->launches + 1);
@@ -305,7 +305,7 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->scan_min = 3;
   cfg->chan_spread = 1;
   cfg->cq_mode = 0;
-  cfg->reserved0 = 0;
+  cfg->sq_eager = 1;
   cfg->preempt = 1;
   cfg->watchdog_ms = 10000;
   cfg->quit_idle_us = 2000;
@@ -489,35 +489,47 @@ int dfx_coll_info(dfx_ctx* c, int coll_id, uint32_t* nchan, uint32_t* slot_bytes
   return DFX_OK;
 }
 
-int dfx_submit(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* recvbuf) {
-  if (!c || rank < 0 || rank >= c->R) return DFX_ERR_INVALID_ARG;
+}  // extern "C"
+
+namespace {
+
+// Write the SQE of one invocation; the caller sees to it that the daemon runs.
+int submit_one(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* recvbuf) {
   if (coll_id < 0 || (uint32_t)coll_id >= c->cfg.max_colls) return DFX_ERR_INVALID_ARG;
   if (c->aborted.load()) return DFX_ERR_ABORTED;
   const CollInfo& ci = c->colls[coll_id];
   if (!ci.prepared) return DFX_ERR_NOT_PREPARED;
   if (!sendbuf || !recvbuf || ((uintptr_t)sendbuf & 15u) || ((uintptr_t)recvbuf & 15u)) return DFX_ERR_INVALID_ARG;
   RankState* rs = c->ranks[rank];
-  int rc;
-  {
-    std::lock_guard<std::mutex> lk(rs->mu);
-    if (rs->sub[coll_id] != rs->done[coll_id]) {
-      drain_cq(c, rank);
-      if (rs->sub[coll_id] != rs->done[coll_id]) return DFX_ERR_BUSY;
-    }
-    DfxStatic e = ci.tmpl;
-    e.seq = rs->sub[coll_id];
-    e.sendbuf = (uint64_t)(uintptr_t)sendbuf;
-    e.recvbuf = (uint64_t)(uintptr_t)recvbuf;
-    rc = push_sqe(c, rank, e);
-    if (rc == DFX_OK) {
-      rs->sub[coll_id]++;
-      rs->n_sub.fetch_add(1, std::memory_order_relaxed);
-    } else {
-      // There is no poller thread: a caller that only retries submissions must still empty the
-      // CQ, or a workgroup blocked on a full CQ stops reading SQEs and the SQ never drains.
-      drain_cq(c, rank);
-    }
+  std::lock_guard<std::mutex> lk(rs->mu);
+  if (rs->sub[coll_id] != rs->done[coll_id]) {
+    drain_cq(c, rank);
+    if (rs->sub[coll_id] != rs->done[coll_id]) return DFX_ERR_BUSY;
   }
+  DfxStatic e = ci.tmpl;
+  e.seq = rs->sub[coll_id];
+  e.sendbuf = (uint64_t)(uintptr_t)sendbuf;
+  e.recvbuf = (uint64_t)(uintptr_t)recvbuf;
+  const int rc = push_sqe(c, rank, e);
+  if (rc == DFX_OK) {
+    rs->sub[coll_id]++;
+    rs->n_sub.fetch_add(1, std::memory_order_relaxed);
+  } else {
+    // A caller that only retries submissions must still empty the CQ, or a workgroup blocked
+    // on a full CQ stops reading SQEs and the SQ never drains.
+    drain_cq(c, rank);
+  }
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dfx_submit(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* recvbuf) {
+  if (!c || rank < 0 || rank >= c->R) return DFX_ERR_INVALID_ARG;
+  const int rc = submit_one(c, rank, coll_id, sendbuf, recvbuf);
+  if (rc != DFX_OK && rc != DFX_ERR_SQ_FULL) return rc;
   // start the daemon on SQE insertion; also when the SQ is full (a quit daemon frees no slots)
   c->user_stopped.store(false);
   int rr = ensure_running(c);
@@ -527,14 +539,26 @@ int dfx_submit(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* rec
 
 int dfx_submit_many(dfx_ctx* c, int rank, int n, const int* coll_ids, const void* const* sendbufs,
                     void* const* recvbufs, uint64_t timeout_ns) {
-  if (!c || n < 0 || (n > 0 && (!coll_ids || !sendbufs || !recvbufs))) return DFX_ERR_INVALID_ARG;
+  if (!c || rank < 0 || rank >= c->R || n < 0 || (n > 0 && (!coll_ids || !sendbufs || !recvbufs))) return DFX_ERR_INVALID_ARG;
   const uint64_t t0 = now_ns();
   uint32_t spins = 0;
-  int i = 0;
+  int i = 0, since_check = 0;
+  c->user_stopped.store(false);
+  // The daemon is looked after (launch state behind one lock, an event query) after the first
+  // entry, then every 32 entries, whenever the SQ is full, and after the last one -- not per entry.
   while (i < n) {
-    const int rc = dfx_submit(c, rank, coll_ids[i], sendbufs[i], recvbufs[i]);
-    if (rc == DFX_OK) { ++i; spins = 0; continue; }
+    const int rc = submit_one(c, rank, coll_ids[i], sendbufs[i], recvbufs[i]);
+    if (rc == DFX_OK) {
+      ++i; spins = 0;
+      if (since_check++ % 32 == 0 || i == n) {
+        const int rr = ensure_running(c);
+        if (rr != DFX_OK) return rr;
+      }
+      continue;
+    }
     if (rc != DFX_ERR_SQ_FULL) return i > 0 ? i : rc;
+    const int rr = ensure_running(c);
+    if (rr != DFX_OK) return i > 0 ? i : rr;
     if (now_ns() - t0 > timeout_ns) return i;
     backoff(spins);
   }

@@ -52,6 +52,13 @@ class DeviceWorkload:
             self.recv[ci] = [torch.full((max(nbytes, 16),), SENTINEL, dtype=torch.uint8, device="cuda")
                              for _ in range(w.R)]
         torch.cuda.synchronize()
+        # the per-rank bursts of the workload's own issue orders, marshalled once (kept out of timed regions)
+        self.bursts = None
+        if colls is None:
+            self.bursts = [dfx.Context.make_burst([w.colls[ci].coll_id for ci in w.orders[r]],
+                                                  [self.send[ci][r].data_ptr() for ci in w.orders[r]],
+                                                  [self.recv[ci][r].data_ptr() for ci in w.orders[r]])
+                           for r in range(w.R)]
 
     def reset_recv(self):
         for ci in self.idx:
@@ -108,9 +115,14 @@ def submit_threads(ctx: "dfx.Context", dw: DeviceWorkload, orders=None, delays_u
     def work(r):
         try:
             if not delays_us:      # one native burst per rank: the host threads really run concurrently
-                ids = [w.colls[ci].coll_id for ci in orders[r]]
-                n = ctx.submit_many(r, ids, [dw.send[ci][r].data_ptr() for ci in orders[r]],
-                                    [dw.recv[ci][r].data_ptr() for ci in orders[r]], timeout_s)
+                if orders is w.orders and dw.bursts is not None:
+                    burst = dw.bursts[r]
+                else:
+                    burst = ctx.make_burst([w.colls[ci].coll_id for ci in orders[r]],
+                                           [dw.send[ci][r].data_ptr() for ci in orders[r]],
+                                           [dw.recv[ci][r].data_ptr() for ci in orders[r]])
+                ids = burst[1]
+                n = ctx.submit_burst(r, burst, timeout_s)
                 if n != len(ids):
                     raise dfx.DfxError(n if n < 0 else dfx.ERR_TIMEOUT, f"dfx_submit_many(rank={r}) -> {n}")
                 return

@@ -127,12 +127,23 @@ def test_sq_backpressure_and_poll_interface():
     import paper_2303_06324_amd as dfx
     w = wi.config5(n_colls=40, seed=9, R=4)
     dw = gh.DeviceWorkload(w)
-    ctx = dfx.Context(4, gh.make_config(sq_depth=4, max_channels=8))
+    import torch
+    stream = torch.cuda.Stream()                     # default priority
+    ctx = dfx.Context(4, gh.make_config(sq_depth=4, max_channels=8), stream=stream.cuda_stream)
     try:
         gh.prepare_all(ctx, w)
-        full = 0
+        # The daemon's launch queues behind a kernel that just waits for a while, so nothing reads the
+        # SQ yet: four entries of vrank 0 fit, the fifth finds the ring full.
+        with torch.cuda.stream(stream):
+            torch.cuda._sleep(20_000_000)
+        for j in range(4):
+            ci = w.orders[0][j]
+            assert ctx.submit(0, ci, dw.send[ci][0].data_ptr(), dw.recv[ci][0].data_ptr()) == dfx.OK
+        ci = w.orders[0][4]
+        assert ctx.submit(0, ci, dw.send[ci][0].data_ptr(), dw.recv[ci][0].data_ptr()) == dfx.ERR_SQ_FULL
+        full = 1
         seen = [set() for _ in range(4)]
-        pos = [0] * 4
+        pos = [4, 0, 0, 0]
         deadline = time.monotonic() + 30
         while any(p < 40 for p in pos) or any(len(s) < 40 for s in seen):
             for r in range(4):
