@@ -147,24 +147,29 @@ def deadlock_prone():
                           ("config4_64_mixed", wi.config4(), "threads"),
                           ("config5_1024_small", wi.config5(), "threads")):
         dw = gh.DeviceWorkload(w, keep_host=False)
-        ctx = dfx.Context(R, gh.make_config())
-        try:
-            gh.prepare_all(ctx, w)
-            t0 = time.perf_counter()
-            if mode == "threads":
-                gh.submit_threads(ctx, dw, delays_us=w.delays_us or None, timeout_s=60)
-            else:
-                gh.submit_round_robin(ctx, dw, timeout_s=60)
-            rc = ctx.wait_all(60.0)
-            dt = time.perf_counter() - t0
-            ctx.stop()
-            st = [ctx.stats(r) for r in range(R)]
-        finally:
-            ctx.finalize()
+        runs = []
+        for rep in range(3):        # a fresh context each time; the first run also pays first-touch costs
+            ctx = dfx.Context(R, gh.make_config())
+            try:
+                gh.prepare_all(ctx, w)
+                t0 = time.perf_counter()
+                if mode == "threads":
+                    gh.submit_threads(ctx, dw, delays_us=w.delays_us or None, timeout_s=60)
+                else:
+                    gh.submit_round_robin(ctx, dw, timeout_s=60)
+                rc = ctx.wait_all(60.0)
+                dt = time.perf_counter() - t0
+                ctx.stop()
+                st = [ctx.stats(r) for r in range(R)]
+            finally:
+                ctx.finalize()
+            runs.append((dt, rc == 0 and sum(s["cqe_posted"] for s in st) == len(w.colls) * R,
+                         sum(s["preemptions"] for s in st), max(s["max_taskq"] for s in st)))
         del dw
-        out[name] = {"completed": rc == 0 and sum(s["cqe_posted"] for s in st) == len(w.colls) * R,
-                     "seconds": round(dt, 4), "preemptions": sum(s["preemptions"] for s in st),
-                     "max_task_queue": max(s["max_taskq"] for s in st)}
+        best = min(runs)
+        out[name] = {"completed": all(r[1] for r in runs), "seconds": round(best[0], 4),
+                     "seconds_all_runs": [round(r[0], 4) for r in runs],
+                     "preemptions": best[2], "max_task_queue": best[3]}
     return out
 
 
