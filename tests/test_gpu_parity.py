@@ -212,3 +212,35 @@ def test_max_min_ties_and_signed_zeros():
                 assert np.array_equal(d[r].cpu().numpy().view(np.uint32), want.view(np.uint32))
         finally:
             ctx.finalize()
+
+
+def _mixed_workload(seed, n_colls=40, R=8):
+    """Config-4-like mix drawn from the seed, widened to all five kinds and all four reducing functions."""
+    g = np.random.default_rng(np.random.SeedSequence([seed, 404]))
+    colls = []
+    for i in range(n_colls):
+        kind = int(g.integers(0, 5))
+        dtype = int(g.integers(0, 4))
+        op = int(g.integers(0, 4))
+        size = int(np.exp(g.uniform(np.log(64), np.log(2 << 20))))          # bytes of the largest per-rank buffer
+        elems = max(1, size // wi.ELEM_BYTES[dtype])
+        count = max(1, elems // R) if kind in (wi.AG, wi.RS) else elems
+        colls.append(wi.CollSpec(i, kind, dtype, count, int(g.integers(0, R)), op))
+    orders = [list(map(int, g.permutation(n_colls))) for _ in range(R)]
+    delays = [list(map(float, g.uniform(0.0, 20.0, size=n_colls))) for _ in range(R)]
+    return wi.Workload(f"mixed_seed{seed}", R, colls, orders, delays_us=delays, seed=seed, cfg=44)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_mix_of_kinds_ops_and_orders(seed):
+    """Forty collectives of random kind (reduce included), dtype, reducing function, ragged size and root,
+    every vrank submitting from its own thread in its own order with small delays; bit-exact against the
+    oracle's closed forms.  Product runs on N(0,1) values: eight factors neither overflow nor vanish."""
+    _run(_mixed_workload(seed), mode="threads", timeout_s=60.0)
+
+
+def test_random_mix_single_queue_forced_preemption():
+    """The same kind of mix with everything on one workgroup per vrank, Alg. 1's own queue handling and the
+    smallest thresholds: every late flag preempts."""
+    _run(_mixed_workload(7, n_colls=24), mode="threads", timeout_s=60.0, max_channels=1, chan_spread=0,
+         scan_min=0, spin_init=1, spin_min=1, spin_max=1, spin_boost=1)
