@@ -190,10 +190,10 @@ def size_sweep(iters: int = 10):
         try:
             ctx.prepare(0, dfx.ALLREDUCE, n, dfx.F32)
             best = 1e9
+            ptrs = ctx.make_all([t.data_ptr() for t in send], [t.data_ptr() for t in recv])
             for _ in range(iters + 2):
                 t0 = time.perf_counter()
-                for r in range(R):
-                    assert ctx.submit(r, 0, send[r].data_ptr(), recv[r].data_ptr()) == dfx.OK
+                assert ctx.submit_all(0, ptrs) == dfx.OK
                 assert ctx.wait_all(30.0) == dfx.OK
                 best = min(best, time.perf_counter() - t0)
             nchan = ctx.coll_info(0)["nchan"]

@@ -175,6 +175,15 @@ int dfx_prepare(dfx_ctx* ctx, int coll_id, dfx_kind kind, size_t count, dfx_dtyp
 int dfx_submit(dfx_ctx* ctx, int rank, int coll_id, const void* sendbuf, void* recvbuf);
 
 /*
+ * One invocation of coll_id on every vrank in a single call (vrank order 0 .. nranks-1):
+ * sendbufs / recvbufs: host arrays of nranks device pointers.  The same as nranks dfx_submit calls,
+ * minus nranks-1 trips through the caller's language binding; for the single-process setting in which
+ * one thread drives all vranks.  Returns DFX_OK, or the first status that is not OK (vranks before it
+ * have been submitted; a full SQ is retried for up to timeout_ns first).
+ */
+int dfx_submit_all(dfx_ctx* ctx, int coll_id, const void* const* sendbufs, void* const* recvbufs, uint64_t timeout_ns);
+
+/*
  * Submit n collectives of one vrank in the given order (a burst of dfcclRun* calls, e.g. the
  * gradient buckets of one backward pass): element i is dfx_submit(ctx, rank, coll_ids[i],
  * sendbufs[i], recvbufs[i]).  A full SQ is retried until timeout_ns has passed.  The three arrays

@@ -70,6 +70,7 @@ def _load() -> C.CDLL:
         "dfx_prepare": ([vp, i, i, sz, i, i, i, i], i),
         "dfx_submit": ([vp, i, i, vp, vp], i),
         "dfx_submit_many": ([vp, i, i, C.POINTER(C.c_int), C.POINTER(vp), C.POINTER(vp), u64], i),
+        "dfx_submit_all": ([vp, i, C.POINTER(vp), C.POINTER(vp), u64], i),
         "dfx_poll": ([vp, i, C.POINTER(Cqe), i], i),
         "dfx_wait": ([vp, i, i, u64], i),
         "dfx_wait_all": ([vp, u64], i),
@@ -126,6 +127,14 @@ class Context:
     def submit(self, rank: int, coll_id: int, sendbuf: int, recvbuf: int) -> int:
         """Returns the status (OK, ERR_SQ_FULL, ERR_BUSY ...) without raising: callers retry."""
         return _lib.dfx_submit(self._h, rank, coll_id, C.c_void_p(sendbuf), C.c_void_p(recvbuf))
+
+    def make_all(self, sendbufs, recvbufs):
+        """Marshal the per-vrank pointers of one invocation once."""
+        return (C.c_void_p * self.nranks)(*sendbufs), (C.c_void_p * self.nranks)(*recvbufs)
+
+    def submit_all(self, coll_id: int, ptrs, timeout_s: float = 30.0) -> int:
+        """One invocation on every vrank in one call; ptrs from make_all. Returns the status."""
+        return _lib.dfx_submit_all(self._h, coll_id, ptrs[0], ptrs[1], int(timeout_s * 1e9))
 
     @staticmethod
     def make_burst(coll_ids, sendbufs, recvbufs):

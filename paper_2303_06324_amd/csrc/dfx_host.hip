@@ -537,6 +537,29 @@ int dfx_submit(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* rec
   return rc;
 }
 
+int dfx_submit_all(dfx_ctx* c, int coll_id, const void* const* sendbufs, void* const* recvbufs, uint64_t timeout_ns) {
+  if (!c || !sendbufs || !recvbufs) return DFX_ERR_INVALID_ARG;
+  const uint64_t t0 = now_ns();
+  c->user_stopped.store(false);
+  for (int r = 0; r < c->R; ++r) {
+    uint32_t spins = 0;
+    for (;;) {
+      const int rc = submit_one(c, r, coll_id, sendbufs[r], recvbufs[r]);
+      if (rc == DFX_OK) break;
+      if (rc != DFX_ERR_SQ_FULL) return rc;
+      const int rr = ensure_running(c);
+      if (rr != DFX_OK) return rr;
+      if (now_ns() - t0 > timeout_ns) return DFX_ERR_SQ_FULL;
+      backoff(spins);
+    }
+    if (r == 0 || r == c->R - 1) {   // start the daemon with the first entry, look again after the last
+      const int rr = ensure_running(c);
+      if (rr != DFX_OK) return rr;
+    }
+  }
+  return DFX_OK;
+}
+
 int dfx_submit_many(dfx_ctx* c, int rank, int n, const int* coll_ids, const void* const* sendbufs,
                     void* const* recvbufs, uint64_t timeout_ns) {
   if (!c || rank < 0 || rank >= c->R || n < 0 || (n > 0 && (!coll_ids || !sendbufs || !recvbufs))) return DFX_ERR_INVALID_ARG;

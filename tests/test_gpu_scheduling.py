@@ -339,3 +339,24 @@ def test_callback_poller_thread():
             _expect(dw, w, ci)
     finally:
         assert ctx.finalize() == dfx.OK
+
+
+def test_submit_all_is_one_invocation_on_every_vrank():
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.Workload("submit_all", 8, [wi.CollSpec(0, wi.AR, wi.I32, 70001)], [[0]] * 8, seed=31, cfg=72)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(8, gh.make_config())
+    try:
+        gh.prepare_all(ctx, w)
+        ptrs = ctx.make_all([t.data_ptr() for t in dw.send[0]], [t.data_ptr() for t in dw.recv[0]])
+        for it in range(3):
+            assert ctx.submit_all(0, ptrs) == dfx.OK
+            if it == 0:
+                assert ctx.submit_all(0, ptrs) == dfx.ERR_BUSY        # the invocation is outstanding on vrank 0
+            assert ctx.wait_all(20.0) == dfx.OK
+            _expect(dw, w, 0)
+        assert ctx.stop() == dfx.OK                      # counters are written back when the workgroups leave
+        assert [s["cqe_posted"] for s in (ctx.stats(r) for r in range(8))] == [3] * 8
+    finally:
+        assert ctx.finalize() == dfx.OK
