@@ -125,3 +125,45 @@ def test_config5_full_1024_small_allreduces():
             assert np.array_equal(got[r].view(np.uint8), want.view(np.uint8)), (ci, r)
     assert sum(s["cqe_posted"] for s in stats) == 1024 * 8
     assert max(s["max_taskq"] for s in stats) <= 1024
+
+
+def test_allreduce_beyond_4GiB_offsets_sampled():
+    """R = 2, int32, 5 GiB + a ragged tail per rank: byte offsets inside one buffer pass 2^32, thousands of
+    slices per channel.  Integer sums are exact in any order, so whole-buffer checks run on the device too;
+    sampled windows (chunk boundary, both ends, around the 4 GiB mark, random) go through the oracle."""
+    import torch
+    import paper_2303_06324_amd as dfx
+    R, n = 2, (5 << 30) // 4 + 12345
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    send = [torch.randint(-(1 << 20), 1 << 20, (n,), device="cuda", dtype=torch.int32, generator=g) for _ in range(R)]
+    recv = [torch.full((n,), -7, device="cuda", dtype=torch.int32) for _ in range(R)]
+    torch.cuda.synchronize()
+    ctx = dfx.Context(R)
+    try:
+        ctx.prepare(0, dfx.ALLREDUCE, n, dfx.I32)
+        info = ctx.coll_info(0)
+        assert info["rounds"] > 100
+        for r in range(R):
+            assert ctx.submit(r, 0, send[r].data_ptr(), recv[r].data_ptr()) == dfx.OK
+        assert ctx.wait_all(60.0) == dfx.OK
+        ctx.stop()
+    finally:
+        ctx.finalize()
+    assert torch.equal(recv[0], recv[1])
+    assert torch.equal(recv[0], send[0] + send[1])           # exact, order-free; on the device
+    rng = np.random.default_rng(8)
+    ce, wins = _windows(n, R, 4, rng, nwin=24)
+    mark = (4 << 30) // 4
+    wins.append((mark - 1024, mark + 1024))
+    for lo, hi in wins:
+        blocks = [s[lo:hi].cpu().numpy() for s in send]
+        got = recv[1][lo:hi].cpu().numpy()
+        want = np.empty(hi - lo, np.int32)
+        i = lo
+        while i < hi:
+            c = i // ce
+            j = min(hi, (c + 1) * ce)
+            want[i - lo:j - lo] = rd.fold_rotated([b[i - lo:j - lo] for b in blocks], c + 1, rd.I32)
+            i = j
+        assert np.array_equal(got, want), (lo, hi)
