@@ -67,14 +67,20 @@ __device__ __forceinline__ void fence_release_system() { __builtin_amdgcn_fence(
 // ------------------------------------------------------------------------------------------
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// two fp32 values -> packed bf16, round to nearest even: one conversion instruction on gfx950
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
+  f32x2_t s;
+  s[0] = lo; s[1] = hi;
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(s, bf16x2_t));
+}
+
 __device__ __forceinline__ uint32_t bf16x2_add(uint32_t a, uint32_t b) {
   // widen (exact), add in fp32, round to nearest even back to bf16
-  float lo = __uint_as_float(a << 16) + __uint_as_float(b << 16);
-  float hi = __uint_as_float(a & 0xffff0000u) + __uint_as_float(b & 0xffff0000u);
-  uint32_t ul = __float_as_uint(lo), uh = __float_as_uint(hi);
-  ul = (ul + 0x7fffu + ((ul >> 16) & 1u)) >> 16;
-  uh = (uh + 0x7fffu + ((uh >> 16) & 1u)) & 0xffff0000u;
-  return uh | ul;
+  return pack_bf16_rne(__uint_as_float(a << 16) + __uint_as_float(b << 16),
+                       __uint_as_float(a & 0xffff0000u) + __uint_as_float(b & 0xffff0000u));
 }
 
 template <int DT>
@@ -114,51 +120,83 @@ __device__ __forceinline__ uint16_t add_half(uint16_t a, uint16_t b) {
 // values (+0 / -0 included) behave the same everywhere.
 enum { OP_SUM = 0, OP_PROD = 1, OP_MAX = 2, OP_MIN = 3 };
 
-__device__ __forceinline__ uint32_t bf16x2_op(uint32_t a, uint32_t b, int op) {
+template <int OP>
+__device__ __forceinline__ uint32_t bf16x2_op(uint32_t a, uint32_t b) {
   const float al = __uint_as_float(a << 16), bl = __uint_as_float(b << 16);
   const float ah = __uint_as_float(a & 0xffff0000u), bh = __uint_as_float(b & 0xffff0000u);
-  if (op == OP_PROD) {
-    uint32_t ul = __float_as_uint(al * bl), uh = __float_as_uint(ah * bh);
-    ul = (ul + 0x7fffu + ((ul >> 16) & 1u)) >> 16;
-    uh = (uh + 0x7fffu + ((uh >> 16) & 1u)) & 0xffff0000u;
-    return uh | ul;
-  }
-  const bool tl = (op == OP_MAX) ? (al > bl) : (al < bl);
-  const bool th = (op == OP_MAX) ? (ah > bh) : (ah < bh);
+  if (OP == OP_PROD) return pack_bf16_rne(al * bl, ah * bh);
+  const bool tl = (OP == OP_MAX) ? (al > bl) : (al < bl);
+  const bool th = (OP == OP_MAX) ? (ah > bh) : (ah < bh);
   return ((tl ? a : b) & 0xffffu) | ((th ? a : b) & 0xffff0000u);
 }
 
-template <int DT>
-__device__ __forceinline__ uint32_t op_word(uint32_t a, uint32_t b, int op) {
-  if (op == OP_SUM) return add_word<DT>(a, b);
+// one 32-bit word (one fp32 / int32 element or two 16-bit ones), reducing function fixed at compile time
+template <int DT, int OP>
+__device__ __forceinline__ uint32_t op_word_t(uint32_t a, uint32_t b) {
+  if (OP == OP_SUM) return add_word<DT>(a, b);
   if (DT == DT_F32) {
     const float x = __uint_as_float(a), y = __uint_as_float(b);
-    if (op == OP_PROD) return __float_as_uint(x * y);
-    return ((op == OP_MAX) ? (x > y) : (x < y)) ? a : b;
+    if (OP == OP_PROD) return __float_as_uint(x * y);
+    return ((OP == OP_MAX) ? (x > y) : (x < y)) ? a : b;
   }
   if (DT == DT_I32) {
-    if (op == OP_PROD) return a * b;
+    if (OP == OP_PROD) return a * b;
     const int x = (int)a, y = (int)b;
-    return ((op == OP_MAX) ? (x > y) : (x < y)) ? a : b;
+    return ((OP == OP_MAX) ? (x > y) : (x < y)) ? a : b;
   }
   if (DT == DT_F16) {
     const half2_t x = __builtin_bit_cast(half2_t, a), y = __builtin_bit_cast(half2_t, b);
-    if (op == OP_PROD) return __builtin_bit_cast(uint32_t, x * y);
-    const bool tl = (op == OP_MAX) ? (x[0] > y[0]) : (x[0] < y[0]);
-    const bool th = (op == OP_MAX) ? (x[1] > y[1]) : (x[1] < y[1]);
+    if (OP == OP_PROD) return __builtin_bit_cast(uint32_t, x * y);
+    const bool tl = (OP == OP_MAX) ? (x[0] > y[0]) : (x[0] < y[0]);
+    const bool th = (OP == OP_MAX) ? (x[1] > y[1]) : (x[1] < y[1]);
     return ((tl ? a : b) & 0xffffu) | ((th ? a : b) & 0xffff0000u);
   }
-  return bf16x2_op(a, b, op);
+  return bf16x2_op<OP>(a, b);
 }
 
+// the same with the reducing function picked at run time (element-wise tails)
 template <int DT>
-__device__ __forceinline__ uint4 op_vec(uint4 a, uint4 b, int op) {
+__device__ __forceinline__ uint32_t op_word(uint32_t a, uint32_t b, int op) {
+  switch (op) {
+    case OP_PROD: return op_word_t<DT, OP_PROD>(a, b);
+    case OP_MAX: return op_word_t<DT, OP_MAX>(a, b);
+    case OP_MIN: return op_word_t<DT, OP_MIN>(a, b);
+    default: return add_word<DT>(a, b);
+  }
+}
+
+template <int DT, int OP>
+__device__ __forceinline__ uint4 op_vec_t(uint4 a, uint4 b) {
   uint4 r;
-  r.x = op_word<DT>(a.x, b.x, op);
-  r.y = op_word<DT>(a.y, b.y, op);
-  r.z = op_word<DT>(a.z, b.z, op);
-  r.w = op_word<DT>(a.w, b.w, op);
+  r.x = op_word_t<DT, OP>(a.x, b.x);
+  r.y = op_word_t<DT, OP>(a.y, b.y);
+  r.z = op_word_t<DT, OP>(a.z, b.z);
+  r.w = op_word_t<DT, OP>(a.w, b.w);
   return r;
+}
+
+// A whole batch of vectors under one (wave-uniform) branch on the reducing function: the branch
+// stays out of the unrolled loads and stores around it.
+template <int DT, int N>
+__device__ __forceinline__ void op_batch(uint4 (&v)[N], const uint4 (&w)[N], int op) {
+  switch (op) {
+    case OP_PROD:
+#pragma unroll
+      for (int u = 0; u < N; ++u) v[u] = op_vec_t<DT, OP_PROD>(v[u], w[u]);
+      break;
+    case OP_MAX:
+#pragma unroll
+      for (int u = 0; u < N; ++u) v[u] = op_vec_t<DT, OP_MAX>(v[u], w[u]);
+      break;
+    case OP_MIN:
+#pragma unroll
+      for (int u = 0; u < N; ++u) v[u] = op_vec_t<DT, OP_MIN>(v[u], w[u]);
+      break;
+    default:
+#pragma unroll
+      for (int u = 0; u < N; ++u) v[u] = add_vec<DT>(v[u], w[u]);
+      break;
+  }
 }
 
 template <int DT>
@@ -254,8 +292,11 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
         uint4 w[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) w[u] = ld_user(&S[i + u * NT]);
+        if (FIN && GEN) op_batch<DT, UNROLL>(v, w, op);
+        else {
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? (GEN ? op_vec<DT>(v[u], w[u], op) : add_vec<DT>(v[u], w[u])) : w[u];
+          for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? add_vec<DT>(v[u], w[u]) : w[u];
+        }
       }
       if (FOUT) {
 #pragma unroll
@@ -278,8 +319,11 @@ __device__ __forceinline__ void move_slice(const void* fin_p, const char* __rest
         uint4 w[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) w[u] = (i + u * NT < nvec) ? ld_user(&S[i + u * NT]) : uint4{0, 0, 0, 0};
+        if (FIN && GEN) op_batch<DT, UNROLL>(v, w, op);
+        else {
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? (GEN ? op_vec<DT>(v[u], w[u], op) : add_vec<DT>(v[u], w[u])) : w[u];
+          for (int u = 0; u < UNROLL; ++u) v[u] = FIN ? add_vec<DT>(v[u], w[u]) : w[u];
+        }
       }
       if (FOUT) {
 #pragma unroll
