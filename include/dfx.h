@@ -82,7 +82,7 @@ typedef struct {
   uint32_t sq_in_device;   /* 0: SQ in pinned host memory (the paper's placement);
                               1: SQ in fine-grained device memory written by the host through the PCIe BAR;
                               2: choose 1 when the device reports a large BAR, else 0 */
-  uint32_t wg_map;         /* 0: workgroup = channel*nranks + rank; 1: workgroup = rank*max_channels + channel */
+  uint32_t wg_map;         /* 0 (default): workgroup = channel*nranks + rank; 1: workgroup = rank*max_channels + channel */
   uint32_t order_policy;   /* 0 = FIFO ordering, 1 = priority ordering (Sec. 4.3) */
   uint32_t trace;          /* 1 = record context-switch latency samples (two clock reads per switch);
                               2 = also time the save / load parts and the wait / data / publish phases;

@@ -310,7 +310,7 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->watchdog_ms = 10000;
   cfg->quit_idle_us = 2000;
   cfg->sq_in_device = 2;
-  cfg->wg_map = 1;
+  cfg->wg_map = 0;
   cfg->order_policy = 0;
   cfg->trace = 0;
   cfg->pool_bytes = 2ull << 30;
