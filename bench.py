@@ -337,13 +337,13 @@ def main():
     ctx = dfx.Context(R, cfg)
     ctx.prepare(0, dfx.ALLREDUCE, n, dfx.F32)
     info = ctx.coll_info(0)
+    ptrs = ctx.make_all([t.data_ptr() for t in send], [t.data_ptr() for t in recv])
 
     def step():
         rc = ctx.start()
         assert rc == dfx.OK, dfx.strerror(rc)
-        for r in range(R):
-            rc = ctx.submit(r, 0, send[r].data_ptr(), recv[r].data_ptr())
-            assert rc == dfx.OK, dfx.strerror(rc)
+        rc = ctx.submit_all(0, ptrs)
+        assert rc == dfx.OK, dfx.strerror(rc)
         rc = ctx.wait_all(30.0)
         assert rc == dfx.OK, dfx.strerror(rc)
         rc = ctx.stop()
