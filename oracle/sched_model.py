@@ -38,6 +38,18 @@ what lets tests explore interleavings.  Host submitters are actors too.
 
 Slices carry real numpy data, so the model's final buffers can be compared with the
 data oracle bit for bit; they also carry (round, step) tags that the receiver checks.
+
+Two variations of Alg. 1 can be switched on, to ask whether they keep its liveness:
+
+  * `lookahead = n > 0`: a successful poll only CLAIMS the slots (the daemon's own view of
+    its connector counters advances) and queues the slice; a separate mover actor per rank
+    moves queued slices in order and only then are the shared counters raised; at most n
+    slices of a rank are claimed and not yet moved.  The wait conditions are evaluated on
+    the claimed view: readable = tail - head - (claimed pops) > 0, writable = tail +
+    (claimed pushes) - head < K.  A collective whose last slice is claimed leaves the task
+    queue at once; its CQE is written when that slice has been moved.
+  * `scan = True`: a pass starts by evaluating the wait conditions of every queue entry and
+    visits only the entries found runnable, each with the minimum threshold.
 """
 from __future__ import annotations
 
@@ -77,6 +89,8 @@ class Policy:
     K: int = 2                    # slots per connector FIFO
     slice_elems: int = 1 << 30    # elements per slice (per round)
     fetch_batch: int = 1          # SQEs fetched in a row when the queue is empty or stuck (0 = all available)
+    lookahead: int = 0            # 0: a slice moves at its successful poll; n: up to n claimed slices per rank, moved by a mover actor
+    scan: bool = False            # a pass visits only the entries whose wait conditions hold at its start
 
 
 @dataclass
@@ -192,6 +206,10 @@ class Daemon:
         self.exit = False
         self.cq: List[Tuple[int, int]] = []
         self.seq_of: Dict[int, int] = {}
+        self.jobs: List[tuple] = []            # claimed slices not yet moved (lookahead)
+        self.ready: Optional[List[int]] = None # queue positions found runnable by the scan of the pass in flight
+        self.rk = 0                            # cursor in self.ready
+        self.removed = 0                       # entries that left the queue during the pass in flight
         self.stats = Stats()
 
     # -- Alg. 1 helpers
@@ -229,7 +247,33 @@ class Daemon:
         self.loaded = None
 
     def idle(self):
-        return not self.taskq and not self.sq
+        return not self.taskq and not self.sq and not self.jobs
+
+    def _conds(self, coll, p):
+        """(readable, writable) of collective `coll`'s primitive p on the claimed view of the connectors."""
+        S = self.S
+        fin = S.fifo[coll][(self.r - 1) % S.R]
+        fout = S.fifo[coll][self.r]
+        pops = sum(1 for j in self.jobs if j[0] == coll and PRIMS[j[3]][0])
+        pushes = sum(1 for j in self.jobs if j[0] == coll and PRIMS[j[3]][1])
+        return fin.tail - fin.head - pops > 0, fout.tail + pushes - fout.head < fout.K
+
+    def _runnable(self, coll):
+        g, p = self.active if self.loaded == coll else self.saved[coll]
+        need_recv, need_send = PRIMS[self.S.progs[coll][self.r][p][0]]
+        rd_ok, wr_ok = self._conds(coll, p)
+        return (not need_recv or rd_ok) and (not need_send or wr_ok)
+
+    def mover_tick(self) -> bool:
+        """Move the oldest claimed slice (lookahead mode): data, shared counters, and the CQE if it was the last."""
+        if not self.jobs:
+            return False
+        coll, g, p, name, sblk, dblk, last = self.jobs.pop(0)
+        S = self.S
+        S.move(coll, self.r, g, p, name, sblk, dblk, S.fifo[coll][(self.r - 1) % S.R], S.fifo[coll][self.r])
+        if last:
+            self.cq.append((coll, self.seq_of[coll]))
+        return True
 
     def tick(self) -> bool:
         """Advance to (and perform) one poll attempt. Returns True if the state changed."""
@@ -252,6 +296,17 @@ class Daemon:
                 if not self.taskq:
                     return changed
                 self.in_pass, self.pos, self.pass_progress = True, 0, False
+                if self.S.policy.scan:
+                    self.ready = [i for i, c in enumerate(self.taskq) if self._runnable(c)]
+                    self.rk, self.removed = 0, 0
+                    if not self.ready:
+                        self.in_pass = False   # nothing can run: the pass is over before it began
+                        if self.loaded is not None:
+                            self._save()
+                            changed = True
+                        return changed
+            if self.S.policy.scan:
+                self.pos = self.ready[self.rk] - self.removed if self.rk < len(self.ready) else len(self.taskq)
             if self.pos >= len(self.taskq):
                 self.in_pass = False
                 if self.loaded is not None:
@@ -264,12 +319,15 @@ class Daemon:
                     self._save()
                 self._load(coll)
                 self.thr = self._thr_init(self.pos)
+                if self.S.policy.scan and self.S.policy.preempt:
+                    self.thr = self.S.policy.spin_min
                 self.spin = 0
                 changed = True
             return self._poll_and_run(coll) or changed
 
     def _poll_and_run(self, coll) -> bool:
         S = self.S
+        P = S.policy
         rounds, prog = S.rounds[coll], S.progs[coll][self.r]
         g, p = self.active
         name, sblk, dblk = prog[p]
@@ -277,7 +335,8 @@ class Daemon:
         fin = S.fifo[coll][(self.r - 1) % S.R]
         fout = S.fifo[coll][self.r]
         self.stats.polls += 1
-        ok = (not need_recv or fin.readable()) and (not need_send or fout.writable())
+        rd_ok, wr_ok = self._conds(coll, p)
+        ok = (not need_recv or rd_ok) and (not need_send or wr_ok)
         if not ok:
             if self.thr >= INF:
                 return False               # spins forever: no state change
@@ -285,27 +344,39 @@ class Daemon:
             if self.spin >= self.thr:
                 self.stats.preemptions += 1
                 self._save()
-                self.pos += 1
+                if P.scan:
+                    self.rk += 1
+                else:
+                    self.pos += 1
             return True
-        # ---- data phase of one slice
-        S.move(coll, self.r, g, p, name, sblk, dblk, fin, fout)
+        if P.lookahead and len(self.jobs) >= P.lookahead:
+            return False                   # every claim slot is taken: wait for the mover (no state change)
+        # ---- the slice is this rank's now: moved at once, or claimed and queued for the mover
+        p2, g2 = p + 1, g
+        if p2 == len(prog):
+            p2, g2 = 0, g + 1
+        last = g2 == rounds
+        if P.lookahead:
+            self.jobs.append((coll, g, p, name, sblk, dblk, last))
+        else:
+            S.move(coll, self.r, g, p, name, sblk, dblk, fin, fout)
         self.stats.prims += 1
         self.dirty = True
         self.pass_progress = True
         self.spin = 0
-        P = S.policy
-        if P.preempt:
+        if P.preempt and not P.scan:
             self.thr = min(P.spin_max, self.thr * P.boost)
-        p += 1
-        if p == len(prog):
-            p, g = 0, g + 1
-        self.active = [g, p]
-        if g == rounds:
+        self.active = [g2, p2]
+        if last:
             # CollectiveSuccess -> SendCQE; entry leaves the queue, position stays
-            self.cq.append((coll, self.seq_of[coll]))
+            if not P.lookahead:
+                self.cq.append((coll, self.seq_of[coll]))
             self.taskq.pop(self.pos)
             self.saved[coll] = [0, 0]
             self.loaded = None
+            if P.scan:
+                self.rk += 1
+                self.removed += 1
         return True
 
 
@@ -387,7 +458,7 @@ class System:
 
     # -- global predicates
     def done(self):
-        return all(not d.taskq and not d.sq for d in self.daemons) and not any(self.pending)
+        return all(not d.taskq and not d.sq and not d.jobs for d in self.daemons) and not any(self.pending)
 
     def total_cqes(self):
         return sum(len(d.cq) for d in self.daemons)
@@ -398,7 +469,9 @@ class System:
         for d in self.daemons:
             ds.append((tuple(d.sq), tuple(d.taskq), d.pos, d.in_pass, d.pass_progress, d.loaded,
                        tuple(d.active) if d.active and d.loaded is not None else None, d.dirty,
-                       tuple(sorted((k, tuple(v)) for k, v in d.saved.items())), d.spin, d.thr, len(d.cq)))
+                       tuple(sorted((k, tuple(v)) for k, v in d.saved.items())), d.spin, d.thr, len(d.cq),
+                       tuple((j[0], j[1], j[2]) for j in d.jobs),
+                       (tuple(d.ready), d.rk, d.removed) if d.in_pass and d.ready is not None else None))
         fs = tuple((f.head, f.tail) for fl in self.fifo for f in fl)
         return (tuple(ds), fs, tuple(tuple(p) for p in self.pending))
 
@@ -428,6 +501,9 @@ class System:
             e.saved = {k: list(v) for k, v in d.saved.items()}
             e.spin, e.thr, e.exit = d.spin, d.thr, d.exit
             e.cq, e.seq_of = list(d.cq), dict(d.seq_of)
+            e.jobs = list(d.jobs)
+            e.ready = list(d.ready) if d.ready is not None else None
+            e.rk, e.removed = d.rk, d.removed
             e.stats = copy.copy(d.stats)
             T.daemons.append(e)
         T.pending = [list(p) for p in self.pending]
@@ -445,6 +521,7 @@ def run_round_robin(S: System, max_ticks: int = 10_000_000) -> int:
         for r in range(S.R):
             S.host_tick(r)
             S.daemons[r].tick()
+            S.daemons[r].mover_tick()
             t += 1
         if t > max_ticks:
             raise TimeoutError("tick watchdog")
@@ -458,9 +535,11 @@ def run_random(S: System, seed: int, max_ticks: int = 10_000_000, host_weight: f
     R = S.R
     while not S.done():
         # draw a batch of choices at once
-        for a in g.integers(0, 2 * R, size=256):
+        for a in g.integers(0, 3 * R, size=256):
             a = int(a)
-            if a >= R:
+            if a >= 2 * R:
+                S.daemons[a - 2 * R].mover_tick()
+            elif a >= R:
                 if g.random() < host_weight * 2:
                     S.host_tick(a - R)
             else:
@@ -480,6 +559,7 @@ def is_deadlocked(S: System) -> bool:
     for r in range(T.R):
         T.host_tick(r)
         T.daemons[r].tick()
+        T.daemons[r].mover_tick()
     return T.key() == k0
 
 
@@ -491,9 +571,11 @@ def explore(S0: System, max_states: int = 2_000_000):
     stack = [S0]
     while stack:
         S = stack.pop()
-        for a in range(2 * S.R):
+        for a in range(3 * S.R):
             T = S.clone()
-            if a >= S.R:
+            if a >= 2 * S.R:
+                moved = T.daemons[a - 2 * S.R].mover_tick()
+            elif a >= S.R:
                 moved = T.host_tick(a - S.R)
             else:
                 moved = T.daemons[a].tick()

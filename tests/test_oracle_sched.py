@@ -175,3 +175,84 @@ def test_batch_fetch_keeps_liveness_and_values(batch):
     sm.run_random(S, 5, max_ticks=5_000_000)
     assert S.total_cqes() == 8 * 3
     _check_data(S, w)
+
+
+# ---------------------------------------------------------------- claim-ahead and scan variations
+VARIANTS = [dict(lookahead=1), dict(lookahead=2), dict(scan=True), dict(lookahead=2, scan=True)]
+
+
+@pytest.mark.parametrize("var", [dict(lookahead=2), dict(scan=True), dict(lookahead=2, scan=True)])
+@pytest.mark.parametrize("orders", [((0, 1), (1, 0)), ((0, 1), (0, 1))])
+def test_variations_exhaustive_interleavings_tiny(orders, var):
+    """Claiming slices ahead of their movement (a mover actor raises the shared counters later) and
+    visiting only runnable entries keep Alg. 1's liveness: in the circular-wait setting no reachable
+    state -- over all interleavings of daemons, movers and host submissions -- is a deadlock, and every
+    one of them finishes with all four CQEs."""
+    # (without the scan the state space is large: one slice per collective there, two with it)
+    w = wi.config1(*orders, n=8)
+    pol = sm.Policy(spin_init=2, spin_min=1, spin_max=2, boost=2, K=2, slice_elems=2 if var.get("scan") else 4, **var)
+    S0 = _system(w, pol, data=False)
+    seen = sm.explore(S0, max_states=600_000)
+    assert len(seen) > 20
+    keys = list(seen)
+    step = 1 if len(keys) < 1000 else 97
+    for k in keys[::step]:
+        T = seen[k].clone()
+        assert not sm.is_deadlocked(T)
+        sm.run_round_robin(T, max_ticks=50_000)
+        assert T.total_cqes() == 4
+
+
+@pytest.mark.parametrize("var", VARIANTS)
+@pytest.mark.parametrize("seed", range(3))
+def test_variations_are_transparent_to_the_values(var, seed):
+    """Mixed kinds on three ranks, random issue orders, random interleavings of daemons, movers and
+    hosts: with slices claimed ahead / runnable-only passes the final buffers equal the data oracle's."""
+    g = np.random.default_rng(seed)
+    R = 3
+    colls = [wi.CollSpec(0, wi.AR, wi.F32, 50), wi.CollSpec(1, wi.AG, wi.F16, 12),
+             wi.CollSpec(2, wi.RS, wi.I32, 16), wi.CollSpec(3, wi.BC, wi.BF16, 40, root=2),
+             wi.CollSpec(4, wi.AR, wi.BF16, 33)]
+    orders = [list(map(int, g.permutation(len(colls)))) for _ in range(R)]
+    w = wi.Workload("var", R, colls, orders, seed=seed, cfg=91)
+    S = _system(w, sm.Policy(spin_init=3, spin_max=6, boost=2, K=2, slice_elems=8, **var))
+    sm.run_random(S, seed + 100, max_ticks=2_000_000)
+    assert S.total_cqes() == R * len(colls)
+    _check_data(S, w)
+
+
+def test_claims_never_overrun_a_connector():
+    """With two claims allowed and two-slot connectors the claimed view keeps every FIFO within its
+    capacity at every tick, and a collective's CQE never precedes the movement of its last slice."""
+    w = wi.config1((0, 1), (1, 0), n=64)
+    S = _system(w, sm.Policy(spin_init=2, spin_max=4, boost=2, K=2, slice_elems=4, lookahead=2))
+    g = np.random.default_rng(3)
+    ticks = 0
+    while not S.done():
+        a = int(g.integers(0, 6))
+        if a >= 4:
+            S.daemons[a - 4].mover_tick()
+        elif a >= 2:
+            S.host_tick(a - 2)
+        else:
+            S.daemons[a].tick()
+        for fl in S.fifo:
+            for f in fl:
+                assert 0 <= f.tail - f.head <= f.K
+        for d in S.daemons:
+            assert len(d.jobs) <= 2
+            done_colls = {c for c, _ in d.cq}
+            assert not any(j[0] in done_colls for j in d.jobs)
+        ticks += 1
+        assert ticks < 1_000_000
+    assert S.total_cqes() == 4
+    _check_data(S, w)
+
+
+def test_negative_control_still_deadlocks_with_claims():
+    """Claim-ahead does not hide the need for preemption: opposite orders without it still deadlock."""
+    w = wi.config1((0, 1), (1, 0))
+    S = _system(w, sm.Policy(preempt=False, K=2, slice_elems=256, taskq_cap=1, lookahead=2), data=False)
+    with pytest.raises(TimeoutError):
+        sm.run_round_robin(S, max_ticks=20_000)
+    assert sm.is_deadlocked(S)
