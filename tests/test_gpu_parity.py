@@ -244,3 +244,13 @@ def test_random_mix_single_queue_forced_preemption():
     smallest thresholds: every late flag preempts."""
     _run(_mixed_workload(7, n_colls=24), mode="threads", timeout_s=60.0, max_channels=1, chan_spread=0,
          scan_min=0, spin_init=1, spin_min=1, spin_max=1, spin_boost=1)
+
+
+def test_fenced_connector_mode_matches_too(monkeypatch):
+    """The comparison mode (ordinary cached connector accesses + agent-scope release / acquire fences,
+    switched on by the environment when a context is created) gives the same bits."""
+    monkeypatch.setenv("DFX_FIFO_FENCED", "1")
+    _run(_one(wi.AR, wi.F32, 1 << 20, 8, seed=41))
+    _run(_one(wi.AR, wi.BF16, 100003, 8, seed=42))
+    _run(_one(wi.RS, wi.F16, 50001, 5, seed=43), max_channels=8)
+    _run(wi.config3(n_buckets=6, bucket_bytes=1 << 20, seed=44))
