@@ -195,6 +195,14 @@ int dfx_submit_many(dfx_ctx* ctx, int rank, int n, const int* coll_ids, const vo
                     void* const* recvbufs, uint64_t timeout_ns);
 
 /*
+ * dfx_submit_many with a pause before every entry: delays_ns[i] nanoseconds of busy waiting precede
+ * entry i (host array of n values, or NULL for none).  For workloads whose submissions are staggered
+ * in time, driven from native threads rather than from an interpreter loop.
+ */
+int dfx_submit_many_paced(dfx_ctx* ctx, int rank, int n, const int* coll_ids, const void* const* sendbufs,
+                          void* const* recvbufs, const uint64_t* delays_ns, uint64_t timeout_ns);
+
+/*
  * Take up to max completions of one vrank (the poller's job, Sec. 3.1).  out: host.
  * Returns the number of CQEs written to out (>= 0) or a negative status.  Restarts a daemon
  * that quit voluntarily while work is outstanding.

@@ -71,6 +71,7 @@ def _load() -> C.CDLL:
         "dfx_submit": ([vp, i, i, vp, vp], i),
         "dfx_submit_many": ([vp, i, i, C.POINTER(C.c_int), C.POINTER(vp), C.POINTER(vp), u64], i),
         "dfx_submit_all": ([vp, i, C.POINTER(vp), C.POINTER(vp), u64], i),
+        "dfx_submit_many_paced": ([vp, i, i, C.POINTER(C.c_int), C.POINTER(vp), C.POINTER(vp), C.POINTER(u64), u64], i),
         "dfx_poll": ([vp, i, C.POINTER(Cqe), i], i),
         "dfx_wait": ([vp, i, i, u64], i),
         "dfx_wait_all": ([vp, u64], i),
@@ -137,15 +138,17 @@ class Context:
         return _lib.dfx_submit_all(self._h, coll_id, ptrs[0], ptrs[1], int(timeout_s * 1e9))
 
     @staticmethod
-    def make_burst(coll_ids, sendbufs, recvbufs):
-        """Marshal a burst once (three C arrays), so that submitting it costs no Python work."""
+    def make_burst(coll_ids, sendbufs, recvbufs, delays_us=None):
+        """Marshal a burst once (C arrays), so that submitting it costs no Python work; delays_us[i] is a
+        pause before entry i."""
         n = len(coll_ids)
-        return n, (C.c_int * n)(*coll_ids), (C.c_void_p * n)(*sendbufs), (C.c_void_p * n)(*recvbufs)
+        d = (C.c_uint64 * n)(*[int(x * 1000.0) for x in delays_us]) if delays_us is not None else None
+        return n, (C.c_int * n)(*coll_ids), (C.c_void_p * n)(*sendbufs), (C.c_void_p * n)(*recvbufs), d
 
     def submit_burst(self, rank: int, burst, timeout_s: float = 30.0) -> int:
         """Burst submission in C (the GIL is released for the whole call). Returns the count submitted."""
-        n, ids, sb, rb = burst
-        return _lib.dfx_submit_many(self._h, rank, n, ids, sb, rb, int(timeout_s * 1e9))
+        n, ids, sb, rb, d = burst
+        return _lib.dfx_submit_many_paced(self._h, rank, n, ids, sb, rb, d, int(timeout_s * 1e9))
 
     def submit_many(self, rank: int, coll_ids, sendbufs, recvbufs, timeout_s: float = 30.0) -> int:
         return self.submit_burst(rank, self.make_burst(coll_ids, sendbufs, recvbufs), timeout_s)

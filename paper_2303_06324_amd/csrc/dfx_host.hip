@@ -560,19 +560,27 @@ int dfx_submit_all(dfx_ctx* c, int coll_id, const void* const* sendbufs, void* c
   return DFX_OK;
 }
 
-int dfx_submit_many(dfx_ctx* c, int rank, int n, const int* coll_ids, const void* const* sendbufs,
-                    void* const* recvbufs, uint64_t timeout_ns) {
+int dfx_submit_many_paced(dfx_ctx* c, int rank, int n, const int* coll_ids, const void* const* sendbufs,
+                          void* const* recvbufs, const uint64_t* delays_ns, uint64_t timeout_ns) {
   if (!c || rank < 0 || rank >= c->R || n < 0 || (n > 0 && (!coll_ids || !sendbufs || !recvbufs))) return DFX_ERR_INVALID_ARG;
   const uint64_t t0 = now_ns();
   uint32_t spins = 0;
   int i = 0, since_check = 0;
+  bool paused = false;
   c->user_stopped.store(false);
   // The daemon is looked after (launch state behind one lock, an event query) after the first
-  // entry, then every 32 entries, whenever the SQ is full, and after the last one -- not per entry.
+  // entry, then every 32 entries, after every pause, whenever the SQ is full, and after the last
+  // entry -- not per entry.
   while (i < n) {
+    if (delays_ns && delays_ns[i] && !paused) {
+      const uint64_t until = now_ns() + delays_ns[i];
+      while (now_ns() < until) _mm_pause();
+      paused = true;
+      since_check = 0;
+    }
     const int rc = submit_one(c, rank, coll_ids[i], sendbufs[i], recvbufs[i]);
     if (rc == DFX_OK) {
-      ++i; spins = 0;
+      ++i; spins = 0; paused = false;
       if (since_check++ % 32 == 0 || i == n) {
         const int rr = ensure_running(c);
         if (rr != DFX_OK) return rr;
@@ -586,6 +594,11 @@ int dfx_submit_many(dfx_ctx* c, int rank, int n, const int* coll_ids, const void
     backoff(spins);
   }
   return i;
+}
+
+int dfx_submit_many(dfx_ctx* c, int rank, int n, const int* coll_ids, const void* const* sendbufs,
+                    void* const* recvbufs, uint64_t timeout_ns) {
+  return dfx_submit_many_paced(c, rank, n, coll_ids, sendbufs, recvbufs, nullptr, timeout_ns);
 }
 
 int dfx_poll(dfx_ctx* c, int rank, dfx_cqe* out, int max) {

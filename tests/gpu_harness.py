@@ -57,7 +57,8 @@ class DeviceWorkload:
         if colls is None:
             self.bursts = [dfx.Context.make_burst([w.colls[ci].coll_id for ci in w.orders[r]],
                                                   [self.send[ci][r].data_ptr() for ci in w.orders[r]],
-                                                  [self.recv[ci][r].data_ptr() for ci in w.orders[r]])
+                                                  [self.recv[ci][r].data_ptr() for ci in w.orders[r]],
+                                                  w.delays_us[r] if w.delays_us else None)
                            for r in range(w.R)]
 
     def reset_recv(self):
@@ -109,29 +110,23 @@ def submit_threads(ctx: "dfx.Context", dw: DeviceWorkload, orders=None, delays_u
     """One host thread per rank, each with its own order and (optional) seeded delays."""
     w = dw.w
     orders = w.orders if orders is None else orders
-    deadline = time.monotonic() + timeout_s
     errs = []
 
     def work(r):
         try:
-            if not delays_us:      # one native burst per rank: the host threads really run concurrently
-                if orders is w.orders and dw.bursts is not None:
-                    burst = dw.bursts[r]
-                else:
-                    burst = ctx.make_burst([w.colls[ci].coll_id for ci in orders[r]],
-                                           [dw.send[ci][r].data_ptr() for ci in orders[r]],
-                                           [dw.recv[ci][r].data_ptr() for ci in orders[r]])
-                ids = burst[1]
-                n = ctx.submit_burst(r, burst, timeout_s)
-                if n != len(ids):
-                    raise dfx.DfxError(n if n < 0 else dfx.ERR_TIMEOUT, f"dfx_submit_many(rank={r}) -> {n}")
-                return
-            for j, ci in enumerate(orders[r]):
-                if delays_us:
-                    t_end = time.perf_counter() + delays_us[r][j] * 1e-6
-                    while time.perf_counter() < t_end:
-                        pass
-                _submit_retry(ctx, r, w.colls[ci].coll_id, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr(), deadline)
+            # one native burst per rank (pauses included): the host threads really run concurrently
+            if orders is w.orders and dw.bursts is not None and (delays_us is None or delays_us is w.delays_us):
+                burst = dw.bursts[r]
+                if delays_us is None and burst[4] is not None:
+                    burst = burst[:4] + (None,)
+            else:
+                burst = ctx.make_burst([w.colls[ci].coll_id for ci in orders[r]],
+                                       [dw.send[ci][r].data_ptr() for ci in orders[r]],
+                                       [dw.recv[ci][r].data_ptr() for ci in orders[r]],
+                                       delays_us[r] if delays_us else None)
+            n = ctx.submit_burst(r, burst, timeout_s)
+            if n != burst[0]:
+                raise dfx.DfxError(n if n < 0 else dfx.ERR_TIMEOUT, f"dfx_submit_many_paced(rank={r}) -> {n}")
         except Exception as e:   # noqa: BLE001
             errs.append(e)
 
