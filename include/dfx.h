@@ -166,9 +166,10 @@ int dfx_prepare(dfx_ctx* ctx, int coll_id, dfx_kind kind, size_t count, dfx_dtyp
  * at once; starts the daemon if it is not running (Sec. 4.4 event-driven start).
  * sendbuf, recvbuf: device, caller-owned, 16-byte aligned, valid and unmodified (sendbuf) /
  * unread (recvbuf) until this rank's CQE for the invocation; they may differ between
- * invocations of one coll_id (Sec. 4.2) and must not overlap each other.
+ * invocations of one coll_id (Sec. 4.2) and must not overlap each other, except that an all-reduce may
+ * run in place (recvbuf == sendbuf).
  * Errors: INVALID_ARG, NOT_PREPARED, BUSY, SQ_FULL (retry), ABORTED, HIP.
- * There is no poller thread: completions wait in the CQ (cq_slots entries per vrank) until
+ * Unless dfx_set_callback has started the poller thread, completions wait in the CQ (cq_slots entries per vrank) until
  * dfx_poll / dfx_wait / dfx_wait_all take them, or until a dfx_submit on that vrank finds the SQ full
  * and moves them to the host-side list itself.  A vrank whose CQ is full stops making progress.
  */

@@ -254,3 +254,27 @@ def test_fenced_connector_mode_matches_too(monkeypatch):
     _run(_one(wi.AR, wi.BF16, 100003, 8, seed=42))
     _run(_one(wi.RS, wi.F16, 50001, 5, seed=43), max_channels=8)
     _run(wi.config3(n_buckets=6, bucket_bytes=1 << 20, seed=44))
+
+
+@pytest.mark.parametrize("dtype,count", [(wi.F32, 1 << 20), (wi.BF16, 300007), (wi.I32, 4099)])
+def test_in_place_allreduce(dtype, count):
+    """recvbuf == sendbuf: the ring reads every location of the send buffer (reduce phase) before the
+    gather phase overwrites it, slice by slice, so an all-reduce may run in place."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    import torch
+    w = _one(wi.AR, dtype, count, 8, seed=count)
+    sends = wi.all_sends(w, 0)
+    want = rd.all_reduce_fold(sends, dtype)
+    bufs = [torch.from_numpy(s.view(np.uint8).copy()).cuda() for s in sends]
+    torch.cuda.synchronize()
+    ctx = dfx.Context(8, gh.make_config())
+    try:
+        ctx.prepare(0, dfx.ALLREDUCE, count, dtype)
+        ptrs = ctx.make_all([b.data_ptr() for b in bufs], [b.data_ptr() for b in bufs])
+        assert ctx.submit_all(0, ptrs) == dfx.OK
+        assert ctx.wait_all(20.0) == dfx.OK
+    finally:
+        ctx.finalize()
+    for b in bufs:
+        assert np.array_equal(b.cpu().numpy(), want.view(np.uint8))
