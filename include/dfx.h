@@ -104,6 +104,12 @@ typedef struct {
                               position in one 64-bit atomic write, validated by the poller against its head) */
   uint32_t sq_eager;       /* 1 (default): a workgroup probes the SQ before every pass over its queue; 0: only when
                               its queue is empty or a whole pass made no progress (FIFO ordering as Sec. 4.3 words it) */
+  uint32_t window;         /* slices of a collective are taken in windows of this many (1, 2 or 4; halved until it
+                              is below nslots, which a ring of fused recv+send primitives needs to stay live):
+                              primitive p of every slice of the window, then primitive p+1 ..., so that the
+                              hop latency of one slice hides behind the data of another.  1 = the whole
+                              primitive sequence slice after slice */
+  uint32_t reserved0;
 } dfx_config;
 
 /* Aggregated over the workgroups of one vrank since dfx_init. */

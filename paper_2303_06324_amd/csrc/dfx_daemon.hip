@@ -1109,13 +1109,22 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         const uint32_t this_p = p;
         if (q.send) ++sent;
         if (q.recv) ++recvd;
-        // next primitive: the chunk index steps down the ring; a new round starts over
-        cidx = (cidx == 0) ? a.R - 1 : cidx - 1;
-        if (++p == S.nprim) {
-          p = 0; ++g;
-          cidx = (kind == KIND_AG) ? rank : ((kind == KIND_BC || kind == KIND_RD || a.R == 1) ? 0u : cidx0_reduce);
+        // Next primitive.  Slices are taken in windows of W: primitive p of every slice of the
+        // window, then primitive p+1 of every slice, ...  The neighbour does the same, so when
+        // this rank comes to (slice, p+1) the neighbour finished (slice, p) one job ago instead of
+        // at this very moment, and the hop latency hides behind the other slice's data.  The
+        // chunk index steps down the ring with p; a new window starts the sequence over.
+        const uint32_t W = a.window;
+        if (((g + 1) & (W - 1)) != 0 && g + 1 < S.rounds) ++g;
+        else {
+          g &= ~(W - 1);
+          cidx = (cidx == 0) ? a.R - 1 : cidx - 1;
+          if (++p == S.nprim) {
+            p = 0; g += W;
+            cidx = (kind == KIND_AG) ? rank : ((kind == KIND_BC || kind == KIND_RD || a.R == 1) ? 0u : cidx0_reduce);
+          }
+          if (kind == KIND_BC || kind == KIND_RD) cidx = 0;
         }
-        if (kind == KIND_BC || kind == KIND_RD) cidx = 0;
         progressed = true;
         pass_progress = true;
         acted = true;
@@ -1124,7 +1133,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           thr *= a.spin_boost;
           if (thr > a.spin_max) thr = a.spin_max;
         }
-        const bool last = (g == S.rounds);
+        const bool last = (g >= S.rounds);
 
         // ---- post the slice (an empty one is only a handshake: the movers just raise the counters)
         if (lane == 0) {

@@ -169,7 +169,7 @@ int launch_locked(dfx_ctx* c) {
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   a.nwg = c->nwg;
-  a.cq_ctl = c->cq_ctl; a.cq_mode = c->cfg.cq_mode; a.sq_eager = c->cfg.sq_eager;
+  a.cq_ctl = c->cq_ctl; a.cq_mode = c->cfg.cq_mode; a.sq_eager = c->cfg.sq_eager; a.window = c->cfg.window;
   a.scan_min = c->cfg.scan_min;
   a.chan_spread = c->cfg.chan_spread;
   a.epoch = (uint32_t)(c->launches + 1);
@@ -306,6 +306,8 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->chan_spread = 1;
   cfg->cq_mode = 0;
   cfg->sq_eager = 1;
+  cfg->window = 2;
+  cfg->reserved0 = 0;
   cfg->preempt = 1;
   cfg->watchdog_ms = 10000;
   cfg->quit_idle_us = 2000;
@@ -331,6 +333,10 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   if (cfg.max_colls < 1 || cfg.max_colls > DFX_MAX_COLLS) return DFX_ERR_INVALID_ARG;
   if (!is_pow2(cfg.sq_depth) || cfg.sq_depth < 2) return DFX_ERR_INVALID_ARG;
   if (cfg.cq_slots < 1 || cfg.cq_mode > 2) return DFX_ERR_INVALID_ARG;
+  if (cfg.window != 1 && cfg.window != 2 && cfg.window != 4) return DFX_ERR_INVALID_ARG;
+  // A ring of fused recv+send primitives that has sent `window` slices ahead on every edge needs one
+  // more free slot to take its next step: with window >= nslots every connector fills and nobody can move.
+  while (cfg.window >= cfg.nslots) cfg.window /= 2;
   if (!is_pow2(cfg.nslots) || cfg.nslots < 2 || cfg.nslots > 64) return DFX_ERR_INVALID_ARG;
   if (cfg.slot_bytes < 16 || (cfg.slot_bytes & 15u)) return DFX_ERR_INVALID_ARG;
   if (cfg.chan_min_bytes < 16) return DFX_ERR_INVALID_ARG;

@@ -47,7 +47,7 @@ static_assert(sizeof(DfxStatic) == 96, "DfxStatic must be 96 bytes");
 // Dynamic context (Sec. 4.2: current chunk id, aborted primitive id) plus the monotone
 // connector counters of this (rank, channel).  32 bytes = two 16-byte vectors.
 struct alignas(16) DfxDyn {
-  uint32_t round;        // slice index ("current data chunk")
+  uint32_t round;        // slice index ("current data chunk"); slices are taken in windows, see the daemon
   uint32_t prim;         // next primitive of the sequence ("aborted primitive")
   uint64_t sent;         // slices ever pushed into the send connector
   uint64_t recvd;        // slices ever taken from the recv connector
@@ -125,7 +125,7 @@ struct DfxDaemonArgs {
   uint32_t epoch;           // number of this launch (exit SQEs name the launch they end)
   uint32_t R, cmax, max_colls, sq_depth, sq_shift, cq_slots;
   uint32_t spin_init, spin_min, spin_max, spin_boost, preempt;
-  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent, chan_spread, cq_mode, sq_eager;
+  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent, chan_spread, cq_mode, sq_eager, window;
   uint64_t watchdog_ticks;  // wall-clock ticks; 0 = off
   uint64_t quit_ticks;      // wall-clock ticks; 0 = off
 };
