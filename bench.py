@@ -340,9 +340,7 @@ def main():
     ptrs = ctx.make_all([t.data_ptr() for t in send], [t.data_ptr() for t in recv])
 
     def step():
-        rc = ctx.start()
-        assert rc == dfx.OK, dfx.strerror(rc)
-        rc = ctx.submit_all(0, ptrs)
+        rc = ctx.submit_all(0, ptrs)          # the first SQE starts the daemon (Sec. 4.4)
         assert rc == dfx.OK, dfx.strerror(rc)
         rc = ctx.wait_all(30.0)
         assert rc == dfx.OK, dfx.strerror(rc)
