@@ -654,14 +654,16 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
     auto complete = [&](uint32_t c_coll, uint32_t c_seq, uint32_t c_nchan) {
       fence_release_system();   // results in the recv buffer are visible to host and later kernels
       uint32_t* dc = &a.done_cnt[(size_t)rank * a.max_colls + c_coll];
-      const uint32_t old = __hip_atomic_fetch_add(dc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
+      // (a collective on one channel has nobody to count with: no round trip for the counter)
+      const uint32_t old = c_nchan > 1 ? __hip_atomic_fetch_add(dc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT) : 0u;
       if (old + 1 == c_nchan) {
-        __hip_atomic_store(dc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
+        if (c_nchan > 1) __hip_atomic_store(dc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
         const u64 tq0 = wall_clock64();
         if (a.cq_mode == 0) {
           // optimized CQ (Sec. 5): one CAS of the id into a writable slot, no ring semantics
           const u64 v = (1ull << 63) | ((u64)(c_seq & 0x7fffffffu) << 32) | c_coll;
-          const uint32_t t = __hip_atomic_fetch_add(&a.cq_ticket[rank], 1u, __ATOMIC_RELAXED, SCOPE_AGENT);
+          // where to try first: spread by id and invocation, no shared ticket to fetch (the CAS decides)
+          const uint32_t t = c_coll * 7u + c_seq;
           uint32_t k = 0;
           for (;;) {
             u64 expected = 0;
@@ -919,14 +921,15 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             }
             burst += n;
             idle = 0;
-            continue;               // probe the SQ again before walking the queue
+            if (n == room) continue;   // the run may go on: probe the SQ again before walking the queue
+            // (fewer entries than lanes looked: the SQ is empty behind them, go on to the pass)
           }
           burst = 0;
           if (qlen == 0) {
-            // idle: back off the SQ probe (it may cross PCIe)
+            // idle: back off the SQ probe (an SQ in host memory is probed across PCIe: back off further)
             ++idle;
-            if (idle < 16) __builtin_amdgcn_s_sleep(8);
-            else if (idle < 64) __builtin_amdgcn_s_sleep(32);
+            if (idle < 64) __builtin_amdgcn_s_sleep(8);
+            else if (a.sq_local || idle < 4096) __builtin_amdgcn_s_sleep(32);
             else __builtin_amdgcn_s_sleep(127);
             continue;
           }

@@ -74,7 +74,6 @@ struct dfx_ctx {
   // device memory
   uint32_t* sq_readers = nullptr;
   uint32_t* done_cnt = nullptr;
-  uint32_t* cq_ticket = nullptr;
   uint32_t* dev_ctl = nullptr;
   uint8_t* pool = nullptr;
   DfxCtxEntry* ctxbuf = nullptr;
@@ -123,7 +122,7 @@ void free_all(dfx_ctx* c) {
   if (c->qmem_sq) { if (c->sq_device) (void)hipFree(c->qmem_sq); else (void)hipHostFree(c->qmem_sq); }
   if (c->qmem_cq) (void)hipHostFree(c->qmem_cq);
   if (c->pinned_tmp) (void)hipHostFree(c->pinned_tmp);
-  void* dev[] = {c->sq_readers, c->done_cnt, c->cq_ticket, c->dev_ctl, c->pool, c->ctxbuf, c->wgstate, c->taskq_store, c->trace};
+  void* dev[] = {c->sq_readers, c->done_cnt, c->dev_ctl, c->pool, c->ctxbuf, c->wgstate, c->taskq_store, c->trace};
   for (void* p : dev) if (p) (void)hipFree(p);
   if (c->ev_start) (void)hipEventDestroy(c->ev_start);
   if (c->ev_stop) (void)hipEventDestroy(c->ev_stop);
@@ -157,7 +156,7 @@ int launch_locked(dfx_ctx* c) {
   DfxDaemonArgs a;
   memset(&a, 0, sizeof(a));
   a.sq = c->sq; a.cq = c->cq; a.host_ctl = c->host_ctl;
-  a.sq_readers = c->sq_readers; a.done_cnt = c->done_cnt; a.cq_ticket = c->cq_ticket; a.dev_ctl = c->dev_ctl;
+  a.sq_readers = c->sq_readers; a.done_cnt = c->done_cnt; a.dev_ctl = c->dev_ctl;
   a.pool = c->pool; a.ctxbuf = c->ctxbuf; a.wgstate = c->wgstate; a.taskq_store = c->taskq_store; a.trace = c->trace;
   a.R = (uint32_t)c->R; a.cmax = c->cfg.max_channels; a.max_colls = c->cfg.max_colls;
   a.sq_depth = c->cfg.sq_depth; a.sq_shift = c->sq_shift; a.cq_slots = c->cfg.cq_slots;
@@ -169,7 +168,7 @@ int launch_locked(dfx_ctx* c) {
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   a.nwg = c->nwg;
-  a.cq_ctl = c->cq_ctl; a.cq_mode = c->cfg.cq_mode; a.sq_eager = c->cfg.sq_eager; a.window = c->cfg.window;
+  a.cq_ctl = c->cq_ctl; a.cq_mode = c->cfg.cq_mode; a.sq_eager = c->cfg.sq_eager; a.window = c->cfg.window; a.sq_local = c->sq_device ? 1u : 0u;
   a.scan_min = c->cfg.scan_min;
   a.chan_spread = c->cfg.chan_spread;
   a.epoch = (uint32_t)(c->launches + 1);
@@ -406,7 +405,6 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   };
   INITCHK(dalloc((void**)&c->sq_readers, R * cfg.sq_depth * sizeof(uint32_t)));
   INITCHK(dalloc((void**)&c->done_cnt, R * cfg.max_colls * sizeof(uint32_t)));
-  INITCHK(dalloc((void**)&c->cq_ticket, R * sizeof(uint32_t) + 64));
   INITCHK(dalloc((void**)&c->dev_ctl, DC_N * sizeof(uint32_t)));
   INITCHK(dalloc((void**)&c->pool, cfg.pool_bytes));
   INITCHK(dalloc((void**)&c->ctxbuf, (size_t)c->nwg * cfg.max_colls * sizeof(DfxCtxEntry)));

@@ -113,7 +113,6 @@ struct DfxDaemonArgs {
   uint32_t* host_ctl;       // [HC_N]          host-visible
   uint32_t* sq_readers;     // [R][sq_depth]   device
   uint32_t* done_cnt;       // [R][max_colls]  device
-  uint32_t* cq_ticket;      // [R]             device
   uint32_t* dev_ctl;        // [DC_N]          device
   uint8_t* pool;            // connector pool  device
   DfxCtxEntry* ctxbuf;      // [nwg][max_colls] device
@@ -125,7 +124,7 @@ struct DfxDaemonArgs {
   uint32_t epoch;           // number of this launch (exit SQEs name the launch they end)
   uint32_t R, cmax, max_colls, sq_depth, sq_shift, cq_slots;
   uint32_t spin_init, spin_min, spin_max, spin_boost, preempt;
-  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent, chan_spread, cq_mode, sq_eager, window;
+  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent, chan_spread, cq_mode, sq_eager, window, sq_local;
   uint64_t watchdog_ticks;  // wall-clock ticks; 0 = off
   uint64_t quit_ticks;      // wall-clock ticks; 0 = off
 };
