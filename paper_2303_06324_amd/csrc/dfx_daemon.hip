@@ -55,7 +55,7 @@ __device__ __forceinline__ uint32_t ld_sys32(const uint32_t* p) { return __hip_a
 
 // Release fences end with an explicit wait: the L2 write-back they issue must have completed
 // before the flag store that follows.  The compiler's own wait is dropped when it believes no
-// memory operation is pending (our stores were drained before the barrier), and the write-back
+// memory operation is pending (the wave's own stores were drained earlier), and the write-back
 // itself is not on its scoreboard.
 __device__ __forceinline__ void fence_acquire_agent() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
 __device__ __forceinline__ void fence_release_agent() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); __builtin_amdgcn_s_waitcnt(0); }
