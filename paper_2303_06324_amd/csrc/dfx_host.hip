@@ -556,12 +556,9 @@ int dfx_submit_all(dfx_ctx* c, int coll_id, const void* const* sendbufs, void* c
       if (now_ns() - t0 > timeout_ns) return DFX_ERR_SQ_FULL;
       backoff(spins);
     }
-    if (r == 0 || r == c->R - 1) {   // start the daemon with the first entry, look again after the last
-      const int rr = ensure_running(c);
-      if (rr != DFX_OK) return rr;
-    }
   }
-  return DFX_OK;
+  // every vrank's entry is in place: now see to the daemon (a launch finds them all at once)
+  return ensure_running(c);
 }
 
 int dfx_submit_many_paced(dfx_ctx* c, int rank, int n, const int* coll_ids, const void* const* sendbufs,
