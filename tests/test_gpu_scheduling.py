@@ -365,3 +365,91 @@ def test_submit_all_is_one_invocation_on_every_vrank():
         assert [s["cqe_posted"] for s in (ctx.stats(r) for r in range(8))] == [3] * 8
     finally:
         assert ctx.finalize() == dfx.OK
+
+
+def test_paced_burst_honours_its_delays():
+    """dfx_submit_many_paced waits delays_ns[i] before entry i (the issue-time jitter of the
+    disordered-invocation experiments, Sec. 6.1); data must still equal the oracle's."""
+    import threading
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    R, n = 4, 6
+    colls = [wi.CollSpec(i, wi.AR, wi.I32, 3000 + 17 * i) for i in range(n)]
+    w = wi.Workload("paced", R, colls, [list(range(n))] * R, seed=77, cfg=73)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(R, gh.make_config())
+    try:
+        gh.prepare_all(ctx, w)
+        delay_us = 20000.0
+        bursts = []
+        for r in range(R):
+            order = list(range(n)) if r % 2 == 0 else list(reversed(range(n)))
+            bursts.append(ctx.make_burst(order, [dw.send[ci][r].data_ptr() for ci in order],
+                                         [dw.recv[ci][r].data_ptr() for ci in order],
+                                         [delay_us if r == 0 else 0.0] * n))
+        out = [None] * R
+        took = [0.0] * R
+
+        def work(r):
+            t0 = time.monotonic()
+            out[r] = ctx.submit_burst(r, bursts[r])
+            took[r] = time.monotonic() - t0
+
+        th = [threading.Thread(target=work, args=(r,)) for r in range(R)]
+        for t in th:
+            t.start()
+        for t in th:
+            t.join()
+        assert out == [n] * R
+        assert took[0] >= n * delay_us * 1e-6            # every pause was taken
+        assert max(took[1:]) < n * delay_us * 1e-6       # and only where one was asked for
+        assert ctx.wait_all(20.0) == dfx.OK
+        for ci in range(n):
+            _expect(dw, w, ci)
+    finally:
+        assert ctx.finalize() == dfx.OK
+
+
+def test_host_error_paths_leave_the_context_usable():
+    """Argument errors are reported by the host side before anything reaches the SQ; a context that
+    has reported them still runs a collective correctly afterwards."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.Workload("errs", 4, [wi.CollSpec(0, wi.AR, wi.F32, 5001), wi.CollSpec(1, wi.BC, wi.I32, 333, root=2)],
+                    [[0, 1]] * 4, seed=9, cfg=74)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(4, gh.make_config(max_colls=8))
+    try:
+        s, d = dw.send[0][0].data_ptr(), dw.recv[0][0].data_ptr()
+        assert ctx.submit(0, 0, s, d) == dfx.ERR_NOT_PREPARED
+        gh.prepare_all(ctx, w)
+        for bad in [dict(coll_id=8), dict(coll_id=-1), dict(kind=5), dict(dtype=4), dict(op=4),
+                    dict(kind=dfx.BROADCAST, root=4), dict(kind=dfx.REDUCE, root=-1),
+                    dict(priority=40000), dict(count=(1 << 40) + 1), dict(coll_id=0)]:
+            a = dict(coll_id=2, kind=dfx.ALLREDUCE, count=64, dtype=dfx.F32, op=dfx.SUM, root=0, priority=0)
+            a.update(bad)
+            with pytest.raises(dfx.DfxError) as ei:
+                ctx.prepare(**a)
+            assert ei.value.status == dfx.ERR_INVALID_ARG, bad
+        assert ctx.submit(4, 0, s, d) == dfx.ERR_INVALID_ARG
+        assert ctx.submit(-1, 0, s, d) == dfx.ERR_INVALID_ARG
+        assert ctx.submit(0, 8, s, d) == dfx.ERR_INVALID_ARG
+        assert ctx.submit(0, 2, s, d) == dfx.ERR_NOT_PREPARED
+        assert ctx.submit(0, 0, 0, d) == dfx.ERR_INVALID_ARG
+        assert ctx.submit(0, 0, s, 0) == dfx.ERR_INVALID_ARG
+        assert ctx.submit(0, 0, s + 4, d) == dfx.ERR_INVALID_ARG          # user buffers are 16-byte aligned
+        assert ctx.submit(0, 0, s, d + 8) == dfx.ERR_INVALID_ARG
+        assert ctx.wait(0, 9) == dfx.ERR_INVALID_ARG
+        assert ctx.wait(7, 0) == dfx.ERR_INVALID_ARG
+        with pytest.raises(dfx.DfxError):
+            ctx.poll(5)
+        with pytest.raises(dfx.DfxError):
+            ctx.coll_info(2)
+        st = [ctx.stats(r) for r in range(4)]
+        assert sum(x["launches"] + x["sqe_fetched"] for x in st) == 0       # nothing reached a queue
+        gh.submit_round_robin(ctx, dw)
+        assert ctx.wait_all(20.0) == dfx.OK
+        for ci in range(2):
+            _expect(dw, w, ci)
+    finally:
+        assert ctx.finalize() == dfx.OK
