@@ -884,11 +884,13 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 if (sh.slot_tag[c_id % DFX_CTX_SLOTS] == c_id) sh.slot_tag[c_id % DFX_CTX_SLOTS] = 0xffffffffu;
               }
               // every workgroup of the rank reads every SQE; the last reader frees the slot (Sec. 5)
-              uint32_t* rc = &a.sq_readers[(size_t)rank * D + ((ri + lane) & (D - 1))];
+              // by writing the entry's generation where the submitter looks for it, in host memory
+              const size_t sq_at = (size_t)rank * D + ((ri + lane) & (D - 1));
+              uint32_t* rc = &a.sq_readers[sq_at];
               const uint32_t old = __hip_atomic_fetch_add(rc, 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT);
               if (old + 1 == a.cmax) {
                 __hip_atomic_store(rc, 0u, __ATOMIC_RELAXED, SCOPE_AGENT);
-                __hip_atomic_store(&sqbase[(ri + lane) & (D - 1)].e.ready, 0u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
+                __hip_atomic_store(&a.sq_freed[sq_at], (uint32_t)((ri + lane) >> a.sq_shift) + 1u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
               }
             }
             // the entries that are this workgroup's join the task queue in SQ order
@@ -1034,14 +1036,49 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       }
 
       // ---- wait phase: lane 0 polls the recv side, lane 1 the send side (Sec. 4.2 (3)).
+      // The first poll is sent off before the slice's geometry is worked out, which depends only on
+      // the sequence position: the arithmetic runs while the counters travel, and a poll that
+      // succeeds is followed by the job at once.
+      u64 seen_cnt = 0;
+      if (lane == 0 && q.recv) seen_cnt = ld_agent64(tail_in);
+      if (lane == 1 && q.send) seen_cnt = ld_agent64(tail_out + 8);
+
+      // ---- slice geometry (elements relative to the block, clipped to the block's true length)
+      const int kind = S.kind, dtype = S.dtype;   // dtype: element type | reducing function << 4
+      const uint32_t eb = ((dtype & 15) == DT_F32 || (dtype & 15) == DT_I32) ? 4u : 2u;
+      const uint32_t slice_elems = S.slice_elems, vch = S.vch;
+      const u64 count = S.count, block_elems = S.block_elems, part_elems = S.part_elems;
+      const bool ring_chunks = (kind == KIND_AR && a.R > 1);
+      u64 blen = count;
+      if (ring_chunks) {
+        const u64 start = (u64)cidx * block_elems;
+        blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
+      }
+      u64 lo = (u64)vch * part_elems + (u64)g * slice_elems;
+      u64 hi = lo + slice_elems;
+      const u64 pend = (u64)(vch + 1) * part_elems;
+      if (hi > pend) hi = pend;
+      if (lo > blen) lo = blen;
+      if (hi > blen) hi = blen;
+      const uint32_t bytes = (uint32_t)(hi - lo) * eb;
+      u64 soff = lo, doff = lo;   // element offsets in the send / recv buffer
+      if (ring_chunks) { soff += (u64)cidx * block_elems; doff = soff; }
+      else if (kind == KIND_RS) soff += (u64)cidx * count;
+      else if (kind == KIND_AG) doff += (u64)cidx * count;
+      const size_t slot_bytes = (size_t)slice_elems * eb;
+      const void* jfin = q.recv ? (const void*)((const uint8_t*)S.fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
+      void* jfout = q.send ? (void*)((uint8_t*)S.fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
+      const char* jsb = q.from_send ? (const char*)S.sendbuf + soff * eb : nullptr;
+      char* jrb = q.to_recv ? (char*)S.recvbuf + doff * eb : nullptr;
+
       // The movers may be busy with earlier slices meanwhile; finished ones are retired between polls.
       uint32_t res = W_OK;
       if (q.recv || q.send) {
         u64 n = 0;
         for (;;) {
           bool ok = true;
-          if (lane == 0 && q.recv) ok = ld_agent64(tail_in) > recvd;
-          if (lane == 1 && q.send) ok = (sent - ld_agent64(tail_out + 8)) < (u64)K;
+          if (lane == 0 && q.recv) ok = seen_cnt > recvd;
+          if (lane == 1 && q.send) ok = (sent - seen_cnt) < (u64)K;
           ++n;
           if (__ballot(!ok) == 0) break;
           retire_finished();
@@ -1064,6 +1101,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             if (bcast0(s)) { res = W_STOP; break; }
           }
           __builtin_amdgcn_s_sleep(1);
+          if (lane == 0 && q.recv) seen_cnt = ld_agent64(tail_in);
+          if (lane == 1 && q.send) seen_cnt = ld_agent64(tail_out + 8);
         }
         if (lane == 0) bump(sh.stat, ST_POLLS, n);
       }
@@ -1081,34 +1120,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           }
         }
         if (given_up) { stop = STOP_ABORT; have = false; continue; }
-        // ---- slice geometry (elements relative to the block, clipped to the block's true length)
-        const int kind = S.kind, dtype = S.dtype;   // dtype: element type | reducing function << 4
-        const uint32_t eb = ((dtype & 15) == DT_F32 || (dtype & 15) == DT_I32) ? 4u : 2u;
-        const uint32_t slice_elems = S.slice_elems, vch = S.vch;
-        const u64 count = S.count, block_elems = S.block_elems, part_elems = S.part_elems;
-        const bool ring_chunks = (kind == KIND_AR && a.R > 1);
-        u64 blen = count;
-        if (ring_chunks) {
-          const u64 start = (u64)cidx * block_elems;
-          blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
-        }
-        u64 lo = (u64)vch * part_elems + (u64)g * slice_elems;
-        u64 hi = lo + slice_elems;
-        const u64 pend = (u64)(vch + 1) * part_elems;
-        if (hi > pend) hi = pend;
-        if (lo > blen) lo = blen;
-        if (hi > blen) hi = blen;
-        const uint32_t bytes = (uint32_t)(hi - lo) * eb;
-        u64 soff = lo, doff = lo;   // element offsets in the send / recv buffer
-        if (ring_chunks) { soff += (u64)cidx * block_elems; doff = soff; }
-        else if (kind == KIND_RS) soff += (u64)cidx * count;
-        else if (kind == KIND_AG) doff += (u64)cidx * count;
         // ---- claim the slots and step the sequence (the data follows, the counters after it)
-        const size_t slot_bytes = (size_t)slice_elems * eb;
-        const void* jfin = q.recv ? (const void*)((const uint8_t*)S.fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
-        void* jfout = q.send ? (void*)((uint8_t*)S.fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
-        const char* jsb = q.from_send ? (const char*)S.sendbuf + soff * eb : nullptr;
-        char* jrb = q.to_recv ? (char*)S.recvbuf + doff * eb : nullptr;
         const uint32_t this_p = p;
         if (q.send) ++sent;
         if (q.recv) ++recvd;

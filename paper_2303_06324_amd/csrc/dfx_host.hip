@@ -71,6 +71,7 @@ struct dfx_ctx {
   uint32_t* host_ctl = nullptr;
   uint64_t* cq = nullptr;
   uint64_t* cq_ctl = nullptr;        // ring bookkeeping of the ring-buffer CQ variants (same allocation as cq)
+  uint32_t* sq_freed = nullptr;      // [R][sq_depth] generation of the last entry every workgroup has read (same allocation as cq)
   // device memory
   uint32_t* sq_readers = nullptr;
   uint32_t* done_cnt = nullptr;
@@ -168,7 +169,7 @@ int launch_locked(dfx_ctx* c) {
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   a.nwg = c->nwg;
-  a.cq_ctl = c->cq_ctl; a.cq_mode = c->cfg.cq_mode; a.sq_eager = c->cfg.sq_eager; a.window = c->cfg.window; a.sq_local = c->sq_device ? 1u : 0u;
+  a.cq_ctl = c->cq_ctl; a.sq_freed = c->sq_freed; a.cq_mode = c->cfg.cq_mode; a.sq_eager = c->cfg.sq_eager; a.window = c->cfg.window; a.sq_local = c->sq_device ? 1u : 0u;
   a.scan_min = c->cfg.scan_min;
   a.chan_spread = c->cfg.chan_spread;
   a.epoch = (uint32_t)(c->launches + 1);
@@ -205,7 +206,12 @@ int push_sqe(dfx_ctx* c, int rank, const DfxStatic& e) {
   const uint32_t D = c->cfg.sq_depth;
   DfxSqSlot* slot = &c->sq[(size_t)rank * D + (rs->sq_tail & (D - 1))];
   volatile uint32_t* ready = &slot->e.ready;
-  if (*ready != 0) return DFX_ERR_SQ_FULL;   // not yet read by every workgroup of the rank
+  // The slot last held the entry of one generation back; the last workgroup to read that one wrote
+  // its generation into host memory.  Nothing is read from the SQ itself: it may lie behind the
+  // PCIe BAR, where a load costs a microsecond.
+  const uint32_t gen_before = (uint32_t)(rs->sq_tail >> c->sq_shift);
+  volatile uint32_t* freed = &c->sq_freed[(size_t)rank * D + (rs->sq_tail & (D - 1))];
+  if (*freed != gen_before) return DFX_ERR_SQ_FULL;   // not yet read by every workgroup of the rank
   std::atomic_thread_fence(std::memory_order_acquire);
   DfxStatic tmp = e;
   tmp.ready = 0;
@@ -383,7 +389,8 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   const size_t R = (size_t)nranks;
   const size_t sq_bytes = R * cfg.sq_depth * sizeof(DfxSqSlot) + HC_N * sizeof(uint32_t) + 256;
   const size_t cq_slots_bytes = round_up(R * cfg.cq_slots * sizeof(uint64_t), 64);
-  const size_t cq_bytes = cq_slots_bytes + R * DFX_CQ_CTL_WORDS * sizeof(uint64_t);
+  const size_t cq_ctl_bytes = round_up(R * DFX_CQ_CTL_WORDS * sizeof(uint64_t), 64);
+  const size_t cq_bytes = cq_slots_bytes + cq_ctl_bytes + R * cfg.sq_depth * sizeof(uint32_t);
   if (c->sq_device) {
     INITCHK(hipExtMallocWithFlags(&c->qmem_sq, sq_bytes, hipDeviceMallocFinegrained));
     INITCHK(hipMemset(c->qmem_sq, 0, sq_bytes));
@@ -397,6 +404,7 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   c->host_ctl = (uint32_t*)((char*)c->qmem_sq + round_up(R * cfg.sq_depth * sizeof(DfxSqSlot), 256));
   c->cq = (uint64_t*)c->qmem_cq;
   c->cq_ctl = (uint64_t*)((char*)c->qmem_cq + cq_slots_bytes);
+  c->sq_freed = (uint32_t*)((char*)c->qmem_cq + cq_slots_bytes + cq_ctl_bytes);
 
   auto dalloc = [&](void** p, size_t bytes) -> hipError_t {
     hipError_t e = hipMalloc(p, bytes);

@@ -40,7 +40,7 @@ struct alignas(16) DfxStatic {
   uint32_t nprim;        // primitives per round on every rank
   uint32_t reserved;
   uint32_t reserved2;
-  uint32_t ready;        // SQ only, written last: generation of the entry, 0 = slot writable
+  uint32_t ready;        // SQ only, written last: generation of the entry
 };
 static_assert(sizeof(DfxStatic) == 96, "DfxStatic must be 96 bytes");
 
@@ -111,6 +111,7 @@ struct DfxDaemonArgs {
   uint64_t* cq;             // [R][cq_slots]   host-visible
   uint64_t* cq_ctl;         // [R][DFX_CQ_CTL_WORDS] host-visible: bookkeeping of the ring-buffer CQ variants
   uint32_t* host_ctl;       // [HC_N]          host-visible
+  uint32_t* sq_freed;       // [R][sq_depth]   host memory: generation of the entry last read by every workgroup
   uint32_t* sq_readers;     // [R][sq_depth]   device
   uint32_t* done_cnt;       // [R][max_colls]  device
   uint32_t* dev_ctl;        // [DC_N]          device
