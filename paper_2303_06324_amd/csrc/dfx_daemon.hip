@@ -1071,6 +1071,28 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       const char* jsb = q.from_send ? (const char*)S.sendbuf + soff * eb : nullptr;
       char* jrb = q.to_recv ? (char*)S.recvbuf + doff * eb : nullptr;
 
+      // The position after this primitive.  Slices are taken in windows of W: primitive p of every
+      // slice of the window, then primitive p+1 of every slice, ...  The neighbour does the same, so
+      // when this rank comes to (slice, p+1) the neighbour finished (slice, p) one job ago instead
+      // of at this very moment, and the hop latency hides behind the other slice's data.  The
+      // chunk index steps down the ring with p; a new window starts the sequence over.
+      uint32_t g_next = g, p_next = p, cidx_next = cidx;
+      {
+        const uint32_t W = a.window;
+        if (((g + 1) & (W - 1)) != 0 && g + 1 < S.rounds) ++g_next;
+        else {
+          g_next &= ~(W - 1);
+          cidx_next = (cidx == 0) ? a.R - 1 : cidx - 1;
+          if (++p_next == S.nprim) {
+            p_next = 0; g_next += W;
+            cidx_next = (kind == KIND_AG) ? rank : ((kind == KIND_BC || kind == KIND_RD || a.R == 1) ? 0u : cidx0_reduce);
+          }
+          if (kind == KIND_BC || kind == KIND_RD) cidx_next = 0;
+        }
+      }
+      const bool last = (g_next >= S.rounds);
+      const uint32_t inv_seq = S.seq, inv_nchan = S.nchan;
+
       // The movers may be busy with earlier slices meanwhile; finished ones are retired between polls.
       uint32_t res = W_OK;
       if (q.recv || q.send) {
@@ -1120,26 +1142,23 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           }
         }
         if (given_up) { stop = STOP_ABORT; have = false; continue; }
-        // ---- claim the slots and step the sequence (the data follows, the counters after it)
-        const uint32_t this_p = p;
+        // ---- post the slice (an empty one is only a handshake: the movers just raise the counters);
+        // this claims the slots: the data follows, the counters after it
         if (q.send) ++sent;
         if (q.recv) ++recvd;
-        // Next primitive.  Slices are taken in windows of W: primitive p of every slice of the
-        // window, then primitive p+1 of every slice, ...  The neighbour does the same, so when
-        // this rank comes to (slice, p+1) the neighbour finished (slice, p) one job ago instead of
-        // at this very moment, and the hop latency hides behind the other slice's data.  The
-        // chunk index steps down the ring with p; a new window starts the sequence over.
-        const uint32_t W = a.window;
-        if (((g + 1) & (W - 1)) != 0 && g + 1 < S.rounds) ++g;
-        else {
-          g &= ~(W - 1);
-          cidx = (cidx == 0) ? a.R - 1 : cidx - 1;
-          if (++p == S.nprim) {
-            p = 0; g += W;
-            cidx = (kind == KIND_AG) ? rank : ((kind == KIND_BC || kind == KIND_RD || a.R == 1) ? 0u : cidx0_reduce);
-          }
-          if (kind == KIND_BC || kind == KIND_RD) cidx = 0;
+        if (lane == 0) {
+          Job j;
+          j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
+          j.bytes = bytes; j.dtype = dtype; j.coll = coll; j.prim = p;
+          sh.job[posted & 1] = j;
+          Flight f;
+          f.tail_out = q.send ? tail_out : nullptr; f.head_in = q.recv ? tail_in + 8 : nullptr;
+          f.sent_new = sent; f.recvd_new = recvd;
+          f.last = last ? 1u : 0u; f.coll = coll; f.seq = inv_seq; f.nchan = inv_nchan;
+          sh.fl[posted & 1] = f;
+          lds_st(&sh.job_seq, posted + 1);
         }
+        g = g_next; p = p_next; cidx = cidx_next;
         progressed = true;
         pass_progress = true;
         acted = true;
@@ -1147,21 +1166,6 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         if (!scanned) {
           thr *= a.spin_boost;
           if (thr > a.spin_max) thr = a.spin_max;
-        }
-        const bool last = (g >= S.rounds);
-
-        // ---- post the slice (an empty one is only a handshake: the movers just raise the counters)
-        if (lane == 0) {
-          Job j;
-          j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
-          j.bytes = bytes; j.dtype = dtype; j.coll = coll; j.prim = this_p;
-          sh.job[posted & 1] = j;
-          Flight f;
-          f.tail_out = q.send ? tail_out : nullptr; f.head_in = q.recv ? tail_in + 8 : nullptr;
-          f.sent_new = sent; f.recvd_new = recvd;
-          f.last = last ? 1u : 0u; f.coll = coll; f.seq = S.seq; f.nchan = S.nchan;
-          sh.fl[posted & 1] = f;
-          lds_st(&sh.job_seq, posted + 1);
         }
         ++posted;
 
