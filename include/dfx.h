@@ -109,7 +109,12 @@ typedef struct {
                               primitive p of every slice of the window, then primitive p+1 ..., so that the
                               hop latency of one slice hides behind the data of another.  1 = the whole
                               primitive sequence slice after slice */
-  uint32_t reserved0;
+  uint32_t focus_bytes;    /* stickiness across ranks (Sec. 4.3 "coalescing the GPUs' choices"): when not 0, a scanned
+                              pass over a queue of at most 64 entries visits the runnable collectives
+                              furthest-along first and ends once it has handed the movers this many bytes, so
+                              that all ranks carry the same few collectives through instead of advancing all
+                              of them side by side (whose FIFO slots together outgrow the memory-side cache);
+                              0 = every runnable collective once per pass, in queue order */
 } dfx_config;
 
 /* Aggregated over the workgroups of one vrank since dfx_init. */

@@ -50,6 +50,10 @@ Two variations of Alg. 1 can be switched on, to ask whether they keep its livene
     queue at once; its CQE is written when that slice has been moved.
   * `scan = True`: a pass starts by evaluating the wait conditions of every queue entry and
     visits only the entries found runnable, each with the minimum threshold.
+  * `focus = n > 0` (with scan): the runnable entries are visited furthest-along first
+    (most primitives done; ties in queue order), and once n slices have been taken in the
+    pass it ends with the entry in hand: every rank ranks the collectives alike, so the
+    ranks settle on the same few of them (the coalescing of choices that Sec. 4.3 aims at).
 """
 from __future__ import annotations
 
@@ -91,6 +95,7 @@ class Policy:
     fetch_batch: int = 1          # SQEs fetched in a row when the queue is empty or stuck (0 = all available)
     lookahead: int = 0            # 0: a slice moves at its successful poll; n: up to n claimed slices per rank, moved by a mover actor
     scan: bool = False            # a pass visits only the entries whose wait conditions hold at its start
+    focus: int = 0                # with scan: furthest-along entries first, and the pass ends after this many slices
 
 
 @dataclass
@@ -209,7 +214,7 @@ class Daemon:
         self.jobs: List[tuple] = []            # claimed slices not yet moved (lookahead)
         self.ready: Optional[List[int]] = None # queue positions found runnable by the scan of the pass in flight
         self.rk = 0                            # cursor in self.ready
-        self.removed = 0                       # entries that left the queue during the pass in flight
+        self.taken = 0                         # slices taken in the pass in flight
         self.stats = Stats()
 
     # -- Alg. 1 helpers
@@ -258,6 +263,20 @@ class Daemon:
         pushes = sum(1 for j in self.jobs if j[0] == coll and PRIMS[j[3]][1])
         return fin.tail - fin.head - pops > 0, fout.tail + pushes - fout.head < fout.K
 
+    def _done(self, coll):
+        """Primitives of the invocation this rank has taken so far."""
+        g, p = self.active if self.loaded == coll else self.saved[coll]
+        return g * len(self.S.progs[coll][self.r]) + p
+
+    def _next_entry(self, left_queue_at: Optional[int] = None):
+        """Scanned pass: go on to the next list entry.  An entry that left the queue moves the
+        ones behind it up by one; a focused pass that has taken its share of slices ends here."""
+        self.rk += 1
+        if left_queue_at is not None:
+            self.ready = [i - 1 if (k >= self.rk and i > left_queue_at) else i for k, i in enumerate(self.ready)]
+        if self.S.policy.focus and self.taken >= self.S.policy.focus:
+            self.rk = len(self.ready)
+
     def _runnable(self, coll):
         g, p = self.active if self.loaded == coll else self.saved[coll]
         need_recv, need_send = PRIMS[self.S.progs[coll][self.r][p][0]]
@@ -298,7 +317,9 @@ class Daemon:
                 self.in_pass, self.pos, self.pass_progress = True, 0, False
                 if self.S.policy.scan:
                     self.ready = [i for i, c in enumerate(self.taskq) if self._runnable(c)]
-                    self.rk, self.removed = 0, 0
+                    if self.S.policy.focus:
+                        self.ready.sort(key=lambda i: (-self._done(self.taskq[i]), i))
+                    self.rk, self.taken = 0, 0
                     if not self.ready:
                         self.in_pass = False   # nothing can run: the pass is over before it began
                         if self.loaded is not None:
@@ -306,7 +327,7 @@ class Daemon:
                             changed = True
                         return changed
             if self.S.policy.scan:
-                self.pos = self.ready[self.rk] - self.removed if self.rk < len(self.ready) else len(self.taskq)
+                self.pos = self.ready[self.rk] if self.rk < len(self.ready) else len(self.taskq)
             if self.pos >= len(self.taskq):
                 self.in_pass = False
                 if self.loaded is not None:
@@ -345,7 +366,7 @@ class Daemon:
                 self.stats.preemptions += 1
                 self._save()
                 if P.scan:
-                    self.rk += 1
+                    self._next_entry()
                 else:
                     self.pos += 1
             return True
@@ -361,6 +382,7 @@ class Daemon:
         else:
             S.move(coll, self.r, g, p, name, sblk, dblk, fin, fout)
         self.stats.prims += 1
+        self.taken += 1
         self.dirty = True
         self.pass_progress = True
         self.spin = 0
@@ -375,8 +397,7 @@ class Daemon:
             self.saved[coll] = [0, 0]
             self.loaded = None
             if P.scan:
-                self.rk += 1
-                self.removed += 1
+                self._next_entry(left_queue_at=self.pos)
         return True
 
 
@@ -471,7 +492,7 @@ class System:
                        tuple(d.active) if d.active and d.loaded is not None else None, d.dirty,
                        tuple(sorted((k, tuple(v)) for k, v in d.saved.items())), d.spin, d.thr, len(d.cq),
                        tuple((j[0], j[1], j[2]) for j in d.jobs),
-                       (tuple(d.ready), d.rk, d.removed) if d.in_pass and d.ready is not None else None))
+                       (tuple(d.ready), d.rk, d.taken if self.policy.focus else 0) if d.in_pass and d.ready is not None else None))
         fs = tuple((f.head, f.tail) for fl in self.fifo for f in fl)
         return (tuple(ds), fs, tuple(tuple(p) for p in self.pending))
 
@@ -503,7 +524,7 @@ class System:
             e.cq, e.seq_of = list(d.cq), dict(d.seq_of)
             e.jobs = list(d.jobs)
             e.ready = list(d.ready) if d.ready is not None else None
-            e.rk, e.removed = d.rk, d.removed
+            e.rk, e.taken = d.rk, d.taken
             e.stats = copy.copy(d.stats)
             T.daemons.append(e)
         T.pending = [list(p) for p in self.pending]

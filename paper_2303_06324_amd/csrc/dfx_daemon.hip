@@ -633,7 +633,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
     bool acted = true, voted = false;
     uint32_t iter = 0, idle = 0, burst = 0;
     bool in_pass = false, pass_progress = false, scanned = false;
-    uint32_t nready = 0, rk = 0, removed = 0;   // readiness list of the pass: length, cursor, entries completed
+    uint32_t nready = 0, rk = 0, pass_bytes = 0;   // readiness list of the pass: length, cursor; bytes posted in the pass
+    bool focus = false;                            // the pass visits the list furthest-along first, up to a byte budget
     uint32_t pos = 0;
     // context-switch sample in flight: t0 = abort decision, ts = after the save, lb/le = load
     u64 sw_t0 = 0, sw_ts = 0, sw_lb = 0, sw_le = 0;
@@ -950,10 +951,12 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           // sixteen memory round trips instead of a thousand context loads and bounded spins.
           scanned = a.scan_min && qlen >= a.scan_min;
           if (scanned) {
-            nready = 0; rk = 0; removed = 0;
+            nready = 0; rk = 0; pass_bytes = 0;
+            focus = a.focus_bytes != 0 && qlen <= 64u;
             for (uint32_t base = 0; base < qlen; base += 64) {
               const uint32_t i = base + lane;
               bool rdy = false;
+              uint32_t key = 0;     // 0 = not runnable; else primitives done so far, then queue position
               if (i < qlen) {
                 const uint4* e = (const uint4*)&myctx[sh.taskq[i]];
                 const uint4 fl = e[2];    // bytes 32..47: part_elems | flags_out
@@ -968,9 +971,24 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 if (pq.recv) okr = ld_agent64((const u64*)f_in) > e_recvd;
                 if (pq.send) oks = (e_sent - ld_agent64((const u64*)f_out + 8)) < (u64)(ge.z & 0xffu);
                 rdy = okr && oks;
+                if (rdy) {
+                  u64 done = (u64)d0.x * (ge.y & 0xffffu) + d0.y;
+                  if (done > 0xfffffu) done = 0xfffffu;
+                  key = (((uint32_t)done << 8) | (63u - lane)) + 1u;
+                }
               }
               const u64 mask = __ballot(rdy);
-              if (rdy) sh.rlist[nready + (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull))] = (uint16_t)i;
+              if (focus) {
+                // One step holds the whole queue.  The runnable entries are visited furthest-along
+                // first (ties: queue order): every rank ranks them alike, so the ranks settle on
+                // the same few collectives and carry those through, instead of moving all of
+                // them forward side by side with all of their FIFO slots in use at once.
+                uint32_t rank_in_pass = 0;
+                const uint32_t nq = qlen < 64u ? qlen : 64u;
+                for (uint32_t j = 0; j < nq; ++j)
+                  rank_in_pass += ((uint32_t)__builtin_amdgcn_readlane((int)key, (int)j) > key) ? 1u : 0u;
+                if (rdy) sh.rlist[rank_in_pass] = (uint16_t)i;
+              } else if (rdy) sh.rlist[nready + (uint32_t)__builtin_popcountll(mask & ((1ull << lane) - 1ull))] = (uint16_t)i;
               nready += (uint32_t)__builtin_popcountll(mask);
             }
             __builtin_amdgcn_wave_barrier();
@@ -983,10 +1001,11 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           }
         }
         if (scanned) {
-          // entries completed earlier in this pass moved the later ones up by one each
           // (a pass that ends is not a switch between two collectives: the latency sample is dropped)
-          if (rk >= nready) { in_pass = false; sw_pending = false; continue; }
-          pos = (uint32_t)sh.rlist[rk] - removed;
+          // A focused pass also ends once it has handed the movers its share of bytes: the next scan
+          // looks again at which collectives are furthest along.
+          if (rk >= nready || (focus && pass_bytes >= a.focus_bytes)) { in_pass = false; sw_pending = false; continue; }
+          pos = (uint32_t)sh.rlist[rk];
         } else if (pos >= qlen) { in_pass = false; sw_pending = false; continue; }
 
         // ---- LoadCollectiveContext: HBM context buffer -> LDS slot, 8 lanes x 16 bytes
@@ -1159,6 +1178,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           lds_st(&sh.job_seq, posted + 1);
         }
         g = g_next; p = p_next; cidx = cidx_next;
+        pass_bytes += bytes;
         progressed = true;
         pass_progress = true;
         acted = true;
@@ -1189,7 +1209,15 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           }
           have = false;
           sw_pending = false;
-          if (scanned) { ++rk; ++removed; }
+          if (scanned) {
+            // the entries behind the one that left have moved up by one: so do their positions in the list
+            ++rk;
+            for (uint32_t base = rk; base < nready; base += 64) {
+              const uint32_t k = base + lane;
+              if (k < nready && (uint32_t)sh.rlist[k] > pos) sh.rlist[k] = (uint16_t)(sh.rlist[k] - 1u);
+            }
+            __builtin_amdgcn_wave_barrier();
+          }
         }
       } else {
         // ---- PreemptCollective + SaveCollectiveContext (lazy: only if it progressed)

@@ -169,7 +169,7 @@ int launch_locked(dfx_ctx* c) {
   a.watchdog_ticks = (uint64_t)((double)c->cfg.watchdog_ms * 1000.0 / c->tick_us);
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   a.nwg = c->nwg;
-  a.cq_ctl = c->cq_ctl; a.sq_freed = c->sq_freed; a.cq_mode = c->cfg.cq_mode; a.sq_eager = c->cfg.sq_eager; a.window = c->cfg.window; a.sq_local = c->sq_device ? 1u : 0u;
+  a.cq_ctl = c->cq_ctl; a.sq_freed = c->sq_freed; a.cq_mode = c->cfg.cq_mode; a.sq_eager = c->cfg.sq_eager; a.window = c->cfg.window; a.sq_local = c->sq_device ? 1u : 0u; a.focus_bytes = c->cfg.focus_bytes;
   a.scan_min = c->cfg.scan_min;
   a.chan_spread = c->cfg.chan_spread;
   a.epoch = (uint32_t)(c->launches + 1);
@@ -312,7 +312,7 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->cq_mode = 0;
   cfg->sq_eager = 1;
   cfg->window = 2;
-  cfg->reserved0 = 0;
+  cfg->focus_bytes = 128u << 10;
   cfg->preempt = 1;
   cfg->watchdog_ms = 10000;
   cfg->quit_idle_us = 2000;

@@ -125,7 +125,7 @@ struct DfxDaemonArgs {
   uint32_t epoch;           // number of this launch (exit SQEs name the launch they end)
   uint32_t R, cmax, max_colls, sq_depth, sq_shift, cq_slots;
   uint32_t spin_init, spin_min, spin_max, spin_boost, preempt;
-  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent, chan_spread, cq_mode, sq_eager, window, sq_local;
+  uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent, chan_spread, cq_mode, sq_eager, window, sq_local, focus_bytes;
   uint64_t watchdog_ticks;  // wall-clock ticks; 0 = off
   uint64_t quit_ticks;      // wall-clock ticks; 0 = off
 };

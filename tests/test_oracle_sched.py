@@ -178,14 +178,17 @@ def test_batch_fetch_keeps_liveness_and_values(batch):
 
 
 # ---------------------------------------------------------------- claim-ahead and scan variations
-VARIANTS = [dict(lookahead=1), dict(lookahead=2), dict(scan=True), dict(lookahead=2, scan=True)]
+VARIANTS = [dict(lookahead=1), dict(lookahead=2), dict(scan=True), dict(lookahead=2, scan=True),
+            dict(scan=True, focus=1), dict(lookahead=2, scan=True, focus=2)]
 
 
-@pytest.mark.parametrize("var", [dict(lookahead=2), dict(scan=True), dict(lookahead=2, scan=True)])
+@pytest.mark.parametrize("var", [dict(lookahead=2), dict(scan=True), dict(lookahead=2, scan=True),
+                                 dict(lookahead=2, scan=True, focus=1)])
 @pytest.mark.parametrize("orders", [((0, 1), (1, 0)), ((0, 1), (0, 1))])
 def test_variations_exhaustive_interleavings_tiny(orders, var):
-    """Claiming slices ahead of their movement (a mover actor raises the shared counters later) and
-    visiting only runnable entries keep Alg. 1's liveness: in the circular-wait setting no reachable
+    """Claiming slices ahead of their movement (a mover actor raises the shared counters later),
+    visiting only runnable entries, and visiting them furthest-along first in passes that end after a
+    fixed number of slices keep Alg. 1's liveness: in the circular-wait setting no reachable
     state -- over all interleavings of daemons, movers and host submissions -- is a deadlock, and every
     one of them finishes with all four CQEs."""
     # (without the scan the state space is large: one slice per collective there, two with it)
@@ -256,3 +259,32 @@ def test_negative_control_still_deadlocks_with_claims():
     with pytest.raises(TimeoutError):
         sm.run_round_robin(S, max_ticks=20_000)
     assert sm.is_deadlocked(S)
+
+
+def test_focused_passes_take_the_furthest_along_first():
+    """focus = 1: after the scan of a pass the daemon works on the runnable collective with the most
+    primitives done (ties: queue order), and the pass ends with that entry."""
+    colls = [wi.CollSpec(i, wi.AR, wi.I32, 24) for i in range(3)]
+    w = wi.Workload("focus", 2, colls, [[0, 1, 2], [0, 1, 2]], seed=4, cfg=92)
+    S = _system(w, sm.Policy(spin_init=1, spin_min=1, spin_max=1, boost=1, K=2, slice_elems=4, scan=True, focus=1, fetch_batch=0))
+    for r in range(2):
+        while S.pending[r]:
+            S.host_tick(r)
+    d0, d1 = S.daemons
+    picks = []
+    for _ in range(400):
+        if S.done():
+            break
+        for d in (d0, d1):
+            was = d.in_pass
+            d.tick()
+            if d is d0 and d.in_pass and not was and d.ready:
+                # a pass has just begun: its list is sorted by primitives done, then queue position
+                done = [d._done(d.taskq[i]) for i in d.ready]
+                assert done == sorted(done, reverse=True)
+                assert all(a < b for a, b, x, y in zip(d.ready, d.ready[1:], done, done[1:]) if x == y)
+                picks.append(d.taskq[d.ready[0]])
+    assert S.done() and S.total_cqes() == 6
+    _check_data(S, w)
+    # the first collective is carried through before the last one is begun
+    assert picks.index(2) > max(i for i, c in enumerate(picks) if c == 0) - 2
