@@ -147,29 +147,32 @@ def deadlock_prone():
                           ("config4_64_mixed", wi.config4(), "threads"),
                           ("config5_1024_small", wi.config5(), "threads")):
         dw = gh.DeviceWorkload(w, keep_host=False)
-        runs = []
-        for rep in range(3):        # a fresh context each time; the first run also pays first-touch costs
-            ctx = dfx.Context(R, gh.make_config())
-            try:
-                gh.prepare_all(ctx, w)
+        # One context, the workload four times back to back inside the resident daemon: after an
+        # idle stretch (context creation) the first run or two are slower (clocks), so every time is
+        # reported and the best one is `seconds`; counters are per run (mean).
+        nrun = 4
+        times = []
+        ctx = dfx.Context(R, gh.make_config(quit_idle_us=0))
+        try:
+            gh.prepare_all(ctx, w)
+            rc = 0
+            for rep in range(nrun):
                 t0 = time.perf_counter()
                 if mode == "threads":
                     gh.submit_threads(ctx, dw, delays_us=w.delays_us or None, timeout_s=60)
                 else:
                     gh.submit_round_robin(ctx, dw, timeout_s=60)
-                rc = ctx.wait_all(60.0)
-                dt = time.perf_counter() - t0
-                ctx.stop()
-                st = [ctx.stats(r) for r in range(R)]
-            finally:
-                ctx.finalize()
-            runs.append((dt, rc == 0 and sum(s["cqe_posted"] for s in st) == len(w.colls) * R,
-                         sum(s["preemptions"] for s in st), max(s["max_taskq"] for s in st)))
+                rc = rc or ctx.wait_all(60.0)
+                times.append(time.perf_counter() - t0)
+            ctx.stop()
+            st = [ctx.stats(r) for r in range(R)]
+        finally:
+            ctx.finalize()
         del dw
-        best = min(runs)
-        out[name] = {"completed": all(r[1] for r in runs), "seconds": round(best[0], 4),
-                     "seconds_all_runs": [round(r[0], 4) for r in runs],
-                     "preemptions": best[2], "max_task_queue": best[3]}
+        out[name] = {"completed": rc == 0 and sum(s["cqe_posted"] for s in st) == len(w.colls) * R * nrun,
+                     "seconds": round(min(times), 4), "seconds_all_runs": [round(t, 4) for t in times],
+                     "preemptions": sum(s["preemptions"] for s in st) // nrun,
+                     "max_task_queue": max(s["max_taskq"] for s in st)}
     return out
 
 
@@ -219,18 +222,21 @@ def spin_sweep():
     d3, d5 = gh.DeviceWorkload(w3, keep_host=False), gh.DeviceWorkload(w5, keep_host=False)
 
     def one(w, dw, mode, **kw):
-        ctx = dfx.Context(R, gh.make_config(**kw))
+        # three runs back to back in one resident daemon, the best one counts (the first follows an idle stretch)
+        ctx = dfx.Context(R, gh.make_config(quit_idle_us=0, **kw))
         try:
             gh.prepare_all(ctx, w)
-            t0 = time.perf_counter()
-            (gh.submit_threads if mode == "threads" else gh.submit_round_robin)(ctx, dw, timeout_s=120)
-            rc = ctx.wait_all(120.0)
-            dt = time.perf_counter() - t0
+            rc, dts = 0, []
+            for rep in range(3):
+                t0 = time.perf_counter()
+                (gh.submit_threads if mode == "threads" else gh.submit_round_robin)(ctx, dw, timeout_s=120)
+                rc = rc or ctx.wait_all(120.0)
+                dts.append(time.perf_counter() - t0)
             ctx.stop()
-            pre = sum(ctx.stats(r)["preemptions"] for r in range(R))
+            pre = sum(ctx.stats(r)["preemptions"] for r in range(R)) // 3
         finally:
             ctx.finalize()
-        return {"completed": rc == 0, "ms": round(dt * 1e3, 2), "preemptions": pre}
+        return {"completed": rc == 0, "ms": round(min(dts) * 1e3, 2), "preemptions": pre}
 
     rows = []
     for n in (1, 2, 4, 8, 16, 64, 256, 1024, 4096, 16384):
@@ -254,47 +260,43 @@ def studies():
     d5 = gh.DeviceWorkload(w5, keep_host=False)
     for mode, name in ((0, "optimized CQ: one CAS into a free slot"), (1, "vanilla ring buffer"),
                        (2, "optimized ring buffer: id + position in one 64-bit write")):
-        best = None
-        for rep in range(3):
-            ctx = dfx.Context(R, gh.make_config(cq_mode=mode))
-            try:
-                gh.prepare_all(ctx, w5)
+        ctx = dfx.Context(R, gh.make_config(cq_mode=mode, quit_idle_us=0))
+        try:
+            gh.prepare_all(ctx, w5)
+            rc, dts = 0, []
+            for rep in range(3):      # back to back in one resident daemon
                 t0 = time.perf_counter()
                 gh.submit_threads(ctx, d5, timeout_s=60)
-                rc = ctx.wait_all(60.0)
-                dt = time.perf_counter() - t0
-                ctx.stop()
-                st = [ctx.stats(r) for r in range(R)]
-            finally:
-                ctx.finalize()
-            n = sum(s["cqe_posted"] for s in st)
-            row = {"cq_mode": mode, "variant": name, "completed": rc == 0 and n == 1024 * R,
-                   "cqe_write_us_mean": round(sum(s["cqe_us"] for s in st) / max(1, n), 3),
-                   "collectives_per_s": round(1024 / dt, 1), "ms": round(dt * 1e3, 2)}
-            if best is None or row["cqe_write_us_mean"] < best["cqe_write_us_mean"]:
-                best = row
+                rc = rc or ctx.wait_all(60.0)
+                dts.append(time.perf_counter() - t0)
+            ctx.stop()
+            st = [ctx.stats(r) for r in range(R)]
+        finally:
+            ctx.finalize()
+        n = sum(s["cqe_posted"] for s in st)
+        best = {"cq_mode": mode, "variant": name, "completed": rc == 0 and n == 3 * 1024 * R,
+                "cqe_write_us_mean": round(sum(s["cqe_us"] for s in st) / max(1, n), 3),
+                "collectives_per_s": round(1024 / min(dts), 1), "ms": round(min(dts) * 1e3, 2)}
         out["cq_variants"].append(best)
     del d5
     w3 = wi.config3()
     d3 = gh.DeviceWorkload(w3, keep_host=False)
     for policy, name in ((0, "FIFO ordering"), (1, "priority ordering, later bucket = higher priority")):
-        best = None
-        for rep in range(3):
-            ctx = dfx.Context(R, gh.make_config(order_policy=policy))
-            try:
-                gh.prepare_all(ctx, w3, priorities=list(range(len(w3.colls))))
+        ctx = dfx.Context(R, gh.make_config(order_policy=policy, quit_idle_us=0))
+        try:
+            gh.prepare_all(ctx, w3, priorities=list(range(len(w3.colls))))
+            rc, dts = 0, []
+            for rep in range(3):      # back to back in one resident daemon
                 t0 = time.perf_counter()
                 gh.submit_round_robin(ctx, d3, timeout_s=60)
-                rc = ctx.wait_all(60.0)
-                dt = time.perf_counter() - t0
-                ctx.stop()
-                pre = sum(ctx.stats(r)["preemptions"] for r in range(R))
-            finally:
-                ctx.finalize()
-            row = {"order_policy": policy, "policy": name, "completed": rc == 0, "ms": round(dt * 1e3, 3),
-                   "preemptions": pre}
-            if best is None or row["ms"] < best["ms"]:
-                best = row
+                rc = rc or ctx.wait_all(60.0)
+                dts.append(time.perf_counter() - t0)
+            ctx.stop()
+            pre = sum(ctx.stats(r)["preemptions"] for r in range(R)) // 3
+        finally:
+            ctx.finalize()
+        best = {"order_policy": policy, "policy": name, "completed": rc == 0, "ms": round(min(dts) * 1e3, 3),
+                "preemptions": pre}
         out["ordering_config3"].append(best)
     return out
 
