@@ -109,7 +109,7 @@ typedef struct {
                               primitive p of every slice of the window, then primitive p+1 ..., so that the
                               hop latency of one slice hides behind the data of another.  1 = the whole
                               primitive sequence slice after slice */
-  uint32_t focus_bytes;    /* stickiness across ranks (Sec. 4.3 "coalescing the GPUs' choices"): when not 0, a scanned
+  uint32_t focus_bytes;    /* stickiness across ranks (the aim of Sec. 4.3's threshold adjustment): when not 0, a scanned
                               pass over a queue of at most 64 entries visits the runnable collectives
                               furthest-along first and ends once it has handed the movers this many bytes, so
                               that all ranks carry the same few collectives through instead of advancing all
