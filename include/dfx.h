@@ -154,6 +154,10 @@ int dfx_config_default(dfx_config* cfg);
  * library uses ONLY for the daemon kernel; nothing else may be enqueued on it (work queued
  * behind a resident daemon would never start).  Allocates SQ, CQ, context buffers, counters
  * and the connector pool; all are library-owned and freed by dfx_finalize.
+ * Several contexts may exist on one device, but their daemons take turns: a context's daemon is not
+ * started while another context's is in flight on the same device (that one leaves after
+ * quit_idle_us without work, or at dfx_stop; with quit_idle_us = 0 only at dfx_stop), and the calls
+ * that wait for completions start it as soon as the device is free.
  * Errors: INVALID_ARG (nranks < 1 or > 64, bad cfg), NO_RESOURCES (grid cannot be co-resident), HIP.
  */
 int dfx_init(dfx_ctx** out, int nranks, const dfx_config* cfg, void* hip_stream);

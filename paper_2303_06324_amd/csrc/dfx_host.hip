@@ -183,6 +183,26 @@ int launch_locked(dfx_ctx* c) {
   return DFX_OK;
 }
 
+// One daemon grid per device at a time.  A grid fills the compute units and every workgroup of it
+// spins on flags that its other workgroups write, so two grids that each got part of the device
+// would wait for each other until their watchdogs fire.  The contexts of a process therefore take
+// turns: a launch is put off while the daemon of another context on the same device is still in
+// flight (it leaves when it has been idle for quit_idle_us, or at dfx_stop), and every call that
+// waits for completions comes back here.  Lock order: a context's launch_mu, then the slot.
+struct DeviceSlot {
+  std::mutex mu;
+  dfx_ctx* owner = nullptr;
+  hipEvent_t until = nullptr;   // the owner's ev_stop: not ready while its grid is in flight
+};
+constexpr int kMaxDevices = 64;
+DeviceSlot g_slot[kMaxDevices];
+
+void release_slot(dfx_ctx* c) {
+  DeviceSlot& s = g_slot[c->device % kMaxDevices];
+  std::lock_guard<std::mutex> lk(s.mu);
+  if (s.owner == c) { s.owner = nullptr; s.until = nullptr; }
+}
+
 // Event-driven start (Sec. 4.4): make sure a daemon is running or queued.
 int ensure_running(dfx_ctx* c) {
   std::lock_guard<std::mutex> lk(c->launch_mu);
@@ -191,7 +211,15 @@ int ensure_running(dfx_ctx* c) {
   if (rc != DFX_OK) return rc;
   if (c->aborted.load()) return DFX_ERR_ABORTED;
   if (!idle) return DFX_OK;
-  return launch_locked(c);
+  DeviceSlot& s = g_slot[c->device % kMaxDevices];
+  std::lock_guard<std::mutex> lk2(s.mu);
+  if (s.owner && s.owner != c) {
+    if (hipEventQuery(s.until) == hipErrorNotReady) return DFX_OK;   // another context's turn
+    s.owner = nullptr;
+  }
+  rc = launch_locked(c);
+  if (rc == DFX_OK) { s.owner = c; s.until = c->ev_stop; }
+  return rc;
 }
 
 bool outstanding(dfx_ctx* c) {
@@ -862,6 +890,7 @@ int dfx_finalize(dfx_ctx* c) {
     if (c->ranks[r]->n_cqe.load() < c->ranks[r]->n_sub.load()) pending = true;
   }
   (void)hipStreamSynchronize(c->stream);
+  release_slot(c);
   free_all(c);
   if (rc == DFX_ERR_HIP) return rc;
   return (pending || rc == DFX_ERR_ABORTED) ? DFX_ERR_ABORTED : DFX_OK;

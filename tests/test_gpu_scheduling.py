@@ -453,3 +453,52 @@ def test_host_error_paths_leave_the_context_usable():
             _expect(dw, w, ci)
     finally:
         assert ctx.finalize() == dfx.OK
+
+
+def test_two_contexts_take_turns_on_the_device():
+    """Two daemon grids cannot be resident together (each fills the device and spins on its own
+    flags), so a context's daemon is started only when no other context's is in flight: both
+    contexts finish their collectives, and a daemon that never quits makes the other one wait
+    until it is stopped."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    wa = wi.Workload("turn_a", 8, [wi.CollSpec(0, wi.AR, wi.I32, 150001)], [[0]] * 8, seed=41, cfg=75)
+    wb = wi.Workload("turn_b", 4, [wi.CollSpec(0, wi.AG, wi.F16, 4099)], [[0]] * 4, seed=42, cfg=76)
+    da, db = gh.DeviceWorkload(wa), gh.DeviceWorkload(wb)
+    A = dfx.Context(8, gh.make_config(quit_idle_us=300))
+    B = dfx.Context(4, gh.make_config(quit_idle_us=300))
+    try:
+        gh.prepare_all(A, wa)
+        gh.prepare_all(B, wb)
+        pa = A.make_all([t.data_ptr() for t in da.send[0]], [t.data_ptr() for t in da.recv[0]])
+        pb = B.make_all([t.data_ptr() for t in db.send[0]], [t.data_ptr() for t in db.recv[0]])
+        for it in range(3):
+            assert A.submit_all(0, pa) == dfx.OK
+            assert B.submit_all(0, pb) == dfx.OK       # B's daemon is put off while A's is in flight
+            assert B.wait_all(20.0) == dfx.OK          # ... and started from here once A's has quit
+            assert A.wait_all(20.0) == dfx.OK
+            _expect(da, wa, 0)
+            _expect(db, wb, 0)
+        assert A.stop() == dfx.OK and B.stop() == dfx.OK
+        assert A.stats(0)["launches"] >= 1 and B.stats(0)["launches"] >= 1
+    finally:
+        ra, rb = A.finalize(), B.finalize()
+    assert (ra, rb) == (dfx.OK, dfx.OK)
+    # a daemon that never quits keeps the device until it is stopped
+    A = dfx.Context(8, gh.make_config(quit_idle_us=0))
+    B = dfx.Context(4, gh.make_config(quit_idle_us=300))
+    try:
+        gh.prepare_all(A, wa)
+        gh.prepare_all(B, wb)
+        pa = A.make_all([t.data_ptr() for t in da.send[0]], [t.data_ptr() for t in da.recv[0]])
+        pb = B.make_all([t.data_ptr() for t in db.send[0]], [t.data_ptr() for t in db.recv[0]])
+        assert A.submit_all(0, pa) == dfx.OK and A.wait_all(20.0) == dfx.OK
+        assert B.submit_all(0, pb) == dfx.OK
+        assert B.wait_all(0.2) == dfx.ERR_TIMEOUT
+        assert B.stats(0)["launches"] == 0
+        assert A.stop() == dfx.OK
+        assert B.wait_all(20.0) == dfx.OK
+        _expect(db, wb, 0)
+    finally:
+        ra, rb = A.finalize(), B.finalize()
+    assert (ra, rb) == (dfx.OK, dfx.OK)
