@@ -219,9 +219,6 @@ __device__ __forceinline__ uint16_t op_half(uint16_t a, uint16_t b, int op) {
 // ------------------------------------------------------------------------------------------
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
-#ifndef DFX_USER_NT
-#define DFX_USER_NT 1
-#endif
 // User-buffer accesses of the main loop are marked non-temporal: each byte is touched once, and
 // keeping it out of the way leaves the memory-side cache to the connector slots (+3 % measured).
 // They are 16-byte accesses through a type that promises only element alignment (2 bytes): the
@@ -230,18 +227,10 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 // slower).
 typedef v4u v4u_user __attribute__((aligned(2)));
 __device__ __forceinline__ uint4 ld_user(const v4u_user* p) {
-#if DFX_USER_NT
   return __builtin_bit_cast(uint4, __builtin_nontemporal_load(p));
-#else
-  return __builtin_bit_cast(uint4, *p);
-#endif
 }
 __device__ __forceinline__ void st_user(v4u_user* p, uint4 v) {
-#if DFX_USER_NT
   __builtin_nontemporal_store(__builtin_bit_cast(v4u, v), p);
-#else
-  *p = __builtin_bit_cast(v4u, v);
-#endif
 }
 
 // cache-policy operand of the buffer instructions (gfx940+): bit 0 = sc0, bit 4 = sc1
@@ -508,6 +497,70 @@ __device__ __forceinline__ u64 timeline_sample(u64 t0, u64 t1, uint32_t coll, ui
   return (t0 & 0xffffffffull) | (dur << 32) | ((u64)(coll & 0xfffu) << 48) | ((u64)(prim & 0xfu) << 60);
 }
 
+// Ring chunk that the first primitive of a sequence works on (see DfxDyn.cidx): an all-gather
+// starts with the rank's own block, the chains (broadcast, reduce) have one block, all-reduce and
+// reduce-scatter start with the chunk of the rank before.
+__device__ __forceinline__ uint32_t first_chunk(int kind, uint32_t rank, uint32_t R) {
+  if (kind == KIND_AG) return rank;
+  if (kind == KIND_BC || kind == KIND_RD || R == 1) return 0u;
+  return (rank + R - 1) % R;
+}
+
+// The SQE of an invocation "cooked" for one workgroup: every address a primitive needs resolved
+// once, so that a context load is a plain copy (Sec. 4.2 (4)).  vch: channel of the collective
+// that this workgroup serves.
+__device__ __forceinline__ DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool, uint32_t rank, uint32_t R, uint32_t vch) {
+  DfxCooked k;
+  k.sendbuf = q.sendbuf; k.recvbuf = q.recvbuf; k.count = q.count;
+  k.block_elems = q.block_elems; k.part_elems = q.part_elems;
+  uint8_t* conn = pool + q.conn_off;   // flags first, then slots
+  const uint32_t e_out = rank, e_in = (rank + R - 1) % R;
+  const size_t fo = (size_t)e_out * q.nchan + vch, fi = (size_t)e_in * q.nchan + vch;
+  uint8_t* slots = conn + (size_t)R * q.nchan * DFX_FLAG_STRIDE;
+  k.flags_out = (uint64_t)(conn + fo * DFX_FLAG_STRIDE);
+  k.flags_in = (uint64_t)(conn + fi * DFX_FLAG_STRIDE);
+  k.fifo_out = (uint64_t)(slots + fo * q.nslots * q.slot_bytes);
+  k.fifo_in = (uint64_t)(slots + fi * q.nslots * q.slot_bytes);
+  k.slice_elems = q.slice_elems; k.rounds = q.rounds; k.seq = q.seq;
+  k.nprim = (uint16_t)q.nprim; k.nchan = q.nchan;
+  k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = (uint8_t)(q.dtype | (q.op << 4));
+  // place in the chain: broadcast starts at the root, reduce at the rank after it
+  const uint32_t bpos = (rank + 2 * R - q.root - (q.kind == KIND_RD ? 1u : 0u)) % R;
+  k.bc_pos = bpos == 0 ? 0 : (bpos == R - 1 ? 2 : 1);
+  k.priority = q.priority; k.vch = (uint16_t)vch;
+  return k;
+}
+
+// Where slice g of ring chunk cidx lies for the workgroup that holds context S: element offsets
+// in the send and the recv buffer and the slice's length in bytes (clipped to the chunk's and the
+// channel's true length: the last ones may be short or empty).
+struct SliceGeom { u64 soff, doff; uint32_t bytes, eb; };
+__device__ __forceinline__ SliceGeom slice_geometry(const DfxCooked& S, uint32_t R, uint32_t g, uint32_t cidx) {
+  const int kind = S.kind, dt = S.dtype & 15;
+  SliceGeom o;
+  o.eb = (dt == DT_F32 || dt == DT_I32) ? 4u : 2u;
+  const uint32_t slice_elems = S.slice_elems, vch = S.vch;
+  const u64 count = S.count, block_elems = S.block_elems, part_elems = S.part_elems;
+  const bool ring_chunks = (kind == KIND_AR && R > 1);
+  u64 blen = count;
+  if (ring_chunks) {
+    const u64 start = (u64)cidx * block_elems;
+    blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
+  }
+  u64 lo = (u64)vch * part_elems + (u64)g * slice_elems;
+  u64 hi = lo + slice_elems;
+  const u64 pend = (u64)(vch + 1) * part_elems;
+  if (hi > pend) hi = pend;
+  if (lo > blen) lo = blen;
+  if (hi > blen) hi = blen;
+  o.bytes = (uint32_t)(hi - lo) * o.eb;
+  o.soff = lo; o.doff = lo;
+  if (ring_chunks) { o.soff += (u64)cidx * block_elems; o.doff = o.soff; }
+  else if (kind == KIND_RS) o.soff += (u64)cidx * count;
+  else if (kind == KIND_AG) o.doff += (u64)cidx * count;
+  return o;
+}
+
 }  // namespace
 
 // Structure of a workgroup: wave 0 is the SCHEDULER, waves 1..4 are the MOVERS.
@@ -585,12 +638,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       if (a.trace_on > 1 && first_wave) t0 = wall_clock64();
       // fenced mode: every wave invalidates before its own loads of the slot (the poll was the scheduler's)
       if (!coh && j.fin && j.bytes) fence_acquire_agent();
-#ifdef DFX_NO_FENCED
-      run_prim<AUX_DEVICE, DFX_MOVERS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
-#else
       if (coh) run_prim<AUX_DEVICE, DFX_MOVERS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
       else run_prim<AUX_CACHED, DFX_MOVERS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
-#endif
       // this wave's stores (and loads) have been performed before it counts itself done
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __builtin_amdgcn_s_waitcnt(0);
@@ -627,8 +676,6 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
     // =====================================================================================
     // scheduler wave
     // =====================================================================================
-    // start values of the ring-chunk index of a fresh sequence (see DfxDyn.cidx)
-    const uint32_t cidx0_reduce = (rank + a.R - 1) % a.R;   // all-reduce / reduce-scatter: chunk rank-1
     u64 last_act = wall_clock64();
     bool acted = true, voted = false;
     uint32_t iter = 0, idle = 0, burst = 0;
@@ -860,28 +907,11 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
               if (mine) {
                 // cook the static context of this invocation into the context buffer (addresses
                 // resolved once, here); restart the sequence, keep the monotone connector counters
-                DfxCooked k;
-                k.sendbuf = q.sendbuf; k.recvbuf = q.recvbuf; k.count = q.count;
-                k.block_elems = q.block_elems; k.part_elems = q.part_elems;
-                uint8_t* conn = a.pool + q.conn_off;   // flags first, then slots
-                const uint32_t e_out = rank, e_in = (rank + a.R - 1) % a.R;
-                const size_t fo = (size_t)e_out * q.nchan + my_vch, fi = (size_t)e_in * q.nchan + my_vch;
-                uint8_t* slots = conn + (size_t)a.R * q.nchan * DFX_FLAG_STRIDE;
-                k.flags_out = (uint64_t)(conn + fo * DFX_FLAG_STRIDE);
-                k.flags_in = (uint64_t)(conn + fi * DFX_FLAG_STRIDE);
-                k.fifo_out = (uint64_t)(slots + fo * q.nslots * q.slot_bytes);
-                k.fifo_in = (uint64_t)(slots + fi * q.nslots * q.slot_bytes);
-                k.slice_elems = q.slice_elems; k.rounds = q.rounds; k.seq = q.seq;
-                k.nprim = (uint16_t)q.nprim; k.nchan = q.nchan;
-                k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = (uint8_t)(q.dtype | (q.op << 4));
-                // place in the chain: broadcast starts at the root, reduce at the rank after it
-                const uint32_t bpos = (rank + 2 * a.R - q.root - (q.kind == KIND_RD ? 1u : 0u)) % a.R;
-                k.bc_pos = bpos == 0 ? 0 : (bpos == a.R - 1 ? 2 : 1);
-                k.priority = q.priority; k.vch = (uint16_t)my_vch;
+                const DfxCooked k = cook_sqe(q, a.pool, rank, a.R, my_vch);
                 myctx[c_id].st = k;
                 DfxDyn* dy = &myctx[c_id].dyn;
                 dy->round = 0; dy->prim = 0; dy->preempted = 0;
-                dy->cidx = (q.kind == KIND_AG) ? rank : ((q.kind == KIND_BC || q.kind == KIND_RD || a.R == 1) ? 0u : cidx0_reduce);
+                dy->cidx = first_chunk(q.kind, rank, a.R);
                 if (sh.slot_tag[c_id % DFX_CTX_SLOTS] == c_id) sh.slot_tag[c_id % DFX_CTX_SLOTS] = 0xffffffffu;
               }
               // every workgroup of the rank reads every SQE; the last reader frees the slot (Sec. 5)
@@ -1062,29 +1092,12 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       if (lane == 0 && q.recv) seen_cnt = ld_agent64(tail_in);
       if (lane == 1 && q.send) seen_cnt = ld_agent64(tail_out + 8);
 
-      // ---- slice geometry (elements relative to the block, clipped to the block's true length)
+      // ---- slice geometry and the job's four pointers
       const int kind = S.kind, dtype = S.dtype;   // dtype: element type | reducing function << 4
-      const uint32_t eb = ((dtype & 15) == DT_F32 || (dtype & 15) == DT_I32) ? 4u : 2u;
-      const uint32_t slice_elems = S.slice_elems, vch = S.vch;
-      const u64 count = S.count, block_elems = S.block_elems, part_elems = S.part_elems;
-      const bool ring_chunks = (kind == KIND_AR && a.R > 1);
-      u64 blen = count;
-      if (ring_chunks) {
-        const u64 start = (u64)cidx * block_elems;
-        blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
-      }
-      u64 lo = (u64)vch * part_elems + (u64)g * slice_elems;
-      u64 hi = lo + slice_elems;
-      const u64 pend = (u64)(vch + 1) * part_elems;
-      if (hi > pend) hi = pend;
-      if (lo > blen) lo = blen;
-      if (hi > blen) hi = blen;
-      const uint32_t bytes = (uint32_t)(hi - lo) * eb;
-      u64 soff = lo, doff = lo;   // element offsets in the send / recv buffer
-      if (ring_chunks) { soff += (u64)cidx * block_elems; doff = soff; }
-      else if (kind == KIND_RS) soff += (u64)cidx * count;
-      else if (kind == KIND_AG) doff += (u64)cidx * count;
-      const size_t slot_bytes = (size_t)slice_elems * eb;
+      const SliceGeom geo = slice_geometry(S, a.R, g, cidx);
+      const uint32_t eb = geo.eb, bytes = geo.bytes;
+      const u64 soff = geo.soff, doff = geo.doff;
+      const size_t slot_bytes = (size_t)S.slice_elems * eb;
       const void* jfin = q.recv ? (const void*)((const uint8_t*)S.fifo_in + (size_t)(recvd & (K - 1)) * slot_bytes) : nullptr;
       void* jfout = q.send ? (void*)((uint8_t*)S.fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
       const char* jsb = q.from_send ? (const char*)S.sendbuf + soff * eb : nullptr;
@@ -1104,7 +1117,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           cidx_next = (cidx == 0) ? a.R - 1 : cidx - 1;
           if (++p_next == S.nprim) {
             p_next = 0; g_next += W;
-            cidx_next = (kind == KIND_AG) ? rank : ((kind == KIND_BC || kind == KIND_RD || a.R == 1) ? 0u : cidx0_reduce);
+            cidx_next = first_chunk(kind, rank, a.R);
           }
           if (kind == KIND_BC || kind == KIND_RD) cidx_next = 0;
         }
