@@ -210,6 +210,43 @@ def size_sweep(iters: int = 10):
     return rows
 
 
+def kinds_sweep(nbytes: int = 256 << 20, iters: int = 8):
+    """Every collective kind at `nbytes` of largest per-rank buffer (fp32, sum, root 3 for the rooted
+    ones) inside one resident daemon: time and algorithmic HBM rate.  Algorithmic bytes per kind as
+    for the all-reduce: reduce-scatter / all-gather (3R-1) x block per rank, broadcast and reduce
+    (3R-2) x message over the chain."""
+    import torch
+    import paper_2303_06324_amd as dfx
+    from tests import gpu_harness as gh
+    n = nbytes // 4
+    a = [torch.randn(n, device="cuda") for _ in range(R)]
+    b = [torch.empty(n, device="cuda") for _ in range(R)]
+    torch.cuda.synchronize()
+    cases = [("all-reduce", dfx.ALLREDUCE, n, algorithmic_bytes(nbytes, R)),
+             ("all-gather", dfx.ALLGATHER, n // R, (3 * R - 1) * (nbytes // R) * R),
+             ("reduce-scatter", dfx.REDUCESCATTER, n // R, (3 * R - 1) * (nbytes // R) * R),
+             ("broadcast", dfx.BROADCAST, n, (3 * R - 2) * nbytes),
+             ("reduce", dfx.REDUCE, n, (3 * R - 2) * nbytes)]
+    rows = []
+    ctx = dfx.Context(R, gh.make_config(quit_idle_us=0))
+    try:
+        ptrs = ctx.make_all([t.data_ptr() for t in a], [t.data_ptr() for t in b])
+        for i, (name, kind, count, alg) in enumerate(cases):
+            ctx.prepare(i, kind, count, dfx.F32, dfx.SUM, 3 if kind in (dfx.BROADCAST, dfx.REDUCE) else 0)
+            best = 1e9
+            for _ in range(iters + 2):
+                t0 = time.perf_counter()
+                assert ctx.submit_all(i, ptrs) == dfx.OK
+                assert ctx.wait_all(30.0) == dfx.OK
+                best = min(best, time.perf_counter() - t0)
+            rows.append({"kind": name, "us": round(best * 1e6, 1), "algorithmic_GB": round(alg / 1e9, 2),
+                         "hbm_frac": round(alg / best / 1e9 / HBM_PEAK_GBS, 4)})
+        ctx.stop()
+    finally:
+        ctx.finalize()
+    return rows
+
+
 def spin_sweep():
     """Overhead against the spin threshold (the paper's Eq. 1-2: T = t[spin] + t[switch] + t[q_len],
     expected U-shaped in N_spin): a FIXED threshold N for every position and no boost (the naive
@@ -314,7 +351,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="add the 8 KiB .. 256 MiB size sweep to the JSON line")
     ap.add_argument("--spin-sweep", action="store_true", help="add the fixed-spin-threshold sweep to the JSON line")
     ap.add_argument("--studies", action="store_true",
-                    help="add the CQ-variant and ordering-policy comparisons to the JSON line")
+                    help="add the CQ-variant and ordering-policy comparisons and every collective kind at 256 MiB to the JSON line")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="after the steps, run one plain copy kernel of this many MiB (untimed): its known "
                          "traffic calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters")
@@ -409,6 +446,7 @@ def main():
         out["spin_sweep"] = spin_sweep()
     if args.studies:
         out["studies"] = studies()
+        out["kinds_256MiB"] = kinds_sweep()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_mib << 20)
     print(json.dumps(out), flush=True)

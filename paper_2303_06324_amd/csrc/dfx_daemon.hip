@@ -592,8 +592,9 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   const bool sched = tid < 64;       // the scheduler wave
   const uint32_t wg = blockIdx.x;
   uint32_t rank, ch;
-  if (a.wg_map == 0) { rank = wg % a.R; ch = wg / a.R; }
-  else { rank = wg / a.cmax; ch = wg % a.cmax; }
+  // Workgroups go to the XCDs round-robin (workgroup w runs on XCD w mod 8).
+  if (a.wg_map == 0) { rank = wg % a.R; ch = wg / a.R; }       // a vrank per XCD (R = 8)
+  else { rank = wg / a.cmax; ch = wg % a.cmax; }               // a channel's whole ring per XCD
   const uint32_t D = a.sq_depth;
   const bool coh = a.fifo_coherent != 0;
 
