@@ -66,6 +66,7 @@ struct dfx_ctx {
 
   // host-visible memory
   void* qmem_sq = nullptr;           // SQ ring + host_ctl (pinned host or fine-grained device)
+  size_t qmem_sq_bytes = 0;
   void* qmem_cq = nullptr;           // CQ slot arrays (pinned host)
   DfxSqSlot* sq = nullptr;
   uint32_t* host_ctl = nullptr;
@@ -119,8 +120,31 @@ inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 inline uint64_t round_up(uint64_t a, uint64_t b) { return ceil_div(a, b) * b; }
 inline bool is_pow2(uint32_t x) { return x && !(x & (x - 1)); }
 
+// Fine-grained device memory that a kernel has read is not given back to the driver while the
+// process lives (memory handed out after such a free has been seen to hold wrong values): a
+// context's SQ goes to this list instead and the next context of the same size takes it over.
+struct ParkedSq { int device; size_t bytes; void* ptr; };
+std::mutex g_parked_mu;
+std::vector<ParkedSq> g_parked_sq;
+
+void* take_parked_sq(int device, size_t bytes) {
+  std::lock_guard<std::mutex> lk(g_parked_mu);
+  for (size_t i = 0; i < g_parked_sq.size(); ++i)
+    if (g_parked_sq[i].device == device && g_parked_sq[i].bytes == bytes) {
+      void* p = g_parked_sq[i].ptr;
+      g_parked_sq.erase(g_parked_sq.begin() + (long)i);
+      return p;
+    }
+  return nullptr;
+}
+
 void free_all(dfx_ctx* c) {
-  if (c->qmem_sq) { if (c->sq_device) (void)hipFree(c->qmem_sq); else (void)hipHostFree(c->qmem_sq); }
+  if (c->qmem_sq) {
+    if (c->sq_device) {
+      std::lock_guard<std::mutex> lk(g_parked_mu);
+      g_parked_sq.push_back({c->device, c->qmem_sq_bytes, c->qmem_sq});
+    } else (void)hipHostFree(c->qmem_sq);
+  }
   if (c->qmem_cq) (void)hipHostFree(c->qmem_cq);
   if (c->pinned_tmp) (void)hipHostFree(c->pinned_tmp);
   void* dev[] = {c->sq_readers, c->done_cnt, c->dev_ctl, c->pool, c->ctxbuf, c->wgstate, c->taskq_store, c->trace};
@@ -420,7 +444,9 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   const size_t cq_ctl_bytes = round_up(R * DFX_CQ_CTL_WORDS * sizeof(uint64_t), 64);
   const size_t cq_bytes = cq_slots_bytes + cq_ctl_bytes + R * cfg.sq_depth * sizeof(uint32_t);
   if (c->sq_device) {
-    INITCHK(hipExtMallocWithFlags(&c->qmem_sq, sq_bytes, hipDeviceMallocFinegrained));
+    c->qmem_sq_bytes = sq_bytes;
+    c->qmem_sq = take_parked_sq(c->device, sq_bytes);
+    if (!c->qmem_sq) INITCHK(hipExtMallocWithFlags(&c->qmem_sq, sq_bytes, hipDeviceMallocFinegrained));
     INITCHK(hipMemset(c->qmem_sq, 0, sq_bytes));
   } else {
     INITCHK(hipHostMalloc(&c->qmem_sq, sq_bytes, hipHostMallocMapped | hipHostMallocCoherent));
