@@ -278,3 +278,13 @@ def test_in_place_allreduce(dtype, count):
         ctx.finalize()
     for b in bufs:
         assert np.array_equal(b.cpu().numpy(), want.view(np.uint8))
+
+
+@pytest.mark.parametrize("knobs", [dict(focus_bytes=0), dict(focus_bytes=16 << 10), dict(window=1), dict(window=4, nslots=8),
+                                   dict(sq_eager=0), dict(wg_map=1), dict(focus_bytes=0, scan_min=0, sq_eager=0, window=1)])
+def test_scheduling_knobs_do_not_change_the_values(knobs):
+    """The scheduler's options (focused passes and their byte budget, slice windows, eager SQ probing, the
+    workgroup map, Alg. 1 as written) change who runs when, never what is computed: the gradient buckets
+    and a random mix in disordered submission stay bit-exact."""
+    _run(wi.config3(n_buckets=10, bucket_bytes=3 << 20, seed=51), **knobs)
+    _run(_mixed_workload(11, n_colls=24), mode="threads", timeout_s=60.0, **knobs)
