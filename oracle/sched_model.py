@@ -50,6 +50,11 @@ Two variations of Alg. 1 can be switched on, to ask whether they keep its livene
     queue at once; its CQE is written when that slice has been moved.
   * `scan = True`: a pass starts by evaluating the wait conditions of every queue entry and
     visits only the entries found runnable, each with the minimum threshold.
+  * `direct = True`: the gather steps of an all-reduce go without FIFO slots.  A rank writes a
+    finished chunk to its recv buffer only and notifies the next rank (the connector's counter is
+    raised, no slot is needed, so no wait for space); the next rank copies it out of that recv
+    buffer; a last step (drain) waits until the next rank has consumed everything, because
+    the recv buffer belongs to the caller again once the completion is posted.
   * `focus = n > 0` (with scan): the runnable entries are visited furthest-along first
     (most primitives done; ties in queue order), and once n slices have been taken in the
     pass it ends with the entry in hand: every rank ranks the collectives alike, so the
@@ -68,16 +73,23 @@ from . import ring_data as rd
 AR, AG, RS, BC = 0, 1, 2, 3
 INF = 1 << 60
 
-# primitive name -> (needs recv, needs send)
+# primitive name -> (needs recv, send side), send side: 0 none, 1 waits for a free slot and fills it,
+# 2 notify (the result stays in the rank's recv buffer, the counter is raised without a slot),
+# 3 drain (no data: waits until the next rank has consumed everything sent or notified so far)
 PRIMS = {
-    "send": (False, True),
-    "copy_send": (False, True),
-    "copy": (False, False),
-    "recv_reduce_send": (True, True),
-    "recv_reduce_copy_send": (True, True),
-    "recv_reduce_copy": (True, False),
-    "recv_copy_send": (True, True),
-    "recv_copy": (True, False),
+    "send": (False, 1),
+    "copy_send": (False, 1),
+    "copy": (False, 0),
+    "recv_reduce_send": (True, 1),
+    "recv_reduce_copy_send": (True, 1),
+    "recv_reduce_copy": (True, 0),
+    "recv_copy_send": (True, 1),
+    "recv_copy": (True, 0),
+    # direct gather steps of an all-reduce (Policy.direct)
+    "recv_reduce_copy_notify": (True, 2),
+    "direct_copy_notify": (True, 2),
+    "direct_copy": (True, 0),
+    "drain": (False, 3),
 }
 
 
@@ -96,6 +108,7 @@ class Policy:
     lookahead: int = 0            # 0: a slice moves at its successful poll; n: up to n claimed slices per rank, moved by a mover actor
     scan: bool = False            # a pass visits only the entries whose wait conditions hold at its start
     focus: int = 0                # with scan: furthest-along entries first, and the pass ends after this many slices
+    direct: bool = False          # all-reduce: the gather steps read the previous rank's recv buffer (notify / drain)
 
 
 @dataclass
@@ -107,7 +120,7 @@ class Coll:
 
 
 def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
-            recv_blocks: List[Tuple[int, int]]):
+            recv_blocks: List[Tuple[int, int]], direct: bool = False):
     """Per-rank primitive sequence: list of (name, send-buffer block, recv-buffer block).
     `blocks` / `recv_blocks` are the element ranges of ring chunk j in the send / recv buffer."""
     none = None
@@ -118,6 +131,15 @@ def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
     if kind == AR:
         p = [("send", b(r - 1), none)]
         p += [("recv_reduce_send", b(r - 1 - s), none) for s in range(1, R - 1)]
+        if direct:
+            # a finished chunk goes to the recv buffer only; the next rank reads it there; the last
+            # step waits until the next rank has read them all (the recv buffer is the caller's again
+            # once the completion is posted)
+            p += [("recv_reduce_copy_notify", b(r), d(r))]
+            p += [("direct_copy_notify", none, d(r - j)) for j in range(1, R - 1)]
+            p += [("direct_copy", none, d(r + 1))]
+            p += [("drain", none, none)]
+            return p
         p += [("recv_reduce_copy_send", b(r), d(r))]
         p += [("recv_copy_send", none, d(r - j)) for j in range(1, R - 1)]
         p += [("recv_copy", none, d(r + 1))]
@@ -160,7 +182,7 @@ class Fifo:
 
     def __init__(self, K):
         self.K, self.head, self.tail = K, 0, 0
-        self.slots = [None] * K
+        self.slots = {}            # position -> entry (a notify is not bounded by K, so not a ring of K)
 
     def readable(self):
         return self.tail > self.head
@@ -168,14 +190,14 @@ class Fifo:
     def writable(self):
         return self.tail - self.head < self.K
 
-    def push(self, x):
-        assert self.writable()
-        self.slots[self.tail % self.K] = x
+    def push(self, x, need_slot=True):
+        assert self.writable() or not need_slot
+        self.slots[self.tail] = x
         self.tail += 1
 
     def pop(self):
         assert self.readable()
-        x = self.slots[self.head % self.K]
+        x = self.slots.pop(self.head)
         self.head += 1
         return x
 
@@ -260,8 +282,9 @@ class Daemon:
         fin = S.fifo[coll][(self.r - 1) % S.R]
         fout = S.fifo[coll][self.r]
         pops = sum(1 for j in self.jobs if j[0] == coll and PRIMS[j[3]][0])
-        pushes = sum(1 for j in self.jobs if j[0] == coll and PRIMS[j[3]][1])
-        return fin.tail - fin.head - pops > 0, fout.tail + pushes - fout.head < fout.K
+        pushes = sum(1 for j in self.jobs if j[0] == coll and PRIMS[j[3]][1] in (1, 2))
+        return (fin.tail - fin.head - pops > 0, fout.tail + pushes - fout.head < fout.K,
+                fout.tail + pushes - fout.head == 0)
 
     def _done(self, coll):
         """Primitives of the invocation this rank has taken so far."""
@@ -279,9 +302,9 @@ class Daemon:
 
     def _runnable(self, coll):
         g, p = self.active if self.loaded == coll else self.saved[coll]
-        need_recv, need_send = PRIMS[self.S.progs[coll][self.r][p][0]]
-        rd_ok, wr_ok = self._conds(coll, p)
-        return (not need_recv or rd_ok) and (not need_send or wr_ok)
+        need_recv, send_side = PRIMS[self.S.progs[coll][self.r][p][0]]
+        rd_ok, wr_ok, drained = self._conds(coll, p)
+        return (not need_recv or rd_ok) and (send_side != 1 or wr_ok) and (send_side != 3 or drained)
 
     def mover_tick(self) -> bool:
         """Move the oldest claimed slice (lookahead mode): data, shared counters, and the CQE if it was the last."""
@@ -352,12 +375,12 @@ class Daemon:
         rounds, prog = S.rounds[coll], S.progs[coll][self.r]
         g, p = self.active
         name, sblk, dblk = prog[p]
-        need_recv, need_send = PRIMS[name]
+        need_recv, send_side = PRIMS[name]
         fin = S.fifo[coll][(self.r - 1) % S.R]
         fout = S.fifo[coll][self.r]
         self.stats.polls += 1
-        rd_ok, wr_ok = self._conds(coll, p)
-        ok = (not need_recv or rd_ok) and (not need_send or wr_ok)
+        rd_ok, wr_ok, drained = self._conds(coll, p)
+        ok = (not need_recv or rd_ok) and (send_side != 1 or wr_ok) and (send_side != 3 or drained)
         if not ok:
             if self.thr >= INF:
                 return False               # spins forever: no state change
@@ -417,7 +440,7 @@ class System:
         self.progs, self.rounds, self.fifo = [], [], []
         for c in colls:
             sb, db, blen = layout(c, R)
-            self.progs.append([program(c.kind, R, r, c.root, sb, db) for r in range(R)])
+            self.progs.append([program(c.kind, R, r, c.root, sb, db, policy.direct) for r in range(R)])
             self.rounds.append(max(1, -(-blen // policy.slice_elems)))
             self.fifo.append([Fifo(policy.K) for _ in range(R)])
         self.daemons = [Daemon(self, r) for r in range(R)]
@@ -454,6 +477,8 @@ class System:
         c = self.colls[ci]
         tag_out = (g, p)
         x = None
+        if name == "drain":
+            return
         if PRIMS[name][0]:
             tag, x = fin.pop()
             # the sender's primitive index of this hop is p-1 in every ring sequence here,
@@ -464,6 +489,9 @@ class System:
             ss, ds = self._slice(sblk, g), self._slice(dblk, g)
             src = self.sends[ci][r]
             dst = self.recvs[ci][r]
+            if isinstance(x, tuple):
+                # a notified chunk: read now from the recv buffer of the rank that holds it
+                x = self.recvs[ci][x[1]][ds[0]:ds[1]].copy()
             if name in ("send", "copy_send", "copy"):
                 y = src[ss[0]:ss[1]].copy()
             elif name.startswith("recv_reduce"):
@@ -474,8 +502,10 @@ class System:
                 dst[ds[0]:ds[1]] = y
         else:
             y = None
-        if PRIMS[name][1]:
+        if PRIMS[name][1] == 1:
             fout.push((tag_out, y))
+        elif PRIMS[name][1] == 2:
+            fout.push((tag_out, ("direct", r) if self.with_data else None), need_slot=False)
 
     # -- global predicates
     def done(self):
@@ -508,7 +538,7 @@ class System:
             row = []
             for f in fl:
                 g = Fifo(f.K)
-                g.head, g.tail, g.slots = f.head, f.tail, list(f.slots)
+                g.head, g.tail, g.slots = f.head, f.tail, dict(f.slots)
                 row.append(g)
             T.fifo.append(row)
         T.daemons = []

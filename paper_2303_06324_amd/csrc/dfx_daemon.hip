@@ -383,7 +383,8 @@ __device__ __forceinline__ void run_prim(int dtype, const void* fin, const char*
                 else move_dispatch<AUX, AUX, true, true, true, false, NTH>(dtype, fin, sb, rb, fout, bytes, tid); }      // recv-reduce-copy
       else move_dispatch<AUX, AUX, true, true, false, true, NTH>(dtype, fin, sb, rb, fout, bytes, tid);                  // recv-reduce-send
     } else {
-      if (fout) move_dispatch<AUX, AUX, true, false, true, true, NTH>(dtype, fin, sb, rb, fout, bytes, tid);             // recv-copy-send
+      if (!rb) move_dispatch<AUX, AUX, true, false, false, true, NTH>(dtype, fin, sb, rb, fout, bytes, tid);             // direct recv-copy (coherent destination)
+      else if (fout) move_dispatch<AUX, AUX, true, false, true, true, NTH>(dtype, fin, sb, rb, fout, bytes, tid);        // recv-copy-send
       else move_dispatch<AUX, AUX, true, false, true, false, NTH>(dtype, fin, sb, rb, fout, bytes, tid);                 // recv-copy
     }
   } else {
@@ -432,13 +433,30 @@ struct Shared {
 // primitive descriptor for (kind, position p in the sequence); the ring-chunk index travels in
 // the dynamic context and is stepped by next_cidx, so nothing here divides
 struct Prim {
-  bool recv, send;         // uses recv / send connector
+  bool recv, send;         // uses recv / send connector (send: waits for a free slot and fills it)
   bool from_send, to_recv; // touches the send buffer / recv buffer
+  // Direct gather steps of an all-reduce: every rank's buffers lie in the same HBM, so the copy
+  // steps need no second copy through a FIFO slot.  notify: the result goes to the own recv buffer
+  // with device-coherent stores and the send connector's counter is raised without a slot being
+  // filled; din: the input is read from the previous rank's recv buffer instead of a slot;
+  // drain: no data, the wait ends when the next rank has consumed everything notified so far
+  // (the recv buffer is the caller's again once the completion is posted).
+  bool notify, din, drain;
 };
 
-__device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos, uint32_t p) {
+__device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos, uint32_t p, bool direct) {
   Prim q;
+  q.notify = q.din = q.drain = false;
   if (R == 1) { q.recv = q.send = false; q.from_send = q.to_recv = true; return q; }   // copy
+  if (kind == KIND_AR && direct) {
+    const uint32_t last_reduce = R - 1;
+    q.recv = p > 0; q.send = p < last_reduce; q.from_send = p <= last_reduce; q.to_recv = p >= last_reduce;
+    if (p == last_reduce) q.notify = true;                                            // recv-reduce-copy, notify
+    else if (p > last_reduce && p < 2u * R - 2) { q.din = true; q.notify = true; }    // direct recv-copy, notify
+    else if (p == 2u * R - 2) q.din = true;                                           // direct recv-copy
+    else if (p == 2u * R - 1) { q.recv = false; q.to_recv = false; q.drain = true; }  // drain
+    return q;
+  }
   if (kind == KIND_AR || kind == KIND_RS) {
     const uint32_t last_reduce = R - 1;
     if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = false; }                         // send
@@ -527,6 +545,7 @@ __device__ __forceinline__ DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool,
   // place in the chain: broadcast starts at the root, reduce at the rank after it
   const uint32_t bpos = (rank + 2 * R - q.root - (q.kind == KIND_RD ? 1u : 0u)) % R;
   k.bc_pos = bpos == 0 ? 0 : (bpos == R - 1 ? 2 : 1);
+  if (q.flags & DFX_SQE_DIRECT) k.bc_pos |= DFX_CTX_DIRECT;   // an all-reduce with direct gather steps
   k.priority = q.priority; k.vch = (uint16_t)vch;
   return k;
 }
@@ -652,7 +671,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         last = (old + 1 == DFX_MOVERS / 64) ? 1u : 0u;
         if (first_wave && a.trace_on > 1) {
           bump(sh.stat, ST_T_DATA, t1 - t0);
-          if (a.trace_on == 3 && trace) trace_put(trace, &sh.trace_n, timeline_sample(t0, t1, j.coll, j.prim));
+          if (a.trace_on == 3 && trace && (j.fin || j.sb)) trace_put(trace, &sh.trace_n, timeline_sample(t0, t1, j.coll, j.prim));   // not the drain step: it moves nothing
         }
       }
       if (bcast0(last)) {
@@ -696,6 +715,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
     uint32_t g = 0, p = 0, cidx = 0;
     u64 sent = 0, recvd = 0, thr = 0;
     bool progressed = false;
+    u64 prev_recv = 0;                  // the previous rank's recv buffer (direct gather steps), 0 = not read yet
     uint32_t posted = 0, retired = 0;   // jobs handed to the movers / jobs whose bookkeeping is done
 
     // ---- completion of this workgroup's share of an invocation (Sec. 5): completion counter,
@@ -910,6 +930,12 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 // resolved once, here); restart the sequence, keep the monotone connector counters
                 const DfxCooked k = cook_sqe(q, a.pool, rank, a.R, my_vch);
                 myctx[c_id].st = k;
+                // direct gather steps: the next rank reads this rank's recv buffer; its address and
+                // the invocation it belongs to go into the send connector's flag line (one 16-byte
+                // device-coherent store, complete before any job of the invocation is posted)
+                if (q.flags & DFX_SQE_DIRECT)
+                  Slot<AUX_DEVICE>((const void*)k.flags_out, DFX_FLAG_STRIDE)
+                      .st16(DFX_DIRECT_OFF, uint4{(uint32_t)q.recvbuf, (uint32_t)(q.recvbuf >> 32), q.seq + 1u, 0u});
                 DfxDyn* dy = &myctx[c_id].dyn;
                 dy->round = 0; dy->prim = 0; dy->preempted = 0;
                 dy->cidx = first_chunk(q.kind, rank, a.R);
@@ -925,6 +951,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 __hip_atomic_store(&a.sq_freed[sq_at], (uint32_t)((ri + lane) >> a.sq_shift) + 1u, __ATOMIC_RELEASE, SCOPE_SYSTEM);
               }
             }
+            // (contexts and published buffer addresses are in memory before anything is built on them)
+            __builtin_amdgcn_s_waitcnt(0);
             // the entries that are this workgroup's join the task queue in SQ order
             const u64 mine_mask = __ballot(mine);
             if (mine) {
@@ -995,12 +1023,13 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 const uint4 ge = e[5];    // bytes 80..95: seq | nprim,nchan | nslots,kind,dtype,bc_pos | priority,vch
                 const uint4 d0 = e[6];    // dyn: round | prim | sent
                 const uint4 d1 = e[7];    // dyn: recvd | preempted | cidx
-                const Prim pq = make_prim((int)((ge.z >> 8) & 0xffu), a.R, ge.z >> 24, d0.y);
+                const Prim pq = make_prim((int)((ge.z >> 8) & 0xffu), a.R, (ge.z >> 24) & 3u, d0.y, ((ge.z >> 24) & DFX_CTX_DIRECT) != 0);
                 const u64 f_out = ((u64)fl.w << 32) | fl.z, f_in = ((u64)fi.y << 32) | fi.x;
                 const u64 e_sent = ((u64)d0.w << 32) | d0.z, e_recvd = ((u64)d1.y << 32) | d1.x;
                 bool okr = true, oks = true;
                 if (pq.recv) okr = ld_agent64((const u64*)f_in) > e_recvd;
                 if (pq.send) oks = (e_sent - ld_agent64((const u64*)f_out + 8)) < (u64)(ge.z & 0xffu);
+                else if (pq.drain) oks = e_sent == ld_agent64((const u64*)f_out + 8);
                 rdy = okr && oks;
                 if (rdy) {
                   u64 done = (u64)d0.x * (ge.y & 0xffffu) + d0.y;
@@ -1060,12 +1089,13 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         thr = a.spin_init >> (pos < 31 ? pos : 31);
         if (thr < a.spin_min || scanned) thr = a.spin_min;
         progressed = false;
+        prev_recv = 0;
         have = true;
       }
 
       // ================= next primitive of the collective in hand =================
       const DfxCooked& S = sh.slot[sl].st;
-      const Prim q = make_prim((int)S.kind, a.R, S.bc_pos, p);
+      const Prim q = make_prim((int)S.kind, a.R, S.bc_pos & 3u, p, (S.bc_pos & DFX_CTX_DIRECT) != 0);
       u64* const tail_out = (u64*)S.flags_out;
       u64* const tail_in = (u64*)S.flags_in;
       const uint32_t K = S.nslots;
@@ -1091,7 +1121,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       // succeeds is followed by the job at once.
       u64 seen_cnt = 0;
       if (lane == 0 && q.recv) seen_cnt = ld_agent64(tail_in);
-      if (lane == 1 && q.send) seen_cnt = ld_agent64(tail_out + 8);
+      if (lane == 1 && (q.send || q.drain)) seen_cnt = ld_agent64(tail_out + 8);
 
       // ---- slice geometry and the job's four pointers
       const int kind = S.kind, dtype = S.dtype;   // dtype: element type | reducing function << 4
@@ -1103,6 +1133,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       void* jfout = q.send ? (void*)((uint8_t*)S.fifo_out + (size_t)(sent & (K - 1)) * slot_bytes) : nullptr;
       const char* jsb = q.from_send ? (const char*)S.sendbuf + soff * eb : nullptr;
       char* jrb = q.to_recv ? (char*)S.recvbuf + doff * eb : nullptr;
+      // a notified result goes to the recv buffer through the coherent path of a slot
+      if (q.notify) { jfout = jrb; jrb = nullptr; }
 
       // The position after this primitive.  Slices are taken in windows of W: primitive p of every
       // slice of the window, then primitive p+1 of every slice, ...  The neighbour does the same, so
@@ -1128,12 +1160,13 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
 
       // The movers may be busy with earlier slices meanwhile; finished ones are retired between polls.
       uint32_t res = W_OK;
-      if (q.recv || q.send) {
+      if (q.recv || q.send || q.drain) {
         u64 n = 0;
         for (;;) {
           bool ok = true;
           if (lane == 0 && q.recv) ok = seen_cnt > recvd;
           if (lane == 1 && q.send) ok = (sent - seen_cnt) < (u64)K;
+          if (lane == 1 && q.drain) ok = sent == seen_cnt;
           ++n;
           if (__ballot(!ok) == 0) break;
           retire_finished();
@@ -1157,7 +1190,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           }
           __builtin_amdgcn_s_sleep(1);
           if (lane == 0 && q.recv) seen_cnt = ld_agent64(tail_in);
-          if (lane == 1 && q.send) seen_cnt = ld_agent64(tail_out + 8);
+          if (lane == 1 && (q.send || q.drain)) seen_cnt = ld_agent64(tail_out + 8);
         }
         if (lane == 0) bump(sh.stat, ST_POLLS, n);
       }
@@ -1175,17 +1208,32 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           }
         }
         if (given_up) { stop = STOP_ABORT; have = false; continue; }
+        if (q.din) {
+          // The previous rank published its recv buffer for this invocation before it notified the
+          // first result (the counter just seen).  Read once per stay of the collective in hand.
+          if (prev_recv == 0) {
+            uint4 w = uint4{0, 0, 0, 0};
+            for (uint32_t tries = 0; tries < 1024u; ++tries) {
+              w = Slot<AUX_DEVICE>((const void*)tail_in, DFX_FLAG_STRIDE).ld16(DFX_DIRECT_OFF);
+              if (w.z == inv_seq + 1u) break;
+              __builtin_amdgcn_s_sleep(2);
+            }
+            if (w.z != inv_seq + 1u) { raise_error(a, 3u, wg); stop = STOP_ABORT; have = false; continue; }
+            prev_recv = ((u64)w.y << 32) | w.x;
+          }
+          jfin = (const void*)((const char*)prev_recv + doff * eb);
+        }
         // ---- post the slice (an empty one is only a handshake: the movers just raise the counters);
         // this claims the slots: the data follows, the counters after it
-        if (q.send) ++sent;
+        if (q.send || q.notify) ++sent;
         if (q.recv) ++recvd;
         if (lane == 0) {
           Job j;
           j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
-          j.bytes = bytes; j.dtype = dtype; j.coll = coll; j.prim = p;
+          j.bytes = q.drain ? 0u : bytes; j.dtype = dtype; j.coll = coll; j.prim = p;
           sh.job[posted & 1] = j;
           Flight f;
-          f.tail_out = q.send ? tail_out : nullptr; f.head_in = q.recv ? tail_in + 8 : nullptr;
+          f.tail_out = (q.send || q.notify) ? tail_out : nullptr; f.head_in = q.recv ? tail_in + 8 : nullptr;
           f.sent_new = sent; f.recvd_new = recvd;
           f.last = last ? 1u : 0u; f.coll = coll; f.seq = inv_seq; f.nchan = inv_nchan;
           sh.fl[posted & 1] = f;

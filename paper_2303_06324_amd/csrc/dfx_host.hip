@@ -365,6 +365,8 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->sq_eager = 1;
   cfg->window = 2;
   cfg->focus_bytes = 128u << 10;
+  cfg->direct = 1;
+  cfg->direct_min_bytes = 2u << 20;
   cfg->preempt = 1;
   cfg->watchdog_ms = 10000;
   cfg->quit_idle_us = 2000;
@@ -398,7 +400,7 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   if (cfg.slot_bytes < 16 || (cfg.slot_bytes & 15u)) return DFX_ERR_INVALID_ARG;
   if (cfg.chan_min_bytes < 16) return DFX_ERR_INVALID_ARG;
   if (cfg.spin_min < 1 || cfg.spin_init < 1 || cfg.spin_boost < 1 || cfg.spin_max < cfg.spin_min) return DFX_ERR_INVALID_ARG;
-  if (cfg.sq_in_device > 2 || cfg.wg_map > 1 || cfg.order_policy > 1) return DFX_ERR_INVALID_ARG;
+  if (cfg.sq_in_device > 2 || cfg.wg_map > 1 || cfg.order_policy > 1 || cfg.direct > 1) return DFX_ERR_INVALID_ARG;
   if (cfg.pool_bytes < (1u << 20)) return DFX_ERR_INVALID_ARG;
 
   dfx_ctx* c = new (std::nothrow) dfx_ctx();
@@ -535,7 +537,12 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
   t.kind = (uint8_t)kind; t.dtype = (uint8_t)dtype; t.op = (uint8_t)op; t.root = (uint8_t)(rooted ? root : 0);
   t.priority = (int16_t)priority;
   if (R == 1) t.nprim = 1;
-  else if (kind == DFX_ALLREDUCE) t.nprim = (uint32_t)(2 * R - 1);
+  else if (kind == DFX_ALLREDUCE) {
+    // direct gather steps (one more step: the drain) where the message is long enough to gain from them
+    const bool direct = c->cfg.direct && count * eb >= c->cfg.direct_min_bytes;
+    if (direct) t.flags |= DFX_SQE_DIRECT;
+    t.nprim = (uint32_t)(2 * R - 1) + (direct ? 1u : 0u);
+  }
   else if (rooted) t.nprim = 1;   // one primitive per slice, which one depends on the place in the chain
   else t.nprim = (uint32_t)R;
   c->pool_used += conn_bytes;

@@ -12,10 +12,13 @@
 #define DFX_CTX_SLOTS 4         // LDS active context slots, direct-mapped by coll_id (Sec. 5)
 #define DFX_TRACE_N 4096        // context-switch latency samples kept per workgroup
 #define DFX_FLAG_STRIDE 128     // bytes per (edge, channel) flag pair: tail at +0, head at +64
+#define DFX_DIRECT_OFF 16       // in the tail's line: the sender's recv buffer (8 bytes), invocation + 1 (4), 0 (4)
 #define DFX_NSTAT 24
 #define DFX_CQ_CTL_WORDS 24      // 64-bit words of ring bookkeeping per vrank: reserve at 0, tail at 8, head at 16
 
 #define DFX_SQE_EXIT 1u
+#define DFX_SQE_DIRECT 2u      // all-reduce whose gather steps read the previous rank's recv buffer
+#define DFX_CTX_DIRECT 0x80u   // the same, in the cooked context's bc_pos byte (bits 0-1: place in a chain)
 
 // Static context of one invocation on one rank: what the host writes into the SQ and what a
 // workgroup keeps in its context buffer (Sec. 4.2: buffer and connector addresses, rank count,

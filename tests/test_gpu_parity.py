@@ -281,10 +281,68 @@ def test_in_place_allreduce(dtype, count):
 
 
 @pytest.mark.parametrize("knobs", [dict(focus_bytes=0), dict(focus_bytes=16 << 10), dict(window=1), dict(window=4, nslots=8),
-                                   dict(sq_eager=0), dict(wg_map=1), dict(focus_bytes=0, scan_min=0, sq_eager=0, window=1)])
+                                   dict(sq_eager=0), dict(wg_map=1), dict(focus_bytes=0, scan_min=0, sq_eager=0, window=1),
+                                   dict(direct=0), dict(direct_min_bytes=0), dict(direct_min_bytes=0, wg_map=1, window=1)])
 def test_scheduling_knobs_do_not_change_the_values(knobs):
     """The scheduler's options (focused passes and their byte budget, slice windows, eager SQ probing, the
     workgroup map, Alg. 1 as written) change who runs when, never what is computed: the gradient buckets
     and a random mix in disordered submission stay bit-exact."""
     _run(wi.config3(n_buckets=10, bucket_bytes=3 << 20, seed=51), **knobs)
     _run(_mixed_workload(11, n_colls=24), mode="threads", timeout_s=60.0, **knobs)
+
+
+# ---------------------------------------------------------------- direct gather steps of the all-reduce
+DIRECT = dict(direct_min_bytes=0)     # every all-reduce, whatever its size, takes the direct gather steps
+
+
+@pytest.mark.parametrize("dtype,count", [(wi.F32, 1), (wi.F32, 70001), (wi.BF16, 300007), (wi.F16, 4099), (wi.I32, 1 << 20),
+                                         (wi.F32, 3 << 20)])
+def test_direct_allreduce_sizes_and_dtypes(dtype, count):
+    """The gather steps read the previous rank's recv buffer instead of a FIFO slot: same bits, for lengths
+    with ragged chunks, sub-vector tails, one slice and several windows."""
+    _run(_one(wi.AR, dtype, count, 8, seed=count), **DIRECT)
+
+
+@pytest.mark.parametrize("R", [2, 3, 5, 16])
+def test_direct_allreduce_rank_counts(R):
+    _run(_one(wi.AR, wi.F32, 100003, R, seed=R), max_channels=8, **DIRECT)
+    _run(_one(wi.AR, wi.BF16, 1 << 19, R, seed=R + 1, op=wi.MAX), max_channels=8, **DIRECT)
+
+
+def test_direct_allreduce_under_forced_preemption_and_disorder():
+    """Smallest thresholds, one shared queue, disordered submission: every late counter (the drain's
+    included) preempts, and the values stay those of the oracle."""
+    _run(wi.config3(n_buckets=8, bucket_bytes=1 << 20, seed=61), max_channels=2, chan_spread=0, scan_min=0,
+         spin_init=1, spin_min=1, spin_max=1, spin_boost=1, **DIRECT)
+    _run(_mixed_workload(13, n_colls=24), mode="threads", timeout_s=60.0, nslots=2, **DIRECT)
+
+
+def test_direct_allreduce_repeated_with_changing_buffers_and_in_place():
+    """The recv buffer's address travels through the connector with every invocation: alternating
+    buffer sets, then the same collective in place (recvbuf == sendbuf)."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    import torch
+    w = _one(wi.AR, wi.F32, 300000, 8, seed=81)
+    dws = [gh.DeviceWorkload(w), gh.DeviceWorkload(wi.Workload(w.name, 8, w.colls, w.orders, seed=82, cfg=50))]
+    ctx = dfx.Context(8, gh.make_config(**DIRECT))
+    try:
+        gh.prepare_all(ctx, w)
+        assert ctx.coll_info(0)["nprim"] == 16          # 2R-1 ring steps and the drain
+        for it in range(6):
+            dw = dws[it % 2]
+            dw.reset_recv()
+            gh.submit_round_robin(ctx, dw)
+            assert ctx.wait_all(20.0) == dfx.OK
+            _check(dw, dw.w, 0)
+        sends = wi.all_sends(w, 0)
+        want = rd.all_reduce_fold(sends, wi.F32)
+        bufs = [torch.from_numpy(s.view(np.uint8).copy()).cuda() for s in sends]
+        torch.cuda.synchronize()
+        ptrs = ctx.make_all([b.data_ptr() for b in bufs], [b.data_ptr() for b in bufs])
+        assert ctx.submit_all(0, ptrs) == dfx.OK
+        assert ctx.wait_all(20.0) == dfx.OK
+        for b in bufs:
+            assert np.array_equal(b.cpu().numpy(), want.view(np.uint8))
+    finally:
+        assert ctx.finalize() == dfx.OK

@@ -179,16 +179,19 @@ def test_batch_fetch_keeps_liveness_and_values(batch):
 
 # ---------------------------------------------------------------- claim-ahead and scan variations
 VARIANTS = [dict(lookahead=1), dict(lookahead=2), dict(scan=True), dict(lookahead=2, scan=True),
-            dict(scan=True, focus=1), dict(lookahead=2, scan=True, focus=2)]
+            dict(scan=True, focus=1), dict(lookahead=2, scan=True, focus=2),
+            dict(direct=True), dict(lookahead=2, scan=True, focus=1, direct=True)]
 
 
 @pytest.mark.parametrize("var", [dict(lookahead=2), dict(scan=True), dict(lookahead=2, scan=True),
-                                 dict(lookahead=2, scan=True, focus=1)])
+                                 dict(lookahead=2, scan=True, focus=1), dict(direct=True),
+                                 dict(lookahead=2, scan=True, direct=True)])
 @pytest.mark.parametrize("orders", [((0, 1), (1, 0)), ((0, 1), (0, 1))])
 def test_variations_exhaustive_interleavings_tiny(orders, var):
     """Claiming slices ahead of their movement (a mover actor raises the shared counters later),
     visiting only runnable entries, and visiting them furthest-along first in passes that end after a
-    fixed number of slices keep Alg. 1's liveness: in the circular-wait setting no reachable
+    fixed number of slices, and direct gather steps (notify without a slot, drain before completion)
+    keep Alg. 1's liveness: in the circular-wait setting no reachable
     state -- over all interleavings of daemons, movers and host submissions -- is a deadlock, and every
     one of them finishes with all four CQEs."""
     # (without the scan the state space is large: one slice per collective there, two with it)
@@ -288,3 +291,39 @@ def test_focused_passes_take_the_furthest_along_first():
     _check_data(S, w)
     # the first collective is carried through before the last one is begun
     assert picks.index(2) > max(i for i, c in enumerate(picks) if c == 0) - 2
+
+
+def test_direct_gather_steps_wait_for_the_reader_before_completing():
+    """direct = True: a rank's completion is posted only after the next rank has copied every notified
+    chunk out of its recv buffer (drain), whatever the interleaving; the values equal the data oracle's
+    and no FIFO slot is ever used by a gather step (the connectors never hold more than K slot entries,
+    notifications aside)."""
+    R = 3
+    colls = [wi.CollSpec(0, wi.AR, wi.F32, 50), wi.CollSpec(1, wi.AR, wi.BF16, 33), wi.CollSpec(2, wi.AR, wi.I32, 7)]
+    for seed in range(4):
+        g = np.random.default_rng(seed)
+        orders = [list(map(int, g.permutation(len(colls)))) for _ in range(R)]
+        w = wi.Workload("direct", R, colls, orders, seed=seed, cfg=93)
+        S = _system(w, sm.Policy(spin_init=2, spin_max=4, boost=2, K=2, slice_elems=8, direct=True, lookahead=2))
+        assert [p[0] for p in S.progs[0][0]][-4:] == ["recv_reduce_copy_notify", "direct_copy_notify", "direct_copy", "drain"]
+        posted = {}
+        rng = np.random.default_rng(100 + seed)
+        for _ in range(2_000_000):
+            if S.done():
+                break
+            a = int(rng.integers(0, 3 * R))
+            r = a % R
+            if a < R:
+                S.host_tick(r)
+            elif a < 2 * R:
+                S.daemons[r].mover_tick()
+            else:
+                S.daemons[r].tick()
+            for d in S.daemons:
+                for (c, seq) in d.cq:
+                    if (d.r, c) not in posted:
+                        posted[(d.r, c)] = True
+                        f = S.fifo[c][d.r]
+                        assert f.tail == f.head, "completion posted while the next rank still had chunks to read"
+        assert S.done() and S.total_cqes() == R * len(colls)
+        _check_data(S, w)
