@@ -21,16 +21,23 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 R = 8
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
-# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md): reads 5 810 100 KiB + writes
-# 5 768 800 KiB per launch at the default workload.  Reported only for that workload.
-MEASURED_TRAFFIC_BYTES = 11856793600
+# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md): reads 5 777 800 KiB + writes
+# 3 934 500 KiB per launch at the default workload.  Reported only for that workload.
+MEASURED_TRAFFIC_BYTES = 9945000000
 
 
 def algorithmic_bytes(msg_bytes: int, nranks: int) -> int:
     """(6R-4)/R * M per rank: every ring step's reads and writes of send buffer, recv buffer and
-    connector slots (send 2B, recv-reduce-send 3B, recv-reduce-copy-send 4B, recv-copy-send 3B,
-    recv-copy 2B with B = M/R), summed over the R ranks."""
+    connector slots by the primitive table (send 2B, recv-reduce-send 3B, recv-reduce-copy-send 4B,
+    recv-copy-send 3B, recv-copy 2B with B = M/R), summed over the R ranks."""
     return (6 * nranks - 4) * msg_bytes
+
+
+def moved_bytes(msg_bytes: int, nranks: int) -> int:
+    """What the library's default path moves for an all-reduce of 2 MiB or more: with the direct
+    gather steps a finished chunk is written once (recv buffer) instead of twice (recv buffer and
+    slot), (5R-3)/R * M per rank."""
+    return (5 * nranks - 3) * msg_bytes
 
 
 def cpu_baseline(sample_bytes: int, min_seconds: float = 10.0, max_reps: int = 40):
@@ -431,7 +438,12 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES if args.msg_mib == 256 else None,
                      "kernel": "dfx_daemon_kernel", "kernel_ms_avg": round(k_ms, 4),
-                     "algorithmic_bytes_per_launch": algorithmic_bytes(M, R)},
+                     "algorithmic_bytes_per_launch": algorithmic_bytes(M, R),
+                     # the direct gather steps leave out the slot copy of the gather phase: bytes the
+                     # launch really moves, and the rate and fraction by that count
+                     "moved_bytes_per_launch": moved_bytes(M, R) if info["nprim"] == 2 * R else algorithmic_bytes(M, R),
+                     "moved_GBs": round((moved_bytes(M, R) if info["nprim"] == 2 * R else algorithmic_bytes(M, R)) / (k_ms * 1e-3) / 1e9, 1),
+                     "moved_frac": round((moved_bytes(M, R) if info["nprim"] == 2 * R else algorithmic_bytes(M, R)) / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "copy_kernel_GBs": round(copy_gbs, 1),
     }
     del send, recv
