@@ -50,7 +50,7 @@ Two variations of Alg. 1 can be switched on, to ask whether they keep its livene
     queue at once; its CQE is written when that slice has been moved.
   * `scan = True`: a pass starts by evaluating the wait conditions of every queue entry and
     visits only the entries found runnable, each with the minimum threshold.
-  * `direct = True`: the gather steps of an all-reduce go without FIFO slots.  A rank writes a
+  * `direct = True`: the gather steps of an all-reduce (and all of an all-gather) go without FIFO slots.  A rank writes a
     finished chunk to its recv buffer only and notifies the next rank (the connector's counter is
     raised, no slot is needed, so no wait for space); the next rank copies it out of that recv
     buffer; a last step (drain) waits until the next rank has consumed everything, because
@@ -89,6 +89,7 @@ PRIMS = {
     "recv_reduce_copy_notify": (True, 2),
     "direct_copy_notify": (True, 2),
     "direct_copy": (True, 0),
+    "copy_notify": (False, 2),
     "drain": (False, 3),
 }
 
@@ -108,7 +109,7 @@ class Policy:
     lookahead: int = 0            # 0: a slice moves at its successful poll; n: up to n claimed slices per rank, moved by a mover actor
     scan: bool = False            # a pass visits only the entries whose wait conditions hold at its start
     focus: int = 0                # with scan: furthest-along entries first, and the pass ends after this many slices
-    direct: bool = False          # all-reduce: the gather steps read the previous rank's recv buffer (notify / drain)
+    direct: bool = False          # all-reduce, all-gather: the gather steps read the previous rank's recv buffer (notify / drain)
 
 
 @dataclass
@@ -148,6 +149,12 @@ def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
         p = [("send", b(r - 1), none)]
         p += [("recv_reduce_send", b(r - 1 - s), none) for s in range(1, R - 1)]
         p += [("recv_reduce_copy", b(r), recv_blocks[0])]
+        return p
+    if kind == AG and direct:
+        p = [("copy_notify", blocks[0], d(r))]
+        p += [("direct_copy_notify", none, d(r - j)) for j in range(1, R - 1)]
+        p += [("direct_copy", none, d(r + 1))]
+        p += [("drain", none, none)]
         return p
     if kind == AG:
         p = [("copy_send", blocks[0], d(r))]
@@ -492,7 +499,7 @@ class System:
             if isinstance(x, tuple):
                 # a notified chunk: read now from the recv buffer of the rank that holds it
                 x = self.recvs[ci][x[1]][ds[0]:ds[1]].copy()
-            if name in ("send", "copy_send", "copy"):
+            if name in ("send", "copy_send", "copy", "copy_notify"):
                 y = src[ss[0]:ss[1]].copy()
             elif name.startswith("recv_reduce"):
                 y = rd.add_hop(x, src[ss[0]:ss[1]], c.dtype)

@@ -464,6 +464,12 @@ __device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos,
     else if (p == last_reduce) { q.recv = true; q.send = (kind == KIND_AR); q.from_send = true; q.to_recv = true; }  // recv-reduce-copy(-send)
     else if (p < 2u * R - 2) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }            // recv-copy-send
     else { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }                               // recv-copy
+  } else if (kind == KIND_AG && direct) {
+    // every block is written once: the own one by a copy that notifies, the others by direct copies
+    q.send = false;
+    if (p == 0) { q.recv = false; q.from_send = true; q.to_recv = true; q.notify = true; }                        // copy, notify
+    else if (p < R) { q.recv = true; q.from_send = false; q.to_recv = true; q.din = true; q.notify = p < R - 1; } // direct recv-copy (, notify)
+    else { q.recv = false; q.from_send = false; q.to_recv = false; q.drain = true; }                              // drain
   } else if (kind == KIND_AG) {
     if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }                          // copy-send
     else if (p < R - 1) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
@@ -545,7 +551,7 @@ __device__ __forceinline__ DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool,
   // place in the chain: broadcast starts at the root, reduce at the rank after it
   const uint32_t bpos = (rank + 2 * R - q.root - (q.kind == KIND_RD ? 1u : 0u)) % R;
   k.bc_pos = bpos == 0 ? 0 : (bpos == R - 1 ? 2 : 1);
-  if (q.flags & DFX_SQE_DIRECT) k.bc_pos |= DFX_CTX_DIRECT;   // an all-reduce with direct gather steps
+  if (q.flags & DFX_SQE_DIRECT) k.bc_pos |= DFX_CTX_DIRECT;   // an all-reduce / all-gather with direct gather steps
   k.priority = q.priority; k.vch = (uint16_t)vch;
   return k;
 }

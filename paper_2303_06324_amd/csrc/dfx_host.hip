@@ -544,6 +544,14 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
     t.nprim = (uint32_t)(2 * R - 1) + (direct ? 1u : 0u);
   }
   else if (rooted) t.nprim = 1;   // one primitive per slice, which one depends on the place in the chain
+  else if (kind == DFX_ALLGATHER && c->cfg.direct && count * eb * R >= c->cfg.direct_min_bytes && (count * eb) % 16 == 0 &&
+           (rounds == 1 || c->cfg.direct_min_bytes == 0)) {
+    // Direct gather steps need every block 16-byte aligned in the recv buffers.  They pay where a
+    // workgroup's share of a block is one slice (8 - 32 MiB gathered: 15 - 25 % faster); with several
+    // slices per share the slots, which stay in the memory-side cache, are as fast or faster.
+    t.flags |= DFX_SQE_DIRECT;
+    t.nprim = (uint32_t)R + 1u;
+  }
   else t.nprim = (uint32_t)R;
   c->pool_used += conn_bytes;
   ci.tmpl = t;

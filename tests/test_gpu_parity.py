@@ -346,3 +346,11 @@ def test_direct_allreduce_repeated_with_changing_buffers_and_in_place():
             assert np.array_equal(b.cpu().numpy(), want.view(np.uint8))
     finally:
         assert ctx.finalize() == dfx.OK
+
+
+@pytest.mark.parametrize("dtype,count", [(wi.F32, 4096), (wi.BF16, 250000), (wi.I32, 4), (wi.F16, 1 << 20), (wi.F16, 1001)])
+@pytest.mark.parametrize("R", [2, 5, 8])
+def test_direct_allgather(dtype, count, R):
+    """All-gather with direct steps: every block is written once and read from the previous rank's recv
+    buffer (blocks that are not 16-byte aligned - the last case - keep the FIFO path)."""
+    _run(_one(wi.AG, dtype, count, R, seed=count + R), **DIRECT)

@@ -306,6 +306,8 @@ def test_direct_gather_steps_wait_for_the_reader_before_completing():
         w = wi.Workload("direct", R, colls, orders, seed=seed, cfg=93)
         S = _system(w, sm.Policy(spin_init=2, spin_max=4, boost=2, K=2, slice_elems=8, direct=True, lookahead=2))
         assert [p[0] for p in S.progs[0][0]][-4:] == ["recv_reduce_copy_notify", "direct_copy_notify", "direct_copy", "drain"]
+        assert [p[0] for p in sm.program(wi.AG, 4, 1, 0, [(0, 8)], [(8 * j, 8 * j + 8) for j in range(4)], True)] == \
+            ["copy_notify", "direct_copy_notify", "direct_copy_notify", "direct_copy", "drain"]
         posted = {}
         rng = np.random.default_rng(100 + seed)
         for _ in range(2_000_000):
