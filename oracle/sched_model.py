@@ -161,6 +161,14 @@ def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
         p += [("recv_copy_send", none, d(r - j)) for j in range(1, R - 1)]
         p += [("recv_copy", none, d(r + 1))]
         return p
+    if kind == BC and direct:
+        # one primitive per slice; the drain is a round of its own after the last slice (see System.rounds)
+        pos = (r - root) % R
+        if pos == 0:
+            return [("copy_notify", blocks[0], recv_blocks[0])]
+        if pos == R - 1:
+            return [("direct_copy", none, recv_blocks[0])]
+        return [("direct_copy_notify", none, recv_blocks[0])]
     if kind == BC:
         pos = (r - root) % R
         if pos == 0:
@@ -307,9 +315,16 @@ class Daemon:
         if self.S.policy.focus and self.taken >= self.S.policy.focus:
             self.rk = len(self.ready)
 
+    def _prim(self, coll, g, p):
+        """(name, send block, recv block) of primitive p of round g."""
+        S = self.S
+        if S.policy.direct and S.colls[coll].kind == BC and S.R > 1 and g == S.rounds[coll] - 1:
+            return ("drain", None, None)
+        return S.progs[coll][self.r][p]
+
     def _runnable(self, coll):
         g, p = self.active if self.loaded == coll else self.saved[coll]
-        need_recv, send_side = PRIMS[self.S.progs[coll][self.r][p][0]]
+        need_recv, send_side = PRIMS[self._prim(coll, g, p)[0]]
         rd_ok, wr_ok, drained = self._conds(coll, p)
         return (not need_recv or rd_ok) and (send_side != 1 or wr_ok) and (send_side != 3 or drained)
 
@@ -381,7 +396,7 @@ class Daemon:
         P = S.policy
         rounds, prog = S.rounds[coll], S.progs[coll][self.r]
         g, p = self.active
-        name, sblk, dblk = prog[p]
+        name, sblk, dblk = self._prim(coll, g, p)
         need_recv, send_side = PRIMS[name]
         fin = S.fifo[coll][(self.r - 1) % S.R]
         fout = S.fifo[coll][self.r]
@@ -449,6 +464,8 @@ class System:
             sb, db, blen = layout(c, R)
             self.progs.append([program(c.kind, R, r, c.root, sb, db, policy.direct) for r in range(R)])
             self.rounds.append(max(1, -(-blen // policy.slice_elems)))
+            if policy.direct and c.kind == BC and R > 1:
+                self.rounds[-1] += 1     # the last round of a direct broadcast is the drain
             self.fifo.append([Fifo(policy.K) for _ in range(R)])
         self.daemons = [Daemon(self, r) for r in range(R)]
         self.pending = [[] for _ in range(R)]   # host side: submissions not yet pushed to the SQ

@@ -478,10 +478,24 @@ __device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos,
     if (bc_pos == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = false; }                    // send
     else if (bc_pos == 2) { q.recv = true; q.send = false; q.from_send = true; q.to_recv = true; }               // recv-reduce-copy
     else { q.recv = true; q.send = true; q.from_send = true; q.to_recv = false; }                                 // recv-reduce-send
+  } else if (direct) {  // broadcast chain with direct steps: every rank writes its recv buffer only
+    q.send = false; q.to_recv = true;
+    q.recv = bc_pos != 0; q.din = bc_pos != 0; q.from_send = bc_pos == 0; q.notify = bc_pos != 2;
   } else {  // broadcast chain root -> root+1 -> ... -> root-1
     if (bc_pos == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }
     else if (bc_pos == 2) { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
     else { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
+  }
+  return q;
+}
+
+// A broadcast has one primitive per slice, so its drain cannot be a step of the per-slice
+// sequence: a direct broadcast counts one round more than it has slices, and that round is the
+// drain (nothing to move; the last rank of the chain has notified nothing and passes at once).
+__device__ __forceinline__ Prim chain_drain_round(Prim q, int kind, bool direct, uint32_t g, uint32_t rounds) {
+  if (direct && kind == KIND_BC && g + 1 == rounds) {
+    q.recv = q.send = q.from_send = q.to_recv = q.notify = q.din = false;
+    q.drain = true;
   }
   return q;
 }
@@ -551,7 +565,7 @@ __device__ __forceinline__ DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool,
   // place in the chain: broadcast starts at the root, reduce at the rank after it
   const uint32_t bpos = (rank + 2 * R - q.root - (q.kind == KIND_RD ? 1u : 0u)) % R;
   k.bc_pos = bpos == 0 ? 0 : (bpos == R - 1 ? 2 : 1);
-  if (q.flags & DFX_SQE_DIRECT) k.bc_pos |= DFX_CTX_DIRECT;   // an all-reduce / all-gather with direct gather steps
+  if (q.flags & DFX_SQE_DIRECT) k.bc_pos |= DFX_CTX_DIRECT;   // an all-reduce / all-gather / broadcast with direct steps
   k.priority = q.priority; k.vch = (uint16_t)vch;
   return k;
 }
@@ -1029,7 +1043,9 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 const uint4 ge = e[5];    // bytes 80..95: seq | nprim,nchan | nslots,kind,dtype,bc_pos | priority,vch
                 const uint4 d0 = e[6];    // dyn: round | prim | sent
                 const uint4 d1 = e[7];    // dyn: recvd | preempted | cidx
-                const Prim pq = make_prim((int)((ge.z >> 8) & 0xffu), a.R, (ge.z >> 24) & 3u, d0.y, ((ge.z >> 24) & DFX_CTX_DIRECT) != 0);
+                Prim pq = make_prim((int)((ge.z >> 8) & 0xffu), a.R, (ge.z >> 24) & 3u, d0.y, ((ge.z >> 24) & DFX_CTX_DIRECT) != 0);
+                if (((ge.z >> 24) & DFX_CTX_DIRECT) && ((ge.z >> 8) & 0xffu) == (uint32_t)KIND_BC)
+                  pq = chain_drain_round(pq, KIND_BC, true, d0.x, e[4].w);   // bytes 64..79: fifo_in | slice_elems | rounds
                 const u64 f_out = ((u64)fl.w << 32) | fl.z, f_in = ((u64)fi.y << 32) | fi.x;
                 const u64 e_sent = ((u64)d0.w << 32) | d0.z, e_recvd = ((u64)d1.y << 32) | d1.x;
                 bool okr = true, oks = true;
@@ -1101,7 +1117,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
 
       // ================= next primitive of the collective in hand =================
       const DfxCooked& S = sh.slot[sl].st;
-      const Prim q = make_prim((int)S.kind, a.R, S.bc_pos & 3u, p, (S.bc_pos & DFX_CTX_DIRECT) != 0);
+      const Prim q = chain_drain_round(make_prim((int)S.kind, a.R, S.bc_pos & 3u, p, (S.bc_pos & DFX_CTX_DIRECT) != 0),
+                                       (int)S.kind, (S.bc_pos & DFX_CTX_DIRECT) != 0, g, S.rounds);
       u64* const tail_out = (u64*)S.flags_out;
       u64* const tail_in = (u64*)S.flags_in;
       const uint32_t K = S.nslots;

@@ -543,7 +543,15 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
     if (direct) t.flags |= DFX_SQE_DIRECT;
     t.nprim = (uint32_t)(2 * R - 1) + (direct ? 1u : 0u);
   }
-  else if (rooted) t.nprim = 1;   // one primitive per slice, which one depends on the place in the chain
+  else if (rooted) {
+    t.nprim = 1;   // one primitive per slice, which one depends on the place in the chain
+    if (kind == DFX_BROADCAST && c->cfg.direct && count * eb >= c->cfg.direct_min_bytes) {
+      // direct steps: every rank writes its recv buffer only and the next one reads it there; one
+      // round more than there are slices, which is the drain
+      t.flags |= DFX_SQE_DIRECT;
+      t.rounds = (uint32_t)rounds + 1u;
+    }
+  }
   else if (kind == DFX_ALLGATHER && c->cfg.direct && count * eb * R >= c->cfg.direct_min_bytes && (count * eb) % 16 == 0 &&
            (rounds == 1 || c->cfg.direct_min_bytes == 0)) {
     // Direct gather steps need every block 16-byte aligned in the recv buffers.  They pay where a

@@ -354,3 +354,11 @@ def test_direct_allgather(dtype, count, R):
     """All-gather with direct steps: every block is written once and read from the previous rank's recv
     buffer (blocks that are not 16-byte aligned - the last case - keep the FIFO path)."""
     _run(_one(wi.AG, dtype, count, R, seed=count + R), **DIRECT)
+
+
+@pytest.mark.parametrize("dtype,count", [(wi.F32, 1), (wi.BF16, 250001), (wi.I32, 1 << 20), (wi.F16, 3 << 20)])
+@pytest.mark.parametrize("R,root", [(2, 1), (5, 0), (8, 3), (8, 7)])
+def test_direct_broadcast(dtype, count, R, root):
+    """Broadcast with direct steps: every rank writes its recv buffer only, the next one reads it there;
+    a drain round after the last slice keeps the completion behind the neighbour's last read."""
+    _run(_one(wi.BC, dtype, count, R, root=root, seed=count + R), **DIRECT)

@@ -329,3 +329,20 @@ def test_direct_gather_steps_wait_for_the_reader_before_completing():
                         assert f.tail == f.head, "completion posted while the next rank still had chunks to read"
         assert S.done() and S.total_cqes() == R * len(colls)
         _check_data(S, w)
+
+
+def test_direct_broadcast_model_drains_after_the_last_slice():
+    """The model's direct broadcast: one primitive per slice, one round more than slices, the drain;
+    mixed with other kinds in random interleavings the values equal the data oracle's."""
+    R = 4
+    colls = [wi.CollSpec(0, wi.BC, wi.F32, 40, root=2), wi.CollSpec(1, wi.AR, wi.I32, 19), wi.CollSpec(2, wi.BC, wi.BF16, 7, root=0),
+             wi.CollSpec(3, wi.AG, wi.F16, 6)]
+    for seed in range(3):
+        g = np.random.default_rng(seed)
+        orders = [list(map(int, g.permutation(len(colls)))) for _ in range(R)]
+        w = wi.Workload("direct_bc", R, colls, orders, seed=seed, cfg=94)
+        S = _system(w, sm.Policy(spin_init=2, spin_max=4, boost=2, K=2, slice_elems=8, direct=True, lookahead=2, scan=True))
+        assert S.rounds[0] == 5 + 1 and S.rounds[2] == 1 + 1
+        sm.run_random(S, seed + 7, max_ticks=3_000_000)
+        assert S.total_cqes() == R * len(colls)
+        _check_data(S, w)
