@@ -117,8 +117,9 @@ typedef struct {
                               of them side by side (whose FIFO slots together outgrow the memory-side cache);
                               0 = every runnable collective once per pass, in queue order */
   uint32_t direct;         /* 1 (default): the gather steps of an all-reduce of at least direct_min_bytes per rank
-                              (and of an all-gather that gathers at least as much, whose blocks are 16-byte
-                              multiples and whose channel shares are single slices) are direct: a rank writes a finished chunk to its recv buffer only and raises the
+                              (of an all-gather that gathers at least as much, whose blocks are 16-byte
+                              multiples and whose channel shares are single slices, and every step of a
+                              broadcast of at least as much) are direct: a rank writes a finished chunk to its recv buffer only and raises the
                               connector's counter, the next rank reads it there (all buffers lie in one HBM),
                               and a last step waits until the next rank has read everything before the
                               completion is posted; 0: every step goes through a FIFO slot, as the primitive
