@@ -50,13 +50,14 @@ def test_same_order_without_preemption_completes():
     assert sum(s["preemptions"] for s in stats) == 0
 
 
-def test_voluntary_quit_and_event_driven_restart():
+@pytest.mark.parametrize("direct_min_bytes", [2 << 20, 0])
+def test_voluntary_quit_and_event_driven_restart(direct_min_bytes):
     """Sec. 4.4: the daemon leaves when idle and is started again by the next SQE; contexts survive."""
     from tests import gpu_harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.Workload("quit", 8, [wi.CollSpec(0, wi.AR, wi.F32, 200000)], [[0]] * 8, seed=5, cfg=70)
     dw = gh.DeviceWorkload(w)
-    ctx = dfx.Context(8, gh.make_config(quit_idle_us=300))
+    ctx = dfx.Context(8, gh.make_config(quit_idle_us=300, direct_min_bytes=direct_min_bytes))
     try:
         gh.prepare_all(ctx, w)
         launches = []
@@ -198,14 +199,16 @@ def test_sq_placements(placement):
         _expect(dw, w, ci)
 
 
-def test_stop_with_outstanding_work_and_resume():
+@pytest.mark.parametrize("direct_min_bytes", [2 << 20, 0])
+def test_stop_with_outstanding_work_and_resume(direct_min_bytes):
     """dfx_stop (exit SQE, Sec. 4.4) while collectives are stuck: their contexts survive in the
-    context buffer (Sec. 4.5) and the next start resumes them."""
+    context buffer (Sec. 4.5) and the next start resumes them (also with the direct gather steps,
+    whose published recv-buffer addresses must survive in the connectors)."""
     from tests import gpu_harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.config3(n_buckets=4, bucket_bytes=1 << 20, seed=15)
     dw = gh.DeviceWorkload(w)
-    ctx = dfx.Context(8, gh.make_config(quit_idle_us=0))
+    ctx = dfx.Context(8, gh.make_config(quit_idle_us=0, direct_min_bytes=direct_min_bytes))
     try:
         gh.prepare_all(ctx, w)
         for ci in range(4):                      # only ranks 0..5 submit: nothing can complete
