@@ -69,7 +69,7 @@ typedef struct {
   uint32_t sq_depth;       /* SQ ring entries per vrank (power of two) */
   uint32_t cq_slots;       /* CQ slot-array length per vrank (Sec. 5 "optimized CQ") */
   uint32_t nslots;         /* K: slots per connector FIFO, >= 2 (a fused recv+send ring cannot run on 1) */
-  uint32_t slot_bytes;     /* S: bytes per FIFO slot and channel, multiple of 16 */
+  uint32_t slot_bytes;     /* S: bytes per FIFO slot and channel, multiple of 16 (default 256 KiB) */
   uint32_t chan_min_bytes; /* a collective uses C = clamp(ceil(ringChunkBytes / chan_min_bytes), 1, max_channels) channels */
   uint32_t spin_init;      /* initial spin threshold (poll attempts) at the task-queue front (Sec. 4.3) */
   uint32_t spin_min;       /* thr(pos) = max(spin_min, spin_init >> pos) */
@@ -90,7 +90,7 @@ typedef struct {
                               3 = phases as in 2, and the trace holds one sample per executed primitive
                                   instead of one per switch (see dfx_trace_read) */
   uint32_t fetch_batch;    /* SQEs a workgroup may fetch in a row when its queue is empty or stuck; 0 = all available */
-  uint64_t pool_bytes;     /* device memory reserved for connectors of all prepared collectives */
+  uint64_t pool_bytes;     /* device memory reserved for connectors of all prepared collectives (default 4 GiB) */
   uint32_t scan_min;       /* a pass over a task queue of at least this many entries starts with a readiness
                               scan (64 entries polled at once, one per lane) and visits only runnable
                               entries; 0 = never scan, poll every entry in turn as Alg. 1 is written */

@@ -352,7 +352,7 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->sq_depth = 256;
   cfg->cq_slots = 256;
   cfg->nslots = 4;
-  cfg->slot_bytes = 128u << 10;
+  cfg->slot_bytes = 256u << 10;
   cfg->chan_min_bytes = 16u << 10;
   cfg->spin_init = 16;
   cfg->spin_min = 1;
@@ -374,7 +374,7 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->wg_map = 0;
   cfg->order_policy = 0;
   cfg->trace = 0;
-  cfg->pool_bytes = 2ull << 30;
+  cfg->pool_bytes = 4ull << 30;
   return DFX_OK;
 }
 
