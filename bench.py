@@ -21,9 +21,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 R = 8
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
-# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md): reads 5 777 800 KiB + writes
-# 3 934 500 KiB per launch at the default workload.  Reported only for that workload.
-MEASURED_TRAFFIC_BYTES = 9945000000
+# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md): reads 5 773 800 KiB + writes
+# 3 932 800 KiB per launch at the default workload.  Reported only for that workload.
+MEASURED_TRAFFIC_BYTES = 9939558400
 
 
 def algorithmic_bytes(msg_bytes: int, nranks: int) -> int:
