@@ -132,7 +132,7 @@ typedef struct {
 typedef struct {
   uint64_t preemptions;    /* waits that hit their spin threshold (context switches) */
   uint64_t ctx_loads;      /* context loads from HBM into an LDS active slot */
-  uint64_t ctx_slot_hits;  /* loads avoided because the direct-mapped LDS slot still held the context */
+  uint64_t ctx_slot_hits;  /* loads avoided because the collective's LDS slot already held the context */
   uint64_t ctx_saves;      /* dynamic-context saves to HBM */
   uint64_t lazy_skips;     /* preemptions that skipped the save (nothing had progressed) */
   uint64_t polls;          /* poll attempts in wait phases */

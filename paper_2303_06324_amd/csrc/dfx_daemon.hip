@@ -421,6 +421,7 @@ struct Shared {
   DfxDaemonArgs args;
   DfxCtxEntry slot[DFX_CTX_SLOTS];   // active context slots (Sec. 5, direct-mapped)
   uint32_t slot_tag[DFX_CTX_SLOTS];
+  uint32_t slot_claim[DFX_CTX_SLOTS];  // readiness scan: which entry of the scan gets to fill a slot (scan step << 8 | lane)
   Job job[2];                        // posted jobs, indexed by job number & 1
   Flight fl[2];
   uint32_t job_seq;                  // jobs posted so far (scheduler -> movers)
@@ -516,6 +517,12 @@ __device__ __forceinline__ void bump(u64* stat, int i, u64 v) {
 }
 
 __device__ __forceinline__ uint32_t bcast0(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// LDS slot of a collective's context: a multiplicative hash, because the ids that share a workgroup's
+// queue are far from random (with single-channel collectives spread over the channels they are all
+// congruent modulo the channel count)
+static_assert(DFX_CTX_SLOTS == 64, "ctx_slot takes the top six bits");
+__device__ __forceinline__ uint32_t ctx_slot(uint32_t coll) { return (coll * 2654435769u) >> 26; }
 
 // LDS words shared between the scheduler and the mover waves
 __device__ __forceinline__ uint32_t lds_ld(const uint32_t* p) { return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP); }
@@ -963,7 +970,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 DfxDyn* dy = &myctx[c_id].dyn;
                 dy->round = 0; dy->prim = 0; dy->preempted = 0;
                 dy->cidx = first_chunk(q.kind, rank, a.R);
-                if (sh.slot_tag[c_id % DFX_CTX_SLOTS] == c_id) sh.slot_tag[c_id % DFX_CTX_SLOTS] = 0xffffffffu;
+                if (sh.slot_tag[ctx_slot(c_id)] == c_id) sh.slot_tag[ctx_slot(c_id)] = 0xffffffffu;
               }
               // every workgroup of the rank reads every SQE; the last reader frees the slot (Sec. 5)
               // by writing the entry's generation where the submitter looks for it, in host memory
@@ -1036,17 +1043,23 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           if (scanned) {
             nready = 0; rk = 0; pass_bytes = 0;
             focus = a.focus_bytes != 0 && qlen <= 64u;
+            if (lane < DFX_CTX_SLOTS) sh.slot_claim[lane] = 0xffffffffu;
             for (uint32_t base = 0; base < qlen; base += 64) {
               const uint32_t i = base + lane;
               bool rdy = false;
               uint32_t key = 0;     // 0 = not runnable; else primitives done so far, then queue position
+              uint32_t cid = 0;
+              uint4 e0 = uint4{0, 0, 0, 0}, e1 = e0, e4 = e0, e2c = e0, e3c = e0, e5c = e0, e6c = e0, e7c = e0;
               if (i < qlen) {
-                const uint4* e = (const uint4*)&myctx[sh.taskq[i]];
+                cid = sh.taskq[i];
+                const uint4* e = (const uint4*)&myctx[cid];
+                e0 = e[0]; e1 = e[1]; e4 = e[4];   // not needed for the vote, but for the deposit below
                 const uint4 fl = e[2];    // bytes 32..47: part_elems | flags_out
                 const uint4 fi = e[3];    // bytes 48..63: flags_in | fifo_out
                 const uint4 ge = e[5];    // bytes 80..95: seq | nprim,nchan | nslots,kind,dtype,bc_pos | priority,vch
                 const uint4 d0 = e[6];    // dyn: round | prim | sent
                 const uint4 d1 = e[7];    // dyn: recvd | preempted | cidx
+                e2c = fl; e3c = fi; e5c = ge; e6c = d0; e7c = d1;
                 Prim pq = make_prim((int)((ge.z >> 8) & 0xffu), a.R, (ge.z >> 24) & 3u, d0.y, ((ge.z >> 24) & DFX_CTX_DIRECT) != 0);
                 if (((ge.z >> 24) & DFX_CTX_DIRECT) && ((ge.z >> 8) & 0xffu) == (uint32_t)KIND_BC)
                   pq = chain_drain_round(pq, KIND_BC, true, d0.x, e[4].w);   // bytes 64..79: fifo_in | slice_elems | rounds
@@ -1062,6 +1075,17 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                   if (done > 0xfffffu) done = 0xfffffu;
                   key = (((uint32_t)done << 8) | (63u - lane)) + 1u;
                 }
+              }
+              // The contexts of the runnable entries are in registers now: they go into their LDS
+              // slots (direct-mapped; of several entries of the scan that share a slot the first one
+              // gets it), so that the pass finds them there instead of loading them from HBM again.
+              if (rdy) (void)__hip_atomic_fetch_min(&sh.slot_claim[ctx_slot(cid)], ((base >> 6) << 8) | lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+              __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+              __builtin_amdgcn_wave_barrier();
+              if (rdy && sh.slot_claim[ctx_slot(cid)] == (((base >> 6) << 8) | lane)) {
+                uint4* dstc = (uint4*)&sh.slot[ctx_slot(cid)];
+                dstc[0] = e0; dstc[1] = e1; dstc[2] = e2c; dstc[3] = e3c; dstc[4] = e4; dstc[5] = e5c; dstc[6] = e6c; dstc[7] = e7c;
+                sh.slot_tag[ctx_slot(cid)] = cid;
               }
               const u64 mask = __ballot(rdy);
               if (focus) {
@@ -1096,7 +1120,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
 
         // ---- LoadCollectiveContext: HBM context buffer -> LDS slot, 8 lanes x 16 bytes
         coll = sh.taskq[pos];
-        sl = coll % DFX_CTX_SLOTS;
+        sl = ctx_slot(coll);
         if (sw_pending && a.trace_on > 1) sw_lb = wall_clock64();
         if (sh.slot_tag[sl] != coll) {
           if (lane < 8) ((uint4*)&sh.slot[sl])[lane] = ((const uint4*)&myctx[coll])[lane];

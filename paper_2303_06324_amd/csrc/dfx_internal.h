@@ -9,7 +9,7 @@
 #endif
 #define DFX_MOVERS (DFX_WG_THREADS - 64)   // threads of the mover wavefronts
 #define DFX_MAX_COLLS 4096      // upper bound for dfx_config.max_colls (LDS task queue = 8 KB)
-#define DFX_CTX_SLOTS 4         // LDS active context slots, direct-mapped by coll_id (Sec. 5)
+#define DFX_CTX_SLOTS 64        // LDS active context slots, indexed by a hash of coll_id (Sec. 5)
 #define DFX_TRACE_N 4096        // context-switch latency samples kept per workgroup
 #define DFX_FLAG_STRIDE 128     // bytes per (edge, channel) flag pair: tail at +0, head at +64
 #define DFX_DIRECT_OFF 16       // in the tail's line: the sender's recv buffer (8 bytes), invocation + 1 (4), 0 (4)
