@@ -35,9 +35,10 @@ def algorithmic_bytes(msg_bytes: int, nranks: int) -> int:
 
 def moved_bytes(msg_bytes: int, nranks: int) -> int:
     """What the library's default path moves for an all-reduce of 2 MiB or more: with the direct
-    gather steps a finished chunk is written once (recv buffer) instead of twice (recv buffer and
-    slot), (5R-3)/R * M per rank."""
-    return (5 * nranks - 3) * msg_bytes
+    steps a finished chunk is written once (recv buffer) instead of twice (recv buffer and slot),
+    and the opening send moves nothing (the next rank reads the chunk from the send buffer):
+    reads (3R-3)/R * M, writes (2R-2)/R * M per rank."""
+    return (5 * nranks - 5) * msg_bytes
 
 
 def cpu_baseline(sample_bytes: int, min_seconds: float = 10.0, max_reps: int = 40):
@@ -233,7 +234,7 @@ def kinds_sweep(nbytes: int = 256 << 20, iters: int = 8):
     b = [torch.empty(n, device="cuda") for _ in range(R)]
     torch.cuda.synchronize()
     # bytes each kind moves with the library's defaults at this size: all-reduce and broadcast take the
-    # direct steps ((5R-3) x M; 2R x M: every rank reads and writes the message once), the others the FIFO steps
+    # direct steps ((5R-5) x M; 2R x M: every rank reads and writes the message once), the others the FIFO steps
     cases = [("all-reduce", dfx.ALLREDUCE, n, moved_bytes(nbytes, R)),
              ("all-gather", dfx.ALLGATHER, n // R, (3 * R - 1) * (nbytes // R) * R),
              ("reduce-scatter", dfx.REDUCESCATTER, n // R, (3 * R - 1) * (nbytes // R) * R),
@@ -442,8 +443,8 @@ def main():
                    "daemon_launches": int(launches)},
         "algbw_GBs": round(algbw, 2),
         "hbm_frac_wall": round(launch_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-        # achieved = the bytes the shipped method has to move per launch / kernel time: (5R-3) x M with the
-        # direct gather steps (a finished chunk is written once), (6R-4) x M by the printed primitive table
+        # achieved = the bytes the shipped method has to move per launch / kernel time: (5R-5) x M with the
+        # direct steps (a finished chunk is written once, the opening send moves nothing), (6R-4) x M by the printed primitive table
         # (every gather step also through a slot), whose figure is given beside it: work per time, which
         # the direct steps raise by moving less.
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

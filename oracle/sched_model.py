@@ -90,6 +90,9 @@ PRIMS = {
     "direct_copy_notify": (True, 2),
     "direct_copy": (True, 0),
     "copy_notify": (False, 2),
+    "notify": (False, 2),                      # nothing moved: the next rank reads this rank's send buffer
+    "direct_reduce_send": (True, 1),           # recv-reduce-send whose input is the previous rank's send buffer
+    "direct_reduce_copy_notify": (True, 2),    # the same as the last reduce step (two ranks)
     "drain": (False, 3),
 }
 
@@ -133,10 +136,16 @@ def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
         p = [("send", b(r - 1), none)]
         p += [("recv_reduce_send", b(r - 1 - s), none) for s in range(1, R - 1)]
         if direct:
-            # a finished chunk goes to the recv buffer only; the next rank reads it there; the last
-            # step waits until the next rank has read them all (the recv buffer is the caller's again
-            # once the completion is posted)
-            p += [("recv_reduce_copy_notify", b(r), d(r))]
+            # the opening send only notifies and the next rank's first reduce step reads the chunk from
+            # this rank's send buffer; a finished chunk goes to the recv buffer only and the next rank
+            # reads it there; the last step waits until the next rank has read them all (the buffers
+            # are the caller's again once the completion is posted)
+            p[0] = ("notify", b(r - 1), none)
+            if R > 2:
+                p[1] = ("direct_reduce_send", b(r - 2), none)
+                p += [("recv_reduce_copy_notify", b(r), d(r))]
+            else:
+                p += [("direct_reduce_copy_notify", b(r), d(r))]
             p += [("direct_copy_notify", none, d(r - j)) for j in range(1, R - 1)]
             p += [("direct_copy", none, d(r + 1))]
             p += [("drain", none, none)]
@@ -514,10 +523,17 @@ class System:
             src = self.sends[ci][r]
             dst = self.recvs[ci][r]
             if isinstance(x, tuple):
-                # a notified chunk: read now from the recv buffer of the rank that holds it
-                x = self.recvs[ci][x[1]][ds[0]:ds[1]].copy()
-            if name in ("send", "copy_send", "copy", "copy_notify"):
+                # a notified chunk: read now from the buffer of the rank that holds it
+                if x[0] == "direct_send":
+                    x = self.sends[ci][x[1]][ss[0]:ss[1]].copy()     # same chunk, same offsets in its send buffer
+                else:
+                    x = self.recvs[ci][x[1]][ds[0]:ds[1]].copy()
+            if name == "notify":
+                y = None
+            elif name in ("send", "copy_send", "copy", "copy_notify"):
                 y = src[ss[0]:ss[1]].copy()
+            elif name.startswith("direct_reduce"):
+                y = rd.add_hop(x, src[ss[0]:ss[1]], c.dtype)
             elif name.startswith("recv_reduce"):
                 y = rd.add_hop(x, src[ss[0]:ss[1]], c.dtype)
             else:
@@ -529,7 +545,8 @@ class System:
         if PRIMS[name][1] == 1:
             fout.push((tag_out, y))
         elif PRIMS[name][1] == 2:
-            fout.push((tag_out, ("direct", r) if self.with_data else None), need_slot=False)
+            tok = ("direct_send", r) if name == "notify" else ("direct", r)
+            fout.push((tag_out, tok if self.with_data else None), need_slot=False)
 
     # -- global predicates
     def done(self):

@@ -447,15 +447,21 @@ struct Prim {
   // drain: no data, the wait ends when the next rank has consumed everything notified so far
   // (the recv buffer is the caller's again once the completion is posted).
   bool notify, din, drain;
+  bool din_send;   // the input is the previous rank's SEND buffer (first reduce step of a direct all-reduce)
 };
 
 __device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos, uint32_t p, bool direct) {
   Prim q;
-  q.notify = q.din = q.drain = false;
+  q.notify = q.din = q.drain = q.din_send = false;
   if (R == 1) { q.recv = q.send = false; q.from_send = q.to_recv = true; return q; }   // copy
   if (kind == KIND_AR && direct) {
     const uint32_t last_reduce = R - 1;
     q.recv = p > 0; q.send = p < last_reduce; q.from_send = p <= last_reduce; q.to_recv = p >= last_reduce;
+    // The opening send moves nothing either: the rank only notifies, and the next rank's first
+    // reduce step reads the chunk out of this rank's send buffer (which the caller leaves alone
+    // until the completion, and the drain keeps the completion behind that read).
+    if (p == 0) { q.send = false; q.from_send = false; q.notify = true; }             // notify only
+    else if (p == 1) q.din_send = true;                                               // recv-reduce-send / -copy from the neighbour's send buffer
     if (p == last_reduce) q.notify = true;                                            // recv-reduce-copy, notify
     else if (p > last_reduce && p < 2u * R - 2) { q.din = true; q.notify = true; }    // direct recv-copy, notify
     else if (p == 2u * R - 2) q.din = true;                                           // direct recv-copy
@@ -702,7 +708,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         last = (old + 1 == DFX_MOVERS / 64) ? 1u : 0u;
         if (first_wave && a.trace_on > 1) {
           bump(sh.stat, ST_T_DATA, t1 - t0);
-          if (a.trace_on == 3 && trace && (j.fin || j.sb)) trace_put(trace, &sh.trace_n, timeline_sample(t0, t1, j.coll, j.prim));   // not the drain step: it moves nothing
+          if (a.trace_on == 3 && trace && j.prim != 0xffu) trace_put(trace, &sh.trace_n, timeline_sample(t0, t1, j.coll, j.prim));   // not the drain step
         }
       }
       if (bcast0(last)) {
@@ -746,7 +752,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
     uint32_t g = 0, p = 0, cidx = 0;
     u64 sent = 0, recvd = 0, thr = 0;
     bool progressed = false;
-    u64 prev_recv = 0;                  // the previous rank's recv buffer (direct gather steps), 0 = not read yet
+    u64 prev_recv = 0, prev_send = 0;   // the previous rank's recv / send buffer (direct steps), 0 = not read yet
     uint32_t posted = 0, retired = 0;   // jobs handed to the movers / jobs whose bookkeeping is done
 
     // ---- completion of this workgroup's share of an invocation (Sec. 5): completion counter,
@@ -965,8 +971,11 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 // the invocation it belongs to go into the send connector's flag line (one 16-byte
                 // device-coherent store, complete before any job of the invocation is posted)
                 if (q.flags & DFX_SQE_DIRECT)
-                  Slot<AUX_DEVICE>((const void*)k.flags_out, DFX_FLAG_STRIDE)
-                      .st16(DFX_DIRECT_OFF, uint4{(uint32_t)q.recvbuf, (uint32_t)(q.recvbuf >> 32), q.seq + 1u, 0u});
+                {
+                  const Slot<AUX_DEVICE> line((const void*)k.flags_out, DFX_FLAG_STRIDE);
+                  line.st16(DFX_DIRECT_OFF, uint4{(uint32_t)q.recvbuf, (uint32_t)(q.recvbuf >> 32), q.seq + 1u, 0u});
+                  line.st16(DFX_DIRECT_OFF + 16, uint4{(uint32_t)q.sendbuf, (uint32_t)(q.sendbuf >> 32), q.seq + 1u, 0u});
+                }
                 DfxDyn* dy = &myctx[c_id].dyn;
                 dy->round = 0; dy->prim = 0; dy->preempted = 0;
                 dy->cidx = first_chunk(q.kind, rank, a.R);
@@ -1259,20 +1268,23 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           }
         }
         if (given_up) { stop = STOP_ABORT; have = false; continue; }
-        if (q.din) {
-          // The previous rank published its recv buffer for this invocation before it notified the
-          // first result (the counter just seen).  Read once per stay of the collective in hand.
+        if (q.din || q.din_send) {
+          // The previous rank published its buffers for this invocation before it notified anything
+          // (the counter just seen).  Read once per stay of the collective in hand.
           if (prev_recv == 0) {
-            uint4 w = uint4{0, 0, 0, 0};
+            const Slot<AUX_DEVICE> line((const void*)tail_in, DFX_FLAG_STRIDE);
+            uint4 w = uint4{0, 0, 0, 0}, w2 = w;
             for (uint32_t tries = 0; tries < 1024u; ++tries) {
-              w = Slot<AUX_DEVICE>((const void*)tail_in, DFX_FLAG_STRIDE).ld16(DFX_DIRECT_OFF);
-              if (w.z == inv_seq + 1u) break;
+              w = line.ld16(DFX_DIRECT_OFF);
+              w2 = line.ld16(DFX_DIRECT_OFF + 16);
+              if (w.z == inv_seq + 1u && w2.z == inv_seq + 1u) break;
               __builtin_amdgcn_s_sleep(2);
             }
-            if (w.z != inv_seq + 1u) { raise_error(a, 3u, wg); stop = STOP_ABORT; have = false; continue; }
+            if (w.z != inv_seq + 1u || w2.z != inv_seq + 1u) { raise_error(a, 3u, wg); stop = STOP_ABORT; have = false; continue; }
             prev_recv = ((u64)w.y << 32) | w.x;
+            prev_send = ((u64)w2.y << 32) | w2.x;
           }
-          jfin = (const void*)((const char*)prev_recv + doff * eb);
+          jfin = q.din_send ? (const void*)((const char*)prev_send + soff * eb) : (const void*)((const char*)prev_recv + doff * eb);
         }
         // ---- post the slice (an empty one is only a handshake: the movers just raise the counters);
         // this claims the slots: the data follows, the counters after it
@@ -1281,7 +1293,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         if (lane == 0) {
           Job j;
           j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
-          j.bytes = q.drain ? 0u : bytes; j.dtype = dtype; j.coll = coll; j.prim = p;
+          j.bytes = (q.drain || (!q.recv && !q.from_send)) ? 0u : bytes;   // drain and notify-only steps move nothing
+          j.dtype = dtype; j.coll = coll; j.prim = q.drain ? 0xffu : p;   // (prim: for the timeline only)
           sh.job[posted & 1] = j;
           Flight f;
           f.tail_out = (q.send || q.notify) ? tail_out : nullptr; f.head_in = q.recv ? tail_in + 8 : nullptr;

@@ -12,7 +12,7 @@
 #define DFX_CTX_SLOTS 64        // LDS active context slots, indexed by a hash of coll_id (Sec. 5)
 #define DFX_TRACE_N 4096        // context-switch latency samples kept per workgroup
 #define DFX_FLAG_STRIDE 128     // bytes per (edge, channel) flag pair: tail at +0, head at +64
-#define DFX_DIRECT_OFF 16       // in the tail's line: the sender's recv buffer (8 bytes), invocation + 1 (4), 0 (4)
+#define DFX_DIRECT_OFF 16       // in the tail's line: the sender's recv buffer (8 bytes), invocation + 1 (4), 0 (4); then the same for its send buffer
 #define DFX_NSTAT 24
 #define DFX_CQ_CTL_WORDS 24      // 64-bit words of ring bookkeeping per vrank: reserve at 0, tail at 8, head at 16
 
