@@ -21,9 +21,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 R = 8
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the
-# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md): reads 5 773 800 KiB + writes
-# 3 932 800 KiB per launch at the default workload.  Reported only for that workload.
-MEASURED_TRAFFIC_BYTES = 9939558400
+# plain copy kernel (profiles/hbm_traffic_allreduce_256MiB.md): reads 5 511 100 KiB + writes
+# 3 671 500 KiB per launch at the default workload.  Reported only for that workload.
+MEASURED_TRAFFIC_BYTES = 9402982400
 
 
 def algorithmic_bytes(msg_bytes: int, nranks: int) -> int:
