@@ -119,7 +119,9 @@ typedef struct {
   uint32_t direct;         /* 1 (default): the gather steps of an all-reduce of at least direct_min_bytes per rank
                               (of an all-gather that gathers at least as much, whose blocks are 16-byte
                               multiples and whose channel shares are single slices, and every step of a
-                              broadcast of at least as much) are direct: a rank writes a finished chunk to its recv buffer only and raises the
+                              broadcast of at least as much) are direct: the opening send of an all-reduce only raises the
+                              connector's counter and the next rank reads that chunk from this rank's send
+                              buffer; a rank writes a finished chunk to its recv buffer only and raises the
                               connector's counter, the next rank reads it there (all buffers lie in one HBM),
                               and a last step waits until the next rank has read everything before the
                               completion is posted; 0: every step goes through a FIFO slot, as the primitive
