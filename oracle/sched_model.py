@@ -54,7 +54,9 @@ Two variations of Alg. 1 can be switched on, to ask whether they keep its livene
     finished chunk to its recv buffer only and notifies the next rank (the connector's counter is
     raised, no slot is needed, so no wait for space); the next rank copies it out of that recv
     buffer; a last step (drain) waits until the next rank has consumed everything, because
-    the recv buffer belongs to the caller again once the completion is posted.
+    the buffers belong to the caller again once the completion is posted.  The opening send of
+    an all-reduce moves nothing either: it only notifies, and the next rank's first reduce step
+    reads the chunk from this rank's send buffer.
   * `focus = n > 0` (with scan): the runnable entries are visited furthest-along first
     (most primitives done; ties in queue order), and once n slices have been taken in the
     pass it ends with the entry in hand: every rank ranks the collectives alike, so the
