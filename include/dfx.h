@@ -117,9 +117,8 @@ typedef struct {
                               of them side by side (whose FIFO slots together outgrow the memory-side cache);
                               0 = every runnable collective once per pass, in queue order */
   uint32_t direct;         /* 1 (default): the gather steps of an all-reduce of at least direct_min_bytes per rank
-                              (of an all-gather that gathers at least as much, whose blocks are 16-byte
-                              multiples and whose channel shares are single slices, and every step of a
-                              broadcast of at least as much) are direct: the opening send of an all-reduce only raises the
+                              (of an all-gather that gathers at least as much and whose blocks are 16-byte
+                              multiples, and every step of a broadcast of at least as much) are direct: the opening send of an all-reduce only raises the
                               connector's counter and the next rank reads that chunk from this rank's send
                               buffer; a rank writes a finished chunk to its recv buffer only and raises the
                               connector's counter, the next rank reads it there (all buffers lie in one HBM),
@@ -127,7 +126,7 @@ typedef struct {
                               completion is posted; 0: every step goes through a FIFO slot, as the primitive
                               table of Sec. 4.2 has it */
   uint32_t direct_min_bytes; /* default 2 MiB: below it the extra step costs more than the saved writes; 0 = every
-                              all-reduce and every all-gather of 16-byte-multiple blocks (tests) */
+                              all-reduce, broadcast and all-gather of 16-byte-multiple blocks */
 } dfx_config;
 
 /* Aggregated over the workgroups of one vrank since dfx_init. */

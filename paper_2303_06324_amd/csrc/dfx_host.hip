@@ -552,11 +552,8 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
       t.rounds = (uint32_t)rounds + 1u;
     }
   }
-  else if (kind == DFX_ALLGATHER && c->cfg.direct && count * eb * R >= c->cfg.direct_min_bytes && (count * eb) % 16 == 0 &&
-           (rounds == 1 || c->cfg.direct_min_bytes == 0)) {
-    // Direct gather steps need every block 16-byte aligned in the recv buffers.  They pay where a
-    // workgroup's share of a block is one slice (8 - 32 MiB gathered: 15 - 25 % faster); with several
-    // slices per share the slots, which stay in the memory-side cache, are as fast or faster.
+  else if (kind == DFX_ALLGATHER && c->cfg.direct && count * eb * R >= c->cfg.direct_min_bytes && (count * eb) % 16 == 0) {
+    // direct gather steps need every block 16-byte aligned in the recv buffers
     t.flags |= DFX_SQE_DIRECT;
     t.nprim = (uint32_t)R + 1u;
   }
