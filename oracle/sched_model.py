@@ -95,6 +95,7 @@ PRIMS = {
     "notify": (False, 2),                      # nothing moved: the next rank reads this rank's send buffer
     "direct_reduce_send": (True, 1),           # recv-reduce-send whose input is the previous rank's send buffer
     "direct_reduce_copy_notify": (True, 2),    # the same as the last reduce step (two ranks)
+    "direct_reduce_copy": (True, 0),           # the same as the last step of a reduce-scatter (two ranks)
     "drain": (False, 3),
 }
 
@@ -114,7 +115,7 @@ class Policy:
     lookahead: int = 0            # 0: a slice moves at its successful poll; n: up to n claimed slices per rank, moved by a mover actor
     scan: bool = False            # a pass visits only the entries whose wait conditions hold at its start
     focus: int = 0                # with scan: furthest-along entries first, and the pass ends after this many slices
-    direct: bool = False          # all-reduce, all-gather: the gather steps read the previous rank's recv buffer (notify / drain)
+    direct: bool = False          # steps that read the previous rank's recv / send buffer instead of a slot (notify / drain)
 
 
 @dataclass
@@ -155,6 +156,19 @@ def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
         p += [("recv_reduce_copy_send", b(r), d(r))]
         p += [("recv_copy_send", none, d(r - j)) for j in range(1, R - 1)]
         p += [("recv_copy", none, d(r + 1))]
+        return p
+    if kind == RS and direct:
+        # as the reduce phase of the direct all-reduce: the opening send only notifies, the next
+        # rank's first reduce step reads the chunk from this rank's send buffer, and the drain keeps
+        # the completion (after which the send buffer is the caller's again) behind that read
+        p = [("notify", b(r - 1), none)]
+        if R > 2:
+            p += [("direct_reduce_send", b(r - 2), none)]
+            p += [("recv_reduce_send", b(r - 1 - s), none) for s in range(2, R - 1)]
+            p += [("recv_reduce_copy", b(r), recv_blocks[0])]
+        else:
+            p += [("direct_reduce_copy", b(r), recv_blocks[0])]
+        p += [("drain", none, none)]
         return p
     if kind == RS:
         p = [("send", b(r - 1), none)]

@@ -447,7 +447,7 @@ struct Prim {
   // drain: no data, the wait ends when the next rank has consumed everything notified so far
   // (the recv buffer is the caller's again once the completion is posted).
   bool notify, din, drain;
-  bool din_send;   // the input is the previous rank's SEND buffer (first reduce step of a direct all-reduce)
+  bool din_send;   // the input is the previous rank's SEND buffer (first reduce step of a direct all-reduce / reduce-scatter)
 };
 
 __device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos, uint32_t p, bool direct) {
@@ -466,6 +466,15 @@ __device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos,
     else if (p > last_reduce && p < 2u * R - 2) { q.din = true; q.notify = true; }    // direct recv-copy, notify
     else if (p == 2u * R - 2) q.din = true;                                           // direct recv-copy
     else if (p == 2u * R - 1) { q.recv = false; q.to_recv = false; q.drain = true; }  // drain
+    return q;
+  }
+  if (kind == KIND_RS && direct) {
+    // the reduce phase of the direct all-reduce: notify only, then the first reduce step reads the
+    // neighbour's send buffer; the drain keeps the completion behind that read
+    q.recv = p > 0 && p < R; q.send = p > 0 && p + 1 < R; q.from_send = q.recv; q.to_recv = p == R - 1;
+    if (p == 0) q.notify = true;
+    else if (p == 1) q.din_send = true;
+    else if (p == R) q.drain = true;
     return q;
   }
   if (kind == KIND_AR || kind == KIND_RS) {
@@ -582,7 +591,7 @@ __device__ __forceinline__ DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool,
   // place in the chain: broadcast starts at the root, reduce at the rank after it
   const uint32_t bpos = (rank + 2 * R - q.root - (q.kind == KIND_RD ? 1u : 0u)) % R;
   k.bc_pos = bpos == 0 ? 0 : (bpos == R - 1 ? 2 : 1);
-  if (q.flags & DFX_SQE_DIRECT) k.bc_pos |= DFX_CTX_DIRECT;   // an all-reduce / all-gather / broadcast with direct steps
+  if (q.flags & DFX_SQE_DIRECT) k.bc_pos |= DFX_CTX_DIRECT;   // a collective with direct steps
   k.priority = q.priority; k.vch = (uint16_t)vch;
   return k;
 }

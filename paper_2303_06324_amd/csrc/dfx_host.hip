@@ -557,6 +557,12 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
     t.flags |= DFX_SQE_DIRECT;
     t.nprim = (uint32_t)R + 1u;
   }
+  else if (kind == DFX_REDUCESCATTER && c->cfg.direct && count * eb * R >= c->cfg.direct_min_bytes && (count * eb) % 16 == 0) {
+    // the opening send only notifies and the next rank reads the block from the send buffer, where
+    // every block then has to be 16-byte aligned; one more step, the drain
+    t.flags |= DFX_SQE_DIRECT;
+    t.nprim = (uint32_t)R + 1u;
+  }
   else t.nprim = (uint32_t)R;
   c->pool_used += conn_bytes;
   ci.tmpl = t;

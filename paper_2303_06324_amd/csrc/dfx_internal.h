@@ -17,7 +17,7 @@
 #define DFX_CQ_CTL_WORDS 24      // 64-bit words of ring bookkeeping per vrank: reserve at 0, tail at 8, head at 16
 
 #define DFX_SQE_EXIT 1u
-#define DFX_SQE_DIRECT 2u      // all-reduce whose gather steps read the previous rank's recv buffer
+#define DFX_SQE_DIRECT 2u      // collective with direct steps (reads the previous rank's recv / send buffer instead of slots)
 #define DFX_CTX_DIRECT 0x80u   // the same, in the cooked context's bc_pos byte (bits 0-1: place in a chain)
 
 // Static context of one invocation on one rank: what the host writes into the SQ and what a

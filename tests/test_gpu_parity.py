@@ -356,6 +356,24 @@ def test_direct_allgather(dtype, count, R):
     _run(_one(wi.AG, dtype, count, R, seed=count + R), **DIRECT)
 
 
+@pytest.mark.parametrize("dtype,count,op", [(wi.F32, 4096, wi.SUM), (wi.BF16, 250000, wi.SUM), (wi.I32, 4, wi.MIN),
+                                            (wi.F16, 1 << 20, wi.MAX), (wi.F32, 1 << 20, wi.PROD), (wi.F16, 1001, wi.SUM)])
+@pytest.mark.parametrize("R", [2, 5, 8])
+def test_direct_reducescatter(dtype, count, op, R):
+    """Reduce-scatter with direct steps: the opening send only notifies and the next rank's first reduce
+    step reads the block from the send buffer; the drain holds the completion behind that read (blocks
+    that are not 16-byte multiples - the last case - keep the FIFO path)."""
+    _run(_one(wi.RS, dtype, count, R, seed=count + R, op=op), **DIRECT)
+
+
+def test_direct_reducescatter_under_forced_preemption_and_disorder():
+    """A random mix of all kinds (the reduce-scatters and all-gathers with 16-byte-multiple blocks take
+    direct steps) in one shared queue with the smallest thresholds and disordered submission: every late
+    counter preempts, the values stay the oracle's."""
+    _run(_mixed_workload(17, n_colls=24), mode="threads", timeout_s=60.0, max_channels=2,
+         chan_spread=0, scan_min=0, spin_init=1, spin_min=1, spin_max=1, spin_boost=1, **DIRECT)
+
+
 @pytest.mark.parametrize("dtype,count", [(wi.F32, 1), (wi.BF16, 250001), (wi.I32, 1 << 20), (wi.F16, 3 << 20)])
 @pytest.mark.parametrize("R,root", [(2, 1), (5, 0), (8, 3), (8, 7)])
 def test_direct_broadcast(dtype, count, R, root):

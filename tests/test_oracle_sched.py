@@ -331,6 +331,43 @@ def test_direct_gather_steps_wait_for_the_reader_before_completing():
         _check_data(S, w)
 
 
+@pytest.mark.parametrize("R", [2, 4])
+def test_direct_reduce_scatter_reads_the_send_buffer_and_drains(R):
+    """direct = True, reduce-scatter: the opening send moves nothing, the next rank's first reduce step
+    takes the block out of this rank's send buffer, and the completion (after which the caller may
+    overwrite the send buffer) waits until that read has happened; values as the data oracle's."""
+    names = [p[0] for p in sm.program(wi.RS, R, 1, 0, [(8 * j, 8 * j + 8) for j in range(R)], [(0, 8)], True)]
+    assert names == (["notify", "direct_reduce_copy", "drain"] if R == 2 else
+                     ["notify", "direct_reduce_send", "recv_reduce_send", "recv_reduce_copy", "drain"])
+    colls = [wi.CollSpec(0, wi.RS, wi.F32, 20), wi.CollSpec(1, wi.RS, wi.BF16, 9), wi.CollSpec(2, wi.AR, wi.I32, 13)]
+    for seed in range(4):
+        g = np.random.default_rng(seed)
+        orders = [list(map(int, g.permutation(len(colls)))) for _ in range(R)]
+        w = wi.Workload("direct_rs", R, colls, orders, seed=seed, cfg=95)
+        S = _system(w, sm.Policy(spin_init=2, spin_max=4, boost=2, K=2, slice_elems=8, direct=True, lookahead=2, scan=bool(seed & 1)))
+        posted = set()
+        rng = np.random.default_rng(200 + seed)
+        for _ in range(2_000_000):
+            if S.done():
+                break
+            a = int(rng.integers(0, 3 * R))
+            r = a % R
+            if a < R:
+                S.host_tick(r)
+            elif a < 2 * R:
+                S.daemons[r].mover_tick()
+            else:
+                S.daemons[r].tick()
+            for d in S.daemons:
+                for (c, seq) in d.cq:
+                    if (d.r, c) not in posted:
+                        posted.add((d.r, c))
+                        f = S.fifo[c][d.r]
+                        assert f.tail == f.head, "completion posted while the next rank still had something to read"
+        assert S.done() and S.total_cqes() == R * len(colls)
+        _check_data(S, w)
+
+
 def test_direct_broadcast_model_drains_after_the_last_slice():
     """The model's direct broadcast: one primitive per slice, one round more than slices, the drain;
     mixed with other kinds in random interleavings the values equal the data oracle's."""
