@@ -69,7 +69,11 @@ typedef struct {
   uint32_t sq_depth;       /* SQ ring entries per vrank (power of two) */
   uint32_t cq_slots;       /* CQ slot-array length per vrank (Sec. 5 "optimized CQ") */
   uint32_t nslots;         /* K: slots per connector FIFO, >= 2 (a fused recv+send ring cannot run on 1) */
-  uint32_t slot_bytes;     /* S: bytes per FIFO slot and channel, multiple of 16 (default 256 KiB) */
+  uint32_t slot_bytes;     /* S: bytes per FIFO slot and channel, multiple of 16 (default 256 KiB).  A slice is
+                              at most this long.  The chains take shorter slices, because their last rank starts
+                              R-1 slices after the first: a broadcast about 2R per channel share, a reduce 4R,
+                              of 32 KiB or more (reduce: at most 64 KiB); a broadcast with direct steps has no
+                              slots and its slices may reach 2 S.  dfx_coll_info reports the slice length */
   uint32_t chan_min_bytes; /* a collective uses C = clamp(ceil(ringChunkBytes / chan_min_bytes), 1, max_channels) channels */
   uint32_t spin_init;      /* initial spin threshold (poll attempts) at the task-queue front (Sec. 4.3) */
   uint32_t spin_min;       /* thr(pos) = max(spin_min, spin_init >> pos) */

@@ -585,6 +585,8 @@ __device__ __forceinline__ DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool,
   k.flags_in = (uint64_t)(conn + fi * DFX_FLAG_STRIDE);
   k.fifo_out = (uint64_t)(slots + fo * q.nslots * q.slot_bytes);
   k.fifo_in = (uint64_t)(slots + fi * q.nslots * q.slot_bytes);
+  // a direct broadcast has no slots (no step of it fills or reads one)
+  if (q.kind == KIND_BC && (q.flags & DFX_SQE_DIRECT)) k.fifo_out = k.fifo_in = 0;
   k.slice_elems = q.slice_elems; k.rounds = q.rounds; k.seq = q.seq;
   k.nprim = (uint16_t)q.nprim; k.nchan = q.nchan;
   k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = (uint8_t)(q.dtype | (q.op << 4));

@@ -514,12 +514,28 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
   C = std::min<uint64_t>(std::max<uint64_t>(C, 1), c->cfg.max_channels);
   uint64_t part = round_up(std::max<uint64_t>(ceil_div(block, C), 1), per16);
   C = std::max<uint64_t>(1, ceil_div(block, part));   // drop channels that would be empty
-  uint64_t slot_bytes = std::min<uint64_t>(c->cfg.slot_bytes, round_up(part * eb, 16));
+  // direct steps of a broadcast: every rank writes its recv buffer only and the next one reads it there
+  const bool bc_direct = kind == DFX_BROADCAST && R > 1 && c->cfg.direct && count * eb >= c->cfg.direct_min_bytes;
+  uint64_t slice_cap = c->cfg.slot_bytes;
+  if (rooted && R > 1) {
+    // A chain's last rank starts R-1 slices after its first, so a chain wants shorter slices than a
+    // ring, where all ranks start at once: measured best (R = 8, 2 - 256 MiB) are about 2R slices per
+    // channel share for the broadcast and 4R for the reduce, of no less than 32 KiB; the reduce, whose
+    // every hop goes through a slot, gains nothing beyond 64 KiB, while the direct broadcast uses no
+    // slots and may take slices of twice the slot size.
+    const uint64_t lo = std::min<uint64_t>(32u << 10, c->cfg.slot_bytes);
+    const uint64_t hi = kind == DFX_BROADCAST ? (bc_direct ? std::min<uint64_t>(2ull * c->cfg.slot_bytes, 1ull << 30) : c->cfg.slot_bytes)
+                                              : std::min<uint64_t>(64u << 10, c->cfg.slot_bytes);
+    const uint64_t want = round_up(part * eb / ((kind == DFX_BROADCAST ? 2 : 4) * R), 16);
+    slice_cap = std::min(std::max(want, lo), hi);
+  }
+  uint64_t slot_bytes = std::min<uint64_t>(slice_cap, round_up(part * eb, 16));
   const uint64_t slice_elems = slot_bytes / eb;
   const uint64_t rounds = std::max<uint64_t>(1, ceil_div(part, slice_elems));
   if (rounds > 0xffffffffull) return DFX_ERR_INVALID_ARG;
   const uint64_t K = c->cfg.nslots;
-  const uint64_t conn_bytes = round_up(R * C * DFX_FLAG_STRIDE + R * C * K * slot_bytes, 256);
+  // (a direct broadcast fills no slot: its connectors are the flag lines alone)
+  const uint64_t conn_bytes = round_up(R * C * DFX_FLAG_STRIDE + (bc_direct ? 0 : R * C * K * slot_bytes), 256);
   if (c->pool_used + conn_bytes > c->cfg.pool_bytes) return DFX_ERR_NO_RESOURCES;
 
   DfxStatic t;
@@ -545,9 +561,8 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
   }
   else if (rooted) {
     t.nprim = 1;   // one primitive per slice, which one depends on the place in the chain
-    if (kind == DFX_BROADCAST && c->cfg.direct && count * eb >= c->cfg.direct_min_bytes) {
-      // direct steps: every rank writes its recv buffer only and the next one reads it there; one
-      // round more than there are slices, which is the drain
+    if (bc_direct) {
+      // one round more than there are slices, which is the drain
       t.flags |= DFX_SQE_DIRECT;
       t.rounds = (uint32_t)rounds + 1u;
     }
