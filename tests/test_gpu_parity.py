@@ -356,6 +356,35 @@ def test_direct_allgather(dtype, count, R):
     _run(_one(wi.AG, dtype, count, R, seed=count + R), **DIRECT)
 
 
+def test_chain_slice_lengths():
+    """Chains take shorter slices than rings (about 2R per channel share for a broadcast, 4R for a reduce, from
+    32 KiB; reduce at most 64 KiB; a direct broadcast, which has no slots, up to twice the slot size), always
+    under the configured slot size for everything that goes through slots; the values do not depend on it: a
+    direct broadcast whose slices are twice the slot size and a reduce with the smallest slices stay bit-exact."""
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    ctx = dfx.Context(8, gh.make_config())
+    try:
+        cases = [(dfx.BROADCAST, 1 << 20, 32 << 10, 1),            # below direct_min_bytes: one 32 KiB slice, no drain
+                 (dfx.BROADCAST, 16 << 20, 32 << 10, 17),          # 512 KiB per channel: sixteen slices and the drain
+                 (dfx.BROADCAST, 64 << 20, 128 << 10, 17),
+                 (dfx.BROADCAST, 256 << 20, 512 << 10, 17),        # twice the slot size
+                 (dfx.BROADCAST, 1 << 30, 512 << 10, 65),
+                 (dfx.REDUCE, 16 << 20, 32 << 10, 16),
+                 (dfx.REDUCE, 64 << 20, 64 << 10, 32),
+                 (dfx.REDUCE, 256 << 20, 64 << 10, 128),
+                 (dfx.ALLREDUCE, 256 << 20, 256 << 10, 4)]         # rings: the slot size
+        for i, (kind, nbytes, slice_bytes, rounds) in enumerate(cases):
+            ctx.prepare(i, kind, nbytes // 4, dfx.F32, dfx.SUM, 3 if kind != dfx.ALLREDUCE else 0)
+            info = ctx.coll_info(i)
+            assert (info["slot_bytes"], info["rounds"]) == (slice_bytes, rounds), (kind, nbytes, info)
+    finally:
+        assert ctx.finalize() == dfx.OK
+    _run(_one(wi.BC, wi.F32, 1 << 19, 8, root=3, seed=5), slot_bytes=16 << 10, max_channels=2, **DIRECT)
+    _run(_one(wi.BC, wi.BF16, (1 << 20) + 3, 5, root=1, seed=6), slot_bytes=16 << 10, max_channels=2, direct=0)
+    _run(_one(wi.RD, wi.F32, (1 << 19) + 77, 8, root=6, seed=7, op=wi.MAX), slot_bytes=4 << 10, max_channels=2)
+
+
 @pytest.mark.parametrize("dtype,count,op", [(wi.F32, 4096, wi.SUM), (wi.BF16, 250000, wi.SUM), (wi.I32, 4, wi.MIN),
                                             (wi.F16, 1 << 20, wi.MAX), (wi.F32, 1 << 20, wi.PROD), (wi.F16, 1001, wi.SUM)])
 @pytest.mark.parametrize("R", [2, 5, 8])
