@@ -224,8 +224,7 @@ def size_sweep(iters: int = 10):
 def kinds_sweep(nbytes: int = 256 << 20, iters: int = 8):
     """Every collective kind at `nbytes` of largest per-rank buffer (fp32, sum, root 3 for the rooted
     ones) inside one resident daemon: time and algorithmic HBM rate.  Algorithmic bytes per kind as
-    for the all-reduce: reduce (3R-2) x message over the chain; the kinds with direct steps by what
-    those move."""
+    for the all-reduce, by what the direct steps move."""
     import torch
     import paper_2303_06324_amd as dfx
     from tests import gpu_harness as gh
@@ -233,14 +232,14 @@ def kinds_sweep(nbytes: int = 256 << 20, iters: int = 8):
     a = [torch.randn(n, device="cuda") for _ in range(R)]
     b = [torch.empty(n, device="cuda") for _ in range(R)]
     torch.cuda.synchronize()
-    # bytes each kind moves with the library's defaults at this size: all-reduce, all-gather, reduce-scatter and
-    # broadcast take the direct steps ((5R-5) x M; 2R blocks per rank; (3R-3) blocks per rank; 2R x M: every
-    # rank reads and writes the message once), the reduce the FIFO steps
+    # bytes each kind moves with the library's defaults at this size (direct steps): all-reduce (5R-5) x M;
+    # all-gather 2R blocks per rank; reduce-scatter (3R-3) blocks per rank; broadcast 2R x M (every rank reads
+    # and writes the message once); reduce (3R-4) x M (the first rank of the chain moves nothing)
     cases = [("all-reduce", dfx.ALLREDUCE, n, moved_bytes(nbytes, R)),
              ("all-gather", dfx.ALLGATHER, n // R, 2 * R * (nbytes // R) * R),
              ("reduce-scatter", dfx.REDUCESCATTER, n // R, (3 * R - 3) * (nbytes // R) * R),
              ("broadcast", dfx.BROADCAST, n, 2 * R * nbytes),
-             ("reduce", dfx.REDUCE, n, (3 * R - 2) * nbytes)]
+             ("reduce", dfx.REDUCE, n, (3 * R - 4) * nbytes)]
     rows = []
     ctx = dfx.Context(R, gh.make_config(quit_idle_us=0))
     try:

@@ -123,16 +123,16 @@ typedef struct {
   uint32_t direct;         /* 1 (default): collectives of at least direct_min_bytes (all-reduce, broadcast: per
                               rank; all-gather, reduce-scatter: all R blocks, which must be 16-byte multiples)
                               take direct steps, since all buffers lie in one HBM.  The opening send of an
-                              all-reduce or reduce-scatter only raises the connector's counter and the next
-                              rank reads that chunk from this rank's send buffer; in the gather steps (of an
+                              all-reduce, a reduce-scatter or a reduce chain (of at least direct_min_bytes
+                              per rank) only raises the connector's counter and the next rank reads that
+                              chunk from this rank's send buffer; in the gather steps (of an
                               all-reduce, an all-gather, a broadcast) a rank writes a chunk to its recv buffer
                               only and raises the counter, and the next rank reads it there; a last step waits
                               until the next rank has read everything before the completion is posted.  0:
-                              every step goes through a FIFO slot, as the primitive table of Sec. 4.2 has it
-                              (the reduce chain always does) */
+                              every step goes through a FIFO slot, as the primitive table of Sec. 4.2 has it */
   uint32_t direct_min_bytes; /* default 2 MiB: below it the extra step costs more than the saved writes; 0 = every
-                              all-reduce and broadcast, every all-gather and reduce-scatter of 16-byte-multiple
-                              blocks */
+                              all-reduce, broadcast and reduce, every all-gather and reduce-scatter of
+                              16-byte-multiple blocks */
 } dfx_config;
 
 /* Aggregated over the workgroups of one vrank since dfx_init. */

@@ -50,13 +50,14 @@ Two variations of Alg. 1 can be switched on, to ask whether they keep its livene
     queue at once; its CQE is written when that slice has been moved.
   * `scan = True`: a pass starts by evaluating the wait conditions of every queue entry and
     visits only the entries found runnable, each with the minimum threshold.
-  * `direct = True`: the gather steps of an all-reduce (and all of an all-gather) go without FIFO slots.  A rank writes a
+  * `direct = True`: the gather steps of an all-reduce (and all steps of an all-gather or a
+    broadcast) go without FIFO slots.  A rank writes a
     finished chunk to its recv buffer only and notifies the next rank (the connector's counter is
     raised, no slot is needed, so no wait for space); the next rank copies it out of that recv
     buffer; a last step (drain) waits until the next rank has consumed everything, because
     the buffers belong to the caller again once the completion is posted.  The opening send of
-    an all-reduce moves nothing either: it only notifies, and the next rank's first reduce step
-    reads the chunk from this rank's send buffer.
+    an all-reduce, a reduce-scatter or a reduce chain moves nothing either: it only notifies, and
+    the next rank's first reduce step reads the chunk from this rank's send buffer.
   * `focus = n > 0` (with scan): the runnable entries are visited furthest-along first
     (most primitives done; ties in queue order), and once n slices have been taken in the
     pass it ends with the entry in hand: every rank ranks the collectives alike, so the
@@ -72,7 +73,8 @@ import numpy as np
 
 from . import ring_data as rd
 
-AR, AG, RS, BC = 0, 1, 2, 3
+AR, AG, RS, BC, RD = 0, 1, 2, 3, 4
+CHAINS = (BC, RD)     # one primitive per slice, which one depends on the rank's place in the chain
 INF = 1 << 60
 
 # primitive name -> (needs recv, send side), send side: 0 none, 1 waits for a free slot and fills it,
@@ -201,6 +203,16 @@ def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
         if pos == R - 1:
             return [("recv_copy", none, recv_blocks[0])]
         return [("recv_copy_send", none, recv_blocks[0])]
+    if kind == RD:
+        # the reduce phase along the chain root+1 -> root+2 -> ... -> root; with direct steps the
+        # first rank only notifies and the second reads the slice out of the first one's send buffer
+        pos = (r - root - 1) % R
+        if pos == 0:
+            return [("notify" if direct else "send", blocks[0], none)]
+        first_in = "direct_reduce" if direct and pos == 1 else "recv_reduce"
+        if pos == R - 1:
+            return [(first_in + "_copy", blocks[0], recv_blocks[0])]
+        return [(first_in + "_send", blocks[0], none)]
     raise ValueError(kind)
 
 
@@ -343,7 +355,7 @@ class Daemon:
     def _prim(self, coll, g, p):
         """(name, send block, recv block) of primitive p of round g."""
         S = self.S
-        if S.policy.direct and S.colls[coll].kind == BC and S.R > 1 and g == S.rounds[coll] - 1:
+        if S.policy.direct and S.colls[coll].kind in CHAINS and S.R > 1 and g == S.rounds[coll] - 1:
             return ("drain", None, None)
         return S.progs[coll][self.r][p]
 
@@ -489,8 +501,8 @@ class System:
             sb, db, blen = layout(c, R)
             self.progs.append([program(c.kind, R, r, c.root, sb, db, policy.direct) for r in range(R)])
             self.rounds.append(max(1, -(-blen // policy.slice_elems)))
-            if policy.direct and c.kind == BC and R > 1:
-                self.rounds[-1] += 1     # the last round of a direct broadcast is the drain
+            if policy.direct and c.kind in CHAINS and R > 1:
+                self.rounds[-1] += 1     # the last round of a chain with direct steps is the drain
             self.fifo.append([Fifo(policy.K) for _ in range(R)])
         self.daemons = [Daemon(self, r) for r in range(R)]
         self.pending = [[] for _ in range(R)]   # host side: submissions not yet pushed to the SQ
@@ -531,8 +543,8 @@ class System:
         if PRIMS[name][0]:
             tag, x = fin.pop()
             # the sender's primitive index of this hop is p-1 in every ring sequence here,
-            # except the broadcast chain where every rank has a one-primitive program
-            want = (g, 0) if c.kind == BC else (g, p - 1)
+            # except the chains (broadcast, reduce) where every rank has a one-primitive program
+            want = (g, 0) if c.kind in CHAINS else (g, p - 1)
             assert tag == want, f"slice out of sequence: got {tag}, want {want}"
         if self.with_data:
             ss, ds = self._slice(sblk, g), self._slice(dblk, g)

@@ -494,10 +494,15 @@ __device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos,
     if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }                          // copy-send
     else if (p < R - 1) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
     else { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
-  } else if (kind == KIND_RD) {  // reduce chain root+1 -> root+2 -> ... -> root (bc_pos: 0 first, 1 middle, 2 the root)
+  } else if (kind == KIND_RD) {  // reduce chain root+1 -> root+2 -> ... -> root (bc_pos: 0 first, 1 middle, 2 the root, 3 second)
     if (bc_pos == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = false; }                    // send
     else if (bc_pos == 2) { q.recv = true; q.send = false; q.from_send = true; q.to_recv = true; }               // recv-reduce-copy
     else { q.recv = true; q.send = true; q.from_send = true; q.to_recv = false; }                                 // recv-reduce-send
+    if (direct) {
+      // the first rank only notifies and the second one reads the slice out of its send buffer
+      if (bc_pos == 0) { q.send = false; q.from_send = false; q.notify = true; }
+      else if (bc_pos == 3 || R == 2) q.din_send = true;
+    }
   } else if (direct) {  // broadcast chain with direct steps: every rank writes its recv buffer only
     q.send = false; q.to_recv = true;
     q.recv = bc_pos != 0; q.din = bc_pos != 0; q.from_send = bc_pos == 0; q.notify = bc_pos != 2;
@@ -509,11 +514,11 @@ __device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos,
   return q;
 }
 
-// A broadcast has one primitive per slice, so its drain cannot be a step of the per-slice
-// sequence: a direct broadcast counts one round more than it has slices, and that round is the
-// drain (nothing to move; the last rank of the chain has notified nothing and passes at once).
+// A chain (broadcast, reduce) has one primitive per slice, so its drain cannot be a step of the
+// per-slice sequence: with direct steps it counts one round more than it has slices, and that
+// round is the drain (nothing to move; the last rank of the chain has sent nothing and passes at once).
 __device__ __forceinline__ Prim chain_drain_round(Prim q, int kind, bool direct, uint32_t g, uint32_t rounds) {
-  if (direct && kind == KIND_BC && g + 1 == rounds) {
+  if (direct && (kind == KIND_BC || kind == KIND_RD) && g + 1 == rounds) {
     q.recv = q.send = q.from_send = q.to_recv = q.notify = q.din = false;
     q.drain = true;
   }
@@ -593,6 +598,7 @@ __device__ __forceinline__ DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool,
   // place in the chain: broadcast starts at the root, reduce at the rank after it
   const uint32_t bpos = (rank + 2 * R - q.root - (q.kind == KIND_RD ? 1u : 0u)) % R;
   k.bc_pos = bpos == 0 ? 0 : (bpos == R - 1 ? 2 : 1);
+  if (q.kind == KIND_RD && (q.flags & DFX_SQE_DIRECT) && bpos == 1 && R > 2) k.bc_pos = 3;   // reads the first rank's send buffer
   if (q.flags & DFX_SQE_DIRECT) k.bc_pos |= DFX_CTX_DIRECT;   // a collective with direct steps
   k.priority = q.priority; k.vch = (uint16_t)vch;
   return k;
@@ -1081,8 +1087,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 const uint4 d1 = e[7];    // dyn: recvd | preempted | cidx
                 e2c = fl; e3c = fi; e5c = ge; e6c = d0; e7c = d1;
                 Prim pq = make_prim((int)((ge.z >> 8) & 0xffu), a.R, (ge.z >> 24) & 3u, d0.y, ((ge.z >> 24) & DFX_CTX_DIRECT) != 0);
-                if (((ge.z >> 24) & DFX_CTX_DIRECT) && ((ge.z >> 8) & 0xffu) == (uint32_t)KIND_BC)
-                  pq = chain_drain_round(pq, KIND_BC, true, d0.x, e[4].w);   // bytes 64..79: fifo_in | slice_elems | rounds
+                if ((ge.z >> 24) & DFX_CTX_DIRECT)
+                  pq = chain_drain_round(pq, (int)((ge.z >> 8) & 0xffu), true, d0.x, e[4].w);   // bytes 64..79: fifo_in | slice_elems | rounds
                 const u64 f_out = ((u64)fl.w << 32) | fl.z, f_in = ((u64)fi.y << 32) | fi.x;
                 const u64 e_sent = ((u64)d0.w << 32) | d0.z, e_recvd = ((u64)d1.y << 32) | d1.x;
                 bool okr = true, oks = true;

@@ -561,7 +561,9 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
   }
   else if (rooted) {
     t.nprim = 1;   // one primitive per slice, which one depends on the place in the chain
-    if (bc_direct) {
+    // the reduce chain's direct step: the first rank only notifies, the second reads its send buffer
+    const bool rd_direct = kind == DFX_REDUCE && c->cfg.direct && count * eb >= c->cfg.direct_min_bytes;
+    if (bc_direct || rd_direct) {
       // one round more than there are slices, which is the drain
       t.flags |= DFX_SQE_DIRECT;
       t.rounds = (uint32_t)rounds + 1u;

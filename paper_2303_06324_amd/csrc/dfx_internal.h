@@ -70,7 +70,7 @@ struct alignas(16) DfxCooked {
   uint32_t slice_elems, rounds, seq;
   uint16_t nprim, nchan;
   uint8_t nslots, kind, dtype;
-  uint8_t bc_pos;        // broadcast: 0 = root, 1 = middle of the chain, 2 = last
+  uint8_t bc_pos;        // place in a chain: 0 = first, 1 = middle, 2 = last, 3 = second of a reduce chain with direct steps; | DFX_CTX_DIRECT
   int16_t priority;
   uint16_t vch;          // channel of the collective that this workgroup serves (0 .. nchan-1)
 };

@@ -356,6 +356,15 @@ def test_direct_allgather(dtype, count, R):
     _run(_one(wi.AG, dtype, count, R, seed=count + R), **DIRECT)
 
 
+@pytest.mark.parametrize("dtype,count,op", [(wi.F32, 1, wi.SUM), (wi.BF16, 250001, wi.SUM), (wi.I32, 1 << 20, wi.MIN),
+                                            (wi.F16, 3 << 20, wi.MAX), (wi.F32, 70001, wi.PROD)])
+@pytest.mark.parametrize("R,root", [(2, 1), (3, 0), (5, 4), (8, 3)])
+def test_direct_reduce(dtype, count, op, R, root):
+    """Reduce chain with its direct opening: the first rank only notifies, the second reduces out of the first
+    one's send buffer, a drain round holds the completions behind that read; only the root's buffer changes."""
+    _run(_one(wi.RD, dtype, count, R, root=root, seed=count + R, op=op), **DIRECT)
+
+
 def test_chain_slice_lengths():
     """Chains take shorter slices than rings (about 2R per channel share for a broadcast, 4R for a reduce, from
     32 KiB; reduce at most 64 KiB; a direct broadcast, which has no slots, up to twice the slot size), always
@@ -370,9 +379,10 @@ def test_chain_slice_lengths():
                  (dfx.BROADCAST, 64 << 20, 128 << 10, 17),
                  (dfx.BROADCAST, 256 << 20, 512 << 10, 17),        # twice the slot size
                  (dfx.BROADCAST, 1 << 30, 512 << 10, 65),
-                 (dfx.REDUCE, 16 << 20, 32 << 10, 16),
-                 (dfx.REDUCE, 64 << 20, 64 << 10, 32),
-                 (dfx.REDUCE, 256 << 20, 64 << 10, 128),
+                 (dfx.REDUCE, 1 << 20, 32 << 10, 1),              # below direct_min_bytes: no drain round
+                 (dfx.REDUCE, 16 << 20, 32 << 10, 17),
+                 (dfx.REDUCE, 64 << 20, 64 << 10, 33),
+                 (dfx.REDUCE, 256 << 20, 64 << 10, 129),
                  (dfx.ALLREDUCE, 256 << 20, 256 << 10, 4)]         # rings: the slot size
         for i, (kind, nbytes, slice_bytes, rounds) in enumerate(cases):
             ctx.prepare(i, kind, nbytes // 4, dfx.F32, dfx.SUM, 3 if kind != dfx.ALLREDUCE else 0)

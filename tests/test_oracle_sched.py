@@ -368,6 +368,52 @@ def test_direct_reduce_scatter_reads_the_send_buffer_and_drains(R):
         _check_data(S, w)
 
 
+@pytest.mark.parametrize("direct", [False, True])
+@pytest.mark.parametrize("R", [2, 3, 5])
+def test_reduce_chain_in_the_model(R, direct):
+    """The reduce collective as a chain root+1 -> ... -> root of one primitive per slice; with direct
+    steps the first rank only notifies, the second reads the first one's send buffer, and a drain round
+    holds every completion behind the neighbour's last read.  Only the root's recv buffer is written."""
+    blocks = [(0, 8)] * R
+    names = [sm.program(sm.RD, R, (2 + 1 + pos) % R, 2 % R, blocks, blocks, direct)[0][0] for pos in range(R)]
+    if R == 2:
+        assert names == (["notify", "direct_reduce_copy"] if direct else ["send", "recv_reduce_copy"])
+    else:
+        mid = ["recv_reduce_send"] * (R - 3)
+        assert names == (["notify", "direct_reduce_send"] + mid + ["recv_reduce_copy"] if direct else
+                         ["send", "recv_reduce_send"] + mid + ["recv_reduce_copy"])
+    colls = [wi.CollSpec(0, wi.RD, wi.F32, 37, root=1 % R), wi.CollSpec(1, wi.RD, wi.BF16, 16, root=0),
+             wi.CollSpec(2, wi.AR, wi.I32, 11), wi.CollSpec(3, wi.BC, wi.F16, 21, root=R - 1)]
+    for seed in range(3):
+        g = np.random.default_rng(seed)
+        orders = [list(map(int, g.permutation(len(colls)))) for _ in range(R)]
+        w = wi.Workload("reduce_chain", R, colls, orders, seed=seed, cfg=96)
+        S = _system(w, sm.Policy(spin_init=2, spin_max=4, boost=2, K=2, slice_elems=8, direct=direct, lookahead=2, scan=bool(seed & 1)))
+        assert S.rounds[0] == 5 + (1 if direct else 0)
+        posted = set()
+        rng = np.random.default_rng(300 + seed)
+        for _ in range(2_000_000):
+            if S.done():
+                break
+            a = int(rng.integers(0, 3 * R))
+            r = a % R
+            if a < R:
+                S.host_tick(r)
+            elif a < 2 * R:
+                S.daemons[r].mover_tick()
+            else:
+                S.daemons[r].tick()
+            if direct:
+                for d in S.daemons:
+                    for (c, seq) in d.cq:
+                        if (d.r, c) not in posted:
+                            posted.add((d.r, c))
+                            f = S.fifo[c][d.r]
+                            assert f.tail == f.head, "completion posted while the next rank still had something to read"
+        assert S.done() and S.total_cqes() == R * len(colls)
+        _check_data(S, w)
+
+
 def test_direct_broadcast_model_drains_after_the_last_slice():
     """The model's direct broadcast: one primitive per slice, one round more than slices, the drain;
     mixed with other kinds in random interleavings the values equal the data oracle's."""
