@@ -365,6 +365,42 @@ def test_direct_reduce(dtype, count, op, R, root):
     _run(_one(wi.RD, dtype, count, R, root=root, seed=count + R, op=op), **DIRECT)
 
 
+@pytest.mark.parametrize("quit_idle_us", [0, 200])
+def test_direct_steps_of_every_kind_survive_stop_and_quit(quit_idle_us):
+    """One collective of every kind with direct steps, stuck because two ranks have not submitted: the daemon
+    is stopped (or leaves by itself when idle), started again, the missing ranks submit, and the values are
+    the oracle's: saved positions, claimed counters and the buffer addresses published in the connectors
+    outlive the grid (Sec. 4.4, 4.5)."""
+    import time
+    from tests import gpu_harness as gh
+    import paper_2303_06324_amd as dfx
+    R = 8
+    colls = [wi.CollSpec(0, wi.AR, wi.F32, 300000), wi.CollSpec(1, wi.AG, wi.BF16, 40000), wi.CollSpec(2, wi.RS, wi.F16, 48000, 0, wi.MAX),
+             wi.CollSpec(3, wi.BC, wi.I32, 250001, 3), wi.CollSpec(4, wi.RD, wi.F32, 270001, 5, wi.SUM)]
+    w = wi.Workload("stop_direct", R, colls, [list(range(5))] * R, seed=91, cfg=50)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(R, gh.make_config(quit_idle_us=quit_idle_us, slot_bytes=16 << 10, **DIRECT))
+    try:
+        gh.prepare_all(ctx, w)
+        for ci in range(5):
+            for r in range(6):
+                assert ctx.submit(r, ci, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr()) == dfx.OK
+        time.sleep(0.02)
+        if quit_idle_us == 0:
+            assert ctx.stop() == dfx.OK
+            assert ctx.start() == dfx.OK
+        else:
+            assert ctx.stats(0)["quits"] > 0           # left by itself, with everything outstanding
+        for ci in (4, 2, 0, 3, 1):
+            for r in (7, 6):
+                assert ctx.submit(r, ci, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr()) == dfx.OK
+        assert ctx.wait_all(20.0) == dfx.OK
+        for ci in range(5):
+            _check(dw, w, ci)
+    finally:
+        assert ctx.finalize() == dfx.OK
+
+
 def test_chain_slice_lengths():
     """Chains take shorter slices than rings (about 2R per channel share for a broadcast, 4R for a reduce, from
     32 KiB; reduce at most 64 KiB; a direct broadcast, which has no slots, up to twice the slot size), always
