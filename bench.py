@@ -234,12 +234,12 @@ def kinds_sweep(nbytes: int = 256 << 20, iters: int = 8):
     torch.cuda.synchronize()
     # bytes each kind moves with the library's defaults at this size (direct steps): all-reduce (5R-5) x M;
     # all-gather 2R blocks per rank; reduce-scatter (3R-3) blocks per rank; broadcast 2R x M (every rank reads
-    # and writes the message once); reduce (3R-4) x M (the first rank of the chain moves nothing)
+    # and writes the message once); reduce (3R-3) x M (the first rank of the chain moves nothing)
     cases = [("all-reduce", dfx.ALLREDUCE, n, moved_bytes(nbytes, R)),
              ("all-gather", dfx.ALLGATHER, n // R, 2 * R * (nbytes // R) * R),
              ("reduce-scatter", dfx.REDUCESCATTER, n // R, (3 * R - 3) * (nbytes // R) * R),
              ("broadcast", dfx.BROADCAST, n, 2 * R * nbytes),
-             ("reduce", dfx.REDUCE, n, (3 * R - 4) * nbytes)]
+             ("reduce", dfx.REDUCE, n, (3 * R - 3) * nbytes)]
     rows = []
     ctx = dfx.Context(R, gh.make_config(quit_idle_us=0))
     try:
