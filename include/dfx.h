@@ -120,11 +120,11 @@ typedef struct {
                               that all ranks carry the same few collectives through instead of advancing all
                               of them side by side (whose FIFO slots together outgrow the memory-side cache);
                               0 = every runnable collective once per pass, in queue order */
-  uint32_t direct;         /* 1 (default): collectives of at least direct_min_bytes (all-reduce, broadcast: per
-                              rank; all-gather, reduce-scatter: all R blocks, which must be 16-byte multiples)
-                              take direct steps, since all buffers lie in one HBM.  The opening send of an
-                              all-reduce, a reduce-scatter or a reduce chain (of at least direct_min_bytes
-                              per rank) only raises the connector's counter and the next rank reads that
+  uint32_t direct;         /* 1 (default): collectives of at least direct_min_bytes (all-reduce, broadcast,
+                              reduce: per rank; all-gather, reduce-scatter: all R blocks, which must be
+                              16-byte multiples) take direct steps, since all buffers lie in one HBM.  The
+                              opening send of an all-reduce, a reduce-scatter or a reduce chain only raises
+                              the connector's counter and the next rank reads that
                               chunk from this rank's send buffer; in the gather steps (of an
                               all-reduce, an all-gather, a broadcast) a rank writes a chunk to its recv buffer
                               only and raises the counter, and the next rank reads it there; a last step waits
