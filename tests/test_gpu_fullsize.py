@@ -65,6 +65,76 @@ def test_config2_largest_size_sampled():
         assert np.all(np.abs(got.astype(np.float64) - ref) <= 1e-6 * rd.abs_sum_f64(blocks, rd.F32))
 
 
+def test_other_kinds_at_the_largest_size():
+    """All-gather, reduce-scatter, broadcast and reduce at 256 MiB of largest per-rank buffer, fp32, library
+    defaults (the configuration of the bench's table of kinds: direct steps, several slices per channel share,
+    512 KiB / 64 KiB slices for the chains).  All-gather and broadcast are compared whole, on the device, with
+    their definitions (concatenation / the root's buffer); the reducing kinds on sampled windows that the oracle
+    folds one by one; buffers a kind must not write keep their fill pattern."""
+    import torch
+    import paper_2303_06324_amd as dfx
+    R, n, root = 8, (256 << 20) // 4, 3
+    blk = n // R
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4321)
+    send = [torch.randn(n, device="cuda", dtype=torch.float32, generator=g) for _ in range(R)]
+    recv = [torch.empty(n, device="cuda", dtype=torch.float32) for _ in range(R)]
+    rng = np.random.default_rng(11)
+
+    def run(ctx, cid):
+        for t in recv:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        for r in reversed(range(R)):
+            assert ctx.submit(r, cid, send[r].data_ptr(), recv[r].data_ptr()) == dfx.OK
+        assert ctx.wait_all(30.0) == dfx.OK
+
+    def windows(length, nwin=24, width=4096):
+        wins = [(0, width), (length - width, length)]
+        wins += [(lo, lo + width) for lo in map(int, rng.integers(0, length - width, size=nwin))]
+        return wins
+
+    ctx = dfx.Context(R)
+    try:
+        ctx.prepare(0, dfx.ALLGATHER, blk, dfx.F32)
+        ctx.prepare(1, dfx.REDUCESCATTER, blk, dfx.F32)
+        ctx.prepare(2, dfx.BROADCAST, n, dfx.F32, dfx.SUM, root)
+        ctx.prepare(3, dfx.REDUCE, n, dfx.F32, dfx.SUM, root)
+        assert ctx.coll_info(0)["rounds"] == 4 and ctx.coll_info(0)["nprim"] == R + 1
+        assert ctx.coll_info(1)["rounds"] == 4 and ctx.coll_info(1)["nprim"] == R + 1
+
+        run(ctx, 0)                                  # all-gather: every rank ends with the concatenation
+        want = torch.cat([s[:blk] for s in send])
+        for r in range(R):
+            assert torch.equal(recv[r].view(torch.int32), want.view(torch.int32)), r
+        del want
+
+        run(ctx, 2)                                  # broadcast: every rank ends with the root's buffer
+        for r in range(R):
+            assert torch.equal(recv[r].view(torch.int32), send[root].view(torch.int32)), r
+
+        run(ctx, 1)                                  # reduce-scatter: rank r ends with block r, folded from rank r+1 on
+        for r in range(R):
+            assert bool(torch.isnan(recv[r][blk:]).all()), r        # nothing written beyond the block
+            for lo, hi in windows(blk, nwin=6):
+                blocks = [s[r * blk + lo:r * blk + hi].cpu().numpy() for s in send]
+                got = recv[r][lo:hi].cpu().numpy()
+                want_w = rd.fold_rotated(blocks, r + 1, rd.F32)
+                assert np.array_equal(got.view(np.uint32), want_w.view(np.uint32)), (r, lo, hi)
+
+        run(ctx, 3)                                  # reduce: the root ends with the fold along the chain root+1 .. root
+        for r in range(R):
+            if r != root:
+                assert bool(torch.isnan(recv[r]).all()), r
+        for lo, hi in windows(n):
+            blocks = [s[lo:hi].cpu().numpy() for s in send]
+            got = recv[root][lo:hi].cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), rd.reduce_fold(blocks, root, rd.F32).view(np.uint32)), (lo, hi)
+        ctx.stop()
+    finally:
+        ctx.finalize()
+
+
 def test_config3_full_bf16_buckets_random_orders():
     """16 bf16 buckets of 25 MiB, every rank submitting in its own random order."""
     from tests import gpu_harness as gh
