@@ -401,6 +401,17 @@ def test_direct_steps_of_every_kind_survive_stop_and_quit(quit_idle_us):
         assert ctx.finalize() == dfx.OK
 
 
+@pytest.mark.parametrize("knobs", [dict(), dict(window=1), dict(window=4, nslots=8), dict(nslots=2)])
+@pytest.mark.parametrize("kind", [wi.AR, wi.AG, wi.RS, wi.BC, wi.RD])
+def test_direct_steps_over_many_slices_and_windows(kind, knobs):
+    """Direct steps with many slices per channel share (16 KiB slots, four channels: 16-32 slices, a ragged
+    last one) in windows of one, two and four and with the fewest slots: the notify counters run far ahead
+    of the slots, the drain waits for all of it, and the values are the oracle's."""
+    count = (1 << 18) + 24 if kind in (wi.AG, wi.RS) else (1 << 20) + 100
+    _run(_one(kind, wi.F32, count, 8, root=5, seed=kind + 40), slot_bytes=16 << 10, max_channels=4, **DIRECT, **knobs)
+    _run(_one(kind, wi.BF16, count, 3, root=2, seed=kind + 50, op=wi.MAX), slot_bytes=16 << 10, max_channels=4, **DIRECT, **knobs)
+
+
 def test_chain_slice_lengths():
     """Chains take shorter slices than rings (about 2R per channel share for a broadcast, 4R for a reduce, from
     32 KiB; reduce at most 64 KiB; a direct broadcast, which has no slots, up to twice the slot size), always
