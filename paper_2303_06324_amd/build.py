@@ -32,5 +32,24 @@ def build(verbose: bool = False) -> str:
     return out
 
 
+def build_c_client() -> str:
+    """The plain C client of the boundary (tests/c_abi/c_client.c: gcc, no Python, no PyTorch) that the GPU
+    tests run; links against the library built above."""
+    root = os.path.dirname(HERE)
+    src = os.path.join(root, "tests", "c_abi", "c_client.c")
+    out = os.path.join(root, "tests", "c_abi", "c_client.bin")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(root, "include"),
+           "-I" + os.path.join(rocm, "include"), src, "-o", out + ".tmp", "-L" + HERE, "-ldfx",
+           "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2303_06324_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed:\n" + " ".join(cmd) + "\n" + res.stderr)
+    os.replace(out + ".tmp", out)
+    return out
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_c_client())

@@ -66,3 +66,14 @@ def test_product_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 txt = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in txt, f"{f} mentions the oracle"
+
+
+def test_c_client_is_built_against_the_library():
+    """The plain C client of the boundary (built by build(), run by a GPU test) exists and resolves the
+    library through its run path."""
+    import subprocess
+    exe = os.path.join(ROOT, "tests", "c_abi", "c_client.bin")
+    assert os.path.exists(exe), "run python -m paper_2303_06324_amd.build first"
+    out = subprocess.run(["ldd", exe], capture_output=True, text=True, timeout=60).stdout
+    line = [l for l in out.splitlines() if "libdfx.so" in l]
+    assert line and "paper_2303_06324_amd/libdfx.so" in line[0] and "not found" not in line[0], out
