@@ -412,6 +412,32 @@ def test_direct_steps_over_many_slices_and_windows(kind, knobs):
     _run(_one(kind, wi.BF16, count, 3, root=2, seed=kind + 50, op=wi.MAX), slot_bytes=16 << 10, max_channels=4, **DIRECT, **knobs)
 
 
+@pytest.mark.parametrize("block", range(4))
+def test_random_mixes_under_random_knobs(block):
+    """Eight random mixes per case (kinds, dtypes, reducing functions, ragged sizes, roots, per-rank orders and
+    delays), each under a random draw of the scheduler's knobs (direct steps at every size or from the default
+    threshold, window, workgroup map, forced preemption, one shared queue, slot size and count, focused
+    passes) and, for half of them, with all-gather / reduce-scatter blocks rounded to 16-byte multiples so
+    that those take the direct steps too.  (Scaled-down form of a 1 900-seed run of the same generator.)"""
+    rng = np.random.default_rng(9100 + block)
+    for seed in range(5000 + 8 * block, 5008 + 8 * block):
+        knobs = {}
+        if rng.integers(0, 4) != 0: knobs["direct_min_bytes"] = 0
+        if rng.integers(0, 2): knobs["window"] = int(rng.choice([1, 2]))
+        if rng.integers(0, 3) == 0: knobs["wg_map"] = 1
+        if rng.integers(0, 3) == 0: knobs.update(spin_init=1, spin_min=1, spin_max=1, spin_boost=1)
+        if rng.integers(0, 3) == 0: knobs.update(max_channels=int(rng.choice([1, 2, 8])), chan_spread=0)
+        if rng.integers(0, 3) == 0: knobs["slot_bytes"] = int(rng.choice([4096, 16384, 65536]))
+        if rng.integers(0, 4) == 0: knobs["focus_bytes"] = 0
+        if rng.integers(0, 4) == 0: knobs["nslots"] = 2
+        w = _mixed_workload(seed, n_colls=int(rng.integers(8, 40)))
+        if rng.integers(0, 2):
+            colls = [wi.CollSpec(c.coll_id, c.kind, c.dtype, max(8, c.count // 8 * 8) if c.kind in (wi.AG, wi.RS) else c.count,
+                                 c.root, c.op) for c in w.colls]
+            w = wi.Workload(w.name + "_aligned", w.R, colls, w.orders, delays_us=w.delays_us, seed=seed, cfg=44)
+        _run(w, mode="threads" if rng.integers(0, 2) else "roundrobin", timeout_s=60.0, **knobs)
+
+
 def test_chain_slice_lengths():
     """Chains take shorter slices than rings (about 2R per channel share for a broadcast, 4R for a reduce, from
     32 KiB; reduce at most 64 KiB; a direct broadcast, which has no slots, up to twice the slot size), always
