@@ -9,10 +9,13 @@
 // and switch to the next collective.  Completion is counted per collective; the last channel
 // posts the CQE.  Connectors are FIFOs of K slots in HBM guarded by monotone tail/head
 // counters; a primitive touches nothing before both its conditions hold (Sec. 4.1, 4.5).
-// The copy steps of long all-reduces, mid-size all-gathers and broadcasts skip the slot: the
-// result goes to the rank's recv buffer only (through the coherent path described below), the
-// counter is raised all the same, and the next rank reads the chunk from that recv buffer; a
-// last step waits until it has read them all (see Prim::notify / din / drain).
+// Long collectives take direct steps, because every rank's buffers lie in the same HBM: in
+// the copy steps (gather phase of an all-reduce, all-gather, broadcast) the result goes to the
+// rank's recv buffer only (through the coherent path described below), the counter is raised
+// all the same, and the next rank reads the chunk from that recv buffer; the opening send of
+// a reduce phase (all-reduce, reduce-scatter, reduce chain) moves nothing, the next rank reads
+// the chunk from this rank's send buffer; a last step waits until the neighbour has read
+// everything (see Prim::notify / din / din_send / drain).
 //
 // Memory-model rules used here (AMDGPU, one agent with one L2 per XCD), two connector modes:
 //   device-coherent accesses (fifo_coherent = 1, the default)
