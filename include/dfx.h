@@ -130,7 +130,10 @@ typedef struct {
                               only and raises the counter, and the next rank reads it there; a last step waits
                               until the next rank has read everything before the completion is posted.  0:
                               every step goes through a FIFO slot, as the primitive table of Sec. 4.2 has it */
-  uint32_t direct_min_bytes; /* default 2 MiB: below it the extra step costs more than the saved writes; 0 = every
+  uint32_t direct_min_bytes; /* default 2 MiB: below it the extra step costs more than the saved writes (the measured
+                              break-even of an all-reduce per rank and of an all-gather in all; a reduce-scatter
+                              takes the direct steps from twice this value in all, a broadcast or reduce from a
+                              quarter of it per rank); 0 = every
                               all-reduce, broadcast and reduce, every all-gather and reduce-scatter of
                               16-byte-multiple blocks */
 } dfx_config;

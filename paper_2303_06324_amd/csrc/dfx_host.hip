@@ -515,7 +515,8 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
   uint64_t part = round_up(std::max<uint64_t>(ceil_div(block, C), 1), per16);
   C = std::max<uint64_t>(1, ceil_div(block, part));   // drop channels that would be empty
   // direct steps of a broadcast: every rank writes its recv buffer only and the next one reads it there
-  const bool bc_direct = kind == DFX_BROADCAST && R > 1 && c->cfg.direct && count * eb >= c->cfg.direct_min_bytes;
+  // (measured break-even points: the rings at direct_min_bytes, a reduce-scatter at twice that, the chains at a quarter)
+  const bool bc_direct = kind == DFX_BROADCAST && R > 1 && c->cfg.direct && count * eb >= c->cfg.direct_min_bytes / 4;
   uint64_t slice_cap = c->cfg.slot_bytes;
   if (rooted && R > 1) {
     // A chain's last rank starts R-1 slices after its first, so a chain wants shorter slices than a
@@ -562,7 +563,7 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
   else if (rooted) {
     t.nprim = 1;   // one primitive per slice, which one depends on the place in the chain
     // the reduce chain's direct step: the first rank only notifies, the second reads its send buffer
-    const bool rd_direct = kind == DFX_REDUCE && c->cfg.direct && count * eb >= c->cfg.direct_min_bytes;
+    const bool rd_direct = kind == DFX_REDUCE && c->cfg.direct && count * eb >= c->cfg.direct_min_bytes / 4;
     if (bc_direct || rd_direct) {
       // one round more than there are slices, which is the drain
       t.flags |= DFX_SQE_DIRECT;
@@ -574,7 +575,7 @@ int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype 
     t.flags |= DFX_SQE_DIRECT;
     t.nprim = (uint32_t)R + 1u;
   }
-  else if (kind == DFX_REDUCESCATTER && c->cfg.direct && count * eb * R >= c->cfg.direct_min_bytes && (count * eb) % 16 == 0) {
+  else if (kind == DFX_REDUCESCATTER && c->cfg.direct && count * eb * R >= 2ull * c->cfg.direct_min_bytes && (count * eb) % 16 == 0) {
     // the opening send only notifies and the next rank reads the block from the send buffer, where
     // every block then has to be 16-byte aligned; one more step, the drain
     t.flags |= DFX_SQE_DIRECT;

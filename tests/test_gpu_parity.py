@@ -447,12 +447,13 @@ def test_chain_slice_lengths():
     import paper_2303_06324_amd as dfx
     ctx = dfx.Context(8, gh.make_config())
     try:
-        cases = [(dfx.BROADCAST, 1 << 20, 32 << 10, 1),            # below direct_min_bytes: one 32 KiB slice, no drain
+        cases = [(dfx.BROADCAST, 256 << 10, 16 << 10, 1),          # below the chains' direct threshold (direct_min_bytes / 4): no drain
+                 (dfx.BROADCAST, 1 << 20, 32 << 10, 2),            # one 32 KiB slice per channel and the drain
                  (dfx.BROADCAST, 16 << 20, 32 << 10, 17),          # 512 KiB per channel: sixteen slices and the drain
                  (dfx.BROADCAST, 64 << 20, 128 << 10, 17),
                  (dfx.BROADCAST, 256 << 20, 512 << 10, 17),        # twice the slot size
                  (dfx.BROADCAST, 1 << 30, 512 << 10, 65),
-                 (dfx.REDUCE, 1 << 20, 32 << 10, 1),              # below direct_min_bytes: no drain round
+                 (dfx.REDUCE, 256 << 10, 16 << 10, 1),            # below the threshold: no drain round
                  (dfx.REDUCE, 16 << 20, 32 << 10, 17),
                  (dfx.REDUCE, 64 << 20, 64 << 10, 33),
                  (dfx.REDUCE, 256 << 20, 64 << 10, 129),
