@@ -371,6 +371,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (virtual ranks share it); --gpus must be 1")
+    from paper_2303_06324_amd import build as _b
+    _b.ensure_built()          # loads what is built; builds only if nothing is
 
     import torch
     import paper_2303_06324_amd as dfx

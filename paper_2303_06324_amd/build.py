@@ -50,6 +50,14 @@ def build_c_client() -> str:
     return out
 
 
+def ensure_built() -> None:
+    """Build what is missing and nothing else (tests, smoke and the bench load what is there)."""
+    if not os.path.exists(LIB):
+        build()
+    if not os.path.exists(os.path.join(os.path.dirname(HERE), "tests", "c_abi", "c_client.bin")):
+        build_c_client()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
     print(build_c_client())

@@ -77,3 +77,18 @@ def test_c_client_is_built_against_the_library():
     out = subprocess.run(["ldd", exe], capture_output=True, text=True, timeout=60).stdout
     line = [l for l in out.splitlines() if "libdfx.so" in l]
     assert line and "paper_2303_06324_amd/libdfx.so" in line[0] and "not found" not in line[0], out
+
+
+def test_build_module_runs_without_the_library():
+    """Importing the package or its build module does not load the binding (which needs the built library), so
+    the build can run in a tree that has no library yet; any use of the binding loads it, and fails loudly
+    when the library is missing."""
+    import subprocess
+    import sys
+    code = ("import sys, paper_2303_06324_amd, paper_2303_06324_amd.build; "
+            "assert 'paper_2303_06324_amd.binding' not in sys.modules; "
+            "paper_2303_06324_amd.ALLREDUCE; assert 'paper_2303_06324_amd.binding' in sys.modules")
+    res = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0, res.stderr
+    src = open(os.path.join(ROOT, "paper_2303_06324_amd", "binding.py")).read()
+    assert "raise ImportError" in src and "no CPU fallback" in src
