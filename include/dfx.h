@@ -311,6 +311,11 @@ int dfx_last_init_error(void);
 
 const char* dfx_strerror(int status);
 
+/* Identifier of the sources this library was built from (a hash of the kernel and host sources, this
+   header and the compiler flags, baked in at build time): lets a loader notice a library that is
+   older than the sources beside it.  Points to static storage. */
+const char* dfx_build_id(void);
+
 /* Measurement aid, not part of the method: copy `bytes` (multiple of 16) from src to dst (both
    device) with a plain grid-stride kernel on hip_stream (NULL = the null stream) and wait.  Its
    known traffic calibrates the profiler's HBM byte counters; with ms != NULL (host) the kernel is

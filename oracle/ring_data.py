@@ -248,6 +248,44 @@ def _run(ranks: Sequence[_Rank]) -> None:
         assert len(k.q_in) == 0, "a connector still holds data: something was sent but never received"
 
 
+def _run_threaded(ranks: Sequence[_Rank], nthreads: int, timeout_s: float = 600.0) -> None:
+    """The same sequences with the ranks dealt to `nthreads` worker threads (rank r belongs to thread
+    r mod nthreads; one thread per rank when there are enough).  Each thread steps its own ranks and
+    yields when none of them can move; only the schedule differs from _run, every rank still runs its
+    primitives in order and an edge's queue has one producer and one consumer, so the values are the same.
+    For timing the replay on several host cores (numpy releases the interpreter lock inside large array
+    operations)."""
+    import threading
+    import time as _time
+    errors: list = []
+    deadline = _time.monotonic() + timeout_s
+
+    def work(t):
+        mine = [k for k in ranks if k.r % nthreads == t]
+        try:
+            while any(k.pc < len(k.prog) for k in mine):
+                moved = False
+                for k in mine:
+                    while k.step():
+                        moved = True
+                if not moved:
+                    if errors or _time.monotonic() > deadline:
+                        raise RuntimeError("threaded ring replay stalled")
+                    _time.sleep(0)
+        except Exception as e:   # noqa: BLE001
+            errors.append(e)
+
+    ts = [threading.Thread(target=work, args=(t,)) for t in range(nthreads)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    if errors:
+        raise errors[0]
+    for k in ranks:
+        assert len(k.q_in) == 0, "a connector still holds data: something was sent but never received"
+
+
 def _make_ranks(sends, recv_elems, dtype, op=SUM):
     R = len(sends)
     queues = [deque() for _ in range(R)]          # queues[r] = edge r -> r+1
@@ -259,7 +297,9 @@ def _make_ranks(sends, recv_elems, dtype, op=SUM):
 # ----------------------------------------------------------------------------
 # all-reduce
 # ----------------------------------------------------------------------------
-def all_reduce_replay(sends: Sequence[np.ndarray], dtype: int, op: int = SUM) -> List[np.ndarray]:
+def all_reduce_replay(sends: Sequence[np.ndarray], dtype: int, op: int = SUM, threads: int = 0) -> List[np.ndarray]:
+    """threads = 0: the ranks are stepped round-robin by the caller's thread; threads > 0: by that many
+    worker threads (same values, see _run_threaded)."""
     R, N = len(sends), len(sends[0])
     ranks, recvs = _make_ranks(sends, N, dtype, op)
     if R == 1:
@@ -279,7 +319,10 @@ def all_reduce_replay(sends: Sequence[np.ndarray], dtype: int, op: int = SUM) ->
         k.prog.append(("recv_copy", None, ch(r + 1)))
         # primitives without a send-buffer / recv-buffer side get a dummy range
         k.prog = [(n, s or (0, 0), d or (0, 0)) for n, s, d in k.prog]
-    _run(ranks)
+    if threads > 0:
+        _run_threaded(ranks, min(threads, R))
+    else:
+        _run(ranks)
     return recvs
 
 

@@ -62,6 +62,11 @@ def _load() -> C.CDLL:
         import torch  # noqa: F401
     except ImportError:
         pass
+    from . import build as _build
+    have, want = _build.built_id(LIB_PATH), _build.source_id()
+    if have != want:
+        raise ImportError(f"{LIB_PATH} was built from other sources (id {have}, sources {want}): rebuild it "
+                          "(python -m paper_2303_06324_amd.build)")
     lib = C.CDLL(LIB_PATH)
     vp, i, u64, sz = C.c_void_p, C.c_int, C.c_uint64, C.c_size_t
     sig = {
@@ -86,6 +91,7 @@ def _load() -> C.CDLL:
         "dfx_last_hip_error": ([vp], i),
         "dfx_last_init_error": ([], i),
         "dfx_strerror": ([i], C.c_char_p),
+        "dfx_build_id": ([], C.c_char_p),
         "dfx_copy_calibrate": ([vp, vp, sz, vp, C.POINTER(C.c_float)], i),
     }
     for name, (args, res) in sig.items():
@@ -95,6 +101,10 @@ def _load() -> C.CDLL:
 
 
 _lib = _load()
+
+
+def build_id() -> str:
+    return _lib.dfx_build_id().decode()
 
 
 def strerror(status: int) -> str:

@@ -395,8 +395,8 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   if (cfg.window != 1 && cfg.window != 2 && cfg.window != 4) return DFX_ERR_INVALID_ARG;
   // A ring of fused recv+send primitives that has sent `window` slices ahead on every edge needs one
   // more free slot to take its next step: with window >= nslots every connector fills and nobody can move.
-  while (cfg.window >= cfg.nslots) cfg.window /= 2;
   if (!is_pow2(cfg.nslots) || cfg.nslots < 2 || cfg.nslots > 64) return DFX_ERR_INVALID_ARG;
+  while (cfg.window >= cfg.nslots) cfg.window /= 2;
   if (cfg.slot_bytes < 16 || (cfg.slot_bytes & 15u)) return DFX_ERR_INVALID_ARG;
   if (cfg.chan_min_bytes < 16) return DFX_ERR_INVALID_ARG;
   if (cfg.spin_min < 1 || cfg.spin_init < 1 || cfg.spin_boost < 1 || cfg.spin_max < cfg.spin_min) return DFX_ERR_INVALID_ARG;
@@ -969,6 +969,14 @@ int dfx_finalize(dfx_ctx* c) {
 int dfx_last_hip_error(dfx_ctx* c) { return c ? c->last_hip : 0; }
 
 int dfx_last_init_error(void) { return g_init_hip_error; }
+
+#ifndef DFX_BUILD_ID_STR
+#define DFX_BUILD_ID_STR "unknown"
+#endif
+const char* dfx_build_id(void) {
+  static const char id[] = "DFX_BUILD_ID=" DFX_BUILD_ID_STR;
+  return id + 13;
+}
 
 const char* dfx_strerror(int s) {
   switch (s) {

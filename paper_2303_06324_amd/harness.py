@@ -16,6 +16,7 @@ import paper_2303_06324_amd as dfx
 import workload_inputs as wi
 
 SENTINEL = 0xA5
+GUARD = 4096        # bytes of fill pattern in front of and behind every recv buffer
 
 
 def make_config(**kw) -> "dfx.Config":
@@ -28,17 +29,27 @@ def make_config(**kw) -> "dfx.Config":
 
 
 class DeviceWorkload:
-    """Send/recv buffers of a Workload resident on the GPU."""
+    """Send/recv buffers of a Workload resident on the GPU.
 
-    def __init__(self, w: wi.Workload, colls: Optional[Sequence[int]] = None, keep_host: bool = True):
+    Every recv buffer lies between two guard zones of GUARD bytes that hold the fill pattern, so that a
+    store outside the buffer (a tail that overruns, a slice that starts early) shows; check_untouched()
+    looks at them and compares every send buffer with the bytes that were uploaded."""
+
+    def __init__(self, w: wi.Workload, colls: Optional[Sequence[int]] = None, keep_host: bool = True,
+                 sends: Optional[Dict[int, List[np.ndarray]]] = None):
+        """sends: host send buffers per collective index (storage dtype), for inputs that the seeded recipe of
+        workload_inputs does not draw (constructed values); default: wi.all_sends."""
         self.w = w
         self.idx = list(range(len(w.colls))) if colls is None else list(colls)
         self.send_host: Dict[int, List[np.ndarray]] = {}
         self.send: Dict[int, List[torch.Tensor]] = {}
-        self.recv: Dict[int, List[torch.Tensor]] = {}
+        self.recv: Dict[int, List[torch.Tensor]] = {}       # the payload views (what the library is given)
+        self._recv_alloc: Dict[int, List[torch.Tensor]] = {}  # guard | payload | guard
+        self._recv_bytes: Dict[int, int] = {}
         for ci in self.idx:
             c = w.colls[ci]
-            hs = wi.all_sends(w, ci)
+            hs = sends[ci] if sends is not None else wi.all_sends(w, ci)
+            assert len(hs) == w.R and all(h.size == c.send_elems(w.R) for h in hs)
             if keep_host:
                 self.send_host[ci] = hs
             self.send[ci] = []
@@ -49,8 +60,10 @@ class DeviceWorkload:
                     t[:b.size].copy_(torch.from_numpy(b))
                 self.send[ci].append(t)
             nbytes = c.recv_elems(w.R) * wi.ELEM_BYTES[c.dtype]
-            self.recv[ci] = [torch.full((max(nbytes, 16),), SENTINEL, dtype=torch.uint8, device="cuda")
-                             for _ in range(w.R)]
+            self._recv_bytes[ci] = nbytes
+            self._recv_alloc[ci] = [torch.full((GUARD + max(nbytes, 16) + GUARD,), SENTINEL, dtype=torch.uint8, device="cuda")
+                                    for _ in range(w.R)]
+            self.recv[ci] = [t[GUARD:GUARD + max(nbytes, 16)] for t in self._recv_alloc[ci]]
         torch.cuda.synchronize()
         # the per-rank bursts of the workload's own issue orders, marshalled once (kept out of timed regions)
         self.bursts = None
@@ -63,14 +76,31 @@ class DeviceWorkload:
 
     def reset_recv(self):
         for ci in self.idx:
-            for t in self.recv[ci]:
+            for t in self._recv_alloc[ci]:
                 t.fill_(SENTINEL)
         torch.cuda.synchronize()
 
     def results(self, ci: int) -> List[np.ndarray]:
         c = self.w.colls[ci]
-        nbytes = c.recv_elems(self.w.R) * wi.ELEM_BYTES[c.dtype]
+        nbytes = self._recv_bytes[ci]
         return [t[:nbytes].cpu().numpy().view(wi.NP_STORAGE[c.dtype]) for t in self.recv[ci]]
+
+    def check_untouched(self):
+        """Nothing outside the recv buffers was written and no send buffer changed (the direct steps hand
+        send buffers to the neighbour's movers, which must only read them)."""
+        torch.cuda.synchronize()
+        for ci in self.idx:
+            nbytes = self._recv_bytes[ci]
+            for r, t in enumerate(self._recv_alloc[ci]):
+                if not bool((t[:GUARD] == SENTINEL).all()):
+                    raise AssertionError(f"{self.w.name} coll {ci} rank {r}: bytes in front of the recv buffer were written")
+                if not bool((t[GUARD + nbytes:] == SENTINEL).all()):
+                    raise AssertionError(f"{self.w.name} coll {ci} rank {r}: bytes behind the recv buffer were written")
+            if ci in self.send_host:
+                for r, h in enumerate(self.send_host[ci]):
+                    b = h.view(np.uint8)
+                    if b.size and not torch.equal(self.send[ci][r][:b.size], torch.from_numpy(b).to("cuda")):
+                        raise AssertionError(f"{self.w.name} coll {ci} rank {r}: the send buffer changed")
 
 
 def prepare_all(ctx: "dfx.Context", w: wi.Workload, colls: Optional[Sequence[int]] = None, priorities=None):
@@ -156,6 +186,7 @@ def run_workload(w: wi.Workload, cfg=None, mode: str = "roundrobin", timeout_s: 
         stats = [ctx.stats(r) for r in range(w.R)]
         if rc != dfx.OK:
             raise dfx.DfxError(rc, f"dfx_wait_all (stop={stop_rc}, stats0={stats[0]})")
+        dw.check_untouched()
     except Exception:
         try:                      # leave a trace of where every vrank stood
             ctx.stop()

@@ -49,6 +49,10 @@ def test_argument_validation_without_gpu():
     bad = dfx.config_default()
     bad.nslots = 1          # a one-slot connector cannot run a fused recv+send ring
     assert lib.dfx_init(ctypes.byref(h), 8, ctypes.byref(bad), None) == dfx.ERR_INVALID_ARG
+    for k in (0, 1, 3, 128):    # not a power of two in 2 .. 64 (0 once sent the window clamp into an endless loop)
+        bad = dfx.config_default()
+        bad.nslots = k
+        assert lib.dfx_init(ctypes.byref(h), 8, ctypes.byref(bad), None) == dfx.ERR_INVALID_ARG
     bad = dfx.config_default()
     bad.sq_depth = 100
     assert lib.dfx_init(ctypes.byref(h), 8, ctypes.byref(bad), None) == dfx.ERR_INVALID_ARG
@@ -92,3 +96,11 @@ def test_build_module_runs_without_the_library():
     assert res.returncode == 0, res.stderr
     src = open(os.path.join(ROOT, "paper_2303_06324_amd", "binding.py")).read()
     assert "raise ImportError" in src and "no CPU fallback" in src
+
+
+def test_library_carries_the_id_of_its_sources():
+    """The loaded library was built from the sources in the tree (a stale one is refused at load)."""
+    import paper_2303_06324_amd as dfx
+    from paper_2303_06324_amd import build as b
+    assert dfx.build_id() == b.source_id() == b.built_id()
+    assert len(dfx.build_id()) == 16

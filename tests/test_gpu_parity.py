@@ -54,7 +54,7 @@ def _check(dw, w, ci):
 
 
 def _run(w, **cfgkw):
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     mode = cfgkw.pop("mode", "roundrobin")
     timeout_s = cfgkw.pop("timeout_s", 30.0)
     cfg = gh.make_config(**cfgkw)
@@ -81,11 +81,6 @@ def test_config1_circular_wait_all_orders(orders, spread):
     inputs: sums are exact in any order."""
     w = wi.config1(*orders)
     stats = _run(w, max_channels=4, spin_init=200, spin_min=8, spin_max=4000, spin_boost=4, chan_spread=spread)
-    from tests import gpu_harness as gh  # noqa: F401
-    for ci in range(2):
-        sends = wi.all_sends(w, ci)
-        exact = sum(s.astype(np.int64) for s in sends)
-        assert exact.shape == (1024,)
     assert sum(s["cqe_posted"] for s in stats) == 4
 
 
@@ -142,7 +137,7 @@ def test_config5_many_small_allreduces():
 
 def test_repeated_invocations_and_changing_buffers():
     """A collective is registered once and run many times, with different buffers (Sec. 3.2, 4.2)."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = _one(wi.AR, wi.F32, 300000, 8, seed=77)
     dws = [gh.DeviceWorkload(w), gh.DeviceWorkload(wi.Workload(w.name, 8, w.colls, w.orders, seed=78, cfg=50))]
@@ -155,6 +150,7 @@ def test_repeated_invocations_and_changing_buffers():
             gh.submit_round_robin(ctx, dw)
             assert ctx.wait_all(20.0) == dfx.OK
             _check(dw, dw.w, 0)
+            dw.check_untouched()
         assert ctx.submit(0, 0, dws[0].send[0][0].data_ptr(), dws[0].recv[0][0].data_ptr()) == dfx.OK
         assert ctx.submit(0, 0, dws[0].send[0][0].data_ptr(), dws[0].recv[0][0].data_ptr()) == dfx.ERR_BUSY
         for r in range(1, 8):
@@ -190,7 +186,7 @@ def test_other_reducing_functions(kind, dtype, op):
 
 def test_max_min_ties_and_signed_zeros():
     """Equal values (and +0 / -0) pass on the own operand: checked on buffers made of few distinct values."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     R, n = 4, 8192
     g = np.random.default_rng(77)
@@ -260,7 +256,7 @@ def test_fenced_connector_mode_matches_too(monkeypatch):
 def test_in_place_allreduce(dtype, count):
     """recvbuf == sendbuf: the ring reads every location of the send buffer (reduce phase) before the
     gather phase overwrites it, slice by slice, so an all-reduce may run in place."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     import torch
     w = _one(wi.AR, dtype, count, 8, seed=count)
@@ -320,7 +316,7 @@ def test_direct_allreduce_under_forced_preemption_and_disorder():
 def test_direct_allreduce_repeated_with_changing_buffers_and_in_place():
     """The recv buffer's address travels through the connector with every invocation: alternating
     buffer sets, then the same collective in place (recvbuf == sendbuf)."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     import torch
     w = _one(wi.AR, wi.F32, 300000, 8, seed=81)
@@ -335,6 +331,7 @@ def test_direct_allreduce_repeated_with_changing_buffers_and_in_place():
             gh.submit_round_robin(ctx, dw)
             assert ctx.wait_all(20.0) == dfx.OK
             _check(dw, dw.w, 0)
+            dw.check_untouched()
         sends = wi.all_sends(w, 0)
         want = rd.all_reduce_fold(sends, wi.F32)
         bufs = [torch.from_numpy(s.view(np.uint8).copy()).cuda() for s in sends]
@@ -372,7 +369,7 @@ def test_direct_steps_of_every_kind_survive_stop_and_quit(quit_idle_us):
     the oracle's: saved positions, claimed counters and the buffer addresses published in the connectors
     outlive the grid (Sec. 4.4, 4.5)."""
     import time
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     R = 8
     colls = [wi.CollSpec(0, wi.AR, wi.F32, 300000), wi.CollSpec(1, wi.AG, wi.BF16, 40000), wi.CollSpec(2, wi.RS, wi.F16, 48000, 0, wi.MAX),
@@ -397,6 +394,7 @@ def test_direct_steps_of_every_kind_survive_stop_and_quit(quit_idle_us):
         assert ctx.wait_all(20.0) == dfx.OK
         for ci in range(5):
             _check(dw, w, ci)
+        dw.check_untouched()
     finally:
         assert ctx.finalize() == dfx.OK
 
@@ -443,7 +441,7 @@ def test_chain_slice_lengths():
     32 KiB; reduce at most 64 KiB; a direct broadcast, which has no slots, up to twice the slot size), always
     under the configured slot size for everything that goes through slots; the values do not depend on it: a
     direct broadcast whose slices are twice the slot size and a reduce with the smallest slices stay bit-exact."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     ctx = dfx.Context(8, gh.make_config())
     try:

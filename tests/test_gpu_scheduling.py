@@ -23,7 +23,7 @@ def test_negative_control_no_preemption_hits_watchdog():
     """Opposite issue orders with preemption disabled = the single-queue deadlock (Sec. 2.3, Fig. 1c;
     Sec. 6.1 reports 100 % for the non-preemptive library).  The in-kernel watchdog turns it into
     a timeout: every wave still leaves the kernel normally."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.config1((0, 1), (1, 0))
     dw = gh.DeviceWorkload(w)
@@ -42,7 +42,7 @@ def test_negative_control_no_preemption_hits_watchdog():
 
 
 def test_same_order_without_preemption_completes():
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     w = wi.config1((0, 1), (0, 1))
     dw, stats, _ = gh.run_workload(w, gh.make_config(preempt=0, watchdog_ms=2000, max_channels=2, chan_spread=0))
     for ci in range(2):
@@ -53,7 +53,7 @@ def test_same_order_without_preemption_completes():
 @pytest.mark.parametrize("direct_min_bytes", [2 << 20, 0])
 def test_voluntary_quit_and_event_driven_restart(direct_min_bytes):
     """Sec. 4.4: the daemon leaves when idle and is started again by the next SQE; contexts survive."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.Workload("quit", 8, [wi.CollSpec(0, wi.AR, wi.F32, 200000)], [[0]] * 8, seed=5, cfg=70)
     dw = gh.DeviceWorkload(w)
@@ -81,7 +81,7 @@ def test_device_synchronize_between_disordered_collectives():
     device-wide synchronisation between collectives issued in opposite orders.  The stuck daemon
     quits voluntarily, the synchronisation returns, the remaining SQEs restart the daemon."""
     import torch
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.config1((0, 1), (1, 0), n=50000)
     dw = gh.DeviceWorkload(w)
@@ -106,7 +106,7 @@ def test_device_synchronize_between_disordered_collectives():
 def test_priority_ordering_policy():
     """Sec. 4.3 priority-based ordering: later-arriving collectives get higher priority (the DP
     overlap scheme); everything still completes and matches."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.config3(n_buckets=12, bucket_bytes=1 << 20, seed=8)
     dw = gh.DeviceWorkload(w)
@@ -124,7 +124,7 @@ def test_priority_ordering_policy():
 def test_sq_backpressure_and_poll_interface():
     """A 4-entry SQ with 40 collectives: submit returns SQ_FULL until every workgroup of the rank
     has read a slot (Sec. 5); dfx_poll hands out each completion exactly once."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.config5(n_colls=40, seed=9, R=4)
     dw = gh.DeviceWorkload(w)
@@ -169,15 +169,18 @@ def test_sq_backpressure_and_poll_interface():
 
 
 def test_stats_are_consistent():
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     w = wi.config3(n_buckets=6, bucket_bytes=512 << 10, seed=12)
     dw, stats, _ = gh.run_workload(w, gh.make_config(spin_init=8, spin_min=1, spin_max=32, spin_boost=2, trace=1,
                                                       chan_spread=0, scan_min=0))   # shared queues, polled in turn
     for s in stats:
         assert s["cqe_posted"] == 6
-        assert s["preemptions"] == s["ctx_saves"] + s["lazy_skips"] or s["ctx_saves"] >= 0
+        # every preemption either saves the dynamic context or skips the save because nothing had moved
+        # (a save without a preemption happens only when the grid is aborted, which this run is not)
+        assert s["preemptions"] == s["ctx_saves"] + s["lazy_skips"]
         assert s["ctx_loads"] + s["ctx_slot_hits"] >= s["preemptions"]
         assert s["max_taskq"] <= 6
+    assert sum(s["preemptions"] for s in stats) > 0 and sum(s["lazy_skips"] for s in stats) > 0
     assert sum(s["switch_samples"] for s in stats) > 0
     assert all(0.0 < s["switch_us_p50"] < 100.0 for s in stats if s["switch_samples"])
 
@@ -186,7 +189,7 @@ def test_stats_are_consistent():
 def test_sq_placements(placement):
     """SQ in pinned host memory (the paper's placement, Sec. 5) and in fine-grained device memory
     written by the host through the PCIe BAR: same results; the device placement needs a large BAR."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.config4(n_colls=12, min_bytes=4096, max_bytes=1 << 20, seed=21)
     try:
@@ -204,7 +207,7 @@ def test_stop_with_outstanding_work_and_resume(direct_min_bytes):
     """dfx_stop (exit SQE, Sec. 4.4) while collectives are stuck: their contexts survive in the
     context buffer (Sec. 4.5) and the next start resumes them (also with the direct gather steps,
     whose published recv-buffer addresses must survive in the connectors)."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.config3(n_buckets=4, bucket_bytes=1 << 20, seed=15)
     dw = gh.DeviceWorkload(w)
@@ -234,7 +237,7 @@ def test_primitive_timeline_trace():
     """trace = 3: one sample per executed primitive and per wait that ended in preemption; every
     workgroup that served the collective reports its 2R-1 primitives per slice, in sequence order,
     with data phases that do not overlap in time."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.Workload("timeline", 8, [wi.CollSpec(0, wi.AR, wi.F32, 1 << 20)], [[0]] * 8, seed=21, cfg=71)
     dw = gh.DeviceWorkload(w)
@@ -278,7 +281,7 @@ def test_primitive_timeline_trace():
 def test_cq_variants_deliver_every_completion_once(cq_mode):
     """The three completion queues of Sec. 5 (CAS slot array, vanilla ring, 64-bit packed ring) behind a
     16-slot CQ that must wrap many times: 200 collectives per rank, every CQE handed out exactly once."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.config5(n_colls=200, seed=23)
     dw = gh.DeviceWorkload(w)
@@ -313,7 +316,7 @@ def test_cq_variants_deliver_every_completion_once(cq_mode):
 def test_callback_poller_thread():
     """Sec. 3.1: a poller thread reads the CQEs and runs the callback; nothing is left for dfx_poll, and
     the thread restarts a daemon that quit while work was outstanding."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     import threading
     w = wi.config3(n_buckets=8, bucket_bytes=256 << 10, seed=24)
@@ -351,7 +354,7 @@ def test_callback_poller_thread():
 
 
 def test_submit_all_is_one_invocation_on_every_vrank():
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.Workload("submit_all", 8, [wi.CollSpec(0, wi.AR, wi.I32, 70001)], [[0]] * 8, seed=31, cfg=72)
     dw = gh.DeviceWorkload(w)
@@ -375,7 +378,7 @@ def test_paced_burst_honours_its_delays():
     """dfx_submit_many_paced waits delays_ns[i] before entry i (the issue-time jitter of the
     disordered-invocation experiments, Sec. 6.1); data must still equal the oracle's."""
     import threading
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     R, n = 4, 6
     colls = [wi.CollSpec(i, wi.AR, wi.I32, 3000 + 17 * i) for i in range(n)]
@@ -417,7 +420,7 @@ def test_paced_burst_honours_its_delays():
 def test_host_error_paths_leave_the_context_usable():
     """Argument errors are reported by the host side before anything reaches the SQ; a context that
     has reported them still runs a collective correctly afterwards."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = wi.Workload("errs", 4, [wi.CollSpec(0, wi.AR, wi.F32, 5001), wi.CollSpec(1, wi.BC, wi.I32, 333, root=2)],
                     [[0, 1]] * 4, seed=9, cfg=74)
@@ -464,7 +467,7 @@ def test_two_contexts_take_turns_on_the_device():
     flags), so a context's daemon is started only when no other context's is in flight: both
     contexts finish their collectives, and a daemon that never quits makes the other one wait
     until it is stopped."""
-    from tests import gpu_harness as gh
+    from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     wa = wi.Workload("turn_a", 8, [wi.CollSpec(0, wi.AR, wi.I32, 150001)], [[0]] * 8, seed=41, cfg=75)
     wb = wi.Workload("turn_b", 4, [wi.CollSpec(0, wi.AG, wi.F16, 4099)], [[0]] * 4, seed=42, cfg=76)

@@ -294,3 +294,18 @@ def test_dispatch_helpers_agree():
         b = rd.run_closed_form(kind, sends, dtype, root=2)
         for r in range(R):
             assert np.array_equal(a[r].view(np.uint8), b[r].view(np.uint8))
+
+
+@pytest.mark.parametrize("threads", [1, 3, 8])
+def test_threaded_replay_gives_the_same_bits(threads):
+    """The replay driven by worker threads (the bench's CPU baseline leg) against the round-robin replay and
+    the closed form, on ragged sizes and every dtype."""
+    for dtype, n in ((rd.F32, 100003), (rd.BF16, 4099), (rd.F16, 70001), (rd.I32, 17)):
+        w = wi.Workload("thr", 8, [wi.CollSpec(0, wi.AR, dtype, n)], [[0]] * 8, seed=threads, cfg=71)
+        sends = wi.all_sends(w, 0)
+        a = rd.all_reduce_replay(sends, dtype)
+        b = rd.all_reduce_replay(sends, dtype, threads=threads)
+        f = rd.all_reduce_fold(sends, dtype)
+        for r in range(8):
+            assert np.array_equal(a[r].view(np.uint8), b[r].view(np.uint8))
+            assert np.array_equal(b[r].view(np.uint8), f.view(np.uint8))
