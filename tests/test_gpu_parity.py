@@ -394,9 +394,9 @@ def test_direct_steps_of_every_kind_survive_stop_and_quit(quit_idle_us):
         assert ctx.wait_all(20.0) == dfx.OK
         for ci in range(5):
             _check(dw, w, ci)
-        dw.check_untouched()
     finally:
         assert ctx.finalize() == dfx.OK
+    dw.check_untouched()      # (synchronises the device: only once the daemon, resident with quit_idle_us = 0, has gone)
 
 
 @pytest.mark.parametrize("knobs", [dict(), dict(window=1), dict(window=4, nslots=8), dict(nslots=2)])
