@@ -51,7 +51,8 @@ typedef enum {
   DFX_ERR_TIMEOUT = -5,   /* wait deadline passed, or the in-kernel watchdog fired */
   DFX_ERR_HIP = -6,       /* a HIP runtime call failed; see dfx_last_hip_error */
   DFX_ERR_NO_RESOURCES = -7, /* grid does not fit the GPU / connector pool exhausted */
-  DFX_ERR_ABORTED = -8    /* the daemon was aborted; context must be finalized */
+  DFX_ERR_ABORTED = -8,   /* the daemon was aborted; context must be finalized */
+  DFX_ERR_TOO_LARGE = -9  /* dfx_collective_noalloc: beyond the sizes its static scratch memory is laid out for */
 } dfx_status;
 
 /* One completion.  In the paper the CQE carries only the collective's ID (Sec. 5); the invocation
@@ -321,6 +322,31 @@ const char* dfx_build_id(void);
    known traffic calibrates the profiler's HBM byte counters; with ms != NULL (host) the kernel is
    timed with HIP events on that stream, which gives the copy bandwidth the chip reaches. */
 int dfx_copy_calibrate(const void* src, void* dst, size_t bytes, void* hip_stream, float* ms);
+
+/*
+ * For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  One invocation of one collective on every vrank -- what dfx_init + dfx_prepare + dfx_submit_all do
+ * with memory they allocate -- with everything the daemon kernel needs beyond the caller's buffers (SQ, CQ,
+ * counters, saved contexts, connector flag lines and slots) in a static device array of the library:
+ * 32.5 MiB per GPU the library runs on, held until the process ends.  The call allocates nothing (no hipMalloc,
+ * hipFree, stream, event or host allocation) and only enqueues work on hip_stream (NULL = the null stream): a
+ * kernel that clears the array's control part, one that writes the submission entries, the daemon kernel
+ * (nranks x min(32, 256 / nranks) workgroups, which leaves by itself when every vrank's completion is posted)
+ * and one that writes the outcome.  It returns when the work is enqueued; the results are in recvbufs once the
+ * stream has reached the end of that work.
+ * nranks: 1 .. 64.  kind / count / dtype / op / root: as for dfx_prepare; same values, bit for bit, as the
+ * context path.  sendbufs / recvbufs: host arrays of nranks device pointers (read during the call), the buffers
+ * under the rules of dfx_submit.  status_dev: device, 4 bytes, may be NULL; written at the end: 0 = completed,
+ * 0x100 | code = the in-kernel watchdog or an internal check fired, 0x200 = a completion is missing.
+ * Limits: no per-rank buffer (send or recv) above DFX_NOALLOC_MAX_BYTES => DFX_ERR_TOO_LARGE.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU race (also from different
+ * streams or threads); a call is refused with DFX_ERR_BUSY while a context's daemon is in flight on the device,
+ * and no context's daemon may be started on the device before the call's work has finished.
+ * Errors: INVALID_ARG, TOO_LARGE, BUSY, NO_RESOURCES (the grid cannot be co-resident on this device), HIP.
+ */
+#define DFX_NOALLOC_MAX_BYTES (1ull << 30)
+int dfx_collective_noalloc(int nranks, dfx_kind kind, size_t count, dfx_dtype dtype, dfx_op op, int root,
+                           const void* const* sendbufs, void* const* recvbufs, uint32_t* status_dev, void* hip_stream);
 
 #ifdef __cplusplus
 }

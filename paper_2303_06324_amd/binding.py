@@ -18,7 +18,8 @@ SUM, PROD, MAX, MIN = 0, 1, 2, 3
 
 OK = 0
 ERR_INVALID_ARG, ERR_NOT_PREPARED, ERR_BUSY, ERR_SQ_FULL = -1, -2, -3, -4
-ERR_TIMEOUT, ERR_HIP, ERR_NO_RESOURCES, ERR_ABORTED = -5, -6, -7, -8
+ERR_TIMEOUT, ERR_HIP, ERR_NO_RESOURCES, ERR_ABORTED, ERR_TOO_LARGE = -5, -6, -7, -8, -9
+NOALLOC_MAX_BYTES = 1 << 30
 
 
 class Config(C.Structure):
@@ -93,6 +94,7 @@ def _load() -> C.CDLL:
         "dfx_strerror": ([i], C.c_char_p),
         "dfx_build_id": ([], C.c_char_p),
         "dfx_copy_calibrate": ([vp, vp, sz, vp, C.POINTER(C.c_float)], i),
+        "dfx_collective_noalloc": ([i, i, sz, i, i, i, C.POINTER(vp), C.POINTER(vp), vp, vp], i),
     }
     for name, (args, res) in sig.items():
         f = getattr(lib, name)
@@ -255,3 +257,14 @@ def copy_calibrate(src: int, dst: int, nbytes: int, stream: Optional[int] = None
     if rc != OK:
         raise DfxError(rc, "dfx_copy_calibrate")
     return ms.value
+
+
+def collective_noalloc(nranks: int, kind: int, count: int, dtype: int, op: int, root: int, sendbufs, recvbufs,
+                       status_dev: int = 0, stream: Optional[int] = None) -> int:
+    """One collective on every vrank through the entry point that allocates nothing; only enqueues work on
+    `stream`.  Returns the status (OK, ERR_TOO_LARGE, ERR_BUSY ...) without raising."""
+    sb = (C.c_void_p * nranks)(*sendbufs)
+    rb = (C.c_void_p * nranks)(*recvbufs)
+    return _lib.dfx_collective_noalloc(nranks, kind, count, dtype, op, root, sb, rb,
+                                       C.c_void_p(status_dev) if status_dev else None,
+                                       C.c_void_p(stream) if stream else None)

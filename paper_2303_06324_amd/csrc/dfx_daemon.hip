@@ -906,6 +906,16 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 ws->dbg[0] = ((u64)sh.taskq[0] << 32) | qlen; ws->dbg[1] = ri; ws->dbg[2] = now - last_act;
                 raise_error(a, 1u, wg);
                 s = STOP_ABORT;
+              } else if (a.oneshot) {
+                // A launch that brings all of its work with it: this workgroup is through when it has read every
+                // entry of its rank's SQ, its queue is empty and its jobs are retired (completions posted).
+                if (!voted && qlen == 0 && ri >= (u64)a.oneshot && retired == posted) {
+                  voted = true;
+                  if (__hip_atomic_fetch_add(&a.dev_ctl[DC_VOTES], 1u, __ATOMIC_ACQ_REL, SCOPE_AGENT) + 1 == a.nwg) {
+                    __hip_atomic_store(&a.dev_ctl[DC_QUIT], 1u, __ATOMIC_RELEASE, SCOPE_AGENT);
+                    s = STOP_QUIT;
+                  }
+                }
               } else if (a.quit_ticks) {
                 // Voluntary quit (Sec. 4.4).  Every workgroup has duties towards the others (each
                 // must read every SQE of its rank before the slot is reusable), so the grid leaves

@@ -333,6 +333,100 @@ void drain_cq(dfx_ctx* c, int rank) {
   }
 }
 
+// Geometry of one collective under a configuration: ring chunk, channels, slice length, rounds, primitive
+// count, whether it takes direct steps, and the bytes of connector memory it needs (flag lines first, then
+// the slots).  Shared by dfx_prepare and the entry point that brings its own static memory.
+int plan_collective(const dfx_config& cfg, int nranks, int coll_id, dfx_kind kind, size_t count, dfx_dtype dtype, dfx_op op,
+                    int root, int priority, uint64_t conn_off, DfxStatic* out, uint64_t* conn_bytes_out) {
+  if ((int)kind < 0 || (int)kind > 4 || (int)dtype < 0 || (int)dtype > 3 || (int)op < 0 || (int)op > 3) return DFX_ERR_INVALID_ARG;
+  const bool rooted = (kind == DFX_BROADCAST || kind == DFX_REDUCE);
+  if (rooted && (root < 0 || root >= nranks)) return DFX_ERR_INVALID_ARG;
+  if (priority < -32768 || priority > 32767) return DFX_ERR_INVALID_ARG;
+  if (count > (1ull << 40)) return DFX_ERR_INVALID_ARG;
+
+  const uint64_t R = (uint64_t)nranks;
+  const uint32_t eb = elem_bytes(dtype);
+  const uint64_t per16 = 16 / eb;
+  // ring chunk: all-reduce cuts the message into R contiguous chunks of ceil(N/R) elements
+  // rounded up to 16 bytes; the other kinds move blocks of `count`
+  uint64_t block = count;
+  if (kind == DFX_ALLREDUCE && R > 1) block = round_up(ceil_div(count, R), per16);
+  const uint64_t block_bytes = block * eb;
+  uint64_t C = ceil_div(std::max<uint64_t>(block_bytes, 1), cfg.chan_min_bytes);
+  C = std::min<uint64_t>(std::max<uint64_t>(C, 1), cfg.max_channels);
+  uint64_t part = round_up(std::max<uint64_t>(ceil_div(block, C), 1), per16);
+  C = std::max<uint64_t>(1, ceil_div(block, part));   // drop channels that would be empty
+  // direct steps of a broadcast: every rank writes its recv buffer only and the next one reads it there
+  // (measured break-even points: the rings at direct_min_bytes, a reduce-scatter at twice that, the chains at a quarter)
+  const bool bc_direct = kind == DFX_BROADCAST && R > 1 && cfg.direct && count * eb >= cfg.direct_min_bytes / 4;
+  uint64_t slice_cap = cfg.slot_bytes;
+  if (rooted && R > 1) {
+    // A chain's last rank starts R-1 slices after its first, so a chain wants shorter slices than a
+    // ring, where all ranks start at once: measured best (R = 8, 2 - 256 MiB) are about 2R slices per
+    // channel share for the broadcast and 4R for the reduce, of no less than 32 KiB; the reduce, whose
+    // every hop goes through a slot, gains nothing beyond 64 KiB, while the direct broadcast uses no
+    // slots and may take slices of twice the slot size.
+    const uint64_t lo = std::min<uint64_t>(32u << 10, cfg.slot_bytes);
+    const uint64_t hi = kind == DFX_BROADCAST ? (bc_direct ? std::min<uint64_t>(2ull * cfg.slot_bytes, 1ull << 30) : cfg.slot_bytes)
+                                              : std::min<uint64_t>(64u << 10, cfg.slot_bytes);
+    const uint64_t want = round_up(part * eb / ((kind == DFX_BROADCAST ? 2 : 4) * R), 16);
+    slice_cap = std::min(std::max(want, lo), hi);
+  }
+  uint64_t slot_bytes = std::min<uint64_t>(slice_cap, round_up(part * eb, 16));
+  const uint64_t slice_elems = slot_bytes / eb;
+  const uint64_t rounds = std::max<uint64_t>(1, ceil_div(part, slice_elems));
+  if (rounds > 0xfffffffeull) return DFX_ERR_INVALID_ARG;
+  const uint64_t K = cfg.nslots;
+  // (a direct broadcast fills no slot: its connectors are the flag lines alone)
+  *conn_bytes_out = round_up(R * C * DFX_FLAG_STRIDE + (bc_direct ? 0 : R * C * K * slot_bytes), 256);
+
+  DfxStatic t;
+  memset(&t, 0, sizeof(t));
+  t.coll_id = (uint32_t)coll_id;
+  t.count = count;
+  t.conn_off = conn_off;
+  t.block_elems = block;
+  t.part_elems = part;
+  t.slice_elems = (uint32_t)slice_elems;
+  t.rounds = (uint32_t)rounds;
+  t.slot_bytes = (uint32_t)slot_bytes;
+  t.nslots = (uint16_t)K;
+  t.nchan = (uint16_t)C;
+  t.kind = (uint8_t)kind; t.dtype = (uint8_t)dtype; t.op = (uint8_t)op; t.root = (uint8_t)(rooted ? root : 0);
+  t.priority = (int16_t)priority;
+  if (R == 1) t.nprim = 1;
+  else if (kind == DFX_ALLREDUCE) {
+    // direct gather steps (one more step: the drain) where the message is long enough to gain from them
+    const bool direct = cfg.direct && count * eb >= cfg.direct_min_bytes;
+    if (direct) t.flags |= DFX_SQE_DIRECT;
+    t.nprim = (uint32_t)(2 * R - 1) + (direct ? 1u : 0u);
+  }
+  else if (rooted) {
+    t.nprim = 1;   // one primitive per slice, which one depends on the place in the chain
+    // the reduce chain's direct step: the first rank only notifies, the second reads its send buffer
+    const bool rd_direct = kind == DFX_REDUCE && cfg.direct && count * eb >= cfg.direct_min_bytes / 4;
+    if (bc_direct || rd_direct) {
+      // one round more than there are slices, which is the drain
+      t.flags |= DFX_SQE_DIRECT;
+      t.rounds = (uint32_t)rounds + 1u;
+    }
+  }
+  else if (kind == DFX_ALLGATHER && cfg.direct && count * eb * R >= cfg.direct_min_bytes && (count * eb) % 16 == 0) {
+    // direct gather steps need every block 16-byte aligned in the recv buffers
+    t.flags |= DFX_SQE_DIRECT;
+    t.nprim = (uint32_t)R + 1u;
+  }
+  else if (kind == DFX_REDUCESCATTER && cfg.direct && count * eb * R >= 2ull * cfg.direct_min_bytes && (count * eb) % 16 == 0) {
+    // the opening send only notifies and the next rank reads the block from the send buffer, where
+    // every block then has to be 16-byte aligned; one more step, the drain
+    t.flags |= DFX_SQE_DIRECT;
+    t.nprim = (uint32_t)R + 1u;
+  }
+  else t.nprim = (uint32_t)R;
+  *out = t;
+  return DFX_OK;
+}
+
 inline void backoff(uint32_t& spins) {
   ++spins;
   if (spins < 2000) _mm_pause();
@@ -494,94 +588,13 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
 int dfx_prepare(dfx_ctx* c, int coll_id, dfx_kind kind, size_t count, dfx_dtype dtype, dfx_op op, int root, int priority) {
   if (!c) return DFX_ERR_INVALID_ARG;
   if (coll_id < 0 || (uint32_t)coll_id >= c->cfg.max_colls) return DFX_ERR_INVALID_ARG;
-  if ((int)kind < 0 || (int)kind > 4 || (int)dtype < 0 || (int)dtype > 3 || (int)op < 0 || (int)op > 3) return DFX_ERR_INVALID_ARG;
-  const bool rooted = (kind == DFX_BROADCAST || kind == DFX_REDUCE);
-  if (rooted && (root < 0 || root >= c->R)) return DFX_ERR_INVALID_ARG;
-  if (priority < -32768 || priority > 32767) return DFX_ERR_INVALID_ARG;
-  if (count > (1ull << 40)) return DFX_ERR_INVALID_ARG;
   CollInfo& ci = c->colls[coll_id];
   if (ci.prepared) return DFX_ERR_INVALID_ARG;
-
-  const uint64_t R = (uint64_t)c->R;
-  const uint32_t eb = elem_bytes(dtype);
-  const uint64_t per16 = 16 / eb;
-  // ring chunk: all-reduce cuts the message into R contiguous chunks of ceil(N/R) elements
-  // rounded up to 16 bytes; the other kinds move blocks of `count`
-  uint64_t block = count;
-  if (kind == DFX_ALLREDUCE && R > 1) block = round_up(ceil_div(count, R), per16);
-  const uint64_t block_bytes = block * eb;
-  uint64_t C = ceil_div(std::max<uint64_t>(block_bytes, 1), c->cfg.chan_min_bytes);
-  C = std::min<uint64_t>(std::max<uint64_t>(C, 1), c->cfg.max_channels);
-  uint64_t part = round_up(std::max<uint64_t>(ceil_div(block, C), 1), per16);
-  C = std::max<uint64_t>(1, ceil_div(block, part));   // drop channels that would be empty
-  // direct steps of a broadcast: every rank writes its recv buffer only and the next one reads it there
-  // (measured break-even points: the rings at direct_min_bytes, a reduce-scatter at twice that, the chains at a quarter)
-  const bool bc_direct = kind == DFX_BROADCAST && R > 1 && c->cfg.direct && count * eb >= c->cfg.direct_min_bytes / 4;
-  uint64_t slice_cap = c->cfg.slot_bytes;
-  if (rooted && R > 1) {
-    // A chain's last rank starts R-1 slices after its first, so a chain wants shorter slices than a
-    // ring, where all ranks start at once: measured best (R = 8, 2 - 256 MiB) are about 2R slices per
-    // channel share for the broadcast and 4R for the reduce, of no less than 32 KiB; the reduce, whose
-    // every hop goes through a slot, gains nothing beyond 64 KiB, while the direct broadcast uses no
-    // slots and may take slices of twice the slot size.
-    const uint64_t lo = std::min<uint64_t>(32u << 10, c->cfg.slot_bytes);
-    const uint64_t hi = kind == DFX_BROADCAST ? (bc_direct ? std::min<uint64_t>(2ull * c->cfg.slot_bytes, 1ull << 30) : c->cfg.slot_bytes)
-                                              : std::min<uint64_t>(64u << 10, c->cfg.slot_bytes);
-    const uint64_t want = round_up(part * eb / ((kind == DFX_BROADCAST ? 2 : 4) * R), 16);
-    slice_cap = std::min(std::max(want, lo), hi);
-  }
-  uint64_t slot_bytes = std::min<uint64_t>(slice_cap, round_up(part * eb, 16));
-  const uint64_t slice_elems = slot_bytes / eb;
-  const uint64_t rounds = std::max<uint64_t>(1, ceil_div(part, slice_elems));
-  if (rounds > 0xffffffffull) return DFX_ERR_INVALID_ARG;
-  const uint64_t K = c->cfg.nslots;
-  // (a direct broadcast fills no slot: its connectors are the flag lines alone)
-  const uint64_t conn_bytes = round_up(R * C * DFX_FLAG_STRIDE + (bc_direct ? 0 : R * C * K * slot_bytes), 256);
-  if (c->pool_used + conn_bytes > c->cfg.pool_bytes) return DFX_ERR_NO_RESOURCES;
-
   DfxStatic t;
-  memset(&t, 0, sizeof(t));
-  t.coll_id = (uint32_t)coll_id;
-  t.count = count;
-  t.conn_off = c->pool_used;
-  t.block_elems = block;
-  t.part_elems = part;
-  t.slice_elems = (uint32_t)slice_elems;
-  t.rounds = (uint32_t)rounds;
-  t.slot_bytes = (uint32_t)slot_bytes;
-  t.nslots = (uint16_t)K;
-  t.nchan = (uint16_t)C;
-  t.kind = (uint8_t)kind; t.dtype = (uint8_t)dtype; t.op = (uint8_t)op; t.root = (uint8_t)(rooted ? root : 0);
-  t.priority = (int16_t)priority;
-  if (R == 1) t.nprim = 1;
-  else if (kind == DFX_ALLREDUCE) {
-    // direct gather steps (one more step: the drain) where the message is long enough to gain from them
-    const bool direct = c->cfg.direct && count * eb >= c->cfg.direct_min_bytes;
-    if (direct) t.flags |= DFX_SQE_DIRECT;
-    t.nprim = (uint32_t)(2 * R - 1) + (direct ? 1u : 0u);
-  }
-  else if (rooted) {
-    t.nprim = 1;   // one primitive per slice, which one depends on the place in the chain
-    // the reduce chain's direct step: the first rank only notifies, the second reads its send buffer
-    const bool rd_direct = kind == DFX_REDUCE && c->cfg.direct && count * eb >= c->cfg.direct_min_bytes / 4;
-    if (bc_direct || rd_direct) {
-      // one round more than there are slices, which is the drain
-      t.flags |= DFX_SQE_DIRECT;
-      t.rounds = (uint32_t)rounds + 1u;
-    }
-  }
-  else if (kind == DFX_ALLGATHER && c->cfg.direct && count * eb * R >= c->cfg.direct_min_bytes && (count * eb) % 16 == 0) {
-    // direct gather steps need every block 16-byte aligned in the recv buffers
-    t.flags |= DFX_SQE_DIRECT;
-    t.nprim = (uint32_t)R + 1u;
-  }
-  else if (kind == DFX_REDUCESCATTER && c->cfg.direct && count * eb * R >= 2ull * c->cfg.direct_min_bytes && (count * eb) % 16 == 0) {
-    // the opening send only notifies and the next rank reads the block from the send buffer, where
-    // every block then has to be 16-byte aligned; one more step, the drain
-    t.flags |= DFX_SQE_DIRECT;
-    t.nprim = (uint32_t)R + 1u;
-  }
-  else t.nprim = (uint32_t)R;
+  uint64_t conn_bytes = 0;
+  const int rc = plan_collective(c->cfg, c->R, coll_id, kind, count, dtype, op, root, priority, c->pool_used, &t, &conn_bytes);
+  if (rc != DFX_OK) return rc;
+  if (c->pool_used + conn_bytes > c->cfg.pool_bytes) return DFX_ERR_NO_RESOURCES;
   c->pool_used += conn_bytes;
   ci.tmpl = t;
   ci.prepared = true;
@@ -989,8 +1002,209 @@ const char* dfx_strerror(int s) {
     case DFX_ERR_HIP: return "HIP runtime error";
     case DFX_ERR_NO_RESOURCES: return "not enough resources";
     case DFX_ERR_ABORTED: return "daemon aborted";
+    case DFX_ERR_TOO_LARGE: return "size beyond what the static scratch memory of this entry point is laid out for";
     default: return "unknown status";
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// One collective without any allocation: the daemon kernel on a static scratch array
+// ------------------------------------------------------------------------------------------
+}  // extern "C"
+
+// Everything a context allocates in dfx_init (SQ, CQ, control words, counters, saved contexts, task-queue store,
+// workgroup state, connector flag lines and slots), laid out in one file-scope device array.  Each GPU the
+// library runs on holds its own copy until the process ends.
+#define DFX_NA_MAX_WG 256u                      // workgroups of the grid = nranks x channels per rank
+#define DFX_NA_SLOT_BYTES (32u << 10)           // bytes per connector slot
+#define DFX_NA_NSLOTS 4u                        // slots per connector
+#define DFX_NA_SQ_DEPTH 2u
+#define DFX_NA_CQ_SLOTS 2u
+#define DFX_NA_MAX_RANKS 64u
+#define DFX_NA_CTL_BYTES (512u << 10)           // everything but the slots: must start at zero on every call
+#define DFX_NA_SLOTS_BYTES ((size_t)DFX_NA_MAX_WG * DFX_NA_NSLOTS * DFX_NA_SLOT_BYTES)
+#define DFX_NA_SCRATCH_BYTES ((size_t)DFX_NA_CTL_BYTES + DFX_NA_SLOTS_BYTES)
+static __device__ __align__(256) unsigned char scratch[DFX_NA_SCRATCH_BYTES];
+
+namespace {
+
+// Offsets inside the zeroed part of the scratch.  The connector pool comes last: its flag lines are the end of
+// the zeroed part and its slots follow them directly (a collective's connector block = flag lines, then slots).
+struct NaLayout {
+  size_t dev_ctl, host_ctl, sq, sq_freed, sq_readers, cq, cq_ctl, done_cnt, wgstate, taskq, ctxbuf, pool, end_of_zeroed;
+};
+constexpr size_t na_up(size_t x) { return (x + 255) & ~(size_t)255; }
+constexpr NaLayout na_layout() {
+  NaLayout L{};
+  size_t o = 0;
+  L.dev_ctl = o; o = na_up(o + DC_N * 4);
+  L.host_ctl = o; o = na_up(o + HC_N * 4);
+  L.sq = o; o = na_up(o + (size_t)DFX_NA_MAX_RANKS * DFX_NA_SQ_DEPTH * sizeof(DfxSqSlot));
+  L.sq_freed = o; o = na_up(o + (size_t)DFX_NA_MAX_RANKS * DFX_NA_SQ_DEPTH * 4);
+  L.sq_readers = o; o = na_up(o + (size_t)DFX_NA_MAX_RANKS * DFX_NA_SQ_DEPTH * 4);
+  L.cq = o; o = na_up(o + (size_t)DFX_NA_MAX_RANKS * DFX_NA_CQ_SLOTS * 8);
+  L.cq_ctl = o; o = na_up(o + (size_t)DFX_NA_MAX_RANKS * DFX_CQ_CTL_WORDS * 8);
+  L.done_cnt = o; o = na_up(o + (size_t)DFX_NA_MAX_RANKS * 4);
+  L.wgstate = o; o = na_up(o + (size_t)DFX_NA_MAX_WG * sizeof(DfxWgState));
+  L.taskq = o; o = na_up(o + (size_t)DFX_NA_MAX_WG * 2);
+  L.ctxbuf = o; o = na_up(o + (size_t)DFX_NA_MAX_WG * sizeof(DfxCtxEntry));
+  // the pool's flag lines end exactly where the zeroed part ends
+  L.pool = DFX_NA_CTL_BYTES - (size_t)DFX_NA_MAX_WG * DFX_FLAG_STRIDE;
+  L.end_of_zeroed = o;
+  return L;
+}
+static_assert(na_layout().end_of_zeroed <= na_layout().pool, "the control structures overlap the connector pool");
+static_assert(DFX_NA_CTL_BYTES % 256 == 0, "alignment of the slots");
+
+struct NaSeed {                       // what the seeding kernel writes into the SQs: one entry per rank
+  DfxStatic tmpl;
+  uint64_t sendbuf[DFX_NA_MAX_RANKS], recvbuf[DFX_NA_MAX_RANKS];
+  uint32_t nranks;
+};
+
+// clears the part of the scratch that must start at zero (a fill kernel, not a memset node: the call may be captured)
+__global__ void __launch_bounds__(256) dfx_na_zero_kernel(uint4* p, uint32_t nvec) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += gridDim.x * blockDim.x) p[i] = uint4{0, 0, 0, 0};
+}
+
+// writes the SQEs the host would have written: entry 0 of every rank's SQ, generation word included
+__global__ void __launch_bounds__(64) dfx_na_seed_kernel(DfxSqSlot* sq, NaSeed sd) {
+  const uint32_t r = threadIdx.x;
+  if (r >= sd.nranks) return;
+  DfxStatic e = sd.tmpl;
+  e.seq = 0;
+  e.sendbuf = sd.sendbuf[r];
+  e.recvbuf = sd.recvbuf[r];
+  e.ready = 1;                        // generation of the first lap
+  sq[(size_t)r * DFX_NA_SQ_DEPTH].e = e;
+}
+
+// after the daemon: 0 = every rank's completion is in its CQ and no error was raised
+__global__ void dfx_na_status_kernel(const uint32_t* dev_ctl, const uint64_t* cq, uint32_t nranks, uint32_t* status) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  uint32_t st = 0;
+  if (dev_ctl[DC_ERR]) st = 0x100u | dev_ctl[DC_ERR];
+  else {
+    uint32_t n = 0;
+    for (uint32_t i = 0; i < nranks * DFX_NA_CQ_SLOTS; ++i) n += (uint32_t)(cq[i] >> 63);
+    if (n != nranks) st = 0x200u;
+  }
+  *status = st;
+}
+
+struct NaDevice {
+  unsigned char* ptr = nullptr;      // this device's copy of `scratch` (hipGetSymbolAddress), never the array's name
+  double tick_us = 0.01;
+  int max_wg = 0;                    // workgroups that can be resident at once
+};
+std::mutex g_na_mu;
+NaDevice g_na_dev[kMaxDevices];
+
+// Once per device, with that device current: the address of its copy of the scratch array and what the launch needs to know.
+int na_setup(int device, NaDevice** out) {
+  if (device < 0 || device >= kMaxDevices) return DFX_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lk(g_na_mu);
+  NaDevice& d = g_na_dev[device];
+  if (!d.ptr) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { g_init_hip_error = (int)e; return DFX_ERR_HIP; }
+    int occ = 0, ncu = 0, wall_khz = 0;
+    e = dfx_daemon_occupancy(&occ);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, device);
+    if (e != hipSuccess) { g_init_hip_error = (int)e; return DFX_ERR_HIP; }
+    if (((DFX_WG_THREADS / 64) & 3) != 0 && occ > 1) occ = 1;   // as in dfx_init
+    d.max_wg = occ * ncu;
+    if (hipDeviceGetAttribute(&wall_khz, hipDeviceAttributeWallClockRate, device) == hipSuccess && wall_khz > 0)
+      d.tick_us = 1000.0 / (double)wall_khz;
+    d.ptr = (unsigned char*)p;
+  }
+  *out = &d;
+  return DFX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dfx_collective_noalloc(int nranks, dfx_kind kind, size_t count, dfx_dtype dtype, dfx_op op, int root,
+                           const void* const* sendbufs, void* const* recvbufs, uint32_t* status_dev, void* hip_stream) {
+  if (nranks < 1 || nranks > (int)DFX_NA_MAX_RANKS || !sendbufs || !recvbufs) return DFX_ERR_INVALID_ARG;
+  if ((int)dtype < 0 || (int)dtype > 3 || (int)kind < 0 || (int)kind > 4) return DFX_ERR_INVALID_ARG;
+  // the stated limit: no per-rank buffer beyond DFX_NOALLOC_MAX_BYTES
+  const uint64_t eb = elem_bytes(dtype);
+  const uint64_t largest = (kind == DFX_ALLGATHER || kind == DFX_REDUCESCATTER) ? (uint64_t)nranks : 1ull;
+  if (count > DFX_NOALLOC_MAX_BYTES / (eb * largest)) return DFX_ERR_TOO_LARGE;
+  for (int r = 0; r < nranks; ++r)
+    if (!sendbufs[r] || !recvbufs[r] || ((uintptr_t)sendbufs[r] & 15u) || ((uintptr_t)recvbufs[r] & 15u)) return DFX_ERR_INVALID_ARG;
+
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess) return DFX_ERR_HIP;
+  NaDevice* nd = nullptr;
+  int rc = na_setup(device, &nd);
+  if (rc != DFX_OK) return rc;
+
+  // the configuration of this path: library defaults under the scratch's sizes
+  dfx_config cfg;
+  dfx_config_default(&cfg);
+  cfg.max_channels = std::min<uint32_t>(32u, DFX_NA_MAX_WG / (uint32_t)nranks);
+  cfg.max_colls = 1;
+  cfg.sq_depth = DFX_NA_SQ_DEPTH;
+  cfg.cq_slots = DFX_NA_CQ_SLOTS;
+  cfg.nslots = DFX_NA_NSLOTS;
+  cfg.slot_bytes = DFX_NA_SLOT_BYTES;
+  const uint32_t nwg = (uint32_t)nranks * cfg.max_channels;
+  if ((int)nwg > nd->max_wg) return DFX_ERR_NO_RESOURCES;   // the grid must be co-resident
+  // a grid shares the device with no other daemon grid: refuse while a context's daemon is in flight here
+  {
+    DeviceSlot& s = g_slot[device % kMaxDevices];
+    std::lock_guard<std::mutex> lk(s.mu);
+    if (s.owner && s.until && hipEventQuery(s.until) == hipErrorNotReady) return DFX_ERR_BUSY;
+  }
+
+  constexpr NaLayout L = na_layout();
+  DfxStatic tmpl;
+  uint64_t conn_bytes = 0;
+  rc = plan_collective(cfg, nranks, 0, kind, count, dtype, op, root, 0, 0, &tmpl, &conn_bytes);
+  if (rc != DFX_OK) return rc;
+  // connector block = flag lines of the collective's R x C edges, then their slots; the scratch holds
+  // DFX_NA_MAX_WG flag lines and as many connectors of DFX_NA_NSLOTS x DFX_NA_SLOT_BYTES
+  const size_t flag_bytes = (size_t)nranks * tmpl.nchan * DFX_FLAG_STRIDE;
+  if (flag_bytes > (size_t)DFX_NA_MAX_WG * DFX_FLAG_STRIDE || conn_bytes - flag_bytes > DFX_NA_SLOTS_BYTES + 256) return DFX_ERR_TOO_LARGE;
+  // the flag lines end where the zeroed part ends, the slots begin right there
+  tmpl.conn_off = (uint64_t)((size_t)DFX_NA_CTL_BYTES - flag_bytes - L.pool);
+
+  unsigned char* base = nd->ptr;
+  DfxDaemonArgs a;
+  memset(&a, 0, sizeof(a));
+  a.sq = (DfxSqSlot*)(base + L.sq); a.cq = (uint64_t*)(base + L.cq); a.cq_ctl = (uint64_t*)(base + L.cq_ctl);
+  a.host_ctl = (uint32_t*)(base + L.host_ctl); a.sq_freed = (uint32_t*)(base + L.sq_freed);
+  a.sq_readers = (uint32_t*)(base + L.sq_readers); a.done_cnt = (uint32_t*)(base + L.done_cnt);
+  a.dev_ctl = (uint32_t*)(base + L.dev_ctl); a.pool = base + L.pool;
+  a.ctxbuf = (DfxCtxEntry*)(base + L.ctxbuf); a.wgstate = (DfxWgState*)(base + L.wgstate);
+  a.taskq_store = (uint16_t*)(base + L.taskq); a.trace = nullptr;
+  a.nwg = nwg; a.scan_min = cfg.scan_min; a.epoch = 1;
+  a.R = (uint32_t)nranks; a.cmax = cfg.max_channels; a.max_colls = 1; a.sq_depth = DFX_NA_SQ_DEPTH; a.sq_shift = 1; a.cq_slots = DFX_NA_CQ_SLOTS;
+  a.spin_init = cfg.spin_init; a.spin_min = cfg.spin_min; a.spin_max = cfg.spin_max; a.spin_boost = cfg.spin_boost; a.preempt = 1;
+  a.wg_map = 0; a.order_policy = 0; a.trace_on = 0; a.fetch_batch = 0xffffffffu; a.fifo_coherent = 1; a.chan_spread = 1;
+  a.cq_mode = 0; a.sq_eager = 1; a.window = cfg.window; a.sq_local = 1; a.focus_bytes = cfg.focus_bytes;
+  a.watchdog_ticks = (uint64_t)((double)cfg.watchdog_ms * 1000.0 / nd->tick_us);
+  a.quit_ticks = 0;
+  a.oneshot = 1;
+
+  NaSeed sd;
+  memset(&sd, 0, sizeof(sd));
+  sd.tmpl = tmpl;
+  sd.nranks = (uint32_t)nranks;
+  for (int r = 0; r < nranks; ++r) { sd.sendbuf[r] = (uint64_t)(uintptr_t)sendbufs[r]; sd.recvbuf[r] = (uint64_t)(uintptr_t)recvbufs[r]; }
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(dfx_na_zero_kernel, dim3(64), dim3(256), 0, st, (uint4*)base, (uint32_t)(DFX_NA_CTL_BYTES / 16));
+  hipLaunchKernelGGL(dfx_na_seed_kernel, dim3(1), dim3(64), 0, st, a.sq, sd);
+  if (hipGetLastError() != hipSuccess) return DFX_ERR_HIP;
+  if (dfx_daemon_launch(nwg, st, a) != hipSuccess) return DFX_ERR_HIP;
+  if (status_dev) hipLaunchKernelGGL(dfx_na_status_kernel, dim3(1), dim3(64), 0, st, a.dev_ctl, a.cq, (uint32_t)nranks, status_dev);
+  return hipGetLastError() == hipSuccess ? DFX_OK : DFX_ERR_HIP;
 }
 
 // Calibration helper for the profiler's HBM byte counters: copies `bytes` (multiple of 16)

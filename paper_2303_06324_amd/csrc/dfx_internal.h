@@ -131,6 +131,9 @@ struct DfxDaemonArgs {
   uint32_t wg_map, order_policy, trace_on, fetch_batch, fifo_coherent, chan_spread, cq_mode, sq_eager, window, sq_local, focus_bytes;
   uint64_t watchdog_ticks;  // wall-clock ticks; 0 = off
   uint64_t quit_ticks;      // wall-clock ticks; 0 = off
+  uint32_t oneshot;         // not 0: the SQs were filled before the launch with this many entries per rank and nobody
+                            // will submit more: a workgroup that has read them all and finished its share votes to
+                            // leave (and never withdraws the vote); the last vote ends the grid
 };
 
 #endif
