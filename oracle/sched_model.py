@@ -62,6 +62,10 @@ Two variations of Alg. 1 can be switched on, to ask whether they keep its livene
     (most primitives done; ties in queue order), and once n slices have been taken in the
     pass it ends with the entry in hand: every rank ranks the collectives alike, so the
     ranks settle on the same few of them (the coalescing of choices that Sec. 4.3 aims at).
+  * `priority_order = True` (Sec. 4.3 "Priority-based Ordering"): the SQ is looked at before every
+    pass, a fetched collective is inserted behind the queued ones of equal or higher user priority
+    (Coll.priority, larger = more urgent), and a focused pass ranks the runnable entries by
+    priority first, progress and queue position only among equals.
 """
 from __future__ import annotations
 
@@ -118,6 +122,7 @@ class Policy:
     scan: bool = False            # a pass visits only the entries whose wait conditions hold at its start
     focus: int = 0                # with scan: furthest-along entries first, and the pass ends after this many slices
     direct: bool = False          # steps that read the previous rank's recv / send buffer instead of a slot (notify / drain)
+    priority_order: bool = False  # priority-based ordering: fetch before every pass, queue sorted by Coll.priority, priority ranks first
 
 
 @dataclass
@@ -126,6 +131,7 @@ class Coll:
     dtype: int
     count: int
     root: int = 0
+    priority: int = 0             # larger = more urgent; used only under Policy.priority_order
 
 
 def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
@@ -306,7 +312,14 @@ class Daemon:
             if coll < 0:
                 self.exit = True
                 return
-            self.taskq.append(coll)
+            if P.priority_order:
+                pr = self.S.colls[coll].priority
+                at = len(self.taskq)
+                while at > 0 and self.S.colls[self.taskq[at - 1]].priority < pr:
+                    at -= 1
+                self.taskq.insert(at, coll)      # stable: behind the queued ones of equal or higher priority
+            else:
+                self.taskq.append(coll)
             self.seq_of[coll] = seq
             self.saved[coll] = [0, 0]
             self.stats.max_taskq = max(self.stats.max_taskq, len(self.taskq))
@@ -385,7 +398,7 @@ class Daemon:
             if not self.in_pass:
                 # FetchSQE: when the queue is empty, or the last pass made no progress
                 before = (len(self.taskq), len(self.sq))
-                if not self.taskq or not self.pass_progress:
+                if not self.taskq or not self.pass_progress or self.S.policy.priority_order:
                     n = self.S.policy.fetch_batch or (1 << 30)
                     while n > 0 and self.sq and not self.exit and len(self.taskq) < self.S.policy.taskq_cap:
                         self._fetch()
@@ -399,7 +412,9 @@ class Daemon:
                 self.in_pass, self.pos, self.pass_progress = True, 0, False
                 if self.S.policy.scan:
                     self.ready = [i for i, c in enumerate(self.taskq) if self._runnable(c)]
-                    if self.S.policy.focus:
+                    if self.S.policy.focus and self.S.policy.priority_order:
+                        self.ready.sort(key=lambda i: (-self.S.colls[self.taskq[i]].priority, -self._done(self.taskq[i]), i))
+                    elif self.S.policy.focus:
                         self.ready.sort(key=lambda i: (-self._done(self.taskq[i]), i))
                     self.rk, self.taken = 0, 0
                     if not self.ready:

@@ -1086,7 +1086,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             for (uint32_t base = 0; base < qlen; base += 64) {
               const uint32_t i = base + lane;
               bool rdy = false;
-              uint32_t key = 0;     // 0 = not runnable; else primitives done so far, then queue position
+              uint32_t key = 0;     // 0 = not runnable; else (priority under priority ordering,) primitives done so far, then queue position
               uint32_t cid = 0;
               uint4 e0 = uint4{0, 0, 0, 0}, e1 = e0, e4 = e0, e2c = e0, e3c = e0, e5c = e0, e6c = e0, e7c = e0;
               if (i < qlen) {
@@ -1111,8 +1111,16 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 rdy = okr && oks;
                 if (rdy) {
                   u64 done = (u64)d0.x * (ge.y & 0xffffu) + d0.y;
-                  if (done > 0xfffffu) done = 0xfffffu;
-                  key = (((uint32_t)done << 8) | (63u - lane)) + 1u;
+                  if (a.order_policy == 1) {
+                    // priority ordering (Sec. 4.3): the user's priority decides first, progress and
+                    // queue position only among equals
+                    if (done > 0xffu) done = 0xffu;
+                    const uint32_t pr = (uint32_t)((int)(int16_t)(ge.w & 0xffffu) + 32768);
+                    key = ((pr << 14) | ((uint32_t)done << 6) | (63u - lane)) + 1u;
+                  } else {
+                    if (done > 0xfffffu) done = 0xfffffu;
+                    key = (((uint32_t)done << 8) | (63u - lane)) + 1u;
+                  }
                 }
               }
               // The contexts of the runnable entries are in registers now: they go into their LDS

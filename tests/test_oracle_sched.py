@@ -11,8 +11,8 @@ from oracle import ring_data as rd
 from oracle import sched_model as sm
 
 
-def _system(w: wi.Workload, policy: sm.Policy, data=True):
-    colls = [sm.Coll(c.kind, c.dtype, c.count, c.root) for c in w.colls]
+def _system(w: wi.Workload, policy: sm.Policy, data=True, priorities=None):
+    colls = [sm.Coll(c.kind, c.dtype, c.count, c.root, 0 if priorities is None else priorities[i]) for i, c in enumerate(w.colls)]
     sends = [wi.all_sends(w, ci) for ci in range(len(w.colls))] if data else None
     S = sm.System(w.R, colls, sends, policy)
     S.plan(w.orders)
@@ -429,3 +429,61 @@ def test_direct_broadcast_model_drains_after_the_last_slice():
         sm.run_random(S, seed + 7, max_ticks=3_000_000)
         assert S.total_cqes() == R * len(colls)
         _check_data(S, w)
+
+
+# ---------------------------------------------------------------- priority-based ordering (Sec. 4.3)
+_OPP, _SAME, _FOCUS = ((0, 1), (1, 0)), ((0, 1), (0, 1)), dict(lookahead=2, scan=True, focus=1)
+
+
+@pytest.mark.parametrize("orders,var,prios", [(_OPP, dict(), (0, 1)), (_OPP, dict(scan=True, focus=1), (0, 1)),
+                                              (_SAME, dict(scan=True, focus=1), (1, 0)), (_OPP, _FOCUS, (1, 0))])
+def test_priority_ordering_exhaustive_interleavings_tiny(orders, var, prios):
+    """Priority-based ordering (the SQ read before every pass, the queue kept sorted by the user's priority,
+    priority first in a focused pass's ranking) keeps Alg. 1's liveness: over all interleavings of the
+    circular-wait setting no reachable state is a deadlock and every one ends with the four CQEs, whichever
+    of the two collectives is the more urgent one."""
+    w = wi.config1(*orders, n=8)
+    pol = sm.Policy(spin_init=2, spin_min=1, spin_max=2, boost=2, K=2, slice_elems=2 if var.get("scan") else 4,
+                    priority_order=True, **var)
+    S0 = _system(w, pol, data=False, priorities=prios)
+    seen = sm.explore(S0, max_states=600_000)
+    assert len(seen) > 20
+    keys = list(seen)
+    step = 1 if len(keys) < 1000 else 97
+    for k in keys[::step]:
+        T = seen[k].clone()
+        assert not sm.is_deadlocked(T)
+        sm.run_round_robin(T, max_ticks=50_000)
+        assert T.total_cqes() == 4
+
+
+@pytest.mark.parametrize("later_first", [True, False])
+def test_priority_ordering_ranks_the_urgent_collective_first(later_first):
+    """Four equal collectives queued in the order 0 .. 3 on both ranks, one queue per rank.  With later = more
+    urgent the task queue is sorted 3, 2, 1, 0, every focused pass starts with the most urgent runnable one,
+    and collective 3 completes first although it arrived last; with the priorities the other way round the
+    order of completion is the order of arrival.  Values are the data oracle's either way."""
+    n = 4
+    colls = [wi.CollSpec(i, wi.AR, wi.I32, 48) for i in range(n)]
+    w = wi.Workload("prio", 2, colls, [list(range(n))] * 2, seed=6, cfg=93)
+    prios = list(range(n)) if later_first else [n - i for i in range(n)]
+    S = _system(w, sm.Policy(spin_init=1, spin_min=1, spin_max=1, boost=1, K=2, slice_elems=4, scan=True, focus=1,
+                             fetch_batch=0, priority_order=True), priorities=prios)
+    S.submit_all()
+    order = []
+    for _ in range(5000):
+        if S.done():
+            break
+        for d in S.daemons:
+            was = d.in_pass
+            d.tick()
+            if d.in_pass and not was and d.ready:
+                pr = [prios[d.taskq[i]] for i in d.ready]
+                assert pr == sorted(pr, reverse=True)                       # most urgent runnable entry first
+            assert [prios[c] for c in d.taskq] == sorted((prios[c] for c in d.taskq), reverse=True)   # sorted queue
+            for c, _ in d.cq:
+                if d.r == 0 and c not in order:
+                    order.append(c)
+    assert S.done() and S.total_cqes() == 2 * n
+    assert order == (list(reversed(range(n))) if later_first else list(range(n))), order
+    _check_data(S, w)
