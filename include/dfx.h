@@ -324,6 +324,22 @@ const char* dfx_build_id(void);
 int dfx_copy_calibrate(const void* src, void* dst, size_t bytes, void* hip_stream, float* ms);
 
 /*
+ * Self-check of the kernel's index arithmetic, on the host, without a GPU (the kernel and this call compile the
+ * same functions).  For collective (kind, count, dtype, op, root, coll_id) among nranks vranks under cfg (NULL =
+ * defaults) and workgroup map wg_map it enumerates every workgroup of the grid and verifies that (i) the map is
+ * a bijection between workgroups and (rank, channel) and every channel of the collective is served by exactly
+ * one workgroup per rank, (ii) both ends of every connector (Sec. 4.1) resolve to the same flag line and the same
+ * slots, inside the collective's connector block, (iii) along every workgroup's walk through its primitive
+ * sequence (Sec. 4.2: slices x primitives, in windows) every read and write stays inside the send / recv buffer,
+ * the neighbour's buffer or the connector's slots, the writes to each recv buffer tile it exactly once, and every
+ * edge carries as many slices as its receiver takes.  wg_map 2 = the labelling "XCD = (rank + channel) mod 8",
+ * which the kernel does not offer, kept here so that the check covers it.  msg (host, may be NULL): receives a
+ * description of the first violation.  Returns DFX_OK, or DFX_ERR_INVALID_ARG with msg filled.
+ */
+int dfx_check_geometry(int nranks, const dfx_config* cfg, dfx_kind kind, size_t count, dfx_dtype dtype, dfx_op op,
+                       int root, int coll_id, uint32_t wg_map, char* msg, size_t msg_bytes);
+
+/*
  * For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  One invocation of one collective on every vrank -- what dfx_init + dfx_prepare + dfx_submit_all do
  * with memory they allocate -- with everything the daemon kernel needs beyond the caller's buffers (SQ, CQ,

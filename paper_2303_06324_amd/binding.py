@@ -94,6 +94,7 @@ def _load() -> C.CDLL:
         "dfx_strerror": ([i], C.c_char_p),
         "dfx_build_id": ([], C.c_char_p),
         "dfx_copy_calibrate": ([vp, vp, sz, vp, C.POINTER(C.c_float)], i),
+        "dfx_check_geometry": ([i, C.POINTER(Config), i, sz, i, i, i, i, C.c_uint32, C.c_char_p, sz], i),
         "dfx_collective_noalloc": ([i, i, sz, i, i, i, C.POINTER(vp), C.POINTER(vp), vp, vp], i),
     }
     for name, (args, res) in sig.items():
@@ -268,3 +269,12 @@ def collective_noalloc(nranks: int, kind: int, count: int, dtype: int, op: int, 
     return _lib.dfx_collective_noalloc(nranks, kind, count, dtype, op, root, sb, rb,
                                        C.c_void_p(status_dev) if status_dev else None,
                                        C.c_void_p(stream) if stream else None)
+
+
+def check_geometry(nranks: int, kind: int, count: int, dtype: int, op: int = SUM, root: int = 0, coll_id: int = 0,
+                   wg_map: int = 0, cfg: Optional[Config] = None) -> str:
+    """Host-side self-check of the kernel's index arithmetic (no GPU needed); returns "" or the first violation."""
+    buf = C.create_string_buffer(512)
+    rc = _lib.dfx_check_geometry(nranks, C.byref(cfg) if cfg is not None else None, kind, count, dtype, op, root,
+                                 coll_id, wg_map, buf, 512)
+    return "" if rc == OK else (buf.value.decode() or strerror(rc))

@@ -36,6 +36,7 @@
 #include <stdint.h>
 
 #include "dfx_internal.h"
+#include "dfx_geometry.h"
 
 namespace {
 
@@ -46,8 +47,7 @@ constexpr int NT = DFX_WG_THREADS;
 #define DFX_UNROLL 8
 #endif
 constexpr int UNROLL = DFX_UNROLL;   // independent 16-byte vectors in flight per source and thread
-constexpr int KIND_AR = 0, KIND_AG = 1, KIND_RS = 2, KIND_BC = 3, KIND_RD = 4;
-constexpr int DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2, DT_I32 = 3, DT_COPY = -1;
+constexpr int DT_COPY = -1;   // a primitive without a reducing side moves bytes, whatever the element type
 
 enum { W_OK = 0, W_TIMEOUT = 1, W_STOP = 2 };
 enum { STOP_NONE = 0, STOP_ABORT = 1, STOP_QUIT = 2, STOP_EXIT = 3 };
@@ -438,96 +438,6 @@ struct Shared {
   uint16_t taskq[DFX_MAX_COLLS];     // task queue (Sec. 4.2 (1))
 };
 
-// primitive descriptor for (kind, position p in the sequence); the ring-chunk index travels in
-// the dynamic context and is stepped by next_cidx, so nothing here divides
-struct Prim {
-  bool recv, send;         // uses recv / send connector (send: waits for a free slot and fills it)
-  bool from_send, to_recv; // touches the send buffer / recv buffer
-  // Direct gather steps of an all-reduce: every rank's buffers lie in the same HBM, so the copy
-  // steps need no second copy through a FIFO slot.  notify: the result goes to the own recv buffer
-  // with device-coherent stores and the send connector's counter is raised without a slot being
-  // filled; din: the input is read from the previous rank's recv buffer instead of a slot;
-  // drain: no data, the wait ends when the next rank has consumed everything notified so far
-  // (the recv buffer is the caller's again once the completion is posted).
-  bool notify, din, drain;
-  bool din_send;   // the input is the previous rank's SEND buffer (first reduce step of a direct all-reduce / reduce-scatter)
-};
-
-__device__ __forceinline__ Prim make_prim(int kind, uint32_t R, uint32_t bc_pos, uint32_t p, bool direct) {
-  Prim q;
-  q.notify = q.din = q.drain = q.din_send = false;
-  if (R == 1) { q.recv = q.send = false; q.from_send = q.to_recv = true; return q; }   // copy
-  if (kind == KIND_AR && direct) {
-    const uint32_t last_reduce = R - 1;
-    q.recv = p > 0; q.send = p < last_reduce; q.from_send = p <= last_reduce; q.to_recv = p >= last_reduce;
-    // The opening send moves nothing either: the rank only notifies, and the next rank's first
-    // reduce step reads the chunk out of this rank's send buffer (which the caller leaves alone
-    // until the completion, and the drain keeps the completion behind that read).
-    if (p == 0) { q.send = false; q.from_send = false; q.notify = true; }             // notify only
-    else if (p == 1) q.din_send = true;                                               // recv-reduce-send / -copy from the neighbour's send buffer
-    if (p == last_reduce) q.notify = true;                                            // recv-reduce-copy, notify
-    else if (p > last_reduce && p < 2u * R - 2) { q.din = true; q.notify = true; }    // direct recv-copy, notify
-    else if (p == 2u * R - 2) q.din = true;                                           // direct recv-copy
-    else if (p == 2u * R - 1) { q.recv = false; q.to_recv = false; q.drain = true; }  // drain
-    return q;
-  }
-  if (kind == KIND_RS && direct) {
-    // the reduce phase of the direct all-reduce: notify only, then the first reduce step reads the
-    // neighbour's send buffer; the drain keeps the completion behind that read
-    q.recv = p > 0 && p < R; q.send = p > 0 && p + 1 < R; q.from_send = q.recv; q.to_recv = p == R - 1;
-    if (p == 0) q.notify = true;
-    else if (p == 1) q.din_send = true;
-    else if (p == R) q.drain = true;
-    return q;
-  }
-  if (kind == KIND_AR || kind == KIND_RS) {
-    const uint32_t last_reduce = R - 1;
-    if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = false; }                         // send
-    else if (p < last_reduce) { q.recv = true; q.send = true; q.from_send = true; q.to_recv = false; }           // recv-reduce-send
-    else if (p == last_reduce) { q.recv = true; q.send = (kind == KIND_AR); q.from_send = true; q.to_recv = true; }  // recv-reduce-copy(-send)
-    else if (p < 2u * R - 2) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }            // recv-copy-send
-    else { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }                               // recv-copy
-  } else if (kind == KIND_AG && direct) {
-    // every block is written once: the own one by a copy that notifies, the others by direct copies
-    q.send = false;
-    if (p == 0) { q.recv = false; q.from_send = true; q.to_recv = true; q.notify = true; }                        // copy, notify
-    else if (p < R) { q.recv = true; q.from_send = false; q.to_recv = true; q.din = true; q.notify = p < R - 1; } // direct recv-copy (, notify)
-    else { q.recv = false; q.from_send = false; q.to_recv = false; q.drain = true; }                              // drain
-  } else if (kind == KIND_AG) {
-    if (p == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }                          // copy-send
-    else if (p < R - 1) { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
-    else { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
-  } else if (kind == KIND_RD) {  // reduce chain root+1 -> root+2 -> ... -> root (bc_pos: 0 first, 1 middle, 2 the root, 3 second)
-    if (bc_pos == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = false; }                    // send
-    else if (bc_pos == 2) { q.recv = true; q.send = false; q.from_send = true; q.to_recv = true; }               // recv-reduce-copy
-    else { q.recv = true; q.send = true; q.from_send = true; q.to_recv = false; }                                 // recv-reduce-send
-    if (direct) {
-      // the first rank only notifies and the second one reads the slice out of its send buffer
-      if (bc_pos == 0) { q.send = false; q.from_send = false; q.notify = true; }
-      else if (bc_pos == 3 || R == 2) q.din_send = true;
-    }
-  } else if (direct) {  // broadcast chain with direct steps: every rank writes its recv buffer only
-    q.send = false; q.to_recv = true;
-    q.recv = bc_pos != 0; q.din = bc_pos != 0; q.from_send = bc_pos == 0; q.notify = bc_pos != 2;
-  } else {  // broadcast chain root -> root+1 -> ... -> root-1
-    if (bc_pos == 0) { q.recv = false; q.send = true; q.from_send = true; q.to_recv = true; }
-    else if (bc_pos == 2) { q.recv = true; q.send = false; q.from_send = false; q.to_recv = true; }
-    else { q.recv = true; q.send = true; q.from_send = false; q.to_recv = true; }
-  }
-  return q;
-}
-
-// A chain (broadcast, reduce) has one primitive per slice, so its drain cannot be a step of the
-// per-slice sequence: with direct steps it counts one round more than it has slices, and that
-// round is the drain (nothing to move; the last rank of the chain has sent nothing and passes at once).
-__device__ __forceinline__ Prim chain_drain_round(Prim q, int kind, bool direct, uint32_t g, uint32_t rounds) {
-  if (direct && (kind == KIND_BC || kind == KIND_RD) && g + 1 == rounds) {
-    q.recv = q.send = q.from_send = q.to_recv = q.notify = q.din = false;
-    q.drain = true;
-  }
-  return q;
-}
-
 __device__ __forceinline__ void raise_error(const DfxDaemonArgs& a, uint32_t code, uint32_t wg) {
   uint32_t expected = 0;
   if (__hip_atomic_compare_exchange_strong(&a.dev_ctl[DC_ERR], &expected, code, __ATOMIC_RELAXED, __ATOMIC_RELAXED, SCOPE_AGENT))
@@ -569,74 +479,6 @@ __device__ __forceinline__ u64 timeline_sample(u64 t0, u64 t1, uint32_t coll, ui
   return (t0 & 0xffffffffull) | (dur << 32) | ((u64)(coll & 0xfffu) << 48) | ((u64)(prim & 0xfu) << 60);
 }
 
-// Ring chunk that the first primitive of a sequence works on (see DfxDyn.cidx): an all-gather
-// starts with the rank's own block, the chains (broadcast, reduce) have one block, all-reduce and
-// reduce-scatter start with the chunk of the rank before.
-__device__ __forceinline__ uint32_t first_chunk(int kind, uint32_t rank, uint32_t R) {
-  if (kind == KIND_AG) return rank;
-  if (kind == KIND_BC || kind == KIND_RD || R == 1) return 0u;
-  return (rank + R - 1) % R;
-}
-
-// The SQE of an invocation "cooked" for one workgroup: every address a primitive needs resolved
-// once, so that a context load is a plain copy (Sec. 4.2 (4)).  vch: channel of the collective
-// that this workgroup serves.
-__device__ __forceinline__ DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool, uint32_t rank, uint32_t R, uint32_t vch) {
-  DfxCooked k;
-  k.sendbuf = q.sendbuf; k.recvbuf = q.recvbuf; k.count = q.count;
-  k.block_elems = q.block_elems; k.part_elems = q.part_elems;
-  uint8_t* conn = pool + q.conn_off;   // flags first, then slots
-  const uint32_t e_out = rank, e_in = (rank + R - 1) % R;
-  const size_t fo = (size_t)e_out * q.nchan + vch, fi = (size_t)e_in * q.nchan + vch;
-  uint8_t* slots = conn + (size_t)R * q.nchan * DFX_FLAG_STRIDE;
-  k.flags_out = (uint64_t)(conn + fo * DFX_FLAG_STRIDE);
-  k.flags_in = (uint64_t)(conn + fi * DFX_FLAG_STRIDE);
-  k.fifo_out = (uint64_t)(slots + fo * q.nslots * q.slot_bytes);
-  k.fifo_in = (uint64_t)(slots + fi * q.nslots * q.slot_bytes);
-  // a direct broadcast has no slots (no step of it fills or reads one)
-  if (q.kind == KIND_BC && (q.flags & DFX_SQE_DIRECT)) k.fifo_out = k.fifo_in = 0;
-  k.slice_elems = q.slice_elems; k.rounds = q.rounds; k.seq = q.seq;
-  k.nprim = (uint16_t)q.nprim; k.nchan = q.nchan;
-  k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = (uint8_t)(q.dtype | (q.op << 4));
-  // place in the chain: broadcast starts at the root, reduce at the rank after it
-  const uint32_t bpos = (rank + 2 * R - q.root - (q.kind == KIND_RD ? 1u : 0u)) % R;
-  k.bc_pos = bpos == 0 ? 0 : (bpos == R - 1 ? 2 : 1);
-  if (q.kind == KIND_RD && (q.flags & DFX_SQE_DIRECT) && bpos == 1 && R > 2) k.bc_pos = 3;   // reads the first rank's send buffer
-  if (q.flags & DFX_SQE_DIRECT) k.bc_pos |= DFX_CTX_DIRECT;   // a collective with direct steps
-  k.priority = q.priority; k.vch = (uint16_t)vch;
-  return k;
-}
-
-// Where slice g of ring chunk cidx lies for the workgroup that holds context S: element offsets
-// in the send and the recv buffer and the slice's length in bytes (clipped to the chunk's and the
-// channel's true length: the last ones may be short or empty).
-struct SliceGeom { u64 soff, doff; uint32_t bytes, eb; };
-__device__ __forceinline__ SliceGeom slice_geometry(const DfxCooked& S, uint32_t R, uint32_t g, uint32_t cidx) {
-  const int kind = S.kind, dt = S.dtype & 15;
-  SliceGeom o;
-  o.eb = (dt == DT_F32 || dt == DT_I32) ? 4u : 2u;
-  const uint32_t slice_elems = S.slice_elems, vch = S.vch;
-  const u64 count = S.count, block_elems = S.block_elems, part_elems = S.part_elems;
-  const bool ring_chunks = (kind == KIND_AR && R > 1);
-  u64 blen = count;
-  if (ring_chunks) {
-    const u64 start = (u64)cidx * block_elems;
-    blen = start >= count ? 0 : (count - start < block_elems ? count - start : block_elems);
-  }
-  u64 lo = (u64)vch * part_elems + (u64)g * slice_elems;
-  u64 hi = lo + slice_elems;
-  const u64 pend = (u64)(vch + 1) * part_elems;
-  if (hi > pend) hi = pend;
-  if (lo > blen) lo = blen;
-  if (hi > blen) hi = blen;
-  o.bytes = (uint32_t)(hi - lo) * o.eb;
-  o.soff = lo; o.doff = lo;
-  if (ring_chunks) { o.soff += (u64)cidx * block_elems; o.doff = o.soff; }
-  else if (kind == KIND_RS) o.soff += (u64)cidx * count;
-  else if (kind == KIND_AG) o.doff += (u64)cidx * count;
-  return o;
-}
-
 }  // namespace
 
 // Structure of a workgroup: wave 0 is the SCHEDULER, waves 1..4 are the MOVERS.
@@ -667,10 +509,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
   const uint32_t lane = tid & 63u;
   const bool sched = tid < 64;       // the scheduler wave
   const uint32_t wg = blockIdx.x;
-  uint32_t rank, ch;
-  // Workgroups go to the XCDs round-robin (workgroup w runs on XCD w mod 8).
-  if (a.wg_map == 0) { rank = wg % a.R; ch = wg / a.R; }       // a vrank per XCD (R = 8)
-  else { rank = wg / a.cmax; ch = wg % a.cmax; }               // a channel's whole ring per XCD
+  const WgPlace place = wg_place(a.wg_map, wg, a.R, a.cmax);
+  const uint32_t rank = place.rank, ch = place.ch;
   const uint32_t D = a.sq_depth;
   const bool coh = a.fifo_coherent != 0;
 
@@ -984,13 +824,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             uint32_t c_id = 0;
             if (lane < n) {
               c_id = q.coll_id;
-              // A collective with fewer channels than the grid has per rank starts at workgroup
-              // (coll_id * nchan) mod cmax, so that many small collectives spread over the rank's
-              // workgroups instead of queueing on the first ones; every rank derives the same
-              // start from the id, which keeps both ends of a connector on the same channel.
-              uint32_t my_vch = ch;
-              if (a.chan_spread && !is_exit_sqe && q.nchan < a.cmax)
-                my_vch = (ch + a.cmax - (c_id * q.nchan) % a.cmax) % a.cmax;
+              const uint32_t my_vch = is_exit_sqe ? ch : serving_channel(a.chan_spread != 0, ch, a.cmax, c_id, q.nchan);
               mine = !is_exit_sqe && my_vch < q.nchan && c_id < a.max_colls;
               if (mine) {
                 // cook the static context of this invocation into the context buffer (addresses
@@ -1234,25 +1068,9 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       // a notified result goes to the recv buffer through the coherent path of a slot
       if (q.notify) { jfout = jrb; jrb = nullptr; }
 
-      // The position after this primitive.  Slices are taken in windows of W: primitive p of every
-      // slice of the window, then primitive p+1 of every slice, ...  The neighbour does the same, so
-      // when this rank comes to (slice, p+1) the neighbour finished (slice, p) one job ago instead
-      // of at this very moment, and the hop latency hides behind the other slice's data.  The
-      // chunk index steps down the ring with p; a new window starts the sequence over.
-      uint32_t g_next = g, p_next = p, cidx_next = cidx;
-      {
-        const uint32_t W = a.window;
-        if (((g + 1) & (W - 1)) != 0 && g + 1 < S.rounds) ++g_next;
-        else {
-          g_next &= ~(W - 1);
-          cidx_next = (cidx == 0) ? a.R - 1 : cidx - 1;
-          if (++p_next == S.nprim) {
-            p_next = 0; g_next += W;
-            cidx_next = first_chunk(kind, rank, a.R);
-          }
-          if (kind == KIND_BC || kind == KIND_RD) cidx_next = 0;
-        }
-      }
+      // the position after this primitive (slices in windows, the chunk index stepping down the ring)
+      const SeqPos nx = next_position(kind, a.R, rank, a.window, S.rounds, S.nprim, g, p, cidx);
+      const uint32_t g_next = nx.g, p_next = nx.p, cidx_next = nx.cidx;
       const bool last = (g_next >= S.rounds);
       const uint32_t inv_seq = S.seq, inv_nchan = S.nchan;
 

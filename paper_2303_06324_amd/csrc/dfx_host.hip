@@ -19,6 +19,7 @@
 
 #include "../../include/dfx.h"
 #include "dfx_internal.h"
+#include "dfx_geometry.h"
 
 // defined next to the kernels
 hipError_t dfx_daemon_occupancy(int* blocks_per_cu);
@@ -1005,6 +1006,150 @@ const char* dfx_strerror(int s) {
     case DFX_ERR_TOO_LARGE: return "size beyond what the static scratch memory of this entry point is laid out for";
     default: return "unknown status";
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// Geometry self-check: the kernel's index arithmetic walked on the host, without a GPU
+// ------------------------------------------------------------------------------------------
+int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t count, dfx_dtype dtype, dfx_op op, int root,
+                       int coll_id, uint32_t wg_map, char* msg, size_t msg_bytes) {
+  auto fail = [&](const char* fmt, auto... v) -> int {
+    if (msg && msg_bytes) snprintf(msg, msg_bytes, fmt, v...);
+    return DFX_ERR_INVALID_ARG;
+  };
+  if (msg && msg_bytes) msg[0] = 0;
+  dfx_config cfg;
+  dfx_config_default(&cfg);
+  if (ucfg) { if (ucfg->struct_bytes != sizeof(dfx_config)) return fail("%s", "config size"); cfg = *ucfg; }
+  if (nranks < 1 || nranks > 64 || coll_id < 0 || (uint32_t)coll_id >= cfg.max_colls || wg_map > 2) return fail("%s", "arguments");
+  if (!is_pow2(cfg.nslots) || cfg.nslots < 2 || cfg.nslots > 64) return fail("%s", "nslots");
+  while (cfg.window >= cfg.nslots) cfg.window /= 2;
+  const uint32_t R = (uint32_t)nranks, cmax = cfg.max_channels, nwg = R * cmax;
+  DfxStatic t;
+  uint64_t conn_bytes = 0;
+  const uint64_t conn_off = 4096;              // some block inside the pool
+  int rc = plan_collective(cfg, nranks, coll_id, kind, count, dtype, op, root, 0, conn_off, &t, &conn_bytes);
+  if (rc != DFX_OK) return fail("plan_collective: %d", rc);
+  const uint32_t eb = elem_bytes(dtype);
+  const uint64_t send_bytes = (kind == DFX_REDUCESCATTER ? count * R : count) * eb;
+  const uint64_t recv_bytes = (kind == DFX_ALLGATHER ? count * R : count) * eb;
+  // made-up addresses, far apart: the pool, and every rank's send and recv buffer
+  const uint64_t pool = 0x100000000000ull;
+  auto sendbase = [&](uint32_t r) { return 0x200000000000ull + (uint64_t)r * 0x010000000000ull; };
+  auto recvbase = [&](uint32_t r) { return 0x300000000000ull + (uint64_t)r * 0x010000000000ull; };
+  const uint64_t blk_lo = pool + conn_off, blk_hi = blk_lo + conn_bytes;
+  const uint64_t flags_hi = blk_lo + (uint64_t)R * t.nchan * DFX_FLAG_STRIDE;
+  const bool direct = (t.flags & DFX_SQE_DIRECT) != 0;
+  const bool no_slots = direct && kind == DFX_BROADCAST;
+
+  // (i) the map is a bijection between workgroups and (rank, channel); under the third labelling too
+  // (XCD = (rank + channel) mod 8: the ranks of every channel's group of R workgroups rotated by the channel)
+  std::vector<int> owner((size_t)R * cmax, -1);
+  std::vector<int> serves((size_t)R * t.nchan, -1);
+  std::vector<DfxCooked> cooked((size_t)R * t.nchan);
+  for (uint32_t wg = 0; wg < nwg; ++wg) {
+    WgPlace w = wg_place(wg_map == 2 ? 0u : wg_map, wg, R, cmax);
+    if (wg_map == 2) w.rank = (w.rank + w.ch) % R;
+    if (w.rank >= R || w.ch >= cmax) return fail("workgroup %u maps to rank %u channel %u", wg, w.rank, w.ch);
+    int& o = owner[(size_t)w.rank * cmax + w.ch];
+    if (o >= 0) return fail("workgroups %d and %u both map to rank %u channel %u", o, wg, w.rank, w.ch);
+    o = (int)wg;
+    const uint32_t vch = serving_channel(cfg.chan_spread != 0, w.ch, cmax, (uint32_t)coll_id, t.nchan);
+    if (vch >= t.nchan) continue;
+    int& sv = serves[(size_t)w.rank * t.nchan + vch];
+    if (sv >= 0) return fail("rank %u channel %u of the collective is served by workgroups %d and %u", w.rank, vch, sv, wg);
+    sv = (int)wg;
+    DfxStatic q = t;
+    q.sendbuf = sendbase(w.rank); q.recvbuf = recvbase(w.rank);
+    cooked[(size_t)w.rank * t.nchan + vch] = cook_sqe(q, (uint8_t*)(uintptr_t)pool, w.rank, R, vch);
+  }
+  for (size_t i = 0; i < serves.size(); ++i)
+    if (serves[i] < 0) return fail("rank %zu channel %zu of the collective has no workgroup", i / t.nchan, i % t.nchan);
+
+  // (ii) both ends of every connector resolve to the same flag line and the same slots, inside the block
+  const uint64_t conn_slot_bytes = (uint64_t)t.nslots * t.slot_bytes;
+  for (uint32_t r = 0; r < R; ++r)
+    for (uint32_t v = 0; v < t.nchan; ++v) {
+      const DfxCooked& me = cooked[(size_t)r * t.nchan + v];
+      const DfxCooked& nx = cooked[(size_t)((r + 1) % R) * t.nchan + v];
+      if (me.flags_out != nx.flags_in) return fail("edge %u channel %u: sender's flag line %llx, receiver's %llx", r, v, (unsigned long long)me.flags_out, (unsigned long long)nx.flags_in);
+      if (me.fifo_out != nx.fifo_in) return fail("edge %u channel %u: sender's slots %llx, receiver's %llx", r, v, (unsigned long long)me.fifo_out, (unsigned long long)nx.fifo_in);
+      if (me.flags_out < blk_lo || me.flags_out + DFX_FLAG_STRIDE > flags_hi || (me.flags_out & (DFX_FLAG_STRIDE - 1)))
+        return fail("edge %u channel %u: flag line %llx outside the block's flag lines", r, v, (unsigned long long)me.flags_out);
+      if (!no_slots && (me.fifo_out < flags_hi || me.fifo_out + conn_slot_bytes > blk_hi))
+        return fail("edge %u channel %u: slots %llx outside the block", r, v, (unsigned long long)me.fifo_out);
+      if (no_slots && (me.fifo_out || me.fifo_in)) return fail("%s", "a direct broadcast has no slots");
+    }
+
+  // (iii) every job of every workgroup's walk through the invocation stays inside its buffers and slots;
+  // what is written to a recv buffer tiles it exactly; what one rank sends on an edge the next one receives
+  struct Iv { uint64_t lo, hi; };
+  std::vector<std::vector<Iv>> written(R);
+  std::vector<uint64_t> n_out((size_t)R * t.nchan, 0), n_in((size_t)R * t.nchan, 0);
+  for (uint32_t r = 0; r < R; ++r)
+    for (uint32_t v = 0; v < t.nchan; ++v) {
+      const DfxCooked& S = cooked[(size_t)r * t.nchan + v];
+      const uint32_t prev = (r + R - 1) % R;
+      uint32_t g = 0, p = 0, cidx = first_chunk(kind, r, R);
+      uint64_t sent = 0, recvd = 0, steps = 0;
+      for (;;) {
+        const Prim q = chain_drain_round(make_prim(kind, R, S.bc_pos & 3u, p, direct), kind, direct, g, S.rounds);
+        const SliceGeom geo = slice_geometry(S, R, g, cidx);
+        const uint64_t slot_b = (uint64_t)S.slice_elems * geo.eb;
+        if (geo.bytes > slot_b) return fail("rank %u channel %u slice %u primitive %u: %u bytes in a slot of %llu", r, v, g, p, geo.bytes, (unsigned long long)slot_b);
+        const bool moves = !(q.drain || (!q.recv && !q.from_send));
+        const uint64_t nb = moves ? geo.bytes : 0;
+        // (an empty slice -- a ragged message's last chunks -- is a handshake only: no address of it is used)
+        if (nb && q.recv && !(q.din || q.din_send)) {
+          const uint64_t a = S.fifo_in + (recvd & (S.nslots - 1)) * slot_b;
+          if (a < S.fifo_in || a + nb > S.fifo_in + conn_slot_bytes) return fail("rank %u channel %u: read of slot at %llx leaves the connector", r, v, (unsigned long long)a);
+        }
+        if (nb && q.send) {
+          const uint64_t a = S.fifo_out + (sent & (S.nslots - 1)) * slot_b;
+          if (a < S.fifo_out || a + nb > S.fifo_out + conn_slot_bytes) return fail("rank %u channel %u: write of slot at %llx leaves the connector", r, v, (unsigned long long)a);
+        }
+        if (nb && q.from_send) {
+          const uint64_t a = S.sendbuf + geo.soff * geo.eb;
+          if (a < sendbase(r) || a + nb > sendbase(r) + send_bytes) return fail("rank %u channel %u slice %u primitive %u: send buffer read %llu+%llu of %llu", r, v, g, p, (unsigned long long)(a - sendbase(r)), (unsigned long long)nb, (unsigned long long)send_bytes);
+        }
+        if (nb && q.din_send) {
+          const uint64_t a = sendbase(prev) + geo.soff * geo.eb;
+          if (a + nb > sendbase(prev) + send_bytes) return fail("rank %u channel %u slice %u: read of the previous rank's send buffer %llu+%llu of %llu", r, v, g, (unsigned long long)(a - sendbase(prev)), (unsigned long long)nb, (unsigned long long)send_bytes);
+        }
+        if (nb && q.din) {
+          const uint64_t a = recvbase(prev) + geo.doff * geo.eb;
+          if (a + nb > recvbase(prev) + recv_bytes) return fail("rank %u channel %u slice %u: read of the previous rank's recv buffer %llu+%llu of %llu", r, v, g, (unsigned long long)(a - recvbase(prev)), (unsigned long long)nb, (unsigned long long)recv_bytes);
+        }
+        if (nb && q.to_recv) {
+          const uint64_t a = S.recvbuf + geo.doff * geo.eb;
+          if (a < recvbase(r) || a + nb > recvbase(r) + recv_bytes) return fail("rank %u channel %u slice %u primitive %u: recv buffer write %llu+%llu of %llu", r, v, g, p, (unsigned long long)(a - recvbase(r)), (unsigned long long)nb, (unsigned long long)recv_bytes);
+          if (nb) written[r].push_back({a - recvbase(r), a - recvbase(r) + nb});
+        }
+        if (q.send || q.notify) { ++sent; ++n_out[(size_t)r * t.nchan + v]; }
+        if (q.recv) { ++recvd; ++n_in[(size_t)r * t.nchan + v]; }
+        const SeqPos nx = next_position(kind, R, r, cfg.window, S.rounds, S.nprim, g, p, cidx);
+        g = nx.g; p = nx.p; cidx = nx.cidx;
+        if (g >= S.rounds) break;
+        if (++steps > (1ull << 26)) return fail("rank %u channel %u: the walk does not end", r, v);
+      }
+    }
+  for (uint32_t r = 0; r < R; ++r)
+    for (uint32_t v = 0; v < t.nchan; ++v)
+      if (n_out[(size_t)r * t.nchan + v] != n_in[(size_t)((r + 1) % R) * t.nchan + v])
+        return fail("edge %u channel %u: %llu slices sent or notified, %llu received", r, v, (unsigned long long)n_out[(size_t)r * t.nchan + v], (unsigned long long)n_in[(size_t)((r + 1) % R) * t.nchan + v]);
+  for (uint32_t r = 0; r < R; ++r) {
+    uint64_t want = recv_bytes;
+    if (kind == DFX_REDUCE && r != (uint32_t)root) want = 0;
+    std::vector<Iv>& w = written[r];
+    std::sort(w.begin(), w.end(), [](const Iv& a, const Iv& b) { return a.lo < b.lo; });
+    uint64_t at = 0;
+    for (const Iv& iv : w) {
+      if (iv.lo != at) return fail("rank %u: recv buffer bytes %llu .. %llu are written %s", r, (unsigned long long)std::min(at, iv.lo), (unsigned long long)std::max(at, iv.lo), iv.lo < at ? "twice" : "never");
+      at = iv.hi;
+    }
+    if (at != want) return fail("rank %u: %llu of %llu recv buffer bytes written", r, (unsigned long long)at, (unsigned long long)want);
+  }
+  return DFX_OK;
 }
 
 // ------------------------------------------------------------------------------------------
