@@ -380,6 +380,91 @@ __device__ __forceinline__ void move_dispatch(int dtype, const void* fin, const 
   }
 }
 
+#ifndef DFX_LDS_STAGE
+#define DFX_LDS_STAGE 0
+#endif
+#if DFX_LDS_STAGE
+// Experiment build (-DDFX_LDS_STAGE=1): the recv-reduce-send step with both inputs staged through LDS.
+// Each mover wave brings the vectors of the connector slot and of the send buffer in with gfx950's
+// 16-byte global -> LDS loads (no registers held while they travel), STAGE_D - 1 batches of STAGE_U
+// vectors per lane and source ahead of the batch being reduced, reads them back with ds_read_b128, adds,
+// and stores to the outgoing slot.  Per lane 2 x STAGE_U x (STAGE_D - 1) = 24 loads are in flight all the
+// time, instead of 16 that are issued together and waited for together.
+// The waits are counted by hand: the compiler would put vmcnt(0) in front of every LDS read that follows
+// an LDS-writing load, which would undo the prefetch.  Vector memory operations of a wave complete in the
+// order they were issued, so "at most N outstanding" means that everything older than the youngest N is
+// done; that is also why both inputs go through LDS: a wait for a register load would wait for every
+// LDS-writing load issued before it.
+constexpr uint32_t STAGE_U = 4;                              // vectors per lane, source and batch
+constexpr uint32_t STAGE_D = 4;                              // batches in LDS per wave (STAGE_D - 1 ahead of the one in use)
+constexpr uint32_t STAGE_BATCH_BYTES = 2 * STAGE_U * 1024;   // two sources x U vectors x 64 lanes x 16 bytes
+constexpr uint32_t STAGE_WAVE_BYTES = STAGE_D * STAGE_BATCH_BYTES;
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+
+template <int N>
+__device__ __forceinline__ void stage_read(uint32_t lds_addr, v4u (&v)[8]) {
+  asm volatile(
+      "s_waitcnt vmcnt(%9)\n\t"
+      "ds_read_b128 %0, %8\n\t"
+      "ds_read_b128 %1, %8 offset:1024\n\t"
+      "ds_read_b128 %2, %8 offset:2048\n\t"
+      "ds_read_b128 %3, %8 offset:3072\n\t"
+      "ds_read_b128 %4, %8 offset:4096\n\t"
+      "ds_read_b128 %5, %8 offset:5120\n\t"
+      "ds_read_b128 %6, %8 offset:6144\n\t"
+      "ds_read_b128 %7, %8 offset:7168\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7])
+      : "v"(lds_addr), "n"(N)
+      : "memory");
+}
+
+// bytes: a multiple of STAGE_U x NTH x 16; fin_p and sb 16-byte aligned; stage: this workgroup's staging
+// area (NTH / 64 waves x STAGE_WAVE_BYTES)
+template <int DT, int NTH>
+__device__ __forceinline__ void move_rrs_staged(const void* fin_p, const char* __restrict__ sb, void* fout_p, uint32_t bytes,
+                                                uint32_t tid, lds_byte* stage) {
+  static_assert(STAGE_U == 4, "stage_read reads 2 x 4 vectors");
+  const Slot<AUX_DEVICE> fout(fout_p, bytes);
+  const uint32_t wave = tid >> 6, lane = tid & 63u;
+  lds_byte* mine = stage + wave * STAGE_WAVE_BYTES;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)mine + lane * 16u;
+  const uint4* F = (const uint4*)fin_p;
+  const uint4* S = (const uint4*)sb;
+  const uint32_t nvec = bytes >> 4, per_batch = STAGE_U * NTH, nbatch = nvec / per_batch;
+  auto bring = [&](uint32_t k) {       // batch k -> its place in LDS: 2 x STAGE_U instructions
+    lds_byte* dst = mine + (k % STAGE_D) * STAGE_BATCH_BYTES;
+    const uint32_t i = tid + k * per_batch;
+#pragma unroll
+    for (uint32_t u = 0; u < STAGE_U; ++u)
+      __builtin_amdgcn_global_load_lds((const void*)&F[i + u * NTH], (__attribute__((address_space(3))) void*)(dst + u * 1024), 16, 0, AUX_DEVICE);
+#pragma unroll
+    for (uint32_t u = 0; u < STAGE_U; ++u)
+      __builtin_amdgcn_global_load_lds((const void*)&S[i + u * NTH], (__attribute__((address_space(3))) void*)(dst + (STAGE_U + u) * 1024), 16, 0, 2 /* nt */);
+  };
+  for (uint32_t k = 0; k + 1 < STAGE_D && k < nbatch; ++k) bring(k);
+  for (uint32_t b = 0; b < nbatch; ++b) {
+    if (b + STAGE_D - 1 < nbatch) bring(b + STAGE_D - 1);
+    asm volatile("" ::: "memory");
+    // Issued after batch b's loads: the loads of the batches ahead (2U each) and, in the steady state, the
+    // stores of the STAGE_D - 1 iterations in between (U each).  Towards the ends the stores are left out of
+    // the count: a smaller count only waits for more.
+    const uint32_t ahead = (nbatch - 1 - b) < (STAGE_D - 1) ? (nbatch - 1 - b) : (STAGE_D - 1);
+    v4u v[8];
+    const uint32_t at = lds0 + (b % STAGE_D) * STAGE_BATCH_BYTES;
+    if (ahead == STAGE_D - 1 && b >= STAGE_D - 1) stage_read<(STAGE_D - 1) * 3 * STAGE_U>(at, v);
+    else if (ahead == 3) stage_read<3 * 2 * STAGE_U>(at, v);
+    else if (ahead == 2) stage_read<2 * 2 * STAGE_U>(at, v);
+    else if (ahead == 1) stage_read<1 * 2 * STAGE_U>(at, v);
+    else stage_read<0>(at, v);
+    const uint32_t i = tid + b * per_batch;
+#pragma unroll
+    for (uint32_t u = 0; u < STAGE_U; ++u)
+      fout.st16((i + u * NTH) << 4, add_vec<DT>(__builtin_bit_cast(uint4, v[u]), __builtin_bit_cast(uint4, v[STAGE_U + u])));
+  }
+}
+#endif
+
 // fin / sb / rb / fout are null when the primitive does not use that side.
 // AUX: how connector slots are accessed (AUX_DEVICE, or AUX_CACHED in the fenced mode).
 template <int AUX, int NTH>
@@ -436,6 +521,9 @@ struct Shared {
   u64 stat[DFX_NSTAT];               // counters (LDS atomics without return: one instruction, no wait)
   uint16_t rlist[DFX_MAX_COLLS];     // queue positions the readiness scan found runnable, ascending
   uint16_t taskq[DFX_MAX_COLLS];     // task queue (Sec. 4.2 (1))
+#if DFX_LDS_STAGE
+  __attribute__((aligned(16))) unsigned char stage[(DFX_MOVERS / 64) * STAGE_WAVE_BYTES];   // experiment build: staging area of the mover waves
+#endif
 };
 
 __device__ __forceinline__ void raise_error(const DfxDaemonArgs& a, uint32_t code, uint32_t wg) {
@@ -539,13 +627,17 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
     // =====================================================================================
     // mover waves
     // =====================================================================================
-    const uint32_t mtid = tid - 64;
+    // The mover waves work in DFX_MOVER_GROUPS groups; group k takes the jobs k, k + GROUPS, ...: with two
+    // groups the drain of one job's stores and the first loads of the next overlap in time.
+    constexpr uint32_t GROUPS = DFX_MOVER_GROUPS, GTHREADS = DFX_MOVERS / GROUPS;
+    const uint32_t mtid = (tid - 64) % GTHREADS;
+    const uint32_t group = (tid - 64) / GTHREADS;
     const bool first_wave = mtid < 64;
-    uint32_t seen = 0;
+    uint32_t seen = group;
     for (;;) {
       // the leave flag is looked at only when no job is waiting: every posted job is executed
       bool go = true;
-      while (lds_ld(&sh.job_seq) == seen) {
+      while ((int32_t)(lds_ld(&sh.job_seq) - seen) <= 0) {
         if (lds_ld(&sh.leave)) { go = false; break; }
         __builtin_amdgcn_s_sleep(1);
       }
@@ -555,8 +647,20 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       if (a.trace_on > 1 && first_wave) t0 = wall_clock64();
       // fenced mode: every wave invalidates before its own loads of the slot (the poll was the scheduler's)
       if (!coh && j.fin && j.bytes) fence_acquire_agent();
-      if (coh) run_prim<AUX_DEVICE, DFX_MOVERS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
-      else run_prim<AUX_CACHED, DFX_MOVERS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
+#if DFX_LDS_STAGE
+      if (coh && GROUPS == 1 && j.fin && j.sb && !j.rb && j.fout && (j.dtype >> 4) == OP_SUM && j.bytes &&
+          j.bytes % (STAGE_U * GTHREADS * 16u) == 0 && (((uintptr_t)j.sb | (uintptr_t)j.fin) & 15u) == 0) {
+        lds_byte* st = (lds_byte*)sh.stage;
+        switch (j.dtype & 15) {
+          case DT_F32: move_rrs_staged<DT_F32, GTHREADS>(j.fin, j.sb, j.fout, j.bytes, mtid, st); break;
+          case DT_BF16: move_rrs_staged<DT_BF16, GTHREADS>(j.fin, j.sb, j.fout, j.bytes, mtid, st); break;
+          case DT_F16: move_rrs_staged<DT_F16, GTHREADS>(j.fin, j.sb, j.fout, j.bytes, mtid, st); break;
+          default: move_rrs_staged<DT_I32, GTHREADS>(j.fin, j.sb, j.fout, j.bytes, mtid, st); break;
+        }
+      } else
+#endif
+      if (coh) run_prim<AUX_DEVICE, GTHREADS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
+      else run_prim<AUX_CACHED, GTHREADS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
       // this wave's stores (and loads) have been performed before it counts itself done
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __builtin_amdgcn_s_waitcnt(0);
@@ -565,29 +669,29 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       uint32_t last = 0;
       if (lane == 0) {
         const uint32_t old = __hip_atomic_fetch_add(&sh.wave_done[seen & 1], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
-        last = (old + 1 == DFX_MOVERS / 64) ? 1u : 0u;
+        last = (old + 1 == GTHREADS / 64) ? 1u : 0u;
         if (first_wave && a.trace_on > 1) {
           bump(sh.stat, ST_T_DATA, t1 - t0);
           if (a.trace_on == 3 && trace && j.prim != 0xffu) trace_put(trace, &sh.trace_n, timeline_sample(t0, t1, j.coll, j.prim));   // not the drain step
         }
       }
       if (bcast0(last)) {
-        // all mover waves have drained job `seen`: its data is in memory, raise the counters
+        // all waves of the group have drained job `seen`: its data is in memory
         if (lane == 0) {
           const Flight f = sh.fl[seen & 1];
+          // Jobs are published in order: a counter raised for job k tells the neighbour that every slice
+          // up to k is there, so the job before must have been published (with one group every wave has
+          // finished it by now and its publisher is a few instructions away; with two it may still run).
+          while (lds_ld(&sh.jobs_done) != seen) __builtin_amdgcn_s_sleep(0);
           if (!coh) fence_release_agent();
           if (f.tail_out) raise_counter(f.tail_out, f.sent_new);
           if (f.head_in) raise_counter(f.head_in, f.recvd_new);
           __hip_atomic_store(&sh.wave_done[seen & 1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
           if (a.trace_on > 1) bump(sh.stat, ST_T_PUB, wall_clock64() - t1);
-          // jobs finish in order (every wave takes them in order), but the publisher of the job
-          // before may still be a few instructions short of reporting it: let it go first (it
-          // waits for nothing), so that the scheduler retires jobs strictly in order
-          while (lds_ld(&sh.jobs_done) != seen) __builtin_amdgcn_s_sleep(0);
           lds_st(&sh.jobs_done, seen + 1);
         }
       }
-      ++seen;
+      seen += GROUPS;
     }
   } else {
     // =====================================================================================

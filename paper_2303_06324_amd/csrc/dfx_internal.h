@@ -8,6 +8,9 @@
 #define DFX_WG_THREADS 320      // threads per daemon workgroup: one scheduler wavefront + the mover wavefronts
 #endif
 #define DFX_MOVERS (DFX_WG_THREADS - 64)   // threads of the mover wavefronts
+#ifndef DFX_MOVER_GROUPS
+#define DFX_MOVER_GROUPS 1      // groups the mover wavefronts work in (1 or 2): group k takes every GROUPS-th job
+#endif
 #define DFX_MAX_COLLS 4096      // upper bound for dfx_config.max_colls (LDS task queue = 8 KB)
 #define DFX_CTX_SLOTS 64        // LDS active context slots, indexed by a hash of coll_id (Sec. 5)
 #define DFX_TRACE_N 4096        // context-switch latency samples kept per workgroup
