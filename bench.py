@@ -41,6 +41,12 @@ def moved_bytes(msg_bytes: int, nranks: int) -> int:
     return (5 * nranks - 5) * msg_bytes
 
 
+def fold_bytes(msg_bytes: int, nranks: int) -> int:
+    """What an all-reduce in fold steps (the default below 2 MiB per rank) moves: rank r reads chunk r out of all R
+    send buffers and writes it once, then reads and writes the other R-1 chunks: (3R-1)/R * M per rank."""
+    return (3 * nranks - 1) * msg_bytes
+
+
 def cpu_baseline(sends, min_seconds: float = 10.0, max_reps: int = 40):
     """The oracle as it stands (numpy replay of the ring schedule: R rank objects exchanging chunks through
     queues) on the bench's own inputs, timed on the machine's host cores: one worker thread per vrank when there

@@ -62,6 +62,13 @@ Two variations of Alg. 1 can be switched on, to ask whether they keep its livene
     (most primitives done; ties in queue order), and once n slices have been taken in the
     pass it ends with the entry in hand: every rank ranks the collectives alike, so the
     ranks settle on the same few of them (the coalescing of choices that Sec. 4.3 aims at).
+  * `fold = True`: an all-reduce runs in three steps that each wait on ALL ranks instead of 2R-1 steps that
+    each wait on the neighbour (every rank's buffers are readable by every other): "fold_all" waits until
+    every rank has fetched (published) the invocation, then rank r combines chunk r out of all R send buffers
+    in the ring's order x[r+1] (op) ... (op) x[r] into its recv buffer; "gather_all" waits until every rank
+    has done so and copies the other chunks out of their owners' recv buffers; "last_wait" waits until every
+    rank has copied and moves nothing.  Three shared counters per collective (published / folded / gathered)
+    carry the waits; each step is still poll-then-move, so a stuck one is preempted like any primitive.
   * `priority_order = True` (Sec. 4.3 "Priority-based Ordering"): the SQ is looked at before every
     pass, a fetched collective is inserted behind the queued ones of equal or higher user priority
     (Coll.priority, larger = more urgent), and a focused pass ranks the runnable entries by
@@ -103,6 +110,11 @@ PRIMS = {
     "direct_reduce_copy_notify": (True, 2),    # the same as the last reduce step (two ranks)
     "direct_reduce_copy": (True, 0),           # the same as the last step of a reduce-scatter (two ranks)
     "drain": (False, 3),
+    # fold steps of an all-reduce (Policy.fold): send side 4 / 5 / 6 = wait until every rank has published /
+    # folded / gathered this invocation (a shared counter reaches (invocation + 1) x R)
+    "fold_all": (False, 4),
+    "gather_all": (False, 5),
+    "last_wait": (False, 6),
 }
 
 
@@ -122,6 +134,7 @@ class Policy:
     scan: bool = False            # a pass visits only the entries whose wait conditions hold at its start
     focus: int = 0                # with scan: furthest-along entries first, and the pass ends after this many slices
     direct: bool = False          # steps that read the previous rank's recv / send buffer instead of a slot (notify / drain)
+    fold: bool = False            # all-reduces in three steps that wait on all ranks (fold_all, gather_all, last_wait)
     priority_order: bool = False  # priority-based ordering: fetch before every pass, queue sorted by Coll.priority, priority ranks first
 
 
@@ -135,7 +148,7 @@ class Coll:
 
 
 def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
-            recv_blocks: List[Tuple[int, int]], direct: bool = False):
+            recv_blocks: List[Tuple[int, int]], direct: bool = False, fold: bool = False):
     """Per-rank primitive sequence: list of (name, send-buffer block, recv-buffer block).
     `blocks` / `recv_blocks` are the element ranges of ring chunk j in the send / recv buffer."""
     none = None
@@ -143,6 +156,8 @@ def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
         return [("copy", blocks[0], recv_blocks[0])]
     b = lambda j: blocks[j % R]
     d = lambda j: recv_blocks[j % R]
+    if kind == AR and fold:
+        return [("fold_all", b(r), d(r)), ("gather_all", none, none), ("last_wait", none, none)]
     if kind == AR:
         p = [("send", b(r - 1), none)]
         p += [("recv_reduce_send", b(r - 1 - s), none) for s in range(1, R - 1)]
@@ -291,6 +306,8 @@ class Daemon:
         self.exit = False
         self.cq: List[Tuple[int, int]] = []
         self.seq_of: Dict[int, int] = {}
+        self.inv_of: Dict[int, int] = {}     # coll -> how often this rank had fetched it before (the same on every rank)
+        self.ninv: Dict[int, int] = {}
         self.jobs: List[tuple] = []            # claimed slices not yet moved (lookahead)
         self.ready: Optional[List[int]] = None # queue positions found runnable by the scan of the pass in flight
         self.rk = 0                            # cursor in self.ready
@@ -321,7 +338,11 @@ class Daemon:
             else:
                 self.taskq.append(coll)
             self.seq_of[coll] = seq
+            self.inv_of[coll] = self.ninv.get(coll, 0)
+            self.ninv[coll] = self.inv_of[coll] + 1
             self.saved[coll] = [0, 0]
+            if self.S.is_fold(coll):
+                self.S.foldcnt[coll][0] += 1     # the buffers of this invocation are published at the fetch
             self.stats.max_taskq = max(self.stats.max_taskq, len(self.taskq))
 
     def _load(self, coll):
@@ -372,11 +393,19 @@ class Daemon:
             return ("drain", None, None)
         return S.progs[coll][self.r][p]
 
+    def _fold_ok(self, coll, send_side):
+        """Fold steps: the shared counter of the step (4 published, 5 folded, 6 gathered) has reached every rank's
+        share of this invocation."""
+        if send_side < 4:
+            return True
+        return self.S.foldcnt[coll][send_side - 4] >= (self.inv_of[coll] + 1) * self.S.R
+
     def _runnable(self, coll):
         g, p = self.active if self.loaded == coll else self.saved[coll]
         need_recv, send_side = PRIMS[self._prim(coll, g, p)[0]]
         rd_ok, wr_ok, drained = self._conds(coll, p)
-        return (not need_recv or rd_ok) and (send_side != 1 or wr_ok) and (send_side != 3 or drained)
+        return ((not need_recv or rd_ok) and (send_side != 1 or wr_ok) and (send_side != 3 or drained)
+                and self._fold_ok(coll, send_side))
 
     def mover_tick(self) -> bool:
         """Move the oldest claimed slice (lookahead mode): data, shared counters, and the CQE if it was the last."""
@@ -454,7 +483,8 @@ class Daemon:
         fout = S.fifo[coll][self.r]
         self.stats.polls += 1
         rd_ok, wr_ok, drained = self._conds(coll, p)
-        ok = (not need_recv or rd_ok) and (send_side != 1 or wr_ok) and (send_side != 3 or drained)
+        ok = ((not need_recv or rd_ok) and (send_side != 1 or wr_ok) and (send_side != 3 or drained)
+              and self._fold_ok(coll, send_side))
         if not ok:
             if self.thr >= INF:
                 return False               # spins forever: no state change
@@ -514,11 +544,13 @@ class System:
         self.progs, self.rounds, self.fifo = [], [], []
         for c in colls:
             sb, db, blen = layout(c, R)
-            self.progs.append([program(c.kind, R, r, c.root, sb, db, policy.direct) for r in range(R)])
-            self.rounds.append(max(1, -(-blen // policy.slice_elems)))
+            is_fold = policy.fold and c.kind == AR and R > 1
+            self.progs.append([program(c.kind, R, r, c.root, sb, db, policy.direct, is_fold) for r in range(R)])
+            self.rounds.append(1 if is_fold else max(1, -(-blen // policy.slice_elems)))   # fold steps: one slice per share
             if policy.direct and c.kind in CHAINS and R > 1:
                 self.rounds[-1] += 1     # the last round of a chain with direct steps is the drain
             self.fifo.append([Fifo(policy.K) for _ in range(R)])
+        self.foldcnt = [[0, 0, 0] for _ in colls]     # fold steps: ranks that have published / folded / gathered, over all invocations
         self.daemons = [Daemon(self, r) for r in range(R)]
         self.pending = [[] for _ in range(R)]   # host side: submissions not yet pushed to the SQ
         self.nsub = [0] * R
@@ -541,6 +573,9 @@ class System:
             while self.host_tick(r):
                 pass
 
+    def is_fold(self, ci) -> bool:
+        return self.policy.fold and self.colls[ci].kind == AR and self.R > 1
+
     # -- data phase
     def _slice(self, blk, g):
         if blk is None:
@@ -553,7 +588,21 @@ class System:
         c = self.colls[ci]
         tag_out = (g, p)
         x = None
-        if name == "drain":
+        if name == "drain" or name == "last_wait":
+            return
+        if name in ("fold_all", "gather_all"):
+            # whole chunks (one slice per share), read out of the other ranks' buffers in place
+            if self.with_data:
+                cb = layout(c, self.R)[0]
+                if name == "fold_all":
+                    lo, hi = cb[r]
+                    self.recvs[ci][r][lo:hi] = rd.fold_rotated([s[lo:hi] for s in self.sends[ci]], r + 1, c.dtype)
+                else:
+                    for j in range(self.R):
+                        if j != r:
+                            lo, hi = cb[j]
+                            self.recvs[ci][r][lo:hi] = self.recvs[ci][j][lo:hi]
+            self.foldcnt[ci][1 if name == "fold_all" else 2] += 1
             return
         if PRIMS[name][0]:
             tag, x = fin.pop()
@@ -608,7 +657,7 @@ class System:
                        tuple((j[0], j[1], j[2]) for j in d.jobs),
                        (tuple(d.ready), d.rk, d.taken if self.policy.focus else 0) if d.in_pass and d.ready is not None else None))
         fs = tuple((f.head, f.tail) for fl in self.fifo for f in fl)
-        return (tuple(ds), fs, tuple(tuple(p) for p in self.pending))
+        return (tuple(ds), fs, tuple(tuple(p) for p in self.pending), tuple(tuple(c) for c in self.foldcnt))
 
     def clone(self):
         """Copy of the token-only model (immutable program tables are shared)."""
@@ -617,6 +666,7 @@ class System:
         T.R, T.colls, T.policy = self.R, self.colls, self.policy
         T.with_data, T.sends, T.recvs = False, None, None
         T.progs, T.rounds = self.progs, self.rounds
+        T.foldcnt = [list(c) for c in self.foldcnt]
         T.fifo = []
         for fl in self.fifo:
             row = []
@@ -636,6 +686,7 @@ class System:
             e.saved = {k: list(v) for k, v in d.saved.items()}
             e.spin, e.thr, e.exit = d.spin, d.thr, d.exit
             e.cq, e.seq_of = list(d.cq), dict(d.seq_of)
+            e.inv_of, e.ninv = dict(d.inv_of), dict(d.ninv)
             e.jobs = list(d.jobs)
             e.ready = list(d.ready) if d.ready is not None else None
             e.rk, e.taken = d.rk, d.taken

@@ -487,12 +487,128 @@ __device__ __forceinline__ void run_prim(int dtype, const void* fin, const char*
 }
 
 // ------------------------------------------------------------------------------------------
+// Fold steps of a short all-reduce (make_fold_prim): the two data movers
+// ------------------------------------------------------------------------------------------
+// a buffer resource over memory whose address every lane holds alike (it came out of LDS)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t uniform_rsrc(u64 addr, uint32_t bytes) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)addr), hi = __builtin_amdgcn_readfirstlane((uint32_t)(addr >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc((void*)(uintptr_t)(((u64)hi << 32) | lo), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 rs_ld16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+  return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, AUX_DEVICE));   // out of range reads return 0
+}
+
+constexpr int FOLD_SRC = 8;    // sources read together
+constexpr int FOLD_U = 2;      // vectors per thread and source in flight
+
+// dst[i] = src[0][i] (op) src[1][i] (op) ... (op) src[nsrc-1][i], left to right: the table lists the ranks in
+// the ring's order of combination.  Sources are other ranks' send buffers: device-coherent loads; the result
+// is read by the other ranks soon: device-coherent stores.
+template <int DT, int NTH>
+__device__ __forceinline__ void fold_slice(const u64* src_tab, uint32_t nsrc, void* dst_p, uint32_t bytes, uint32_t tid, int op) {
+  const Slot<AUX_DEVICE> dst(dst_p, bytes);
+  const uint32_t nvec = bytes >> 4;
+  for (uint32_t i = tid; i < nvec; i += FOLD_U * NTH) {
+    uint4 acc[FOLD_U];
+    for (uint32_t base = 0; base < nsrc; base += FOLD_SRC) {
+      uint4 w[FOLD_SRC][FOLD_U];
+#pragma unroll
+      for (int k = 0; k < FOLD_SRC; ++k) {
+        if (base + k < nsrc) {
+          const __amdgpu_buffer_rsrc_t r = uniform_rsrc(src_tab[base + k], bytes);
+#pragma unroll
+          for (int u = 0; u < FOLD_U; ++u) w[k][u] = rs_ld16(r, (i + u * NTH) << 4);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < FOLD_SRC; ++k) {
+        if (base + k < nsrc) {
+          if (base + k == 0) {
+#pragma unroll
+            for (int u = 0; u < FOLD_U; ++u) acc[u] = w[0][u];
+          } else op_batch<DT, FOLD_U>(acc, w[k], op);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < FOLD_U; ++u) if (i + u * NTH < nvec) dst.st16((i + u * NTH) << 4, acc[u]);
+  }
+  // the sub-vector tail of a message whose length is no multiple of 16 bytes
+  const uint32_t done = nvec << 4;
+  if (done < bytes) {
+    constexpr uint32_t EB = (DT == DT_F32 || DT == DT_I32) ? 4u : 2u;
+    for (uint32_t o = done + tid * EB; o < bytes; o += NTH * EB) {
+      uint32_t v = 0;
+      for (uint32_t k = 0; k < nsrc; ++k) {
+        const Slot<AUX_DEVICE> src((const void*)(uintptr_t)src_tab[k], bytes);
+        const uint32_t x = EB == 4 ? src.ld4(o) : (uint32_t)src.ld2(o);
+        v = k == 0 ? x : (EB == 4 ? op_word<DT>(v, x, op) : (uint32_t)op_half<DT>((uint16_t)v, (uint16_t)x, op));
+      }
+      if (EB == 4) dst.st4(o, v); else dst.st2(o, (uint16_t)v);
+    }
+  }
+}
+
+template <int NTH>
+__device__ __forceinline__ void fold_dispatch(int dtype, const u64* src_tab, uint32_t nsrc, void* dst, uint32_t bytes, uint32_t tid) {
+  const int op = dtype >> 4;
+  switch (dtype & 15) {
+    case DT_F32: fold_slice<DT_F32, NTH>(src_tab, nsrc, dst, bytes, tid, op); break;
+    case DT_BF16: fold_slice<DT_BF16, NTH>(src_tab, nsrc, dst, bytes, tid, op); break;
+    case DT_F16: fold_slice<DT_F16, NTH>(src_tab, nsrc, dst, bytes, tid, op); break;
+    default: fold_slice<DT_I32, NTH>(src_tab, nsrc, dst, bytes, tid, op); break;
+  }
+}
+
+// The gather step: segment s is len[s] bytes copied from src[s] (another rank's recv buffer: device-coherent
+// loads) to dst[s] (the own recv buffer); the loads of up to eight segments travel together.
+template <int NTH>
+__device__ __forceinline__ void gather_slices(const u64* src_tab, const u64* dst_tab, const uint32_t* len_tab, uint32_t nseg,
+                                              uint32_t maxbytes, uint32_t tid) {
+  const uint32_t maxvec = maxbytes >> 4;
+  for (uint32_t base = 0; base < nseg; base += FOLD_SRC) {
+    for (uint32_t i = tid; i < maxvec; i += FOLD_U * NTH) {
+      uint4 w[FOLD_SRC][FOLD_U];
+#pragma unroll
+      for (int k = 0; k < FOLD_SRC; ++k) {
+        if (base + k < nseg) {
+          const __amdgpu_buffer_rsrc_t r = uniform_rsrc(src_tab[base + k], len_tab[base + k]);
+#pragma unroll
+          for (int u = 0; u < FOLD_U; ++u) w[k][u] = rs_ld16(r, (i + u * NTH) << 4);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < FOLD_SRC; ++k) {
+        if (base + k < nseg) {
+          v4u_user* D = (v4u_user*)(uintptr_t)dst_tab[base + k];
+          const uint32_t nv = len_tab[base + k] >> 4;
+#pragma unroll
+          for (int u = 0; u < FOLD_U; ++u) if (i + u * NTH < nv) st_user(&D[i + u * NTH], w[k][u]);
+        }
+      }
+    }
+  }
+  // sub-vector tails (only the message's last chunk can have one); every dtype is a multiple of 2 bytes
+  for (uint32_t s2 = 0; s2 < nseg; ++s2) {
+    const uint32_t len = len_tab[s2], done = (len >> 4) << 4;
+    if (done < len) {
+      const Slot<AUX_DEVICE> src((const void*)(uintptr_t)src_tab[s2], len);
+      uint16_t* D = (uint16_t*)(uintptr_t)dst_tab[s2];
+      for (uint32_t o = done + (tid << 1); o < len; o += NTH << 1) D[o >> 1] = src.ld2(o);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // LDS state of one workgroup
 // ------------------------------------------------------------------------------------------
 struct Job {                         // what the scheduler wave hands to the mover waves for one slice
   const void* fin; const char* sb; char* rb; void* fout;
   uint32_t bytes; int dtype;
   uint32_t coll, prim;               // for the timeline trace only
+  uint32_t mode;                     // 0: the four pointers above; 1: fold step (sources in the job's tables, fout = destination);
+                                     // 2: gather step (segments in the job's tables, bytes = the longest one)
+  uint32_t nseg;                     // entries of the tables
 };
 
 // What publishing and retiring a posted job needs.  Written by the scheduler when it posts the
@@ -503,6 +619,7 @@ struct Flight {
   u64 sent_new, recvd_new;           // their new values
   uint32_t last;                     // the primitive ends this workgroup's share of the invocation
   uint32_t coll, seq, nchan;
+  u64* add_one;                      // fold steps: shared counter to add 1 to (null = none)
 };
 
 struct Shared {
@@ -512,6 +629,9 @@ struct Shared {
   uint32_t slot_claim[DFX_CTX_SLOTS];  // readiness scan: which entry of the scan gets to fill a slot (scan step << 8 | lane)
   Job job[2];                        // posted jobs, indexed by job number & 1
   Flight fl[2];
+  u64 tab_src[2][64];                // fold / gather steps: source addresses of the job, in order
+  u64 tab_dst[2][64];                // gather steps: destination addresses
+  uint32_t tab_len[2][64];           // gather steps: bytes of each segment
   uint32_t job_seq;                  // jobs posted so far (scheduler -> movers)
   uint32_t wave_done[2];             // mover waves that have finished job k, at index k & 1
   uint32_t jobs_done;                // jobs finished and published (movers -> scheduler)
@@ -659,7 +779,9 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         }
       } else
 #endif
-      if (coh) run_prim<AUX_DEVICE, GTHREADS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
+      if (j.mode == 1) fold_dispatch<GTHREADS>(j.dtype, sh.tab_src[seen & 1], j.nseg, j.fout, j.bytes, mtid);
+      else if (j.mode == 2) gather_slices<GTHREADS>(sh.tab_src[seen & 1], sh.tab_dst[seen & 1], sh.tab_len[seen & 1], j.nseg, j.bytes, mtid);
+      else if (coh) run_prim<AUX_DEVICE, GTHREADS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
       else run_prim<AUX_CACHED, GTHREADS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
       // this wave's stores (and loads) have been performed before it counts itself done
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -686,6 +808,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           if (!coh) fence_release_agent();
           if (f.tail_out) raise_counter(f.tail_out, f.sent_new);
           if (f.head_in) raise_counter(f.head_in, f.recvd_new);
+          if (f.add_one) (void)__hip_atomic_fetch_add(f.add_one, 1ull, __ATOMIC_RELAXED, SCOPE_AGENT);
           __hip_atomic_store(&sh.wave_done[seen & 1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
           if (a.trace_on > 1) bump(sh.stat, ST_T_PUB, wall_clock64() - t1);
           lds_st(&sh.jobs_done, seen + 1);
@@ -961,6 +1084,10 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             }
             // (contexts and published buffer addresses are in memory before anything is built on them)
             __builtin_amdgcn_s_waitcnt(0);
+            // fold steps: the channel's count of published invocations (after the addresses, which it vouches for)
+            if (mine && (q.flags & DFX_SQE_FOLD))
+              (void)__hip_atomic_fetch_add((u64*)(fold_shared_line(myctx[c_id].st.flags_out, rank, a.R, q.nchan) + DFX_FOLD_PUB), 1ull,
+                                           __ATOMIC_RELAXED, SCOPE_AGENT);
             // the entries that are this workgroup's join the task queue in SQ order
             const u64 mine_mask = __ballot(mine);
             if (mine) {
@@ -1037,12 +1164,16 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 const uint4 d0 = e[6];    // dyn: round | prim | sent
                 const uint4 d1 = e[7];    // dyn: recvd | preempted | cidx
                 e2c = fl; e3c = fi; e5c = ge; e6c = d0; e7c = d1;
-                Prim pq = make_prim((int)((ge.z >> 8) & 0xffu), a.R, (ge.z >> 24) & 3u, d0.y, ((ge.z >> 24) & DFX_CTX_DIRECT) != 0);
-                if ((ge.z >> 24) & DFX_CTX_DIRECT)
+                const bool e_fold = ((ge.z >> 24) & DFX_CTX_FOLD) != 0;
+                Prim pq = e_fold ? make_fold_prim(d0.y)
+                                 : make_prim((int)((ge.z >> 8) & 0xffu), a.R, (ge.z >> 24) & 3u, d0.y, ((ge.z >> 24) & DFX_CTX_DIRECT) != 0);
+                if (!e_fold && ((ge.z >> 24) & DFX_CTX_DIRECT))
                   pq = chain_drain_round(pq, (int)((ge.z >> 8) & 0xffu), true, d0.x, e[4].w);   // bytes 64..79: fifo_in | slice_elems | rounds
                 const u64 f_out = ((u64)fl.w << 32) | fl.z, f_in = ((u64)fi.y << 32) | fi.x;
                 const u64 e_sent = ((u64)d0.w << 32) | d0.z, e_recvd = ((u64)d1.y << 32) | d1.x;
                 bool okr = true, oks = true;
+                if (pq.fold)   // every rank of the channel has got as far as this step needs: (seq + 1) x R on the step's counter
+                  okr = ld_agent64((const u64*)(fold_shared_line(f_out, rank, a.R, ge.y >> 16) + 8u * (pq.fold - 1u))) >= ((u64)ge.x + 1u) * a.R;
                 if (pq.recv) okr = ld_agent64((const u64*)f_in) > e_recvd;
                 if (pq.send) oks = (e_sent - ld_agent64((const u64*)f_out + 8)) < (u64)(ge.z & 0xffu);
                 else if (pq.drain) oks = e_sent == ld_agent64((const u64*)f_out + 8);
@@ -1130,8 +1261,13 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
 
       // ================= next primitive of the collective in hand =================
       const DfxCooked& S = sh.slot[sl].st;
-      const Prim q = chain_drain_round(make_prim((int)S.kind, a.R, S.bc_pos & 3u, p, (S.bc_pos & DFX_CTX_DIRECT) != 0),
-                                       (int)S.kind, (S.bc_pos & DFX_CTX_DIRECT) != 0, g, S.rounds);
+      const bool fold = (S.bc_pos & DFX_CTX_FOLD) != 0;
+      const Prim q = fold ? make_fold_prim(p)
+                          : chain_drain_round(make_prim((int)S.kind, a.R, S.bc_pos & 3u, p, (S.bc_pos & DFX_CTX_DIRECT) != 0),
+                                              (int)S.kind, (S.bc_pos & DFX_CTX_DIRECT) != 0, g, S.rounds);
+      // fold steps wait for one of the channel's shared counters to reach (invocation + 1) x R
+      const u64* const fold_cnt = fold ? (const u64*)(fold_shared_line(S.flags_out, rank, a.R, S.nchan) + 8u * (q.fold - 1u)) : nullptr;
+      const u64 fold_target = ((u64)S.seq + 1u) * a.R;
       u64* const tail_out = (u64*)S.flags_out;
       u64* const tail_in = (u64*)S.flags_in;
       const uint32_t K = S.nslots;
@@ -1158,6 +1294,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       u64 seen_cnt = 0;
       if (lane == 0 && q.recv) seen_cnt = ld_agent64(tail_in);
       if (lane == 1 && (q.send || q.drain)) seen_cnt = ld_agent64(tail_out + 8);
+      if (lane == 0 && q.fold) seen_cnt = ld_agent64(fold_cnt);
 
       // ---- slice geometry and the job's four pointers
       const int kind = S.kind, dtype = S.dtype;   // dtype: element type | reducing function << 4
@@ -1180,10 +1317,11 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
 
       // The movers may be busy with earlier slices meanwhile; finished ones are retired between polls.
       uint32_t res = W_OK;
-      if (q.recv || q.send || q.drain) {
+      if (q.recv || q.send || q.drain || q.fold) {
         u64 n = 0;
         for (;;) {
           bool ok = true;
+          if (lane == 0 && q.fold) ok = seen_cnt >= fold_target;
           if (lane == 0 && q.recv) ok = seen_cnt > recvd;
           if (lane == 1 && q.send) ok = (sent - seen_cnt) < (u64)K;
           if (lane == 1 && q.drain) ok = sent == seen_cnt;
@@ -1211,6 +1349,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           __builtin_amdgcn_s_sleep(1);
           if (lane == 0 && q.recv) seen_cnt = ld_agent64(tail_in);
           if (lane == 1 && (q.send || q.drain)) seen_cnt = ld_agent64(tail_out + 8);
+          if (lane == 0 && q.fold) seen_cnt = ld_agent64(fold_cnt);
         }
         if (lane == 0) bump(sh.stat, ST_POLLS, n);
       }
@@ -1246,6 +1385,37 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           }
           jfin = q.din_send ? (const void*)((const char*)prev_send + soff * eb) : (const void*)((const char*)prev_recv + doff * eb);
         }
+        uint32_t jmode = 0, jnseg = 0, jbytes_fold = 0;
+        if (q.fold == 1 || q.fold == 2) {
+          // The addresses every rank published for this invocation (before it counted itself published, which the
+          // wait has seen for all of them): lane k looks up the rank k places down the ring.  Fold step: the send
+          // buffers, in the ring's order of combination for this rank's chunk (rank + 1 first, this rank last).
+          // Gather step: the other ranks' recv buffers, each with its own chunk.
+          const uint32_t nk = q.fold == 1 ? a.R : a.R - 1;
+          const uint32_t peer = (rank + 1 + lane) % a.R;
+          bool bad = false;
+          if (lane < nk) {
+            const Slot<AUX_DEVICE> line((const void*)fold_line(S.flags_out, rank, peer, S.nchan), DFX_FLAG_STRIDE);
+            uint4 w = uint4{0, 0, 0, 0};
+            for (uint32_t tries = 0; tries < 1024u; ++tries) {
+              w = line.ld16(q.fold == 1 ? DFX_DIRECT_OFF + 16 : DFX_DIRECT_OFF);
+              if (w.z == inv_seq + 1u) break;
+              __builtin_amdgcn_s_sleep(2);
+            }
+            bad = w.z != inv_seq + 1u;
+            const u64 base = ((u64)w.y << 32) | w.x;
+            const SliceGeom gk = slice_geometry(S, a.R, 0u, q.fold == 1 ? rank : peer);
+            sh.tab_src[posted & 1][lane] = base + (q.fold == 1 ? gk.soff : gk.doff) * gk.eb;
+            sh.tab_dst[posted & 1][lane] = (u64)S.recvbuf + gk.doff * gk.eb;
+            sh.tab_len[posted & 1][lane] = gk.bytes;
+          }
+          if (__ballot(bad)) { if (lane == 0) raise_error(a, 3u, wg); stop = STOP_ABORT; have = false; continue; }
+          jmode = q.fold; jnseg = nk;
+          const SliceGeom own = slice_geometry(S, a.R, 0u, rank);
+          if (q.fold == 1) { jfout = (char*)S.recvbuf + own.doff * own.eb; jbytes_fold = own.bytes; }
+          else jbytes_fold = (uint32_t)S.slice_elems * own.eb;      // the longest segment: a channel's share of a full chunk
+          __builtin_amdgcn_wave_barrier();
+        }
         // ---- post the slice (an empty one is only a handshake: the movers just raise the counters);
         // this claims the slots: the data follows, the counters after it
         if (q.send || q.notify) ++sent;
@@ -1254,12 +1424,15 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           Job j;
           j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
           j.bytes = (q.drain || (!q.recv && !q.from_send)) ? 0u : bytes;   // drain and notify-only steps move nothing
-          j.dtype = dtype; j.coll = coll; j.prim = q.drain ? 0xffu : p;   // (prim: for the timeline only)
+          if (q.fold) j.bytes = jbytes_fold;                               // (the last fold step: nothing)
+          j.mode = jmode; j.nseg = jnseg;
+          j.dtype = dtype; j.coll = coll; j.prim = (q.drain || q.fold == 3) ? 0xffu : p;   // (prim: for the timeline only)
           sh.job[posted & 1] = j;
           Flight f;
           f.tail_out = (q.send || q.notify) ? tail_out : nullptr; f.head_in = q.recv ? tail_in + 8 : nullptr;
           f.sent_new = sent; f.recvd_new = recvd;
           f.last = last ? 1u : 0u; f.coll = coll; f.seq = inv_seq; f.nchan = inv_nchan;
+          f.add_one = (q.fold == 1 || q.fold == 2) ? (u64*)(fold_shared_line(S.flags_out, rank, a.R, S.nchan) + 8u * q.fold) : nullptr;
           sh.fl[posted & 1] = f;
           lds_st(&sh.job_seq, posted + 1);
         }

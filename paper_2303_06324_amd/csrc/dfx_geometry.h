@@ -55,11 +55,44 @@ struct Prim {
   // (the recv buffer is the caller's again once the completion is posted).
   bool notify, din, drain;
   bool din_send;   // the input is the previous rank's SEND buffer (first reduce step of a direct all-reduce / reduce-scatter)
+  // Fold steps of a short all-reduce (see make_fold_prim): fold = 1 the fold step, 2 the gather step, 3 the
+  // last wait; 0 = none of them.  Their wait phase looks at one of the channel's shared counters.
+  uint8_t fold;
 };
+
+// A short all-reduce in fold steps.  Every rank's buffers lie in the same HBM, so the 2R-1 dependent hops of the
+// ring (a few microseconds each, whatever the size) can be replaced by three steps that wait on all ranks at once:
+//   p = 0  fold:   when every rank has published this invocation's buffers, rank r reads chunk r out of all R send
+//                  buffers and combines them in the ring's own order, x[r+1] (op) x[r+2] (op) ... (op) x[r] -- the
+//                  same association as the reduce phase of the ring, hence the same bits -- into its recv buffer;
+//   p = 1  gather: when every rank has finished its fold step, rank r copies the other R-1 chunks out of their
+//                  owners' recv buffers;
+//   p = 2  last:   no data; when every rank has finished its gather step, nobody reads this rank's buffers any
+//                  more and the completion may be posted.
+// Each step is a bounded wait followed by the data, like any primitive: nothing is touched before the wait has
+// succeeded, so a collective stuck in any of them is preempted like any other.
+DFX_HD Prim make_fold_prim(uint32_t p) {
+  Prim q;
+  q.recv = q.send = q.notify = q.din = q.drain = q.din_send = false;
+  q.from_send = (p == 0);
+  q.to_recv = (p < 2);
+  q.fold = (uint8_t)(p + 1);
+  return q;
+}
+
+// Where a fold collective's lines are, from a workgroup's own line: the line of rank r on the same channel,
+// and the channel's shared line.
+DFX_HD uint64_t fold_line(uint64_t own_line, uint32_t rank, uint32_t r, uint32_t nchan) {
+  return own_line + ((uint64_t)r - (uint64_t)rank) * nchan * DFX_FLAG_STRIDE;
+}
+DFX_HD uint64_t fold_shared_line(uint64_t own_line, uint32_t rank, uint32_t R, uint32_t nchan) {
+  return own_line + ((uint64_t)R - (uint64_t)rank) * nchan * DFX_FLAG_STRIDE;
+}
 
 DFX_HD Prim make_prim(int kind, uint32_t R, uint32_t bc_pos, uint32_t p, bool direct) {
   Prim q;
   q.notify = q.din = q.drain = q.din_send = false;
+  q.fold = 0;
   if (R == 1) { q.recv = q.send = false; q.from_send = q.to_recv = true; return q; }   // copy
   if (kind == KIND_AR && direct) {
     const uint32_t last_reduce = R - 1;
@@ -157,7 +190,7 @@ DFX_HD DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool, uint32_t rank, uint
   k.fifo_out = (uint64_t)(slots + fo * q.nslots * q.slot_bytes);
   k.fifo_in = (uint64_t)(slots + fi * q.nslots * q.slot_bytes);
   // a direct broadcast has no slots (no step of it fills or reads one)
-  if (q.kind == KIND_BC && (q.flags & DFX_SQE_DIRECT)) k.fifo_out = k.fifo_in = 0;
+  if ((q.kind == KIND_BC && (q.flags & DFX_SQE_DIRECT)) || (q.flags & DFX_SQE_FOLD)) k.fifo_out = k.fifo_in = 0;
   k.slice_elems = q.slice_elems; k.rounds = q.rounds; k.seq = q.seq;
   k.nprim = (uint16_t)q.nprim; k.nchan = q.nchan;
   k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = (uint8_t)(q.dtype | (q.op << 4));
@@ -166,6 +199,7 @@ DFX_HD DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool, uint32_t rank, uint
   k.bc_pos = bpos == 0 ? 0 : (bpos == R - 1 ? 2 : 1);
   if (q.kind == KIND_RD && (q.flags & DFX_SQE_DIRECT) && bpos == 1 && R > 2) k.bc_pos = 3;   // reads the first rank's send buffer
   if (q.flags & DFX_SQE_DIRECT) k.bc_pos |= DFX_CTX_DIRECT;   // a collective with direct steps
+  if (q.flags & DFX_SQE_FOLD) k.bc_pos |= DFX_CTX_FOLD;       // an all-reduce in fold steps
   k.priority = q.priority; k.vch = (uint16_t)vch;
   return k;
 }

@@ -373,13 +373,18 @@ int plan_collective(const dfx_config& cfg, int nranks, int coll_id, dfx_kind kin
     const uint64_t want = round_up(part * eb / ((kind == DFX_BROADCAST ? 2 : 4) * R), 16);
     slice_cap = std::min(std::max(want, lo), hi);
   }
+  // fold steps of a short all-reduce: no slots, one slice per channel share whatever its length
+  const bool fold = kind == DFX_ALLREDUCE && R > 1 && cfg.fold_max_bytes && count * eb < cfg.fold_max_bytes;
+  if (fold) slice_cap = 1ull << 31;
   uint64_t slot_bytes = std::min<uint64_t>(slice_cap, round_up(part * eb, 16));
   const uint64_t slice_elems = slot_bytes / eb;
   const uint64_t rounds = std::max<uint64_t>(1, ceil_div(part, slice_elems));
   if (rounds > 0xfffffffeull) return DFX_ERR_INVALID_ARG;
   const uint64_t K = cfg.nslots;
   // (a direct broadcast fills no slot: its connectors are the flag lines alone)
-  *conn_bytes_out = round_up(R * C * DFX_FLAG_STRIDE + (bc_direct ? 0 : R * C * K * slot_bytes), 256);
+  // (a collective in fold steps has none either: R x C lines with the published addresses and C shared lines of counters)
+  *conn_bytes_out = fold ? round_up((R + 1) * C * DFX_FLAG_STRIDE, 256)
+                         : round_up(R * C * DFX_FLAG_STRIDE + (bc_direct ? 0 : R * C * K * slot_bytes), 256);
 
   DfxStatic t;
   memset(&t, 0, sizeof(t));
@@ -396,6 +401,10 @@ int plan_collective(const dfx_config& cfg, int nranks, int coll_id, dfx_kind kin
   t.kind = (uint8_t)kind; t.dtype = (uint8_t)dtype; t.op = (uint8_t)op; t.root = (uint8_t)(rooted ? root : 0);
   t.priority = (int16_t)priority;
   if (R == 1) t.nprim = 1;
+  else if (fold) {
+    t.flags |= DFX_SQE_DIRECT | DFX_SQE_FOLD;   // (buffers are published as for the direct steps)
+    t.nprim = 3;                                // fold, gather, last wait
+  }
   else if (kind == DFX_ALLREDUCE) {
     // direct gather steps (one more step: the drain) where the message is long enough to gain from them
     const bool direct = cfg.direct && count * eb >= cfg.direct_min_bytes;
@@ -462,6 +471,7 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->focus_bytes = 128u << 10;
   cfg->direct = 1;
   cfg->direct_min_bytes = 2u << 20;
+  cfg->fold_max_bytes = 64u << 20;
   cfg->preempt = 1;
   cfg->watchdog_ms = 10000;
   cfg->quit_idle_us = 2000;
@@ -1040,7 +1050,8 @@ int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t
   const uint64_t blk_lo = pool + conn_off, blk_hi = blk_lo + conn_bytes;
   const uint64_t flags_hi = blk_lo + (uint64_t)R * t.nchan * DFX_FLAG_STRIDE;
   const bool direct = (t.flags & DFX_SQE_DIRECT) != 0;
-  const bool no_slots = direct && kind == DFX_BROADCAST;
+  const bool fold = (t.flags & DFX_SQE_FOLD) != 0;
+  const bool no_slots = (direct && kind == DFX_BROADCAST) || fold;
 
   // (i) the map is a bijection between workgroups and (rank, channel); under the third labelling too
   // (XCD = (rank + channel) mod 8: the ranks of every channel's group of R workgroups rotated by the channel)
@@ -1078,7 +1089,16 @@ int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t
         return fail("edge %u channel %u: flag line %llx outside the block's flag lines", r, v, (unsigned long long)me.flags_out);
       if (!no_slots && (me.fifo_out < flags_hi || me.fifo_out + conn_slot_bytes > blk_hi))
         return fail("edge %u channel %u: slots %llx outside the block", r, v, (unsigned long long)me.fifo_out);
-      if (no_slots && (me.fifo_out || me.fifo_in)) return fail("%s", "a direct broadcast has no slots");
+      if (no_slots && (me.fifo_out || me.fifo_in)) return fail("%s", "a collective without slots has slot addresses");
+      if (fold) {
+        // every rank of the channel finds the same lines: rank k's from any rank's own line, and the shared one
+        const uint64_t sh_line = fold_shared_line(me.flags_out, r, R, t.nchan);
+        if (sh_line < flags_hi || sh_line + DFX_FLAG_STRIDE > blk_hi) return fail("rank %u channel %u: shared line %llx outside the block", r, v, (unsigned long long)sh_line);
+        if (sh_line != fold_shared_line(nx.flags_out, (r + 1) % R, R, t.nchan)) return fail("ranks %u and %u channel %u disagree on the shared line", r, (r + 1) % R, v);
+        for (uint32_t k = 0; k < R; ++k)
+          if (fold_line(me.flags_out, r, k, t.nchan) != cooked[(size_t)k * t.nchan + v].flags_out)
+            return fail("rank %u channel %u: line of rank %u resolves to %llx", r, v, k, (unsigned long long)fold_line(me.flags_out, r, k, t.nchan));
+      }
     }
 
   // (iii) every job of every workgroup's walk through the invocation stays inside its buffers and slots;
@@ -1093,6 +1113,29 @@ int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t
       uint32_t g = 0, p = 0, cidx = first_chunk(kind, r, R);
       uint64_t sent = 0, recvd = 0, steps = 0;
       for (;;) {
+        if (fold) {
+          // fold steps: chunk r out of every send buffer into the own recv buffer, then every other chunk out of
+          // its owner's recv buffer
+          if (g != 0 || S.rounds != 1) return fail("rank %u channel %u: a collective in fold steps has one slice per share", r, v);
+          for (uint32_t k = 0; k < R && p < 2; ++k) {
+            const uint32_t peer = (r + 1 + k) % R;
+            if (p == 1 && peer == r) continue;
+            const SliceGeom gk = slice_geometry(S, R, 0u, p == 0 ? r : peer);
+            if ((uint64_t)gk.bytes > (uint64_t)S.slice_elems * gk.eb) return fail("rank %u channel %u: a segment longer than the share", r, v);
+            if (!gk.bytes) continue;
+            const uint64_t rd = (p == 0 ? gk.soff : gk.doff) * gk.eb, lim = p == 0 ? send_bytes : recv_bytes;
+            if (rd + gk.bytes > lim) return fail("rank %u channel %u fold step %u: read of rank %u's buffer %llu+%u of %llu", r, v, p, peer, (unsigned long long)rd, gk.bytes, (unsigned long long)lim);
+            if (p == 0 && k + 1 < R) continue;       // (the fold step writes once, after the last source)
+            const uint64_t wr = gk.doff * gk.eb;
+            if (wr + gk.bytes > recv_bytes) return fail("rank %u channel %u fold step %u: recv buffer write %llu+%u of %llu", r, v, p, (unsigned long long)wr, gk.bytes, (unsigned long long)recv_bytes);
+            written[r].push_back({wr, wr + gk.bytes});
+          }
+          const SeqPos nx = next_position(kind, R, r, cfg.window, S.rounds, S.nprim, g, p, cidx);
+          g = nx.g; p = nx.p; cidx = nx.cidx;
+          if (g >= S.rounds) break;
+          if (++steps > 8) return fail("rank %u channel %u: the fold steps do not end", r, v);
+          continue;
+        }
         const Prim q = chain_drain_round(make_prim(kind, R, S.bc_pos & 3u, p, direct), kind, direct, g, S.rounds);
         const SliceGeom geo = slice_geometry(S, R, g, cidx);
         const uint64_t slot_b = (uint64_t)S.slice_elems * geo.eb;
@@ -1166,6 +1209,7 @@ int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t
 #define DFX_NA_SQ_DEPTH 2u
 #define DFX_NA_CQ_SLOTS 2u
 #define DFX_NA_MAX_RANKS 64u
+#define DFX_NA_LINES (DFX_NA_MAX_WG + 64u)      // flag lines: one per connector, and a collective in fold steps has one more per channel
 #define DFX_NA_CTL_BYTES (512u << 10)           // everything but the slots: must start at zero on every call
 #define DFX_NA_SLOTS_BYTES ((size_t)DFX_NA_MAX_WG * DFX_NA_NSLOTS * DFX_NA_SLOT_BYTES)
 #define DFX_NA_SCRATCH_BYTES ((size_t)DFX_NA_CTL_BYTES + DFX_NA_SLOTS_BYTES)
@@ -1194,7 +1238,7 @@ constexpr NaLayout na_layout() {
   L.taskq = o; o = na_up(o + (size_t)DFX_NA_MAX_WG * 2);
   L.ctxbuf = o; o = na_up(o + (size_t)DFX_NA_MAX_WG * sizeof(DfxCtxEntry));
   // the pool's flag lines end exactly where the zeroed part ends
-  L.pool = DFX_NA_CTL_BYTES - (size_t)DFX_NA_MAX_WG * DFX_FLAG_STRIDE;
+  L.pool = DFX_NA_CTL_BYTES - (size_t)DFX_NA_LINES * DFX_FLAG_STRIDE;
   L.end_of_zeroed = o;
   return L;
 }
@@ -1314,8 +1358,8 @@ int dfx_collective_noalloc(int nranks, dfx_kind kind, size_t count, dfx_dtype dt
   if (rc != DFX_OK) return rc;
   // connector block = flag lines of the collective's R x C edges, then their slots; the scratch holds
   // DFX_NA_MAX_WG flag lines and as many connectors of DFX_NA_NSLOTS x DFX_NA_SLOT_BYTES
-  const size_t flag_bytes = (size_t)nranks * tmpl.nchan * DFX_FLAG_STRIDE;
-  if (flag_bytes > (size_t)DFX_NA_MAX_WG * DFX_FLAG_STRIDE || conn_bytes - flag_bytes > DFX_NA_SLOTS_BYTES + 256) return DFX_ERR_TOO_LARGE;
+  const size_t flag_bytes = (size_t)(nranks + ((tmpl.flags & DFX_SQE_FOLD) ? 1 : 0)) * tmpl.nchan * DFX_FLAG_STRIDE;
+  if (flag_bytes > (size_t)DFX_NA_LINES * DFX_FLAG_STRIDE || conn_bytes > flag_bytes + DFX_NA_SLOTS_BYTES + 256) return DFX_ERR_TOO_LARGE;
   // the flag lines end where the zeroed part ends, the slots begin right there
   tmpl.conn_off = (uint64_t)((size_t)DFX_NA_CTL_BYTES - flag_bytes - L.pool);
 

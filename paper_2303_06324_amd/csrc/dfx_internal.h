@@ -22,6 +22,14 @@
 #define DFX_SQE_EXIT 1u
 #define DFX_SQE_DIRECT 2u      // collective with direct steps (reads the previous rank's recv / send buffer instead of slots)
 #define DFX_CTX_DIRECT 0x80u   // the same, in the cooked context's bc_pos byte (bits 0-1: place in a chain)
+#define DFX_SQE_FOLD 4u        // all-reduce in fold steps (always together with DFX_SQE_DIRECT: the buffers are published the same way)
+#define DFX_CTX_FOLD 0x40u     // the same, in the cooked context's bc_pos byte
+// A collective in fold steps has no slots.  Its connector block is R x nchan flag lines, one per (rank, channel),
+// that carry the published buffer addresses (DFX_DIRECT_OFF), and behind them nchan shared lines, one per
+// channel, with three counters that every rank of the channel adds to:
+#define DFX_FOLD_PUB 0         //   +0  invocations published (buffer addresses written at SQE fetch)
+#define DFX_FOLD_RED 8         //   +8  fold steps finished (the rank's own chunk is reduced and in its recv buffer)
+#define DFX_FOLD_GAT 16        //   +16 gather steps finished (the rank has copied every other chunk)
 
 // Static context of one invocation on one rank: what the host writes into the SQ and what a
 // workgroup keeps in its context buffer (Sec. 4.2: buffer and connector addresses, rank count,

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
 def test_config_struct_matches_header_size():
     import paper_2303_06324_amd as dfx
     cfg = dfx.config_default()
-    assert cfg.struct_bytes == ctypes.sizeof(dfx.Config) == 120
+    assert cfg.struct_bytes == ctypes.sizeof(dfx.Config) == 128
     assert cfg.nslots >= 2 and cfg.max_colls <= 4096 and cfg.preempt == 1
     assert dfx.strerror(0) == "ok" and "timeout" in dfx.strerror(dfx.ERR_TIMEOUT)
 

@@ -44,11 +44,12 @@ def _equal_whole(t, want, what):
         raise AssertionError(f"{what}: {bad.size} words differ, first at element {int(bad[0])}")
 
 
-@pytest.mark.parametrize("knobs", [dict(), dict(direct=0), dict(direct=0, slot_bytes=128 << 10)],
-                         ids=["defaults", "every_step_through_a_slot", "slots_128KiB"])
+@pytest.mark.parametrize("knobs", [dict(), dict(direct=0), dict(direct=0, slot_bytes=128 << 10), dict(fold_max_bytes=512 << 20)],
+                         ids=["defaults", "every_step_through_a_slot", "slots_128KiB", "fold_steps"])
 def test_config2_largest_size_whole_buffers(big, knobs):
     """The size the headline metric is quoted on: all 8 x 64 Mi elements compared with the oracle's fold,
-    for the library defaults (direct steps) and with every step through a FIFO slot; two invocations, so
+    for the library defaults (the ring with direct steps), with every step through a FIFO slot, and in fold steps
+    (which the defaults take below 64 MiB); two invocations, so
     that the second one starts with the connectors' counters mid-ring."""
     import paper_2303_06324_amd as dfx
     from paper_2303_06324_amd import harness as gh
@@ -59,7 +60,7 @@ def test_config2_largest_size_whole_buffers(big, knobs):
     ctx = dfx.Context(R, gh.make_config(**knobs))
     try:
         ctx.prepare(0, dfx.ALLREDUCE, n, dfx.F32)
-        assert (ctx.coll_info(0)["nprim"] == 2 * R) == (knobs.get("direct", 1) == 1)
+        assert ctx.coll_info(0)["nprim"] == (3 if "fold_max_bytes" in knobs else 2 * R if knobs.get("direct", 1) else 2 * R - 1)
         for it in range(2):
             dw.reset_recv()
             for r in range(R):
@@ -139,13 +140,13 @@ def test_other_kinds_at_the_largest_size(big):
 
 def test_config3_full_bf16_buckets_random_orders():
     """16 bf16 buckets of 25 MiB, every rank submitting in its own random order: all sixteen buckets, every
-    rank, whole, against the oracle's fold; also with every step through a FIFO slot."""
+    rank, whole, against the oracle's fold: in fold steps (the default for buckets of this size) and as rings."""
     from paper_2303_06324_amd import harness as gh
     w = wi.config3()
     assert len(w.colls) == 16 and w.colls[0].count == 25 * (1 << 20) // 2
     dw = gh.DeviceWorkload(w)
     want = [rd.all_reduce_fold(dw.send_host[ci], rd.BF16) for ci in range(16)]
-    for knobs in (dict(), dict(direct=0)):
+    for knobs in (dict(), dict(fold_max_bytes=0), dict(fold_max_bytes=0, direct=0)):   # fold steps (the default at this size), the ring with direct steps, the ring through slots
         dw.reset_recv()
         _, stats, _ = gh.run_workload(w, gh.make_config(**knobs), dw=dw, timeout_s=90.0)   # guards and send buffers too
         for ci in range(16):

@@ -69,30 +69,36 @@ def _one(kind, dtype, count, R, root=0, seed=0, op=wi.SUM):
                        [[0]] * R, seed=seed, cfg=50)
 
 
-def test_smallest_allreduce_two_ranks():
-    _run(_one(wi.AR, wi.F32, 1024, 2), max_channels=4)
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
+def test_smallest_allreduce_two_ranks(fold):
+    _run(_one(wi.AR, wi.F32, 1024, 2), max_channels=4, fold_max_bytes=fold)
 
 
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
 @pytest.mark.parametrize("spread", [0, 1])
 @pytest.mark.parametrize("orders", list(itertools.product([(0, 1), (1, 0)], repeat=2)))
-def test_config1_circular_wait_all_orders(orders, spread):
+def test_config1_circular_wait_all_orders(orders, spread, fold):
     """Two all-reduces issued in every combination of orders on two ranks; opposite orders are the
     single-queue deadlock of Sec. 2.3 when both share one workgroup (spread=0). Integer-valued
     inputs: sums are exact in any order."""
     w = wi.config1(*orders)
-    stats = _run(w, max_channels=4, spin_init=200, spin_min=8, spin_max=4000, spin_boost=4, chan_spread=spread)
+    stats = _run(w, max_channels=4, spin_init=200, spin_min=8, spin_max=4000, spin_boost=4, chan_spread=spread, fold_max_bytes=fold)
     assert sum(s["cqe_posted"] for s in stats) == 4
 
 
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
 @pytest.mark.parametrize("dtype", [wi.F32, wi.BF16, wi.F16, wi.I32])
 @pytest.mark.parametrize("count", [1, 7, 4096, 100003, 1 << 20])
-def test_allreduce_sizes_and_dtypes_R8(dtype, count):
-    _run(_one(wi.AR, dtype, count, 8, seed=count))
+def test_allreduce_sizes_and_dtypes_R8(dtype, count, fold):
+    """The ring through FIFO slots (fold_max_bytes = 0) and the fold steps that short all-reduces take by default
+    (below 64 MiB per rank)."""
+    _run(_one(wi.AR, dtype, count, 8, seed=count), fold_max_bytes=fold)
 
 
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
 @pytest.mark.parametrize("R", [1, 2, 3, 5, 8, 16])
-def test_allreduce_rank_counts(R):
-    _run(_one(wi.AR, wi.F32, 50000 + R, R, seed=R), max_channels=8)
+def test_allreduce_rank_counts(R, fold):
+    _run(_one(wi.AR, wi.F32, 50000 + R, R, seed=R), max_channels=8, fold_max_bytes=fold)
 
 
 @pytest.mark.parametrize("kind", [wi.AG, wi.RS, wi.BC])
@@ -105,23 +111,25 @@ def test_zero_count_collective_completes():
     _run(_one(wi.AR, wi.F32, 0, 4), max_channels=4)
 
 
-def test_forced_preemption_is_transparent():
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
+def test_forced_preemption_is_transparent(fold):
     """Tiny spin thresholds force thousands of context switches; results must not change
     (Sec. 4.5: restart without under- or re-transmitting data)."""
     w = wi.config3(n_buckets=8, bucket_bytes=1 << 20, seed=3)
-    stats = _run(w, spin_init=4, spin_min=1, spin_max=16, spin_boost=2, slot_bytes=8192, nslots=2, trace=1)
+    stats = _run(w, spin_init=4, spin_min=1, spin_max=16, spin_boost=2, slot_bytes=8192, nslots=2, trace=1, fold_max_bytes=fold)
     assert sum(s["preemptions"] for s in stats) > 100
     assert sum(s["ctx_saves"] for s in stats) > 0
     # the same collectives with thresholds so large that nothing is ever preempted need a
     # consistent issue order (otherwise this is the deadlock the method exists to prevent)
     same = wi.Workload(w.name, w.R, w.colls, [list(range(8))] * 8, sigma=w.sigma, seed=w.seed, cfg=w.cfg)
-    huge = _run(same, spin_init=1 << 30, spin_min=1 << 30, spin_max=1 << 31, spin_boost=1)
+    huge = _run(same, spin_init=1 << 30, spin_min=1 << 30, spin_max=1 << 31, spin_boost=1, fold_max_bytes=fold)
     assert sum(s["cqe_posted"] for s in huge) == 8 * 8
     assert sum(s["preemptions"] for s in huge) == 0
 
 
-def test_config3_small_bf16_buckets_random_orders():
-    _run(wi.config3(n_buckets=16, bucket_bytes=2 << 20, seed=1), timeout_s=60.0)
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
+def test_config3_small_bf16_buckets_random_orders(fold):
+    _run(wi.config3(n_buckets=16, bucket_bytes=(2 << 20) - 4096, seed=1), timeout_s=60.0, fold_max_bytes=fold)
 
 
 def test_config4_mixed_small():
@@ -129,19 +137,21 @@ def test_config4_mixed_small():
     _run(w, mode="threads", timeout_s=60.0)
 
 
-def test_config5_many_small_allreduces():
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
+def test_config5_many_small_allreduces(fold):
     w = wi.config5(n_colls=256, seed=4)
-    stats = _run(w, mode="threads", timeout_s=90.0, sq_depth=64)
+    stats = _run(w, mode="threads", timeout_s=90.0, sq_depth=64, fold_max_bytes=fold)
     assert sum(s["cqe_posted"] for s in stats) == 256 * 8
 
 
-def test_repeated_invocations_and_changing_buffers():
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
+def test_repeated_invocations_and_changing_buffers(fold):
     """A collective is registered once and run many times, with different buffers (Sec. 3.2, 4.2)."""
     from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     w = _one(wi.AR, wi.F32, 300000, 8, seed=77)
     dws = [gh.DeviceWorkload(w), gh.DeviceWorkload(wi.Workload(w.name, 8, w.colls, w.orders, seed=78, cfg=50))]
-    ctx = dfx.Context(8, gh.make_config())
+    ctx = dfx.Context(8, gh.make_config(fold_max_bytes=fold))
     try:
         gh.prepare_all(ctx, w)
         for it in range(6):
@@ -235,11 +245,12 @@ def test_random_mix_of_kinds_ops_and_orders(seed):
     _run(_mixed_workload(seed), mode="threads", timeout_s=60.0)
 
 
-def test_random_mix_single_queue_forced_preemption():
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
+def test_random_mix_single_queue_forced_preemption(fold):
     """The same kind of mix with everything on one workgroup per vrank, Alg. 1's own queue handling and the
     smallest thresholds: every late flag preempts."""
     _run(_mixed_workload(7, n_colls=24), mode="threads", timeout_s=60.0, max_channels=1, chan_spread=0,
-         scan_min=0, spin_init=1, spin_min=1, spin_max=1, spin_boost=1)
+         scan_min=0, spin_init=1, spin_min=1, spin_max=1, spin_boost=1, fold_max_bytes=fold)
 
 
 def test_fenced_connector_mode_matches_too(monkeypatch):
@@ -252,8 +263,9 @@ def test_fenced_connector_mode_matches_too(monkeypatch):
     _run(wi.config3(n_buckets=6, bucket_bytes=1 << 20, seed=44))
 
 
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
 @pytest.mark.parametrize("dtype,count", [(wi.F32, 1 << 20), (wi.BF16, 300007), (wi.I32, 4099)])
-def test_in_place_allreduce(dtype, count):
+def test_in_place_allreduce(dtype, count, fold):
     """recvbuf == sendbuf: the ring reads every location of the send buffer (reduce phase) before the
     gather phase overwrites it, slice by slice, so an all-reduce may run in place."""
     from paper_2303_06324_amd import harness as gh
@@ -264,7 +276,7 @@ def test_in_place_allreduce(dtype, count):
     want = rd.all_reduce_fold(sends, dtype)
     bufs = [torch.from_numpy(s.view(np.uint8).copy()).cuda() for s in sends]
     torch.cuda.synchronize()
-    ctx = dfx.Context(8, gh.make_config())
+    ctx = dfx.Context(8, gh.make_config(fold_max_bytes=fold))
     try:
         ctx.prepare(0, dfx.ALLREDUCE, count, dtype)
         ptrs = ctx.make_all([b.data_ptr() for b in bufs], [b.data_ptr() for b in bufs])
@@ -278,7 +290,8 @@ def test_in_place_allreduce(dtype, count):
 
 @pytest.mark.parametrize("knobs", [dict(focus_bytes=0), dict(focus_bytes=16 << 10), dict(window=1), dict(window=4, nslots=8),
                                    dict(sq_eager=0), dict(wg_map=1), dict(focus_bytes=0, scan_min=0, sq_eager=0, window=1),
-                                   dict(direct=0), dict(direct_min_bytes=0), dict(direct_min_bytes=0, wg_map=1, window=1)])
+                                   dict(direct=0), dict(direct_min_bytes=0), dict(direct_min_bytes=0, wg_map=1, window=1),
+                                   dict(fold_max_bytes=0), dict(fold_max_bytes=1 << 20), dict(fold_max_bytes=1 << 20, wg_map=1, scan_min=0)])
 def test_scheduling_knobs_do_not_change_the_values(knobs):
     """The scheduler's options (focused passes and their byte budget, slice windows, eager SQ probing, the
     workgroup map, Alg. 1 as written) change who runs when, never what is computed: the gradient buckets
@@ -288,7 +301,7 @@ def test_scheduling_knobs_do_not_change_the_values(knobs):
 
 
 # ---------------------------------------------------------------- direct gather steps of the all-reduce
-DIRECT = dict(direct_min_bytes=0)     # every all-reduce, whatever its size, takes the direct gather steps
+DIRECT = dict(direct_min_bytes=0, fold_max_bytes=0)     # every all-reduce, whatever its size, takes the ring with direct gather steps
 
 
 @pytest.mark.parametrize("dtype,count", [(wi.F32, 1), (wi.F32, 70001), (wi.BF16, 300007), (wi.F16, 4099), (wi.I32, 1 << 20),
@@ -362,8 +375,9 @@ def test_direct_reduce(dtype, count, op, R, root):
     _run(_one(wi.RD, dtype, count, R, root=root, seed=count + R, op=op), **DIRECT)
 
 
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
 @pytest.mark.parametrize("quit_idle_us", [0, 200])
-def test_direct_steps_of_every_kind_survive_stop_and_quit(quit_idle_us):
+def test_direct_steps_of_every_kind_survive_stop_and_quit(quit_idle_us, fold):
     """One collective of every kind with direct steps, stuck because two ranks have not submitted: the daemon
     is stopped (or leaves by itself when idle), started again, the missing ranks submit, and the values are
     the oracle's: saved positions, claimed counters and the buffer addresses published in the connectors
@@ -376,7 +390,7 @@ def test_direct_steps_of_every_kind_survive_stop_and_quit(quit_idle_us):
              wi.CollSpec(3, wi.BC, wi.I32, 250001, 3), wi.CollSpec(4, wi.RD, wi.F32, 270001, 5, wi.SUM)]
     w = wi.Workload("stop_direct", R, colls, [list(range(5))] * R, seed=91, cfg=50)
     dw = gh.DeviceWorkload(w)
-    ctx = dfx.Context(R, gh.make_config(quit_idle_us=quit_idle_us, slot_bytes=16 << 10, **DIRECT))
+    ctx = dfx.Context(R, gh.make_config(quit_idle_us=quit_idle_us, slot_bytes=16 << 10, direct_min_bytes=0, fold_max_bytes=fold))
     try:
         gh.prepare_all(ctx, w)
         for ci in range(5):
@@ -428,6 +442,7 @@ def test_random_mixes_under_random_knobs(block):
         if rng.integers(0, 3) == 0: knobs["slot_bytes"] = int(rng.choice([4096, 16384, 65536]))
         if rng.integers(0, 4) == 0: knobs["focus_bytes"] = 0
         if rng.integers(0, 4) == 0: knobs["nslots"] = 2
+        if rng.integers(0, 2) == 0: knobs["fold_max_bytes"] = int(rng.choice([0, 64 << 10, 64 << 20]))
         w = _mixed_workload(seed, n_colls=int(rng.integers(8, 40)))
         if rng.integers(0, 2):
             colls = [wi.CollSpec(c.coll_id, c.kind, c.dtype, max(8, c.count // 8 * 8) if c.kind in (wi.AG, wi.RS) else c.count,
@@ -491,3 +506,32 @@ def test_direct_broadcast(dtype, count, R, root):
     """Broadcast with direct steps: every rank writes its recv buffer only, the next one reads it there;
     a drain round after the last slice keeps the completion behind the neighbour's last read."""
     _run(_one(wi.BC, dtype, count, R, root=root, seed=count + R), **DIRECT)
+
+
+# ---------------------------------------------------------------- fold steps of short all-reduces
+@pytest.mark.parametrize("op", [wi.SUM, wi.PROD, wi.MAX, wi.MIN])
+@pytest.mark.parametrize("dtype", [wi.F32, wi.BF16, wi.F16, wi.I32])
+def test_fold_steps_dtypes_functions_and_ragged_sizes(dtype, op):
+    """Fold steps at every size up to several channels and slices' worth (the limit raised to 64 MiB): the chunk a
+    rank combines out of all send buffers has the ring's association order, so the bits are the ring's; ragged
+    counts give short and empty last chunks and sub-vector tails."""
+    for count in (1, 9, 1000, 70001, (1 << 20) + 13):
+        _run(_one(wi.AR, dtype, count, 8, seed=count + op, op=op), fold_max_bytes=64 << 20)
+
+
+@pytest.mark.parametrize("R", [2, 3, 5, 9, 16, 33, 64])
+def test_fold_steps_rank_counts(R):
+    """More ranks than the eight sources a mover reads together, up to the 64 of a wavefront's lanes."""
+    cm = max(1, min(8, 256 // R))
+    _run(_one(wi.AR, wi.F32, 20000 + R, R, seed=R), max_channels=cm, fold_max_bytes=64 << 20)
+    _run(_one(wi.AR, wi.BF16, 3001, R, seed=R + 1, op=wi.MIN), max_channels=cm, fold_max_bytes=64 << 20)
+
+
+def test_fold_steps_under_forced_preemption_and_disorder():
+    """One shared queue per rank, the smallest thresholds, every rank its own order: each of the three waits of
+    every collective is abandoned many times, and the values stay the oracle's."""
+    stats = _run(wi.config5(n_colls=96, seed=6), mode="threads", timeout_s=60.0, max_channels=2, chan_spread=0, scan_min=0,
+                 spin_init=1, spin_min=1, spin_max=1, spin_boost=1)
+    assert sum(s["preemptions"] for s in stats) > 100
+    _run(wi.config3(n_buckets=8, bucket_bytes=1 << 20, seed=62), max_channels=2, chan_spread=0,
+         spin_init=1, spin_min=1, spin_max=1, spin_boost=1)

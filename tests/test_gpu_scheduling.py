@@ -121,21 +121,38 @@ def test_priority_ordering_policy():
         ctx.finalize()
 
 
-def _completion_order(order_policy, priorities, n_colls=8, nbytes=8 << 20, **knobs):
-    """n equal all-reduces on ONE channel per vrank (one task queue per rank), submitted 0, 1, ... on every
-    rank in one burst; returns the order in which vrank 0's completions are seen by a tight poll loop."""
+def _completion_order(order_policy, priorities, n_colls=8, nbytes=8 << 20, late_last_ms=0.0, **knobs):
+    """n equal all-reduces on ONE channel per vrank (one task queue per rank), submitted 0, 1, ... on every rank;
+    returns the order in which vrank 0's completions are seen by a tight poll loop.  The daemon's launch waits
+    behind a kernel that only sleeps, so every submission is in the SQs when the daemon first looks (host
+    scheduling has no say); with late_last_ms the last collective is submitted that much later, while the
+    others are under way."""
     import time
+    import torch
     from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
     R = 8
     colls = [wi.CollSpec(i, wi.AR, wi.F32, nbytes // 4) for i in range(n_colls)]
     w = wi.Workload("prio_order", R, colls, [list(range(n_colls))] * R, seed=31, cfg=50)
     dw = gh.DeviceWorkload(w)
-    ctx = dfx.Context(R, gh.make_config(order_policy=order_policy, max_channels=1, chan_spread=0, quit_idle_us=0, **knobs))
+    stream = torch.cuda.Stream()                     # default priority
+    ctx = dfx.Context(R, gh.make_config(order_policy=order_policy, max_channels=1, chan_spread=0, quit_idle_us=0, **knobs),
+                      stream=stream.cuda_stream)
     order = []
     try:
         gh.prepare_all(ctx, w, priorities=priorities)
-        gh.submit_threads(ctx, dw, timeout_s=30)
+        slept = torch.cuda.Event()
+        with torch.cuda.stream(stream):
+            torch.cuda._sleep(20_000_000)            # some milliseconds: the submissions below take microseconds
+            slept.record(stream)
+        first = n_colls - 1 if late_last_ms else n_colls
+        gh.submit_round_robin(ctx, dw, orders=[list(range(first))] * R, timeout_s=30)
+        if late_last_ms:
+            deadline = time.monotonic() + 10.0
+            while not slept.query():                 # the sleeping kernel has ended: the daemon starts on the others now
+                assert time.monotonic() < deadline
+            time.sleep(late_last_ms * 1e-3)
+            gh.submit_round_robin(ctx, dw, orders=[[n_colls - 1]] * R, timeout_s=30)
         deadline = time.monotonic() + 30.0
         while len(order) < n_colls:
             order += [cid for cid, _ in ctx.poll(0, 64)]
@@ -153,18 +170,25 @@ def test_priority_ordering_decides_who_completes_first():
     """Eight equal all-reduces (8 MiB, one channel: milliseconds each) queued on every vrank in the order
     0 .. 7.  Under FIFO ordering the one submitted first completes first and the one submitted last does
     not; under priority ordering with later = more urgent (the DP-overlap scheme of Sec. 4.3) the one
-    submitted last completes first although the others were queued, and partly under way, before it; with
-    the priorities the other way round the order is the FIFO one again."""
+    submitted last completes first; with the priorities the other way round the order is the FIFO one again."""
     fifo = _completion_order(0, None)
-    assert fifo[0] == 0 and fifo[-1] != 0 and fifo.index(7) > 3, fifo
+    assert fifo[0] == 0 and fifo.index(7) > 3, fifo
     later_first = _completion_order(1, list(range(8)))
-    assert later_first[0] == 7 and later_first.index(0) > 3, later_first
-    assert later_first[:4] == [7, 6, 5, 4], later_first
+    assert later_first[:4] == [7, 6, 5, 4] and later_first.index(0) > 3, later_first
     earlier_first = _completion_order(1, [8 - i for i in range(8)])
-    assert earlier_first[0] == 0 and earlier_first[:4] == [0, 1, 2, 3], earlier_first
+    assert earlier_first[:4] == [0, 1, 2, 3], earlier_first
     # the same with Alg. 1's own queue handling (no readiness scan: the sorted queue and the thresholds decide)
     alg1 = _completion_order(1, list(range(8)), scan_min=0)
     assert alg1.index(7) < alg1.index(0), alg1
+
+
+def test_priority_ordering_lets_a_late_urgent_collective_overtake():
+    """Seven all-reduces are under way when an eighth, more urgent one is submitted half a millisecond later: under
+    priority ordering it overtakes those queued and begun before it; under FIFO ordering it completes last."""
+    fifo = _completion_order(0, None, nbytes=16 << 20, late_last_ms=0.5)       # (16 MiB on one channel: milliseconds each)
+    assert fifo[-1] == 7, fifo
+    prio = _completion_order(1, list(range(8)), nbytes=16 << 20, late_last_ms=0.5)
+    assert prio.index(7) <= 2, prio
 
 
 def test_sq_backpressure_and_poll_interface():

@@ -49,9 +49,9 @@ def _check_exact(dw, w):
                     f"inputs {ins}")
 
 
-@pytest.mark.parametrize("count_rs,knobs", [(15013, dict()),
-                                            (15016, dict(direct_min_bytes=0, slot_bytes=4096, nslots=2, max_channels=4))],
-                         ids=["defaults", "direct_steps_small_slots"])
+@pytest.mark.parametrize("count_rs,knobs", [(15013, dict()), (15013, dict(fold_max_bytes=0)),
+                                            (15016, dict(direct_min_bytes=0, fold_max_bytes=0, slot_bytes=4096, nslots=2, max_channels=4))],
+                         ids=["defaults_fold_steps", "ring_through_slots", "ring_direct_steps_small_slots"])
 @pytest.mark.parametrize("R", [8, 3])
 def test_constructed_values_every_dtype_function_and_reducing_kind(R, count_rs, knobs):
     """48 collectives (all-reduce, reduce-scatter, reduce x four dtypes x four reducing functions) on

@@ -487,3 +487,76 @@ def test_priority_ordering_ranks_the_urgent_collective_first(later_first):
     assert S.done() and S.total_cqes() == 2 * n
     assert order == (list(reversed(range(n))) if later_first else list(range(n))), order
     _check_data(S, w)
+
+
+# ---------------------------------------------------------------- fold steps of an all-reduce
+@pytest.mark.parametrize("var", [dict(), dict(scan=True), dict(lookahead=2, scan=True, focus=1)])
+@pytest.mark.parametrize("orders", [_OPP, _SAME])
+def test_fold_steps_exhaustive_interleavings_tiny(orders, var):
+    """All-reduces in fold steps (three waits on all ranks: published, folded, gathered) keep Alg. 1's liveness:
+    in the circular-wait setting no reachable state -- over all interleavings of daemons, movers and host
+    submissions -- is a deadlock, and every one of them ends with the four CQEs."""
+    w = wi.config1(*orders, n=8)
+    pol = sm.Policy(spin_init=2, spin_min=1, spin_max=2, boost=2, K=2, slice_elems=4, fold=True, **var)
+    S0 = _system(w, pol, data=False)
+    seen = sm.explore(S0, max_states=600_000)
+    assert len(seen) > 20
+    keys = list(seen)
+    step = 1 if len(keys) < 1000 else 97
+    for k in keys[::step]:
+        T = seen[k].clone()
+        assert not sm.is_deadlocked(T)
+        sm.run_round_robin(T, max_ticks=50_000)
+        assert T.total_cqes() == 4
+
+
+def test_fold_steps_without_preemption_still_deadlock_on_opposite_orders():
+    """The fold step waits for every rank to have fetched the collective: with one-entry task queues, opposite
+    orders and no preemption each rank waits for the other to fetch what it will never fetch."""
+    w = wi.config1((0, 1), (1, 0))
+    S = _system(w, sm.Policy(preempt=False, K=2, slice_elems=256, taskq_cap=1, fold=True), data=False)
+    with pytest.raises(TimeoutError):
+        sm.run_round_robin(S, max_ticks=20_000)
+    assert sm.is_deadlocked(S)
+
+
+@pytest.mark.parametrize("var", [dict(), dict(lookahead=2, scan=True, focus=1, direct=True)])
+@pytest.mark.parametrize("seed", range(4))
+def test_fold_steps_values_and_completion_order(var, seed):
+    """Mixed kinds on three ranks (the all-reduces in fold steps), random orders, random interleavings: the final
+    buffers are the data oracle's -- the fold step's order of combination is the ring's -- and no rank posts an
+    all-reduce's completion before every rank has finished its gather step (the recv buffer, which the others
+    read, is the caller's again after the completion)."""
+    g = np.random.default_rng(seed)
+    R = 3
+    colls = [wi.CollSpec(0, wi.AR, wi.F32, 50), wi.CollSpec(1, wi.AG, wi.F16, 12), wi.CollSpec(2, wi.AR, wi.BF16, 33),
+             wi.CollSpec(3, wi.BC, wi.BF16, 40, root=2), wi.CollSpec(4, wi.AR, wi.I32, 7)]
+    orders = [list(map(int, g.permutation(len(colls)))) for _ in range(R)]
+    w = wi.Workload("fold", R, colls, orders, seed=seed, cfg=94)
+    S = _system(w, sm.Policy(spin_init=2, spin_max=4, boost=2, K=2, slice_elems=8, fold=True, **var))
+    ticks = 0
+    while not S.done():
+        a = int(g.integers(0, 3 * R))
+        if a >= 2 * R:
+            S.daemons[a - 2 * R].mover_tick()
+        elif a >= R:
+            S.host_tick(a - R)
+        else:
+            S.daemons[a].tick()
+        for d in S.daemons:
+            for c, _ in d.cq:
+                if colls[c].kind == wi.AR:      # (every collective is invoked once here)
+                    assert S.foldcnt[c][2] >= R and S.foldcnt[c][1] >= R
+        ticks += 1
+        assert ticks < 3_000_000
+    assert S.total_cqes() == R * len(colls)
+    _check_data(S, w)
+
+
+def test_fold_programs_move_fewer_blocks_than_the_ring():
+    """Per rank, in chunks: the fold step reads R and writes 1, the gather step reads and writes R - 1."""
+    for R in (2, 3, 8):
+        blocks = [(8 * j, 8 * j + 8) for j in range(R)]
+        prog = sm.program(sm.AR, R, 1, 0, blocks, blocks, False, True)
+        assert [n for n, _, _ in prog] == ["fold_all", "gather_all", "last_wait"]
+        assert prog[0][1] == blocks[1] and prog[0][2] == blocks[1]        # rank r combines chunk r

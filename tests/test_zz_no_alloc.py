@@ -40,12 +40,12 @@ def _both_paths(kind, dtype, count, R, root=0, op=wi.SUM, seed=0):
 
 
 def test_noalloc_two_calls_in_a_row_second_one_smaller():
-    _both_paths(wi.AR, wi.F32, 3 * (1 << 20) + 7, 8, seed=1)     # 12 MiB per rank: direct steps, several slices per channel
-    _both_paths(wi.AR, wi.F32, 4099, 8, seed=2)                   # smaller: fewer channels, through the slots
+    _both_paths(wi.AR, wi.F32, 17 * (1 << 20) + 7, 8, seed=1)    # 68 MiB per rank: the ring, direct steps, many slices through the scratch's slots
+    _both_paths(wi.AR, wi.F32, 4099, 8, seed=2)                   # smaller: one channel, fold steps
     _both_paths(wi.AR, wi.BF16, 300007, 8, op=wi.MAX, seed=3)
 
 
-@pytest.mark.parametrize("kind,dtype,count,R,root", [(wi.AG, wi.F16, 40008, 8, 0), (wi.RS, wi.I32, 30001, 5, 0),
+@pytest.mark.parametrize("kind,dtype,count,R,root", [(wi.AG, wi.F16, 40008, 8, 0), (wi.RS, wi.I32, 30001, 5, 0), (wi.RS, wi.F32, 1 << 20, 8, 0),
                                                      (wi.BC, wi.F32, 1 << 20, 8, 3), (wi.RD, wi.BF16, 270001, 3, 2),
                                                      (wi.AR, wi.F32, 1, 16, 0), (wi.AR, wi.I32, 0, 4, 0)])
 def test_noalloc_other_kinds_and_rank_counts(kind, dtype, count, R, root):
