@@ -58,6 +58,7 @@ def cpu_baseline(sends, min_seconds: float = 10.0, max_reps: int = 40):
     box = os.cpu_count() or 1
     nthr = max(1, min(R, box))
     reps, total, out = 0, 0.0, None
+    max_reps = max(max_reps, 150)
     while total < min_seconds and reps < max_reps:
         t0 = time.perf_counter()
         out = rd.all_reduce_replay(sends, rd.F32, threads=nthr)
@@ -103,8 +104,13 @@ def _switch_summary(rc, dt, st, n, st2):
             "samples": sum(s["switch_samples"] for s in st),
             "p50_us": round(max(s["switch_us_p50"] for s in st), 3),
             "p99_us": round(max(s["switch_us_p99"] for s in st), 3),
+            # the parts of a switch (a second run with five clock reads per switch instead of two): saving the
+            # dynamic context, going on to the next queue entry (finished jobs are retired on the way), loading
+            # its context, and setting up its primitive up to the first poll
             "save_us_mean": round(sum(s["save_us_mean"] for s in st2) / len(st2), 3),
-            "load_us_mean": round(sum(s["load_us_mean"] for s in st2) / len(st2), 3)}
+            "advance_us_mean": round(sum(s["advance_us_mean"] for s in st2) / len(st2), 3),
+            "load_us_mean": round(sum(s["load_us_mean"] for s in st2) / len(st2), 3),
+            "setup_us_mean": round(sum(s["setup_us_mean"] for s in st2) / len(st2), 3)}
 
 
 def _switch_config1(trace: int, iters: int = 400):
@@ -136,12 +142,15 @@ def _switch_config1(trace: int, iters: int = 400):
 def switch_latency():
     """Context-switch latency (abort decision -> first poll of the next collective of the same pass):
     1024 small all-reduces issued in a different random order on every vrank, with the library
-    defaults and with the queue handling of Alg. 1 as written (one shared queue per vrank, every
-    entry polled in turn); and the circular-wait pair with the smallest thresholds.  Each case runs
+    defaults (fold steps) and with the queue handling of Alg. 1 as written (one shared queue per vrank, every
+    entry polled in turn), the latter also as rings through the connectors' slots; and the circular-wait pair
+    with the smallest thresholds.  Each case runs
     twice: with two clock reads per switch (the latency), and with the save / load parts timed too."""
     out = _switch_summary(*_switch_run(1), _switch_run(2)[2])
     alg1 = dict(chan_spread=0, scan_min=0)
     out["alg1_single_queue"] = _switch_summary(*_switch_run(1, **alg1), _switch_run(2, **alg1)[2])
+    ring = dict(chan_spread=0, scan_min=0, fold_max_bytes=0)
+    out["alg1_single_queue_rings"] = _switch_summary(*_switch_run(1, **ring), _switch_run(2, **ring)[2])
     out["config1_tiny_threshold"] = _switch_summary(*_switch_config1(1), _switch_config1(2)[2])
     return out
 
@@ -222,14 +231,15 @@ def size_sweep(iters: int = 10):
                 assert ctx.wait_all(30.0) == dfx.OK
                 best = min(best, time.perf_counter() - t0)
             nchan = ctx.coll_info(0)["nchan"]
-            direct = ctx.coll_info(0)["nprim"] == 2 * R
+            nprim = ctx.coll_info(0)["nprim"]
         finally:
             ctx.finalize()
-        nb = moved_bytes(nbytes, R) if direct else algorithmic_bytes(nbytes, R)
+        path = {3: "fold steps", 2 * R: "ring, direct steps"}.get(nprim, "ring through slots")
+        nb = {3: fold_bytes, 2 * R: moved_bytes}.get(nprim, algorithmic_bytes)(nbytes, R)     # what the path taken moves
         rows.append({"bytes": nbytes, "us": round(best * 1e6, 1), "channels": nchan,
                      "algbw_GBs": round(nbytes / best / 1e9, 2),
                      "busbw_GBs": round(nbytes / best * 2 * (R - 1) / R / 1e9, 2),
-                     "direct": direct,
+                     "path": path, "moved_GB": round(nb / 1e9, 4),
                      "hbm_frac": round(nb / best / 1e9 / HBM_PEAK_GBS, 4)})
         del send, recv
     return rows
@@ -312,6 +322,58 @@ def spin_sweep():
     return rows
 
 
+def ordering_staggered(n_buckets: int = 16, bucket_bytes: int = 25 << 20):
+    """FIFO against priority ordering where the order can matter (Sec. 4.3: the DP-overlap scheme, later-arriving =
+    more urgent): the gradient buckets are submitted in the same order 0 .. 15 on every vrank but 20-50 us apart
+    (seeded), as a backward pass produces them, from one native thread per vrank; vrank 0's completions are
+    time-stamped by a tight poll loop.  Reported per policy: when the first and the last bucket complete,
+    measured from the first submission, how long the last-submitted (most urgent) bucket took from its own
+    submission, and the order of completion.  Best of three runs by total time."""
+    import threading
+    import numpy as np
+    import workload_inputs as wi
+    import paper_2303_06324_amd as dfx
+    from paper_2303_06324_amd import harness as gh
+    w = wi.config3(n_buckets=n_buckets, bucket_bytes=bucket_bytes)
+    dw = gh.DeviceWorkload(w, keep_host=False)
+    g = np.random.default_rng(1234)
+    delays = [[0.0] + list(map(float, g.uniform(20.0, 50.0, size=n_buckets - 1))) for _ in range(R)]
+    orders = [list(range(n_buckets))] * R
+    rows = []
+    for policy, name in ((0, "FIFO ordering"), (1, "priority ordering, later bucket = more urgent")):
+        ctx = dfx.Context(R, gh.make_config(order_policy=policy, quit_idle_us=0))
+        best = None
+        try:
+            gh.prepare_all(ctx, w, priorities=list(range(n_buckets)))
+            ctx.start()
+            time.sleep(0.01)
+            for rep in range(3):
+                done_at, order = {}, []
+                th = threading.Thread(target=gh.submit_threads, args=(ctx, dw), kwargs=dict(orders=orders, delays_us=delays, timeout_s=60))
+                t0 = time.perf_counter()
+                th.start()
+                while len(order) < n_buckets and time.perf_counter() - t0 < 30.0:
+                    for cid, _ in ctx.poll(0, 64):
+                        done_at[cid] = time.perf_counter() - t0
+                        order.append(cid)
+                th.join()
+                rc = ctx.wait_all(30.0)
+                last_submit = sum(delays[0]) * 1e-6           # vrank 0's last bucket leaves the host about then
+                row = {"policy": name, "completed": rc == 0 and len(order) == n_buckets,
+                       "first_bucket_done_ms": round(min(done_at.values()) * 1e3, 3),
+                       "all_done_ms": round(max(done_at.values()) * 1e3, 3),
+                       "last_submitted_bucket_done_ms": round(done_at[n_buckets - 1] * 1e3, 3),
+                       "last_submitted_bucket_latency_ms": round((done_at[n_buckets - 1] - last_submit) * 1e3, 3),
+                       "completion_order": order}
+                if best is None or row["all_done_ms"] < best["all_done_ms"]:
+                    best = row
+            ctx.stop()
+        finally:
+            ctx.finalize()
+        rows.append(best)
+    return rows
+
+
 def studies():
     """Two comparisons the paper makes (Sec. 5 "Optimizing CQ", Fig. 7c; Sec. 4.3 ordering policies):
     CQE write time of the three completion-queue variants on the small-collective workload, and FIFO
@@ -343,6 +405,7 @@ def studies():
                 "collectives_per_s": round(1024 / min(dts), 1), "ms": round(min(dts) * 1e3, 2)}
         out["cq_variants"].append(best)
     del d5
+    out["ordering_staggered_arrivals"] = ordering_staggered()
     w3 = wi.config3()
     d3 = gh.DeviceWorkload(w3, keep_host=False)
     for policy, name in ((0, "FIFO ordering"), (1, "priority ordering, later bucket = higher priority")):
@@ -372,6 +435,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--msg-mib", type=int, default=256, help="per-rank message size in MiB")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-fold", action="store_true", help="skip the run of the same workload in fold steps")
     ap.add_argument("--no-switch", action="store_true", help="skip the context-switch latency leg")
     ap.add_argument("--no-orders", action="store_true", help="skip the deadlock-prone-orders leg")
     ap.add_argument("--sweep", action="store_true", help="add the 8 KiB .. 256 MiB size sweep to the JSON line")
@@ -435,6 +499,25 @@ def main():
     # what the last timed step left in the recv buffers (checked against the oracle below, outside the timed region)
     got = {r: recv[r].cpu().numpy() for r in (0, 5)}
     same_on_all_ranks = all(torch.equal(recv[0].view(torch.int32), recv[r].view(torch.int32)) for r in range(1, R))
+    # the same workload in fold steps (the default below 64 MiB per rank), for the record: fewer bytes, no FIFOs
+    fold_ms = None
+    if not args.no_fold:
+        cfg2 = gh.make_config(quit_idle_us=0, fold_max_bytes=min(2 * M, (1 << 32) - 1))
+        ctx2 = dfx.Context(R, cfg2)
+        try:
+            ctx2.prepare(0, dfx.ALLREDUCE, n, dfx.F32)
+            assert ctx2.coll_info(0)["nprim"] == 3
+            ts = []
+            for it in range(8):
+                t0f = time.perf_counter()
+                assert ctx2.submit_all(0, ptrs) == dfx.OK and ctx2.wait_all(30.0) == dfx.OK
+                ts.append(time.perf_counter() - t0f)
+            fold_ms = min(ts[2:]) * 1e3
+            ctx2.stop()
+            fold_same = all(torch.equal(recv[0].view(torch.int32), recv[r].view(torch.int32)) for r in range(1, R))
+            fold_got = recv[5].cpu().numpy()
+        finally:
+            ctx2.finalize()
     # what a plain copy kernel reaches on this chip (reads + writes over its HIP-event time): context
     # for the roofline fraction, which is priced against the published 8 TB/s
     copy_ms = []
@@ -486,6 +569,12 @@ def main():
                      "primitive_table_frac": round(table_rate / HBM_PEAK_GBS, 4)},
         "copy_kernel_GBs": round(copy_gbs, 1),
     }
+    if fold_ms is not None:
+        out["fold_steps_same_workload"] = {
+            "note": "the same all-reduce in fold steps (library default below 64 MiB per rank; here forced): resident daemon, "
+                    "submit -> last CQE, best of 6; moves (3R-1) x M instead of (5R-5) x M and uses no FIFO slots",
+            "ms": round(fold_ms, 4), "busbw_GBs": round(M / (fold_ms * 1e-3) / 1e9 * 2 * (R - 1) / R, 2),
+            "bytes_moved": fold_bytes(M, R), "hbm_frac": round(fold_bytes(M, R) / (fold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     del send, recv
     torch.cuda.empty_cache()
     if not args.no_switch:
@@ -504,6 +593,9 @@ def main():
         # the CPU leg replays the same inputs; its result is also the check of what the timed steps computed
         out["cpu_baseline"], want = cpu_baseline(host)
         verified = bool(same_on_all_ranks and all(np.array_equal(got[r].view(np.uint32), want[r].view(np.uint32)) for r in got))
+        if fold_ms is not None:
+            out["fold_steps_same_workload"]["verified"] = bool(fold_same and np.array_equal(fold_got.view(np.uint32), want[5].view(np.uint32)))
+            verified = verified and out["fold_steps_same_workload"]["verified"]
     out["verified"] = verified
     out["verified_how"] = ("ranks 0 and 5: whole recv buffers of the last timed step bit-identical to the CPU oracle's replay of "
                            "the same seeded inputs; all 8 ranks bit-identical to each other (on the device)"

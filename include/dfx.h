@@ -175,6 +175,10 @@ typedef struct {
   double publish_us;       /* ... between the last mover wave's drain and its counter updates */
   uint64_t scan_skips;     /* queue entries a readiness scan found not runnable (no context load, no spin) */
   double cqe_us;           /* time spent writing CQEs (first to last host-memory operation), summed; always counted */
+  double advance_us_mean;  /* with trace = 2: the part of a switch between the save and the load (retiring finished jobs, next queue entry) */
+  double setup_us_mean;    /* with trace = 2: the part after the load (thresholds, the primitive's descriptor) up to the first poll */
+  double clock_read_us;    /* with trace = 1 or 2: what one read of the wall clock costs the scheduler (a switch sample holds two
+                              reads, a split sample five) */
 } dfx_stats_t;
 
 /* Fill *cfg with defaults (struct_bytes set). cfg: host, caller-owned. */
@@ -297,8 +301,8 @@ int dfx_coll_info(dfx_ctx* ctx, int coll_id, uint32_t* nchan, uint32_t* slot_byt
 
 /* Raw trace samples of one workgroup (0 <= wg < nranks * max_channels), oldest first while fewer than
    4096 have been written (a ring afterwards); valid once the daemon has stopped or quit.  With
-   trace = 1 or 2 a sample is one context switch: bits 0-23 total ticks, 24-43 save ticks, 44-63 load
-   ticks.  With trace = 3 a sample is one executed primitive (the breakdown of Sec. 6.3 per
+   trace = 1 or 2 a sample is one context switch: bits 0-15 total ticks, and with trace = 2 bits 16-27 save,
+   28-39 queue advance, 40-51 load, 52-63 set-up ticks (each saturating).  With trace = 3 a sample is one executed primitive (the breakdown of Sec. 6.3 per
    workgroup): bits 0-31 low word of the wall clock when its data phase began, 32-47 ticks the data
    phase took (saturating), 48-59 collective id (low 12 bits), 60-63 index in the primitive sequence
    (low 4 bits), or 15 for a wait phase that ended in preemption (then the two times are those of

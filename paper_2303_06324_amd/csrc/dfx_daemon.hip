@@ -821,6 +821,14 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
     // scheduler wave
     // =====================================================================================
     u64 last_act = wall_clock64();
+    if (a.trace_on && a.trace_on < 3) {
+      // what one clock read costs (the switch samples contain two of them, the split samples five): 16 in a row
+      u64 tc = last_act;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) tc = wall_clock64();
+      if (lane == 0) { bump(sh.stat, ST_T_STAMP, tc - last_act); bump(sh.stat, ST_N_STAMP, 16); }
+      last_act = tc;
+    }
     bool acted = true, voted = false;
     uint32_t iter = 0, idle = 0, burst = 0;
     bool in_pass = false, pass_progress = false, scanned = false;
@@ -1272,20 +1280,23 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       u64* const tail_in = (u64*)S.flags_in;
       const uint32_t K = S.nslots;
 
-      u64 tm0 = 0;
-      if (a.trace_on > 1) tm0 = wall_clock64();
       if (sw_pending) {   // the first poll of the next collective ends the context switch
         const u64 t1 = wall_clock64();
         if (trace && a.trace_on < 3 && lane == 0) {
-          u64 tot = t1 - sw_t0, sv = sw_ts - sw_t0, ldt = sw_le - sw_lb;
-          if (a.trace_on < 2) { sv = 0; ldt = 0; }
-          if (tot > 0xffffffu) tot = 0xffffffu;
-          if (sv > 0xfffffu) sv = 0xfffffu;
-          if (ldt > 0xfffffu) ldt = 0xfffffu;
-          trace_put(trace, &sh.trace_n, tot | (sv << 24) | (ldt << 44));
+          // total | save | queue advance (save done -> context load begins) | load | set-up of the primitive (load done -> here)
+          u64 tot = t1 - sw_t0, sv = sw_ts - sw_t0, adv = sw_lb - sw_ts, ldt = sw_le - sw_lb, su = t1 - sw_le;
+          if (a.trace_on < 2) { sv = 0; adv = 0; ldt = 0; su = 0; }
+          if (tot > 0xffffu) tot = 0xffffu;
+          if (sv > 0xfffu) sv = 0xfffu;
+          if (adv > 0xfffu) adv = 0xfffu;
+          if (ldt > 0xfffu) ldt = 0xfffu;
+          if (su > 0xfffu) su = 0xfffu;
+          trace_put(trace, &sh.trace_n, tot | (sv << 16) | (adv << 28) | (ldt << 40) | (su << 52));
         }
         sw_pending = false;
       }
+      u64 tm0 = 0;
+      if (a.trace_on > 1) tm0 = wall_clock64();
 
       // ---- wait phase: lane 0 polls the recv side, lane 1 the send side (Sec. 4.2 (3)).
       // The first poll is sent off before the slice's geometry is worked out, which depends only on

@@ -861,6 +861,7 @@ int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
   HIPCHK(c, hipStreamSynchronize(c->side));
   std::vector<uint32_t> wgs;
   std::vector<uint32_t> tn;
+  uint64_t stamp_ticks = 0, stamp_n = 0;
   for (uint32_t wg = 0; wg < c->nwg; ++wg) {
     uint32_t r = c->cfg.wg_map == 0 ? wg % (uint32_t)c->R : wg / c->cfg.max_channels;
     if ((int)r != rank) continue;
@@ -873,13 +874,15 @@ int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
     out->publish_us += (double)s[ST_T_PUB] * c->tick_us;
     out->scan_skips += s[ST_SCAN_SKIPS];
     out->cqe_us += (double)s[ST_T_CQE] * c->tick_us;
+    stamp_ticks += s[ST_T_STAMP]; stamp_n += s[ST_N_STAMP];
     wgs.push_back(wg);
     tn.push_back(h[wg].trace_n);
   }
   out->launches = c->launches;
+  if (stamp_n) out->clock_read_us = (double)stamp_ticks * c->tick_us / (double)stamp_n;
   if (c->trace && c->cfg.trace < 3) {
     std::vector<double> tot;
-    double sv = 0, ld = 0;
+    double sv = 0, ld = 0, adv = 0, su = 0;
     uint64_t* buf = (uint64_t*)c->pinned_tmp;
     for (size_t i = 0; i < wgs.size(); ++i) {
       const uint32_t n = std::min<uint32_t>(tn[i], DFX_TRACE_N);
@@ -888,9 +891,11 @@ int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
       HIPCHK(c, hipStreamSynchronize(c->side));
       for (uint32_t k = 0; k < n; ++k) {
         const uint64_t v = buf[k];
-        tot.push_back((double)(v & 0xffffffu) * c->tick_us);
-        sv += (double)((v >> 24) & 0xfffffu) * c->tick_us;
-        ld += (double)((v >> 44) & 0xfffffu) * c->tick_us;
+        tot.push_back((double)(v & 0xffffu) * c->tick_us);
+        sv += (double)((v >> 16) & 0xfffu) * c->tick_us;
+        adv += (double)((v >> 28) & 0xfffu) * c->tick_us;
+        ld += (double)((v >> 40) & 0xfffu) * c->tick_us;
+        su += (double)((v >> 52) & 0xfffu) * c->tick_us;
       }
     }
     if (!tot.empty()) {
@@ -903,6 +908,8 @@ int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
       out->switch_us_mean = sum / (double)tot.size();
       out->save_us_mean = sv / (double)tot.size();
       out->load_us_mean = ld / (double)tot.size();
+      out->advance_us_mean = adv / (double)tot.size();
+      out->setup_us_mean = su / (double)tot.size();
     }
   }
   return DFX_OK;
