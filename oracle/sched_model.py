@@ -62,13 +62,19 @@ Two variations of Alg. 1 can be switched on, to ask whether they keep its livene
     (most primitives done; ties in queue order), and once n slices have been taken in the
     pass it ends with the entry in hand: every rank ranks the collectives alike, so the
     ranks settle on the same few of them (the coalescing of choices that Sec. 4.3 aims at).
-  * `fold = True`: an all-reduce runs in three steps that each wait on ALL ranks instead of 2R-1 steps that
+  * `fold = True`: collectives run in steps that each wait on ALL ranks (see below for the kinds other than the
+    all-reduce); an all-reduce runs in three steps that each wait on ALL ranks instead of 2R-1 steps that
     each wait on the neighbour (every rank's buffers are readable by every other): "fold_all" waits until
     every rank has fetched (published) the invocation, then rank r combines chunk r out of all R send buffers
     in the ring's order x[r+1] (op) ... (op) x[r] into its recv buffer; "gather_all" waits until every rank
     has done so and copies the other chunks out of their owners' recv buffers; "last_wait" waits until every
     rank has copied and moves nothing.  Three shared counters per collective (published / folded / gathered)
     carry the waits; each step is still poll-then-move, so a stuck one is preempted like any primitive.
+    Reduce-scatter: "fold_all" (block r into the own recv buffer), "last_wait_red" (every rank has folded: the
+    send buffers are free).  Reduce: "fold_root" (rank r combines chunk r of the message in the chain's order
+    x[root+1] (op) ... (op) x[root] into the ROOT's recv buffer), "last_wait_red".  All-gather and broadcast:
+    "gather_pub" (once every rank has published: all R blocks out of the send buffers / the root's send
+    buffer), "last_wait".
   * `priority_order = True` (Sec. 4.3 "Priority-based Ordering"): the SQ is looked at before every
     pass, a fetched collective is inserted behind the queued ones of equal or higher user priority
     (Coll.priority, larger = more urgent), and a focused pass ranks the runnable entries by
@@ -115,6 +121,9 @@ PRIMS = {
     "fold_all": (False, 4),
     "gather_all": (False, 5),
     "last_wait": (False, 6),
+    "fold_root": (False, 4),        # reduce: chunk r into the root's recv buffer
+    "gather_pub": (False, 4),       # all-gather, broadcast: copies out of send buffers once everybody has published
+    "last_wait_red": (False, 5),    # reduce-scatter, reduce: every rank has folded
 }
 
 
@@ -158,6 +167,12 @@ def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
     d = lambda j: recv_blocks[j % R]
     if kind == AR and fold:
         return [("fold_all", b(r), d(r)), ("gather_all", none, none), ("last_wait", none, none)]
+    if kind == RS and fold:
+        return [("fold_all", b(r), recv_blocks[0]), ("last_wait_red", none, none)]
+    if kind == RD and fold:
+        return [("fold_root", none, none), ("last_wait_red", none, none)]
+    if kind in (AG, BC) and fold:
+        return [("gather_pub", none, none), ("last_wait", none, none)]
     if kind == AR:
         p = [("send", b(r - 1), none)]
         p += [("recv_reduce_send", b(r - 1 - s), none) for s in range(1, R - 1)]
@@ -389,7 +404,7 @@ class Daemon:
     def _prim(self, coll, g, p):
         """(name, send block, recv block) of primitive p of round g."""
         S = self.S
-        if S.policy.direct and S.colls[coll].kind in CHAINS and S.R > 1 and g == S.rounds[coll] - 1:
+        if S.policy.direct and not S.is_fold(coll) and S.colls[coll].kind in CHAINS and S.R > 1 and g == S.rounds[coll] - 1:
             return ("drain", None, None)
         return S.progs[coll][self.r][p]
 
@@ -544,10 +559,10 @@ class System:
         self.progs, self.rounds, self.fifo = [], [], []
         for c in colls:
             sb, db, blen = layout(c, R)
-            is_fold = policy.fold and c.kind == AR and R > 1
+            is_fold = policy.fold and R > 1
             self.progs.append([program(c.kind, R, r, c.root, sb, db, policy.direct, is_fold) for r in range(R)])
             self.rounds.append(1 if is_fold else max(1, -(-blen // policy.slice_elems)))   # fold steps: one slice per share
-            if policy.direct and c.kind in CHAINS and R > 1:
+            if policy.direct and c.kind in CHAINS and R > 1 and not is_fold:
                 self.rounds[-1] += 1     # the last round of a chain with direct steps is the drain
             self.fifo.append([Fifo(policy.K) for _ in range(R)])
         self.foldcnt = [[0, 0, 0] for _ in colls]     # fold steps: ranks that have published / folded / gathered, over all invocations
@@ -574,7 +589,7 @@ class System:
                 pass
 
     def is_fold(self, ci) -> bool:
-        return self.policy.fold and self.colls[ci].kind == AR and self.R > 1
+        return self.policy.fold and self.R > 1
 
     # -- data phase
     def _slice(self, blk, g):
@@ -588,21 +603,30 @@ class System:
         c = self.colls[ci]
         tag_out = (g, p)
         x = None
-        if name == "drain" or name == "last_wait":
+        if name in ("drain", "last_wait", "last_wait_red"):
             return
-        if name in ("fold_all", "gather_all"):
+        if name in ("fold_all", "fold_root", "gather_all", "gather_pub"):
             # whole chunks (one slice per share), read out of the other ranks' buffers in place
             if self.with_data:
-                cb = layout(c, self.R)[0]
-                if name == "fold_all":
-                    lo, hi = cb[r]
-                    self.recvs[ci][r][lo:hi] = rd.fold_rotated([s[lo:hi] for s in self.sends[ci]], r + 1, c.dtype)
-                else:
-                    for j in range(self.R):
+                R = self.R
+                if name == "fold_all":        # all-reduce: chunk r; reduce-scatter: block r; the ring's order, which begins behind r
+                    (slo, shi), (dlo, dhi) = sblk, dblk
+                    self.recvs[ci][r][dlo:dhi] = rd.fold_rotated([s[slo:shi] for s in self.sends[ci]], r + 1, c.dtype)
+                elif name == "fold_root":     # reduce: chunk r of the message, the chain's order, into the root's buffer
+                    lo, hi = rd.chunk_bounds(c.count, R, rd.ELEM_BYTES[c.dtype])[r]
+                    self.recvs[ci][c.root][lo:hi] = rd.fold_rotated([s[lo:hi] for s in self.sends[ci]], c.root + 1, c.dtype)
+                elif name == "gather_all":    # all-reduce: the other chunks out of their owners' recv buffers
+                    cb = layout(c, R)[0]
+                    for j in range(R):
                         if j != r:
                             lo, hi = cb[j]
                             self.recvs[ci][r][lo:hi] = self.recvs[ci][j][lo:hi]
-            self.foldcnt[ci][1 if name == "fold_all" else 2] += 1
+                elif c.kind == AG:            # all-gather: block j out of rank j's send buffer
+                    for j in range(R):
+                        self.recvs[ci][r][j * c.count:(j + 1) * c.count] = self.sends[ci][j][:c.count]
+                else:                         # broadcast: the root's send buffer
+                    self.recvs[ci][r][:c.count] = self.sends[ci][c.root][:c.count]
+            self.foldcnt[ci][1 if name.startswith("fold") else 2] += 1
             return
         if PRIMS[name][0]:
             tag, x = fin.pop()

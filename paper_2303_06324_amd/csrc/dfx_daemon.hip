@@ -1173,7 +1173,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 const uint4 d1 = e[7];    // dyn: recvd | preempted | cidx
                 e2c = fl; e3c = fi; e5c = ge; e6c = d0; e7c = d1;
                 const bool e_fold = ((ge.z >> 24) & DFX_CTX_FOLD) != 0;
-                Prim pq = e_fold ? make_fold_prim(d0.y)
+                Prim pq = e_fold ? make_fold_prim((int)((ge.z >> 8) & 0xffu), d0.y)
                                  : make_prim((int)((ge.z >> 8) & 0xffu), a.R, (ge.z >> 24) & 3u, d0.y, ((ge.z >> 24) & DFX_CTX_DIRECT) != 0);
                 if (!e_fold && ((ge.z >> 24) & DFX_CTX_DIRECT))
                   pq = chain_drain_round(pq, (int)((ge.z >> 8) & 0xffu), true, d0.x, e[4].w);   // bytes 64..79: fifo_in | slice_elems | rounds
@@ -1181,7 +1181,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 const u64 e_sent = ((u64)d0.w << 32) | d0.z, e_recvd = ((u64)d1.y << 32) | d1.x;
                 bool okr = true, oks = true;
                 if (pq.fold)   // every rank of the channel has got as far as this step needs: (seq + 1) x R on the step's counter
-                  okr = ld_agent64((const u64*)(fold_shared_line(f_out, rank, a.R, ge.y >> 16) + 8u * (pq.fold - 1u))) >= ((u64)ge.x + 1u) * a.R;
+                  okr = ld_agent64((const u64*)(fold_shared_line(f_out, rank, a.R, ge.y >> 16) + 8u * pq.fwait)) >= ((u64)ge.x + 1u) * a.R;
                 if (pq.recv) okr = ld_agent64((const u64*)f_in) > e_recvd;
                 if (pq.send) oks = (e_sent - ld_agent64((const u64*)f_out + 8)) < (u64)(ge.z & 0xffu);
                 else if (pq.drain) oks = e_sent == ld_agent64((const u64*)f_out + 8);
@@ -1270,11 +1270,11 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       // ================= next primitive of the collective in hand =================
       const DfxCooked& S = sh.slot[sl].st;
       const bool fold = (S.bc_pos & DFX_CTX_FOLD) != 0;
-      const Prim q = fold ? make_fold_prim(p)
+      const Prim q = fold ? make_fold_prim((int)S.kind, p)
                           : chain_drain_round(make_prim((int)S.kind, a.R, S.bc_pos & 3u, p, (S.bc_pos & DFX_CTX_DIRECT) != 0),
                                               (int)S.kind, (S.bc_pos & DFX_CTX_DIRECT) != 0, g, S.rounds);
       // fold steps wait for one of the channel's shared counters to reach (invocation + 1) x R
-      const u64* const fold_cnt = fold ? (const u64*)(fold_shared_line(S.flags_out, rank, a.R, S.nchan) + 8u * (q.fold - 1u)) : nullptr;
+      const u64* const fold_cnt = fold ? (const u64*)(fold_shared_line(S.flags_out, rank, a.R, S.nchan) + 8u * q.fwait) : nullptr;
       const u64 fold_target = ((u64)S.seq + 1u) * a.R;
       u64* const tail_out = (u64*)S.flags_out;
       u64* const tail_in = (u64*)S.flags_in;
@@ -1398,34 +1398,49 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         }
         uint32_t jmode = 0, jnseg = 0, jbytes_fold = 0;
         if (q.fold == 1 || q.fold == 2) {
-          // The addresses every rank published for this invocation (before it counted itself published, which the
-          // wait has seen for all of them): lane k looks up the rank k places down the ring.  Fold step: the send
-          // buffers, in the ring's order of combination for this rank's chunk (rank + 1 first, this rank last).
-          // Gather step: the other ranks' recv buffers, each with its own chunk.
-          const uint32_t nk = q.fold == 1 ? a.R : a.R - 1;
-          const uint32_t peer = (rank + 1 + lane) % a.R;
-          bool bad = false;
-          if (lane < nk) {
+          // The addresses every rank published for this invocation (before it counted itself published, which a
+          // wait of this invocation has seen for all of them): lane k looks up one rank.
+          //   fold step: the R send buffers in the order of combination, which begins behind this rank (all-reduce,
+          //     reduce-scatter: the ring's order for this rank's chunk) or behind the root (reduce: the chain's);
+          //     a reduce writes the root's recv buffer, whose address lane R looks up.
+          //   gather step: all-reduce: the other R-1 ranks' recv buffers, each with its own chunk; all-gather: all R
+          //     send buffers, each with its block; broadcast: the root's send buffer.
+          const int kd = (int)S.kind;
+          const uint32_t root = S.nslots;                       // (a collective in fold steps keeps its root there)
+          const bool from_send = q.fold == 1 || kd != KIND_AR;  // which published address: the send or the recv buffer
+          const uint32_t first = (q.fold == 1 && kd == KIND_RD) ? root + 1 : (kd == KIND_AR || kd == KIND_RS) ? rank + 1 : 0u;
+          uint32_t nk = a.R;
+          if (q.fold == 2) nk = kd == KIND_AR ? a.R - 1 : (kd == KIND_BC ? 1u : a.R);
+          // (a reduce in fold steps has at most 63 ranks: the root's recv buffer is looked up by the lane behind the R sources)
+          const bool want_root_recv = q.fold == 1 && kd == KIND_RD;      // one more look-up, in lane nk
+          const uint32_t peer = (want_root_recv && lane == nk) ? root : (q.fold == 2 && kd == KIND_BC) ? root : (first + lane) % a.R;
+          bool bad = want_root_recv && nk >= 64u;
+          if (lane < nk + (want_root_recv ? 1u : 0u)) {
+            const bool rd_send = from_send && !(want_root_recv && lane == nk);
             const Slot<AUX_DEVICE> line((const void*)fold_line(S.flags_out, rank, peer, S.nchan), DFX_FLAG_STRIDE);
             uint4 w = uint4{0, 0, 0, 0};
             for (uint32_t tries = 0; tries < 1024u; ++tries) {
-              w = line.ld16(q.fold == 1 ? DFX_DIRECT_OFF + 16 : DFX_DIRECT_OFF);
+              w = line.ld16(rd_send ? DFX_DIRECT_OFF + 16 : DFX_DIRECT_OFF);
               if (w.z == inv_seq + 1u) break;
               __builtin_amdgcn_s_sleep(2);
             }
-            bad = w.z != inv_seq + 1u;
+            bad = bad || w.z != inv_seq + 1u;
             const u64 base = ((u64)w.y << 32) | w.x;
-            const SliceGeom gk = slice_geometry(S, a.R, 0u, q.fold == 1 ? rank : peer);
-            sh.tab_src[posted & 1][lane] = base + (q.fold == 1 ? gk.soff : gk.doff) * gk.eb;
-            sh.tab_dst[posted & 1][lane] = (u64)S.recvbuf + gk.doff * gk.eb;
-            sh.tab_len[posted & 1][lane] = gk.bytes;
+            // the chunk this entry is about: the rank's own one in a fold step, the peer's in a gather step
+            const SliceGeom gk = slice_geometry(S, a.R, 0u, q.fold == 1 ? rank : (kd == KIND_BC ? 0u : peer));
+            if (want_root_recv && lane == nk) sh.tab_dst[posted & 1][0] = base + gk.doff * gk.eb;
+            else {
+              sh.tab_src[posted & 1][lane] = base + (rd_send ? gk.soff : gk.doff) * gk.eb;
+              if (!(want_root_recv && lane == 0)) sh.tab_dst[posted & 1][lane] = (u64)S.recvbuf + gk.doff * gk.eb;
+              sh.tab_len[posted & 1][lane] = gk.bytes;
+            }
           }
           if (__ballot(bad)) { if (lane == 0) raise_error(a, 3u, wg); stop = STOP_ABORT; have = false; continue; }
+          __builtin_amdgcn_wave_barrier();
           jmode = q.fold; jnseg = nk;
           const SliceGeom own = slice_geometry(S, a.R, 0u, rank);
-          if (q.fold == 1) { jfout = (char*)S.recvbuf + own.doff * own.eb; jbytes_fold = own.bytes; }
+          if (q.fold == 1) { jfout = (void*)(uintptr_t)sh.tab_dst[posted & 1][0]; jbytes_fold = own.bytes; }
           else jbytes_fold = (uint32_t)S.slice_elems * own.eb;      // the longest segment: a channel's share of a full chunk
-          __builtin_amdgcn_wave_barrier();
         }
         // ---- post the slice (an empty one is only a handshake: the movers just raise the counters);
         // this claims the slots: the data follows, the counters after it
@@ -1443,7 +1458,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           f.tail_out = (q.send || q.notify) ? tail_out : nullptr; f.head_in = q.recv ? tail_in + 8 : nullptr;
           f.sent_new = sent; f.recvd_new = recvd;
           f.last = last ? 1u : 0u; f.coll = coll; f.seq = inv_seq; f.nchan = inv_nchan;
-          f.add_one = (q.fold == 1 || q.fold == 2) ? (u64*)(fold_shared_line(S.flags_out, rank, a.R, S.nchan) + 8u * q.fold) : nullptr;
+          f.add_one = q.fadd ? (u64*)(fold_shared_line(S.flags_out, rank, a.R, S.nchan) + 8u * q.fadd) : nullptr;
           sh.fl[posted & 1] = f;
           lds_st(&sh.job_seq, posted + 1);
         }

@@ -55,28 +55,38 @@ struct Prim {
   // (the recv buffer is the caller's again once the completion is posted).
   bool notify, din, drain;
   bool din_send;   // the input is the previous rank's SEND buffer (first reduce step of a direct all-reduce / reduce-scatter)
-  // Fold steps of a short all-reduce (see make_fold_prim): fold = 1 the fold step, 2 the gather step, 3 the
-  // last wait; 0 = none of them.  Their wait phase looks at one of the channel's shared counters.
-  uint8_t fold;
+  // Fold steps of a short collective (see make_fold_prim): fold = 1 a fold step, 2 a gather step, 3 a last wait
+  // that moves nothing; 0 = none of them.  fwait: the channel's shared counter the wait phase looks at
+  // (0 published, 1 folded, 2 gathered); fadd: the counter the step adds to when its data is in memory (0 = none).
+  uint8_t fold, fwait, fadd;
 };
 
-// A short all-reduce in fold steps.  Every rank's buffers lie in the same HBM, so the 2R-1 dependent hops of the
-// ring (a few microseconds each, whatever the size) can be replaced by three steps that wait on all ranks at once:
-//   p = 0  fold:   when every rank has published this invocation's buffers, rank r reads chunk r out of all R send
-//                  buffers and combines them in the ring's own order, x[r+1] (op) x[r+2] (op) ... (op) x[r] -- the
-//                  same association as the reduce phase of the ring, hence the same bits -- into its recv buffer;
-//   p = 1  gather: when every rank has finished its fold step, rank r copies the other R-1 chunks out of their
-//                  owners' recv buffers;
-//   p = 2  last:   no data; when every rank has finished its gather step, nobody reads this rank's buffers any
-//                  more and the completion may be posted.
+// Short collectives in fold steps.  Every rank's buffers lie in the same HBM, so the dependent hops of a ring or
+// a chain (a few microseconds each, whatever the size) can be replaced by steps that wait on all ranks at once:
+//   fold step:   when every rank has published this invocation's buffers, a rank reads one chunk out of all R
+//                send buffers and combines them in the ring's (the chain's) own order -- the same association as
+//                the hops would give, hence the same bits;
+//   gather step: copies chunks out of other ranks' buffers into the own recv buffer;
+//   last wait:   no data; when every rank has got far enough, nobody reads this rank's buffers any more and
+//                the completion may be posted.
+// all-reduce:      fold (rank r: chunk r, x[r+1] (op) ... (op) x[r], into its recv buffer), gather (when every rank
+//                  has folded: the other R-1 chunks out of their owners' recv buffers), last wait (all gathered)
+// reduce-scatter:  fold (rank r: block r into its recv buffer), last wait (all folded: the send buffers are free)
+// reduce:          fold (rank r: chunk r of the message, x[root+1] (op) ... (op) x[root], into the ROOT's recv
+//                  buffer), last wait (all folded)
+// all-gather:      gather (all R blocks out of the send buffers), last wait (all gathered)
+// broadcast:       gather (the channel's share of the root's send buffer), last wait (all gathered)
 // Each step is a bounded wait followed by the data, like any primitive: nothing is touched before the wait has
 // succeeded, so a collective stuck in any of them is preempted like any other.
-DFX_HD Prim make_fold_prim(uint32_t p) {
+DFX_HD uint32_t fold_nprim(int kind) { return kind == KIND_AR ? 3u : 2u; }
+DFX_HD Prim make_fold_prim(int kind, uint32_t p) {
   Prim q;
   q.recv = q.send = q.notify = q.din = q.drain = q.din_send = false;
-  q.from_send = (p == 0);
-  q.to_recv = (p < 2);
-  q.fold = (uint8_t)(p + 1);
+  q.from_send = q.to_recv = false;
+  const bool reduces = (kind == KIND_AR || kind == KIND_RS || kind == KIND_RD);
+  if (p == 0) { q.fold = reduces ? 1 : 2; q.fwait = 0; q.fadd = reduces ? 1 : 2; q.from_send = true; q.to_recv = true; }
+  else if (kind == KIND_AR && p == 1) { q.fold = 2; q.fwait = 1; q.fadd = 2; q.to_recv = true; }
+  else { q.fold = 3; q.fwait = (kind == KIND_RS || kind == KIND_RD) ? 1 : 2; q.fadd = 0; }
   return q;
 }
 
@@ -92,7 +102,7 @@ DFX_HD uint64_t fold_shared_line(uint64_t own_line, uint32_t rank, uint32_t R, u
 DFX_HD Prim make_prim(int kind, uint32_t R, uint32_t bc_pos, uint32_t p, bool direct) {
   Prim q;
   q.notify = q.din = q.drain = q.din_send = false;
-  q.fold = 0;
+  q.fold = q.fwait = q.fadd = 0;
   if (R == 1) { q.recv = q.send = false; q.from_send = q.to_recv = true; return q; }   // copy
   if (kind == KIND_AR && direct) {
     const uint32_t last_reduce = R - 1;
@@ -193,7 +203,8 @@ DFX_HD DfxCooked cook_sqe(const DfxStatic& q, uint8_t* pool, uint32_t rank, uint
   if ((q.kind == KIND_BC && (q.flags & DFX_SQE_DIRECT)) || (q.flags & DFX_SQE_FOLD)) k.fifo_out = k.fifo_in = 0;
   k.slice_elems = q.slice_elems; k.rounds = q.rounds; k.seq = q.seq;
   k.nprim = (uint16_t)q.nprim; k.nchan = q.nchan;
-  k.nslots = (uint8_t)q.nslots; k.kind = q.kind; k.dtype = (uint8_t)(q.dtype | (q.op << 4));
+  k.nslots = (uint8_t)((q.flags & DFX_SQE_FOLD) ? q.root : q.nslots);   // (no slots in fold steps: the byte carries the root)
+  k.kind = q.kind; k.dtype = (uint8_t)(q.dtype | (q.op << 4));
   // place in the chain: broadcast starts at the root, reduce at the rank after it
   const uint32_t bpos = (rank + 2 * R - q.root - (q.kind == KIND_RD ? 1u : 0u)) % R;
   k.bc_pos = bpos == 0 ? 0 : (bpos == R - 1 ? 2 : 1);
@@ -214,7 +225,8 @@ DFX_HD SliceGeom slice_geometry(const DfxCooked& S, uint32_t R, uint32_t g, uint
   o.eb = (dt == DT_F32 || dt == DT_I32) ? 4u : 2u;
   const uint32_t slice_elems = S.slice_elems, vch = S.vch;
   const uint64_t count = S.count, block_elems = S.block_elems, part_elems = S.part_elems;
-  const bool ring_chunks = (kind == KIND_AR && R > 1);
+  // (a reduce in fold steps is cut into R chunks like an all-reduce: rank r combines chunk r)
+  const bool ring_chunks = R > 1 && (kind == KIND_AR || (kind == KIND_RD && (S.bc_pos & DFX_CTX_FOLD)));
   uint64_t blen = count;
   if (ring_chunks) {
     const uint64_t start = (uint64_t)cidx * block_elems;

@@ -350,8 +350,15 @@ int plan_collective(const dfx_config& cfg, int nranks, int coll_id, dfx_kind kin
   const uint64_t per16 = 16 / eb;
   // ring chunk: all-reduce cuts the message into R contiguous chunks of ceil(N/R) elements
   // rounded up to 16 bytes; the other kinds move blocks of `count`
+  // Fold steps (see dfx_config.fold_max_bytes): every kind whose largest per-rank buffer is below the limit; the blocks
+  // of an all-gather / reduce-scatter must be 16-byte multiples (they are read with 16-byte vectors where they lie).
+  const uint64_t largest_bytes = (kind == DFX_ALLGATHER || kind == DFX_REDUCESCATTER) ? count * eb * R : count * eb;
+  const bool blocks_ok = !(kind == DFX_ALLGATHER || kind == DFX_REDUCESCATTER) || (count * eb) % 16 == 0;
+  // (a reduce's fold step has one look-up more than it has ranks, one per lane of the scheduler wavefront: at most 63 ranks)
+  const bool fold = R > 1 && cfg.fold_max_bytes && largest_bytes < cfg.fold_max_bytes && blocks_ok && !(kind == DFX_REDUCE && R > 63);
   uint64_t block = count;
-  if (kind == DFX_ALLREDUCE && R > 1) block = round_up(ceil_div(count, R), per16);
+  // (a reduce in fold steps is cut into chunks like an all-reduce: rank r combines chunk r into the root's buffer)
+  if ((kind == DFX_ALLREDUCE || (kind == DFX_REDUCE && fold)) && R > 1) block = round_up(ceil_div(count, R), per16);
   const uint64_t block_bytes = block * eb;
   uint64_t C = ceil_div(std::max<uint64_t>(block_bytes, 1), cfg.chan_min_bytes);
   C = std::min<uint64_t>(std::max<uint64_t>(C, 1), cfg.max_channels);
@@ -359,9 +366,9 @@ int plan_collective(const dfx_config& cfg, int nranks, int coll_id, dfx_kind kin
   C = std::max<uint64_t>(1, ceil_div(block, part));   // drop channels that would be empty
   // direct steps of a broadcast: every rank writes its recv buffer only and the next one reads it there
   // (measured break-even points: the rings at direct_min_bytes, a reduce-scatter at twice that, the chains at a quarter)
-  const bool bc_direct = kind == DFX_BROADCAST && R > 1 && cfg.direct && count * eb >= cfg.direct_min_bytes / 4;
+  const bool bc_direct = kind == DFX_BROADCAST && R > 1 && !fold && cfg.direct && count * eb >= cfg.direct_min_bytes / 4;
   uint64_t slice_cap = cfg.slot_bytes;
-  if (rooted && R > 1) {
+  if (rooted && R > 1 && !fold) {
     // A chain's last rank starts R-1 slices after its first, so a chain wants shorter slices than a
     // ring, where all ranks start at once: measured best (R = 8, 2 - 256 MiB) are about 2R slices per
     // channel share for the broadcast and 4R for the reduce, of no less than 32 KiB; the reduce, whose
@@ -373,8 +380,7 @@ int plan_collective(const dfx_config& cfg, int nranks, int coll_id, dfx_kind kin
     const uint64_t want = round_up(part * eb / ((kind == DFX_BROADCAST ? 2 : 4) * R), 16);
     slice_cap = std::min(std::max(want, lo), hi);
   }
-  // fold steps of a short all-reduce: no slots, one slice per channel share whatever its length
-  const bool fold = kind == DFX_ALLREDUCE && R > 1 && cfg.fold_max_bytes && count * eb < cfg.fold_max_bytes;
+  // fold steps: no slots, one slice per channel share whatever its length
   if (fold) slice_cap = 1ull << 31;
   uint64_t slot_bytes = std::min<uint64_t>(slice_cap, round_up(part * eb, 16));
   const uint64_t slice_elems = slot_bytes / eb;
@@ -403,7 +409,7 @@ int plan_collective(const dfx_config& cfg, int nranks, int coll_id, dfx_kind kin
   if (R == 1) t.nprim = 1;
   else if (fold) {
     t.flags |= DFX_SQE_DIRECT | DFX_SQE_FOLD;   // (buffers are published as for the direct steps)
-    t.nprim = 3;                                // fold, gather, last wait
+    t.nprim = fold_nprim((int)kind);            // all-reduce: fold, gather, last wait; the others: one step and the last wait
   }
   else if (kind == DFX_ALLREDUCE) {
     // direct gather steps (one more step: the drain) where the message is long enough to gain from them
@@ -1121,21 +1127,29 @@ int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t
       uint64_t sent = 0, recvd = 0, steps = 0;
       for (;;) {
         if (fold) {
-          // fold steps: chunk r out of every send buffer into the own recv buffer, then every other chunk out of
-          // its owner's recv buffer
+          // fold steps: the same look-ups as the scheduler makes when it posts a fold or a gather step
           if (g != 0 || S.rounds != 1) return fail("rank %u channel %u: a collective in fold steps has one slice per share", r, v);
-          for (uint32_t k = 0; k < R && p < 2; ++k) {
-            const uint32_t peer = (r + 1 + k) % R;
-            if (p == 1 && peer == r) continue;
-            const SliceGeom gk = slice_geometry(S, R, 0u, p == 0 ? r : peer);
-            if ((uint64_t)gk.bytes > (uint64_t)S.slice_elems * gk.eb) return fail("rank %u channel %u: a segment longer than the share", r, v);
-            if (!gk.bytes) continue;
-            const uint64_t rd = (p == 0 ? gk.soff : gk.doff) * gk.eb, lim = p == 0 ? send_bytes : recv_bytes;
-            if (rd + gk.bytes > lim) return fail("rank %u channel %u fold step %u: read of rank %u's buffer %llu+%u of %llu", r, v, p, peer, (unsigned long long)rd, gk.bytes, (unsigned long long)lim);
-            if (p == 0 && k + 1 < R) continue;       // (the fold step writes once, after the last source)
-            const uint64_t wr = gk.doff * gk.eb;
-            if (wr + gk.bytes > recv_bytes) return fail("rank %u channel %u fold step %u: recv buffer write %llu+%u of %llu", r, v, p, (unsigned long long)wr, gk.bytes, (unsigned long long)recv_bytes);
-            written[r].push_back({wr, wr + gk.bytes});
+          const Prim fq = make_fold_prim(kind, p);
+          const uint32_t rt = S.nslots;      // the root
+          if (fq.fold == 1 || fq.fold == 2) {
+            const bool from_send = fq.fold == 1 || kind != KIND_AR;
+            const uint32_t first = (fq.fold == 1 && kind == KIND_RD) ? rt + 1 : (kind == KIND_AR || kind == KIND_RS) ? r + 1 : 0u;
+            uint32_t nk = R;
+            if (fq.fold == 2) nk = kind == KIND_AR ? R - 1 : (kind == KIND_BC ? 1u : R);
+            for (uint32_t k = 0; k < nk; ++k) {
+              const uint32_t peer = (fq.fold == 2 && kind == KIND_BC) ? rt : (first + k) % R;
+              const SliceGeom gk = slice_geometry(S, R, 0u, fq.fold == 1 ? r : (kind == KIND_BC ? 0u : peer));
+              if ((uint64_t)gk.bytes > (uint64_t)S.slice_elems * gk.eb) return fail("rank %u channel %u: a segment longer than the share", r, v);
+              if (!gk.bytes) continue;
+              const uint64_t rd = (from_send ? gk.soff : gk.doff) * gk.eb, lim = from_send ? send_bytes : recv_bytes;
+              if (rd + gk.bytes > lim) return fail("rank %u channel %u fold step %u: read of rank %u's buffer %llu+%u of %llu", r, v, p, peer, (unsigned long long)rd, gk.bytes, (unsigned long long)lim);
+              if ((kind == KIND_AG || kind == KIND_RS) && (rd & 15u)) return fail("rank %u channel %u fold step %u: a 16-byte read at offset %llu", r, v, p, (unsigned long long)rd);
+              if (fq.fold == 1 && k + 1 < nk) continue;       // (a fold step writes once, after the last source)
+              const uint64_t wr = gk.doff * gk.eb;
+              if (wr + gk.bytes > recv_bytes) return fail("rank %u channel %u fold step %u: recv buffer write %llu+%u of %llu", r, v, p, (unsigned long long)wr, gk.bytes, (unsigned long long)recv_bytes);
+              // (the fold step of a reduce writes the root's recv buffer)
+              written[(fq.fold == 1 && kind == KIND_RD) ? rt : r].push_back({wr, wr + gk.bytes});
+            }
           }
           const SeqPos nx = next_position(kind, R, r, cfg.window, S.rounds, S.nprim, g, p, cidx);
           g = nx.g; p = nx.p; cidx = nx.cidx;

@@ -22,6 +22,7 @@ IO = {
     "recv_reduce_copy_notify": (2, 1), "direct_copy_notify": (1, 1), "direct_copy": (1, 1),
     # fold steps (R ranks): chunk r out of all R send buffers into the recv buffer; the other R-1 chunks copied
     "fold_all": lambda R: (R, 1), "gather_all": lambda R: (R - 1, R - 1), "last_wait": (0, 0),
+    "fold_root": lambda R: (R, 1), "gather_pub": lambda R: (R, R), "last_wait_red": (0, 0),
 }
 
 

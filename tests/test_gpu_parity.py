@@ -101,10 +101,13 @@ def test_allreduce_rank_counts(R, fold):
     _run(_one(wi.AR, wi.F32, 50000 + R, R, seed=R), max_channels=8, fold_max_bytes=fold)
 
 
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
 @pytest.mark.parametrize("kind", [wi.AG, wi.RS, wi.BC])
 @pytest.mark.parametrize("dtype,count", [(wi.F32, 4096), (wi.F16, 1001), (wi.I32, 3), (wi.BF16, 250000)])
-def test_other_collectives(kind, dtype, count):
-    _run(_one(kind, dtype, count, 8, root=5, seed=kind * 10 + dtype))
+def test_other_collectives(kind, dtype, count, fold):
+    """(In fold steps where they apply: all-gather / reduce-scatter blocks that are no 16-byte multiples, the
+    second and third case, stay rings.)"""
+    _run(_one(kind, dtype, count, 8, root=5, seed=kind * 10 + dtype), fold_max_bytes=fold)
 
 
 def test_zero_count_collective_completes():
@@ -174,13 +177,16 @@ def test_repeated_invocations_and_changing_buffers(fold):
 @pytest.mark.parametrize("dtype", [wi.F32, wi.BF16, wi.F16, wi.I32])
 @pytest.mark.parametrize("count", [1, 4099, 1 << 20])
 def test_reduce_to_every_root_R8(dtype, count):
-    """The reduce collective (Sec. 4.1): chain ending at the root; only the root's recv buffer changes."""
+    """The reduce collective (Sec. 4.1): chain ending at the root, and in fold steps (every rank combines one chunk
+    into the root's buffer, in the chain's order); only the root's recv buffer changes."""
     for root in (0, 3, 7):
+        _run(_one(wi.RD, dtype, count, 8, root=root, seed=count + root), fold_max_bytes=0)
         _run(_one(wi.RD, dtype, count, 8, root=root, seed=count + root))
 
 
 @pytest.mark.parametrize("R", [1, 2, 3, 5, 16])
 def test_reduce_other_rank_counts(R):
+    _run(_one(wi.RD, wi.F32, 30000 + R, R, root=R - 1, seed=R), max_channels=8, fold_max_bytes=0)
     _run(_one(wi.RD, wi.F32, 30000 + R, R, root=R - 1, seed=R), max_channels=8)
 
 
@@ -191,6 +197,8 @@ def test_other_reducing_functions(kind, dtype, op):
     """Product / maximum / minimum as the reducing function (Sec. 4.1), bit-exact against the oracle's fold,
     at a ragged size that exercises the vector loop, its predicated tail and the element-wise path."""
     for count in (7, 100003):
+        _run(_one(kind, dtype, count, 8, root=5, seed=op * 10 + kind, op=op), fold_max_bytes=0)
+    for count in (8, 100000):      # (reduce-scatter blocks of 16-byte multiples: fold steps)
         _run(_one(kind, dtype, count, 8, root=5, seed=op * 10 + kind, op=op))
 
 
@@ -237,12 +245,18 @@ def _mixed_workload(seed, n_colls=40, R=8):
     return wi.Workload(f"mixed_seed{seed}", R, colls, orders, delays_us=delays, seed=seed, cfg=44)
 
 
+@pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
 @pytest.mark.parametrize("seed", [1, 2, 3])
-def test_random_mix_of_kinds_ops_and_orders(seed):
+def test_random_mix_of_kinds_ops_and_orders(seed, fold):
     """Forty collectives of random kind (reduce included), dtype, reducing function, ragged size and root,
     every vrank submitting from its own thread in its own order with small delays; bit-exact against the
     oracle's closed forms.  Product runs on N(0,1) values: eight factors neither overflow nor vanish."""
-    _run(_mixed_workload(seed), mode="threads", timeout_s=60.0)
+    w = _mixed_workload(seed)
+    if fold:    # all-gather / reduce-scatter blocks rounded to 16-byte multiples, so that they take the fold steps too
+        colls = [wi.CollSpec(c.coll_id, c.kind, c.dtype, max(8, c.count // 8 * 8) if c.kind in (wi.AG, wi.RS) else c.count, c.root, c.op)
+                 for c in w.colls]
+        w = wi.Workload(w.name + "_aligned", w.R, colls, w.orders, delays_us=w.delays_us, seed=seed, cfg=44)
+    _run(w, mode="threads", timeout_s=60.0, fold_max_bytes=fold)
 
 
 @pytest.mark.parametrize("fold", [0, 64 << 20], ids=["ring", "fold"])
@@ -458,7 +472,7 @@ def test_chain_slice_lengths():
     direct broadcast whose slices are twice the slot size and a reduce with the smallest slices stay bit-exact."""
     from paper_2303_06324_amd import harness as gh
     import paper_2303_06324_amd as dfx
-    ctx = dfx.Context(8, gh.make_config())
+    ctx = dfx.Context(8, gh.make_config(fold_max_bytes=0))     # (the chains proper: no fold steps)
     try:
         cases = [(dfx.BROADCAST, 256 << 10, 16 << 10, 1),          # below the chains' direct threshold (direct_min_bytes / 4): no drain
                  (dfx.BROADCAST, 1 << 20, 32 << 10, 2),            # one 32 KiB slice per channel and the drain
@@ -478,8 +492,8 @@ def test_chain_slice_lengths():
     finally:
         assert ctx.finalize() == dfx.OK
     _run(_one(wi.BC, wi.F32, 1 << 19, 8, root=3, seed=5), slot_bytes=16 << 10, max_channels=2, **DIRECT)
-    _run(_one(wi.BC, wi.BF16, (1 << 20) + 3, 5, root=1, seed=6), slot_bytes=16 << 10, max_channels=2, direct=0)
-    _run(_one(wi.RD, wi.F32, (1 << 19) + 77, 8, root=6, seed=7, op=wi.MAX), slot_bytes=4 << 10, max_channels=2)
+    _run(_one(wi.BC, wi.BF16, (1 << 20) + 3, 5, root=1, seed=6), slot_bytes=16 << 10, max_channels=2, direct=0, fold_max_bytes=0)
+    _run(_one(wi.RD, wi.F32, (1 << 19) + 77, 8, root=6, seed=7, op=wi.MAX), slot_bytes=4 << 10, max_channels=2, fold_max_bytes=0)
 
 
 @pytest.mark.parametrize("dtype,count,op", [(wi.F32, 4096, wi.SUM), (wi.BF16, 250000, wi.SUM), (wi.I32, 4, wi.MIN),
@@ -535,3 +549,30 @@ def test_fold_steps_under_forced_preemption_and_disorder():
     assert sum(s["preemptions"] for s in stats) > 100
     _run(wi.config3(n_buckets=8, bucket_bytes=1 << 20, seed=62), max_channels=2, chan_spread=0,
          spin_init=1, spin_min=1, spin_max=1, spin_boost=1)
+
+
+@pytest.mark.parametrize("kind", [wi.AG, wi.RS, wi.BC, wi.RD])
+def test_fold_steps_of_the_other_kinds(kind):
+    """All-gather, reduce-scatter, broadcast and reduce in fold steps: dtypes, reducing functions, roots, counts
+    from one element to several channels' worth, 2 to 64 ranks."""
+    for dtype, count, op in ((wi.F32, 4, wi.SUM), (wi.BF16, 8, wi.MAX), (wi.F16, 40008, wi.PROD), (wi.I32, 262148, wi.MIN), (wi.F32, 70004, wi.SUM)):
+        for R, root in ((8, 5), (3, 0)):
+            _run(_one(kind, dtype, count, R, root=root, seed=count + R, op=op), fold_max_bytes=64 << 20)
+    if kind in (wi.BC, wi.RD):     # ragged counts: sub-vector tails, short and empty last chunks
+        for count in (1, 7, 100003):
+            _run(_one(kind, wi.BF16, count, 8, root=7, seed=count), fold_max_bytes=64 << 20)
+    for R in (2, 9, 33, 64):
+        cm = max(1, min(8, 256 // R))
+        _run(_one(kind, wi.F32, 4000 + 4 * R, R, root=R - 1, seed=R), max_channels=cm, fold_max_bytes=64 << 20)
+
+
+def test_fold_steps_of_every_kind_under_forced_preemption_and_disorder():
+    """A random mix of all kinds in fold steps, one shared queue per rank, the smallest thresholds, every rank its
+    own order and delays: every wait is abandoned many times; the values stay the oracle's."""
+    w = _mixed_workload(23, n_colls=32)
+    colls = [wi.CollSpec(c.coll_id, c.kind, c.dtype, max(8, c.count // 8 * 8) if c.kind in (wi.AG, wi.RS) else c.count, c.root, c.op)
+             for c in w.colls]
+    w = wi.Workload(w.name + "_aligned", w.R, colls, w.orders, delays_us=w.delays_us, seed=23, cfg=44)
+    stats = _run(w, mode="threads", timeout_s=60.0, max_channels=2, chan_spread=0, scan_min=0,
+                 spin_init=1, spin_min=1, spin_max=1, spin_boost=1)
+    assert sum(s["preemptions"] for s in stats) > 100

@@ -183,12 +183,14 @@ def test_priority_ordering_decides_who_completes_first():
 
 
 def test_priority_ordering_lets_a_late_urgent_collective_overtake():
-    """Seven all-reduces are under way when an eighth, more urgent one is submitted half a millisecond later: under
+    """Seven all-reduces (milliseconds each) are under way when an eighth, more urgent one is submitted 0.3 ms later: under
     priority ordering it overtakes those queued and begun before it; under FIFO ordering it completes last."""
-    fifo = _completion_order(0, None, nbytes=16 << 20, late_last_ms=0.5)       # (16 MiB on one channel: milliseconds each)
+    # (rings: cut into 256 KiB slices, so that the urgent one gets the movers slice by slice; in fold steps a step of a
+    # collective on ONE channel is a single job of megabytes, and what is posted is not taken back)
+    fifo = _completion_order(0, None, late_last_ms=0.3, fold_max_bytes=0)
     assert fifo[-1] == 7, fifo
-    prio = _completion_order(1, list(range(8)), nbytes=16 << 20, late_last_ms=0.5)
-    assert prio.index(7) <= 2, prio
+    prio = _completion_order(1, list(range(8)), late_last_ms=0.3, fold_max_bytes=0)
+    assert prio.index(7) <= 1, prio
 
 
 def test_sq_backpressure_and_poll_interface():

@@ -523,14 +523,15 @@ def test_fold_steps_without_preemption_still_deadlock_on_opposite_orders():
 @pytest.mark.parametrize("var", [dict(), dict(lookahead=2, scan=True, focus=1, direct=True)])
 @pytest.mark.parametrize("seed", range(4))
 def test_fold_steps_values_and_completion_order(var, seed):
-    """Mixed kinds on three ranks (the all-reduces in fold steps), random orders, random interleavings: the final
+    """All five kinds on three ranks in fold steps, random orders, random interleavings: the final
     buffers are the data oracle's -- the fold step's order of combination is the ring's -- and no rank posts an
     all-reduce's completion before every rank has finished its gather step (the recv buffer, which the others
     read, is the caller's again after the completion)."""
     g = np.random.default_rng(seed)
     R = 3
     colls = [wi.CollSpec(0, wi.AR, wi.F32, 50), wi.CollSpec(1, wi.AG, wi.F16, 12), wi.CollSpec(2, wi.AR, wi.BF16, 33),
-             wi.CollSpec(3, wi.BC, wi.BF16, 40, root=2), wi.CollSpec(4, wi.AR, wi.I32, 7)]
+             wi.CollSpec(3, wi.BC, wi.BF16, 40, root=2), wi.CollSpec(4, wi.AR, wi.I32, 7), wi.CollSpec(5, wi.RS, wi.F32, 16),
+             wi.CollSpec(6, wi.RD, wi.F16, 41, root=1)]
     orders = [list(map(int, g.permutation(len(colls)))) for _ in range(R)]
     w = wi.Workload("fold", R, colls, orders, seed=seed, cfg=94)
     S = _system(w, sm.Policy(spin_init=2, spin_max=4, boost=2, K=2, slice_elems=8, fold=True, **var))
@@ -544,13 +545,35 @@ def test_fold_steps_values_and_completion_order(var, seed):
         else:
             S.daemons[a].tick()
         for d in S.daemons:
-            for c, _ in d.cq:
-                if colls[c].kind == wi.AR:      # (every collective is invoked once here)
-                    assert S.foldcnt[c][2] >= R and S.foldcnt[c][1] >= R
+            for c, _ in d.cq:                   # (every collective is invoked once here)
+                k = colls[c].kind
+                assert S.foldcnt[c][0] >= R
+                if k in (wi.AR, wi.RS, wi.RD):
+                    assert S.foldcnt[c][1] >= R     # every rank has folded: nobody reads a send buffer any more
+                if k in (wi.AR, wi.AG, wi.BC):
+                    assert S.foldcnt[c][2] >= R     # every rank has gathered
         ticks += 1
         assert ticks < 3_000_000
     assert S.total_cqes() == R * len(colls)
     _check_data(S, w)
+
+
+@pytest.mark.parametrize("kinds", [(sm.RS, sm.AG), (sm.BC, sm.RD)])
+def test_fold_steps_of_the_other_kinds_exhaustive_interleavings_tiny(kinds):
+    """Two collectives of the other kinds in fold steps, issued in opposite orders on two ranks: no reachable state
+    deadlocks and all end with the four CQEs."""
+    colls = [wi.CollSpec(0, kinds[0], wi.F32, 8, root=1), wi.CollSpec(1, kinds[1], wi.F32, 8, root=0)]
+    w = wi.Workload("fold2", 2, colls, [[0, 1], [1, 0]], seed=1, cfg=95)
+    for var in (dict(), dict(lookahead=2, scan=True, focus=1)):
+        S0 = _system(w, sm.Policy(spin_init=2, spin_min=1, spin_max=2, boost=2, K=2, slice_elems=4, fold=True, **var), data=False)
+        seen = sm.explore(S0, max_states=600_000)
+        assert len(seen) > 20
+        keys = list(seen)
+        for k in keys[::1 if len(keys) < 1000 else 97]:
+            T = seen[k].clone()
+            assert not sm.is_deadlocked(T)
+            sm.run_round_robin(T, max_ticks=50_000)
+            assert T.total_cqes() == 4
 
 
 def test_fold_programs_move_fewer_blocks_than_the_ring():
