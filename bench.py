@@ -42,9 +42,10 @@ def moved_bytes(msg_bytes: int, nranks: int) -> int:
 
 
 def fold_bytes(msg_bytes: int, nranks: int) -> int:
-    """What an all-reduce in fold steps (the default below 2 MiB per rank) moves: rank r reads chunk r out of all R
-    send buffers and writes it once, then reads and writes the other R-1 chunks: (3R-1)/R * M per rank."""
-    return (3 * nranks - 1) * msg_bytes
+    """What an all-reduce in fold steps (the default below 64 MiB per rank) moves: rank r reads chunk r out of all R
+    send buffers and writes the result into all R recv buffers: 2 * M per rank, every input read once and every
+    output written once."""
+    return 2 * nranks * msg_bytes
 
 
 def cpu_baseline(sends, min_seconds: float = 10.0, max_reps: int = 40):
@@ -234,8 +235,8 @@ def size_sweep(iters: int = 10):
             nprim = ctx.coll_info(0)["nprim"]
         finally:
             ctx.finalize()
-        path = {3: "fold steps", 2 * R: "ring, direct steps"}.get(nprim, "ring through slots")
-        nb = {3: fold_bytes, 2 * R: moved_bytes}.get(nprim, algorithmic_bytes)(nbytes, R)     # what the path taken moves
+        path = {2: "fold steps", 2 * R: "ring, direct steps"}.get(nprim, "ring through slots")
+        nb = {2: fold_bytes, 2 * R: moved_bytes}.get(nprim, algorithmic_bytes)(nbytes, R)     # what the path taken moves
         rows.append({"bytes": nbytes, "us": round(best * 1e6, 1), "channels": nchan,
                      "algbw_GBs": round(nbytes / best / 1e9, 2),
                      "busbw_GBs": round(nbytes / best * 2 * (R - 1) / R / 1e9, 2),
@@ -572,7 +573,7 @@ def main():
     if fold_ms is not None:
         out["fold_steps_same_workload"] = {
             "note": "the same all-reduce in fold steps (library default below 64 MiB per rank; here forced): resident daemon, "
-                    "submit -> last CQE, best of 6; moves (3R-1) x M instead of (5R-5) x M and uses no FIFO slots",
+                    "submit -> last CQE, best of 6; moves 2R x M (every input read once, every output written once) instead of (5R-5) x M and uses no FIFO slots",
             "ms": round(fold_ms, 4), "busbw_GBs": round(M / (fold_ms * 1e-3) / 1e9 * 2 * (R - 1) / R, 2),
             "bytes_moved": fold_bytes(M, R), "hbm_frac": round(fold_bytes(M, R) / (fold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     del send, recv

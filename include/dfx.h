@@ -140,11 +140,11 @@ typedef struct {
   uint32_t fold_max_bytes; /* default 64 MiB: an all-reduce of fewer bytes per rank runs in fold steps instead of ring steps.
                               The 2R-1 ring steps depend on one another and cost a few microseconds each whatever the
                               size, and a short message gives a channel one slice, so nothing hides them; with all
-                              buffers in one HBM three steps that wait on all ranks at once do the same work: (1) when
+                              buffers in one HBM two steps that wait on all ranks at once do the same work: (1) when
                               every rank has submitted, rank r combines chunk r out of all R send buffers in the ring's
-                              own order (x[r+1] (op) ... (op) x[r]: same association, same bits) into its recv buffer;
-                              (2) when every rank has done so, it copies the other chunks out of their owners' recv
-                              buffers; (3) when every rank has copied, it posts the completion.  Each step is a bounded
+                              own order (x[r+1] (op) ... (op) x[r]: same association, same bits) and writes the result
+                              into chunk r of all R recv buffers; (2) when every rank has done so, it posts the
+                              completion (every input read once, every output written once).  Each step is a bounded
                               wait (Sec. 4.2) followed by the data, preempted like any primitive.  From this size on the
                               ring through the connectors' FIFOs keeps its movers busy and is what runs.  0 = off */
 } dfx_config;

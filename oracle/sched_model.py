@@ -63,13 +63,14 @@ Two variations of Alg. 1 can be switched on, to ask whether they keep its livene
     pass it ends with the entry in hand: every rank ranks the collectives alike, so the
     ranks settle on the same few of them (the coalescing of choices that Sec. 4.3 aims at).
   * `fold = True`: collectives run in steps that each wait on ALL ranks (see below for the kinds other than the
-    all-reduce); an all-reduce runs in three steps that each wait on ALL ranks instead of 2R-1 steps that
-    each wait on the neighbour (every rank's buffers are readable by every other): "fold_all" waits until
-    every rank has fetched (published) the invocation, then rank r combines chunk r out of all R send buffers
-    in the ring's order x[r+1] (op) ... (op) x[r] into its recv buffer; "gather_all" waits until every rank
-    has done so and copies the other chunks out of their owners' recv buffers; "last_wait" waits until every
-    rank has copied and moves nothing.  Three shared counters per collective (published / folded / gathered)
-    carry the waits; each step is still poll-then-move, so a stuck one is preempted like any primitive.
+    all-reduce); an all-reduce runs in two steps that each wait on ALL ranks instead of 2R-1 steps that
+    each wait on the neighbour (every rank's buffers are readable and writable by every other): "fold_scatter"
+    waits until every rank has fetched (published) the invocation, then rank r combines chunk r out of all R
+    send buffers in the ring's order x[r+1] (op) ... (op) x[r] and writes the result into chunk r of ALL R recv
+    buffers; "last_wait_red" waits until every rank has done so (then every chunk of the own recv buffer has
+    arrived and nobody reads the own send buffer any more) and moves nothing.  Shared counters per collective
+    (published / folded / gathered) carry the waits; each step is still poll-then-move, so a stuck one is
+    preempted like any primitive.
     Reduce-scatter: "fold_all" (block r into the own recv buffer), "last_wait_red" (every rank has folded: the
     send buffers are free).  Reduce: "fold_root" (rank r combines chunk r of the message in the chain's order
     x[root+1] (op) ... (op) x[root] into the ROOT's recv buffer), "last_wait_red".  All-gather and broadcast:
@@ -119,7 +120,7 @@ PRIMS = {
     # fold steps of an all-reduce (Policy.fold): send side 4 / 5 / 6 = wait until every rank has published /
     # folded / gathered this invocation (a shared counter reaches (invocation + 1) x R)
     "fold_all": (False, 4),
-    "gather_all": (False, 5),
+    "fold_scatter": (False, 4),     # all-reduce: chunk r combined and written into every rank's recv buffer
     "last_wait": (False, 6),
     "fold_root": (False, 4),        # reduce: chunk r into the root's recv buffer
     "gather_pub": (False, 4),       # all-gather, broadcast: copies out of send buffers once everybody has published
@@ -143,7 +144,7 @@ class Policy:
     scan: bool = False            # a pass visits only the entries whose wait conditions hold at its start
     focus: int = 0                # with scan: furthest-along entries first, and the pass ends after this many slices
     direct: bool = False          # steps that read the previous rank's recv / send buffer instead of a slot (notify / drain)
-    fold: bool = False            # all-reduces in three steps that wait on all ranks (fold_all, gather_all, last_wait)
+    fold: bool = False            # collectives in steps that wait on all ranks (all-reduce: fold_scatter, last_wait_red)
     priority_order: bool = False  # priority-based ordering: fetch before every pass, queue sorted by Coll.priority, priority ranks first
 
 
@@ -166,7 +167,7 @@ def program(kind: int, R: int, r: int, root: int, blocks: List[Tuple[int, int]],
     b = lambda j: blocks[j % R]
     d = lambda j: recv_blocks[j % R]
     if kind == AR and fold:
-        return [("fold_all", b(r), d(r)), ("gather_all", none, none), ("last_wait", none, none)]
+        return [("fold_scatter", b(r), d(r)), ("last_wait_red", none, none)]
     if kind == RS and fold:
         return [("fold_all", b(r), recv_blocks[0]), ("last_wait_red", none, none)]
     if kind == RD and fold:
@@ -605,22 +606,21 @@ class System:
         x = None
         if name in ("drain", "last_wait", "last_wait_red"):
             return
-        if name in ("fold_all", "fold_root", "gather_all", "gather_pub"):
+        if name in ("fold_all", "fold_scatter", "fold_root", "gather_pub"):
             # whole chunks (one slice per share), read out of the other ranks' buffers in place
             if self.with_data:
                 R = self.R
-                if name == "fold_all":        # all-reduce: chunk r; reduce-scatter: block r; the ring's order, which begins behind r
+                if name == "fold_all":        # reduce-scatter: block r; the ring's order, which begins behind r
                     (slo, shi), (dlo, dhi) = sblk, dblk
                     self.recvs[ci][r][dlo:dhi] = rd.fold_rotated([s[slo:shi] for s in self.sends[ci]], r + 1, c.dtype)
+                elif name == "fold_scatter":  # all-reduce: chunk r in the same order, into every rank's recv buffer
+                    (slo, shi), (dlo, dhi) = sblk, dblk
+                    x = rd.fold_rotated([s[slo:shi] for s in self.sends[ci]], r + 1, c.dtype)
+                    for j in range(R):
+                        self.recvs[ci][j][dlo:dhi] = x
                 elif name == "fold_root":     # reduce: chunk r of the message, the chain's order, into the root's buffer
                     lo, hi = rd.chunk_bounds(c.count, R, rd.ELEM_BYTES[c.dtype])[r]
                     self.recvs[ci][c.root][lo:hi] = rd.fold_rotated([s[lo:hi] for s in self.sends[ci]], c.root + 1, c.dtype)
-                elif name == "gather_all":    # all-reduce: the other chunks out of their owners' recv buffers
-                    cb = layout(c, R)[0]
-                    for j in range(R):
-                        if j != r:
-                            lo, hi = cb[j]
-                            self.recvs[ci][r][lo:hi] = self.recvs[ci][j][lo:hi]
                 elif c.kind == AG:            # all-gather: block j out of rank j's send buffer
                     for j in range(R):
                         self.recvs[ci][r][j * c.count:(j + 1) * c.count] = self.sends[ci][j][:c.count]

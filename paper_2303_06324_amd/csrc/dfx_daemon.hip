@@ -487,7 +487,7 @@ __device__ __forceinline__ void run_prim(int dtype, const void* fin, const char*
 }
 
 // ------------------------------------------------------------------------------------------
-// Fold steps of a short all-reduce (make_fold_prim): the two data movers
+// Fold steps (make_fold_prim): the two data movers
 // ------------------------------------------------------------------------------------------
 // a buffer resource over memory whose address every lane holds alike (it came out of LDS)
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t uniform_rsrc(u64 addr, uint32_t bytes) {
@@ -501,12 +501,13 @@ __device__ __forceinline__ uint4 rs_ld16(__amdgpu_buffer_rsrc_t r, uint32_t off)
 constexpr int FOLD_SRC = 8;    // sources read together
 constexpr int FOLD_U = 2;      // vectors per thread and source in flight
 
-// dst[i] = src[0][i] (op) src[1][i] (op) ... (op) src[nsrc-1][i], left to right: the table lists the ranks in
-// the ring's order of combination.  Sources are other ranks' send buffers: device-coherent loads; the result
-// is read by the other ranks soon: device-coherent stores.
+// dst[d][i] = src[0][i] (op) src[1][i] (op) ... (op) src[nsrc-1][i], left to right, for every destination d: the
+// source table lists the ranks in the ring's order of combination.  Sources are other ranks' send buffers:
+// device-coherent loads; the destinations are recv buffers of this and of other ranks, whose workgroups post the
+// completion: device-coherent stores, which are in memory when the step counts itself done.
 template <int DT, int NTH>
-__device__ __forceinline__ void fold_slice(const u64* src_tab, uint32_t nsrc, void* dst_p, uint32_t bytes, uint32_t tid, int op) {
-  const Slot<AUX_DEVICE> dst(dst_p, bytes);
+__device__ __forceinline__ void fold_slice(const u64* src_tab, uint32_t nsrc, const u64* dst_tab, uint32_t ndst, uint32_t bytes,
+                                           uint32_t tid, int op) {
   const uint32_t nvec = bytes >> 4;
   for (uint32_t i = tid; i < nvec; i += FOLD_U * NTH) {
     uint4 acc[FOLD_U];
@@ -530,8 +531,12 @@ __device__ __forceinline__ void fold_slice(const u64* src_tab, uint32_t nsrc, vo
         }
       }
     }
+    for (uint32_t d = 0; d < ndst; ++d) {
+      const __amdgpu_buffer_rsrc_t r = uniform_rsrc(dst_tab[d], bytes);
 #pragma unroll
-    for (int u = 0; u < FOLD_U; ++u) if (i + u * NTH < nvec) dst.st16((i + u * NTH) << 4, acc[u]);
+      for (int u = 0; u < FOLD_U; ++u)
+        if (i + u * NTH < nvec) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, acc[u]), r, (int)((i + u * NTH) << 4), 0, AUX_DEVICE);
+    }
   }
   // the sub-vector tail of a message whose length is no multiple of 16 bytes
   const uint32_t done = nvec << 4;
@@ -544,24 +549,28 @@ __device__ __forceinline__ void fold_slice(const u64* src_tab, uint32_t nsrc, vo
         const uint32_t x = EB == 4 ? src.ld4(o) : (uint32_t)src.ld2(o);
         v = k == 0 ? x : (EB == 4 ? op_word<DT>(v, x, op) : (uint32_t)op_half<DT>((uint16_t)v, (uint16_t)x, op));
       }
-      if (EB == 4) dst.st4(o, v); else dst.st2(o, (uint16_t)v);
+      for (uint32_t d = 0; d < ndst; ++d) {
+        const Slot<AUX_DEVICE> dst((void*)(uintptr_t)dst_tab[d], bytes);
+        if (EB == 4) dst.st4(o, v); else dst.st2(o, (uint16_t)v);
+      }
     }
   }
 }
 
 template <int NTH>
-__device__ __forceinline__ void fold_dispatch(int dtype, const u64* src_tab, uint32_t nsrc, void* dst, uint32_t bytes, uint32_t tid) {
+__device__ __forceinline__ void fold_dispatch(int dtype, const u64* src_tab, uint32_t nsrc, const u64* dst_tab, uint32_t ndst,
+                                              uint32_t bytes, uint32_t tid) {
   const int op = dtype >> 4;
   switch (dtype & 15) {
-    case DT_F32: fold_slice<DT_F32, NTH>(src_tab, nsrc, dst, bytes, tid, op); break;
-    case DT_BF16: fold_slice<DT_BF16, NTH>(src_tab, nsrc, dst, bytes, tid, op); break;
-    case DT_F16: fold_slice<DT_F16, NTH>(src_tab, nsrc, dst, bytes, tid, op); break;
-    default: fold_slice<DT_I32, NTH>(src_tab, nsrc, dst, bytes, tid, op); break;
+    case DT_F32: fold_slice<DT_F32, NTH>(src_tab, nsrc, dst_tab, ndst, bytes, tid, op); break;
+    case DT_BF16: fold_slice<DT_BF16, NTH>(src_tab, nsrc, dst_tab, ndst, bytes, tid, op); break;
+    case DT_F16: fold_slice<DT_F16, NTH>(src_tab, nsrc, dst_tab, ndst, bytes, tid, op); break;
+    default: fold_slice<DT_I32, NTH>(src_tab, nsrc, dst_tab, ndst, bytes, tid, op); break;
   }
 }
 
-// The gather step: segment s is len[s] bytes copied from src[s] (another rank's recv buffer: device-coherent
-// loads) to dst[s] (the own recv buffer); the loads of up to eight segments travel together.
+// The gather step: segment s is len[s] bytes copied from src[s] (a rank's send buffer: device-coherent loads)
+// to dst[s] (the own recv buffer); the loads of up to eight segments travel together.
 template <int NTH>
 __device__ __forceinline__ void gather_slices(const u64* src_tab, const u64* dst_tab, const uint32_t* len_tab, uint32_t nseg,
                                               uint32_t maxbytes, uint32_t tid) {
@@ -606,9 +615,10 @@ struct Job {                         // what the scheduler wave hands to the mov
   const void* fin; const char* sb; char* rb; void* fout;
   uint32_t bytes; int dtype;
   uint32_t coll, prim;               // for the timeline trace only
-  uint32_t mode;                     // 0: the four pointers above; 1: fold step (sources in the job's tables, fout = destination);
+  uint32_t mode;                     // 0: the four pointers above; 1: fold step (sources and destinations in the job's tables);
                                      // 2: gather step (segments in the job's tables, bytes = the longest one)
-  uint32_t nseg;                     // entries of the tables
+  uint32_t nseg;                     // sources of a fold step, segments of a gather step
+  uint32_t ndst;                     // destinations of a fold step
 };
 
 // What publishing and retiring a posted job needs.  Written by the scheduler when it posts the
@@ -630,7 +640,7 @@ struct Shared {
   Job job[2];                        // posted jobs, indexed by job number & 1
   Flight fl[2];
   u64 tab_src[2][64];                // fold / gather steps: source addresses of the job, in order
-  u64 tab_dst[2][64];                // gather steps: destination addresses
+  u64 tab_dst[2][64];                // fold steps: where the result goes; gather steps: where each segment goes
   uint32_t tab_len[2][64];           // gather steps: bytes of each segment
   uint32_t job_seq;                  // jobs posted so far (scheduler -> movers)
   uint32_t wave_done[2];             // mover waves that have finished job k, at index k & 1
@@ -779,7 +789,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         }
       } else
 #endif
-      if (j.mode == 1) fold_dispatch<GTHREADS>(j.dtype, sh.tab_src[seen & 1], j.nseg, j.fout, j.bytes, mtid);
+      if (j.mode == 1) fold_dispatch<GTHREADS>(j.dtype, sh.tab_src[seen & 1], j.nseg, sh.tab_dst[seen & 1], j.ndst, j.bytes, mtid);
       else if (j.mode == 2) gather_slices<GTHREADS>(sh.tab_src[seen & 1], sh.tab_dst[seen & 1], sh.tab_len[seen & 1], j.nseg, j.bytes, mtid);
       else if (coh) run_prim<AUX_DEVICE, GTHREADS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
       else run_prim<AUX_CACHED, GTHREADS>(j.dtype, j.fin, j.sb, j.rb, j.fout, j.bytes, mtid);
@@ -1396,50 +1406,48 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           }
           jfin = q.din_send ? (const void*)((const char*)prev_send + soff * eb) : (const void*)((const char*)prev_recv + doff * eb);
         }
-        uint32_t jmode = 0, jnseg = 0, jbytes_fold = 0;
+        uint32_t jmode = 0, jnseg = 0, jndst = 0, jbytes_fold = 0;
         if (q.fold == 1 || q.fold == 2) {
           // The addresses every rank published for this invocation (before it counted itself published, which a
           // wait of this invocation has seen for all of them): lane k looks up one rank.
-          //   fold step: the R send buffers in the order of combination, which begins behind this rank (all-reduce,
-          //     reduce-scatter: the ring's order for this rank's chunk) or behind the root (reduce: the chain's);
-          //     a reduce writes the root's recv buffer, whose address lane R looks up.
-          //   gather step: all-reduce: the other R-1 ranks' recv buffers, each with its own chunk; all-gather: all R
-          //     send buffers, each with its block; broadcast: the root's send buffer.
+          // fold_peer / fold_chunk say which rank and which chunk entry k is about.  Every entry reads a send buffer;
+          // the result of a fold step goes to the own recv buffer (reduce-scatter), to the root's (reduce: its address
+          // is looked up by the lane behind the R sources, hence at most 63 ranks) or to every entry's rank's
+          // (all-reduce: each lane reads both addresses of its rank).
           const int kd = (int)S.kind;
           const uint32_t root = S.nslots;                       // (a collective in fold steps keeps its root there)
-          const bool from_send = q.fold == 1 || kd != KIND_AR;  // which published address: the send or the recv buffer
-          const uint32_t first = (q.fold == 1 && kd == KIND_RD) ? root + 1 : (kd == KIND_AR || kd == KIND_RS) ? rank + 1 : 0u;
-          uint32_t nk = a.R;
-          if (q.fold == 2) nk = kd == KIND_AR ? a.R - 1 : (kd == KIND_BC ? 1u : a.R);
-          // (a reduce in fold steps has at most 63 ranks: the root's recv buffer is looked up by the lane behind the R sources)
-          const bool want_root_recv = q.fold == 1 && kd == KIND_RD;      // one more look-up, in lane nk
-          const uint32_t peer = (want_root_recv && lane == nk) ? root : (q.fold == 2 && kd == KIND_BC) ? root : (first + lane) % a.R;
+          const uint32_t nk = fold_entries(kd, q.fold, a.R);
+          const uint32_t target = q.fold == 1 ? fold_dest(kd) : 0u;
+          const bool want_root_recv = target == 1u;             // one more look-up, in lane nk
+          const bool root_lane = want_root_recv && lane == nk;
+          const uint32_t peer = root_lane ? root : fold_peer(kd, q.fold, a.R, rank, root, lane);
           bool bad = want_root_recv && nk >= 64u;
           if (lane < nk + (want_root_recv ? 1u : 0u)) {
-            const bool rd_send = from_send && !(want_root_recv && lane == nk);
             const Slot<AUX_DEVICE> line((const void*)fold_line(S.flags_out, rank, peer, S.nchan), DFX_FLAG_STRIDE);
-            uint4 w = uint4{0, 0, 0, 0};
+            uint4 w = uint4{0, 0, 0, 0}, wr = w;
             for (uint32_t tries = 0; tries < 1024u; ++tries) {
-              w = line.ld16(rd_send ? DFX_DIRECT_OFF + 16 : DFX_DIRECT_OFF);
-              if (w.z == inv_seq + 1u) break;
+              w = line.ld16(root_lane ? DFX_DIRECT_OFF : DFX_DIRECT_OFF + 16);
+              if (target == 2u) wr = line.ld16(DFX_DIRECT_OFF);
+              if (w.z == inv_seq + 1u && (target != 2u || wr.z == inv_seq + 1u)) break;
               __builtin_amdgcn_s_sleep(2);
             }
-            bad = bad || w.z != inv_seq + 1u;
+            bad = bad || w.z != inv_seq + 1u || (target == 2u && wr.z != inv_seq + 1u);
             const u64 base = ((u64)w.y << 32) | w.x;
-            // the chunk this entry is about: the rank's own one in a fold step, the peer's in a gather step
-            const SliceGeom gk = slice_geometry(S, a.R, 0u, q.fold == 1 ? rank : (kd == KIND_BC ? 0u : peer));
-            if (want_root_recv && lane == nk) sh.tab_dst[posted & 1][0] = base + gk.doff * gk.eb;
+            const u64 peer_recv = ((u64)wr.y << 32) | wr.x;
+            const SliceGeom gk = slice_geometry(S, a.R, 0u, fold_chunk(kd, q.fold, rank, peer));
+            if (root_lane) sh.tab_dst[posted & 1][0] = base + gk.doff * gk.eb;
             else {
-              sh.tab_src[posted & 1][lane] = base + (rd_send ? gk.soff : gk.doff) * gk.eb;
-              if (!(want_root_recv && lane == 0)) sh.tab_dst[posted & 1][lane] = (u64)S.recvbuf + gk.doff * gk.eb;
+              sh.tab_src[posted & 1][lane] = base + gk.soff * gk.eb;
+              if (!(want_root_recv && lane == 0))
+                sh.tab_dst[posted & 1][lane] = (target == 2u ? peer_recv : (u64)S.recvbuf) + gk.doff * gk.eb;
               sh.tab_len[posted & 1][lane] = gk.bytes;
             }
           }
           if (__ballot(bad)) { if (lane == 0) raise_error(a, 3u, wg); stop = STOP_ABORT; have = false; continue; }
           __builtin_amdgcn_wave_barrier();
-          jmode = q.fold; jnseg = nk;
+          jmode = q.fold; jnseg = nk; jndst = target == 2u ? nk : 1u;
           const SliceGeom own = slice_geometry(S, a.R, 0u, rank);
-          if (q.fold == 1) { jfout = (void*)(uintptr_t)sh.tab_dst[posted & 1][0]; jbytes_fold = own.bytes; }
+          if (q.fold == 1) jbytes_fold = own.bytes;
           else jbytes_fold = (uint32_t)S.slice_elems * own.eb;      // the longest segment: a channel's share of a full chunk
         }
         // ---- post the slice (an empty one is only a handshake: the movers just raise the counters);
@@ -1451,7 +1459,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
           j.bytes = (q.drain || (!q.recv && !q.from_send)) ? 0u : bytes;   // drain and notify-only steps move nothing
           if (q.fold) j.bytes = jbytes_fold;                               // (the last fold step: nothing)
-          j.mode = jmode; j.nseg = jnseg;
+          j.mode = jmode; j.nseg = jnseg; j.ndst = jndst;
           j.dtype = dtype; j.coll = coll; j.prim = (q.drain || q.fold == 3) ? 0xffu : p;   // (prim: for the timeline only)
           sh.job[posted & 1] = j;
           Flight f;

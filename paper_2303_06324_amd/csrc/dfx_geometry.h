@@ -65,12 +65,14 @@ struct Prim {
 // a chain (a few microseconds each, whatever the size) can be replaced by steps that wait on all ranks at once:
 //   fold step:   when every rank has published this invocation's buffers, a rank reads one chunk out of all R
 //                send buffers and combines them in the ring's (the chain's) own order -- the same association as
-//                the hops would give, hence the same bits;
-//   gather step: copies chunks out of other ranks' buffers into the own recv buffer;
+//                the hops would give, hence the same bits -- and writes the result where it belongs: its own recv
+//                buffer, the root's, or everybody's;
+//   gather step: copies chunks out of other ranks' send buffers into the own recv buffer;
 //   last wait:   no data; when every rank has got far enough, nobody reads this rank's buffers any more and
 //                the completion may be posted.
-// all-reduce:      fold (rank r: chunk r, x[r+1] (op) ... (op) x[r], into its recv buffer), gather (when every rank
-//                  has folded: the other R-1 chunks out of their owners' recv buffers), last wait (all gathered)
+// all-reduce:      fold (rank r: chunk r, x[r+1] (op) ... (op) x[r], into chunk r of ALL R recv buffers: every input is
+//                  read once and every output written once), last wait (all folded: every chunk of the own recv
+//                  buffer has arrived and nobody reads the own send buffer any more)
 // reduce-scatter:  fold (rank r: block r into its recv buffer), last wait (all folded: the send buffers are free)
 // reduce:          fold (rank r: chunk r of the message, x[root+1] (op) ... (op) x[root], into the ROOT's recv
 //                  buffer), last wait (all folded)
@@ -78,17 +80,32 @@ struct Prim {
 // broadcast:       gather (the channel's share of the root's send buffer), last wait (all gathered)
 // Each step is a bounded wait followed by the data, like any primitive: nothing is touched before the wait has
 // succeeded, so a collective stuck in any of them is preempted like any other.
-DFX_HD uint32_t fold_nprim(int kind) { return kind == KIND_AR ? 3u : 2u; }
+DFX_HD uint32_t fold_nprim(int) { return 2u; }
 DFX_HD Prim make_fold_prim(int kind, uint32_t p) {
   Prim q;
   q.recv = q.send = q.notify = q.din = q.drain = q.din_send = false;
   q.from_send = q.to_recv = false;
   const bool reduces = (kind == KIND_AR || kind == KIND_RS || kind == KIND_RD);
   if (p == 0) { q.fold = reduces ? 1 : 2; q.fwait = 0; q.fadd = reduces ? 1 : 2; q.from_send = true; q.to_recv = true; }
-  else if (kind == KIND_AR && p == 1) { q.fold = 2; q.fwait = 1; q.fadd = 2; q.to_recv = true; }
-  else { q.fold = 3; q.fwait = (kind == KIND_RS || kind == KIND_RD) ? 1 : 2; q.fadd = 0; }
+  else { q.fold = 3; q.fwait = reduces ? 1 : 2; q.fadd = 0; }
   return q;
 }
+
+// The tables of a fold or gather step (Prim::fold 1 or 2).  Entry k of a fold step is a source, listed in the order
+// of combination, which begins behind this rank (all-reduce, reduce-scatter: the ring's order for this rank's chunk)
+// or behind the root (reduce: the chain's); every entry is about the rank's own chunk.  Entry k of a gather step is
+// a segment: all-gather: block k out of rank k's send buffer; broadcast: the root's send buffer.
+DFX_HD uint32_t fold_entries(int kind, uint32_t step, uint32_t R) { return (step == 2 && kind == KIND_BC) ? 1u : R; }
+DFX_HD uint32_t fold_peer(int kind, uint32_t step, uint32_t R, uint32_t rank, uint32_t root, uint32_t k) {
+  if (step == 2) return kind == KIND_BC ? root : k % R;
+  return ((kind == KIND_RD ? root : rank) + 1u + k) % R;
+}
+DFX_HD uint32_t fold_chunk(int kind, uint32_t step, uint32_t rank, uint32_t peer) {
+  return step == 1 ? rank : (kind == KIND_BC ? 0u : peer);
+}
+// Where a fold step's result goes: 0 the own recv buffer (reduce-scatter), 1 the root's (reduce), 2 the recv buffer
+// of every entry's rank (all-reduce).
+DFX_HD uint32_t fold_dest(int kind) { return kind == KIND_AR ? 2u : (kind == KIND_RD ? 1u : 0u); }
 
 // Where a fold collective's lines are, from a workgroup's own line: the line of rank r on the same channel,
 // and the channel's shared line.

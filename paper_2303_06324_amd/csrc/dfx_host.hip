@@ -409,7 +409,7 @@ int plan_collective(const dfx_config& cfg, int nranks, int coll_id, dfx_kind kin
   if (R == 1) t.nprim = 1;
   else if (fold) {
     t.flags |= DFX_SQE_DIRECT | DFX_SQE_FOLD;   // (buffers are published as for the direct steps)
-    t.nprim = fold_nprim((int)kind);            // all-reduce: fold, gather, last wait; the others: one step and the last wait
+    t.nprim = fold_nprim((int)kind);            // one step with data and the last wait
   }
   else if (kind == DFX_ALLREDUCE) {
     // direct gather steps (one more step: the drain) where the message is long enough to gain from them
@@ -1132,23 +1132,24 @@ int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t
           const Prim fq = make_fold_prim(kind, p);
           const uint32_t rt = S.nslots;      // the root
           if (fq.fold == 1 || fq.fold == 2) {
-            const bool from_send = fq.fold == 1 || kind != KIND_AR;
-            const uint32_t first = (fq.fold == 1 && kind == KIND_RD) ? rt + 1 : (kind == KIND_AR || kind == KIND_RS) ? r + 1 : 0u;
-            uint32_t nk = R;
-            if (fq.fold == 2) nk = kind == KIND_AR ? R - 1 : (kind == KIND_BC ? 1u : R);
+            const uint32_t nk = fold_entries(kind, fq.fold, R);
+            const uint32_t target = fq.fold == 1 ? fold_dest(kind) : 0u;
+            if (nk > 64u || (target == 1u && nk > 63u)) return fail("rank %u channel %u: %u table entries for 64 lanes", r, v, nk);
             for (uint32_t k = 0; k < nk; ++k) {
-              const uint32_t peer = (fq.fold == 2 && kind == KIND_BC) ? rt : (first + k) % R;
-              const SliceGeom gk = slice_geometry(S, R, 0u, fq.fold == 1 ? r : (kind == KIND_BC ? 0u : peer));
+              const uint32_t peer = fold_peer(kind, fq.fold, R, r, rt, k);
+              if (peer >= R) return fail("rank %u channel %u fold step %u: entry %u names rank %u", r, v, p, k, peer);
+              const SliceGeom gk = slice_geometry(S, R, 0u, fold_chunk(kind, fq.fold, r, peer));
               if ((uint64_t)gk.bytes > (uint64_t)S.slice_elems * gk.eb) return fail("rank %u channel %u: a segment longer than the share", r, v);
               if (!gk.bytes) continue;
-              const uint64_t rd = (from_send ? gk.soff : gk.doff) * gk.eb, lim = from_send ? send_bytes : recv_bytes;
-              if (rd + gk.bytes > lim) return fail("rank %u channel %u fold step %u: read of rank %u's buffer %llu+%u of %llu", r, v, p, peer, (unsigned long long)rd, gk.bytes, (unsigned long long)lim);
+              const uint64_t rd = gk.soff * gk.eb;            // every entry reads its rank's send buffer
+              if (rd + gk.bytes > send_bytes) return fail("rank %u channel %u fold step %u: read of rank %u's buffer %llu+%u of %llu", r, v, p, peer, (unsigned long long)rd, gk.bytes, (unsigned long long)send_bytes);
               if ((kind == KIND_AG || kind == KIND_RS) && (rd & 15u)) return fail("rank %u channel %u fold step %u: a 16-byte read at offset %llu", r, v, p, (unsigned long long)rd);
-              if (fq.fold == 1 && k + 1 < nk) continue;       // (a fold step writes once, after the last source)
+              // a fold step writes its result to the own recv buffer (once, entry 0 stands for it), the root's, or
+              // the recv buffer of every entry's rank; a gather step writes every segment to the own recv buffer
+              if (fq.fold == 1 && target != 2u && k != 0) continue;
               const uint64_t wr = gk.doff * gk.eb;
               if (wr + gk.bytes > recv_bytes) return fail("rank %u channel %u fold step %u: recv buffer write %llu+%u of %llu", r, v, p, (unsigned long long)wr, gk.bytes, (unsigned long long)recv_bytes);
-              // (the fold step of a reduce writes the root's recv buffer)
-              written[(fq.fold == 1 && kind == KIND_RD) ? rt : r].push_back({wr, wr + gk.bytes});
+              written[target == 2u ? peer : (target == 1u ? rt : r)].push_back({wr, wr + gk.bytes});
             }
           }
           const SeqPos nx = next_position(kind, R, r, cfg.window, S.rounds, S.nprim, g, p, cidx);

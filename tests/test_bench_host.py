@@ -20,8 +20,9 @@ IO = {
     "notify": (0, 0), "drain": (0, 0), "copy_notify": (1, 1),
     "direct_reduce_send": (2, 1), "direct_reduce_copy_notify": (2, 1), "direct_reduce_copy": (2, 1),
     "recv_reduce_copy_notify": (2, 1), "direct_copy_notify": (1, 1), "direct_copy": (1, 1),
-    # fold steps (R ranks): chunk r out of all R send buffers into the recv buffer; the other R-1 chunks copied
-    "fold_all": lambda R: (R, 1), "gather_all": lambda R: (R - 1, R - 1), "last_wait": (0, 0),
+    # fold steps (R ranks): chunk r out of all R send buffers into the own recv buffer (reduce-scatter) or into
+    # all R recv buffers (all-reduce)
+    "fold_all": lambda R: (R, 1), "fold_scatter": lambda R: (R, R), "last_wait": (0, 0),
     "fold_root": lambda R: (R, 1), "gather_pub": lambda R: (R, R), "last_wait_red": (0, 0),
 }
 
@@ -46,7 +47,7 @@ def test_roofline_byte_counts_follow_from_the_primitive_programs(R):
     chunk = M // R
     assert _blocks_moved(sm.AR, R, False) * chunk == bench.algorithmic_bytes(M, R)
     assert _blocks_moved(sm.AR, R, True) * chunk == bench.moved_bytes(M, R)
-    assert _blocks_moved(sm.AR, R, False, fold=True) * chunk == bench.fold_bytes(M, R)      # (3R-1) x M in fold steps
+    assert _blocks_moved(sm.AR, R, False, fold=True) * chunk == bench.fold_bytes(M, R)      # 2R x M in fold steps
     # per rank, in blocks: all-gather 3R-1 -> 2R, reduce-scatter 3R-1 -> 3R-3; chains, in messages: broadcast
     # 3R-1 -> 2R, reduce 3R-1 -> 3R-3
     assert _blocks_moved(sm.AG, R, False) == R * (3 * R - 1) and _blocks_moved(sm.AG, R, True) == R * 2 * R

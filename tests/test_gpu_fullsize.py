@@ -60,7 +60,7 @@ def test_config2_largest_size_whole_buffers(big, knobs):
     ctx = dfx.Context(R, gh.make_config(**knobs))
     try:
         ctx.prepare(0, dfx.ALLREDUCE, n, dfx.F32)
-        assert ctx.coll_info(0)["nprim"] == (3 if "fold_max_bytes" in knobs else 2 * R if knobs.get("direct", 1) else 2 * R - 1)
+        assert ctx.coll_info(0)["nprim"] == (2 if "fold_max_bytes" in knobs else 2 * R if knobs.get("direct", 1) else 2 * R - 1)
         for it in range(2):
             dw.reset_recv()
             for r in range(R):

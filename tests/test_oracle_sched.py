@@ -493,7 +493,7 @@ def test_priority_ordering_ranks_the_urgent_collective_first(later_first):
 @pytest.mark.parametrize("var", [dict(), dict(scan=True), dict(lookahead=2, scan=True, focus=1)])
 @pytest.mark.parametrize("orders", [_OPP, _SAME])
 def test_fold_steps_exhaustive_interleavings_tiny(orders, var):
-    """All-reduces in fold steps (three waits on all ranks: published, folded, gathered) keep Alg. 1's liveness:
+    """All-reduces in fold steps (waits on all ranks through shared counters: published, folded) keep Alg. 1's liveness:
     in the circular-wait setting no reachable state -- over all interleavings of daemons, movers and host
     submissions -- is a deadlock, and every one of them ends with the four CQEs."""
     w = wi.config1(*orders, n=8)
@@ -524,9 +524,9 @@ def test_fold_steps_without_preemption_still_deadlock_on_opposite_orders():
 @pytest.mark.parametrize("seed", range(4))
 def test_fold_steps_values_and_completion_order(var, seed):
     """All five kinds on three ranks in fold steps, random orders, random interleavings: the final
-    buffers are the data oracle's -- the fold step's order of combination is the ring's -- and no rank posts an
-    all-reduce's completion before every rank has finished its gather step (the recv buffer, which the others
-    read, is the caller's again after the completion)."""
+    buffers are the data oracle's -- the fold step's order of combination is the ring's -- and no rank posts a
+    completion before every rank has finished the step with data (folded: the send buffers, which the others read, and
+    the recv buffers, which the others write, are the caller's again after the completion)."""
     g = np.random.default_rng(seed)
     R = 3
     colls = [wi.CollSpec(0, wi.AR, wi.F32, 50), wi.CollSpec(1, wi.AG, wi.F16, 12), wi.CollSpec(2, wi.AR, wi.BF16, 33),
@@ -550,7 +550,7 @@ def test_fold_steps_values_and_completion_order(var, seed):
                 assert S.foldcnt[c][0] >= R
                 if k in (wi.AR, wi.RS, wi.RD):
                     assert S.foldcnt[c][1] >= R     # every rank has folded: nobody reads a send buffer any more
-                if k in (wi.AR, wi.AG, wi.BC):
+                if k in (wi.AG, wi.BC):
                     assert S.foldcnt[c][2] >= R     # every rank has gathered
         ticks += 1
         assert ticks < 3_000_000
@@ -577,9 +577,10 @@ def test_fold_steps_of_the_other_kinds_exhaustive_interleavings_tiny(kinds):
 
 
 def test_fold_programs_move_fewer_blocks_than_the_ring():
-    """Per rank, in chunks: the fold step reads R and writes 1, the gather step reads and writes R - 1."""
+    """Per rank, in chunks: the one data step of an all-reduce reads R and writes R (every input read once, every
+    output written once); the second step only waits."""
     for R in (2, 3, 8):
         blocks = [(8 * j, 8 * j + 8) for j in range(R)]
         prog = sm.program(sm.AR, R, 1, 0, blocks, blocks, False, True)
-        assert [n for n, _, _ in prog] == ["fold_all", "gather_all", "last_wait"]
+        assert [n for n, _, _ in prog] == ["fold_scatter", "last_wait_red"]
         assert prog[0][1] == blocks[1] and prog[0][2] == blocks[1]        # rank r combines chunk r
