@@ -111,7 +111,8 @@ def _switch_summary(rc, dt, st, n, st2):
             "save_us_mean": round(sum(s["save_us_mean"] for s in st2) / len(st2), 3),
             "advance_us_mean": round(sum(s["advance_us_mean"] for s in st2) / len(st2), 3),
             "load_us_mean": round(sum(s["load_us_mean"] for s in st2) / len(st2), 3),
-            "setup_us_mean": round(sum(s["setup_us_mean"] for s in st2) / len(st2), 3)}
+            "setup_us_mean": round(sum(s["setup_us_mean"] for s in st2) / len(st2), 3),
+            "clock_read_us": round(max(s["clock_read_us"] for s in st2), 4)}
 
 
 def _switch_config1(trace: int, iters: int = 400):
@@ -175,7 +176,7 @@ def deadlock_prone():
         t_c1 += time.perf_counter() - t0
         ok = ok and sum(s["cqe_posted"] for s in st) == 4
     out["config1_four_order_combinations"] = {"completed": ok, "seconds": round(t_c1, 4)}
-    for name, w, mode in (("config3_16x25MiB_bf16", wi.config3(), "roundrobin"),
+    for name, w, mode in (("config3_16x25MiB_bf16", wi.config3(), "bursts"),
                           ("config4_64_mixed", wi.config4(), "threads"),
                           ("config5_1024_small", wi.config5(), "threads")):
         dw = gh.DeviceWorkload(w, keep_host=False)
@@ -192,6 +193,8 @@ def deadlock_prone():
                 t0 = time.perf_counter()
                 if mode == "threads":
                     gh.submit_threads(ctx, dw, delays_us=w.delays_us or None, timeout_s=60)
+                elif mode == "bursts":      # one thread, one native call per vrank (its whole issue order)
+                    gh.submit_bursts(ctx, dw, timeout_s=60)
                 else:
                     gh.submit_round_robin(ctx, dw, timeout_s=60)
                 rc = rc or ctx.wait_all(60.0)
@@ -209,41 +212,86 @@ def deadlock_prone():
 
 
 def size_sweep(iters: int = 10):
-    """All-reduce latency / bandwidth over the sweep's sizes inside one resident daemon
-    (submit of the first vrank -> last CQE seen by the host; best of `iters`)."""
+    """All-reduce latency / bandwidth over the sweep's sizes inside one resident daemon (submit of the first
+    vrank -> last CQE seen by the host; best of `iters`) with the library's defaults, and beside it the same
+    sizes as rings only (`fold_max_bytes = 0`) and in fold steps only (the limit raised above every size)."""
     import torch
     import paper_2303_06324_amd as dfx
     from paper_2303_06324_amd import harness as gh
     import workload_inputs as wi
-    rows = []
-    for nbytes in wi.CONFIG2_SIZES:
-        n = nbytes // 4
-        send = [torch.randn(n, device="cuda") for _ in range(R)]
-        recv = [torch.empty(n, device="cuda") for _ in range(R)]
-        torch.cuda.synchronize()
-        ctx = dfx.Context(R, gh.make_config())
+    nmax = max(wi.CONFIG2_SIZES) // 4
+    send = [torch.randn(nmax, device="cuda") for _ in range(R)]
+    recv = [torch.empty(nmax, device="cuda") for _ in range(R)]
+    torch.cuda.synchronize()
+    variants = (("default", {}), ("ring", dict(fold_max_bytes=0)), ("fold", dict(fold_max_bytes=2 * max(wi.CONFIG2_SIZES))))
+    res = {}
+    for vname, knobs in variants:
+        ctx = dfx.Context(R, gh.make_config(quit_idle_us=0, **knobs))
         try:
-            ctx.prepare(0, dfx.ALLREDUCE, n, dfx.F32)
-            best = 1e9
             ptrs = ctx.make_all([t.data_ptr() for t in send], [t.data_ptr() for t in recv])
-            for _ in range(iters + 2):
-                t0 = time.perf_counter()
-                assert ctx.submit_all(0, ptrs) == dfx.OK
-                assert ctx.wait_all(30.0) == dfx.OK
-                best = min(best, time.perf_counter() - t0)
-            nchan = ctx.coll_info(0)["nchan"]
-            nprim = ctx.coll_info(0)["nprim"]
+            for i, nbytes in enumerate(wi.CONFIG2_SIZES):
+                ctx.prepare(i, dfx.ALLREDUCE, nbytes // 4, dfx.F32)
+                best = 1e9
+                for _ in range(iters + 2):
+                    t0 = time.perf_counter()
+                    assert ctx.submit_all(i, ptrs) == dfx.OK
+                    assert ctx.wait_all(30.0) == dfx.OK
+                    best = min(best, time.perf_counter() - t0)
+                res[(vname, nbytes)] = (best, ctx.coll_info(i)["nchan"], ctx.coll_info(i)["nprim"])
+            ctx.stop()
         finally:
             ctx.finalize()
+    rows = []
+    for nbytes in wi.CONFIG2_SIZES:
+        best, nchan, nprim = res[("default", nbytes)]
         path = {2: "fold steps", 2 * R: "ring, direct steps"}.get(nprim, "ring through slots")
         nb = {2: fold_bytes, 2 * R: moved_bytes}.get(nprim, algorithmic_bytes)(nbytes, R)     # what the path taken moves
         rows.append({"bytes": nbytes, "us": round(best * 1e6, 1), "channels": nchan,
                      "algbw_GBs": round(nbytes / best / 1e9, 2),
                      "busbw_GBs": round(nbytes / best * 2 * (R - 1) / R / 1e9, 2),
                      "path": path, "moved_GB": round(nb / 1e9, 4),
-                     "hbm_frac": round(nb / best / 1e9 / HBM_PEAK_GBS, 4)})
-        del send, recv
+                     "hbm_frac": round(nb / best / 1e9 / HBM_PEAK_GBS, 4),
+                     "ring_only_us": round(res[("ring", nbytes)][0] * 1e6, 1),
+                     "fold_only_us": round(res[("fold", nbytes)][0] * 1e6, 1)})
+    del send, recv
     return rows
+
+
+def kinds_by_size(sizes=(8 << 10, 1 << 20, 8 << 20, 32 << 20, 256 << 20), iters: int = 8):
+    """The four other kinds over sizes (largest per-rank buffer; fp32, sum, root 3): rings / chains
+    (`fold_max_bytes = 0`) against fold steps at every size; the library's default takes the fold steps
+    below 64 MiB."""
+    import torch
+    import paper_2303_06324_amd as dfx
+    from paper_2303_06324_amd import harness as gh
+    nmax = max(sizes) // 4
+    a = [torch.randn(nmax, device="cuda") for _ in range(R)]
+    b = [torch.empty(nmax, device="cuda") for _ in range(R)]
+    torch.cuda.synchronize()
+    kinds = (("all-gather", dfx.ALLGATHER), ("reduce-scatter", dfx.REDUCESCATTER), ("broadcast", dfx.BROADCAST), ("reduce", dfx.REDUCE))
+    res = {}
+    for vname, fold in (("ring_or_chain_us", 0), ("fold_steps_us", 2 * max(sizes))):
+        ctx = dfx.Context(R, gh.make_config(quit_idle_us=0, fold_max_bytes=fold))
+        try:
+            ptrs = ctx.make_all([t.data_ptr() for t in a], [t.data_ptr() for t in b])
+            cid = 0
+            for name, kind in kinds:
+                for nbytes in sizes:
+                    n = nbytes // 4
+                    ctx.prepare(cid, kind, n // R if kind in (dfx.ALLGATHER, dfx.REDUCESCATTER) else n, dfx.F32, dfx.SUM, 3)
+                    best = 1e9
+                    for _ in range(iters + 2):
+                        t0 = time.perf_counter()
+                        assert ctx.submit_all(cid, ptrs) == dfx.OK
+                        assert ctx.wait_all(30.0) == dfx.OK
+                        best = min(best, time.perf_counter() - t0)
+                    res[(name, nbytes, vname)] = round(best * 1e6, 1)
+                    cid += 1
+            ctx.stop()
+        finally:
+            ctx.finalize()
+    return [{"kind": name, "bytes": nbytes, "ring_or_chain_us": res[(name, nbytes, "ring_or_chain_us")],
+             "fold_steps_us": res[(name, nbytes, "fold_steps_us")]} for name, _ in kinds for nbytes in sizes]
 
 
 def kinds_sweep(nbytes: int = 256 << 20, iters: int = 8):
@@ -304,7 +352,7 @@ def spin_sweep():
             rc, dts = 0, []
             for rep in range(3):
                 t0 = time.perf_counter()
-                (gh.submit_threads if mode == "threads" else gh.submit_round_robin)(ctx, dw, timeout_s=120)
+                (gh.submit_threads if mode == "threads" else gh.submit_bursts)(ctx, dw, timeout_s=120)
                 rc = rc or ctx.wait_all(120.0)
                 dts.append(time.perf_counter() - t0)
             ctx.stop()
@@ -316,10 +364,10 @@ def spin_sweep():
     rows = []
     for n in (1, 2, 4, 8, 16, 64, 256, 1024, 4096, 16384):
         kw = dict(spin_init=n, spin_min=n, spin_max=n, spin_boost=1)
-        rows.append({"fixed_threshold": n, "config3_16x25MiB": one(w3, d3, "roundrobin", **kw),
+        rows.append({"fixed_threshold": n, "config3_16x25MiB": one(w3, d3, "bursts", **kw),
                      "config5_256_small": one(w5, d5, "threads", **kw)})
     rows.append({"fixed_threshold": None, "policy": "adaptive default",
-                 "config3_16x25MiB": one(w3, d3, "roundrobin"), "config5_256_small": one(w5, d5, "threads")})
+                 "config3_16x25MiB": one(w3, d3, "bursts"), "config5_256_small": one(w5, d5, "threads")})
     return rows
 
 
@@ -350,9 +398,12 @@ def ordering_staggered(n_buckets: int = 16, bucket_bytes: int = 25 << 20):
             time.sleep(0.01)
             for rep in range(3):
                 done_at, order = {}, []
-                th = threading.Thread(target=gh.submit_threads, args=(ctx, dw), kwargs=dict(orders=orders, delays_us=delays, timeout_s=60))
-                t0 = time.perf_counter()
+                ready = threading.Barrier(R + 1)      # the clock starts when all eight submitters are at their native call
+                th = threading.Thread(target=gh.submit_threads, args=(ctx, dw),
+                                      kwargs=dict(orders=orders, delays_us=delays, timeout_s=60, barrier=ready))
                 th.start()
+                ready.wait()
+                t0 = time.perf_counter()
                 while len(order) < n_buckets and time.perf_counter() - t0 < 30.0:
                     for cid, _ in ctx.poll(0, 64):
                         done_at[cid] = time.perf_counter() - t0
@@ -416,7 +467,7 @@ def studies():
             rc, dts = 0, []
             for rep in range(3):      # back to back in one resident daemon
                 t0 = time.perf_counter()
-                gh.submit_round_robin(ctx, d3, timeout_s=60)
+                gh.submit_bursts(ctx, d3, timeout_s=60)
                 rc = rc or ctx.wait_all(60.0)
                 dts.append(time.perf_counter() - t0)
             ctx.stop()
@@ -507,7 +558,7 @@ def main():
         ctx2 = dfx.Context(R, cfg2)
         try:
             ctx2.prepare(0, dfx.ALLREDUCE, n, dfx.F32)
-            assert ctx2.coll_info(0)["nprim"] == 3
+            assert ctx2.coll_info(0)["nprim"] == 2
             ts = []
             for it in range(8):
                 t0f = time.perf_counter()
@@ -589,6 +640,7 @@ def main():
     if args.studies:
         out["studies"] = studies()
         out["kinds_256MiB"] = kinds_sweep()
+        out["kinds_by_size"] = kinds_by_size()
     verified = None
     if not args.no_cpu:
         # the CPU leg replays the same inputs; its result is also the check of what the timed steps computed

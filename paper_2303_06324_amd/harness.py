@@ -136,26 +136,47 @@ def submit_round_robin(ctx: "dfx.Context", dw: DeviceWorkload, orders=None, time
                 _submit_retry(ctx, r, w.colls[ci].coll_id, dw.send[ci][r].data_ptr(), dw.recv[ci][r].data_ptr(), deadline)
 
 
-def submit_threads(ctx: "dfx.Context", dw: DeviceWorkload, orders=None, delays_us=None, timeout_s: float = 30.0):
-    """One host thread per rank, each with its own order and (optional) seeded delays."""
+def submit_bursts(ctx: "dfx.Context", dw: DeviceWorkload, timeout_s: float = 30.0):
+    """One host thread, one native burst per rank in turn (rank 0's whole issue order, then rank 1's ...): the
+    workload's per-rank orders without a Python call per submission."""
+    assert dw.bursts is not None
+    for r in range(dw.w.R):
+        burst = dw.bursts[r]
+        if burst[4] is not None:
+            burst = burst[:4] + (None,)
+        n = ctx.submit_burst(r, burst, timeout_s)
+        if n != burst[0]:
+            raise dfx.DfxError(n if n < 0 else dfx.ERR_TIMEOUT, f"dfx_submit_many(rank={r}) -> {n}")
+
+
+def submit_threads(ctx: "dfx.Context", dw: DeviceWorkload, orders=None, delays_us=None, timeout_s: float = 30.0,
+                   barrier=None):
+    """One host thread per rank, each with its own order and (optional) seeded delays.  Every thread makes one
+    native call (pauses included), so the submitters really run concurrently; the bursts are marshalled before
+    the threads start.  `barrier` (a threading.Barrier for R + 1 parties): every thread waits at it before its
+    call, so that a caller who times the run can start its clock when all submitters are ready."""
     w = dw.w
     orders = w.orders if orders is None else orders
     errs = []
+    bursts = []
+    for r in range(w.R):
+        if orders is w.orders and dw.bursts is not None and (delays_us is None or delays_us is w.delays_us):
+            burst = dw.bursts[r]
+            if delays_us is None and burst[4] is not None:
+                burst = burst[:4] + (None,)
+        else:
+            burst = ctx.make_burst([w.colls[ci].coll_id for ci in orders[r]],
+                                   [dw.send[ci][r].data_ptr() for ci in orders[r]],
+                                   [dw.recv[ci][r].data_ptr() for ci in orders[r]],
+                                   delays_us[r] if delays_us else None)
+        bursts.append(burst)
 
     def work(r):
         try:
-            # one native burst per rank (pauses included): the host threads really run concurrently
-            if orders is w.orders and dw.bursts is not None and (delays_us is None or delays_us is w.delays_us):
-                burst = dw.bursts[r]
-                if delays_us is None and burst[4] is not None:
-                    burst = burst[:4] + (None,)
-            else:
-                burst = ctx.make_burst([w.colls[ci].coll_id for ci in orders[r]],
-                                       [dw.send[ci][r].data_ptr() for ci in orders[r]],
-                                       [dw.recv[ci][r].data_ptr() for ci in orders[r]],
-                                       delays_us[r] if delays_us else None)
-            n = ctx.submit_burst(r, burst, timeout_s)
-            if n != burst[0]:
+            if barrier is not None:
+                barrier.wait()
+            n = ctx.submit_burst(r, bursts[r], timeout_s)
+            if n != bursts[r][0]:
                 raise dfx.DfxError(n if n < 0 else dfx.ERR_TIMEOUT, f"dfx_submit_many_paced(rank={r}) -> {n}")
         except Exception as e:   # noqa: BLE001
             errs.append(e)
