@@ -76,6 +76,10 @@ typedef struct {
                               of 32 KiB or more (reduce: at most 64 KiB); a broadcast with direct steps has no
                               slots and its slices may reach 2 S.  dfx_coll_info reports the slice length */
   uint32_t chan_min_bytes; /* a collective uses C = clamp(ceil(ringChunkBytes / chan_min_bytes), 1, max_channels) channels */
+  /* The four spin_* fields shape the thresholds of passes that poll every queue entry in turn, as Alg. 1 is
+     written: queues shorter than scan_min, or every queue with scan_min = 0.  A pass that began with a readiness
+     scan visits only entries found runnable and waits at most spin_min polls on each; there the order of the
+     visits (focus_bytes, order_policy) does what the adjusted thresholds are for. */
   uint32_t spin_init;      /* initial spin threshold (poll attempts) at the task-queue front (Sec. 4.3) */
   uint32_t spin_min;       /* thr(pos) = max(spin_min, spin_init >> pos) */
   uint32_t spin_max;       /* cap after boosting */

@@ -166,19 +166,36 @@ def _completion_order(order_policy, priorities, n_colls=8, nbytes=8 << 20, late_
     return order
 
 
-def test_priority_ordering_decides_who_completes_first():
-    """Eight equal all-reduces (8 MiB, one channel: milliseconds each) queued on every vrank in the order
+def _out_of_order_pairs(order, want):
+    """Pairs of completions that came in the opposite order to `want` (a list of all ids); 0 = exactly `want`."""
+    rank = {c: i for i, c in enumerate(want)}
+    return sum(1 for i in range(len(order)) for j in range(i + 1, len(order)) if rank[order[i]] > rank[order[j]])
+
+
+@pytest.mark.parametrize("path", ["ring", "fold"])
+def test_priority_ordering_decides_who_completes_first(path):
+    """Eight equal all-reduces (8 MiB, one channel: about a millisecond each) queued on every vrank in the order
     0 .. 7.  Under FIFO ordering the one submitted first completes first and the one submitted last does
     not; under priority ordering with later = more urgent (the DP-overlap scheme of Sec. 4.3) the one
-    submitted last completes first; with the priorities the other way round the order is the FIFO one again."""
-    fifo = _completion_order(0, None)
-    assert fifo[0] == 0 and fifo.index(7) > 3, fifo
-    later_first = _completion_order(1, list(range(8)))
-    assert later_first[:4] == [7, 6, 5, 4] and later_first.index(0) > 3, later_first
-    earlier_first = _completion_order(1, [8 - i for i in range(8)])
-    assert earlier_first[:4] == [0, 1, 2, 3], earlier_first
+    submitted last completes first; with the priorities the other way round the order is the FIFO one again.
+    As rings every collective's opening step is runnable from the start, so the order is exact.  In fold steps a
+    collective is runnable once ALL vranks have fetched it, and the eight per-collective counters of the first burst
+    fill in any order: a daemon that looks in between starts on what is runnable then, so one completion may come out
+    of turn (at most 7 of the 28 pairs swapped; a policy that is ignored swaps all 28, chance 14)."""
+    knobs = dict(fold_max_bytes=0) if path == "ring" else {}
+    up, down = list(range(8)), list(range(7, -1, -1))
+
+    def check(order, want):
+        if path == "ring":
+            assert order[:4] == want[:4] and order.index(want[-1]) > 3, (order, want)
+        else:
+            assert order.index(want[0]) <= 1 and order.index(want[-1]) >= 6 and _out_of_order_pairs(order, want) <= 7, (order, want)
+
+    check(_completion_order(0, None, **knobs), up)
+    check(_completion_order(1, list(range(8)), **knobs), down)
+    check(_completion_order(1, [8 - i for i in range(8)], **knobs), up)
     # the same with Alg. 1's own queue handling (no readiness scan: the sorted queue and the thresholds decide)
-    alg1 = _completion_order(1, list(range(8)), scan_min=0)
+    alg1 = _completion_order(1, list(range(8)), scan_min=0, **knobs)
     assert alg1.index(7) < alg1.index(0), alg1
 
 
@@ -303,6 +320,40 @@ def test_stop_with_outstanding_work_and_resume(direct_min_bytes):
             _expect(dw, w, ci)
     finally:
         assert ctx.finalize() == dfx.OK
+
+
+def test_focused_passes_keep_a_workgroup_longer_on_one_collective():
+    """focus_bytes (the default path's stand-in for Sec. 4.3's stickiness): with sixteen disordered buckets as rings,
+    a scanned pass that visits the furthest-along collective first and ends after its byte budget makes a workgroup
+    stay longer with one collective than passes that visit every runnable collective once in queue order.  Measured
+    on the per-workgroup timeline (trace = 3): mean length of the runs of consecutive primitives of one collective,
+    2.8-3.0 with the default budget against 2.4-2.5 without (the effect is real and small; the values are the
+    oracle's either way)."""
+    from paper_2303_06324_amd import harness as gh
+    import paper_2303_06324_amd as dfx
+    w = wi.config3(n_buckets=16, bucket_bytes=4 << 20)
+    dw = gh.DeviceWorkload(w)
+    run_len = {}
+    for focus in (128 << 10, 0):
+        ctx = dfx.Context(8, gh.make_config(quit_idle_us=0, trace=3, fold_max_bytes=0, focus_bytes=focus))
+        try:
+            gh.prepare_all(ctx, w)
+            gh.submit_bursts(ctx, dw, timeout_s=60)
+            assert ctx.wait_all(60.0) == dfx.OK
+            assert ctx.stop() == dfx.OK
+            for ci in (0, 7, 15):
+                _expect(dw, w, ci)
+            runs = []
+            for wg in range(0, 8 * gh.make_config().max_channels, 5):
+                samples, _ = ctx.trace_read(wg)
+                ids = [(s >> 48) & 0xfff for s in samples if (s >> 60) != 15]
+                if len(ids) >= 16:
+                    runs.append(len(ids) / (1 + sum(1 for a, b in zip(ids, ids[1:]) if a != b)))
+            assert len(runs) >= 20
+            run_len[focus] = float(np.mean(runs))
+        finally:
+            assert ctx.finalize() == dfx.OK
+    assert run_len[128 << 10] > 1.08 * run_len[0], run_len
 
 
 def test_primitive_timeline_trace():
