@@ -1435,12 +1435,15 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             const u64 base = ((u64)w.y << 32) | w.x;
             const u64 peer_recv = ((u64)wr.y << 32) | wr.x;
             const SliceGeom gk = slice_geometry(S, a.R, 0u, fold_chunk(kd, q.fold, rank, peer));
+            // (a broadcast's one source goes in pieces: entry k is the k-th piece of the share)
+            const bool pieces = q.fold == 2 && kd == KIND_BC;
+            const uint32_t off = pieces ? bc_piece_off(gk.bytes, lane) : 0u;
             if (root_lane) sh.tab_dst[posted & 1][0] = base + gk.doff * gk.eb;
             else {
-              sh.tab_src[posted & 1][lane] = base + gk.soff * gk.eb;
+              sh.tab_src[posted & 1][lane] = base + gk.soff * gk.eb + off;
               if (!(want_root_recv && lane == 0))
-                sh.tab_dst[posted & 1][lane] = (target == 2u ? peer_recv : (u64)S.recvbuf) + gk.doff * gk.eb;
-              sh.tab_len[posted & 1][lane] = gk.bytes;
+                sh.tab_dst[posted & 1][lane] = (target == 2u ? peer_recv : (u64)S.recvbuf) + gk.doff * gk.eb + off;
+              sh.tab_len[posted & 1][lane] = pieces ? bc_piece_len(gk.bytes, lane) : gk.bytes;
             }
           }
           if (__ballot(bad)) { if (lane == 0) raise_error(a, 3u, wg); stop = STOP_ABORT; have = false; continue; }
@@ -1448,7 +1451,10 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           jmode = q.fold; jnseg = nk; jndst = target == 2u ? nk : 1u;
           const SliceGeom own = slice_geometry(S, a.R, 0u, rank);
           if (q.fold == 1) jbytes_fold = own.bytes;
-          else jbytes_fold = (uint32_t)S.slice_elems * own.eb;      // the longest segment: a channel's share of a full chunk
+          else {                                                    // the longest segment: a channel's share of a full chunk
+            jbytes_fold = (uint32_t)S.slice_elems * own.eb;
+            if (kd == KIND_BC) jbytes_fold = bc_piece_bytes(jbytes_fold);
+          }
         }
         // ---- post the slice (an empty one is only a handshake: the movers just raise the counters);
         // this claims the slots: the data follows, the counters after it

@@ -94,8 +94,17 @@ DFX_HD Prim make_fold_prim(int kind, uint32_t p) {
 // The tables of a fold or gather step (Prim::fold 1 or 2).  Entry k of a fold step is a source, listed in the order
 // of combination, which begins behind this rank (all-reduce, reduce-scatter: the ring's order for this rank's chunk)
 // or behind the root (reduce: the chain's); every entry is about the rank's own chunk.  Entry k of a gather step is
-// a segment: all-gather: block k out of rank k's send buffer; broadcast: the root's send buffer.
-DFX_HD uint32_t fold_entries(int kind, uint32_t step, uint32_t R) { return (step == 2 && kind == KIND_BC) ? 1u : R; }
+// a segment: all-gather: block k out of rank k's send buffer; broadcast: the k-th of eight pieces of the channel's
+// share of the root's send buffer (one source cut up, so that as many loads travel together as in an all-gather).
+constexpr uint32_t DFX_BC_PIECES = 8;
+DFX_HD uint32_t fold_entries(int kind, uint32_t step, uint32_t R) { return (step == 2 && kind == KIND_BC) ? DFX_BC_PIECES : R; }
+DFX_HD uint32_t bc_piece_bytes(uint32_t share_bytes) { return (((share_bytes + DFX_BC_PIECES - 1) / DFX_BC_PIECES) + 15u) & ~15u; }
+// piece k of a share of share_bytes: where it begins and how long it is (0 = nothing left for it)
+DFX_HD uint32_t bc_piece_off(uint32_t share_bytes, uint32_t k) { return k * bc_piece_bytes(share_bytes); }
+DFX_HD uint32_t bc_piece_len(uint32_t share_bytes, uint32_t k) {
+  const uint32_t pb = bc_piece_bytes(share_bytes), off = k * pb;
+  return off >= share_bytes ? 0u : (share_bytes - off < pb ? share_bytes - off : pb);
+}
 DFX_HD uint32_t fold_peer(int kind, uint32_t step, uint32_t R, uint32_t rank, uint32_t root, uint32_t k) {
   if (step == 2) return kind == KIND_BC ? root : k % R;
   return ((kind == KIND_RD ? root : rank) + 1u + k) % R;

@@ -1138,8 +1138,14 @@ int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t
             for (uint32_t k = 0; k < nk; ++k) {
               const uint32_t peer = fold_peer(kind, fq.fold, R, r, rt, k);
               if (peer >= R) return fail("rank %u channel %u fold step %u: entry %u names rank %u", r, v, p, k, peer);
-              const SliceGeom gk = slice_geometry(S, R, 0u, fold_chunk(kind, fq.fold, r, peer));
+              SliceGeom gk = slice_geometry(S, R, 0u, fold_chunk(kind, fq.fold, r, peer));
               if ((uint64_t)gk.bytes > (uint64_t)S.slice_elems * gk.eb) return fail("rank %u channel %u: a segment longer than the share", r, v);
+              if (fq.fold == 2 && kind == KIND_BC) {          // entry k is the k-th piece of the share
+                const uint32_t off = bc_piece_off(gk.bytes, k), len = bc_piece_len(gk.bytes, k);
+                if (len > bc_piece_bytes((uint32_t)S.slice_elems * gk.eb)) return fail("rank %u channel %u: piece %u longer than the job's bound", r, v, k);
+                if (off % gk.eb) return fail("rank %u channel %u: piece %u splits an element", r, v, k);
+                gk.soff += off / gk.eb; gk.doff += off / gk.eb; gk.bytes = len;
+              }
               if (!gk.bytes) continue;
               const uint64_t rd = gk.soff * gk.eb;            // every entry reads its rank's send buffer
               if (rd + gk.bytes > send_bytes) return fail("rank %u channel %u fold step %u: read of rank %u's buffer %llu+%u of %llu", r, v, p, peer, (unsigned long long)rd, gk.bytes, (unsigned long long)send_bytes);
