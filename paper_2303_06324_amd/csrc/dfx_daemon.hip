@@ -1338,7 +1338,25 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
 
       // The movers may be busy with earlier slices meanwhile; finished ones are retired between polls.
       uint32_t res = W_OK;
+      // While the first poll travels: which entry would the pass visit next, and is its context in its LDS slot?
+      // If not, its load from the context buffer sets off now.  Should this wait be given up, the switch finds
+      // the answer in registers (nothing below changes the queue, the list, another collective's slot or its
+      // saved context before then).
+      bool nx_ok = false, nx_hit = false;
+      uint32_t nx_pos = 0, nx_coll = 0, nx_sl = 0;
+      DfxDyn nx_dyn = {};
+      uint4 nx_ctx = uint4{0, 0, 0, 0};
       if (q.recv || q.send || q.drain || q.fold) {
+        const uint32_t ni = scanned ? rk + 1u : pos + 1u;
+        if (scanned ? (ni < nready && !(focus && pass_bytes >= a.focus_bytes)) : (ni < qlen)) {
+          nx_pos = scanned ? (uint32_t)sh.rlist[ni] : ni;
+          nx_coll = sh.taskq[nx_pos];
+          nx_sl = ctx_slot(nx_coll);
+          nx_ok = true;
+          nx_hit = sh.slot_tag[nx_sl] == nx_coll;
+          if (nx_hit) nx_dyn = sh.slot[nx_sl].dyn;
+          else if (lane < 8) nx_ctx = ((const uint4*)&myctx[nx_coll])[lane];
+        }
         u64 n = 0;
         for (;;) {
           bool ok = true;
@@ -1538,6 +1556,27 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         have = false;
         if (res == W_STOP) { stop = STOP_ABORT; continue; }
         if (scanned) ++rk; else ++pos;
+        if (nx_ok && res == W_TIMEOUT) {
+          // LoadCollectiveContext of the entry looked up during the wait (the same steps as at the head of the
+          // loop): its context is in its slot and the dynamic part in registers, or the load is under way and
+          // goes into the slot now
+          pos = nx_pos; coll = nx_coll; sl = nx_sl;
+          if (nx_hit) {
+            if (lane == 0) bump(sh.stat, ST_HIT, 1);
+          } else {
+            if (lane < 8) ((uint4*)&sh.slot[sl])[lane] = nx_ctx;
+            if (lane == 0) { sh.slot_tag[sl] = coll; bump(sh.stat, ST_LOAD, 1); }
+            __builtin_amdgcn_wave_barrier();
+            nx_dyn = sh.slot[sl].dyn;
+          }
+          g = nx_dyn.round; p = nx_dyn.prim; sent = nx_dyn.sent; recvd = nx_dyn.recvd; cidx = nx_dyn.cidx;
+          thr = a.spin_init >> (pos < 31 ? pos : 31);
+          if (thr < a.spin_min || scanned) thr = a.spin_min;
+          progressed = false;
+          prev_recv = 0;
+          have = true;
+          if (sw_pending && a.trace_on > 1) { sw_lb = wall_clock64(); sw_le = sw_lb; }
+        }
       }
     }
 
