@@ -1396,9 +1396,13 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       if (res == W_OK) {
         u64 tm1 = 0;
         if (a.trace_on > 1) { tm1 = wall_clock64(); if (lane == 0) bump(sh.stat, ST_T_WAIT, tm1 - tm0); }
+        // The last wait of a collective in fold steps moves nothing, and the counter it has just seen says that every
+        // rank's data step of this channel -- this workgroup's own job included -- is in memory: the completion is
+        // posted here and now instead of queueing as an empty job behind the data jobs of other collectives.
+        const bool done_here = q.fold == 3;
         // a flight slot: at most two jobs are posted and not yet retired
         bool given_up = false;
-        while (posted - retired >= 2u) {
+        while (!done_here && posted - retired >= 2u) {
           retire_finished();
           if (posted - retired >= 2u) {
             if ((++spins & 0xffffu) == 0 && abort_seen()) { given_up = true; break; }
@@ -1478,7 +1482,9 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         // this claims the slots: the data follows, the counters after it
         if (q.send || q.notify) ++sent;
         if (q.recv) ++recvd;
-        if (lane == 0) {
+        if (done_here) {
+          if (lane == 0) { bump(sh.stat, ST_PRIMS, 1); complete(coll, inv_seq, inv_nchan); }
+        } else if (lane == 0) {
           Job j;
           j.fin = jfin; j.fout = jfout; j.sb = jsb; j.rb = jrb;
           j.bytes = (q.drain || (!q.recv && !q.from_send)) ? 0u : bytes;   // drain and notify-only steps move nothing
@@ -1504,7 +1510,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           thr *= a.spin_boost;
           if (thr > a.spin_max) thr = a.spin_max;
         }
-        ++posted;
+        if (!done_here) ++posted;
 
         if (last) {
           // ---- CollectiveSuccess: the entry leaves the queue now; the completion counter and the
