@@ -637,11 +637,13 @@ def test_two_contexts_take_turns_on_the_device():
 def test_plain_c_client_of_the_boundary():
     """A C program (gcc, no Python, no PyTorch, hipMalloc'ed buffers) drives the library through include/dfx.h
     alone: the circular wait of two all-reduces, then an all-reduce, a direct reduce-scatter and a broadcast
-    on eight vranks in per-rank orders, checked against element-wise integer sums written out in C."""
+    on eight vranks in per-rank orders (rings and chains), then a small all-reduce in fold steps two hundred times
+    inside a resident daemon; all checked against element-wise integer sums written out in C."""
     import os
     import subprocess
     exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi", "c_client.bin")
     assert os.path.exists(exe), "the C client is not built (python -m paper_2303_06324_amd.build)"
     res = subprocess.run([exe], capture_output=True, text=True, timeout=100)
     assert res.returncode == 0, (res.returncode, res.stdout, res.stderr)
-    assert "circular wait ok" in res.stdout and "eight ranks ok" in res.stdout
+    assert "circular wait ok" in res.stdout and "eight ranks ok" in res.stdout and "small all-reduce ok" in res.stdout
+    print(res.stdout)
