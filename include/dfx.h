@@ -93,7 +93,10 @@ typedef struct {
                               1: SQ in fine-grained device memory written by the host through the PCIe BAR;
                               2: choose 1 when the device reports a large BAR, else 0 */
   uint32_t wg_map;         /* 0 (default): workgroup = channel*nranks + rank; 1: workgroup = rank*max_channels + channel */
-  uint32_t order_policy;   /* 0 = FIFO ordering, 1 = priority ordering (Sec. 4.3) */
+  uint32_t order_policy;   /* 0 = FIFO ordering, 1 = priority ordering (Sec. 4.3): a fetched collective joins the queue
+                              behind those of equal or higher priority, a scanned pass ranks the runnable collectives by
+                              priority first, and the pass looks again (SQ probe, scan, ranking) after at most 32 KiB of
+                              posted work, so that an urgent collective waits for little that was chosen before it came */
   uint32_t trace;          /* 1 = record context-switch latency samples (two clock reads per switch);
                               2 = also time the save / load parts and the wait / data / publish phases;
                               3 = phases as in 2, and the trace holds one sample per executed primitive

@@ -195,6 +195,9 @@ int launch_locked(dfx_ctx* c) {
   a.quit_ticks = (uint64_t)((double)c->cfg.quit_idle_us / c->tick_us);
   a.nwg = c->nwg;
   a.cq_ctl = c->cq_ctl; a.sq_freed = c->sq_freed; a.cq_mode = c->cfg.cq_mode; a.sq_eager = c->cfg.sq_eager; a.window = c->cfg.window; a.sq_local = c->sq_device ? 1u : 0u; a.focus_bytes = c->cfg.focus_bytes;
+  // Priority ordering looks again (SQ probe, scan, ranking) after 32 KiB of posted work at most: an urgent
+  // collective that arrives waits for less work that was chosen before it was there.
+  if (c->cfg.order_policy == 1 && a.focus_bytes > (32u << 10)) a.focus_bytes = 32u << 10;
   a.scan_min = c->cfg.scan_min;
   a.chan_spread = c->cfg.chan_spread;
   a.epoch = (uint32_t)(c->launches + 1);
