@@ -28,8 +28,8 @@
 // that carry the published buffer addresses (DFX_DIRECT_OFF), and behind them nchan shared lines, one per
 // channel, with three counters that every rank of the channel adds to:
 #define DFX_FOLD_PUB 0         //   +0  invocations published (buffer addresses written at SQE fetch)
-#define DFX_FOLD_RED 8         //   +8  fold steps finished (the rank's own chunk is reduced and in its recv buffer)
-#define DFX_FOLD_GAT 16        //   +16 gather steps finished (the rank has copied every other chunk)
+#define DFX_FOLD_RED 8         //   +8  fold steps finished (the rank's chunk is combined and written where it belongs: every recv buffer, its own, or the root's)
+#define DFX_FOLD_GAT 16        //   +16 gather steps finished (all-gather, broadcast: the rank has copied every block / its share)
 
 // Static context of one invocation on one rank: what the host writes into the SQ and what a
 // workgroup keeps in its context buffer (Sec. 4.2: buffer and connector addresses, rank count,
