@@ -256,33 +256,60 @@ bool outstanding(dfx_ctx* c) {
   return false;
 }
 
-// Write one SQE (caller holds the rank's mutex).
-int push_sqe(dfx_ctx* c, int rank, const DfxStatic& e) {
+// Writing an SQE has two halves (the caller holds the rank's mutex): the body goes into the slot `ahead` entries
+// behind the tail, and -- after a store fence -- the generation word, which the daemon looks for, makes it
+// visible.  Several bodies may be written before one fence and their generation words after it, so a burst
+// costs two fences in all instead of two per entry (behind the PCIe BAR a fence is a third of a microsecond).
+bool sqe_slot_free(dfx_ctx* c, int rank, uint32_t ahead) {
   RankState* rs = c->ranks[rank];
   const uint32_t D = c->cfg.sq_depth;
-  DfxSqSlot* slot = &c->sq[(size_t)rank * D + (rs->sq_tail & (D - 1))];
-  volatile uint32_t* ready = &slot->e.ready;
+  const uint64_t at = rs->sq_tail + ahead;
   // The slot last held the entry of one generation back; the last workgroup to read that one wrote
   // its generation into host memory.  Nothing is read from the SQ itself: it may lie behind the
   // PCIe BAR, where a load costs a microsecond.
-  const uint32_t gen_before = (uint32_t)(rs->sq_tail >> c->sq_shift);
-  volatile uint32_t* freed = &c->sq_freed[(size_t)rank * D + (rs->sq_tail & (D - 1))];
-  if (*freed != gen_before) return DFX_ERR_SQ_FULL;   // not yet read by every workgroup of the rank
+  const uint32_t gen_before = (uint32_t)(at >> c->sq_shift);
+  volatile uint32_t* freed = &c->sq_freed[(size_t)rank * D + (at & (D - 1))];
+  if (ahead >= D || *freed != gen_before) return false;   // not yet read by every workgroup of the rank
   std::atomic_thread_fence(std::memory_order_acquire);
+  return true;
+}
+void sqe_write_body(dfx_ctx* c, int rank, uint32_t ahead, const DfxStatic& e) {
+  RankState* rs = c->ranks[rank];
+  const uint32_t D = c->cfg.sq_depth;
+  DfxSqSlot* slot = &c->sq[(size_t)rank * D + ((rs->sq_tail + ahead) & (D - 1))];
   DfxStatic tmp = e;
   tmp.ready = 0;
-  // body first (six 16-byte stores), then the generation word
+  // six 16-byte stores, the last one without its last word (the generation)
   const __m128i* src = (const __m128i*)&tmp;
   __m128i* dst = (__m128i*)&slot->e;
   for (int i = 0; i < 5; ++i) _mm_storeu_si128(dst + i, _mm_loadu_si128(src + i));
   uint32_t* lastw = (uint32_t*)(dst + 5);
   const uint32_t* lasts = (const uint32_t*)(src + 5);
   lastw[0] = lasts[0]; lastw[1] = lasts[1]; lastw[2] = lasts[2];
+}
+void sqe_fence() {
   std::atomic_thread_fence(std::memory_order_release);
   _mm_sfence();   // orders write-combined stores when the SQ lives behind the PCIe BAR
-  *ready = (uint32_t)(rs->sq_tail >> c->sq_shift) + 1u;
+}
+// generation words of the `n` bodies written at the tail, in order; the tail moves on
+void sqe_publish(dfx_ctx* c, int rank, uint32_t n) {
+  RankState* rs = c->ranks[rank];
+  const uint32_t D = c->cfg.sq_depth;
+  for (uint32_t k = 0; k < n; ++k) {
+    DfxSqSlot* slot = &c->sq[(size_t)rank * D + (rs->sq_tail & (D - 1))];
+    volatile uint32_t* ready = &slot->e.ready;
+    *ready = (uint32_t)(rs->sq_tail >> c->sq_shift) + 1u;
+    rs->sq_tail++;
+  }
+}
+
+// Write one SQE (caller holds the rank's mutex).
+int push_sqe(dfx_ctx* c, int rank, const DfxStatic& e) {
+  if (!sqe_slot_free(c, rank, 0)) return DFX_ERR_SQ_FULL;
+  sqe_write_body(c, rank, 0, e);
+  sqe_fence();
+  sqe_publish(c, rank, 1);
   _mm_sfence();
-  rs->sq_tail++;
   return DFX_OK;
 }
 
@@ -636,32 +663,57 @@ int dfx_coll_info(dfx_ctx* c, int coll_id, uint32_t* nchan, uint32_t* slot_bytes
 
 namespace {
 
-// Write the SQE of one invocation; the caller sees to it that the daemon runs.
-int submit_one(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* recvbuf) {
+// The body of one invocation's SQE, `ahead` entries behind the tail (the caller holds the rank's mutex and
+// publishes afterwards).  Counts the invocation as submitted, so that the same id again in one run is BUSY.
+int stage_one(dfx_ctx* c, int rank, uint32_t ahead, int coll_id, const void* sendbuf, void* recvbuf) {
   if (coll_id < 0 || (uint32_t)coll_id >= c->cfg.max_colls) return DFX_ERR_INVALID_ARG;
   if (c->aborted.load()) return DFX_ERR_ABORTED;
   const CollInfo& ci = c->colls[coll_id];
   if (!ci.prepared) return DFX_ERR_NOT_PREPARED;
   if (!sendbuf || !recvbuf || ((uintptr_t)sendbuf & 15u) || ((uintptr_t)recvbuf & 15u)) return DFX_ERR_INVALID_ARG;
   RankState* rs = c->ranks[rank];
-  std::lock_guard<std::mutex> lk(rs->mu);
   if (rs->sub[coll_id] != rs->done[coll_id]) {
     drain_cq(c, rank);
     if (rs->sub[coll_id] != rs->done[coll_id]) return DFX_ERR_BUSY;
   }
+  if (!sqe_slot_free(c, rank, ahead)) return DFX_ERR_SQ_FULL;
   DfxStatic e = ci.tmpl;
   e.seq = rs->sub[coll_id];
   e.sendbuf = (uint64_t)(uintptr_t)sendbuf;
   e.recvbuf = (uint64_t)(uintptr_t)recvbuf;
-  const int rc = push_sqe(c, rank, e);
-  if (rc == DFX_OK) {
-    rs->sub[coll_id]++;
-    rs->n_sub.fetch_add(1, std::memory_order_relaxed);
-  } else {
-    // A caller that only retries submissions must still empty the CQ, or a workgroup blocked
-    // on a full CQ stops reading SQEs and the SQ never drains.
-    drain_cq(c, rank);
+  sqe_write_body(c, rank, ahead, e);
+  rs->sub[coll_id]++;
+  return DFX_OK;
+}
+
+// Up to 32 invocations of one rank in a row: bodies, one fence, generation words, one fence.  Returns how many
+// went in; *rc is the status of the first that did not (DFX_OK if all did).  The caller sees to it that the
+// daemon runs.
+int submit_run(dfx_ctx* c, int rank, int n, const int* coll_ids, const void* const* sendbufs, void* const* recvbufs, int* rc) {
+  RankState* rs = c->ranks[rank];
+  std::lock_guard<std::mutex> lk(rs->mu);
+  int k = 0;
+  *rc = DFX_OK;
+  for (; k < n && k < 32; ++k) {
+    *rc = stage_one(c, rank, (uint32_t)k, coll_ids[k], sendbufs[k], recvbufs[k]);
+    if (*rc != DFX_OK) break;
   }
+  if (k) {
+    sqe_fence();
+    sqe_publish(c, rank, (uint32_t)k);
+    _mm_sfence();
+    rs->n_sub.fetch_add((uint64_t)k, std::memory_order_relaxed);
+  }
+  // A caller that only retries submissions must still empty the CQ, or a workgroup blocked
+  // on a full CQ stops reading SQEs and the SQ never drains.
+  if (*rc == DFX_ERR_SQ_FULL) drain_cq(c, rank);
+  return k;
+}
+
+// Write the SQE of one invocation; the caller sees to it that the daemon runs.
+int submit_one(dfx_ctx* c, int rank, int coll_id, const void* sendbuf, void* recvbuf) {
+  int rc = DFX_OK;
+  (void)submit_run(c, rank, 1, &coll_id, &sendbuf, &recvbuf, &rc);
   return rc;
 }
 
@@ -684,17 +736,31 @@ int dfx_submit_all(dfx_ctx* c, int coll_id, const void* const* sendbufs, void* c
   if (!c || !sendbufs || !recvbufs) return DFX_ERR_INVALID_ARG;
   const uint64_t t0 = now_ns();
   c->user_stopped.store(false);
-  for (int r = 0; r < c->R; ++r) {
-    uint32_t spins = 0;
-    for (;;) {
-      const int rc = submit_one(c, r, coll_id, sendbufs[r], recvbufs[r]);
-      if (rc == DFX_OK) break;
-      if (rc != DFX_ERR_SQ_FULL) return rc;
-      const int rr = ensure_running(c);
-      if (rr != DFX_OK) return rr;
-      if (now_ns() - t0 > timeout_ns) return DFX_ERR_SQ_FULL;
-      backoff(spins);
+  uint32_t spins = 0;
+  for (;;) {
+    // every vrank's body, one fence, every vrank's generation word, one fence: the eight entries reach the
+    // device together (rank mutexes are taken in rank order; every other path holds one at a time)
+    int rc = DFX_OK, staged = 0;
+    for (; staged < c->R; ++staged) {
+      c->ranks[staged]->mu.lock();
+      rc = stage_one(c, staged, 0u, coll_id, sendbufs[staged], recvbufs[staged]);
+      if (rc != DFX_OK) { c->ranks[staged]->mu.unlock(); break; }
     }
+    if (rc == DFX_OK) {
+      sqe_fence();
+      for (int r = 0; r < c->R; ++r) sqe_publish(c, r, 1);
+      _mm_sfence();
+      for (int r = 0; r < c->R; ++r) { c->ranks[r]->n_sub.fetch_add(1, std::memory_order_relaxed); c->ranks[r]->mu.unlock(); }
+      break;
+    }
+    // one vrank could not take it: nothing has been published, the staged ones are taken back
+    for (int r = 0; r < staged; ++r) { c->ranks[r]->sub[coll_id]--; c->ranks[r]->mu.unlock(); }
+    if (rc != DFX_ERR_SQ_FULL) return rc;
+    { std::lock_guard<std::mutex> lk(c->ranks[staged]->mu); drain_cq(c, staged); }
+    const int rr = ensure_running(c);
+    if (rr != DFX_OK) return rr;
+    if (now_ns() - t0 > timeout_ns) return DFX_ERR_SQ_FULL;
+    backoff(spins);
   }
   // every vrank's entry is in place: now see to the daemon (a launch finds them all at once)
   return ensure_running(c);
@@ -705,28 +771,32 @@ int dfx_submit_many_paced(dfx_ctx* c, int rank, int n, const int* coll_ids, cons
   if (!c || rank < 0 || rank >= c->R || n < 0 || (n > 0 && (!coll_ids || !sendbufs || !recvbufs))) return DFX_ERR_INVALID_ARG;
   const uint64_t t0 = now_ns();
   uint32_t spins = 0;
-  int i = 0, since_check = 0;
+  int i = 0, since_check = -1;       // (-1: the daemon has not been looked after yet)
   bool paused = false;
   c->user_stopped.store(false);
-  // The daemon is looked after (launch state behind one lock, an event query) after the first
-  // entry, then every 32 entries, after every pause, whenever the SQ is full, and after the last
-  // entry -- not per entry.
+  // Entries without a pause between them go in runs of up to 32 (two store fences per run, not per entry).
+  // The daemon is looked after (launch state behind one lock, an event query) after the first run, then
+  // every 32 entries, after every pause, whenever the SQ is full, and after the last entry -- not per entry.
   while (i < n) {
     if (delays_ns && delays_ns[i] && !paused) {
       const uint64_t until = now_ns() + delays_ns[i];
       while (now_ns() < until) _mm_pause();
       paused = true;
-      since_check = 0;
+      since_check = -1;
     }
-    const int rc = submit_one(c, rank, coll_ids[i], sendbufs[i], recvbufs[i]);
-    if (rc == DFX_OK) {
-      ++i; spins = 0; paused = false;
-      if (since_check++ % 32 == 0 || i == n) {
+    int run = 1;
+    while (i + run < n && run < 32 && !(delays_ns && delays_ns[i + run])) ++run;
+    int rc = DFX_OK;
+    const int k = submit_run(c, rank, run, coll_ids + i, sendbufs + i, recvbufs + i, &rc);
+    if (k > 0) {
+      i += k; spins = 0; paused = false;
+      if (since_check < 0 || (since_check += k) >= 32 || i == n) {
         const int rr = ensure_running(c);
         if (rr != DFX_OK) return rr;
+        since_check = 0;
       }
-      continue;
     }
+    if (rc == DFX_OK) continue;
     if (rc != DFX_ERR_SQ_FULL) return i > 0 ? i : rc;
     const int rr = ensure_running(c);
     if (rr != DFX_OK) return i > 0 ? i : rr;
