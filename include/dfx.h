@@ -237,15 +237,17 @@ int dfx_submit(dfx_ctx* ctx, int rank, int coll_id, const void* sendbuf, void* r
  * One invocation of coll_id on every vrank in a single call (vrank order 0 .. nranks-1):
  * sendbufs / recvbufs: host arrays of nranks device pointers.  The same as nranks dfx_submit calls,
  * minus nranks-1 trips through the caller's language binding; for the single-process setting in which
- * one thread drives all vranks.  Returns DFX_OK, or the first status that is not OK (vranks before it
- * have been submitted; a full SQ is retried for up to timeout_ns first).
+ * one thread drives all vranks, and with all entries made visible together (their bodies, one store fence,
+ * their generation words).  All or nothing: returns DFX_OK when every vrank's entry is in its SQ, else the first
+ * status that is not OK with no vrank submitted (a full SQ is retried for up to timeout_ns first).
  */
 int dfx_submit_all(dfx_ctx* ctx, int coll_id, const void* const* sendbufs, void* const* recvbufs, uint64_t timeout_ns);
 
 /*
  * Submit n collectives of one vrank in the given order (a burst of dfcclRun* calls, e.g. the
  * gradient buckets of one backward pass): element i is dfx_submit(ctx, rank, coll_ids[i],
- * sendbufs[i], recvbufs[i]).  A full SQ is retried until timeout_ns has passed.  The three arrays
+ * sendbufs[i], recvbufs[i]), made visible to the daemon in runs of up to 32 entries (the bodies of a run, one
+ * store fence, its generation words).  A full SQ is retried until timeout_ns has passed.  The three arrays
  * are host arrays of n entries, read only during the call; the buffers they point to are device
  * memory under the rules of dfx_submit.  Returns how many were submitted (n on success, fewer on
  * timeout or on an error after the first), or the negative status of the first submission.
