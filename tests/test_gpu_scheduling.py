@@ -634,6 +634,40 @@ def test_two_contexts_take_turns_on_the_device():
     assert (ra, rb) == (dfx.OK, dfx.OK)
 
 
+def test_submit_all_is_all_or_nothing_and_bursts_keep_their_order():
+    """dfx_submit_all takes every vrank's entry or none: with one vrank's invocation of the collective still
+    outstanding it returns BUSY and leaves the other vranks free to be submitted one by one.  A burst
+    (dfx_submit_many) with the same id twice stops at the repeat and reports how many went in."""
+    from paper_2303_06324_amd import harness as gh
+    import paper_2303_06324_amd as dfx
+    R = 8
+    w = wi.Workload("all_or_nothing", R, [wi.CollSpec(0, wi.AR, wi.I32, 5000), wi.CollSpec(1, wi.AR, wi.F32, 777)], [[0, 1]] * R, seed=5, cfg=52)
+    dw = gh.DeviceWorkload(w)
+    ctx = dfx.Context(R, gh.make_config())
+    try:
+        gh.prepare_all(ctx, w)
+        ptrs = ctx.make_all([dw.send[0][r].data_ptr() for r in range(R)], [dw.recv[0][r].data_ptr() for r in range(R)])
+        assert ctx.submit(3, 0, dw.send[0][3].data_ptr(), dw.recv[0][3].data_ptr()) == dfx.OK
+        assert ctx.submit_all(0, ptrs) == dfx.ERR_BUSY            # vrank 3 has it outstanding: nobody is submitted
+        for r in range(R):
+            if r != 3:
+                assert ctx.submit(r, 0, dw.send[0][r].data_ptr(), dw.recv[0][r].data_ptr()) == dfx.OK
+        assert ctx.wait_all(20.0) == dfx.OK
+        _expect(dw, w, 0)
+        # a burst of vrank 0: ids 1, 0, 1 -- the third is a repeat of an outstanding one
+        burst = ctx.make_burst([1, 0, 1], [dw.send[1][0].data_ptr(), dw.send[0][0].data_ptr(), dw.send[1][0].data_ptr()],
+                               [dw.recv[1][0].data_ptr(), dw.recv[0][0].data_ptr(), dw.recv[1][0].data_ptr()])
+        assert ctx.submit_burst(0, burst, 5.0) == 2
+        for r in range(1, R):
+            assert ctx.submit(r, 1, dw.send[1][r].data_ptr(), dw.recv[1][r].data_ptr()) == dfx.OK
+            assert ctx.submit(r, 0, dw.send[0][r].data_ptr(), dw.recv[0][r].data_ptr()) == dfx.OK
+        assert ctx.wait_all(20.0) == dfx.OK
+        _expect(dw, w, 0)
+        _expect(dw, w, 1)
+    finally:
+        assert ctx.finalize() == dfx.OK
+
+
 def test_plain_c_client_of_the_boundary():
     """A C program (gcc, no Python, no PyTorch, hipMalloc'ed buffers) drives the library through include/dfx.h
     alone: the circular wait of two all-reduces, then an all-reduce, a direct reduce-scatter and a broadcast
