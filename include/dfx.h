@@ -67,7 +67,7 @@ typedef struct {
   uint32_t struct_bytes;   /* sizeof(dfx_config) the caller was compiled with */
   uint32_t max_channels;   /* workgroups per vrank; daemon grid = nranks * max_channels (Sec. 5: launched with the largest grid) */
   uint32_t max_colls;      /* coll_id range [0, max_colls); also task-queue capacity (<= 4096) */
-  uint32_t sq_depth;       /* SQ ring entries per vrank (power of two) */
+  uint32_t sq_depth;       /* SQ ring entries per vrank (power of two; default 1024: a burst of a thousand submissions does not wait for the daemon) */
   uint32_t cq_slots;       /* CQ slot-array length per vrank (Sec. 5 "optimized CQ") */
   uint32_t nslots;         /* K: slots per connector FIFO, >= 2 (a fused recv+send ring cannot run on 1) */
   uint32_t slot_bytes;     /* S: bytes per FIFO slot and channel, multiple of 16 (default 256 KiB).  A slice is

@@ -489,7 +489,7 @@ int dfx_config_default(dfx_config* cfg) {
   cfg->struct_bytes = (uint32_t)sizeof(dfx_config);
   cfg->max_channels = 32;
   cfg->max_colls = 2048;
-  cfg->sq_depth = 256;
+  cfg->sq_depth = 1024;
   cfg->cq_slots = 256;
   cfg->nslots = 4;
   cfg->slot_bytes = 256u << 10;
