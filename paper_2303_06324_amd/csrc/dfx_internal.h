@@ -2,6 +2,7 @@
 #ifndef DFX_INTERNAL_H
 #define DFX_INTERNAL_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifndef DFX_WG_THREADS
@@ -86,6 +87,13 @@ struct alignas(16) DfxCooked {
   uint16_t vch;          // channel of the collective that this workgroup serves (0 .. nchan-1)
 };
 static_assert(sizeof(DfxCooked) == 96, "DfxCooked must be 96 bytes");
+// (the scheduler reads some of it as 16-byte words: the readiness scan and the set-up of a primitive)
+static_assert(offsetof(DfxCooked, part_elems) == 32 && offsetof(DfxCooked, flags_out) == 40 && offsetof(DfxCooked, flags_in) == 48 &&
+              offsetof(DfxCooked, fifo_in) == 64 && offsetof(DfxCooked, slice_elems) == 72 && offsetof(DfxCooked, rounds) == 76 &&
+              offsetof(DfxCooked, seq) == 80 && offsetof(DfxCooked, nprim) == 84 && offsetof(DfxCooked, nchan) == 86 &&
+              offsetof(DfxCooked, nslots) == 88 && offsetof(DfxCooked, kind) == 89 && offsetof(DfxCooked, dtype) == 90 &&
+              offsetof(DfxCooked, bc_pos) == 91 && offsetof(DfxCooked, priority) == 92 && offsetof(DfxCooked, vch) == 94,
+              "DfxCooked layout");
 
 struct alignas(16) DfxCtxEntry {
   DfxCooked st;
