@@ -112,7 +112,12 @@ def _switch_summary(rc, dt, st, n, st2):
             "advance_us_mean": round(sum(s["advance_us_mean"] for s in st2) / len(st2), 3),
             "load_us_mean": round(sum(s["load_us_mean"] for s in st2) / len(st2), 3),
             "setup_us_mean": round(sum(s["setup_us_mean"] for s in st2) / len(st2), 3),
-            "clock_read_us": round(max(s["clock_read_us"] for s in st2), 4)}
+            "clock_read_us": round(max(s["clock_read_us"] for s in st2), 4),
+            # the other workload-independent overheads of Sec. 6.2 (Fig. 7), from the run without the extra stamps:
+            # reading an SQE (per entry and workgroup: every workgroup of a vrank reads every entry; a run of up to 64
+            # is taken at once) and writing a CQE (first to last host-memory operation)
+            "sqe_read_us_mean": round(sum(s["sqe_us"] for s in st) / max(1, sum(s["sqe_fetched"] for s in st)), 4),
+            "cqe_write_us_mean": round(sum(s["cqe_us"] for s in st) / max(1, sum(s["cqe_posted"] for s in st)), 3)}
 
 
 def _switch_config1(trace: int, iters: int = 400):
@@ -141,6 +146,23 @@ def _switch_config1(trace: int, iters: int = 400):
     return rc, dt, st, 2 * iters
 
 
+def _prepare_time(n_colls: int = 1024) -> float:
+    """Host time of dfx_prepare per collective (registering the 1024 small all-reduces: geometry, connector
+    block; Sec. 6.2's "prepare" overhead), in microseconds."""
+    import workload_inputs as wi
+    import paper_2303_06324_amd as dfx
+    from paper_2303_06324_amd import harness as gh
+    w = wi.config5(n_colls=n_colls, seed=4)
+    ctx = dfx.Context(R, gh.make_config())
+    try:
+        t0 = time.perf_counter()
+        gh.prepare_all(ctx, w)
+        dt = time.perf_counter() - t0
+    finally:
+        ctx.finalize()
+    return round(dt / n_colls * 1e6, 3)
+
+
 def switch_latency():
     """Context-switch latency (abort decision -> first poll of the next collective of the same pass):
     1024 small all-reduces issued in a different random order on every vrank, with the library
@@ -149,6 +171,7 @@ def switch_latency():
     with the smallest thresholds.  Each case runs
     twice: with two clock reads per switch (the latency), and with the save / load parts timed too."""
     out = _switch_summary(*_switch_run(1), _switch_run(2)[2])
+    out["prepare_us_mean"] = _prepare_time()
     alg1 = dict(chan_spread=0, scan_min=0)
     out["alg1_single_queue"] = _switch_summary(*_switch_run(1, **alg1), _switch_run(2, **alg1)[2])
     ring = dict(chan_spread=0, scan_min=0, fold_max_bytes=0)

@@ -186,6 +186,9 @@ typedef struct {
   double setup_us_mean;    /* with trace = 2: the part after the load (thresholds, the primitive's descriptor) up to the first poll */
   double clock_read_us;    /* with trace = 1 or 2: what one read of the wall clock costs the scheduler (a switch sample holds two
                               reads, a split sample five) */
+  double sqe_us;           /* time the vrank's workgroups spent fetching SQEs (entry seen -> run of up to 64 entries read,
+                              cooked into contexts, queued), summed over workgroups; always counted.  Every workgroup reads
+                              every entry of its vrank: divide by sqe_fetched for the time per entry and workgroup */
 } dfx_stats_t;
 
 /* Fill *cfg with defaults (struct_bytes set). cfg: host, caller-owned. */

@@ -35,7 +35,7 @@ class Stats(C.Structure):
         "cqe_posted", "max_taskq", "passes", "quits", "launches", "switch_samples")] + [(n, C.c_double) for n in (
         "switch_us_p50", "switch_us_p99", "switch_us_mean", "save_us_mean", "load_us_mean", "wait_us", "data_us",
         "publish_us")] + [("scan_skips", C.c_uint64), ("cqe_us", C.c_double), ("advance_us_mean", C.c_double),
-                          ("setup_us_mean", C.c_double), ("clock_read_us", C.c_double)]
+                          ("setup_us_mean", C.c_double), ("clock_read_us", C.c_double), ("sqe_us", C.c_double)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

@@ -1035,6 +1035,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           // taken one by one (a fence, six loads, an atomic with its answer) they cost more than
           // the collectives they describe.
           if (got) {
+            const u64 tf0 = wall_clock64();
             // how many consecutive entries from the read index on are there?
             uint32_t room = a.max_colls - qlen;
             if (room > 64) room = 64;
@@ -1122,6 +1123,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             qlen += (uint32_t)__builtin_popcountll(mine_mask);
             if (lane == 0) {
               bump(sh.stat, ST_SQE, n);
+              bump(sh.stat, ST_T_SQE, wall_clock64() - tf0);
               __hip_atomic_fetch_max(&sh.stat[ST_MAXQ], (u64)qlen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
             __builtin_amdgcn_wave_barrier();

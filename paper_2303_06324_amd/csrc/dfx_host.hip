@@ -953,6 +953,7 @@ int dfx_stats(dfx_ctx* c, int rank, dfx_stats_t* out) {
     out->publish_us += (double)s[ST_T_PUB] * c->tick_us;
     out->scan_skips += s[ST_SCAN_SKIPS];
     out->cqe_us += (double)s[ST_T_CQE] * c->tick_us;
+    out->sqe_us += (double)s[ST_T_SQE] * c->tick_us;
     stamp_ticks += s[ST_T_STAMP]; stamp_n += s[ST_N_STAMP];
     wgs.push_back(wg);
     tn.push_back(h[wg].trace_n);

@@ -120,7 +120,8 @@ struct alignas(16) DfxWgState {
 enum { ST_PREEMPT = 0, ST_LOAD, ST_HIT, ST_SAVE, ST_LAZY, ST_POLLS, ST_PRIMS, ST_SQE, ST_CQE, ST_MAXQ, ST_PASSES, ST_QUITS,
        ST_T_WAIT, ST_T_DATA, ST_T_PUB, ST_SCAN_SKIPS,   // T_*: wall-clock ticks, only with trace on
        ST_T_CQE,                                         // ticks spent writing CQEs (always counted)
-       ST_T_STAMP, ST_N_STAMP };                         // ticks of back-to-back clock reads and their number (trace 1, 2)
+       ST_T_STAMP, ST_N_STAMP,                           // ticks of back-to-back clock reads and their number (trace 1, 2)
+       ST_T_SQE };                                       // ticks spent fetching SQEs: probe seen -> entries cooked and queued (always counted)
 
 // dev_ctl words (device memory)
 // (abort and quit share one aligned 64-bit word: the scheduler reads both with one load; the host
