@@ -87,8 +87,11 @@ typedef struct {
   uint32_t preempt;        /* 0 = never abort a wait (the non-preemptive negative control) */
   uint32_t watchdog_ms;    /* in-kernel: work queued but no progress for this long => error + daemon exit */
   uint32_t quit_idle_us;   /* voluntary quit (Sec. 4.4): a workgroup leaves after this long without a
-                              successful primitive or SQE fetch; 0 = stay resident until dfx_stop (a device-wide
-                              synchronisation or a kernel that needs the whole device then waits for dfx_stop) */
+                              successful primitive or SQE fetch; 0 = stay resident until dfx_stop.  While the daemon
+                              is resident a device-wide synchronisation, a kernel that needs the whole device, and
+                              work of another stream that the runtime has put on the daemon's hardware queue (streams
+                              share a few of them; a synchronous copy of results to the host has been seen to) wait
+                              until it leaves: keep this above 0 unless the process does nothing else on the device */
   uint32_t sq_in_device;   /* 0: SQ in pinned host memory (the paper's placement);
                               1: SQ in fine-grained device memory written by the host through the PCIe BAR;
                               2: choose 1 when the device reports a large BAR, else 0 */

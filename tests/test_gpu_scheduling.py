@@ -103,6 +103,49 @@ def test_device_synchronize_between_disordered_collectives():
         ctx.finalize()
 
 
+@pytest.mark.parametrize("path", ["ring", "fold"])
+@pytest.mark.parametrize("single_queue", [0, 1])
+def test_eight_allreduces_in_a_new_random_order_every_iteration(path, single_queue):
+    """The shape of the first deadlock program of Sec. 6.1: eight vranks, eight all-reduces of 256 B .. 1 MiB, two
+    hundred iterations, in every iteration every vrank submits the eight in a fresh random order of its own (a
+    non-preemptive library deadlocks on the first disagreement; Sec. 6.1 reports 100 %).  All iterations complete,
+    the values are the oracle's, and the daemon got there by preempting (with one shared queue per vrank, the
+    single-queue setting of Sec. 2.3, and with the collectives spread over the workgroups)."""
+    from paper_2303_06324_amd import harness as gh
+    import paper_2303_06324_amd as dfx
+    R, iters = 8, 200
+    sizes = [256, 1024, 4096, 16384, 65536, 262144, 524288, 1 << 20]
+    colls = [wi.CollSpec(i, wi.AR, wi.F32, nb // 4) for i, nb in enumerate(sizes)]
+    w = wi.Workload("deadlock_program_1", R, colls, [list(range(8))] * R, seed=61, cfg=53)
+    dw = gh.DeviceWorkload(w)
+    knobs = dict(fold_max_bytes=0) if path == "ring" else {}
+    if single_queue:
+        knobs.update(chan_spread=0, max_channels=1)
+    ctx = dfx.Context(R, gh.make_config(**knobs))      # (default idle quit: reading results back waits for the daemon to leave)
+    g = np.random.default_rng(2024)
+    try:
+        gh.prepare_all(ctx, w)
+        for it in range(iters):
+            orders = [list(map(int, g.permutation(8))) for _ in range(R)]
+            gh.submit_round_robin(ctx, dw, orders=orders, timeout_s=30)
+            assert ctx.wait_all(30.0) == dfx.OK, it
+            if it in (0, iters - 1):
+                for ci in range(8):
+                    _expect(dw, w, ci)
+                if it == 0:       # wipe the results (on the current stream only: the daemon's stream never drains)
+                    import torch
+                    for ci in range(8):
+                        for r in range(R):
+                            dw.recv[ci][r].zero_()
+                    torch.cuda.current_stream().synchronize()
+        assert ctx.stop() == dfx.OK
+        st = [ctx.stats(r) for r in range(R)]
+        assert sum(s["cqe_posted"] for s in st) == iters * 8 * R
+        assert sum(s["preemptions"] for s in st) > iters          # it did have to switch away from stuck collectives
+    finally:
+        assert ctx.finalize() == dfx.OK
+
+
 def test_priority_ordering_policy():
     """Sec. 4.3 priority-based ordering: later-arriving collectives get higher priority (the DP
     overlap scheme); everything still completes and matches."""
