@@ -99,7 +99,8 @@ typedef struct {
   uint32_t order_policy;   /* 0 = FIFO ordering, 1 = priority ordering (Sec. 4.3): a fetched collective joins the queue
                               behind those of equal or higher priority, a scanned pass ranks the runnable collectives by
                               priority first, and the pass looks again (SQ probe, scan, ranking) after at most 32 KiB of
-                              posted work, so that an urgent collective waits for little that was chosen before it came */
+                              posted work and keeps one fold step in flight instead of two, so that an urgent collective waits for
+                              little that was chosen before it came */
   uint32_t trace;          /* 1 = record context-switch latency samples (two clock reads per switch);
                               2 = also time the save / load parts and the wait / data / publish phases;
                               3 = phases as in 2, and the trace holds one sample per executed primitive

@@ -1402,11 +1402,14 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
         // rank's data step of this channel -- this workgroup's own job included -- is in memory: the completion is
         // posted here and now instead of queueing as an empty job behind the data jobs of other collectives.
         const bool done_here = q.fold == 3;
-        // a flight slot: at most two jobs are posted and not yet retired
+        // a flight slot: at most two jobs are posted and not yet retired (under priority ordering a step of a
+        // collective in fold steps, which is one long job, waits until the movers have nothing else: what is
+        // posted cannot be overtaken by a more urgent collective that arrives)
+        const uint32_t depth = (a.order_policy == 1 && q.fold) ? 1u : 2u;
         bool given_up = false;
-        while (!done_here && posted - retired >= 2u) {
+        while (!done_here && posted - retired >= depth) {
           retire_finished();
-          if (posted - retired >= 2u) {
+          if (posted - retired >= depth) {
             if ((++spins & 0xffffu) == 0 && abort_seen()) { given_up = true; break; }
             __builtin_amdgcn_s_sleep(1);
           }
