@@ -145,6 +145,8 @@ class Policy:
     focus: int = 0                # with scan: furthest-along entries first, and the pass ends after this many slices
     direct: bool = False          # steps that read the previous rank's recv / send buffer instead of a slot (notify / drain)
     fold: bool = False            # collectives in steps that wait on all ranks (all-reduce: fold_scatter, last_wait_red)
+    fold_slice: int = 0           # with fold: elements per slice of the step with data (0 = the whole chunk at once); the
+                                  # step is taken slice after slice, the last wait once, behind the last slice
     priority_order: bool = False  # priority-based ordering: fetch before every pass, queue sorted by Coll.priority, priority ranks first
 
 
@@ -414,7 +416,9 @@ class Daemon:
         share of this invocation."""
         if send_side < 4:
             return True
-        return self.S.foldcnt[coll][send_side - 4] >= (self.inv_of[coll] + 1) * self.S.R
+        # (published: once per rank and invocation; folded / gathered: once per rank, invocation and slice)
+        per_rank = 1 if send_side == 4 else self.S.rounds[coll]
+        return self.S.foldcnt[coll][send_side - 4] >= (self.inv_of[coll] + 1) * self.S.R * per_rank
 
     def _runnable(self, coll):
         g, p = self.active if self.loaded == coll else self.saved[coll]
@@ -517,7 +521,13 @@ class Daemon:
             return False                   # every claim slot is taken: wait for the mover (no state change)
         # ---- the slice is this rank's now: moved at once, or claimed and queued for the mover
         p2, g2 = p + 1, g
-        if p2 == len(prog):
+        if S.is_fold(coll) and len(prog) == 2:
+            # fold steps: the step with data for every slice, then the last wait once
+            if p == 0:
+                p2, g2 = (0, g + 1) if g + 1 < rounds else (1, g)
+            else:
+                p2, g2 = 0, rounds
+        elif p2 == len(prog):
             p2, g2 = 0, g + 1
         last = g2 == rounds
         if P.lookahead:
@@ -562,7 +572,10 @@ class System:
             sb, db, blen = layout(c, R)
             is_fold = policy.fold and R > 1
             self.progs.append([program(c.kind, R, r, c.root, sb, db, policy.direct, is_fold) for r in range(R)])
-            self.rounds.append(1 if is_fold else max(1, -(-blen // policy.slice_elems)))   # fold steps: one slice per share
+            if is_fold:      # fold steps: one slice per share, or slices of fold_slice elements
+                self.rounds.append(max(1, -(-blen // policy.fold_slice)) if policy.fold_slice else 1)
+            else:
+                self.rounds.append(max(1, -(-blen // policy.slice_elems)))
             if policy.direct and c.kind in CHAINS and R > 1 and not is_fold:
                 self.rounds[-1] += 1     # the last round of a chain with direct steps is the drain
             self.fifo.append([Fifo(policy.K) for _ in range(R)])
@@ -607,25 +620,32 @@ class System:
         if name in ("drain", "last_wait", "last_wait_red"):
             return
         if name in ("fold_all", "fold_scatter", "fold_root", "gather_pub"):
-            # whole chunks (one slice per share), read out of the other ranks' buffers in place
+            # slice g of the chunk (the whole chunk when there is one slice), read out of the other ranks' buffers in place
             if self.with_data:
                 R = self.R
+                fs = self.policy.fold_slice
+
+                def cut(blk):
+                    lo, hi = blk
+                    return (lo, hi) if not fs else (min(lo + g * fs, hi), min(lo + (g + 1) * fs, hi))
                 if name == "fold_all":        # reduce-scatter: block r; the ring's order, which begins behind r
-                    (slo, shi), (dlo, dhi) = sblk, dblk
+                    (slo, shi), (dlo, dhi) = cut(sblk), cut(dblk)
                     self.recvs[ci][r][dlo:dhi] = rd.fold_rotated([s[slo:shi] for s in self.sends[ci]], r + 1, c.dtype)
                 elif name == "fold_scatter":  # all-reduce: chunk r in the same order, into every rank's recv buffer
-                    (slo, shi), (dlo, dhi) = sblk, dblk
+                    (slo, shi), (dlo, dhi) = cut(sblk), cut(dblk)
                     x = rd.fold_rotated([s[slo:shi] for s in self.sends[ci]], r + 1, c.dtype)
                     for j in range(R):
                         self.recvs[ci][j][dlo:dhi] = x
                 elif name == "fold_root":     # reduce: chunk r of the message, the chain's order, into the root's buffer
-                    lo, hi = rd.chunk_bounds(c.count, R, rd.ELEM_BYTES[c.dtype])[r]
+                    lo, hi = cut(rd.chunk_bounds(c.count, R, rd.ELEM_BYTES[c.dtype])[r])
                     self.recvs[ci][c.root][lo:hi] = rd.fold_rotated([s[lo:hi] for s in self.sends[ci]], c.root + 1, c.dtype)
                 elif c.kind == AG:            # all-gather: block j out of rank j's send buffer
+                    lo, hi = cut((0, c.count))
                     for j in range(R):
-                        self.recvs[ci][r][j * c.count:(j + 1) * c.count] = self.sends[ci][j][:c.count]
+                        self.recvs[ci][r][j * c.count + lo:j * c.count + hi] = self.sends[ci][j][lo:hi]
                 else:                         # broadcast: the root's send buffer
-                    self.recvs[ci][r][:c.count] = self.sends[ci][c.root][:c.count]
+                    lo, hi = cut((0, c.count))
+                    self.recvs[ci][r][lo:hi] = self.sends[ci][c.root][lo:hi]
             self.foldcnt[ci][1 if name.startswith("fold") else 2] += 1
             return
         if PRIMS[name][0]:

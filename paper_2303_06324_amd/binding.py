@@ -26,7 +26,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in (
         "struct_bytes", "max_channels", "max_colls", "sq_depth", "cq_slots", "nslots", "slot_bytes",
         "chan_min_bytes", "spin_init", "spin_min", "spin_max", "spin_boost", "preempt", "watchdog_ms",
-        "quit_idle_us", "sq_in_device", "wg_map", "order_policy", "trace", "fetch_batch")] + [("pool_bytes", C.c_uint64), ("scan_min", C.c_uint32), ("chan_spread", C.c_uint32), ("cq_mode", C.c_uint32), ("sq_eager", C.c_uint32), ("window", C.c_uint32), ("focus_bytes", C.c_uint32), ("direct", C.c_uint32), ("direct_min_bytes", C.c_uint32), ("fold_max_bytes", C.c_uint32)]
+        "quit_idle_us", "sq_in_device", "wg_map", "order_policy", "trace", "fetch_batch")] + [("pool_bytes", C.c_uint64), ("scan_min", C.c_uint32), ("chan_spread", C.c_uint32), ("cq_mode", C.c_uint32), ("sq_eager", C.c_uint32), ("window", C.c_uint32), ("focus_bytes", C.c_uint32), ("direct", C.c_uint32), ("direct_min_bytes", C.c_uint32), ("fold_max_bytes", C.c_uint32), ("fold_slice_bytes", C.c_uint32), ("reserved0", C.c_uint32)]
 
 
 class Stats(C.Structure):

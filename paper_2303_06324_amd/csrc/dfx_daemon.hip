@@ -1193,7 +1193,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
                 const u64 e_sent = ((u64)d0.w << 32) | d0.z, e_recvd = ((u64)d1.y << 32) | d1.x;
                 bool okr = true, oks = true;
                 if (pq.fold)   // every rank of the channel has got as far as this step needs: (seq + 1) x R on the step's counter
-                  okr = ld_agent64((const u64*)(fold_shared_line(f_out, rank, a.R, ge.y >> 16) + 8u * pq.fwait)) >= ((u64)ge.x + 1u) * a.R;
+                  okr = ld_agent64((const u64*)(fold_shared_line(f_out, rank, a.R, ge.y >> 16) + 8u * pq.fwait))
+                        >= ((u64)ge.x + 1u) * a.R * (pq.fwait ? (u64)e[4].w : 1ull);   // (a data step counts once per slice: bytes 64..79 end in rounds)
                 if (pq.recv) okr = ld_agent64((const u64*)f_in) > e_recvd;
                 if (pq.send) oks = (e_sent - ld_agent64((const u64*)f_out + 8)) < (u64)(ge.z & 0xffu);
                 else if (pq.drain) oks = e_sent == ld_agent64((const u64*)f_out + 8);
@@ -1285,9 +1286,10 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       const Prim q = fold ? make_fold_prim((int)S.kind, p)
                           : chain_drain_round(make_prim((int)S.kind, a.R, S.bc_pos & 3u, p, (S.bc_pos & DFX_CTX_DIRECT) != 0),
                                               (int)S.kind, (S.bc_pos & DFX_CTX_DIRECT) != 0, g, S.rounds);
-      // fold steps wait for one of the channel's shared counters to reach (invocation + 1) x R
+      // fold steps wait for one of the channel's shared counters: every rank has published the invocation
+      // ((invocation + 1) x R), or every rank has finished its data step for every slice (x slices per share)
       const u64* const fold_cnt = fold ? (const u64*)(fold_shared_line(S.flags_out, rank, a.R, S.nchan) + 8u * q.fwait) : nullptr;
-      const u64 fold_target = ((u64)S.seq + 1u) * a.R;
+      const u64 fold_target = ((u64)S.seq + 1u) * a.R * (q.fwait ? (u64)S.rounds : 1ull);
       u64* const tail_out = (u64*)S.flags_out;
       u64* const tail_in = (u64*)S.flags_in;
       const uint32_t K = S.nslots;
@@ -1333,7 +1335,8 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
       if (q.notify) { jfout = jrb; jrb = nullptr; }
 
       // the position after this primitive (slices in windows, the chunk index stepping down the ring)
-      const SeqPos nx = next_position(kind, a.R, rank, a.window, S.rounds, S.nprim, g, p, cidx);
+      const SeqPos nx = fold ? next_fold_position(S.rounds, g, p, cidx)
+                             : next_position(kind, a.R, rank, a.window, S.rounds, S.nprim, g, p, cidx);
       const uint32_t g_next = nx.g, p_next = nx.p, cidx_next = nx.cidx;
       const bool last = (g_next >= S.rounds);
       const uint32_t inv_seq = S.seq, inv_nchan = S.nchan;
@@ -1461,7 +1464,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
             bad = bad || w.z != inv_seq + 1u || (target == 2u && wr.z != inv_seq + 1u);
             const u64 base = ((u64)w.y << 32) | w.x;
             const u64 peer_recv = ((u64)wr.y << 32) | wr.x;
-            const SliceGeom gk = slice_geometry(S, a.R, 0u, fold_chunk(kd, q.fold, rank, peer));
+            const SliceGeom gk = slice_geometry(S, a.R, g, fold_chunk(kd, q.fold, rank, peer));
             // (a broadcast's one source goes in pieces: entry k is the k-th piece of the share)
             const bool pieces = q.fold == 2 && kd == KIND_BC;
             const uint32_t off = pieces ? bc_piece_off(gk.bytes, lane) : 0u;
@@ -1476,7 +1479,7 @@ extern "C" __global__ void __launch_bounds__(DFX_WG_THREADS) dfx_daemon_kernel(D
           if (__ballot(bad)) { if (lane == 0) raise_error(a, 3u, wg); stop = STOP_ABORT; have = false; continue; }
           __builtin_amdgcn_wave_barrier();
           jmode = q.fold; jnseg = nk; jndst = target == 2u ? nk : 1u;
-          const SliceGeom own = slice_geometry(S, a.R, 0u, rank);
+          const SliceGeom own = slice_geometry(S, a.R, g, rank);
           if (q.fold == 1) jbytes_fold = own.bytes;
           else {                                                    // the longest segment: a channel's share of a full chunk
             jbytes_fold = (uint32_t)S.slice_elems * own.eb;

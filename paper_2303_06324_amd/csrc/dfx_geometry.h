@@ -297,4 +297,16 @@ DFX_HD SeqPos next_position(int kind, uint32_t R, uint32_t rank, uint32_t W, uin
   return n;
 }
 
+// The walk of a collective in fold steps: the step with data (p = 0) for every slice of the share, then the
+// last wait (p = 1) once.  g >= rounds afterwards: that was it.
+DFX_HD SeqPos next_fold_position(uint32_t rounds, uint32_t g, uint32_t p, uint32_t cidx) {
+  SeqPos n;
+  n.cidx = cidx;
+  if (p == 0) {
+    if (g + 1 < rounds) { n.g = g + 1; n.p = 0; }
+    else { n.g = g; n.p = 1; }
+  } else { n.g = rounds; n.p = 0; }
+  return n;
+}
+
 #endif

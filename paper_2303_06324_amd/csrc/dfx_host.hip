@@ -410,8 +410,8 @@ int plan_collective(const dfx_config& cfg, int nranks, int coll_id, dfx_kind kin
     const uint64_t want = round_up(part * eb / ((kind == DFX_BROADCAST ? 2 : 4) * R), 16);
     slice_cap = std::min(std::max(want, lo), hi);
   }
-  // fold steps: no slots, one slice per channel share whatever its length
-  if (fold) slice_cap = 1ull << 31;
+  // fold steps: no slots; slices of fold_slice_bytes, or (0) one slice, the whole channel share
+  if (fold) slice_cap = cfg.fold_slice_bytes ? cfg.fold_slice_bytes : (1ull << 31);
   uint64_t slot_bytes = std::min<uint64_t>(slice_cap, round_up(part * eb, 16));
   const uint64_t slice_elems = slot_bytes / eb;
   const uint64_t rounds = std::max<uint64_t>(1, ceil_div(part, slice_elems));
@@ -539,6 +539,7 @@ int dfx_init(dfx_ctx** out, int nranks, const dfx_config* ucfg, void* hip_stream
   if (!is_pow2(cfg.nslots) || cfg.nslots < 2 || cfg.nslots > 64) return DFX_ERR_INVALID_ARG;
   while (cfg.window >= cfg.nslots) cfg.window /= 2;
   if (cfg.slot_bytes < 16 || (cfg.slot_bytes & 15u)) return DFX_ERR_INVALID_ARG;
+  if ((cfg.fold_slice_bytes & 15u) || cfg.reserved0) return DFX_ERR_INVALID_ARG;
   if (cfg.chan_min_bytes < 16) return DFX_ERR_INVALID_ARG;
   if (cfg.spin_min < 1 || cfg.spin_init < 1 || cfg.spin_boost < 1 || cfg.spin_max < cfg.spin_min) return DFX_ERR_INVALID_ARG;
   if (cfg.sq_in_device > 2 || cfg.wg_map > 1 || cfg.order_policy > 1 || cfg.direct > 1) return DFX_ERR_INVALID_ARG;
@@ -1202,7 +1203,6 @@ int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t
       for (;;) {
         if (fold) {
           // fold steps: the same look-ups as the scheduler makes when it posts a fold or a gather step
-          if (g != 0 || S.rounds != 1) return fail("rank %u channel %u: a collective in fold steps has one slice per share", r, v);
           const Prim fq = make_fold_prim(kind, p);
           const uint32_t rt = S.nslots;      // the root
           if (fq.fold == 1 || fq.fold == 2) {
@@ -1212,7 +1212,7 @@ int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t
             for (uint32_t k = 0; k < nk; ++k) {
               const uint32_t peer = fold_peer(kind, fq.fold, R, r, rt, k);
               if (peer >= R) return fail("rank %u channel %u fold step %u: entry %u names rank %u", r, v, p, k, peer);
-              SliceGeom gk = slice_geometry(S, R, 0u, fold_chunk(kind, fq.fold, r, peer));
+              SliceGeom gk = slice_geometry(S, R, g, fold_chunk(kind, fq.fold, r, peer));
               if ((uint64_t)gk.bytes > (uint64_t)S.slice_elems * gk.eb) return fail("rank %u channel %u: a segment longer than the share", r, v);
               if (fq.fold == 2 && kind == KIND_BC) {          // entry k is the k-th piece of the share
                 const uint32_t off = bc_piece_off(gk.bytes, k), len = bc_piece_len(gk.bytes, k);
@@ -1232,10 +1232,10 @@ int dfx_check_geometry(int nranks, const dfx_config* ucfg, dfx_kind kind, size_t
               written[target == 2u ? peer : (target == 1u ? rt : r)].push_back({wr, wr + gk.bytes});
             }
           }
-          const SeqPos nx = next_position(kind, R, r, cfg.window, S.rounds, S.nprim, g, p, cidx);
+          const SeqPos nx = next_fold_position(S.rounds, g, p, cidx);
           g = nx.g; p = nx.p; cidx = nx.cidx;
           if (g >= S.rounds) break;
-          if (++steps > 8) return fail("rank %u channel %u: the fold steps do not end", r, v);
+          if (++steps > (uint64_t)S.rounds + 8) return fail("rank %u channel %u: the fold steps do not end", r, v);
           continue;
         }
         const Prim q = chain_drain_round(make_prim(kind, R, S.bc_pos & 3u, p, direct), kind, direct, g, S.rounds);

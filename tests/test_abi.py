@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
 def test_config_struct_matches_header_size():
     import paper_2303_06324_amd as dfx
     cfg = dfx.config_default()
-    assert cfg.struct_bytes == ctypes.sizeof(dfx.Config) == 128
+    assert cfg.struct_bytes == ctypes.sizeof(dfx.Config) == 136
     assert cfg.nslots >= 2 and cfg.max_colls <= 4096 and cfg.preempt == 1
     assert dfx.strerror(0) == "ok" and "timeout" in dfx.strerror(dfx.ERR_TIMEOUT)
 
@@ -53,6 +53,9 @@ def test_argument_validation_without_gpu():
         bad = dfx.config_default()
         bad.nslots = k
         assert lib.dfx_init(ctypes.byref(h), 8, ctypes.byref(bad), None) == dfx.ERR_INVALID_ARG
+    bad = dfx.config_default()
+    bad.fold_slice_bytes = 100      # not a multiple of 16 bytes
+    assert lib.dfx_init(ctypes.byref(h), 8, ctypes.byref(bad), None) == dfx.ERR_INVALID_ARG
     bad = dfx.config_default()
     bad.sq_depth = 100
     assert lib.dfx_init(ctypes.byref(h), 8, ctypes.byref(bad), None) == dfx.ERR_INVALID_ARG

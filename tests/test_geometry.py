@@ -50,7 +50,9 @@ def test_ragged_counts_rank_counts_and_dtypes(kind):
 
 @pytest.mark.parametrize("knobs", [dict(direct=0), dict(direct_min_bytes=0), dict(window=1), dict(window=4, nslots=8), dict(nslots=2),
                                    dict(slot_bytes=4096, max_channels=4), dict(chan_spread=0), dict(chan_min_bytes=1 << 20),
-                                   dict(direct_min_bytes=0, slot_bytes=16 << 10, max_channels=2, window=1)])
+                                   dict(direct_min_bytes=0, slot_bytes=16 << 10, max_channels=2, window=1),
+                                   dict(fold_slice_bytes=4096), dict(fold_slice_bytes=48, max_channels=2), dict(order_policy=1, fold_slice_bytes=32 << 10),
+                                   dict(fold_slice_bytes=1 << 16, fold_max_bytes=1 << 30)])
 def test_scheduler_knobs(knobs):
     cfg = _cfg(**knobs)
     for kind in KINDS:

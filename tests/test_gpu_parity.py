@@ -576,3 +576,29 @@ def test_fold_steps_of_every_kind_under_forced_preemption_and_disorder():
     stats = _run(w, mode="threads", timeout_s=60.0, max_channels=2, chan_spread=0, scan_min=0,
                  spin_init=1, spin_min=1, spin_max=1, spin_boost=1)
     assert sum(s["preemptions"] for s in stats) > 100
+
+
+# ---------------------------------------------------------------- fold steps in slices
+@pytest.mark.parametrize("kind", [wi.AR, wi.AG, wi.RS, wi.BC, wi.RD])
+@pytest.mark.parametrize("knobs", [dict(fold_slice_bytes=4096), dict(fold_slice_bytes=48, max_channels=2),
+                                   dict(order_policy=1, fold_slice_bytes=32 << 10)],
+                         ids=["slices_4KiB", "slices_48B_two_channels", "priority_ordering_32KiB"])
+def test_fold_steps_in_slices(kind, knobs):
+    """The step with data taken slice after slice (one mover job each), the last wait once behind the last slice:
+    the shared counters then count slices, and the values are the same bits.  Ragged counts give short and empty
+    last slices; 48-byte slices make hundreds of jobs per share."""
+    small = knobs.get("fold_slice_bytes") == 48
+    for dtype, count, op, R, root in ((wi.F32, 70004 if not small else 5004, wi.SUM, 8, 5), (wi.BF16, 100003 if not small else 3001, wi.MAX, 8, 0),
+                                      (wi.I32, (1 << 20) + 24 if not small else 1032, wi.PROD, 3, 2), (wi.F16, 8, wi.MIN, 5, 4)):
+        c = count // 8 * 8 if kind in (wi.AG, wi.RS) else count       # (16-byte-multiple blocks take the fold steps)
+        _run(_one(kind, dtype, max(c, 8), R, root=root, seed=count + R, op=op), fold_max_bytes=64 << 20, **knobs)
+
+
+def test_fold_steps_in_slices_under_forced_preemption_disorder_and_quit():
+    """Sliced fold steps with the smallest thresholds, one shared queue per rank, every rank its own order; and a
+    daemon that quits while collectives are half way through their slices picks them up again."""
+    stats = _run(wi.config5(n_colls=64, seed=8), mode="threads", timeout_s=60.0, max_channels=2, chan_spread=0, scan_min=0,
+                 spin_init=1, spin_min=1, spin_max=1, spin_boost=1, fold_slice_bytes=1024)
+    assert sum(s["preemptions"] for s in stats) > 100
+    stats = _run(wi.config3(n_buckets=8, bucket_bytes=1 << 20, seed=63), fold_slice_bytes=2048, quit_idle_us=20)
+    _run(_mixed_workload(29, n_colls=24), mode="threads", timeout_s=60.0, fold_slice_bytes=512, order_policy=1)

@@ -490,7 +490,8 @@ def test_priority_ordering_ranks_the_urgent_collective_first(later_first):
 
 
 # ---------------------------------------------------------------- fold steps of an all-reduce
-@pytest.mark.parametrize("var", [dict(), dict(scan=True), dict(lookahead=2, scan=True, focus=1)])
+@pytest.mark.parametrize("var", [dict(), dict(scan=True), dict(lookahead=2, scan=True, focus=1), dict(fold_slice=2),
+                                 dict(lookahead=2, scan=True, focus=1, fold_slice=2)])
 @pytest.mark.parametrize("orders", [_OPP, _SAME])
 def test_fold_steps_exhaustive_interleavings_tiny(orders, var):
     """All-reduces in fold steps (waits on all ranks through shared counters: published, folded) keep Alg. 1's liveness:
@@ -520,7 +521,8 @@ def test_fold_steps_without_preemption_still_deadlock_on_opposite_orders():
     assert sm.is_deadlocked(S)
 
 
-@pytest.mark.parametrize("var", [dict(), dict(lookahead=2, scan=True, focus=1, direct=True)])
+@pytest.mark.parametrize("var", [dict(), dict(lookahead=2, scan=True, focus=1, direct=True), dict(fold_slice=8),
+                                 dict(lookahead=2, scan=True, focus=2, fold_slice=5)])
 @pytest.mark.parametrize("seed", range(4))
 def test_fold_steps_values_and_completion_order(var, seed):
     """All five kinds on three ranks in fold steps, random orders, random interleavings: the final
@@ -549,9 +551,9 @@ def test_fold_steps_values_and_completion_order(var, seed):
                 k = colls[c].kind
                 assert S.foldcnt[c][0] >= R
                 if k in (wi.AR, wi.RS, wi.RD):
-                    assert S.foldcnt[c][1] >= R     # every rank has folded: nobody reads a send buffer any more
+                    assert S.foldcnt[c][1] >= R * S.rounds[c]     # every rank has folded every slice: nobody reads a send buffer any more
                 if k in (wi.AG, wi.BC):
-                    assert S.foldcnt[c][2] >= R     # every rank has gathered
+                    assert S.foldcnt[c][2] >= R * S.rounds[c]     # every rank has gathered every slice
         ticks += 1
         assert ticks < 3_000_000
     assert S.total_cqes() == R * len(colls)
@@ -564,7 +566,7 @@ def test_fold_steps_of_the_other_kinds_exhaustive_interleavings_tiny(kinds):
     deadlocks and all end with the four CQEs."""
     colls = [wi.CollSpec(0, kinds[0], wi.F32, 8, root=1), wi.CollSpec(1, kinds[1], wi.F32, 8, root=0)]
     w = wi.Workload("fold2", 2, colls, [[0, 1], [1, 0]], seed=1, cfg=95)
-    for var in (dict(), dict(lookahead=2, scan=True, focus=1)):
+    for var in (dict(), dict(lookahead=2, scan=True, focus=1), dict(lookahead=2, scan=True, focus=1, fold_slice=4)):
         S0 = _system(w, sm.Policy(spin_init=2, spin_min=1, spin_max=2, boost=2, K=2, slice_elems=4, fold=True, **var), data=False)
         seen = sm.explore(S0, max_states=600_000)
         assert len(seen) > 20
